@@ -1,0 +1,656 @@
+/*
+ * skm_oracle.c -- plain CPU oracle for the SuperKMeans iteration.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, fp64 statement of
+ * what the method computes.  It shares no code with the HIP library and must
+ * never be called from the product path; only the test-suite, the smoke check
+ * and the CPU-baseline leg of the benchmark load it.
+ *
+ * Every function follows one passage of the paper (arxiv 2603.20009):
+ *   - Algorithm 1            : the whole fit (rotation, init, iteration 1 as a
+ *                              full exact assignment, iterations >= 2 as
+ *                              partial distance + progressive pruning, update,
+ *                              d' adjustment, ETR, un-rotation);
+ *   - Section 3.1            : random rotation, Forgy initialisation, norms;
+ *   - Section 3.2            : d' = floor(d * 12.5%), 64-dim steps, update,
+ *                              split of empty clusters, adjustment of d';
+ *   - Section 3.3            : termination, Early Termination by Recall;
+ *   - Section 3.4            : progressive pruning, initial threshold;
+ *   - Section 4.8            : the 95%..97% band and the 20% step for d'.
+ *
+ * The pruning bound theta(t, tau) is not printed in the paper, which defers
+ * to the ADSampling paper; the form used here is ADSampling's hypothesis test
+ * written for squared distances (see orc_theta_ratio).
+ *
+ * Arithmetic: inputs are fp32, everything else is fp64; distances are direct
+ * sums of squared differences (no norm expansion).  Loops are in the order of
+ * the paper's pseudocode; OpenMP only splits the outermost loop over points.
+ *
+ * Readings of the paper that are choices of this build (all listed in the
+ * design notes): tau is frozen inside a group of G consecutive centroids and
+ * refreshed after the group (G = 1 is Algorithm 1 to the letter); the
+ * incumbent wins ties; d' is kept a multiple of 16; empty clusters are
+ * re-seeded from a donor drawn with probability proportional to its size.
+ *
+ * Parity pins (tests/ with -m "not gpu"): brute-force argmin, one-sidedness,
+ * witnesses for every false prune, no-regress / monotone objective, centroid
+ * means, rotation invariance, closed-form theta values, ETR closed form.
+ * Unpinned by the paper (fixed by this build's reading only): eps0's default,
+ * the split constants, d' rounding, ETR stop-rule details.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_BLOCK 64 /* Section 3.2: delta-d = 64 */
+
+/* ------------------------------------------------------------------ */
+/* Integer PRNG: splitmix64 (public-domain generator by S. Vigna).     */
+/* Streams are separated by adding stream * ORC_STREAM_STRIDE to seed. */
+/* ------------------------------------------------------------------ */
+#define ORC_STREAM_STRIDE 0xD1342543DE82EF95ULL
+
+uint64_t orc_rng_next(uint64_t *state) {
+  uint64_t z;
+  *state += 0x9E3779B97F4A7C15ULL;
+  z = *state;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+  return z ^ (z >> 31);
+}
+
+uint64_t orc_rng_stream(uint64_t seed, uint64_t stream) {
+  return seed + stream * ORC_STREAM_STRIDE;
+}
+
+/* Section 3.1 "Centroids Initialization": k distinct rows, uniformly at
+ * random (partial Fisher-Yates over 0..n-1, stream 0 of the seed). */
+int orc_sample_rows(uint64_t seed, uint64_t stream, int64_t n, int32_t k,
+                    int64_t *idx_out) {
+  int64_t *perm;
+  int64_t i;
+  uint64_t st = orc_rng_stream(seed, stream);
+  if (k > n || k < 0) return -1;
+  perm = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n > 0 ? n : 1));
+  if (!perm) return -2;
+  for (i = 0; i < n; ++i) perm[i] = i;
+  for (i = 0; i < k; ++i) {
+    uint64_t r = orc_rng_next(&st) % (uint64_t)(n - i);
+    int64_t j = i + (int64_t)r;
+    int64_t tmp = perm[i];
+    perm[i] = perm[j];
+    perm[j] = tmp;
+    idx_out[i] = perm[i];
+  }
+  free(perm);
+  return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* theta(t, tau) = tau * ratio(t).                                     */
+/* ADSampling rejects "dist <= r" after t of d rotated dimensions when */
+/*   sqrt(d/t) * ||partial|| > (1 + eps0/sqrt(t)) * r,                 */
+/* i.e. for squared quantities  partial^2 > tau * (t/d)(1+eps0/sqrt t)^2.*/
+/* A partial sum of squares never exceeds the full one, so tau itself  */
+/* is always a valid bound as well: the ratio is capped at 1.          */
+/* ------------------------------------------------------------------ */
+double orc_theta_ratio(int32_t d, int32_t t, double eps0) {
+  double r, s;
+  if (t >= d) return 1.0;
+  if (t <= 0) return 0.0;
+  s = 1.0 + eps0 / sqrt((double)t);
+  r = ((double)t / (double)d) * s * s;
+  return r < 1.0 ? r : 1.0;
+}
+
+/* d' handling.  Algorithm 1: d' = floor(d * 12.5%).  This build keeps d' a
+ * multiple of 16 inside [16, 16*floor(d/16)] (nearest multiple, halves up). */
+static int32_t round16_clamp(double v, int32_t d) {
+  int32_t hi = (d / 16) * 16;
+  int32_t r = (int32_t)floor(v / 16.0 + 0.5) * 16;
+  if (hi < 16) hi = 16;
+  if (r < 16) r = 16;
+  if (r > hi) r = hi;
+  return r;
+}
+
+int32_t orc_dprime_init(int32_t d, double frac) {
+  return round16_clamp(floor((double)d * frac), d);
+}
+
+/* Section 4.8: more than `hi` of the pairs pruned by the first test ->
+ * shrink d' by step*d'; fewer than `lo` -> grow it by step*d'. */
+int32_t orc_dprime_adjust(int32_t d, int32_t dprime, double f, double lo,
+                          double hi, double step) {
+  double v = (double)dprime;
+  if (f > hi)
+    v = v - step * v;
+  else if (f < lo)
+    v = v + step * v;
+  else
+    return dprime;
+  return round16_clamp(v, d);
+}
+
+/* ------------------------------------------------------------------ */
+/* Rotation (Algorithm 1, first two lines; last line for the inverse). */
+/* ------------------------------------------------------------------ */
+void orc_rotate(const float *X, int64_t n, int32_t d, const float *R,
+                double *Xr) {
+  int64_t i;
+#pragma omp parallel for schedule(static)
+  for (i = 0; i < n; ++i) {
+    int32_t c, j;
+    for (c = 0; c < d; ++c) {
+      double s = 0.0;
+      for (j = 0; j < d; ++j)
+        s += (double)X[i * d + j] * (double)R[(int64_t)j * d + c];
+      Xr[i * d + c] = s;
+    }
+  }
+}
+
+/* Y = Yr * R^T (R orthogonal, so R^T undoes X*R). */
+void orc_unrotate(const double *Yr, int32_t k, int32_t d, const float *R,
+                  double *Y) {
+  int32_t i, c, j;
+  for (i = 0; i < k; ++i)
+    for (c = 0; c < d; ++c) {
+      double s = 0.0;
+      for (j = 0; j < d; ++j)
+        s += Yr[(int64_t)i * d + j] * (double)R[(int64_t)c * d + j];
+      Y[(int64_t)i * d + c] = s;
+    }
+}
+
+static double sqdist_range(const double *x, const double *y, int32_t lo,
+                           int32_t hi) {
+  double s = 0.0;
+  int32_t j;
+  for (j = lo; j < hi; ++j) {
+    double df = x[j] - y[j];
+    s += df * df;
+  }
+  return s;
+}
+
+/* ------------------------------------------------------------------ */
+/* Iteration 1 (Algorithm 1, "Full GEMM" part): exact nearest centroid, */
+/* lowest index on ties.                                                */
+/* ------------------------------------------------------------------ */
+void orc_assign_full(const double *Xr, int64_t n, int32_t d, const double *Y,
+                     int32_t k, int32_t *assign, double *dist) {
+  int64_t i;
+#pragma omp parallel for schedule(dynamic, 8)
+  for (i = 0; i < n; ++i) {
+    const double *x = Xr + i * d;
+    double best = INFINITY;
+    int32_t bj = 0, j;
+    for (j = 0; j < k; ++j) {
+      double s = sqdist_range(x, Y + (int64_t)j * d, 0, d);
+      if (s < best) {
+        best = s;
+        bj = j;
+      }
+    }
+    assign[i] = bj;
+    dist[i] = best;
+  }
+}
+
+/* ------------------------------------------------------------------ */
+/* Iterations >= 2 (Algorithm 1, loop over points and centroids;        */
+/* Section 3.4).  For point i:                                          */
+/*   tau   = || x_i - y_prev(i) ||^2 over all d dims (initial threshold)*/
+/*   centroids are visited in index order in groups of G; inside a group*/
+/*   tau is frozen:                                                     */
+/*     p = partial distance on dims [0, d')                             */
+/*     p > theta(d', tau)            -> pruned by the first test        */
+/*     else add 64 dims at a time; after each block with t < d dims     */
+/*     seen, p > theta(t, tau)       -> pruned                          */
+/*     reaching t = d completes the distance                            */
+/*   after the group the smallest completed distance replaces tau and   */
+/*   the assignment iff it is strictly below tau.                       */
+/* With prev == NULL the incumbent is seeded with the centroid of       */
+/* smallest partial distance on [0, d') (lowest index on ties).         */
+/*                                                                      */
+/* Optional outputs:                                                    */
+/*   pruned_first : number of pairs (i, j != incumbent) cut by test one */
+/*   enter[m]     : pairs that entered trailing block m (m = 0..nb-1),  */
+/*                  enter[nb] = pairs that completed                    */
+/*   fate[i*k+j]  : number of dims seen when (i,j) was dropped; d if it */
+/*                  completed; 0 for the incumbent (tiny inputs only)   */
+/* ------------------------------------------------------------------ */
+void orc_assign_pruned(const double *Xr, int64_t n, int32_t d, const double *Y,
+                       int32_t k, const int32_t *prev, int32_t dprime,
+                       double eps0, int32_t G, int32_t *assign, double *dist,
+                       int64_t *pruned_first, int64_t *enter, int32_t *fate) {
+  int32_t nb = (d - dprime + ORC_BLOCK - 1) / ORC_BLOCK;
+  int64_t i;
+  int64_t pf_total = 0;
+  int64_t *enter_tot = (int64_t *)calloc((size_t)nb + 1, sizeof(int64_t));
+  if (G < 1) G = 1;
+#pragma omp parallel
+  {
+    int64_t pf = 0;
+    int64_t *ent = (int64_t *)calloc((size_t)nb + 1, sizeof(int64_t));
+    int32_t m;
+#pragma omp for schedule(dynamic, 8)
+    for (i = 0; i < n; ++i) {
+      const double *x = Xr + i * d;
+      int32_t inc, best, g0;
+      double tau;
+      if (prev) {
+        inc = prev[i];
+      } else {
+        double bp = INFINITY;
+        int32_t j;
+        inc = 0;
+        for (j = 0; j < k; ++j) {
+          double p = sqdist_range(x, Y + (int64_t)j * d, 0, dprime);
+          if (p < bp) {
+            bp = p;
+            inc = j;
+          }
+        }
+      }
+      tau = sqdist_range(x, Y + (int64_t)inc * d, 0, d);
+      best = inc;
+      if (fate) fate[i * k + inc] = 0;
+      for (g0 = 0; g0 < k; g0 += G) {
+        int32_t g1 = (g0 + G < k) ? g0 + G : k;
+        double gd = INFINITY;
+        int32_t gj = -1, j;
+        for (j = g0; j < g1; ++j) {
+          const double *y = Y + (int64_t)j * d;
+          double p;
+          int32_t t = dprime, alive = 1;
+          if (j == inc) continue;
+          p = sqdist_range(x, y, 0, dprime);
+          if (p > tau * orc_theta_ratio(d, dprime, eps0)) {
+            pf++;
+            if (fate) fate[i * k + j] = dprime;
+            continue;
+          }
+          for (m = 0; m < nb; ++m) {
+            int32_t t1 = t + ORC_BLOCK < d ? t + ORC_BLOCK : d;
+            ent[m]++;
+            p += sqdist_range(x, y, t, t1);
+            t = t1;
+            if (t < d && p > tau * orc_theta_ratio(d, t, eps0)) {
+              alive = 0;
+              break;
+            }
+          }
+          if (fate) fate[i * k + j] = t;
+          if (!alive) continue;
+          ent[nb]++;
+          if (p < gd) {
+            gd = p;
+            gj = j;
+          }
+        }
+        if (gj >= 0 && gd < tau) {
+          tau = gd;
+          best = gj;
+        }
+      }
+      assign[i] = best;
+      dist[i] = tau;
+    }
+#pragma omp critical
+    {
+      pf_total += pf;
+      for (m = 0; m <= nb; ++m) enter_tot[m] += ent[m];
+    }
+    free(ent);
+  }
+  if (pruned_first) *pruned_first = pf_total;
+  if (enter) memcpy(enter, enter_tot, sizeof(int64_t) * ((size_t)nb + 1));
+  free(enter_tot);
+}
+
+/* ------------------------------------------------------------------ */
+/* Update (Section 3.2 "Update Centroids"): mean of the assigned points.*/
+/* A cluster with no point keeps its old centroid (the split follows).  */
+/* ------------------------------------------------------------------ */
+void orc_update(const double *Xr, int64_t n, int32_t d, const int32_t *assign,
+                int32_t k, double *Y, int64_t *counts) {
+  double *sum = (double *)calloc((size_t)k * d, sizeof(double));
+  int64_t i;
+  int32_t c, j;
+  for (c = 0; c < k; ++c) counts[c] = 0;
+  for (i = 0; i < n; ++i) {
+    double *s = sum + (int64_t)assign[i] * d;
+    const double *x = Xr + i * d;
+    counts[assign[i]]++;
+    for (j = 0; j < d; ++j) s[j] += x[j];
+  }
+  for (c = 0; c < k; ++c) {
+    if (counts[c] == 0) continue;
+    for (j = 0; j < d; ++j)
+      Y[(int64_t)c * d + j] = sum[(int64_t)c * d + j] / (double)counts[c];
+  }
+  free(sum);
+}
+
+/* ------------------------------------------------------------------ */
+/* Split of empty clusters (Section 3.2 "Split Centroids").  Empty      */
+/* clusters are visited in increasing index.  The donor is drawn with   */
+/* probability proportional to its size among clusters holding at least */
+/* two points; both copies get a small symmetric perturbation           */
+/*   y_e = y_c * (1 + eps*s),  y_c = y_c * (1 - eps*s),  s_j = (-1)^j   */
+/* and the donor's count is shared floor(n/2) / rest.                   */
+/* Returns the number of clusters re-seeded; pairs (e, c) go to `log`.  */
+/* ------------------------------------------------------------------ */
+int32_t orc_split_empty(double *Y, int64_t *counts, int32_t k, int32_t d,
+                        uint64_t *rng_state, double eps, int32_t *log) {
+  int32_t e, c, j, nsplit = 0;
+  for (e = 0; e < k; ++e) {
+    uint64_t total = 0, r, cum = 0;
+    int32_t donor = -1;
+    if (counts[e] != 0) continue;
+    for (c = 0; c < k; ++c)
+      if (counts[c] >= 2) total += (uint64_t)counts[c];
+    if (total == 0) continue;
+    r = orc_rng_next(rng_state) % total;
+    for (c = 0; c < k; ++c) {
+      if (counts[c] < 2) continue;
+      cum += (uint64_t)counts[c];
+      if (cum > r) {
+        donor = c;
+        break;
+      }
+    }
+    for (j = 0; j < d; ++j) {
+      double s = (j & 1) ? -1.0 : 1.0;
+      double y = Y[(int64_t)donor * d + j];
+      Y[(int64_t)e * d + j] = y * (1.0 + eps * s);
+      Y[(int64_t)donor * d + j] = y * (1.0 - eps * s);
+    }
+    counts[e] = counts[donor] / 2;
+    counts[donor] -= counts[e];
+    if (log) {
+      log[2 * nsplit] = e;
+      log[2 * nsplit + 1] = donor;
+    }
+    nsplit++;
+  }
+  return nsplit;
+}
+
+/* ------------------------------------------------------------------ */
+/* Early Termination by Recall (Section 3.3).                           */
+/* Ground truth: exact top-K neighbours of each query in X by squared   */
+/* L2, closest first, lowest index on ties.                             */
+/* ------------------------------------------------------------------ */
+void orc_ground_truth(const float *X, int64_t n, int32_t d, const float *Q,
+                      int32_t nq, int32_t K, int64_t *gt) {
+  int32_t q;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (q = 0; q < nq; ++q) {
+    double *bd = (double *)malloc(sizeof(double) * (size_t)K);
+    int64_t *bi = (int64_t *)malloc(sizeof(int64_t) * (size_t)K);
+    int32_t cnt = 0, j, p;
+    int64_t i;
+    for (i = 0; i < n; ++i) {
+      double s = 0.0;
+      for (j = 0; j < d; ++j) {
+        double df = (double)Q[(int64_t)q * d + j] - (double)X[i * d + j];
+        s += df * df;
+      }
+      if (cnt == K && !(s < bd[K - 1])) continue;
+      /* insertion keeping (distance, index) ascending */
+      p = cnt < K ? cnt : K - 1;
+      while (p > 0 && bd[p - 1] > s) {
+        bd[p] = bd[p - 1];
+        bi[p] = bi[p - 1];
+        --p;
+      }
+      bd[p] = s;
+      bi[p] = i;
+      if (cnt < K) cnt++;
+    }
+    for (j = 0; j < K; ++j) gt[(int64_t)q * K + j] = j < cnt ? bi[j] : -1;
+    free(bd);
+    free(bi);
+  }
+}
+
+/* Recall@K of an IVF search that probes the nprobe nearest centroids and
+ * scans the probed clusters exhaustively: a true neighbour is found iff its
+ * cluster is probed.  Qr are the queries in the space of Y. */
+double orc_recall(const double *Qr, int32_t nq, int32_t d, const double *Y,
+                  int32_t k, int32_t nprobe, const int64_t *gt, int32_t K,
+                  const int32_t *assign) {
+  int64_t hits = 0, total = 0;
+  int32_t q;
+#pragma omp parallel for schedule(dynamic, 4) reduction(+ : hits, total)
+  for (q = 0; q < nq; ++q) {
+    double *cd = (double *)malloc(sizeof(double) * (size_t)k);
+    char *probed = (char *)calloc((size_t)k, 1);
+    int32_t j, s;
+    for (j = 0; j < k; ++j)
+      cd[j] = sqdist_range(Qr + (int64_t)q * d, Y + (int64_t)j * d, 0, d);
+    for (s = 0; s < nprobe && s < k; ++s) {
+      int32_t bj = -1;
+      for (j = 0; j < k; ++j)
+        if (!probed[j] && (bj < 0 || cd[j] < cd[bj])) bj = j;
+      probed[bj] = 1;
+    }
+    for (j = 0; j < K; ++j) {
+      int64_t id = gt[(int64_t)q * K + j];
+      if (id < 0) continue;
+      total++;
+      if (probed[assign[id]]) hits++;
+    }
+    free(cd);
+    free(probed);
+  }
+  return total ? (double)hits / (double)total : 0.0;
+}
+
+int32_t orc_nprobe(int32_t k, double probe_frac) {
+  int32_t np = (int32_t)floor(probe_frac * (double)k + 0.5);
+  if (np < 1) np = 1;
+  if (np > k) np = k;
+  return np;
+}
+
+/* ------------------------------------------------------------------ */
+/* The whole fit, Algorithm 1 top to bottom.                            */
+/* ------------------------------------------------------------------ */
+typedef struct orc_params {
+  double dprime_frac;    /* 0.125 */
+  double eps0;           /* 2.1; INFINITY disables the statistical test */
+  int32_t tau_group;     /* G; <= 0 means k */
+  int32_t adjust_dprime; /* 1 */
+  double adj_lo, adj_hi, adj_step; /* 0.95 0.97 0.20 */
+  double split_eps;      /* 2^-10 */
+  int32_t final_assign;  /* 1 */
+  /* ETR */
+  int32_t etr;           /* 0 */
+  int32_t nq, topk;      /* queries, K */
+  double probe_frac;     /* 0.01 */
+  double etr_tol;        /* 0.005 */
+  int32_t etr_patience;  /* 2 */
+} orc_params;
+
+typedef struct orc_trace_row {
+  double objective;      /* sum of min distances found by this assignment */
+  double prune_frac;     /* first-test prune fraction (0 for iteration 1) */
+  double recall;         /* -1 when ETR is off */
+  int64_t pruned_first;
+  int64_t nempty;
+  int32_t dprime;        /* d' used by this assignment step */
+  int32_t pad;
+  int64_t enter[32];     /* pairs entering trailing block m; [nb] = completed */
+} orc_trace_row;
+
+void orc_params_default(orc_params *p) {
+  memset(p, 0, sizeof(*p));
+  p->dprime_frac = 0.125;
+  p->eps0 = 2.1;
+  p->tau_group = 0;
+  p->adjust_dprime = 1;
+  p->adj_lo = 0.95;
+  p->adj_hi = 0.97;
+  p->adj_step = 0.20;
+  p->split_eps = 1.0 / 1024.0;
+  p->final_assign = 1;
+  p->etr = 0;
+  p->nq = 1000;
+  p->topk = 10;
+  p->probe_frac = 0.01;
+  p->etr_tol = 0.005;
+  p->etr_patience = 2;
+}
+
+static double sum_d(const double *v, int64_t n) {
+  double s = 0.0;
+  int64_t i;
+  for (i = 0; i < n; ++i) s += v[i];
+  return s;
+}
+
+/*
+ * X        n x d fp32 (original space)
+ * R        d x d fp32 rotation, or NULL for the identity
+ * init_idx k row indices of the initial centroids
+ * Q, gt    ETR queries (nq x d, original space) and their ground truth
+ *          (nq x topk); used only when p->etr != 0
+ * outputs  Y (k x d, original space), Yr (k x d, rotated space; may be NULL),
+ *          assign (n), dist (n), trace (iters + 1 rows; row `iters_run` is
+ *          the final assignment pass when final_assign is set)
+ * returns  number of update steps run (<= iters), negative on error.
+ */
+int32_t orc_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters,
+                uint64_t seed, const orc_params *p, const float *R,
+                const int64_t *init_idx, const float *Q, const int64_t *gt,
+                double *Y, double *Yr_out, int32_t *assign, double *dist,
+                orc_trace_row *trace) {
+  double *Xr = (double *)malloc(sizeof(double) * (size_t)n * d);
+  double *Yr = (double *)malloc(sizeof(double) * (size_t)k * d);
+  double *Qr = NULL;
+  int64_t *counts = (int64_t *)malloc(sizeof(int64_t) * (size_t)k);
+  int32_t G = p->tau_group > 0 ? p->tau_group : k;
+  int32_t dprime, t, c, j, run = 0, streak = 0;
+  double best_recall = -1.0;
+  uint64_t split_rng = orc_rng_stream(seed, 1);
+  int64_t i;
+  if (!Xr || !Yr || !counts) return -2;
+
+  /* Algorithm 1: rotate, initialise, d' */
+  if (R) {
+    orc_rotate(X, n, d, R, Xr);
+  } else {
+    for (i = 0; i < n * d; ++i) Xr[i] = (double)X[i];
+  }
+  for (c = 0; c < k; ++c)
+    for (j = 0; j < d; ++j)
+      Yr[(int64_t)c * d + j] = Xr[init_idx[c] * d + j];
+  dprime = orc_dprime_init(d, p->dprime_frac);
+  if (p->etr) {
+    Qr = (double *)malloc(sizeof(double) * (size_t)p->nq * d);
+    if (R) {
+      orc_rotate(Q, p->nq, d, R, Qr);
+    } else {
+      for (i = 0; i < (int64_t)p->nq * d; ++i) Qr[i] = (double)Q[i];
+    }
+  }
+
+  for (t = 1; t <= iters; ++t) {
+    orc_trace_row *tr = trace ? &trace[t - 1] : NULL;
+    int64_t pf = 0;
+    int64_t enter[33];
+    int32_t nsplit, nempty = 0, stop = 0;
+    double recall = -1.0;
+    memset(enter, 0, sizeof(enter));
+    if (t == 1) {
+      orc_assign_full(Xr, n, d, Yr, k, assign, dist);
+    } else {
+      int32_t *prev = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
+      memcpy(prev, assign, sizeof(int32_t) * (size_t)n);
+      orc_assign_pruned(Xr, n, d, Yr, k, prev, dprime, p->eps0, G, assign,
+                        dist, &pf, enter, NULL);
+      free(prev);
+    }
+    if (p->etr)
+      recall = orc_recall(Qr, p->nq, d, Yr, k, orc_nprobe(k, p->probe_frac),
+                          gt, p->topk, assign);
+    if (tr) {
+      memset(tr, 0, sizeof(*tr));
+      tr->objective = sum_d(dist, n);
+      tr->pruned_first = pf;
+      tr->prune_frac =
+          (t > 1 && k > 1) ? (double)pf / ((double)n * (double)(k - 1)) : 0.0;
+      tr->recall = recall;
+      tr->dprime = t > 1 ? dprime : d;
+      memcpy(tr->enter, enter, sizeof(int64_t) * 32);
+    }
+    /* update + split */
+    orc_update(Xr, n, d, assign, k, Yr, counts);
+    for (c = 0; c < k; ++c)
+      if (counts[c] == 0) nempty++;
+    nsplit = orc_split_empty(Yr, counts, k, d, &split_rng, p->split_eps, NULL);
+    (void)nsplit;
+    if (tr) tr->nempty = nempty;
+    run = t;
+    /* adjust d' (only after an iteration that pruned) */
+    if (t > 1 && p->adjust_dprime && k > 1) {
+      double f = (double)pf / ((double)n * (double)(k - 1));
+      dprime = orc_dprime_adjust(d, dprime, f, p->adj_lo, p->adj_hi,
+                                 p->adj_step);
+    }
+    /* ETR stop rule */
+    if (p->etr) {
+      if (t == 1) {
+        best_recall = recall;
+      } else {
+        if (recall - best_recall <= p->etr_tol)
+          streak++;
+        else
+          streak = 0;
+        if (recall > best_recall) best_recall = recall;
+        if (streak >= p->etr_patience) stop = 1;
+      }
+    }
+    if (stop) break;
+  }
+
+  /* final assignment with the two-phase approach (Section 3.3, last line) */
+  if (p->final_assign && run >= 1) {
+    int64_t pf = 0;
+    int64_t enter[33];
+    int32_t *prev = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
+    memset(enter, 0, sizeof(enter));
+    memcpy(prev, assign, sizeof(int32_t) * (size_t)n);
+    orc_assign_pruned(Xr, n, d, Yr, k, prev, dprime, p->eps0, G, assign, dist,
+                      &pf, enter, NULL);
+    free(prev);
+    if (trace) {
+      orc_trace_row *tr = &trace[run];
+      memset(tr, 0, sizeof(*tr));
+      tr->objective = sum_d(dist, n);
+      tr->pruned_first = pf;
+      tr->prune_frac = k > 1 ? (double)pf / ((double)n * (double)(k - 1)) : 0.0;
+      tr->recall = -1.0;
+      tr->dprime = dprime;
+      memcpy(tr->enter, enter, sizeof(int64_t) * 32);
+    }
+  }
+
+  /* Algorithm 1, last line: centroids back in the original space */
+  if (Yr_out) memcpy(Yr_out, Yr, sizeof(double) * (size_t)k * d);
+  if (R) {
+    orc_unrotate(Yr, k, d, R, Y);
+  } else {
+    memcpy(Y, Yr, sizeof(double) * (size_t)k * d);
+  }
+  free(Xr);
+  free(Yr);
+  free(Qr);
+  free(counts);
+  return run;
+}
