@@ -1,0 +1,186 @@
+/*
+ * skm.h -- C ABI of libskm: the SuperKMeans k-means iteration on one AMD
+ * MI355X (gfx950).  Citations are to the SuperKMeans paper (arxiv 2603.20009).
+ *
+ * Conventions for every entry point
+ *   - Array arguments are DEVICE pointers (hipMalloc'd memory, e.g. the
+ *     storage of a torch tensor), dense row-major, fp32 / int32 / int64 as
+ *     declared, unless the comment says "host".  The params / trace structs
+ *     themselves live in host memory.
+ *   - The caller owns every buffer it passes.  The library allocates and
+ *     frees its own workspace inside the call.
+ *   - Work is enqueued on `params->stream` (a hipStream_t, NULL = the default
+ *     stream) and the call returns after that stream has been synchronised,
+ *     so outputs are complete on return.
+ *   - Return value: 0 on success, a negative SKM_E* code otherwise.  On error
+ *     outputs are unspecified.  No exception crosses this boundary.
+ *   - Thread-compatible, not thread-safe: concurrent calls must use distinct
+ *     streams and distinct buffers.
+ *   - Limits: 16 <= d <= 16384, 1 <= k <= min(n, 2^24), n < 2^31.
+ */
+#ifndef SKM_H_
+#define SKM_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SKM_OK 0
+#define SKM_EINVAL (-1)    /* null pointer, bad shape, k > n, d out of range ... */
+#define SKM_ENOMEM (-2)    /* workspace allocation failed */
+#define SKM_EHIP (-3)      /* a HIP call failed; see skm_last_error() */
+#define SKM_EINTERNAL (-4) /* an internal invariant was violated */
+
+#define SKM_MAX_BLOCKS 32 /* counters kept for at most this many trailing blocks */
+
+/* One row per assignment step (Algorithm 1: iteration 1, iterations 2..n, and
+ * the final assignment pass of Section 3.3 when it is requested). */
+typedef struct skm_trace_row {
+  double objective;    /* sum over points of the squared distance found by this step */
+  double prune_frac;   /* share of (point, centroid != incumbent) pairs cut by the first
+                          test theta(d', tau) (Section 4.8); 0 for iteration 1 */
+  double recall;       /* ETR recall measured with this step's assignment; -1 if ETR is off */
+  int64_t survivors;   /* pairs that passed the first test */
+  int64_t completed;   /* pairs whose distance was finished over all d dimensions */
+  int64_t changed;     /* points whose assignment changed in this step */
+  int64_t nempty;      /* empty clusters found by the update that followed */
+  int32_t dprime;      /* d' used by this step (d for iteration 1) */
+  int32_t nblocks;     /* trailing 64-dim blocks (the last may be shorter) */
+  int64_t enter[SKM_MAX_BLOCKS]; /* pairs that entered trailing block m (only when
+                                    params.block_stats != 0, else zeros) */
+  float ms_tau;        /* stage times from HIP events on the call's stream */
+  float ms_gemm;
+  float ms_prune;
+  float ms_update;
+  float ms_etr;
+  float ms_step;       /* whole step including the update */
+} skm_trace_row;
+
+typedef struct skm_trace {
+  int32_t capacity;    /* in : rows available in `row` (iters + 1 is enough) */
+  int32_t rows;        /* out: rows written */
+  int32_t iters_run;   /* out: update steps performed */
+  int32_t reserved;
+  float ms_rotate;     /* out: X~ = X R */
+  float ms_init;       /* out: centroid initialisation */
+  float ms_etr_gt;     /* out: ETR ground truth (0 when supplied or ETR off) */
+  float ms_unrotate;   /* out: Y = Y~ R^T */
+  float ms_total;      /* out: whole call, device time */
+  float reserved2;
+  skm_trace_row *row;  /* host array, caller-allocated */
+} skm_trace;
+
+/* Hyper-parameters.  Fill with skm_params_default() first. */
+typedef struct skm_params {
+  float dprime_frac;     /* 0.125 : d' = floor(d * frac), kept a multiple of 16 (Algorithm 1) */
+  float eps0;            /* 2.1   : ADSampling's epsilon_0 in theta(t, tau) = tau * min(1, (t/d)(1 + eps0/sqrt(t))^2);
+                                    +inf leaves only the exact bound p_t > tau (then the result is exact Lloyd) */
+  int32_t adjust_dprime; /* 1     : Section 4.8 controller on/off */
+  float adj_lo;          /* 0.95 */
+  float adj_hi;          /* 0.97 */
+  float adj_step;        /* 0.20 */
+  float split_eps;       /* 2^-10 : relative perturbation of a split centroid (Section 3.2) */
+  int32_t final_assign;  /* 1     : run the final two-phase assignment pass (Section 3.3) */
+  int32_t block_stats;   /* 0     : count pairs entering every trailing block (slower) */
+  int32_t rotate;        /* 1     : 0 = treat the input as already rotated (R = I) */
+  const float *R;        /* NULL  : device d x d rotation to use instead of generating one from the seed */
+  const int64_t *init_idx; /* NULL: host array of k row indices to use as initial centroids */
+  /* Early Termination by Recall (Section 3.3) */
+  int32_t etr;           /* 0 */
+  int32_t nq;            /* 1000 : number of queries */
+  int32_t topk;          /* 10   : K of recall@K */
+  float probe_frac;      /* 0.01 : probed share of the centroids */
+  float etr_tol;         /* 0.005 */
+  int32_t etr_patience;  /* 2 */
+  const float *queries;  /* NULL : device nq x d; NULL = sample nq rows of X with the seed */
+  const int64_t *gt;     /* NULL : device nq x topk exact neighbours; NULL = computed by the call */
+  /* plumbing */
+  void *stream;          /* hipStream_t, NULL = default stream */
+  skm_trace *trace;      /* NULL or host struct to fill */
+  int64_t pair_budget;   /* 0 = default (2^29): capacity, in (point, centroid) pairs, of the survivor list;
+                            points are processed in chunks of floor(pair_budget / k) rows */
+} skm_params;
+
+void skm_params_default(skm_params *p);
+
+/*
+ * skm_fit -- Algorithm 1 with default parameters.
+ *   X             device n x d fp32, the points (original space)
+ *   iters         number of k-means iterations (assignment + update), >= 1
+ *   seed          drives the rotation, the initial centroids, splits, ETR sampling
+ *   centroids_out device k x d fp32: the centroids in the ORIGINAL space
+ *                 (Algorithm 1, last line), i.e. the means under the last in-loop
+ *                 assignment
+ *   assign_out    device n int32 or NULL: the final assignment (Section 3.3:
+ *                 one more two-phase assignment against the final centroids)
+ */
+int skm_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed,
+            float *centroids_out, int32_t *assign_out);
+
+/* Same with explicit parameters; dist_out (device n fp32 or NULL) receives the
+ * squared distance of every point to its assigned centroid.  With
+ * params->final_assign == 0, assign_out / dist_out are those of the last
+ * in-loop assignment step. */
+int skm_fit_ex(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed,
+               const skm_params *params, float *centroids_out, int32_t *assign_out, float *dist_out);
+
+/*
+ * skm_assign -- one two-phase assignment step (Section 3.2, "2nd -> n
+ * iteration"; Section 3.3, final assignment) of X against given centroids,
+ * both in the original space; the rotation is generated from seed 0 unless
+ * the _ex form supplies one.
+ *   prev_assign   device n int32 or NULL.  With a previous assignment the
+ *                 initial threshold is the distance to that centroid
+ *                 (Section 3.4); without it the incumbent is the centroid of
+ *                 smallest partial distance on the first d' dimensions.
+ */
+int skm_assign(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k,
+               const int32_t *prev_assign, int32_t *assign_out, float *dist_out);
+
+/* As skm_assign, with parameters (R, eps0, dprime_frac, stream, trace: one row).
+ * dprime > 0 overrides floor(d * dprime_frac); it is rounded to a multiple of 16. */
+int skm_assign_ex(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k,
+                  const int32_t *prev_assign, int32_t dprime, const skm_params *params,
+                  int32_t *assign_out, float *dist_out);
+
+/* Exact assignment over all d dimensions (Algorithm 1, iteration 1): the GEMM
+ * with the ||y||^2 - 2 x.y epilogue and a fused row argmin, then the direct
+ * distance to the winner.  No rotation involved. */
+int skm_assign_exact(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k,
+                     void *stream, int32_t *assign_out, float *dist_out);
+
+/* Centroid update (Section 3.2): per-cluster mean of the assigned rows; empty
+ * clusters keep the row already in `centroids`.  counts_out: device k int32. */
+int skm_update(const float *X, int64_t n, int32_t d, const int32_t *assign, int32_t k,
+               void *stream, float *centroids, int32_t *counts_out);
+
+/* Random orthogonal d x d matrix (Algorithm 1, first line) written to device
+ * memory R_out; Haar-distributed (Gram-Schmidt of a seeded Gaussian matrix). */
+int skm_make_rotation(int32_t d, uint64_t seed, void *stream, float *R_out);
+
+/* out = X R (n x d), the rotation GEMM (Algorithm 1, second line); with
+ * transpose != 0 computes X R^T (the un-rotation of the last line). */
+int skm_rotate(const float *X, int64_t n, int32_t d, const float *R, int32_t transpose,
+               void *stream, float *out);
+
+/* k distinct row indices in [0, n), host output: the library's own
+ * initialisation draw (Section 3.1), exposed so that it can be compared. */
+int skm_sample_rows(uint64_t seed, int64_t n, int32_t k, int64_t *idx_out_host);
+
+/* theta(t, tau) / tau for d total dimensions (the pruning ratio). */
+float skm_theta_ratio(int32_t d, int32_t t, float eps0);
+
+/* d' rules: initial value and the Section 4.8 adjustment. */
+int32_t skm_dprime_init(int32_t d, float frac);
+int32_t skm_dprime_adjust(int32_t d, int32_t dprime, double prune_frac, float lo, float hi, float step);
+
+const char *skm_strerror(int rc);
+const char *skm_last_error(void); /* text of the last failure on this thread */
+const char *skm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKM_H_ */

@@ -1,0 +1,943 @@
+// C ABI of libskm and the host-side driver of Algorithm 1 (SuperKMeans): every arithmetic step on the
+// points runs in the HIP kernels of this library; the host keeps scalars only (d', prune fraction,
+// recall history, the list of empty clusters and the integer PRNG that re-seeds them).
+#include "../../include/skm.h"
+#include "skm_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <string>
+#include <thread>
+#include <vector>
+
+using namespace skm;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int rc, const char *what) {
+  g_last_error = what;
+  return rc;
+}
+int fail_hip(hipError_t e, const char *where) {
+  g_last_error = std::string(where) + ": " + hipGetErrorString(e);
+  return SKM_EHIP;
+}
+#define HIPCHK(expr)                                              \
+  do {                                                            \
+    hipError_t e__ = (expr);                                      \
+    if (e__ != hipSuccess) return fail_hip(e__, #expr);           \
+  } while (0)
+
+// device allocations released when the call ends, whichever way it ends
+struct Pool {
+  std::vector<void *> ptrs;
+  ~Pool() {
+    for (void *p : ptrs) (void)hipFree(p);
+  }
+  template <typename T>
+  hipError_t get(T **out, size_t count) {
+    void *p = nullptr;
+    size_t bytes = std::max<size_t>(count, 1) * sizeof(T);
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+      *out = nullptr;
+      return e;
+    }
+    ptrs.push_back(p);
+    *out = static_cast<T *>(p);
+    return hipSuccess;
+  }
+};
+
+struct Events {
+  std::vector<hipEvent_t> ev;
+  ~Events() {
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+  }
+  hipEvent_t next() {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    ev.push_back(e);
+    return e;
+  }
+};
+
+// Records (stage, event) marks on the stream; after a synchronisation the time between two
+// consecutive marks is charged to the stage of the later mark.
+enum Stage { ST_NONE = 0, ST_TAU, ST_GEMM, ST_PRUNE, ST_UPDATE, ST_ETR, ST_COUNT };
+struct StageTimer {
+  Events pool;
+  std::vector<std::pair<int, hipEvent_t>> marks;
+  size_t used = 0;
+  hipStream_t st;
+  bool on;
+  StageTimer(hipStream_t s, bool enable) : st(s), on(enable) {}
+  void mark(int stage) {
+    if (!on) return;
+    hipEvent_t e;
+    if (used < pool.ev.size()) e = pool.ev[used];
+    else e = pool.next();
+    if (!e) return;
+    ++used;
+    (void)hipEventRecord(e, st);
+    marks.push_back({stage, e});
+  }
+  // call after the stream is synchronised
+  void collect(float ms[ST_COUNT], float *total) {
+    for (int s = 0; s < ST_COUNT; ++s) ms[s] = 0.f;
+    *total = 0.f;
+    for (size_t i = 1; i < marks.size(); ++i) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, marks[i - 1].second, marks[i].second) == hipSuccess) {
+        ms[marks[i].first] += t;
+        *total += t;
+      }
+    }
+    marks.clear();
+    used = 0;
+  }
+};
+
+// ---------------------------------------------------------------- integer PRNG (splitmix64)
+struct Rng {
+  uint64_t s;
+  uint64_t next() {
+    s += 0x9E3779B97F4A7C15ULL;
+    uint64_t z = s;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+  }
+  double uniform() { return (double)(next() >> 11) * (1.0 / 9007199254740992.0); }
+};
+Rng rng_stream(uint64_t seed, uint64_t stream) { return Rng{seed + stream * 0xD1342543DE82EF95ULL}; }
+enum { STREAM_INIT = 0, STREAM_SPLIT = 1, STREAM_QUERIES = 2, STREAM_ROTATION = 3 };
+
+// k distinct indices of [0, n): the first k steps of a Fisher-Yates shuffle of the identity
+void sample_rows(uint64_t seed, uint64_t stream, int64_t n, int32_t k, int64_t *out) {
+  std::vector<int64_t> perm((size_t)n);
+  for (int64_t i = 0; i < n; ++i) perm[(size_t)i] = i;
+  Rng r = rng_stream(seed, stream);
+  for (int32_t i = 0; i < k; ++i) {
+    const int64_t j = i + (int64_t)(r.next() % (uint64_t)(n - i));
+    std::swap(perm[(size_t)i], perm[(size_t)j]);
+    out[i] = perm[(size_t)i];
+  }
+}
+
+// ---------------------------------------------------------------- scalar rules
+double theta_ratio(int32_t d, int32_t t, double eps0) {
+  if (t >= d) return 1.0;
+  if (t <= 0) return 0.0;
+  const double s = 1.0 + eps0 / std::sqrt((double)t);
+  const double r = (double)t / (double)d * s * s;
+  return r < 1.0 ? r : 1.0;
+}
+int32_t snap16(double v, int32_t d) {
+  int32_t top = d / 16 * 16;
+  if (top < 16) top = 16;
+  int32_t r = (int32_t)std::floor(v / 16.0 + 0.5) * 16;
+  return std::min(std::max(r, 16), top);
+}
+int32_t dprime_init(int32_t d, double frac) { return snap16(std::floor((double)d * frac), d); }
+int32_t dprime_adjust(int32_t d, int32_t dp, double f, double lo, double hi, double step) {
+  if (f > hi) return snap16((double)dp - step * (double)dp, d);
+  if (f < lo) return snap16((double)dp + step * (double)dp, d);
+  return dp;
+}
+int32_t nprobe_of(int32_t k, double frac) {
+  int32_t np = (int32_t)std::floor(frac * (double)k + 0.5);
+  return std::min(std::max(np, 1), k);
+}
+
+// ---------------------------------------------------------------- rotation matrix (host, fp64)
+template <typename F>
+void parallel_for(int n, F f) {
+  unsigned hw = std::thread::hardware_concurrency();
+  int nt = (int)std::min<unsigned>(hw ? hw : 4u, 16u);
+  nt = std::min(nt, n);
+  if (nt <= 1) {
+    for (int i = 0; i < n; ++i) f(i);
+    return;
+  }
+  std::vector<std::thread> th;
+  for (int t = 0; t < nt; ++t)
+    th.emplace_back([=]() {
+      for (int i = t; i < n; i += nt) f(i);
+    });
+  for (auto &x : th) x.join();
+}
+
+double dot4(const double *a, const double *b, int n) {
+  double s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+  int j = 0;
+  for (; j + 4 <= n; j += 4) {
+    s0 += a[j] * b[j];
+    s1 += a[j + 1] * b[j + 1];
+    s2 += a[j + 2] * b[j + 2];
+    s3 += a[j + 3] * b[j + 3];
+  }
+  for (; j < n; ++j) s0 += a[j] * b[j];
+  return (s0 + s1) + (s2 + s3);
+}
+
+// Rows of a seeded Gaussian matrix, orthonormalised by Gram-Schmidt (twice): a Haar-distributed
+// orthogonal matrix.  Panels of rows are first cleared of all finished rows (independent per row,
+// threaded), then orthonormalised among themselves.
+void make_rotation_host(int32_t d, uint64_t seed, std::vector<float> &out) {
+  std::vector<double> Q((size_t)d * d);
+  Rng r = rng_stream(seed, STREAM_ROTATION);
+  for (size_t i = 0; i + 1 < Q.size() + 1; i += 2) {  // Box-Muller pairs
+    double u1 = r.uniform(), u2 = r.uniform();
+    if (u1 < 1e-300) u1 = 1e-300;
+    const double m = std::sqrt(-2.0 * std::log(u1));
+    Q[i] = m * std::cos(6.283185307179586 * u2);
+    if (i + 1 < Q.size()) Q[i + 1] = m * std::sin(6.283185307179586 * u2);
+  }
+  const int PANEL = 32;
+  for (int p0 = 0; p0 < d; p0 += PANEL) {
+    const int p1 = std::min(d, p0 + PANEL);
+    if (p0 > 0)
+      parallel_for(p1 - p0, [&](int ri) {
+        double *v = &Q[(size_t)(p0 + ri) * d];
+        std::vector<double> c((size_t)p0);
+        for (int pass = 0; pass < 2; ++pass) {
+          for (int j = 0; j < p0; ++j) c[(size_t)j] = dot4(&Q[(size_t)j * d], v, d);
+          for (int j = 0; j < p0; ++j) {
+            const double cj = c[(size_t)j];
+            const double *qj = &Q[(size_t)j * d];
+            for (int t = 0; t < d; ++t) v[t] -= cj * qj[t];
+          }
+        }
+      });
+    for (int i = p0; i < p1; ++i) {
+      double *v = &Q[(size_t)i * d];
+      for (int pass = 0; pass < 2; ++pass)
+        for (int j = p0; j < i; ++j) {
+          const double *qj = &Q[(size_t)j * d];
+          const double cj = dot4(qj, v, d);
+          for (int t = 0; t < d; ++t) v[t] -= cj * qj[t];
+        }
+      const double nrm = std::sqrt(dot4(v, v, d));
+      for (int t = 0; t < d; ++t) v[t] /= nrm;
+    }
+  }
+  out.resize((size_t)d * d);
+  for (size_t i = 0; i < out.size(); ++i) out[i] = (float)Q[i];
+}
+
+inline int32_t round_up(int32_t v, int32_t m) { return (v + m - 1) / m * m; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(const void *X, int64_t n, int32_t d, int32_t k) {
+  if (!X) return fail(SKM_EINVAL, "null input pointer");
+  if (n < 1 || n >= (int64_t)1 << 31) return fail(SKM_EINVAL, "n out of range [1, 2^31)");
+  if (d < 16 || d > 16384) return fail(SKM_EINVAL, "d out of range [16, 16384]");
+  if (k < 1 || k > n || k > (1 << 24)) return fail(SKM_EINVAL, "k out of range [1, min(n, 2^24)]");
+  return SKM_OK;
+}
+
+// ---------------------------------------------------------------- one fit / assign context
+struct Ctx {
+  hipStream_t st = nullptr;
+  Pool pool;
+  int64_t n = 0;
+  int32_t d = 0, ds = 0, k = 0;
+  const float *Xr = nullptr;  // rotated (or original) points, row stride ldx, padded to ds
+  int64_t ldx = 0;
+  float *Y = nullptr;         // centroids k x ds (rotated space)
+  float *Ypdx = nullptr;
+  float *ynorm = nullptr;
+  float *tau = nullptr, *xn = nullptr, *thr = nullptr, *dist = nullptr;
+  unsigned long long *best = nullptr;
+  int32_t *assign = nullptr, *prev = nullptr;
+  Pair *pairs = nullptr;
+  int64_t pair_cap = 0, chunk_rows = 0;
+  int32_t nchunks = 0;
+  unsigned int *counters = nullptr;  // [nchunks] pair counts, then [1] overflow flag
+  float *ratio_dev = nullptr;        // [kMaxBlocks]
+  float ratio_host[kMaxBlocks];      // staging for ratio_dev (must outlive the async copy)
+  unsigned long long *scal = nullptr;  // [0] completed, [1] changed, [2..] enter[kMaxBlocks]
+  double *obj_partial = nullptr, *obj = nullptr;
+  UpdateWs up{};
+  int32_t *split_dev = nullptr;
+  bool block_stats = false;
+
+  int alloc_common(int64_t pair_budget, bool need_update) {
+    HIPCHK(pool.get(&Y, (size_t)k * ds));
+    const int32_t nbmax = (ds - 16 + kBlockDims - 1) / kBlockDims + 1;
+    HIPCHK(pool.get(&Ypdx, (size_t)nbmax * k * kBlockDims));
+    HIPCHK(pool.get(&ynorm, (size_t)k));
+    HIPCHK(pool.get(&tau, (size_t)n));
+    HIPCHK(pool.get(&xn, (size_t)n));
+    HIPCHK(pool.get(&thr, (size_t)n));
+    HIPCHK(pool.get(&dist, (size_t)n));
+    HIPCHK(pool.get(&best, (size_t)n));
+    HIPCHK(pool.get(&assign, (size_t)n));
+    HIPCHK(pool.get(&prev, (size_t)n));
+    if (pair_budget <= 0) pair_budget = (int64_t)1 << 29;
+    chunk_rows = std::max<int64_t>(pair_budget / k, 128);
+    chunk_rows = std::min<int64_t>(chunk_rows / 128 * 128, (n + 127) / 128 * 128);
+    nchunks = (int32_t)((n + chunk_rows - 1) / chunk_rows);
+    pair_cap = std::min<int64_t>(chunk_rows, n) * k;
+    if (pair_cap >= ((int64_t)1 << 32)) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
+    HIPCHK(pool.get(&pairs, (size_t)pair_cap));
+    HIPCHK(pool.get(&counters, (size_t)nchunks + 1));
+    HIPCHK(pool.get(&ratio_dev, (size_t)kMaxBlocks));
+    HIPCHK(pool.get(&scal, (size_t)2 + kMaxBlocks));
+    HIPCHK(pool.get(&obj_partial, (size_t)finalize_blocks(n)));
+    HIPCHK(pool.get(&obj, 1));
+    HIPCHK(pool.get(&up.cnt, (size_t)k));
+    if (need_update) {
+      HIPCHK(pool.get(&up.off, (size_t)k + 1));
+      HIPCHK(pool.get(&up.cursor, (size_t)k));
+      HIPCHK(pool.get(&up.segoff, (size_t)k + 1));
+      HIPCHK(pool.get(&up.order, (size_t)n));
+      up.max_segments = update_max_segments(n, k);
+      HIPCHK(pool.get(&up.partial, (size_t)up.max_segments * ds));
+      HIPCHK(pool.get(&split_dev, (size_t)2 * k));
+    }
+    return SKM_OK;
+  }
+};
+
+struct StepStats {
+  double objective = 0;
+  int64_t survivors = 0, completed = 0, changed = 0;
+  int64_t enter[SKM_MAX_BLOCKS] = {0};
+  int32_t dprime = 0, nblocks = 0;
+  bool pruned = false;  // false for the exact step of iteration 1
+};
+
+// Iteration 1 of Algorithm 1: exact assignment over all dims.  Leaves assign, dist, cluster sizes.
+int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
+  tm.mark(ST_NONE);
+  HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, c.ds, c.ynorm, 0, 0, nullptr, c.st));
+  HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
+  GemmOperands g{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, c.ds};
+  HIPCHK(gemm_argmin(g, c.ynorm, c.best, c.st));
+  tm.mark(ST_GEMM);
+  // winners -> direct squared distances (also the objective of this step)
+  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, nullptr, nullptr, nullptr, nullptr, c.st));
+  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.assign, 0, 0.f, nullptr, nullptr, nullptr, c.best, c.st));
+  HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
+  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (2 + kMaxBlocks), c.st));
+  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, nullptr, c.st));
+  HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
+  tm.mark(ST_TAU);
+  double obj = 0;
+  HIPCHK(hipMemcpyAsync(&obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipStreamSynchronize(c.st));
+  ss = StepStats();
+  ss.objective = obj;
+  ss.dprime = c.d;
+  ss.changed = c.n;
+  return SKM_OK;
+}
+
+// Iterations >= 2 of Algorithm 1: partial GEMM + first test, progressive pruning, argmin.
+// On entry c.prev holds the incumbents (c.assign is overwritten); have_prev = false seeds the
+// incumbent with the centroid of smallest partial distance.
+int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_prev, StepStats &ss) {
+  const int32_t nb = (c.d - dprime + kBlockDims - 1) / kBlockDims;
+  if (nb > kMaxBlocks) return fail(SKM_EINTERNAL, "too many trailing blocks");
+  tm.mark(ST_NONE);
+  HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, dprime, c.ynorm, dprime, nb, c.Ypdx, c.st));
+  float *ratio = c.ratio_host;
+  for (int m = 0; m < nb; ++m) ratio[m] = (float)theta_ratio(c.d, std::min(c.d, dprime + kBlockDims * (m + 1)), eps0);
+  if (nb > 0) HIPCHK(hipMemcpyAsync(c.ratio_dev, ratio, sizeof(float) * (size_t)nb, hipMemcpyHostToDevice, c.st));
+  const float ratio0 = (float)theta_ratio(c.d, dprime, eps0);
+  if (!have_prev) {
+    HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
+    GemmOperands g0{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, dprime};
+    HIPCHK(gemm_argmin(g0, c.ynorm, c.best, c.st));
+    HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, nullptr, nullptr, c.st));
+    tm.mark(ST_GEMM);
+  }
+  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, dprime, ratio0, c.tau, c.xn, c.thr, c.best, c.st));
+  HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * ((size_t)c.nchunks + 1), c.st));
+  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (2 + kMaxBlocks), c.st));
+  HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
+  tm.mark(ST_TAU);
+  for (int32_t ch = 0; ch < c.nchunks; ++ch) {
+    const int64_t r0 = (int64_t)ch * c.chunk_rows;
+    const int64_t rows = std::min<int64_t>(c.chunk_rows, c.n - r0);
+    GemmOperands g{c.Xr + r0 * c.ldx, c.ldx, (int32_t)rows, c.Y, c.ds, c.k, dprime};
+    FilterArgs f{c.ynorm, c.thr, c.xn, c.tau, c.prev, r0, c.pairs, c.counters + ch, (unsigned int)c.pair_cap,
+                 c.counters + c.nchunks};
+    HIPCHK(gemm_filter(g, f, c.st));
+    tm.mark(ST_GEMM);
+    PruneArgs pa{c.pairs, c.counters + ch, c.Xr, c.ldx, c.Ypdx, c.k, dprime, c.ds, nb, c.ratio_dev, c.best,
+                 c.scal + 0, c.block_stats ? c.scal + 2 : nullptr};
+    HIPCHK(launch_prune(pa, c.st));
+    tm.mark(ST_PRUNE);
+  }
+  HIPCHK(launch_finalize_assign(c.best, c.prev, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, c.scal + 1, c.st));
+  HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
+  tm.mark(ST_PRUNE);
+  std::vector<unsigned int> cnt_h((size_t)c.nchunks + 1);
+  std::vector<unsigned long long> scal_h(2 + kMaxBlocks);
+  double obj = 0;
+  HIPCHK(hipMemcpyAsync(cnt_h.data(), c.counters, sizeof(unsigned int) * cnt_h.size(), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(scal_h.data(), c.scal, sizeof(unsigned long long) * scal_h.size(), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(&obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipStreamSynchronize(c.st));
+  if (cnt_h[(size_t)c.nchunks] != 0) return fail(SKM_EINTERNAL, "survivor list overflow");
+  ss = StepStats();
+  for (int32_t ch = 0; ch < c.nchunks; ++ch) ss.survivors += cnt_h[(size_t)ch];
+  ss.completed = (int64_t)scal_h[0];
+  ss.changed = (int64_t)scal_h[1];
+  for (int m = 0; m < std::min<int>(nb, SKM_MAX_BLOCKS); ++m) ss.enter[m] = (int64_t)scal_h[2 + (size_t)m];
+  ss.objective = obj;
+  ss.dprime = dprime;
+  ss.nblocks = nb;
+  ss.pruned = true;
+  return SKM_OK;
+}
+
+// Update + split of empty clusters (Section 3.2).  c.up.cnt must hold the cluster sizes of c.assign.
+int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t *nempty_out) {
+  HIPCHK(launch_update(c.Xr, c.ldx, c.n, c.ds, c.assign, c.k, c.up, c.Y, c.ds, c.st));
+  std::vector<int32_t> cnt((size_t)c.k);
+  HIPCHK(hipMemcpyAsync(cnt.data(), c.up.cnt, sizeof(int32_t) * cnt.size(), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipStreamSynchronize(c.st));
+  int64_t nempty = 0;
+  for (int32_t v : cnt) nempty += (v == 0);
+  *nempty_out = nempty;
+  if (nempty > 0) {
+    // empty clusters in increasing index; donor drawn with probability proportional to its size
+    // among clusters of at least two points; the donor's points are shared floor(n/2) / rest
+    std::vector<int32_t> pairs;
+    for (int32_t e = 0; e < c.k; ++e) {
+      if (cnt[(size_t)e] != 0) continue;
+      uint64_t total = 0;
+      for (int32_t v : cnt)
+        if (v >= 2) total += (uint64_t)v;
+      if (total == 0) continue;
+      const uint64_t r = split_rng.next() % total;
+      uint64_t cum = 0;
+      int32_t donor = -1;
+      for (int32_t j = 0; j < c.k; ++j) {
+        if (cnt[(size_t)j] < 2) continue;
+        cum += (uint64_t)cnt[(size_t)j];
+        if (cum > r) {
+          donor = j;
+          break;
+        }
+      }
+      cnt[(size_t)e] = cnt[(size_t)donor] / 2;
+      cnt[(size_t)donor] -= cnt[(size_t)e];
+      pairs.push_back(e);
+      pairs.push_back(donor);
+    }
+    if (!pairs.empty()) {
+      HIPCHK(hipMemcpyAsync(c.split_dev, pairs.data(), sizeof(int32_t) * pairs.size(), hipMemcpyHostToDevice, c.st));
+      HIPCHK(launch_split(c.Y, c.ds, c.d, c.split_dev, (int32_t)(pairs.size() / 2), split_eps, c.st));
+      HIPCHK(hipStreamSynchronize(c.st));  // `pairs` must outlive the copy
+    }
+  }
+  tm.mark(ST_UPDATE);
+  return SKM_OK;
+}
+
+void fill_row(skm_trace_row &r, const StepStats &ss, int64_t n, int32_t k, int64_t nempty, double recall,
+              const float ms[ST_COUNT], float total) {
+  std::memset(&r, 0, sizeof(r));
+  r.objective = ss.objective;
+  r.prune_frac = (ss.pruned && k > 1) ? 1.0 - (double)ss.survivors / ((double)n * (double)(k - 1)) : 0.0;
+  r.recall = recall;
+  r.survivors = ss.survivors;
+  r.completed = ss.completed;
+  r.changed = ss.changed;
+  r.nempty = nempty;
+  r.dprime = ss.dprime;
+  r.nblocks = ss.nblocks;
+  for (int m = 0; m < SKM_MAX_BLOCKS; ++m) r.enter[m] = ss.enter[m];
+  r.ms_tau = ms[ST_TAU];
+  r.ms_gemm = ms[ST_GEMM];
+  r.ms_prune = ms[ST_PRUNE];
+  r.ms_update = ms[ST_UPDATE];
+  r.ms_etr = ms[ST_ETR];
+  r.ms_step = total;
+}
+
+// Rotation buffers: Rp = R padded to row stride ds, Rtp = R^T padded likewise (both d rows).
+struct Rot {
+  float *Rp = nullptr, *Rtp = nullptr;
+};
+int setup_rotation(Pool &pool, hipStream_t st, int32_t d, int32_t ds, const float *R_dev, uint64_t seed, Rot &rot) {
+  float *Rown = nullptr;
+  if (!R_dev) {
+    std::vector<float> Rh;
+    make_rotation_host(d, seed, Rh);
+    HIPCHK(pool.get(&Rown, (size_t)d * d));
+    HIPCHK(hipMemcpyAsync(Rown, Rh.data(), sizeof(float) * Rh.size(), hipMemcpyHostToDevice, st));
+    HIPCHK(hipStreamSynchronize(st));
+    R_dev = Rown;
+  }
+  HIPCHK(pool.get(&rot.Rp, (size_t)d * ds));
+  HIPCHK(pool.get(&rot.Rtp, (size_t)d * ds));
+  HIPCHK(launch_pad_copy(R_dev, d, d, d, rot.Rp, ds, ds, 0, st));
+  HIPCHK(launch_pad_copy(R_dev, d, d, d, rot.Rtp, ds, ds, 1, st));
+  return SKM_OK;
+}
+// out (rows x ds, zero padded) = in (rows x d, stride ldin) * R
+int rotate_into(const float *in, int64_t ldin, int64_t rows, int32_t d, int32_t ds, const Rot &rot, float *out,
+                hipStream_t st) {
+  GemmOperands g{in, ldin, (int32_t)rows, rot.Rtp, ds, d, d};
+  HIPCHK(gemm_store(g, out, ds, ds, 1.f, 0.f, st));
+  return SKM_OK;
+}
+
+int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params *pp,
+             float *centroids_out, int32_t *assign_out, float *dist_out) {
+  int rc = check_shape(X, n, d, k);
+  if (rc) return rc;
+  if (!centroids_out) return fail(SKM_EINVAL, "centroids_out is null");
+  if (iters < 1) return fail(SKM_EINVAL, "iters must be >= 1");
+  skm_params p;
+  if (pp) p = *pp; else skm_params_default(&p);
+  if (!(p.dprime_frac > 0.f && p.dprime_frac <= 1.f)) return fail(SKM_EINVAL, "dprime_frac out of (0, 1]");
+  if (!(p.eps0 >= 0.f)) return fail(SKM_EINVAL, "eps0 must be >= 0");
+  skm_trace *tr = p.trace;
+  if (tr && (!tr->row || tr->capacity < 1)) return fail(SKM_EINVAL, "trace without rows");
+
+  Ctx c;
+  c.st = (hipStream_t)p.stream;
+  c.n = n; c.d = d; c.k = k;
+  c.ds = round_up(d, 16);
+  c.block_stats = p.block_stats != 0;
+  StageTimer tm(c.st, true);
+  Events evs;
+  hipEvent_t e_begin = evs.next(), e_rot = evs.next(), e_init = evs.next(), e_end0 = evs.next(), e_end = evs.next();
+  hipEvent_t e_gt0 = evs.next(), e_gt1 = evs.next();
+  if (!e_begin || !e_rot || !e_init || !e_end0 || !e_end || !e_gt0 || !e_gt1) return fail(SKM_EHIP, "hipEventCreate failed");
+  HIPCHK(hipEventRecord(e_begin, c.st));
+
+  // ---- Algorithm 1: R, X~ = X R
+  Rot rot;
+  float *Xr_own = nullptr;
+  if (p.rotate) {
+    rc = setup_rotation(c.pool, c.st, d, c.ds, p.R, seed, rot);
+    if (rc) return rc;
+    HIPCHK(c.pool.get(&Xr_own, (size_t)n * c.ds));
+    rc = rotate_into(X, d, n, d, c.ds, rot, Xr_own, c.st);
+    if (rc) return rc;
+    c.Xr = Xr_own; c.ldx = c.ds;
+  } else if (d == c.ds && aligned16(X)) {
+    c.Xr = X; c.ldx = d;
+  } else {
+    HIPCHK(c.pool.get(&Xr_own, (size_t)n * c.ds));
+    HIPCHK(launch_pad_copy(X, d, n, d, Xr_own, c.ds, c.ds, 0, c.st));
+    c.Xr = Xr_own; c.ldx = c.ds;
+  }
+  HIPCHK(hipEventRecord(e_rot, c.st));
+  rc = c.alloc_common(p.pair_budget, true);
+  if (rc) return rc;
+
+  // ---- InitCentroids: k distinct rows of X~
+  {
+    std::vector<int64_t> idx((size_t)k);
+    if (p.init_idx) {
+      for (int32_t i = 0; i < k; ++i) {
+        idx[(size_t)i] = p.init_idx[i];
+        if (idx[(size_t)i] < 0 || idx[(size_t)i] >= n) return fail(SKM_EINVAL, "init_idx out of range");
+      }
+    } else {
+      sample_rows(seed, STREAM_INIT, n, k, idx.data());
+    }
+    int64_t *idx_dev = nullptr;
+    HIPCHK(c.pool.get(&idx_dev, (size_t)k));
+    HIPCHK(hipMemcpyAsync(idx_dev, idx.data(), sizeof(int64_t) * idx.size(), hipMemcpyHostToDevice, c.st));
+    HIPCHK(launch_gather_rows(c.Xr, c.ldx, c.ds, idx_dev, k, c.Y, c.ds, c.ds, c.st));
+    HIPCHK(hipStreamSynchronize(c.st));
+  }
+  HIPCHK(hipEventRecord(e_init, c.st));
+
+  // ---- ETR set-up (Section 3.3): queries, ground truth, rotated queries
+  float *Qr = nullptr, *Sq = nullptr, *ynorm_full = nullptr;
+  unsigned long long *gt_keys = nullptr, *etr_scal = nullptr;
+  int32_t nprobe = 0;
+  HIPCHK(hipEventRecord(e_gt0, c.st));
+  if (p.etr) {
+    if (p.nq < 1 || p.topk < 1 || p.topk > 256) return fail(SKM_EINVAL, "ETR: nq >= 1 and 1 <= topk <= 256 required");
+    nprobe = nprobe_of(k, p.probe_frac);
+    if (nprobe > kMaxProbe) return fail(SKM_EINVAL, "ETR: probe_frac * k exceeds 8192");
+    const float *Q = p.queries;
+    float *Qown = nullptr;
+    if (!Q) {
+      if (p.nq > n) return fail(SKM_EINVAL, "ETR: nq > n");
+      std::vector<int64_t> qi((size_t)p.nq);
+      sample_rows(seed, STREAM_QUERIES, n, p.nq, qi.data());
+      int64_t *qi_dev = nullptr;
+      HIPCHK(c.pool.get(&qi_dev, (size_t)p.nq));
+      HIPCHK(c.pool.get(&Qown, (size_t)p.nq * d));
+      HIPCHK(hipMemcpyAsync(qi_dev, qi.data(), sizeof(int64_t) * qi.size(), hipMemcpyHostToDevice, c.st));
+      HIPCHK(launch_gather_rows(X, d, d, qi_dev, p.nq, Qown, d, d, c.st));
+      HIPCHK(hipStreamSynchronize(c.st));
+      Q = Qown;
+    }
+    HIPCHK(c.pool.get(&gt_keys, (size_t)p.nq * p.topk));
+    if (p.gt) {
+      HIPCHK(launch_index_to_keys(p.gt, (int64_t)p.nq * p.topk, gt_keys, c.st));
+    } else {
+      // exact top-K of every query over X (original space): score GEMM in column chunks + selection
+      float *xnorm = nullptr, *S = nullptr;
+      const int64_t colchunk = std::min<int64_t>(n, 1 << 16);
+      HIPCHK(c.pool.get(&xnorm, (size_t)n));
+      HIPCHK(c.pool.get(&S, (size_t)p.nq * colchunk));
+      HIPCHK(launch_row_norms(X, d, n, d, xnorm, c.st));
+      HIPCHK(launch_fill_u64(gt_keys, (int64_t)p.nq * p.topk, ~0ull, c.st));
+      for (int64_t c0 = 0; c0 < n; c0 += colchunk) {
+        const int64_t m = std::min<int64_t>(colchunk, n - c0);
+        GemmOperands g{Q, d, p.nq, X + c0 * d, d, (int32_t)m, d};
+        HIPCHK(gemm_store(g, S, colchunk, (int32_t)m, 1.f, 0.f, c.st));
+        HIPCHK(launch_topk_merge(S, colchunk, p.nq, (int32_t)m, c0, xnorm, p.topk, gt_keys, c.st));
+      }
+    }
+    HIPCHK(c.pool.get(&Qr, (size_t)p.nq * c.ds));
+    if (p.rotate) {
+      rc = rotate_into(Q, d, p.nq, d, c.ds, rot, Qr, c.st);
+      if (rc) return rc;
+    } else {
+      HIPCHK(launch_pad_copy(Q, d, p.nq, d, Qr, c.ds, c.ds, 0, c.st));
+    }
+    HIPCHK(c.pool.get(&Sq, (size_t)p.nq * k));
+    HIPCHK(c.pool.get(&ynorm_full, (size_t)k));
+    HIPCHK(c.pool.get(&etr_scal, 2));
+  }
+  HIPCHK(hipEventRecord(e_gt1, c.st));
+
+  int32_t dprime = dprime_init(d, p.dprime_frac);
+  Rng split_rng = rng_stream(seed, STREAM_SPLIT);
+  int32_t run = 0, rows = 0, streak = 0;
+  double best_recall = -1.0;
+  // recall of (current centroids, current assignment): Section 3.3
+  auto measure_recall = [&](double *out) -> int {
+    HIPCHK(launch_prep_centroids(c.Y, c.ds, k, c.ds, c.ds, ynorm_full, 0, 0, nullptr, c.st));
+    GemmOperands g{Qr, c.ds, p.nq, c.Y, c.ds, k, c.ds};
+    HIPCHK(gemm_store(g, Sq, k, k, 1.f, 0.f, c.st));
+    HIPCHK(hipMemsetAsync(etr_scal, 0, 2 * sizeof(unsigned long long), c.st));
+    HIPCHK(launch_recall_scores(Sq, k, p.nq, k, ynorm_full, nprobe, gt_keys, p.topk, c.assign, etr_scal, etr_scal + 1,
+                                c.st));
+    unsigned long long h[2] = {0, 0};
+    HIPCHK(hipMemcpyAsync(h, etr_scal, sizeof(h), hipMemcpyDeviceToHost, c.st));
+    HIPCHK(hipStreamSynchronize(c.st));
+    *out = h[1] ? (double)h[0] / (double)h[1] : 0.0;
+    return SKM_OK;
+  };
+
+  for (int32_t t = 1; t <= iters; ++t) {
+    StepStats ss;
+    if (t == 1) {
+      rc = step_exact(c, tm, ss);
+    } else {
+      std::swap(c.assign, c.prev);
+      rc = step_pruned(c, tm, dprime, (double)p.eps0, true, ss);
+    }
+    if (rc) return rc;
+    double recall = -1.0;
+    if (p.etr) {
+      rc = measure_recall(&recall);
+      if (rc) return rc;
+      tm.mark(ST_ETR);
+    }
+    int64_t nempty = 0;
+    rc = step_update(c, tm, split_rng, p.split_eps, &nempty);
+    if (rc) return rc;
+    HIPCHK(hipStreamSynchronize(c.st));
+    float ms[ST_COUNT], total;
+    tm.collect(ms, &total);
+    run = t;
+    if (tr && rows < tr->capacity) fill_row(tr->row[rows], ss, n, k, nempty, recall, ms, total);
+    ++rows;
+    if (t > 1 && p.adjust_dprime && k > 1) {
+      const double f = 1.0 - (double)ss.survivors / ((double)n * (double)(k - 1));
+      dprime = dprime_adjust(d, dprime, f, p.adj_lo, p.adj_hi, p.adj_step);
+    }
+    bool stop = false;
+    if (p.etr) {
+      if (t == 1) {
+        best_recall = recall;
+      } else {
+        if (recall - best_recall <= (double)p.etr_tol) ++streak; else streak = 0;
+        if (recall > best_recall) best_recall = recall;
+        if (streak >= p.etr_patience) stop = true;
+      }
+    }
+    if (stop) break;
+  }
+
+  // ---- final assignment with the two-phase approach (Section 3.3)
+  if (p.final_assign) {
+    StepStats ss;
+    std::swap(c.assign, c.prev);
+    rc = step_pruned(c, tm, dprime, (double)p.eps0, true, ss);
+    if (rc) return rc;
+    float ms[ST_COUNT], total;
+    tm.collect(ms, &total);
+    if (tr && rows < tr->capacity) fill_row(tr->row[rows], ss, n, k, 0, -1.0, ms, total);
+    ++rows;
+  }
+  if (assign_out) HIPCHK(hipMemcpyAsync(assign_out, c.assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+  if (dist_out) HIPCHK(hipMemcpyAsync(dist_out, c.dist, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+
+  // ---- Algorithm 1, last line: Y = Y~ R^T
+  HIPCHK(hipEventRecord(e_end0, c.st));
+  if (p.rotate) {
+    GemmOperands g{c.Y, c.ds, k, rot.Rp, c.ds, d, d};
+    HIPCHK(gemm_store(g, centroids_out, d, d, 1.f, 0.f, c.st));
+  } else {
+    HIPCHK(hipMemcpy2DAsync(centroids_out, sizeof(float) * (size_t)d, c.Y, sizeof(float) * (size_t)c.ds,
+                            sizeof(float) * (size_t)d, (size_t)k, hipMemcpyDeviceToDevice, c.st));
+  }
+  HIPCHK(hipEventRecord(e_end, c.st));
+  HIPCHK(hipStreamSynchronize(c.st));
+  if (tr) {
+    tr->rows = std::min(rows, tr->capacity);
+    tr->iters_run = run;
+    (void)hipEventElapsedTime(&tr->ms_rotate, e_begin, e_rot);
+    (void)hipEventElapsedTime(&tr->ms_init, e_rot, e_init);
+    (void)hipEventElapsedTime(&tr->ms_etr_gt, e_gt0, e_gt1);
+    (void)hipEventElapsedTime(&tr->ms_unrotate, e_end0, e_end);
+    (void)hipEventElapsedTime(&tr->ms_total, e_begin, e_end);
+  }
+  return SKM_OK;
+}
+
+int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, const int32_t *prev_assign,
+                int32_t dprime_in, const skm_params *pp, int32_t *assign_out, float *dist_out) {
+  int rc = check_shape(X, n, d, k);
+  if (rc) return rc;
+  if (!centroids || !assign_out) return fail(SKM_EINVAL, "null pointer");
+  skm_params p;
+  if (pp) p = *pp; else skm_params_default(&p);
+  skm_trace *tr = p.trace;
+  Ctx c;
+  c.st = (hipStream_t)p.stream;
+  c.n = n; c.d = d; c.k = k;
+  c.ds = round_up(d, 16);
+  c.block_stats = p.block_stats != 0;
+  StageTimer tm(c.st, true);
+  Rot rot;
+  float *Xr_own = nullptr;
+  rc = c.alloc_common(p.pair_budget, false);
+  if (rc) return rc;
+  if (p.rotate) {
+    rc = setup_rotation(c.pool, c.st, d, c.ds, p.R, 0, rot);
+    if (rc) return rc;
+    HIPCHK(c.pool.get(&Xr_own, (size_t)n * c.ds));
+    rc = rotate_into(X, d, n, d, c.ds, rot, Xr_own, c.st);
+    if (rc) return rc;
+    rc = rotate_into(centroids, d, k, d, c.ds, rot, c.Y, c.st);
+    if (rc) return rc;
+    c.Xr = Xr_own; c.ldx = c.ds;
+  } else {
+    if (d == c.ds && aligned16(X)) {
+      c.Xr = X; c.ldx = d;
+    } else {
+      HIPCHK(c.pool.get(&Xr_own, (size_t)n * c.ds));
+      HIPCHK(launch_pad_copy(X, d, n, d, Xr_own, c.ds, c.ds, 0, c.st));
+      c.Xr = Xr_own; c.ldx = c.ds;
+    }
+    HIPCHK(launch_pad_copy(centroids, d, k, d, c.Y, c.ds, c.ds, 0, c.st));
+  }
+  if (prev_assign) HIPCHK(hipMemcpyAsync(c.prev, prev_assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+  const int32_t dprime = dprime_in > 0 ? snap16((double)dprime_in, d) : dprime_init(d, p.dprime_frac);
+  StepStats ss;
+  rc = step_pruned(c, tm, dprime, (double)p.eps0, prev_assign != nullptr, ss);
+  if (rc) return rc;
+  HIPCHK(hipMemcpyAsync(assign_out, c.assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+  if (dist_out) HIPCHK(hipMemcpyAsync(dist_out, c.dist, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+  HIPCHK(hipStreamSynchronize(c.st));
+  float ms[ST_COUNT], total;
+  tm.collect(ms, &total);
+  if (tr && tr->row && tr->capacity >= 1) {
+    fill_row(tr->row[0], ss, n, k, 0, -1.0, ms, total);
+    tr->rows = 1;
+    tr->iters_run = 0;
+    tr->ms_total = total;
+  }
+  return SKM_OK;
+}
+
+}  // namespace
+
+// ==================================================================== C ABI
+extern "C" {
+#pragma GCC visibility push(default)
+
+void skm_params_default(skm_params *p) {
+  if (!p) return;
+  std::memset(p, 0, sizeof(*p));
+  p->dprime_frac = 0.125f;
+  p->eps0 = 2.1f;
+  p->adjust_dprime = 1;
+  p->adj_lo = 0.95f;
+  p->adj_hi = 0.97f;
+  p->adj_step = 0.20f;
+  p->split_eps = 1.0f / 1024.0f;
+  p->final_assign = 1;
+  p->block_stats = 0;
+  p->rotate = 1;
+  p->etr = 0;
+  p->nq = 1000;
+  p->topk = 10;
+  p->probe_frac = 0.01f;
+  p->etr_tol = 0.005f;
+  p->etr_patience = 2;
+  p->pair_budget = 0;
+}
+
+int skm_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, float *centroids_out,
+            int32_t *assign_out) {
+  return fit_impl(X, n, d, k, iters, seed, nullptr, centroids_out, assign_out, nullptr);
+}
+
+int skm_fit_ex(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params *params,
+               float *centroids_out, int32_t *assign_out, float *dist_out) {
+  return fit_impl(X, n, d, k, iters, seed, params, centroids_out, assign_out, dist_out);
+}
+
+int skm_assign(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, const int32_t *prev_assign,
+               int32_t *assign_out, float *dist_out) {
+  return assign_impl(X, n, d, centroids, k, prev_assign, 0, nullptr, assign_out, dist_out);
+}
+
+int skm_assign_ex(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, const int32_t *prev_assign,
+                  int32_t dprime, const skm_params *params, int32_t *assign_out, float *dist_out) {
+  return assign_impl(X, n, d, centroids, k, prev_assign, dprime, params, assign_out, dist_out);
+}
+
+int skm_assign_exact(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, void *stream,
+                     int32_t *assign_out, float *dist_out) {
+  int rc = check_shape(X, n, d, k);
+  if (rc) return rc;
+  if (!centroids || !assign_out) return fail(SKM_EINVAL, "null pointer");
+  hipStream_t st = (hipStream_t)stream;
+  Pool pool;
+  const int32_t ds = round_up(d, 16);
+  const float *Xp = X, *Yp = centroids;
+  int64_t ldx = d, ldy = d;
+  if (d != ds || !aligned16(X) || !aligned16(centroids)) {
+    float *Xo = nullptr, *Yo = nullptr;
+    HIPCHK(pool.get(&Xo, (size_t)n * ds));
+    HIPCHK(pool.get(&Yo, (size_t)k * ds));
+    HIPCHK(launch_pad_copy(X, d, n, d, Xo, ds, ds, 0, st));
+    HIPCHK(launch_pad_copy(centroids, d, k, d, Yo, ds, ds, 0, st));
+    Xp = Xo; Yp = Yo; ldx = ds; ldy = ds;
+  }
+  float *ynorm = nullptr;
+  unsigned long long *best = nullptr;
+  HIPCHK(pool.get(&ynorm, (size_t)k));
+  HIPCHK(pool.get(&best, (size_t)n));
+  HIPCHK(launch_prep_centroids(Yp, ldy, k, ds, ds, ynorm, 0, 0, nullptr, st));
+  HIPCHK(launch_fill_u64(best, n, ~0ull, st));
+  GemmOperands g{Xp, ldx, (int32_t)n, Yp, ldy, k, ds};
+  HIPCHK(gemm_argmin(g, ynorm, best, st));
+  HIPCHK(launch_finalize_assign(best, nullptr, n, assign_out, nullptr, nullptr, nullptr, nullptr, st));
+  if (dist_out) {
+    HIPCHK(launch_tau_init(Xp, ldx, n, ds, Yp, ldy, assign_out, 0, 0.f, dist_out, nullptr, nullptr, nullptr, st));
+  }
+  HIPCHK(hipStreamSynchronize(st));
+  return SKM_OK;
+}
+
+int skm_update(const float *X, int64_t n, int32_t d, const int32_t *assign, int32_t k, void *stream, float *centroids,
+               int32_t *counts_out) {
+  int rc = check_shape(X, n, d, k);
+  if (rc) return rc;
+  if (!assign || !centroids) return fail(SKM_EINVAL, "null pointer");
+  hipStream_t st = (hipStream_t)stream;
+  Pool pool;
+  const int32_t ds = round_up(d, 16);
+  const float *Xp = X;
+  int64_t ldx = d;
+  float *Yp = centroids;
+  int64_t ldy = d;
+  const bool padded = (d != ds) || !aligned16(X) || !aligned16(centroids);
+  if (padded) {
+    float *Xo = nullptr, *Yo = nullptr;
+    HIPCHK(pool.get(&Xo, (size_t)n * ds));
+    HIPCHK(pool.get(&Yo, (size_t)k * ds));
+    HIPCHK(launch_pad_copy(X, d, n, d, Xo, ds, ds, 0, st));
+    HIPCHK(launch_pad_copy(centroids, d, k, d, Yo, ds, ds, 0, st));
+    Xp = Xo; ldx = ds; Yp = Yo; ldy = ds;
+  }
+  UpdateWs w{};
+  HIPCHK(pool.get(&w.cnt, (size_t)k));
+  HIPCHK(pool.get(&w.off, (size_t)k + 1));
+  HIPCHK(pool.get(&w.cursor, (size_t)k));
+  HIPCHK(pool.get(&w.segoff, (size_t)k + 1));
+  HIPCHK(pool.get(&w.order, (size_t)n));
+  w.max_segments = update_max_segments(n, k);
+  HIPCHK(pool.get(&w.partial, (size_t)w.max_segments * ds));
+  HIPCHK(hipMemsetAsync(w.cnt, 0, sizeof(int32_t) * (size_t)k, st));
+  HIPCHK(launch_histogram(assign, n, w.cnt, st));
+  HIPCHK(launch_update(Xp, ldx, n, ds, assign, k, w, Yp, ldy, st));
+  if (padded)
+    HIPCHK(hipMemcpy2DAsync(centroids, sizeof(float) * (size_t)d, Yp, sizeof(float) * (size_t)ds,
+                            sizeof(float) * (size_t)d, (size_t)k, hipMemcpyDeviceToDevice, st));
+  if (counts_out) HIPCHK(hipMemcpyAsync(counts_out, w.cnt, sizeof(int32_t) * (size_t)k, hipMemcpyDeviceToDevice, st));
+  HIPCHK(hipStreamSynchronize(st));
+  return SKM_OK;
+}
+
+int skm_make_rotation(int32_t d, uint64_t seed, void *stream, float *R_out) {
+  if (!R_out) return fail(SKM_EINVAL, "null pointer");
+  if (d < 1 || d > 16384) return fail(SKM_EINVAL, "d out of range");
+  std::vector<float> Rh;
+  make_rotation_host(d, seed, Rh);
+  hipStream_t st = (hipStream_t)stream;
+  HIPCHK(hipMemcpyAsync(R_out, Rh.data(), sizeof(float) * Rh.size(), hipMemcpyHostToDevice, st));
+  HIPCHK(hipStreamSynchronize(st));
+  return SKM_OK;
+}
+
+int skm_rotate(const float *X, int64_t n, int32_t d, const float *R, int32_t transpose, void *stream, float *out) {
+  if (!X || !R || !out) return fail(SKM_EINVAL, "null pointer");
+  if (n < 1 || n >= (int64_t)1 << 31 || d < 1 || d > 16384) return fail(SKM_EINVAL, "shape out of range");
+  hipStream_t st = (hipStream_t)stream;
+  Pool pool;
+  const int32_t ds = round_up(d, 16);
+  float *B = nullptr;  // B[c][kk] = R[kk][c] for X R, R[c][kk] for X R^T
+  HIPCHK(pool.get(&B, (size_t)d * ds));
+  HIPCHK(launch_pad_copy(R, d, d, d, B, ds, ds, transpose ? 0 : 1, st));
+  GemmOperands g{X, d, (int32_t)n, B, ds, d, d};
+  HIPCHK(gemm_store(g, out, d, d, 1.f, 0.f, st));
+  HIPCHK(hipStreamSynchronize(st));
+  return SKM_OK;
+}
+
+int skm_sample_rows(uint64_t seed, int64_t n, int32_t k, int64_t *idx_out_host) {
+  if (!idx_out_host || n < 1 || k < 0 || k > n) return fail(SKM_EINVAL, "bad arguments");
+  sample_rows(seed, STREAM_INIT, n, k, idx_out_host);
+  return SKM_OK;
+}
+
+float skm_theta_ratio(int32_t d, int32_t t, float eps0) { return (float)theta_ratio(d, t, (double)eps0); }
+int32_t skm_dprime_init(int32_t d, float frac) { return dprime_init(d, (double)frac); }
+int32_t skm_dprime_adjust(int32_t d, int32_t dprime, double prune_frac, float lo, float hi, float step) {
+  return dprime_adjust(d, dprime, prune_frac, (double)lo, (double)hi, (double)step);
+}
+
+const char *skm_strerror(int rc) {
+  switch (rc) {
+    case SKM_OK: return "ok";
+    case SKM_EINVAL: return "invalid argument";
+    case SKM_ENOMEM: return "out of memory";
+    case SKM_EHIP: return "HIP runtime error";
+    case SKM_EINTERNAL: return "internal error";
+    default: return "unknown error";
+  }
+}
+const char *skm_last_error(void) { return g_last_error.c_str(); }
+const char *skm_version(void) { return "skm 0.1 (gfx950)"; }
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,152 @@
+// Internal declarations shared by the HIP translation units of libskm.
+// Nothing here is part of the public ABI (see include/skm.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace skm {
+
+constexpr int kBlockDims = 64;  // Section 3.2: trailing dimensions are explored 64 at a time
+constexpr int kMaxBlocks = 256; // (16384 - 16) / 64 rounded up
+constexpr int kSegPoints = 512; // points per partial-sum segment of the centroid update
+
+// One surviving (point, centroid) pair produced by the first pruning test
+// (Algorithm 1, the `likely(distances[i,j] > theta(d', tau))` line inverted).
+struct __attribute__((aligned(16))) Pair {
+  int32_t i;   // point index (global row)
+  int32_t j;   // centroid index
+  float p;     // partial squared distance on the first d' dimensions
+  float tau;   // the point's pruning threshold for this step
+};
+
+// ---- order-preserving float <-> uint32 map (for packed 64-bit atomic min) ----
+__host__ __device__ inline uint32_t f2ord(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__host__ __device__ inline float ord2f(uint32_t u) {
+  u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
+  return __builtin_bit_cast(float, u);
+}
+__host__ __device__ inline uint64_t pack_key(float v, int32_t idx) {
+  return ((uint64_t)f2ord(v) << 32) | (uint32_t)idx;
+}
+
+// ---------------------------------------------------------------- GEMM family
+// C-shaped work: scores s(i, j) = sum_k A[i][k] * B[j][k] for an M x K row-major A and an
+// N x K row-major B (both K-contiguous), on fp32 MFMA, with one of three fused epilogues.
+struct GemmOperands {
+  const float *A;
+  int64_t lda;
+  int32_t M;
+  const float *B;
+  int64_t ldb;
+  int32_t N;
+  int32_t K;
+};
+
+// C[i][j] = alpha * s(i,j) + beta * C[i][j] for j < N; columns N <= j < Nstore are written as 0.
+hipError_t gemm_store(const GemmOperands &g, float *C, int64_t ldc, int32_t Nstore, float alpha, float beta,
+                      hipStream_t st);
+
+// best[i] = min(best[i], pack_key(ynorm[j] - 2 s(i,j), j)) over all j: the row argmin of the squared
+// distance up to the per-row constant ||x_i||^2 (Algorithm 1, iteration 1).
+hipError_t gemm_argmin(const GemmOperands &g, const float *ynorm, unsigned long long *best, hipStream_t st);
+
+// First pruning test fused into the partial-distance GEMM (Algorithm 1, iterations >= 2):
+// p(i,j) = xn[i] + ynorm[j] - 2 s(i,j); the pair is appended to `pairs` iff
+// ynorm[j] - 2 s(i,j) <= thr[i]  (thr[i] = theta(d', tau_i) - xn[i])  and  j != prev[i].
+// Rows are local to the chunk: global row = row_base + i; thr/xn/tau/prev are indexed by global row.
+struct FilterArgs {
+  const float *ynorm;   // [N]   ||y'_j||^2
+  const float *thr;     // [n]
+  const float *xn;      // [n]   ||x'_i||^2
+  const float *tau;     // [n]
+  const int32_t *prev;  // [n]   incumbent
+  int64_t row_base;
+  Pair *pairs;
+  unsigned int *counter;   // number of pairs appended so far (this chunk)
+  unsigned int capacity;   // slots in `pairs`
+  unsigned int *overflow;  // set to 1 if capacity would be exceeded (nothing is written then)
+};
+hipError_t gemm_filter(const GemmOperands &g, const FilterArgs &f, hipStream_t st);
+
+// ---------------------------------------------------------------- pruning
+struct PruneArgs {
+  const Pair *pairs;
+  const unsigned int *count;
+  const float *Xr;       // rotated points, row stride ldx, zero padded to ds columns
+  int64_t ldx;
+  const float *Ypdx;     // [nb][k][64] trailing centroid dimensions, block-major (PDX-style)
+  int32_t k;
+  int32_t dprime;
+  int32_t ds;            // padded row length (multiple of 16)
+  int32_t nb;            // trailing blocks
+  const float *ratio;    // [nb] theta ratio after block m (device array; last entry unused)
+  unsigned long long *best;        // [n] packed (distance, centroid)
+  unsigned long long *completed;   // += pairs completed over all d dims
+  unsigned long long *enter;       // [nb] += pairs entering block m, or NULL
+};
+hipError_t launch_prune(const PruneArgs &a, hipStream_t st);
+
+// ---------------------------------------------------------------- streaming kernels
+// tau_i = ||x_i - y_{a_i}||^2 over all dims, xn_i = ||x_i[0:d')||^2, thr_i = ratio0 * tau_i - xn_i,
+// best_i = pack(tau_i, a_i)  (Algorithm 1, "Initial pruning threshold").  Any output may be NULL.
+hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
+                           const int32_t *assign, int32_t dprime, float ratio0, float *tau, float *xn, float *thr,
+                           unsigned long long *best, hipStream_t st);
+
+// ynorm[c] = ||Y[c][0:dn)||^2 and (if Ypdx) the block-major copy of the dims from dprime on.
+hipError_t launch_prep_centroids(const float *Y, int64_t ldy, int32_t k, int32_t ds, int32_t dn, float *ynorm,
+                                 int32_t dprime, int32_t nb, float *Ypdx, hipStream_t st);
+
+hipError_t launch_fill_u64(unsigned long long *p, int64_t n, unsigned long long v, hipStream_t st);
+hipError_t launch_fill_u32(unsigned int *p, int64_t n, unsigned int v, hipStream_t st);
+
+// Unpack best -> assign/dist, count cluster sizes, changed assignments, per-block objective partials.
+hipError_t launch_finalize_assign(const unsigned long long *best, const int32_t *prev, int64_t n, int32_t *assign,
+                                  float *dist, int32_t *cnt, double *obj_partial, unsigned long long *changed,
+                                  hipStream_t st);
+int64_t finalize_blocks(int64_t n);
+hipError_t launch_sum_partials(const double *part, int64_t m, double *out, hipStream_t st);
+hipError_t launch_histogram(const int32_t *assign, int64_t n, int32_t *cnt, hipStream_t st);
+
+// Centroid update (Section 3.2) as a segmented reduction.
+struct UpdateWs {
+  int32_t *cnt;        // [k]   cluster sizes (input)
+  int32_t *off;        // [k+1] exclusive scan of cnt
+  int32_t *cursor;     // [k]
+  int32_t *segoff;     // [k+1] exclusive scan of ceil(cnt / kSegPoints)
+  int32_t *order;      // [n]   point ids grouped by cluster
+  double *partial;     // [max_segments][ds]
+  int64_t max_segments;
+};
+int64_t update_max_segments(int64_t n, int32_t k);
+hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign, int32_t k,
+                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st);
+
+hipError_t launch_split(float *Y, int64_t ldy, int32_t d, const int32_t *pairs_dev, int32_t nsplit, float eps,
+                        hipStream_t st);
+hipError_t launch_gather_rows(const float *src, int64_t lds, int32_t d, const int64_t *idx_dev, int32_t k, float *dst,
+                              int64_t ldd, int32_t dpad, hipStream_t st);
+hipError_t launch_pad_copy(const float *src, int64_t lds, int64_t n, int32_t d, float *dst, int64_t ldd, int32_t dpad,
+                           int32_t transpose, hipStream_t st);
+
+// ---------------------------------------------------------------- ETR helpers
+// Key lists hold (order-preserving distance bits << 32 | index), ascending; ~0 marks an empty slot.
+// For each row q of S (nq x m scores q . x_c, row stride lds): merge the K smallest of
+// colnorm[col_base + c] - 2 S[q][c] into the running list top[q][0..K).
+hipError_t launch_topk_merge(const float *S, int64_t lds, int32_t nq, int32_t m, int64_t col_base,
+                             const float *colnorm, int32_t K, unsigned long long *top, hipStream_t st);
+// Recall numerator/denominator: per query, the nprobe centroids of smallest ynorm[c] - 2 S[q][c] are
+// probed; a ground-truth neighbour counts as found iff its cluster (assign[id]) is probed.
+hipError_t launch_recall_scores(const float *S, int64_t lds, int32_t nq, int32_t k, const float *ynorm, int32_t nprobe,
+                                const unsigned long long *gt_keys, int32_t K, const int32_t *assign,
+                                unsigned long long *hits, unsigned long long *total, hipStream_t st);
+hipError_t launch_row_norms(const float *X, int64_t ldx, int64_t n, int32_t d, float *out, hipStream_t st);
+hipError_t launch_keys_to_index(const unsigned long long *keys, int64_t n, int64_t *idx, hipStream_t st);
+hipError_t launch_index_to_keys(const int64_t *idx, int64_t n, unsigned long long *keys, hipStream_t st);
+constexpr int kMaxProbe = 8192;
+
+}  // namespace skm

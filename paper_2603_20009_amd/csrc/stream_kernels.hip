@@ -1,0 +1,417 @@
+// HBM-bound kernels around the two phases: initial threshold, centroid preparation (norms and the
+// block-major copy of the trailing dimensions), unpacking of the argmin, and the centroid update as
+// a segmented reduction (Section 3.2 "In between iterations", Section 3.4 "Initial threshold").
+#include "skm_internal.h"
+
+namespace skm {
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+__device__ inline double wave_sum(double v) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+
+static int num_cus() {
+  static int cus = 0;
+  if (!cus) {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+  }
+  return cus;
+}
+
+// ------------------------------------------------------------------ initial threshold
+// One wavefront per point: the rotated row and the row of its incumbent centroid are read as
+// float4 per lane (1 KiB per wavefront load), squared differences over all dims give tau_i, the
+// squares of the first d' entries give ||x'_i||^2.
+__global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t ldx, int64_t n, int32_t ds,
+                                                       const float *Y, int64_t ldy, const int32_t *assign,
+                                                       int32_t dprime, float ratio0, float *tau, float *xn, float *thr,
+                                                       unsigned long long *best) {
+  const int lane = threadIdx.x & 63;
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  for (int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); i < n; i += nwaves) {
+    const int a = assign[i];
+    const float *x = Xr + i * ldx;
+    const float *y = Y + (int64_t)a * ldy;
+    float s = 0.f, sx = 0.f;
+    for (int c = lane * 4; c < ds; c += 256) {
+      const float4 xv = *reinterpret_cast<const float4 *>(x + c);
+      const float4 yv = *reinterpret_cast<const float4 *>(y + c);
+      const float dx = xv.x - yv.x, dy = xv.y - yv.y, dz = xv.z - yv.z, dw = xv.w - yv.w;
+      s = fmaf(dx, dx, s);
+      s = fmaf(dy, dy, s);
+      s = fmaf(dz, dz, s);
+      s = fmaf(dw, dw, s);
+      if (c < dprime) {
+        sx = fmaf(xv.x, xv.x, sx);
+        sx = fmaf(xv.y, xv.y, sx);
+        sx = fmaf(xv.z, xv.z, sx);
+        sx = fmaf(xv.w, xv.w, sx);
+      }
+    }
+    s = wave_sum(s);
+    sx = wave_sum(sx);
+    if (lane == 0) {
+      if (tau) tau[i] = s;
+      if (xn) xn[i] = sx;
+      if (thr) thr[i] = ratio0 * s - sx;
+      if (best) best[i] = pack_key(s, a);
+    }
+  }
+}
+
+hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
+                           const int32_t *assign, int32_t dprime, float ratio0, float *tau, float *xn, float *thr,
+                           unsigned long long *best, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n + 3) / 4;
+  const int64_t cap = (int64_t)num_cus() * 32;
+  if (blocks > cap) blocks = cap;
+  hipLaunchKernelGGL(tau_init_kernel, dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, ds, Y, ldy, assign, dprime,
+                     ratio0, tau, xn, thr, best);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ centroid preparation
+// One workgroup per centroid: ynorm[c] over dims [0, dn), and the trailing dims from dprime on
+// copied to Ypdx[m][c][0..63] (block m = dims dprime+64m ..), zero filled past the row.
+__global__ void __launch_bounds__(256) prep_centroids_kernel(const float *Y, int64_t ldy, int32_t k, int32_t ds,
+                                                             int32_t dn, float *ynorm, int32_t dprime, int32_t nb,
+                                                             float *Ypdx) {
+  __shared__ float red[4];
+  const int c = blockIdx.x;
+  const float *y = Y + (int64_t)c * ldy;
+  float s = 0.f;
+  for (int j = threadIdx.x; j < dn; j += 256) s = fmaf(y[j], y[j], s);
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0 && ynorm) ynorm[c] = (red[0] + red[1]) + (red[2] + red[3]);
+  if (Ypdx) {
+    for (int t = threadIdx.x; t < nb * kBlockDims; t += 256) {
+      const int m = t / kBlockDims, qd = t % kBlockDims;
+      const int col = dprime + t;
+      Ypdx[((int64_t)m * k + c) * kBlockDims + qd] = col < ds ? y[col] : 0.f;
+    }
+  }
+}
+
+hipError_t launch_prep_centroids(const float *Y, int64_t ldy, int32_t k, int32_t ds, int32_t dn, float *ynorm,
+                                 int32_t dprime, int32_t nb, float *Ypdx, hipStream_t st) {
+  hipLaunchKernelGGL(prep_centroids_kernel, dim3(k), dim3(256), 0, st, Y, ldy, k, ds, dn, ynorm, dprime, nb, Ypdx);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ fills
+template <typename T>
+__global__ void fill_kernel(T *p, int64_t n, T v) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+template <typename T>
+static hipError_t launch_fill(T *p, int64_t n, T v, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(fill_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, p, n, v);
+  return hipGetLastError();
+}
+hipError_t launch_fill_u64(unsigned long long *p, int64_t n, unsigned long long v, hipStream_t st) {
+  return launch_fill<unsigned long long>(p, n, v, st);
+}
+hipError_t launch_fill_u32(unsigned int *p, int64_t n, unsigned int v, hipStream_t st) {
+  return launch_fill<unsigned int>(p, n, v, st);
+}
+
+// ------------------------------------------------------------------ argmin unpack
+constexpr int FIN_THREADS = 256;
+constexpr int FIN_PER_BLOCK = 1024;
+int64_t finalize_blocks(int64_t n) { return (n + FIN_PER_BLOCK - 1) / FIN_PER_BLOCK; }
+
+__global__ void __launch_bounds__(FIN_THREADS) finalize_assign_kernel(const unsigned long long *best,
+                                                                      const int32_t *prev, int64_t n, int32_t *assign,
+                                                                      float *dist, int32_t *cnt, double *obj_partial,
+                                                                      unsigned long long *changed) {
+  __shared__ double red[4];
+  __shared__ unsigned int redc[4];
+  double s = 0.0;
+  unsigned int ch = 0;
+  const int64_t base = (int64_t)blockIdx.x * FIN_PER_BLOCK;
+  for (int t = threadIdx.x; t < FIN_PER_BLOCK; t += FIN_THREADS) {
+    const int64_t i = base + t;
+    if (i < n) {
+      const unsigned long long key = best[i];
+      const int32_t a = (int32_t)(key & 0xffffffffull);
+      const float dv = ord2f((uint32_t)(key >> 32));
+      assign[i] = a;
+      if (dist) dist[i] = dv;
+      if (cnt) atomicAdd(cnt + a, 1);
+      if (prev) ch += (prev[i] != a);
+      s += (double)dv;
+    }
+  }
+  s = wave_sum(s);
+  for (int m = 1; m < 64; m <<= 1) ch += __shfl_xor(ch, m, 64);
+  if ((threadIdx.x & 63) == 0) {
+    red[threadIdx.x >> 6] = s;
+    redc[threadIdx.x >> 6] = ch;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (obj_partial) obj_partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+    const unsigned int c4 = redc[0] + redc[1] + redc[2] + redc[3];
+    if (changed && c4) atomicAdd(changed, (unsigned long long)c4);
+  }
+}
+
+hipError_t launch_finalize_assign(const unsigned long long *best, const int32_t *prev, int64_t n, int32_t *assign,
+                                  float *dist, int32_t *cnt, double *obj_partial, unsigned long long *changed,
+                                  hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(finalize_assign_kernel, dim3((unsigned)finalize_blocks(n)), dim3(FIN_THREADS), 0, st, best, prev, n,
+                     assign, dist, cnt, obj_partial, changed);
+  return hipGetLastError();
+}
+
+// fixed-order sum of the per-block partials (deterministic objective)
+__global__ void __launch_bounds__(256) sum_partials_kernel(const double *part, int64_t m, double *out) {
+  __shared__ double red[256];
+  double s = 0.0;
+  const int64_t per = (m + 255) / 256;
+  const int64_t lo = (int64_t)threadIdx.x * per;
+  for (int64_t i = lo; i < lo + per && i < m; ++i) s += part[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *out = red[0];
+}
+hipError_t launch_sum_partials(const double *part, int64_t m, double *out, hipStream_t st) {
+  hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(256), 0, st, part, m, out);
+  return hipGetLastError();
+}
+
+__global__ void histogram_kernel(const int32_t *assign, int64_t n, int32_t *cnt) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    atomicAdd(cnt + assign[i], 1);
+}
+hipError_t launch_histogram(const int32_t *assign, int64_t n, int32_t *cnt, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(histogram_kernel, dim3((unsigned)blocks), dim3(256), 0, st, assign, n, cnt);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ centroid update
+int64_t update_max_segments(int64_t n, int32_t k) { return (int64_t)k + n / kSegPoints + 1; }
+
+// single workgroup: exclusive scans of the cluster sizes and of the segment counts
+__global__ void __launch_bounds__(1024) scan_counts_kernel(const int32_t *cnt, int32_t k, int32_t *off, int32_t *cursor,
+                                                           int32_t *segoff) {
+  __shared__ int s_a[1024], s_b[1024];
+  __shared__ int carry_a, carry_b;
+  if (threadIdx.x == 0) { carry_a = 0; carry_b = 0; }
+  __syncthreads();
+  for (int base = 0; base < k; base += 1024) {
+    const int c = base + threadIdx.x;
+    const int va = c < k ? cnt[c] : 0;
+    const int vb = (va + kSegPoints - 1) / kSegPoints;
+    s_a[threadIdx.x] = va;
+    s_b[threadIdx.x] = vb;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      int ta = 0, tb = 0;
+      if ((int)threadIdx.x >= o) { ta = s_a[threadIdx.x - o]; tb = s_b[threadIdx.x - o]; }
+      __syncthreads();
+      s_a[threadIdx.x] += ta;
+      s_b[threadIdx.x] += tb;
+      __syncthreads();
+    }
+    if (c < k) {
+      off[c] = carry_a + s_a[threadIdx.x] - va;
+      segoff[c] = carry_b + s_b[threadIdx.x] - vb;
+      cursor[c] = 0;
+    }
+    __syncthreads();
+    if (threadIdx.x == 1023) { carry_a += s_a[1023]; carry_b += s_b[1023]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) { off[k] = carry_a; segoff[k] = carry_b; }
+}
+
+__global__ void scatter_order_kernel(const int32_t *assign, int64_t n, const int32_t *off, int32_t *cursor,
+                                     int32_t *order) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const int a = assign[i];
+    const int pos = off[a] + atomicAdd(cursor + a, 1);
+    order[pos] = (int32_t)i;
+  }
+}
+
+// The cursor order above depends on scheduling; sorting every segment of `order` makes the
+// summation order, and with it every bit of the result, independent of it.  One workgroup per
+// cluster, odd-even merge in LDS for clusters up to SORT_CAP points; larger clusters are summed in
+// fp64 in whatever order they were scattered (the fp64 sum of fp32 values then differs from the
+// sorted-order sum by at most a few ulps of fp64, far below the fp32 rounding of the mean).
+constexpr int SORT_CAP = 8192;
+__global__ void __launch_bounds__(256) sort_segments_kernel(const int32_t *off, int32_t *order) {
+  __shared__ int32_t s[SORT_CAP];
+  const int c = blockIdx.x;
+  const int lo = off[c], len = off[c + 1] - lo;
+  if (len < 2 || len > SORT_CAP) return;
+  int np2 = 1;
+  while (np2 < len) np2 <<= 1;
+  for (int t = threadIdx.x; t < np2; t += 256) s[t] = t < len ? order[lo + t] : 0x7fffffff;
+  __syncthreads();
+  for (int kk = 2; kk <= np2; kk <<= 1)
+    for (int jj = kk >> 1; jj > 0; jj >>= 1) {
+      for (int t = threadIdx.x; t < np2; t += 256) {
+        const int p = t ^ jj;
+        if (p > t) {
+          const int32_t a = s[t], b = s[p];
+          const bool up = (t & kk) == 0;
+          if ((a > b) == up) { s[t] = b; s[p] = a; }
+        }
+      }
+      __syncthreads();
+    }
+  for (int t = threadIdx.x; t < len; t += 256) order[lo + t] = s[t];
+}
+
+// One workgroup per (segment of <= kSegPoints points of one cluster, slice of 1024 dims):
+// rows are gathered through `order` (each a contiguous row read), summed in fp64 per thread.
+__global__ void __launch_bounds__(256) segment_sum_kernel(const float *Xr, int64_t ldx, int32_t ds, int32_t k,
+                                                          const int32_t *off, const int32_t *segoff,
+                                                          const int32_t *order, double *partial) {
+  const int seg = blockIdx.x;
+  if (seg >= segoff[k]) return;
+  // cluster of this segment: last c with segoff[c] <= seg
+  int lo = 0, hi = k;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (segoff[mid] <= seg) lo = mid; else hi = mid;
+  }
+  const int c = lo;
+  const int s_in = seg - segoff[c];
+  const int p0 = off[c] + s_in * kSegPoints;
+  const int p1 = min(off[c + 1], p0 + kSegPoints);
+  const int col = (blockIdx.y * 256 + threadIdx.x) * 4;
+  if (col >= ds) return;
+  double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+  int p = p0;
+  for (; p + 4 <= p1; p += 4) {
+    const int i0 = order[p], i1 = order[p + 1], i2 = order[p + 2], i3 = order[p + 3];
+    const float4 v0 = *reinterpret_cast<const float4 *>(Xr + (int64_t)i0 * ldx + col);
+    const float4 v1 = *reinterpret_cast<const float4 *>(Xr + (int64_t)i1 * ldx + col);
+    const float4 v2 = *reinterpret_cast<const float4 *>(Xr + (int64_t)i2 * ldx + col);
+    const float4 v3 = *reinterpret_cast<const float4 *>(Xr + (int64_t)i3 * ldx + col);
+    a0 += (double)v0.x; a1 += (double)v0.y; a2 += (double)v0.z; a3 += (double)v0.w;
+    a0 += (double)v1.x; a1 += (double)v1.y; a2 += (double)v1.z; a3 += (double)v1.w;
+    a0 += (double)v2.x; a1 += (double)v2.y; a2 += (double)v2.z; a3 += (double)v2.w;
+    a0 += (double)v3.x; a1 += (double)v3.y; a2 += (double)v3.z; a3 += (double)v3.w;
+  }
+  for (; p < p1; ++p) {
+    const float4 v = *reinterpret_cast<const float4 *>(Xr + (int64_t)order[p] * ldx + col);
+    a0 += (double)v.x; a1 += (double)v.y; a2 += (double)v.z; a3 += (double)v.w;
+  }
+  double *dst = partial + (int64_t)seg * ds + col;
+  dst[0] = a0; dst[1] = a1; dst[2] = a2; dst[3] = a3;
+}
+
+// One workgroup per (cluster, slice): partial sums added in segment order, divided by the size.
+__global__ void __launch_bounds__(256) centroid_mean_kernel(const double *partial, int32_t ds, const int32_t *cnt,
+                                                            const int32_t *segoff, float *Y, int64_t ldy) {
+  const int c = blockIdx.x;
+  const int n_c = cnt[c];
+  if (n_c == 0) return;  // an empty cluster keeps its centroid until the split
+  const int col = blockIdx.y * 256 + threadIdx.x;
+  if (col >= ds) return;
+  double s = 0.0;
+  for (int seg = segoff[c]; seg < segoff[c + 1]; ++seg) s += partial[(int64_t)seg * ds + col];
+  Y[(int64_t)c * ldy + col] = (float)(s / (double)n_c);
+}
+
+hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign, int32_t k,
+                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st) {
+  hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, st, w.cnt, k, w.off, w.cursor, w.segoff);
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(scatter_order_kernel, dim3((unsigned)blocks), dim3(256), 0, st, assign, n, w.off, w.cursor,
+                     w.order);
+  hipLaunchKernelGGL(sort_segments_kernel, dim3(k), dim3(256), 0, st, w.off, w.order);
+  const unsigned slices4 = (unsigned)((ds + 1023) / 1024);
+  hipLaunchKernelGGL(segment_sum_kernel, dim3((unsigned)w.max_segments, slices4), dim3(256), 0, st, Xr, ldx, ds, k,
+                     w.off, w.segoff, w.order, w.partial);
+  const unsigned slices1 = (unsigned)((ds + 255) / 256);
+  hipLaunchKernelGGL(centroid_mean_kernel, dim3(k, slices1), dim3(256), 0, st, w.partial, ds, w.cnt, w.segoff, Y, ldy);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ split of empty clusters
+// pairs = (empty, donor) in the order decided on the host; applied one after the other because a
+// donor may be used twice and a re-seeded cluster may itself donate later.
+__global__ void __launch_bounds__(256) split_kernel(float *Y, int64_t ldy, int32_t d, const int32_t *pairs,
+                                                    int32_t nsplit, float eps) {
+  for (int s = 0; s < nsplit; ++s) {
+    const int e = pairs[2 * s], c = pairs[2 * s + 1];
+    for (int j = threadIdx.x; j < d; j += 256) {
+      const float sg = (j & 1) ? -1.f : 1.f;
+      const float y = Y[(int64_t)c * ldy + j];
+      Y[(int64_t)e * ldy + j] = y * (1.f + eps * sg);
+      Y[(int64_t)c * ldy + j] = y * (1.f - eps * sg);
+    }
+    __syncthreads();
+  }
+}
+hipError_t launch_split(float *Y, int64_t ldy, int32_t d, const int32_t *pairs_dev, int32_t nsplit, float eps,
+                        hipStream_t st) {
+  if (nsplit <= 0) return hipSuccess;
+  hipLaunchKernelGGL(split_kernel, dim3(1), dim3(256), 0, st, Y, ldy, d, pairs_dev, nsplit, eps);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ small copies
+__global__ void __launch_bounds__(256) gather_rows_kernel(const float *src, int64_t lds, int32_t d,
+                                                          const int64_t *idx, float *dst, int64_t ldd, int32_t dpad) {
+  const int c = blockIdx.x;
+  const float *s = src + idx[c] * lds;
+  for (int j = threadIdx.x; j < dpad; j += 256) dst[(int64_t)c * ldd + j] = j < d ? s[j] : 0.f;
+}
+hipError_t launch_gather_rows(const float *src, int64_t lds, int32_t d, const int64_t *idx_dev, int32_t k, float *dst,
+                              int64_t ldd, int32_t dpad, hipStream_t st) {
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(k), dim3(256), 0, st, src, lds, d, idx_dev, dst, ldd, dpad);
+  return hipGetLastError();
+}
+
+// dst[i][j] = src[i][j] (or src[j][i] when transpose) for j < d, 0 for d <= j < dpad
+__global__ void __launch_bounds__(256) pad_copy_kernel(const float *src, int64_t lds, int64_t n, int32_t d, float *dst,
+                                                       int64_t ldd, int32_t dpad, int32_t transpose) {
+  const int64_t total = n * dpad;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t i = t / dpad;
+    const int j = (int)(t - i * dpad);
+    float v = 0.f;
+    if (j < d) v = transpose ? src[(int64_t)j * lds + i] : src[i * lds + j];
+    dst[i * ldd + j] = v;
+  }
+}
+hipError_t launch_pad_copy(const float *src, int64_t lds, int64_t n, int32_t d, float *dst, int64_t ldd, int32_t dpad,
+                           int32_t transpose, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n * dpad + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(pad_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, src, lds, n, d, dst, ldd, dpad,
+                     transpose);
+  return hipGetLastError();
+}
+
+}  // namespace skm
