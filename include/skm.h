@@ -63,8 +63,8 @@ typedef struct skm_trace {
   int32_t rows;        /* out: rows written */
   int32_t iters_run;   /* out: update steps performed */
   int32_t reserved;
-  float ms_rotate;     /* out: X~ = X R */
-  float ms_init;       /* out: centroid initialisation */
+  float ms_rotate;     /* out: the X~ = X R GEMM alone (events around its launch) */
+  float ms_init;       /* out: everything before iteration 1: workspace, R, rotation, initial centroids, ETR set-up */
   float ms_etr_gt;     /* out: ETR ground truth (0 when supplied or ETR off) */
   float ms_unrotate;   /* out: Y = Y~ R^T */
   float ms_total;      /* out: whole call, device time */

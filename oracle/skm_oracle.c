@@ -120,17 +120,23 @@ int32_t orc_dprime_init(int32_t d, double frac) {
 }
 
 /* Section 4.8: more than `hi` of the pairs pruned by the first test ->
- * shrink d' by step*d'; fewer than `lo` -> grow it by step*d'. */
+ * shrink d' by step*d'; fewer than `lo` -> grow it by step*d'.  The result is
+ * snapped to the nearest multiple of 16 but moves by at least 16 in the chosen
+ * direction (a 20% step of a small d' would otherwise round back to d'). */
 int32_t orc_dprime_adjust(int32_t d, int32_t dprime, double f, double lo,
                           double hi, double step) {
   double v = (double)dprime;
-  if (f > hi)
-    v = v - step * v;
-  else if (f < lo)
-    v = v + step * v;
-  else
-    return dprime;
-  return round16_clamp(v, d);
+  int32_t r;
+  if (f > hi) {
+    r = round16_clamp(v - step * v, d);
+    if (r > dprime - 16) r = round16_clamp((double)(dprime - 16), d);
+  } else if (f < lo) {
+    r = round16_clamp(v + step * v, d);
+    if (r < dprime + 16) r = round16_clamp((double)(dprime + 16), d);
+  } else {
+    r = dprime;
+  }
+  return r;
 }
 
 /* ------------------------------------------------------------------ */

@@ -146,8 +146,9 @@ int32_t snap16(double v, int32_t d) {
 }
 int32_t dprime_init(int32_t d, double frac) { return snap16(std::floor((double)d * frac), d); }
 int32_t dprime_adjust(int32_t d, int32_t dp, double f, double lo, double hi, double step) {
-  if (f > hi) return snap16((double)dp - step * (double)dp, d);
-  if (f < lo) return snap16((double)dp + step * (double)dp, d);
+  // nearest multiple of 16, but at least one step of 16 in the chosen direction
+  if (f > hi) return std::min(snap16((double)dp - step * (double)dp, d), snap16((double)dp - 16.0, d));
+  if (f < lo) return std::max(snap16((double)dp + step * (double)dp, d), snap16((double)dp + 16.0, d));
   return dp;
 }
 int32_t nprobe_of(int32_t k, double frac) {
@@ -515,8 +516,9 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   StageTimer tm(c.st, true);
   Events evs;
   hipEvent_t e_begin = evs.next(), e_rot = evs.next(), e_init = evs.next(), e_end0 = evs.next(), e_end = evs.next();
-  hipEvent_t e_gt0 = evs.next(), e_gt1 = evs.next();
-  if (!e_begin || !e_rot || !e_init || !e_end0 || !e_end || !e_gt0 || !e_gt1) return fail(SKM_EHIP, "hipEventCreate failed");
+  hipEvent_t e_gt0 = evs.next(), e_gt1 = evs.next(), e_rot0 = evs.next();
+  if (!e_begin || !e_rot || !e_init || !e_end0 || !e_end || !e_gt0 || !e_gt1 || !e_rot0)
+    return fail(SKM_EHIP, "hipEventCreate failed");
   HIPCHK(hipEventRecord(e_begin, c.st));
 
   // ---- Algorithm 1: R, X~ = X R
@@ -526,8 +528,10 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     rc = setup_rotation(c.pool, c.st, d, c.ds, p.R, seed, rot);
     if (rc) return rc;
     HIPCHK(c.pool.get(&Xr_own, (size_t)n * c.ds));
+    HIPCHK(hipEventRecord(e_rot0, c.st));
     rc = rotate_into(X, d, n, d, c.ds, rot, Xr_own, c.st);
     if (rc) return rc;
+    HIPCHK(hipEventRecord(e_rot, c.st));
     c.Xr = Xr_own; c.ldx = c.ds;
   } else if (d == c.ds && aligned16(X)) {
     c.Xr = X; c.ldx = d;
@@ -536,7 +540,10 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     HIPCHK(launch_pad_copy(X, d, n, d, Xr_own, c.ds, c.ds, 0, c.st));
     c.Xr = Xr_own; c.ldx = c.ds;
   }
-  HIPCHK(hipEventRecord(e_rot, c.st));
+  if (!p.rotate) {
+    HIPCHK(hipEventRecord(e_rot0, c.st));
+    HIPCHK(hipEventRecord(e_rot, c.st));
+  }
   rc = c.alloc_common(p.pair_budget, true);
   if (rc) return rc;
 
@@ -557,7 +564,6 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     HIPCHK(launch_gather_rows(c.Xr, c.ldx, c.ds, idx_dev, k, c.Y, c.ds, c.ds, c.st));
     HIPCHK(hipStreamSynchronize(c.st));
   }
-  HIPCHK(hipEventRecord(e_init, c.st));
 
   // ---- ETR set-up (Section 3.3): queries, ground truth, rotated queries
   float *Qr = nullptr, *Sq = nullptr, *ynorm_full = nullptr;
@@ -612,6 +618,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     HIPCHK(c.pool.get(&etr_scal, 2));
   }
   HIPCHK(hipEventRecord(e_gt1, c.st));
+  HIPCHK(hipEventRecord(e_init, c.st));
 
   int32_t dprime = dprime_init(d, p.dprime_frac);
   Rng split_rng = rng_stream(seed, STREAM_SPLIT);
@@ -701,12 +708,23 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   if (tr) {
     tr->rows = std::min(rows, tr->capacity);
     tr->iters_run = run;
-    (void)hipEventElapsedTime(&tr->ms_rotate, e_begin, e_rot);
-    (void)hipEventElapsedTime(&tr->ms_init, e_rot, e_init);
+    (void)hipEventElapsedTime(&tr->ms_rotate, e_rot0, e_rot);
+    (void)hipEventElapsedTime(&tr->ms_init, e_begin, e_init);
     (void)hipEventElapsedTime(&tr->ms_etr_gt, e_gt0, e_gt1);
     (void)hipEventElapsedTime(&tr->ms_unrotate, e_end0, e_end);
     (void)hipEventElapsedTime(&tr->ms_total, e_begin, e_end);
   }
+  return SKM_OK;
+}
+
+// a label outside [0, k) would index past the centroid table: refuse it here
+int labels_in_range(const int32_t *a, int64_t n, int32_t k, unsigned int *flag_dev, hipStream_t st) {
+  unsigned int bad = 0;
+  HIPCHK(hipMemsetAsync(flag_dev, 0, sizeof(unsigned int), st));
+  HIPCHK(launch_check_labels(a, n, k, flag_dev, st));
+  HIPCHK(hipMemcpyAsync(&bad, flag_dev, sizeof(bad), hipMemcpyDeviceToHost, st));
+  HIPCHK(hipStreamSynchronize(st));
+  if (bad) return fail(SKM_EINVAL, "assignment label outside [0, k)");
   return SKM_OK;
 }
 
@@ -747,7 +765,11 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
     }
     HIPCHK(launch_pad_copy(centroids, d, k, d, c.Y, c.ds, c.ds, 0, c.st));
   }
-  if (prev_assign) HIPCHK(hipMemcpyAsync(c.prev, prev_assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+  if (prev_assign) {
+    rc = labels_in_range(prev_assign, n, k, c.counters, c.st);
+    if (rc) return rc;
+    HIPCHK(hipMemcpyAsync(c.prev, prev_assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+  }
   const int32_t dprime = dprime_in > 0 ? snap16((double)dprime_in, d) : dprime_init(d, p.dprime_frac);
   StepStats ss;
   rc = step_pruned(c, tm, dprime, (double)p.eps0, prev_assign != nullptr, ss);
@@ -877,6 +899,8 @@ int skm_update(const float *X, int64_t n, int32_t d, const int32_t *assign, int3
   HIPCHK(pool.get(&w.order, (size_t)n));
   w.max_segments = update_max_segments(n, k);
   HIPCHK(pool.get(&w.partial, (size_t)w.max_segments * ds));
+  rc = labels_in_range(assign, n, k, reinterpret_cast<unsigned int *>(w.cursor), st);
+  if (rc) return rc;
   HIPCHK(hipMemsetAsync(w.cnt, 0, sizeof(int32_t) * (size_t)k, st));
   HIPCHK(launch_histogram(assign, n, w.cnt, st));
   HIPCHK(launch_update(Xp, ldx, n, ds, assign, k, w, Yp, ldy, st));

@@ -111,6 +111,7 @@ hipError_t launch_finalize_assign(const unsigned long long *best, const int32_t 
 int64_t finalize_blocks(int64_t n);
 hipError_t launch_sum_partials(const double *part, int64_t m, double *out, hipStream_t st);
 hipError_t launch_histogram(const int32_t *assign, int64_t n, int32_t *cnt, hipStream_t st);
+hipError_t launch_check_labels(const int32_t *a, int64_t n, int32_t k, unsigned int *bad, hipStream_t st);
 
 // Centroid update (Section 3.2) as a segmented reduction.
 struct UpdateWs {

@@ -211,6 +211,19 @@ hipError_t launch_histogram(const int32_t *assign, int64_t n, int32_t *cnt, hipS
   return hipGetLastError();
 }
 
+// sets *bad to 1 if any label is outside [0, k)
+__global__ void check_labels_kernel(const int32_t *a, int64_t n, int32_t k, unsigned int *bad) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    if (a[i] < 0 || a[i] >= k) *bad = 1u;
+}
+hipError_t launch_check_labels(const int32_t *a, int64_t n, int32_t k, unsigned int *bad, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(check_labels_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a, n, k, bad);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ centroid update
 int64_t update_max_segments(int64_t n, int32_t k) { return (int64_t)k + n / kSegPoints + 1; }
 

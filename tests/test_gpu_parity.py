@@ -1,0 +1,334 @@
+"""GPU parity: libskm (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Tolerances are those of the build's contract: assignments agree on >= 99.9 % of the points and
+every disagreement is a near-tie (fp64 distances of the two centroids within 1e-4 relative);
+centroids within 1e-3 relative L2; objective within 1e-4 relative.  Integer by-products (cluster
+sizes, sampled indices) must be bit-exact; survivor counters within 0.1 %.
+"""
+import numpy as np
+import pytest
+import torch
+
+from parity import EPS0, check_assignment, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def skm():
+    from paper_2603_20009_amd import skm as m
+    m.lib()
+    assert torch.cuda.is_available()
+    return m
+
+
+@pytest.fixture(scope="module")
+def dg():
+    from paper_2603_20009_amd import datagen
+    return datagen
+
+
+def cuda(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ rotation
+@pytest.mark.parametrize("n,d", [(300, 80), (1000, 128), (257, 100), (130, 75), (64, 1536), (1, 16)])
+def test_rotation_gemm(skm, orc, dg, n, d):
+    say("rotate", n, d)
+    X = dg.mixture(n, d, 10, 1, "linear").numpy()
+    R = orc.random_rotation(d, 3)
+    got = skm.rotate(cuda(X), cuda(R)).cpu().numpy()
+    assert np.abs(got - orc.rotate(X, R)).max() < 2e-6
+    back = skm.rotate(cuda(got), cuda(R), True).cpu().numpy()     # (X R) R^T = X
+    assert np.abs(back - X).max() < 4e-6
+    want_t = X.astype(np.float64) @ R.astype(np.float64).T
+    assert np.abs(skm.rotate(cuda(X), cuda(R), True).cpu().numpy() - want_t).max() < 2e-6
+
+
+def test_library_rotation_is_orthogonal_and_seeded(skm):
+    for d in (16, 100, 384):
+        R = skm.make_rotation(d, 5).cpu().numpy().astype(np.float64)
+        assert np.abs(R @ R.T - np.eye(d)).max() < 1e-6
+        assert np.abs(np.linalg.det(R)) == pytest.approx(1.0, abs=1e-4)
+    a = skm.make_rotation(64, 1).cpu().numpy()
+    b = skm.make_rotation(64, 1).cpu().numpy()
+    c = skm.make_rotation(64, 2).cpu().numpy()
+    assert np.array_equal(a, b) and np.abs(a - c).max() > 0.05
+    # entries of a Haar matrix have variance 1/d
+    assert np.var(skm.make_rotation(384, 3).cpu().numpy()) == pytest.approx(1.0 / 384, rel=0.02)
+
+
+# ------------------------------------------------------------------ exact assignment (iteration 1)
+@pytest.mark.parametrize("n,d,k", [(1000, 128, 300), (257, 208, 129), (5000, 64, 17), (129, 16, 1), (3, 100, 3),
+                                   (700, 75, 130)])
+def test_exact_assignment(skm, orc, dg, n, d, k):
+    say("exact", n, d, k)
+    rng = np.random.default_rng(n + d + k)
+    X = dg.mixture(n, d, 20, 2, "linear").numpy()
+    Y = X[rng.choice(n, k, replace=False)] + (0.01 * rng.standard_normal((k, d))).astype(np.float32)
+    a, dist = skm.assign_exact(cuda(X), cuda(Y))
+    a = a.cpu().numpy()
+    ao, do = orc.assign_full(X.astype(np.float64), Y.astype(np.float64))
+    check_assignment(a, ao, X, Y, min_agree=0.999)
+    same = a == ao
+    assert np.abs(dist.cpu().numpy()[same] - do[same]).max() < 1e-6 * max(1.0, do.max())
+
+
+# ------------------------------------------------------------------ one pruned step
+def pruned_case(orc, dg, n, d, k, seed, recipe):
+    rng = np.random.default_rng(seed)
+    X = dg.mixture(n, d, 30, seed, recipe).numpy()
+    R = orc.random_rotation(d, seed + 1)
+    Y = X[rng.choice(n, k, replace=False)] + (0.01 * rng.standard_normal((k, d))).astype(np.float32)
+    Xr = orc.rotate(X, R)
+    Yr = orc.rotate(Y, R)
+    prev = orc.assign_full(Xr, Yr)[0]
+    prev[::4] = rng.integers(0, k, len(prev[::4]))          # a quarter of the points start from a poor incumbent
+    return X, R, Y, Xr, Yr, prev.astype(np.int32)
+
+
+@pytest.mark.parametrize("n,d,k,dp,budget", [
+    (2000, 128, 100, 0, 0),
+    (3000, 208, 257, 0, 0),          # d' = 32, trailing 176 = 2 x 64 + 48 (short tail block)
+    (1000, 1536, 64, 0, 0),          # d' = 192, 21 full blocks
+    (1500, 1536, 300, 160, 0),       # d' not a multiple of 64: last block holds 32 dims
+    (4000, 100, 50, 48, 0),          # d not a multiple of 16: padded rows
+    (3000, 128, 130, 128, 0),        # d' = d: the first test is the exact comparison, no trailing block
+    (5000, 128, 129, 0, 129 * 1024),  # survivor list sized for 1024 rows: 5 chunks
+])
+def test_pruned_step(skm, orc, dg, n, d, k, dp, budget):
+    say("pruned", n, d, k, dp, budget)
+    X, R, Y, Xr, Yr, prev = pruned_case(orc, dg, n, d, k, n + k, "linear" if d < 512 else "embed")
+    dp = dp or orc.dprime_init(d)
+    ref = orc.assign_pruned(Xr, Yr, prev, dp, EPS0, 0)
+    opts = skm.FitOptions(R=cuda(R), block_stats=True, pair_budget=budget)
+    a, dist, row = skm.assign(cuda(X), cuda(Y), cuda(prev), dp, opts)
+    a = a.cpu().numpy()
+    check_assignment(a, ref.assign, Xr, Yr)
+    same = a == ref.assign
+    assert np.abs(dist.cpu().numpy()[same] - ref.dist[same]).max() < 2e-6 * max(1.0, ref.dist.max())
+    surv_ref = n * (k - 1) - ref.pruned_first
+    assert abs(row["survivors"] - surv_ref) <= max(2, 1e-3 * surv_ref)
+    assert row["dprime"] == dp and row["nblocks"] == len(ref.enter) - 1
+    for m in range(row["nblocks"]):
+        assert abs(row["enter"][m] - ref.enter[m]) <= max(2, 1e-3 * ref.enter[m])
+    assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])
+    assert row["objective"] == pytest.approx(ref.dist.sum(), rel=1e-5)
+    assert row["changed"] == int((a != prev).sum())
+
+
+def test_pruned_step_without_previous_assignment(skm, orc, dg):
+    X, R, Y, Xr, Yr, _ = pruned_case(orc, dg, 2500, 128, 90, 5, "linear")
+    ref = orc.assign_pruned(Xr, Yr, None, 16, EPS0, 0)
+    a, dist, _ = skm.assign(cuda(X), cuda(Y), None, 16, skm.FitOptions(R=cuda(R)))
+    check_assignment(a.cpu().numpy(), ref.assign, Xr, Yr)
+
+
+def test_pruned_step_without_statistical_test_is_exact(skm, orc, dg):
+    X, R, Y, Xr, Yr, prev = pruned_case(orc, dg, 3000, 144, 77, 9, "linear")
+    exact, _ = orc.assign_full(Xr, Yr)
+    a, dist, row = skm.assign(cuda(X), cuda(Y), cuda(prev), 0, skm.FitOptions(R=cuda(R), eps0=float("inf")))
+    check_assignment(a.cpu().numpy(), exact, Xr, Yr, min_agree=0.9995)
+    # and the same with no rotation at all (R = I)
+    a2, _, _ = skm.assign(cuda(X), cuda(Y), cuda(prev), 0, skm.FitOptions(rotate=False, eps0=float("inf")))
+    check_assignment(a2.cpu().numpy(), orc.assign_full(X.astype(np.float64), Y.astype(np.float64))[0], X, Y,
+                     min_agree=0.9995)
+
+
+def test_default_entry_points(skm, orc, dg):
+    """skm_assign / skm_fit (defaults, library's own rotation): checked through properties."""
+    n, d, k = 6000, 128, 40
+    X = dg.mixture(n, d, 50, 21, "linear")
+    Xc = X.cuda()
+    cent, a = skm.fit_default(Xc, k, 6, 3)
+    Xn = X.numpy().astype(np.float64)
+    Yn = cent.cpu().numpy().astype(np.float64)
+    D = ((Xn[:, None, :] - Yn[None, :, :]) ** 2).sum(2)
+    an = a.cpu().numpy()
+    assert (an == D.argmin(1)).mean() > 0.995                      # final pass: nearest centroid, rare false prunes
+    ref = orc.fit(X.numpy(), k, 6, 3, orc.FitParams(eps0=EPS0), R=orc.random_rotation(d, 3))
+    assert D.min(1).sum() == pytest.approx(ref.trace[-1]["objective"], rel=0.02)   # same quality, other rotation
+    a2, dist2 = skm.assign_default(Xc, cent, a)
+    assert (a2.cpu().numpy() == an).mean() > 0.999
+    assert np.allclose(dist2.cpu().numpy(), D[np.arange(n), a2.cpu().numpy()], rtol=1e-4, atol=1e-6)
+
+
+def test_bad_labels_are_refused(skm, dg):
+    X = dg.mixture(500, 32, 5, 1, "linear").cuda()
+    Y = X[:7].clone()
+    prev = torch.full((500,), 7, dtype=torch.int32, device="cuda")
+    with pytest.raises(skm.SkmError):
+        skm.assign(X, Y, prev)
+    with pytest.raises(skm.SkmError):
+        skm.update(X, prev, Y)
+
+
+# ------------------------------------------------------------------ update
+@pytest.mark.parametrize("n,d,k", [(5000, 128, 100), (3000, 100, 37), (40_000, 64, 5), (2000, 1536, 700)])
+def test_update(skm, orc, dg, n, d, k):
+    say("update", n, d, k)
+    rng = np.random.default_rng(n + k)
+    X = dg.mixture(n, d, 30, 4, "linear").numpy()
+    a = rng.integers(0, max(k - 2, 1), n).astype(np.int32)     # the last two clusters stay empty
+    if k == 5:
+        a[: n * 3 // 4] = 1                                    # one cluster above the in-LDS sort limit
+    Y0 = rng.standard_normal((k, d)).astype(np.float32)
+    Yg = cuda(Y0)
+    cnt = skm.update(cuda(X), cuda(a), Yg).cpu().numpy()
+    Yo, co = orc.update(X.astype(np.float64), a, Y0.astype(np.float64))
+    assert (cnt == co).all()                                   # integer work: bit-exact
+    assert np.abs(Yg.cpu().numpy() - Yo).max() < 1e-6
+    assert np.array_equal(Yg.cpu().numpy()[co == 0], Y0[co == 0])
+
+
+# ------------------------------------------------------------------ whole fit
+def fit_pair(skm, orc, X, k, iters, seed, R, init_idx=None, **kw):
+    kw.setdefault("eps0", EPS0)
+    idx = orc.sample_rows(seed, len(X), k) if init_idx is None else np.asarray(init_idx, dtype=np.int64)
+    ref = orc.fit(X, k, iters, seed, orc.FitParams(**kw), R=R, init_idx=idx)
+    # without init_idx the library draws the same initial rows from the seed
+    opts = skm.FitOptions(R=None if R is None else cuda(R), rotate=R is not None, block_stats=True,
+                          init_idx=None if init_idx is None else list(idx), **kw)
+    got = skm.fit(cuda(X), k, iters, seed, opts)
+    return ref, got
+
+
+def test_fit_c1_full_parity(skm, orc, dg):
+    """Workload C1 (20 000 x 128, k = 100, 10 iterations): every tolerance of the contract."""
+    X = dg.config_data("C1").numpy()
+    R = orc.random_rotation(128, 42)
+    ref, got = fit_pair(skm, orc, X, 100, 10, 42, R, adjust_dprime=False)
+    Xr = orc.rotate(X, R)
+    check_assignment(got.assign.cpu().numpy(), ref.assign, Xr, ref.centroids_rot)
+    assert rel_l2(got.centroids.cpu().numpy(), ref.centroids) < 1e-3
+    assert got.iters_run == ref.iters_run == 10 and len(got.trace) == len(ref.trace) == 11
+    for g, r in zip(got.trace, ref.trace):
+        assert g["objective"] == pytest.approx(r["objective"], rel=1e-4)
+        assert g["dprime"] == r["dprime"] and g["nempty"] == r["nempty"]
+        assert g["prune_frac"] == pytest.approx(r["prune_frac"], abs=1e-3)
+    obj = [g["objective"] for g in got.trace]
+    assert all(b <= a * (1 + 1e-6) for a, b in zip(obj, obj[1:]))          # Lloyd objective never increases
+    same = got.assign.cpu().numpy() == ref.assign
+    assert np.abs(got.dist.cpu().numpy()[same] - ref.dist[same]).max() < 1e-5
+
+
+def test_fit_with_dprime_adjustment(skm, orc, dg):
+    X = dg.mixture(12_000, 256, 64, 8, "embed").numpy()
+    R = orc.random_rotation(256, 8)
+    ref, got = fit_pair(skm, orc, X, 64, 8, 5, R, adjust_dprime=True)
+    assert [g["dprime"] for g in got.trace] == [r["dprime"] for r in ref.trace]
+    assert len({g["dprime"] for g in got.trace[1:]}) > 1                    # the controller did move d'
+    assert got.trace[-1]["objective"] == pytest.approx(ref.trace[-1]["objective"], rel=1e-4)
+    assert rel_l2(got.centroids.cpu().numpy(), ref.centroids) < 1e-3
+
+
+def test_fit_without_rotation_or_final_pass(skm, orc, dg):
+    X = dg.mixture(5000, 96, 20, 3, "linear").numpy()
+    ref, got = fit_pair(skm, orc, X, 24, 5, 11, None, adjust_dprime=False, final_assign=False)
+    check_assignment(got.assign.cpu().numpy(), ref.assign, X, ref.centroids_rot)
+    assert rel_l2(got.centroids.cpu().numpy(), ref.centroids) < 1e-3
+    # centroids are the means of the returned (last in-loop) assignment
+    a = got.assign.cpu().numpy()
+    S = np.zeros((24, 96))
+    np.add.at(S, a, X.astype(np.float64))
+    assert np.abs(got.centroids.cpu().numpy() - S / np.bincount(a, minlength=24)[:, None]).max() < 1e-6
+
+
+def test_fit_splits_empty_clusters_like_the_oracle(skm, orc, dg):
+    """Repeated initial rows leave clusters empty after iteration 1 (identical centroids tie and the
+    lowest index wins on both sides); the split must re-seed them from the same donors."""
+    X = dg.mixture(6000, 64, 24, 10, "linear").numpy()
+    R = orc.random_rotation(64, 10)
+    idx = orc.sample_rows(1, 6000, 12)
+    idx[1] = idx[0]
+    idx[2] = idx[0]
+    idx[7] = idx[6]
+    ref, got = fit_pair(skm, orc, X, 12, 5, 1, R, init_idx=idx, adjust_dprime=False)
+    assert [g["nempty"] for g in got.trace] == [r["nempty"] for r in ref.trace] and ref.trace[0]["nempty"] == 3
+    check_assignment(got.assign.cpu().numpy(), ref.assign, orc.rotate(X, R), ref.centroids_rot)
+    assert rel_l2(got.centroids.cpu().numpy(), ref.centroids) < 1e-3
+    assert (np.bincount(got.assign.cpu().numpy(), minlength=12) > 0).all()
+
+
+def test_fit_is_bitwise_reproducible(skm, orc, dg):
+    X = cuda(dg.mixture(30_000, 128, 64, 12, "linear").numpy())
+    R = cuda(orc.random_rotation(128, 2))
+    a = skm.fit(X, 200, 5, 9, skm.FitOptions(R=R))
+    b = skm.fit(X, 200, 5, 9, skm.FitOptions(R=R))
+    assert torch.equal(a.assign, b.assign) and torch.equal(a.centroids, b.centroids) and torch.equal(a.dist, b.dist)
+    assert [r["survivors"] for r in a.trace] == [r["survivors"] for r in b.trace]
+
+
+# ------------------------------------------------------------------ ETR
+def test_etr_ground_truth_recall_and_stop(skm, orc, dg):
+    n, d, k, nq, K = 20_000, 64, 50, 40, 10
+    X = dg.mixture(n, d, 30, 3, "linear").numpy()
+    Q = dg.mixture(nq, d, 30, 4, "linear").numpy()
+    R = orc.random_rotation(d, 6)
+    idx = orc.sample_rows(2, n, k)
+    kw = dict(etr=True, topk=K, probe_frac=0.1, adjust_dprime=False)
+    for tol, want_stop in ((0.5, True), (-1.0, False)):
+        ref = orc.fit(X, k, 6, 2, orc.FitParams(eps0=EPS0, etr_tol=tol, **kw), R=R, init_idx=idx, queries=Q)
+        got = skm.fit(cuda(X), k, 6, 2, skm.FitOptions(R=cuda(R), queries=cuda(Q), etr_tol=tol, **kw))
+        assert got.iters_run == ref.iters_run and (got.iters_run == 3) == want_stop
+        for g, r in zip(got.trace[: got.iters_run], ref.trace):
+            assert g["recall"] == pytest.approx(r["recall"], abs=2.0 / (nq * K))
+    # user-supplied ground truth gives the same recalls as the computed one
+    gt = orc.ground_truth(X, Q, K)
+    got2 = skm.fit(cuda(X), k, 6, 2, skm.FitOptions(R=cuda(R), queries=cuda(Q), gt=cuda(gt), etr_tol=-1.0, **kw))
+    assert [g["recall"] for g in got2.trace[:6]] == [g["recall"] for g in got.trace[:6]]
+    # queries sampled from X by the library: every query finds itself, recall stays high
+    got3 = skm.fit(cuda(X), k, 3, 2, skm.FitOptions(R=cuda(R), etr=True, nq=25, topk=1, probe_frac=0.02,
+                                                    etr_tol=-1.0, adjust_dprime=False))
+    assert all(g["recall"] >= 0.9 for g in got3.trace[:3])
+
+
+# ------------------------------------------------------------------ full size, bench launch configuration
+def test_c2_full_size_sampled_parity(skm, orc, dg):
+    """Workload C2 (1 000 000 x 1536, k = 1024) exactly as bench.py runs it; the oracle checks
+    a sample of the rows one by one (pruned step and exact step) and a sample of the clusters."""
+    torch.cuda.empty_cache()
+    n, d, k = 1_000_000, 1536, 1024
+    say("generating C2")
+    X = dg.config_data("C2", device="cuda")
+    Rn = orc.random_rotation(d, 42)
+    R = cuda(Rn)
+    say("fit 2 iterations")
+    fr = skm.fit(X, k, 2, 42, skm.FitOptions(R=R, final_assign=False, adjust_dprime=False))
+    assert fr.trace[1]["survivors"] > 0
+    say("assign step")
+    a3, d3, row = skm.assign(X, fr.centroids, fr.assign, 0, skm.FitOptions(R=R))
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(n, 1536, replace=False))
+    Xs = X[torch.from_numpy(rows).cuda()].cpu().numpy()
+    Y = fr.centroids.cpu().numpy()
+    Xr = orc.rotate(Xs, Rn)
+    Yr = orc.rotate(Y, Rn)
+    say("oracle on the sample")
+    ref = orc.assign_pruned(Xr, Yr, fr.assign.cpu().numpy()[rows], orc.dprime_init(d), EPS0, 0)
+    check_assignment(a3.cpu().numpy()[rows], ref.assign, Xr, Yr, min_agree=0.998)
+    same = a3.cpu().numpy()[rows] == ref.assign
+    assert np.abs(d3.cpu().numpy()[rows][same] - ref.dist[same]).max() < 1e-5
+    surv_ref = len(rows) * (k - 1) - ref.pruned_first
+    assert row["survivors"] / n == pytest.approx(surv_ref / len(rows), rel=0.1)     # same survivor density
+    say("exact step on the sample")
+    ae, de = skm.assign_exact(X, fr.centroids)
+    ao, do = orc.assign_full(Xs.astype(np.float64), Y.astype(np.float64))
+    check_assignment(ae.cpu().numpy()[rows], ao, Xs, Y, min_agree=0.998)
+    say("update on sampled clusters")
+    Yn = fr.centroids.clone()
+    cnt = skm.update(X, a3, Yn).cpu().numpy()
+    assert cnt.sum() == n and (cnt == np.bincount(a3.cpu().numpy(), minlength=k)).all()
+    for c in rng.choice(k, 6, replace=False):
+        members = torch.nonzero(a3 == int(c)).flatten()
+        if len(members) == 0:
+            continue
+        mean = X[members].cpu().numpy().astype(np.float64).mean(0)
+        assert np.abs(Yn[int(c)].cpu().numpy() - mean).max() < 1e-6
+    del X, fr
+    torch.cuda.empty_cache()

@@ -93,6 +93,8 @@ def test_dprime_rules(orc):
     assert orc.dprime_adjust(1536, 192, 0.90) == 224      # 230.4 -> 224
     assert orc.dprime_adjust(1536, 192, 0.96) == 192
     assert orc.dprime_adjust(1536, 192, 0.95) == 192 and orc.dprime_adjust(1536, 192, 0.97) == 192
+    assert orc.dprime_adjust(256, 32, 0.90) == 48 and orc.dprime_adjust(256, 32, 0.99) == 16   # at least one step of 16
+    assert orc.dprime_adjust(384, 48, 0.90) == 64 and orc.dprime_adjust(384, 48, 0.99) == 32
     assert orc.dprime_adjust(128, 16, 0.99) == 16         # lower clamp
     assert orc.dprime_adjust(128, 128, 0.5) == 128        # upper clamp
     assert orc.dprime_adjust(100, 96, 0.5) == 96          # upper clamp is the last multiple of 16
