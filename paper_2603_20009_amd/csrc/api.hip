@@ -244,6 +244,9 @@ int check_shape(const void *X, int64_t n, int32_t d, int32_t k) {
 }
 
 // ---------------------------------------------------------------- one fit / assign context
+// device scalars of one assignment step
+enum { SC_COMPLETED = 0, SC_CHANGED = 1, SC_SURVIVORS = 2, SC_ENTER = 3, SC_COUNT = 3 + kMaxBlocks };
+
 struct Ctx {
   hipStream_t st = nullptr;
   Pool pool;
@@ -254,43 +257,49 @@ struct Ctx {
   float *Y = nullptr;         // centroids k x ds (rotated space)
   float *Ypdx = nullptr;
   float *ynorm = nullptr;
-  float *tau = nullptr, *xn = nullptr, *thr = nullptr, *dist = nullptr;
+  float *tau = nullptr, *dist = nullptr;
   unsigned long long *best = nullptr;
   int32_t *assign = nullptr, *prev = nullptr;
   Pair *pairs = nullptr;
   int64_t pair_cap = 0, chunk_rows = 0;
   int32_t nchunks = 0;
+  unsigned int emit_max = 0;         // a tile with at most this many alive pairs goes to the gather kernel
   unsigned int *counters = nullptr;  // [nchunks] pair counts, then [1] overflow flag
-  float *ratio_dev = nullptr;        // [kMaxBlocks]
-  float ratio_host[kMaxBlocks];      // staging for ratio_dev (must outlive the async copy)
-  unsigned long long *scal = nullptr;  // [0] completed, [1] changed, [2..] enter[kMaxBlocks]
+  float *ratio_dev = nullptr;        // [kMaxBlocks + 1]
+  float ratio_host[kMaxBlocks + 1];  // staging for ratio_dev (must outlive the async copy)
+  unsigned long long *scal = nullptr;  // [SC_COUNT]
   double *obj_partial = nullptr, *obj = nullptr;
   UpdateWs up{};
   int32_t *split_dev = nullptr;
   bool block_stats = false;
 
-  int alloc_common(int64_t pair_budget, bool need_update) {
+  int alloc_common(int64_t pair_budget, float dense_frac, bool need_update) {
     HIPCHK(pool.get(&Y, (size_t)k * ds));
     const int32_t nbmax = (ds - 16 + kBlockDims - 1) / kBlockDims + 1;
     HIPCHK(pool.get(&Ypdx, (size_t)nbmax * k * kBlockDims));
     HIPCHK(pool.get(&ynorm, (size_t)k));
     HIPCHK(pool.get(&tau, (size_t)n));
-    HIPCHK(pool.get(&xn, (size_t)n));
-    HIPCHK(pool.get(&thr, (size_t)n));
     HIPCHK(pool.get(&dist, (size_t)n));
     HIPCHK(pool.get(&best, (size_t)n));
     HIPCHK(pool.get(&assign, (size_t)n));
     HIPCHK(pool.get(&prev, (size_t)n));
+    // Every tile hands over at most emit_max pairs, so a chunk of rows needs tiles * emit_max slots.
+    const int64_t tile_pairs = progressive_tile_pairs();
+    if (!(dense_frac >= 0.f)) dense_frac = 0.f;
+    if (dense_frac > 1.f) dense_frac = 1.f;
+    emit_max = (unsigned int)std::llround((double)dense_frac * (double)tile_pairs);
+    const int64_t per_tile = std::max<int64_t>(emit_max, 1);
     if (pair_budget <= 0) pair_budget = (int64_t)1 << 29;
-    chunk_rows = std::max<int64_t>(pair_budget / k, 128);
-    chunk_rows = std::min<int64_t>(chunk_rows / 128 * 128, (n + 127) / 128 * 128);
+    const int64_t col_tiles = progressive_tiles(1, k);
+    int64_t row_tiles = std::max<int64_t>(pair_budget / (per_tile * col_tiles), 1);
+    chunk_rows = std::min<int64_t>(row_tiles * 128, (n + 127) / 128 * 128);
     nchunks = (int32_t)((n + chunk_rows - 1) / chunk_rows);
-    pair_cap = std::min<int64_t>(chunk_rows, n) * k;
+    pair_cap = progressive_tiles(std::min<int64_t>(chunk_rows, n), k) * per_tile;
     if (pair_cap >= ((int64_t)1 << 32)) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
     HIPCHK(pool.get(&pairs, (size_t)pair_cap));
     HIPCHK(pool.get(&counters, (size_t)nchunks + 1));
-    HIPCHK(pool.get(&ratio_dev, (size_t)kMaxBlocks));
-    HIPCHK(pool.get(&scal, (size_t)2 + kMaxBlocks));
+    HIPCHK(pool.get(&ratio_dev, (size_t)kMaxBlocks + 1));
+    HIPCHK(pool.get(&scal, (size_t)SC_COUNT));
     HIPCHK(pool.get(&obj_partial, (size_t)finalize_blocks(n)));
     HIPCHK(pool.get(&obj, 1));
     HIPCHK(pool.get(&up.cnt, (size_t)k));
@@ -325,9 +334,9 @@ int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
   tm.mark(ST_GEMM);
   // winners -> direct squared distances (also the objective of this step)
   HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, nullptr, nullptr, nullptr, nullptr, c.st));
-  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.assign, 0, 0.f, nullptr, nullptr, nullptr, c.best, c.st));
+  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.assign, nullptr, c.best, c.st));
   HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
-  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (2 + kMaxBlocks), c.st));
+  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT, c.st));
   HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, nullptr, c.st));
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
@@ -341,18 +350,18 @@ int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
   return SKM_OK;
 }
 
-// Iterations >= 2 of Algorithm 1: partial GEMM + first test, progressive pruning, argmin.
-// On entry c.prev holds the incumbents (c.assign is overwritten); have_prev = false seeds the
-// incumbent with the centroid of smallest partial distance.
+// Iterations >= 2 of Algorithm 1: initial threshold, progressive-pruning GEMM, gather kernel for the
+// pairs of sparse tiles, argmin.  On entry c.prev holds the incumbents (c.assign is overwritten);
+// have_prev = false seeds the incumbent with the centroid of smallest partial distance.
 int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_prev, StepStats &ss) {
   const int32_t nb = (c.d - dprime + kBlockDims - 1) / kBlockDims;
   if (nb > kMaxBlocks) return fail(SKM_EINTERNAL, "too many trailing blocks");
   tm.mark(ST_NONE);
   HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, dprime, c.ynorm, dprime, nb, c.Ypdx, c.st));
+  // theta ratio at checkpoint m: t_m = min(d, d' + 64 m) dimensions seen
   float *ratio = c.ratio_host;
-  for (int m = 0; m < nb; ++m) ratio[m] = (float)theta_ratio(c.d, std::min(c.d, dprime + kBlockDims * (m + 1)), eps0);
-  if (nb > 0) HIPCHK(hipMemcpyAsync(c.ratio_dev, ratio, sizeof(float) * (size_t)nb, hipMemcpyHostToDevice, c.st));
-  const float ratio0 = (float)theta_ratio(c.d, dprime, eps0);
+  for (int m = 0; m <= nb; ++m) ratio[m] = (float)theta_ratio(c.d, std::min(c.d, dprime + kBlockDims * m), eps0);
+  HIPCHK(hipMemcpyAsync(c.ratio_dev, ratio, sizeof(float) * ((size_t)nb + 1), hipMemcpyHostToDevice, c.st));
   if (!have_prev) {
     HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
     GemmOperands g0{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, dprime};
@@ -360,40 +369,49 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, nullptr, nullptr, c.st));
     tm.mark(ST_GEMM);
   }
-  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, dprime, ratio0, c.tau, c.xn, c.thr, c.best, c.st));
+  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st));
   HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * ((size_t)c.nchunks + 1), c.st));
-  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (2 + kMaxBlocks), c.st));
+  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT, c.st));
   HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
   tm.mark(ST_TAU);
   for (int32_t ch = 0; ch < c.nchunks; ++ch) {
     const int64_t r0 = (int64_t)ch * c.chunk_rows;
     const int64_t rows = std::min<int64_t>(c.chunk_rows, c.n - r0);
-    GemmOperands g{c.Xr + r0 * c.ldx, c.ldx, (int32_t)rows, c.Y, c.ds, c.k, dprime};
-    FilterArgs f{c.ynorm, c.thr, c.xn, c.tau, c.prev, r0, c.pairs, c.counters + ch, (unsigned int)c.pair_cap,
-                 c.counters + c.nchunks};
-    HIPCHK(gemm_filter(g, f, c.st));
+    ProgArgs g{};
+    g.A = c.Xr + r0 * c.ldx; g.lda = c.ldx; g.M = (int32_t)rows;
+    g.B = c.Y; g.ldb = c.ds; g.N = c.k;
+    g.ds = c.ds; g.d = c.d; g.dprime = dprime; g.nb = nb;
+    g.ratio = c.ratio_dev; g.tau = c.tau; g.prev = c.prev; g.row_base = r0;
+    g.pairs = c.pairs; g.pair_count = c.counters + ch; g.capacity = (unsigned int)c.pair_cap;
+    g.overflow = c.counters + c.nchunks; g.emit_max = c.emit_max;
+    g.best = c.best; g.survivors = c.scal + SC_SURVIVORS; g.completed = c.scal + SC_COMPLETED;
+    g.enter = c.block_stats ? c.scal + SC_ENTER : nullptr;
+    HIPCHK(launch_progressive(g, c.st));
     tm.mark(ST_GEMM);
-    PruneArgs pa{c.pairs, c.counters + ch, c.Xr, c.ldx, c.Ypdx, c.k, dprime, c.ds, nb, c.ratio_dev, c.best,
-                 c.scal + 0, c.block_stats ? c.scal + 2 : nullptr};
-    HIPCHK(launch_prune(pa, c.st));
-    tm.mark(ST_PRUNE);
+    if (c.emit_max > 0) {
+      PruneArgs pa{c.pairs, c.counters + ch, c.Xr, c.ldx, c.Ypdx, c.k, dprime, c.ds, nb, c.ratio_dev, c.best,
+                   c.scal + SC_COMPLETED, c.block_stats ? c.scal + SC_ENTER : nullptr};
+      HIPCHK(launch_prune(pa, c.st));
+      tm.mark(ST_PRUNE);
+    }
   }
-  HIPCHK(launch_finalize_assign(c.best, c.prev, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, c.scal + 1, c.st));
+  HIPCHK(launch_finalize_assign(c.best, c.prev, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, c.scal + SC_CHANGED,
+                                c.st));
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
-  tm.mark(ST_PRUNE);
-  std::vector<unsigned int> cnt_h((size_t)c.nchunks + 1);
-  std::vector<unsigned long long> scal_h(2 + kMaxBlocks);
+  tm.mark(ST_TAU);
+  unsigned int overflow = 0;
+  std::vector<unsigned long long> scal_h((size_t)SC_COUNT);
   double obj = 0;
-  HIPCHK(hipMemcpyAsync(cnt_h.data(), c.counters, sizeof(unsigned int) * cnt_h.size(), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(&overflow, c.counters + c.nchunks, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipMemcpyAsync(scal_h.data(), c.scal, sizeof(unsigned long long) * scal_h.size(), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipMemcpyAsync(&obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipStreamSynchronize(c.st));
-  if (cnt_h[(size_t)c.nchunks] != 0) return fail(SKM_EINTERNAL, "survivor list overflow");
+  if (overflow != 0) return fail(SKM_EINTERNAL, "survivor list overflow");
   ss = StepStats();
-  for (int32_t ch = 0; ch < c.nchunks; ++ch) ss.survivors += cnt_h[(size_t)ch];
-  ss.completed = (int64_t)scal_h[0];
-  ss.changed = (int64_t)scal_h[1];
-  for (int m = 0; m < std::min<int>(nb, SKM_MAX_BLOCKS); ++m) ss.enter[m] = (int64_t)scal_h[2 + (size_t)m];
+  ss.survivors = (int64_t)scal_h[SC_SURVIVORS];
+  ss.completed = (int64_t)scal_h[SC_COMPLETED];
+  ss.changed = (int64_t)scal_h[SC_CHANGED];
+  for (int m = 0; m < std::min<int>(nb, SKM_MAX_BLOCKS); ++m) ss.enter[m] = (int64_t)scal_h[SC_ENTER + (size_t)m];
   ss.objective = obj;
   ss.dprime = dprime;
   ss.nblocks = nb;
@@ -544,7 +562,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     HIPCHK(hipEventRecord(e_rot0, c.st));
     HIPCHK(hipEventRecord(e_rot, c.st));
   }
-  rc = c.alloc_common(p.pair_budget, true);
+  rc = c.alloc_common(p.pair_budget, p.dense_frac, true);
   if (rc) return rc;
 
   // ---- InitCentroids: k distinct rows of X~
@@ -744,7 +762,7 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
   StageTimer tm(c.st, true);
   Rot rot;
   float *Xr_own = nullptr;
-  rc = c.alloc_common(p.pair_budget, false);
+  rc = c.alloc_common(p.pair_budget, p.dense_frac, false);
   if (rc) return rc;
   if (p.rotate) {
     rc = setup_rotation(c.pool, c.st, d, c.ds, p.R, 0, rot);
@@ -814,6 +832,7 @@ void skm_params_default(skm_params *p) {
   p->etr_tol = 0.005f;
   p->etr_patience = 2;
   p->pair_budget = 0;
+  p->dense_frac = 0.02f;
 }
 
 int skm_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, float *centroids_out,
@@ -864,7 +883,7 @@ int skm_assign_exact(const float *X, int64_t n, int32_t d, const float *centroid
   HIPCHK(gemm_argmin(g, ynorm, best, st));
   HIPCHK(launch_finalize_assign(best, nullptr, n, assign_out, nullptr, nullptr, nullptr, nullptr, st));
   if (dist_out) {
-    HIPCHK(launch_tau_init(Xp, ldx, n, ds, Yp, ldy, assign_out, 0, 0.f, dist_out, nullptr, nullptr, nullptr, st));
+    HIPCHK(launch_tau_init(Xp, ldx, n, ds, Yp, ldy, assign_out, dist_out, nullptr, st));
   }
   HIPCHK(hipStreamSynchronize(st));
   return SKM_OK;

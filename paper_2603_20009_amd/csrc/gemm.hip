@@ -1,4 +1,4 @@
-// fp32 MFMA "NT" GEMM for gfx950 with three fused epilogues.
+// fp32 MFMA "NT" GEMM for gfx950 with two fused epilogues (store, row argmin).
 //
 // The GEMM phase of SuperKMeans (Algorithm 1: iteration 1 over all d dimensions, later iterations
 // over the first d' dimensions; Section 3.1 for the rotation X R) is a product of two K-contiguous
@@ -7,9 +7,8 @@
 // K is consumed in slabs of BK floats that are staged global -> registers -> LDS (two LDS buffers,
 // one barrier per slab) while the previous slab is multiplied.
 //
-// The score matrix is never written for the distance uses: the epilogue either reduces it to a row
-// argmin (iteration 1) or applies the first pruning test theta(d', tau_i) and appends the few
-// surviving (point, centroid, partial distance) triples to a list (iterations >= 2).
+// The score matrix is never written for the distance use of iteration 1: the epilogue reduces it to
+// a row argmin.  Iterations >= 2 use the progressive kernel of progressive.hip, built on the same tile.
 #include "skm_internal.h"
 
 namespace skm {
@@ -21,7 +20,7 @@ constexpr int WTM = 64, WTN = 64;  // wavefront tile
 constexpr int TM = 2, TN = 2;      // 32 x 32 MFMA tiles per wavefront
 constexpr int NTHREADS = 256;
 
-enum { EPI_STORE = 0, EPI_ARGMIN = 1, EPI_FILTER = 2 };
+enum { EPI_STORE = 0, EPI_ARGMIN = 1 };
 
 struct StoreArgs {
   float *C;
@@ -43,10 +42,6 @@ struct EpiArgs<EPI_STORE> {
 template <>
 struct EpiArgs<EPI_ARGMIN> {
   typedef ArgminArgs type;
-};
-template <>
-struct EpiArgs<EPI_FILTER> {
-  typedef FilterArgs type;
 };
 
 // Workgroups are dispatched round-robin over the 8 XCDs (each with its own L2).  Give every XCD a
@@ -251,77 +246,6 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmOperands g, typename
       const int gr = row0 + tid;
       if (gr < g.M && key != ~0ull) atomicMin(e.best + gr, key);
     }
-  } else {
-    // first pruning test and compaction of the survivors
-    float *s_thr = smem;                                   // [BM]
-    float *s_xn = smem + BM;                               // [BM]
-    float *s_tau = smem + 2 * BM;                          // [BM]
-    int *s_prev = reinterpret_cast<int *>(smem + 3 * BM);  // [BM]
-    if (tid < BM) {
-      const int64_t gr = (int64_t)row0 + tid;
-      const bool ok = gr < g.M;
-      const int64_t gi = e.row_base + gr;
-      s_thr[tid] = ok ? e.thr[gi] : -__builtin_inff();
-      s_xn[tid] = ok ? e.xn[gi] : 0.f;
-      s_tau[tid] = ok ? e.tau[gi] : 0.f;
-      s_prev[tid] = ok ? e.prev[gi] : -1;
-    }
-    __syncthreads();
-    float yn[TN];
-    int gc[TN];
-#pragma unroll
-    for (int b = 0; b < TN; ++b) {
-      gc[b] = col0 + wn * WTN + b * 32 + r32;
-      yn[b] = gc[b] < g.N ? e.ynorm[gc[b]] : __builtin_inff();
-    }
-    // pass 1: one keep-bit per accumulator element
-    unsigned long long bits = 0ull;
-#pragma unroll
-    for (int a = 0; a < TM; ++a)
-#pragma unroll
-      for (int b = 0; b < TN; ++b)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int rl = row_of(a, v);
-          const float val = yn[b] - 2.f * acc[a][b][v];
-          const bool keep = (val <= s_thr[rl]) && (gc[b] != s_prev[rl]);
-          bits |= (unsigned long long)keep << ((a * TN + b) * 16 + v);
-        }
-    int total = __popcll(bits);
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) total += __shfl_xor(total, m, 64);
-    if (total > 0) {   // wave-uniform
-      unsigned int base = 0;
-      if (lane == 0) base = atomicAdd(e.counter, (unsigned int)total);
-      base = __shfl(base, 0, 64);
-      if ((unsigned long long)base + (unsigned long long)total > (unsigned long long)e.capacity) {
-        if (lane == 0) *e.overflow = 1u;
-      } else {
-        // pass 2: element-major order, so that the lanes of one ballot write consecutive slots
-        unsigned int run = base;
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const bool keep = (bits >> ((a * TN + b) * 16 + v)) & 1ull;
-              const unsigned long long m = __ballot(keep);
-              if (keep) {
-                const int rl = row_of(a, v);
-                const unsigned int pos = run + __builtin_amdgcn_mbcnt_hi((unsigned int)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)m, 0u));
-                Pair pr;
-                pr.i = (int32_t)(e.row_base + row0 + rl);
-                pr.j = gc[b];
-                const float p = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
-                pr.p = p > 0.f ? p : 0.f;
-                pr.tau = s_tau[rl];
-                e.pairs[pos] = pr;
-              }
-              run += (unsigned int)__popcll(m);
-            }
-      }
-    }
   }
 }
 
@@ -372,10 +296,6 @@ hipError_t gemm_store(const GemmOperands &g, float *C, int64_t ldc, int32_t Nsto
 hipError_t gemm_argmin(const GemmOperands &g, const float *ynorm, unsigned long long *best, hipStream_t st) {
   ArgminArgs e{ynorm, best};
   return launch_any<EPI_ARGMIN>(g, e, st);
-}
-
-hipError_t gemm_filter(const GemmOperands &g, const FilterArgs &f, hipStream_t st) {
-  return launch_any<EPI_FILTER>(g, f, st);
 }
 
 }  // namespace skm

@@ -1,0 +1,351 @@
+// Progressive-pruning GEMM (Algorithm 1, iterations >= 2; Section 3.4 "Progressive Pruning").
+//
+// The paper multiplies only the first d' dimensions densely and finishes survivors one by one.
+// On MI355X a 64-dimension step of a dense 128 x 128 tile on the fp32 matrix cores costs about as
+// much as gathering the same step for 2 % of the tile's pairs, so this kernel keeps multiplying a
+// tile densely, 64 dimensions at a time, while more than a small share of its pairs is alive, and
+// hands the pairs over to the gather kernel (prune.hip) only once the tile is sparse.  The tests are
+// the paper's: after t = d', d'+64, d'+128, ... dimensions a pair is dropped when its partial squared
+// distance exceeds theta(t, tau_i); a pair that reaches t = d is offered to the point's packed
+// (distance, centroid) minimum if it beats tau_i.
+//
+// Partial distances come from the norm expansion ||x_t||^2 + ||y_t||^2 - 2 x_t.y_t (Section 3.1).
+// The prefix norms are a by-product of staging: every thread squares the float4 it moves into LDS,
+// and the four lanes that share a tile row add up at each checkpoint.
+#include "skm_internal.h"
+
+namespace skm {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+namespace {
+constexpr int BM = 128, BN = 128;
+constexpr int WTM = 64, WTN = 64, TM = 2, TN = 2;
+constexpr int NT = 256;
+
+// sum over the F4_ROW (4 or 8) consecutive lanes that stage one tile row; all of them get the total
+template <int LANES>
+__device__ inline float rowgroup_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  if (LANES == 8)
+    v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+  return v;
+}
+
+__device__ inline void tile_of_block(int nrt, int nct, int &rt, int &ct) {
+  const int nwg = gridDim.x, bid = blockIdx.x;
+  const int xcd = bid & 7, q = bid >> 3;
+  const int base = nwg >> 3, rem = nwg & 7;
+  const int logical = xcd * base + (xcd < rem ? xcd : rem) + q;
+  constexpr int PC = 16;
+  const int panel_sz = PC * nrt;
+  const int p = logical / panel_sz;
+  const int r = logical - p * panel_sz;
+  const int pc = (nct - p * PC) < PC ? (nct - p * PC) : PC;
+  rt = r / pc;
+  ct = p * PC + (r - rt * pc);
+}
+}  // namespace
+
+// Slabs of BK dimensions start at koff = -((BK - d' % BK) % BK), so that slab ends fall on every
+// checkpoint d' + 64 m; dimensions below 0 or past ds are read as zero.
+template <int BK>
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) progressive_kernel(ProgArgs g) {
+  constexpr int LS = BK + 4;
+  constexpr int F4_ROW = BK / 4;              // lanes per tile row
+  constexpr int ROWS_PASS = NT / F4_ROW;      // tile rows staged per pass
+  constexpr int A_F4 = BM / ROWS_PASS;
+  constexpr int B_F4 = BN / ROWS_PASS;
+  extern __shared__ __align__(16) float smem[];
+  float *As = smem;                  // [2][BM][LS]
+  float *Bs = smem + 2 * BM * LS;    // [2][BN][LS]
+  __shared__ float s_tau[BM], s_thr[BM], s_xn[BM], s_yn[BN];
+  __shared__ int s_prev[BM];
+  __shared__ float s_ratio[kMaxBlocks + 1];
+  __shared__ unsigned int s_cnt[2];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int r32 = lane & 31, kh = lane >> 5;
+  const int nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
+  int rt, ct;
+  tile_of_block(nrt, nct, rt, ct);
+  const int row0 = rt * BM, col0 = ct * BN;
+
+  if (tid < BM) {
+    const int gr = row0 + tid;
+    const bool ok = gr < g.M;
+    s_tau[tid] = ok ? g.tau[g.row_base + gr] : 0.f;
+    s_prev[tid] = ok ? g.prev[g.row_base + gr] : -1;
+  }
+  for (int m = tid; m <= g.nb; m += NT) s_ratio[m] = g.ratio[m];
+  if (tid < 2) s_cnt[tid] = 0u;
+
+  float4 ra[A_F4], rb[B_F4];
+  float na[A_F4], nbv[B_F4];
+#pragma unroll
+  for (int s = 0; s < A_F4; ++s) na[s] = 0.f;
+#pragma unroll
+  for (int s = 0; s < B_F4; ++s) nbv[s] = 0.f;
+  const int st_row = tid / F4_ROW, st_kq = tid % F4_ROW;  // staging: rows st_row + ROWS_PASS * s
+  const int koff = -((BK - g.dprime % BK) % BK);
+  auto gload = [&](int k0) {
+    const int kk = k0 + 4 * st_kq;
+    const bool kok = kk >= 0 && kk < g.ds;
+#pragma unroll
+    for (int s = 0; s < A_F4; ++s) {
+      const int gr = row0 + st_row + ROWS_PASS * s;
+      ra[s] = (kok && gr < g.M) ? *reinterpret_cast<const float4 *>(g.A + (int64_t)gr * g.lda + kk)
+                                : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int s = 0; s < B_F4; ++s) {
+      const int gc = col0 + st_row + ROWS_PASS * s;
+      rb[s] = (kok && gc < g.N) ? *reinterpret_cast<const float4 *>(g.B + (int64_t)gc * g.ldb + kk)
+                                : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int s = 0; s < A_F4; ++s) {
+      *reinterpret_cast<float4 *>(As + (buf * BM + st_row + ROWS_PASS * s) * LS + 4 * st_kq) = ra[s];
+      na[s] = fmaf(ra[s].x, ra[s].x, fmaf(ra[s].y, ra[s].y, fmaf(ra[s].z, ra[s].z, fmaf(ra[s].w, ra[s].w, na[s]))));
+    }
+#pragma unroll
+    for (int s = 0; s < B_F4; ++s) {
+      *reinterpret_cast<float4 *>(Bs + (buf * BN + st_row + ROWS_PASS * s) * LS + 4 * st_kq) = rb[s];
+      nbv[s] = fmaf(rb[s].x, rb[s].x, fmaf(rb[s].y, rb[s].y, fmaf(rb[s].z, rb[s].z, fmaf(rb[s].w, rb[s].w, nbv[s]))));
+    }
+  };
+  // prefix norms of the rows / columns of this tile over the dimensions staged so far
+  auto publish_norms = [&](float ratio) {
+#pragma unroll
+    for (int s = 0; s < A_F4; ++s) {
+      const float v = rowgroup_sum<F4_ROW>(na[s]);
+      if (st_kq == 0) {
+        const int rl = st_row + ROWS_PASS * s;
+        s_xn[rl] = v;
+        s_thr[rl] = ratio * s_tau[rl] - v;
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < B_F4; ++s) {
+      const float v = rowgroup_sum<F4_ROW>(nbv[s]);
+      if (st_kq == 0) s_yn[st_row + ROWS_PASS * s] = v;
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int a = 0; a < TM; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  auto row_of = [&](int a, int v) { return wm * WTM + a * 32 + 8 * (v >> 2) + 4 * kh + (v & 3); };
+  int gc[TN];
+#pragma unroll
+  for (int b = 0; b < TN; ++b) gc[b] = col0 + wn * WTN + b * 32 + r32;
+
+  const int nslab = (g.ds - koff + BK - 1) / BK;
+  gload(koff);
+  sstore(0);
+  __syncthreads();
+
+  // one alive-bit per accumulator element; the incumbent and the padding of ragged tiles start dead
+  unsigned long long bits = 0ull;
+#pragma unroll
+  for (int a = 0; a < TM; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int rl = row_of(a, v);
+        const bool ok = (row0 + rl < g.M) && (gc[b] < g.N) && (gc[b] != s_prev[rl]);
+        bits |= (unsigned long long)ok << ((a * TN + b) * 16 + v);
+      }
+
+  int fin_mode = 0, fin_m = 0;   // how the tile ended: 1 = reached t = d, 2 = handed over at checkpoint fin_m
+  float yn[TN] = {0.f, 0.f};
+  for (int s = 0; s < nslab; ++s) {
+    const int buf = s & 1;
+    if (s + 1 < nslab) gload(koff + (s + 1) * BK);
+    const float *Ab = As + (buf * BM + wm * WTM + r32) * LS + kh * 4;
+    const float *Bb = Bs + (buf * BN + wn * WTN + r32) * LS + kh * 4;
+#pragma unroll
+    for (int kg = 0; kg < BK / 8; ++kg) {
+      float4 af[TM], bf[TN];
+#pragma unroll
+      for (int a = 0; a < TM; ++a) af[a] = *reinterpret_cast<const float4 *>(Ab + a * 32 * LS + kg * 8);
+#pragma unroll
+      for (int b = 0; b < TN; ++b) bf[b] = *reinterpret_cast<const float4 *>(Bb + b * 32 * LS + kg * 8);
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].x, bf[b].x, acc[a][b], 0, 0, 0);
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].y, bf[b].y, acc[a][b], 0, 0, 0);
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].z, bf[b].z, acc[a][b], 0, 0, 0);
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].w, bf[b].w, acc[a][b], 0, 0, 0);
+    }
+
+    const int tdone = koff + BK * (s + 1);   // dimensions multiplied so far
+    const bool last = (s + 1 == nslab);
+    const bool check = !last && tdone >= g.dprime && tdone < g.d && ((tdone - g.dprime) & (kBlockDims - 1)) == 0;
+    const bool cp = check || last;
+    const int m = last ? g.nb : (tdone - g.dprime) / kBlockDims;   // checkpoint index, t_m = min(d, d' + 64 m)
+    if (cp) publish_norms(s_ratio[m]);      // norms over the slabs multiplied so far (the next slab is added below)
+    if (s + 1 < nslab) sstore(buf ^ 1);
+    __syncthreads();
+    if (cp) {
+#pragma unroll
+      for (int b = 0; b < TN; ++b) yn[b] = s_yn[wn * WTN + b * 32 + r32];
+      if (!last || g.nb == 0) {
+        // test theta(t_m, tau_i): drop the pair when its partial distance exceeds it
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float th = s_thr[row_of(a, v)];
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+              const bool keep = (yn[b] - 2.f * acc[a][b][v]) <= th;
+              bits &= ~((unsigned long long)(!keep) << ((a * TN + b) * 16 + v));
+            }
+          }
+      }
+      // alive pairs of the whole tile
+      int cnt = __popcll(bits);
+#pragma unroll
+      for (int sh = 1; sh < 64; sh <<= 1) cnt += __shfl_xor(cnt, sh, 64);
+      if (lane == 0 && cnt) atomicAdd(&s_cnt[m & 1], (unsigned int)cnt);
+      __syncthreads();
+      const unsigned int total = s_cnt[m & 1];
+      if (tid == 0) {
+        s_cnt[(m + 1) & 1] = 0u;   // next checkpoint's counter; nobody reads it before the next barrier
+        if (total) {
+          if (m == 0) atomicAdd(g.survivors, (unsigned long long)total);
+          if (!last && g.enter) atomicAdd(g.enter + m, (unsigned long long)total);
+          if (last) atomicAdd(g.completed, (unsigned long long)total);
+        }
+      }
+      if (total == 0u) return;
+      if (last) {
+        fin_mode = 1;
+        fin_m = m;
+        break;
+      }
+      if (total <= g.emit_max) {
+        fin_mode = 2;
+        fin_m = m;
+        break;
+      }
+    }
+  }
+
+  if (fin_mode == 1) {
+    // finished distances: offer those below tau_i to the point's packed minimum
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int rl = row_of(a, v);
+        unsigned long long key = ~0ull;
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+          if ((bits >> ((a * TN + b) * 16 + v)) & 1ull) {
+            float dist = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
+            dist = dist > 0.f ? dist : 0.f;
+            if (dist < s_tau[rl]) {
+              const unsigned long long kb = pack_key(dist, gc[b]);
+              key = kb < key ? kb : key;
+            }
+          }
+        }
+        if (__ballot(key != ~0ull)) {
+#pragma unroll
+          for (int sh = 1; sh < 32; sh <<= 1) {
+            const unsigned long long o = __shfl_xor(key, sh, 64);
+            key = o < key ? o : key;
+          }
+          if (r32 == 0 && key != ~0ull) atomicMin(g.best + g.row_base + row0 + rl, key);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+  } else if (fin_mode == 2) {
+    // sparse enough: hand the alive pairs to the gather kernel, which resumes at block fin_m
+    int wtot = __popcll(bits);
+#pragma unroll
+    for (int sh = 1; sh < 64; sh <<= 1) wtot += __shfl_xor(wtot, sh, 64);
+    if (wtot > 0) {
+      unsigned int base = 0;
+      if (lane == 0) base = atomicAdd(g.pair_count, (unsigned int)wtot);
+      base = __shfl(base, 0, 64);
+      if ((unsigned long long)base + (unsigned long long)wtot > (unsigned long long)g.capacity) {
+        if (lane == 0) *g.overflow = 1u;
+      } else {
+        unsigned int run = base;
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const bool keep = (bits >> ((a * TN + b) * 16 + v)) & 1ull;
+              const unsigned long long mk = __ballot(keep);
+              if (keep) {
+                const int rl = row_of(a, v);
+                const unsigned int pos =
+                    run + __builtin_amdgcn_mbcnt_hi((unsigned int)(mk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mk, 0u));
+                Pair pr;
+                pr.i = (int32_t)(g.row_base + row0 + rl);
+                pr.j = (int32_t)((uint32_t)gc[b] | ((uint32_t)fin_m << 24));
+                const float p = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
+                pr.p = p > 0.f ? p : 0.f;
+                pr.tau = s_tau[rl];
+                g.pairs[pos] = pr;
+              }
+              run += (unsigned int)__popcll(mk);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+      }
+    }
+  }
+}
+
+hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
+  if (g.M <= 0 || g.N <= 0) return hipSuccess;
+  if (g.ds % 16 != 0 || g.dprime % 16 != 0 || g.dprime < 16 || g.dprime > g.ds || g.lda % 4 != 0 || g.ldb % 4 != 0 ||
+      g.nb > kMaxBlocks || (reinterpret_cast<uintptr_t>(g.A) & 15u) || (reinterpret_cast<uintptr_t>(g.B) & 15u) ||
+      g.N > (1 << 24))
+    return hipErrorInvalidValue;
+  constexpr int BK = 32;
+  constexpr size_t smem = (size_t)2 * (BM + BN) * (BK + 4) * sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel<BK>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (rc != hipSuccess) return rc;
+    attr_set = true;
+  }
+  const int64_t nwg = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  if (nwg > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(progressive_kernel<BK>, dim3((unsigned)nwg), dim3(NT), smem, st, g);
+  return hipGetLastError();
+}
+
+int64_t progressive_tiles(int64_t rows, int32_t k) { return ((rows + BM - 1) / BM) * (int64_t)((k + BN - 1) / BN); }
+int32_t progressive_tile_pairs() { return BM * BN; }
+
+}  // namespace skm

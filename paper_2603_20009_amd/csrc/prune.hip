@@ -26,11 +26,11 @@ constexpr int PRUNE_THREADS = 256;
 
 template <bool STATS>
 __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
-  __shared__ float s_ratio[kMaxBlocks];
-  __shared__ unsigned int s_enter[kMaxBlocks];
+  __shared__ float s_ratio[kMaxBlocks + 1];
+  __shared__ unsigned int s_enter[kMaxBlocks + 1];
   __shared__ unsigned int s_completed;
   const int tid = threadIdx.x;
-  for (int m = tid; m < a.nb; m += PRUNE_THREADS) {
+  for (int m = tid; m <= a.nb; m += PRUNE_THREADS) {
     s_ratio[m] = a.ratio[m];
     s_enter[m] = 0u;
   }
@@ -44,10 +44,16 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
   bool active = p < total;
   int i = 0, j = 0, m = 0;
   float acc = 0.f, tau = 0.f;
-  if (active) {
+  auto fetch = [&]() {
     const Pair pr = a.pairs[p];
-    i = pr.i; j = pr.j; acc = pr.p; tau = pr.tau;
-  }
+    const unsigned int jm = (unsigned int)pr.j;
+    i = pr.i;
+    j = (int)(jm & 0xffffffu);
+    m = (int)(jm >> 24);   // first block still to be added
+    acc = pr.p;
+    tau = pr.tau;
+  };
+  if (active) fetch();
   while (__any(active)) {
     if (active) {
       if (m < a.nb) {
@@ -61,7 +67,6 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
         s = fmaf(dz, dz, s);
         s = fmaf(dw, dw, s);
         acc += row16_sum(s);
-        if (STATS && q == 0) atomicAdd(&s_enter[m], 1u);
         ++m;
       }
       const bool done = m >= a.nb;
@@ -72,16 +77,13 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
           if (acc < tau) atomicMin(a.best + i, pack_key(acc, j));
         }
       } else {
-        drop = acc > s_ratio[m - 1] * tau;
+        drop = acc > s_ratio[m] * tau;   // checkpoint m: t = d' + 64 m dimensions seen
+        if (STATS && !drop && q == 0) atomicAdd(&s_enter[m], 1u);
       }
       if (done || drop) {
         p += ngroups;
         active = p < total;
-        if (active) {
-          const Pair pr = a.pairs[p];
-          i = pr.i; j = pr.j; acc = pr.p; tau = pr.tau;
-          m = 0;
-        }
+        if (active) fetch();
       }
     }
   }

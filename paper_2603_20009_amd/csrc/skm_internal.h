@@ -15,8 +15,8 @@ constexpr int kSegPoints = 512; // points per partial-sum segment of the centroi
 // (Algorithm 1, the `likely(distances[i,j] > theta(d', tau))` line inverted).
 struct __attribute__((aligned(16))) Pair {
   int32_t i;   // point index (global row)
-  int32_t j;   // centroid index
-  float p;     // partial squared distance on the first d' dimensions
+  int32_t j;   // centroid index in bits 0..23, first trailing block still to be added in bits 24..31
+  float p;     // partial squared distance on the dimensions seen so far
   float tau;   // the point's pruning threshold for this step
 };
 
@@ -54,23 +54,36 @@ hipError_t gemm_store(const GemmOperands &g, float *C, int64_t ldc, int32_t Nsto
 // distance up to the per-row constant ||x_i||^2 (Algorithm 1, iteration 1).
 hipError_t gemm_argmin(const GemmOperands &g, const float *ynorm, unsigned long long *best, hipStream_t st);
 
-// First pruning test fused into the partial-distance GEMM (Algorithm 1, iterations >= 2):
-// p(i,j) = xn[i] + ynorm[j] - 2 s(i,j); the pair is appended to `pairs` iff
-// ynorm[j] - 2 s(i,j) <= thr[i]  (thr[i] = theta(d', tau_i) - xn[i])  and  j != prev[i].
-// Rows are local to the chunk: global row = row_base + i; thr/xn/tau/prev are indexed by global row.
-struct FilterArgs {
-  const float *ynorm;   // [N]   ||y'_j||^2
-  const float *thr;     // [n]
-  const float *xn;      // [n]   ||x'_i||^2
-  const float *tau;     // [n]
-  const int32_t *prev;  // [n]   incumbent
+// Progressive-pruning GEMM (Algorithm 1, iterations >= 2): a 128 x 128 tile is multiplied densely over
+// d', d'+64, d'+128, ... dimensions; after each step the pairs whose partial distance exceeds
+// theta(t, tau_i) die; the tile stops when nothing is alive, hands its pairs to the gather kernel when
+// at most emit_max are alive, and offers finished distances below tau_i to best[] at t = d.
+// Rows are local to the chunk: global row = row_base + i; tau/prev/best are indexed by global row.
+struct ProgArgs {
+  const float *A;          // rotated points of the chunk, zero padded to ds columns
+  int64_t lda;
+  int32_t M;
+  const float *B;          // rotated centroids, k x ds
+  int64_t ldb;
+  int32_t N;
+  int32_t ds, d, dprime, nb;
+  const float *ratio;      // [nb + 1] theta ratio at checkpoint m (t_m = min(d, d' + 64 m)); device array
+  const float *tau;        // [n]
+  const int32_t *prev;     // [n] incumbent (never a challenger)
   int64_t row_base;
   Pair *pairs;
-  unsigned int *counter;   // number of pairs appended so far (this chunk)
-  unsigned int capacity;   // slots in `pairs`
-  unsigned int *overflow;  // set to 1 if capacity would be exceeded (nothing is written then)
+  unsigned int *pair_count;
+  unsigned int capacity;
+  unsigned int *overflow;
+  unsigned int emit_max;   // a tile with at most this many alive pairs is handed over
+  unsigned long long *best;       // [n] packed (distance, centroid)
+  unsigned long long *survivors;  // += pairs alive after the first test
+  unsigned long long *completed;  // += pairs finished over all d dims
+  unsigned long long *enter;      // [nb] += pairs entering trailing block m, or NULL
 };
-hipError_t gemm_filter(const GemmOperands &g, const FilterArgs &f, hipStream_t st);
+hipError_t launch_progressive(const ProgArgs &g, hipStream_t st);
+int64_t progressive_tiles(int64_t rows, int32_t k);
+int32_t progressive_tile_pairs();
 
 // ---------------------------------------------------------------- pruning
 struct PruneArgs {
@@ -83,19 +96,18 @@ struct PruneArgs {
   int32_t dprime;
   int32_t ds;            // padded row length (multiple of 16)
   int32_t nb;            // trailing blocks
-  const float *ratio;    // [nb] theta ratio after block m (device array; last entry unused)
+  const float *ratio;    // [nb + 1] theta ratio at checkpoint m, t_m = min(d, d' + 64 m) (device array)
   unsigned long long *best;        // [n] packed (distance, centroid)
   unsigned long long *completed;   // += pairs completed over all d dims
-  unsigned long long *enter;       // [nb] += pairs entering block m, or NULL
+  unsigned long long *enter;       // [nb] += pairs entering block m after surviving block m - 1 here, or NULL
 };
 hipError_t launch_prune(const PruneArgs &a, hipStream_t st);
 
 // ---------------------------------------------------------------- streaming kernels
-// tau_i = ||x_i - y_{a_i}||^2 over all dims, xn_i = ||x_i[0:d')||^2, thr_i = ratio0 * tau_i - xn_i,
-// best_i = pack(tau_i, a_i)  (Algorithm 1, "Initial pruning threshold").  Any output may be NULL.
+// tau_i = ||x_i - y_{a_i}||^2 over all dims, best_i = pack(tau_i, a_i)
+// (Algorithm 1, "Initial pruning threshold").  Either output may be NULL.
 hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
-                           const int32_t *assign, int32_t dprime, float ratio0, float *tau, float *xn, float *thr,
-                           unsigned long long *best, hipStream_t st);
+                           const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st);
 
 // ynorm[c] = ||Y[c][0:dn)||^2 and (if Ypdx) the block-major copy of the dims from dprime on.
 hipError_t launch_prep_centroids(const float *Y, int64_t ldy, int32_t k, int32_t ds, int32_t dn, float *ynorm,

@@ -28,11 +28,9 @@ static int num_cus() {
 
 // ------------------------------------------------------------------ initial threshold
 // One wavefront per point: the rotated row and the row of its incumbent centroid are read as
-// float4 per lane (1 KiB per wavefront load), squared differences over all dims give tau_i, the
-// squares of the first d' entries give ||x'_i||^2.
+// float4 per lane (1 KiB per wavefront load); squared differences over all dims give tau_i.
 __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t ldx, int64_t n, int32_t ds,
-                                                       const float *Y, int64_t ldy, const int32_t *assign,
-                                                       int32_t dprime, float ratio0, float *tau, float *xn, float *thr,
+                                                       const float *Y, int64_t ldy, const int32_t *assign, float *tau,
                                                        unsigned long long *best) {
   const int lane = threadIdx.x & 63;
   const int64_t nwaves = (int64_t)gridDim.x * 4;
@@ -40,7 +38,7 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
     const int a = assign[i];
     const float *x = Xr + i * ldx;
     const float *y = Y + (int64_t)a * ldy;
-    float s = 0.f, sx = 0.f;
+    float s = 0.f;
     for (int c = lane * 4; c < ds; c += 256) {
       const float4 xv = *reinterpret_cast<const float4 *>(x + c);
       const float4 yv = *reinterpret_cast<const float4 *>(y + c);
@@ -49,33 +47,23 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
       s = fmaf(dy, dy, s);
       s = fmaf(dz, dz, s);
       s = fmaf(dw, dw, s);
-      if (c < dprime) {
-        sx = fmaf(xv.x, xv.x, sx);
-        sx = fmaf(xv.y, xv.y, sx);
-        sx = fmaf(xv.z, xv.z, sx);
-        sx = fmaf(xv.w, xv.w, sx);
-      }
     }
     s = wave_sum(s);
-    sx = wave_sum(sx);
     if (lane == 0) {
       if (tau) tau[i] = s;
-      if (xn) xn[i] = sx;
-      if (thr) thr[i] = ratio0 * s - sx;
       if (best) best[i] = pack_key(s, a);
     }
   }
 }
 
 hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
-                           const int32_t *assign, int32_t dprime, float ratio0, float *tau, float *xn, float *thr,
-                           unsigned long long *best, hipStream_t st) {
+                           const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   int64_t blocks = (n + 3) / 4;
   const int64_t cap = (int64_t)num_cus() * 32;
   if (blocks > cap) blocks = cap;
-  hipLaunchKernelGGL(tau_init_kernel, dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, ds, Y, ldy, assign, dprime,
-                     ratio0, tau, xn, thr, best);
+  hipLaunchKernelGGL(tau_init_kernel, dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, ds, Y, ldy, assign, tau,
+                     best);
   return hipGetLastError();
 }
 

@@ -92,6 +92,7 @@ def pruned_case(orc, dg, n, d, k, seed, recipe):
     return X, R, Y, Xr, Yr, prev.astype(np.int32)
 
 
+@pytest.mark.parametrize("dense", [0.02, 1.0, 0.0, 0.3])   # default, hand-over after the first test, dense tiles only
 @pytest.mark.parametrize("n,d,k,dp,budget", [
     (2000, 128, 100, 0, 0),
     (3000, 208, 257, 0, 0),          # d' = 32, trailing 176 = 2 x 64 + 48 (short tail block)
@@ -99,19 +100,20 @@ def pruned_case(orc, dg, n, d, k, seed, recipe):
     (1500, 1536, 300, 160, 0),       # d' not a multiple of 64: last block holds 32 dims
     (4000, 100, 50, 48, 0),          # d not a multiple of 16: padded rows
     (3000, 128, 130, 128, 0),        # d' = d: the first test is the exact comparison, no trailing block
-    (5000, 128, 129, 0, 129 * 1024),  # survivor list sized for 1024 rows: 5 chunks
+    (5000, 128, 129, 0, 5248),       # hand-over list sized for 8 row tiles: 5 chunks of rows
 ])
-def test_pruned_step(skm, orc, dg, n, d, k, dp, budget):
-    say("pruned", n, d, k, dp, budget)
+def test_pruned_step(skm, orc, dg, n, d, k, dp, budget, dense):
+    say("pruned", n, d, k, dp, budget, dense)
     X, R, Y, Xr, Yr, prev = pruned_case(orc, dg, n, d, k, n + k, "linear" if d < 512 else "embed")
     dp = dp or orc.dprime_init(d)
     ref = orc.assign_pruned(Xr, Yr, prev, dp, EPS0, 0)
-    opts = skm.FitOptions(R=cuda(R), block_stats=True, pair_budget=budget)
+    opts = skm.FitOptions(R=cuda(R), block_stats=True, pair_budget=budget, dense_frac=dense)
     a, dist, row = skm.assign(cuda(X), cuda(Y), cuda(prev), dp, opts)
     a = a.cpu().numpy()
     check_assignment(a, ref.assign, Xr, Yr)
     same = a == ref.assign
-    assert np.abs(dist.cpu().numpy()[same] - ref.dist[same]).max() < 2e-6 * max(1.0, ref.dist.max())
+    # a distance finished inside a dense tile comes from the norm expansion accumulated in fp32 over d terms
+    assert np.abs(dist.cpu().numpy()[same] - ref.dist[same]).max() < 2e-5 * max(1.0, ref.dist.max())
     surv_ref = n * (k - 1) - ref.pruned_first
     assert abs(row["survivors"] - surv_ref) <= max(2, 1e-3 * surv_ref)
     assert row["dprime"] == dp and row["nblocks"] == len(ref.enter) - 1
