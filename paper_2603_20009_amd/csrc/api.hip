@@ -264,7 +264,7 @@ struct Ctx {
   int64_t pair_cap = 0, chunk_rows = 0;
   int32_t nchunks = 0;
   unsigned int emit_max = 0;         // a tile with at most this many alive pairs goes to the gather kernel
-  unsigned int *counters = nullptr;  // [nchunks] pair counts, then [1] overflow flag
+  unsigned int *counters = nullptr;  // [nchunks] pair counts, then [1] error flag (list overflow / unset point)
   float *ratio_dev = nullptr;        // [kMaxBlocks + 1]
   float ratio_host[kMaxBlocks + 1];  // staging for ratio_dev (must outlive the async copy)
   unsigned long long *scal = nullptr;  // [SC_COUNT]
@@ -292,6 +292,7 @@ struct Ctx {
     if (pair_budget <= 0) pair_budget = (int64_t)1 << 29;
     const int64_t col_tiles = progressive_tiles(1, k);
     int64_t row_tiles = std::max<int64_t>(pair_budget / (per_tile * col_tiles), 1);
+    row_tiles = std::min<int64_t>(row_tiles, std::max<int64_t>(((1 << 24) - 1) / col_tiles, 1));  // launch size limit
     chunk_rows = std::min<int64_t>(row_tiles * 128, (n + 127) / 128 * 128);
     nchunks = (int32_t)((n + chunk_rows - 1) / chunk_rows);
     pair_cap = progressive_tiles(std::min<int64_t>(chunk_rows, n), k) * per_tile;
@@ -327,22 +328,26 @@ struct StepStats {
 // Iteration 1 of Algorithm 1: exact assignment over all dims.  Leaves assign, dist, cluster sizes.
 int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
   tm.mark(ST_NONE);
+  HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * ((size_t)c.nchunks + 1), c.st));
   HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, c.ds, c.ynorm, 0, 0, nullptr, c.st));
   HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
   GemmOperands g{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, c.ds};
   HIPCHK(gemm_argmin(g, c.ynorm, c.best, c.st));
   tm.mark(ST_GEMM);
   // winners -> direct squared distances (also the objective of this step)
-  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, nullptr, nullptr, nullptr, nullptr, c.st));
+  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, nullptr, nullptr, nullptr, nullptr, c.counters + c.nchunks, c.st));
   HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.assign, nullptr, c.best, c.st));
   HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
   HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT, c.st));
-  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, nullptr, c.st));
+  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, nullptr, nullptr, c.st));
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
   double obj = 0;
+  unsigned int flag = 0;
   HIPCHK(hipMemcpyAsync(&obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(&flag, c.counters + c.nchunks, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipStreamSynchronize(c.st));
+  if (flag != 0) return fail(SKM_EINTERNAL, "a point was left without a centroid");
   ss = StepStats();
   ss.objective = obj;
   ss.dprime = c.d;
@@ -362,15 +367,15 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   float *ratio = c.ratio_host;
   for (int m = 0; m <= nb; ++m) ratio[m] = (float)theta_ratio(c.d, std::min(c.d, dprime + kBlockDims * m), eps0);
   HIPCHK(hipMemcpyAsync(c.ratio_dev, ratio, sizeof(float) * ((size_t)nb + 1), hipMemcpyHostToDevice, c.st));
+  HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * ((size_t)c.nchunks + 1), c.st));
   if (!have_prev) {
     HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
     GemmOperands g0{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, dprime};
     HIPCHK(gemm_argmin(g0, c.ynorm, c.best, c.st));
-    HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, nullptr, nullptr, c.st));
+    HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, nullptr, nullptr, c.counters + c.nchunks, c.st));
     tm.mark(ST_GEMM);
   }
   HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st));
-  HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * ((size_t)c.nchunks + 1), c.st));
   HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT, c.st));
   HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
   tm.mark(ST_TAU);
@@ -396,7 +401,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     }
   }
   HIPCHK(launch_finalize_assign(c.best, c.prev, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, c.scal + SC_CHANGED,
-                                c.st));
+                                nullptr, c.st));
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
   unsigned int overflow = 0;
@@ -406,7 +411,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   HIPCHK(hipMemcpyAsync(scal_h.data(), c.scal, sizeof(unsigned long long) * scal_h.size(), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipMemcpyAsync(&obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipStreamSynchronize(c.st));
-  if (overflow != 0) return fail(SKM_EINTERNAL, "survivor list overflow");
+  if (overflow != 0) return fail(SKM_EINTERNAL, "hand-over list overflow or a point left without a centroid");
   ss = StepStats();
   ss.survivors = (int64_t)scal_h[SC_SURVIVORS];
   ss.completed = (int64_t)scal_h[SC_COMPLETED];
@@ -881,7 +886,7 @@ int skm_assign_exact(const float *X, int64_t n, int32_t d, const float *centroid
   HIPCHK(launch_fill_u64(best, n, ~0ull, st));
   GemmOperands g{Xp, ldx, (int32_t)n, Yp, ldy, k, ds};
   HIPCHK(gemm_argmin(g, ynorm, best, st));
-  HIPCHK(launch_finalize_assign(best, nullptr, n, assign_out, nullptr, nullptr, nullptr, nullptr, st));
+  HIPCHK(launch_finalize_assign(best, nullptr, n, assign_out, nullptr, nullptr, nullptr, nullptr, nullptr, st));
   if (dist_out) {
     HIPCHK(launch_tau_init(Xp, ldx, n, ds, Yp, ldy, assign_out, dist_out, nullptr, st));
   }

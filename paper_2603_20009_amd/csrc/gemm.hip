@@ -11,6 +11,9 @@
 // a row argmin.  Iterations >= 2 use the progressive kernel of progressive.hip, built on the same tile.
 #include "skm_internal.h"
 
+#include <algorithm>
+#include <cstdlib>
+
 namespace skm {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -249,6 +252,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmOperands g, typename
   }
 }
 
+constexpr int64_t kMaxTilesPerLaunchFwd = (1 << 24) - 1;
 template <int BK>
 constexpr size_t smem_bytes() {
   return (size_t)2 * (BM + BN) * (BK + 4) * sizeof(float);
@@ -272,10 +276,17 @@ static hipError_t launch_one(const GemmOperands &g, const typename EpiArgs<EPI>:
   const int64_t nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
   const int64_t nwg = nrt * nct;
   if (nwg <= 0) return hipSuccess;
-  if (nwg > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (nwg > kMaxTilesPerLaunchFwd) return hipErrorInvalidValue;
   hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(NTHREADS), smem_bytes<BK>(), st, g, e);
   return hipGetLastError();
 }
+
+// A launch may not exceed 2^32 threads in total: at 256 threads per tile that is 2^24 - 1 tiles, so
+// tall problems are cut into bands of row tiles (the epilogue pointers move with the band).
+constexpr int64_t kMaxTilesPerLaunch = (1 << 24) - 1;
+
+inline void shift_rows(StoreArgs &e, int64_t r0) { e.C += r0 * e.ldc; }
+inline void shift_rows(ArgminArgs &e, int64_t r0) { e.best += r0; }
 
 template <int EPI>
 static hipError_t launch_any(const GemmOperands &g, const typename EpiArgs<EPI>::type &e, hipStream_t st) {
@@ -283,8 +294,26 @@ static hipError_t launch_any(const GemmOperands &g, const typename EpiArgs<EPI>:
   const bool al = operands_aligned(g);
   // slabs of 32 for long K; slabs of 16 when K is short or not a multiple of 32 (d' is a multiple of 16)
   const bool bk32 = (g.K % 32 == 0) && g.K >= 256;
-  if (al) return bk32 ? launch_one<32, EPI, true>(g, e, st) : launch_one<16, EPI, true>(g, e, st);
-  return bk32 ? launch_one<32, EPI, false>(g, e, st) : launch_one<16, EPI, false>(g, e, st);
+  const int64_t nct = (g.N + BN - 1) / BN;
+  // SKM_TEST_MAX_TILES lowers the limit so that the banding can be exercised on small inputs
+  static const int64_t max_tiles = []() {
+    const char *e = std::getenv("SKM_TEST_MAX_TILES");
+    const int64_t v = e ? std::atoll(e) : 0;
+    return (v > 0 && v < kMaxTilesPerLaunch) ? v : kMaxTilesPerLaunch;
+  }();
+  const int64_t band_rows = std::max<int64_t>(max_tiles / nct, 1) * BM;
+  for (int64_t r0 = 0; r0 < g.M; r0 += band_rows) {
+    GemmOperands gb = g;
+    gb.A = g.A + r0 * g.lda;
+    gb.M = (int32_t)std::min<int64_t>(band_rows, g.M - r0);
+    typename EpiArgs<EPI>::type eb = e;
+    shift_rows(eb, r0);
+    hipError_t rc;
+    if (al) rc = bk32 ? launch_one<32, EPI, true>(gb, eb, st) : launch_one<16, EPI, true>(gb, eb, st);
+    else rc = bk32 ? launch_one<32, EPI, false>(gb, eb, st) : launch_one<16, EPI, false>(gb, eb, st);
+    if (rc != hipSuccess) return rc;
+  }
+  return hipSuccess;
 }
 
 hipError_t gemm_store(const GemmOperands &g, float *C, int64_t ldc, int32_t Nstore, float alpha, float beta,

@@ -340,7 +340,7 @@ hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
     attr_set = true;
   }
   const int64_t nwg = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  if (nwg > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (nwg >= (1 << 24)) return hipErrorInvalidValue;   // 2^32 threads per launch at most; the caller chunks rows
   hipLaunchKernelGGL(progressive_kernel<BK>, dim3((unsigned)nwg), dim3(NT), smem, st, g);
   return hipGetLastError();
 }

@@ -125,7 +125,7 @@ int64_t finalize_blocks(int64_t n) { return (n + FIN_PER_BLOCK - 1) / FIN_PER_BL
 __global__ void __launch_bounds__(FIN_THREADS) finalize_assign_kernel(const unsigned long long *best,
                                                                       const int32_t *prev, int64_t n, int32_t *assign,
                                                                       float *dist, int32_t *cnt, double *obj_partial,
-                                                                      unsigned long long *changed) {
+                                                                      unsigned long long *changed, unsigned int *unset) {
   __shared__ double red[4];
   __shared__ unsigned int redc[4];
   double s = 0.0;
@@ -135,8 +135,13 @@ __global__ void __launch_bounds__(FIN_THREADS) finalize_assign_kernel(const unsi
     const int64_t i = base + t;
     if (i < n) {
       const unsigned long long key = best[i];
-      const int32_t a = (int32_t)(key & 0xffffffffull);
-      const float dv = ord2f((uint32_t)(key >> 32));
+      int32_t a = (int32_t)(key & 0xffffffffull);
+      float dv = ord2f((uint32_t)(key >> 32));
+      if (key == ~0ull) {   // a point no kernel offered a centroid for: reported through `unset`, kept in range
+        a = 0;
+        dv = 0.f;
+        if (unset) *unset = 1u;
+      }
       assign[i] = a;
       if (dist) dist[i] = dv;
       if (cnt) atomicAdd(cnt + a, 1);
@@ -160,10 +165,10 @@ __global__ void __launch_bounds__(FIN_THREADS) finalize_assign_kernel(const unsi
 
 hipError_t launch_finalize_assign(const unsigned long long *best, const int32_t *prev, int64_t n, int32_t *assign,
                                   float *dist, int32_t *cnt, double *obj_partial, unsigned long long *changed,
-                                  hipStream_t st) {
+                                  unsigned int *unset, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(finalize_assign_kernel, dim3((unsigned)finalize_blocks(n)), dim3(FIN_THREADS), 0, st, best, prev, n,
-                     assign, dist, cnt, obj_partial, changed);
+                     assign, dist, cnt, obj_partial, changed, unset);
   return hipGetLastError();
 }
 

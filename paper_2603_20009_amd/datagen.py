@@ -27,8 +27,11 @@ SIGMA_W = 0.5  # within/between ratio of the ``embed`` recipe
 
 
 def mixture(n: int, d: int, components: int, seed: int, recipe: str = "embed", device: str = "cpu",
-            chunk: int = 1 << 18, return_labels: bool = False):
-    """n x d fp32 rows of unit norm drawn from a `components`-component mixture."""
+            chunk: int = 1 << 18, return_labels: bool = False, sample_seed: int | None = None):
+    """n x d fp32 rows of unit norm drawn from a `components`-component mixture.
+
+    `seed` fixes the mixture (its means); `sample_seed` (default: seed + 1) fixes the rows drawn from
+    it, so that held-out rows of the same mixture are a second call with another `sample_seed`."""
     dev = torch.device(device)
     g = torch.Generator(device=dev)
     g.manual_seed(int(seed))
@@ -43,6 +46,7 @@ def mixture(n: int, d: int, components: int, seed: int, recipe: str = "embed", d
     else:
         raise ValueError(recipe)
     means = torch.randn(components, d, generator=g, device=dev, dtype=torch.float32) * mean_scale
+    g.manual_seed(int(seed) + 1 if sample_seed is None else int(sample_seed))
     out = torch.empty(n, d, device=dev, dtype=torch.float32)
     labels = torch.empty(n, device=dev, dtype=torch.int64) if return_labels else None
     for s in range(0, n, chunk):
@@ -76,8 +80,7 @@ def config_data(name: str, device: str = "cpu", n: int | None = None):
 
 
 def config_queries(name: str, device: str = "cpu", nq: int | None = None):
-    """Held-out queries: same mixture means (same seed for the means) is not
-    needed for the method; queries come from the same recipe with their own
-    seed, as rows the data set does not contain."""
+    """Held-out queries: rows of the same mixture as the data (same means) drawn with their own seed."""
     c = CONFIGS[name]
-    return mixture(nq or c.get("nq", 1000), c["d"], c["components"], SEED_QUERY, c["recipe"], device)
+    return mixture(nq or c.get("nq", 1000), c["d"], c["components"], SEED_DATA, c["recipe"], device,
+                   sample_seed=SEED_QUERY)

@@ -334,3 +334,29 @@ def test_c2_full_size_sampled_parity(skm, orc, dg):
         assert np.abs(Yn[int(c)].cpu().numpy() - mean).max() < 1e-6
     del X, fr
     torch.cuda.empty_cache()
+
+
+def test_tall_problems_are_cut_into_bands_of_row_tiles(orc, dg):
+    """A launch holds at most 2^24 - 1 tiles; the limit is lowered through the environment in a child
+    process so that the banding of the GEMM launches runs on a small input."""
+    import subprocess
+    import sys
+    import os
+    code = r'''
+import sys, numpy as np, torch
+sys.path.insert(0, %r)
+from paper_2603_20009_amd import skm, datagen
+from oracle import oracle as orc
+X = datagen.mixture(3000, 64, 20, 2, "linear").numpy()
+Y = X[:300].copy()
+a, dist = skm.assign_exact(torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda())
+ao, do = orc.assign_full(X.astype(np.float64), Y.astype(np.float64))
+assert (a.cpu().numpy() == ao).mean() > 0.999, (a.cpu().numpy() == ao).mean()
+R = orc.random_rotation(64, 1)
+out = skm.rotate(torch.from_numpy(X).cuda(), torch.from_numpy(R).cuda()).cpu().numpy()
+assert np.abs(out - orc.rotate(X, R)).max() < 2e-6
+print("banded ok")
+''' % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, SKM_TEST_MAX_TILES="7")   # 3 column tiles -> bands of 2 row tiles
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=240)
+    assert r.returncode == 0 and "banded ok" in r.stdout, r.stderr[-2000:]
