@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--n", type=int, default=0, help="override the number of points (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=12288)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one 1 GiB device copy first (a kernel of known traffic for scaling rocprofv3 --pmc counters)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (optional)")
     args = ap.parse_args()
@@ -69,6 +71,12 @@ def main():
     d, k, iters = cfg["d"], cfg["k"], cfg["iters"]
     seed = datagen.SEED_FIT
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     X = datagen.config_data(args.config, device="cuda", n=n)
     queries = datagen.config_queries(args.config, device="cuda") if cfg.get("etr") else None
     torch.cuda.synchronize()
@@ -99,46 +107,61 @@ def main():
         return float(np.mean([f(r) for r in results]))
 
     ds = (d + 15) // 16 * 16
+    tile_flop = 2.0 * 128 * 128           # MFMA flop per multiplied dimension of one 128 x 128 tile
     ms_rot = avg(lambda r: r.timing["ms_rotate"])
     ms_it1_gemm = avg(lambda r: r.trace[0]["ms_gemm"])
     later = lambda r: r.trace[1:]
-    ms_filter = avg(lambda r: np.mean([t["ms_gemm"] for t in later(r)]))
+    ms_prog = avg(lambda r: np.mean([t["ms_gemm"] for t in later(r)]))
     ms_tau = avg(lambda r: np.mean([t["ms_tau"] for t in later(r)]))
     ms_prune = avg(lambda r: np.mean([t["ms_prune"] for t in later(r)]))
     ms_update = avg(lambda r: np.mean([t["ms_update"] for t in r.trace[:r.iters_run]]))
     ms_iter1 = avg(lambda r: r.trace[0]["ms_step"])
     ms_iter_rest = avg(lambda r: np.median([t["ms_step"] for t in r.trace[1:r.iters_run]])) if iters_run > 1 else 0.0
-    dprimes = [t["dprime"] for t in results[-1].trace]
-    mean_dp = float(np.mean(dprimes[1:])) if len(dprimes) > 1 else 0.0
-    surv = [t["survivors"] for t in results[-1].trace[1:]]
+    last = results[-1]
+    dprimes = [t["dprime"] for t in last.trace]
+    steps2 = last.trace[1:]
+    # algorithmic flop of the progressive kernel per pruned step: the first-test GEMM on d' dims (2 n k d') plus
+    # 2 * 64 flop for every (alive pair, trailing block) step that ran inside a dense tile
+    flop_alg = float(np.mean([2.0 * n * k * t["dprime"] + 128.0 * t["dense_pair_blocks"] for t in steps2])) if steps2 else 0.0
+    flop_exec = float(np.mean([tile_flop * t["dense_dims"] for t in steps2])) if steps2 else 0.0
+    total_prog = float(np.sum([t["ms_gemm"] for t in steps2]))
     flops_rot = 2.0 * n * d * d
     flops_it1 = 2.0 * n * k * ds
     stages = {
         "rotation_gemm": dict(bound="mfma", ms=ms_rot, achieved=flops_rot / ms_rot / 1e9, unit="TFLOP/s"),
         "iter1_gemm_argmin": dict(bound="mfma", ms=ms_it1_gemm, achieved=flops_it1 / ms_it1_gemm / 1e9, unit="TFLOP/s"),
-        "partial_gemm_filter": dict(bound="mfma", ms=ms_filter, achieved=2.0 * n * k * mean_dp / ms_filter / 1e9,
-                                    unit="TFLOP/s"),
-        "tau_init": dict(bound="hbm", ms=ms_tau, achieved=(n * ds * 4.0 + 24.0 * n) / ms_tau / 1e6, unit="GB/s"),
-        "prune": dict(bound="hbm", ms=ms_prune,
-                      achieved=(n * (ds - mean_dp) * 4.0 + 16.0 * float(np.mean(surv) if surv else 0)) / ms_prune / 1e6,
-                      unit="GB/s"),
+        "progressive_gemm": dict(bound="mfma", ms=ms_prog, achieved=flop_alg / ms_prog / 1e9, unit="TFLOP/s",
+                                 executed=flop_exec / ms_prog / 1e9),
+        "tau_init": dict(bound="hbm", ms=ms_tau, achieved=(n * ds * 4.0 + 12.0 * n) / ms_tau / 1e6, unit="GB/s"),
+        "gather_prune": dict(bound="hbm", ms=ms_prune, achieved=None, unit="GB/s"),
         "update": dict(bound="hbm", ms=ms_update, achieved=(n * ds * 4.0 + 8.0 * n + 2.0 * k * ds * 4.0) / ms_update / 1e6,
                        unit="GB/s"),
     }
     for s in stages.values():
-        s["frac"] = s["achieved"] / (PEAK_FP32_MFMA_TFLOPS if s["bound"] == "mfma" else PEAK_HBM_GBS)
-    # dominant kernel of the fit = the fp32 MFMA GEMM; its longest launch is the rotation (2 n d^2 flop)
-    dom = "rotation_gemm" if ms_rot >= ms_it1_gemm else "iter1_gemm_argmin"
+        if s["achieved"] is not None:
+            s["frac"] = s["achieved"] / (PEAK_FP32_MFMA_TFLOPS if s["bound"] == "mfma" else PEAK_HBM_GBS)
+    # dominant kernel of the fit by total time
+    totals = {"rotation_gemm": ms_rot, "iter1_gemm_argmin": ms_it1_gemm, "progressive_gemm": total_prog}
+    dom = max(totals, key=totals.get)
     traffic = None
     if os.path.exists(args.traffic_json):
         try:
             traffic = json.load(open(args.traffic_json)).get(args.config, {}).get(dom)
         except Exception:
             traffic = None
-    roofline = dict(bound="mfma", kernel=f"skm::gemm_kernel ({dom})", achieved=stages[dom]["achieved"],
-                    peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s", frac=stages[dom]["frac"], traffic=traffic,
-                    ms_per_launch=stages[dom]["ms"],
-                    flops_per_launch=flops_rot if dom == "rotation_gemm" else flops_it1)
+    kname = {"rotation_gemm": "skm::gemm_kernel<32,store>", "iter1_gemm_argmin": "skm::gemm_kernel<32,argmin>",
+             "progressive_gemm": "skm::progressive_kernel<32>"}[dom]
+    roofline = dict(bound="mfma", kernel=kname, achieved=stages[dom]["achieved"], peak=PEAK_FP32_MFMA_TFLOPS,
+                    unit="TFLOP/s", frac=stages[dom]["frac"], traffic=traffic,
+                    ms_per_step=stages[dom]["ms"], total_ms_per_fit=totals[dom],
+                    flop_per_step={"rotation_gemm": flops_rot, "iter1_gemm_argmin": flops_it1,
+                                   "progressive_gemm": flop_alg}[dom],
+                    note="achieved = algorithmic flop (first-test GEMM 2nkd' + 128 per alive pair-block done densely) per "
+                         "pruned step / device time of the kernel's launches in that step (HIP events); 'executed' in "
+                         "stages counts every dimension the tiles multiplied")
+    if dom == "progressive_gemm":
+        roofline["executed"] = stages[dom]["executed"]
+        roofline["executed_frac"] = stages[dom]["executed"] / PEAK_FP32_MFMA_TFLOPS
 
     out = {
         "metric": "point*centroid*dim per second over one SuperKMeans fit (seconds per k-means iteration alongside)",

@@ -46,6 +46,10 @@ typedef struct skm_trace_row {
   int64_t completed;   /* pairs whose distance was finished over all d dimensions */
   int64_t changed;     /* points whose assignment changed in this step */
   int64_t nempty;      /* empty clusters found by the update that followed */
+  int64_t dense_dims;  /* dimensions multiplied on the matrix cores, summed over the 128 x 128 tiles of the step
+                          (x 2*128*128 = executed MFMA flop of the progressive kernel) */
+  int64_t dense_pair_blocks; /* (pair, trailing block) steps of alive pairs that were done inside dense tiles
+                                (the rest of the steps went through the gather kernel) */
   int32_t dprime;      /* d' used by this step (d for iteration 1) */
   int32_t nblocks;     /* trailing 64-dim blocks (the last may be shorter) */
   int64_t enter[SKM_MAX_BLOCKS]; /* pairs that entered trailing block m (only when

@@ -245,7 +245,7 @@ int check_shape(const void *X, int64_t n, int32_t d, int32_t k) {
 
 // ---------------------------------------------------------------- one fit / assign context
 // device scalars of one assignment step
-enum { SC_COMPLETED = 0, SC_CHANGED = 1, SC_SURVIVORS = 2, SC_ENTER = 3, SC_COUNT = 3 + kMaxBlocks };
+enum { SC_COMPLETED = 0, SC_CHANGED = 1, SC_SURVIVORS = 2, SC_DENSE_DIMS = 3, SC_DENSE_PB = 4, SC_ENTER = 5, SC_COUNT = 5 + kMaxBlocks };
 
 struct Ctx {
   hipStream_t st = nullptr;
@@ -319,7 +319,7 @@ struct Ctx {
 
 struct StepStats {
   double objective = 0;
-  int64_t survivors = 0, completed = 0, changed = 0;
+  int64_t survivors = 0, completed = 0, changed = 0, dense_dims = 0, dense_pair_blocks = 0;
   int64_t enter[SKM_MAX_BLOCKS] = {0};
   int32_t dprime = 0, nblocks = 0;
   bool pruned = false;  // false for the exact step of iteration 1
@@ -391,6 +391,8 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     g.overflow = c.counters + c.nchunks; g.emit_max = c.emit_max;
     g.best = c.best; g.survivors = c.scal + SC_SURVIVORS; g.completed = c.scal + SC_COMPLETED;
     g.enter = c.block_stats ? c.scal + SC_ENTER : nullptr;
+    g.dense_dims = c.scal + SC_DENSE_DIMS;
+    g.dense_pair_blocks = c.scal + SC_DENSE_PB;
     HIPCHK(launch_progressive(g, c.st));
     tm.mark(ST_GEMM);
     if (c.emit_max > 0) {
@@ -416,6 +418,8 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   ss.survivors = (int64_t)scal_h[SC_SURVIVORS];
   ss.completed = (int64_t)scal_h[SC_COMPLETED];
   ss.changed = (int64_t)scal_h[SC_CHANGED];
+  ss.dense_dims = (int64_t)scal_h[SC_DENSE_DIMS];
+  ss.dense_pair_blocks = (int64_t)scal_h[SC_DENSE_PB];
   for (int m = 0; m < std::min<int>(nb, SKM_MAX_BLOCKS); ++m) ss.enter[m] = (int64_t)scal_h[SC_ENTER + (size_t)m];
   ss.objective = obj;
   ss.dprime = dprime;
@@ -478,6 +482,8 @@ void fill_row(skm_trace_row &r, const StepStats &ss, int64_t n, int32_t k, int64
   r.survivors = ss.survivors;
   r.completed = ss.completed;
   r.changed = ss.changed;
+  r.dense_dims = ss.dense_dims;
+  r.dense_pair_blocks = ss.dense_pair_blocks;
   r.nempty = nempty;
   r.dprime = ss.dprime;
   r.nblocks = ss.nblocks;

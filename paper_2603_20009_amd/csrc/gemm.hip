@@ -51,13 +51,12 @@ struct EpiArgs<EPI_ARGMIN> {
 // contiguous range of logical tile ids, and walk the tiles in panels of PC column tiles with the
 // row tile advancing slowest inside a panel, so that the workgroups resident on one XCD share a
 // few row tiles of A and one panel of B.
-__device__ inline void tile_of_block(int nrt, int nct, int &rt, int &ct) {
+__device__ inline void tile_of_block(int nrt, int nct, int PC, int &rt, int &ct) {
   const int nwg = gridDim.x;
   const int bid = blockIdx.x;
   const int xcd = bid & 7, q = bid >> 3;
   const int base = nwg >> 3, rem = nwg & 7;
   const int logical = xcd * base + (xcd < rem ? xcd : rem) + q;
-  constexpr int PC = 16;
   const int panel_sz = PC * nrt;
   const int p = logical / panel_sz;
   const int r = logical - p * panel_sz;
@@ -83,7 +82,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmOperands g, typename
 
   const int nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
   int rt, ct;
-  tile_of_block(nrt, nct, rt, ct);
+  tile_of_block(nrt, nct, g.panel_cols, rt, ct);
   const int row0 = rt * BM, col0 = ct * BN;
 
   float4 ra[A_F4], rb[B_F4];
@@ -285,6 +284,17 @@ static hipError_t launch_one(const GemmOperands &g, const typename EpiArgs<EPI>:
 // tall problems are cut into bands of row tiles (the epilogue pointers move with the band).
 constexpr int64_t kMaxTilesPerLaunch = (1 << 24) - 1;
 
+// Column tiles per panel of the tile walk.  Measured on MI355X (rotation and iteration-1 GEMMs of the
+// 1M x 1536 workload, widths 1..12): no effect on the run time, the kernel is bound by the matrix pipe;
+// SKM_TEST_PANEL_COLS overrides the width for experiments.
+static int panel_cols_for(int) {
+  static const int forced = []() {
+    const char *e = std::getenv("SKM_TEST_PANEL_COLS");
+    return e ? std::atoi(e) : 0;
+  }();
+  return forced > 0 ? forced : 16;
+}
+
 inline void shift_rows(StoreArgs &e, int64_t r0) { e.C += r0 * e.ldc; }
 inline void shift_rows(ArgminArgs &e, int64_t r0) { e.best += r0; }
 
@@ -304,6 +314,7 @@ static hipError_t launch_any(const GemmOperands &g, const typename EpiArgs<EPI>:
   const int64_t band_rows = std::max<int64_t>(max_tiles / nct, 1) * BM;
   for (int64_t r0 = 0; r0 < g.M; r0 += band_rows) {
     GemmOperands gb = g;
+    gb.panel_cols = panel_cols_for(g.K);
     gb.A = g.A + r0 * g.lda;
     gb.M = (int32_t)std::min<int64_t>(band_rows, g.M - r0);
     typename EpiArgs<EPI>::type eb = e;

@@ -239,6 +239,10 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
           if (!last && g.enter) atomicAdd(g.enter + m, (unsigned long long)total);
           if (last) atomicAdd(g.completed, (unsigned long long)total);
         }
+        if (total == 0u || last || total <= g.emit_max)   // the tile ends here
+          atomicAdd(g.dense_dims, (unsigned long long)(BK * (s + 1)));
+        else                                               // the next block of these pairs is done densely
+          atomicAdd(g.dense_pair_blocks, (unsigned long long)total);
       }
       if (total == 0u) return;
       if (last) {

@@ -44,6 +44,7 @@ struct GemmOperands {
   int64_t ldb;
   int32_t N;
   int32_t K;
+  int32_t panel_cols = 16;  // column tiles per panel of the tile walk (set by the launcher)
 };
 
 // C[i][j] = alpha * s(i,j) + beta * C[i][j] for j < N; columns N <= j < Nstore are written as 0.
@@ -80,6 +81,8 @@ struct ProgArgs {
   unsigned long long *survivors;  // += pairs alive after the first test
   unsigned long long *completed;  // += pairs finished over all d dims
   unsigned long long *enter;      // [nb] += pairs entering trailing block m, or NULL
+  unsigned long long *dense_dims; // += dimensions multiplied, summed over tiles
+  unsigned long long *dense_pair_blocks;  // += (alive pairs) per trailing block that was multiplied densely
 };
 hipError_t launch_progressive(const ProgArgs &g, hipStream_t st);
 int64_t progressive_tiles(int64_t rows, int32_t k);

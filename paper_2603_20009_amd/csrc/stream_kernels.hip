@@ -29,6 +29,9 @@ static int num_cus() {
 // ------------------------------------------------------------------ initial threshold
 // One wavefront per point: the rotated row and the row of its incumbent centroid are read as
 // float4 per lane (1 KiB per wavefront load); squared differences over all dims give tau_i.
+// NV = float4 loads per lane and operand (rows of up to 256 * NV floats): all loads of a row pair are
+// issued before the first use, so that a wavefront keeps 2 * NV KiB in flight.
+template <int NV>
 __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t ldx, int64_t n, int32_t ds,
                                                        const float *Y, int64_t ldy, const int32_t *assign, float *tau,
                                                        unsigned long long *best) {
@@ -39,14 +42,36 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
     const float *x = Xr + i * ldx;
     const float *y = Y + (int64_t)a * ldy;
     float s = 0.f;
-    for (int c = lane * 4; c < ds; c += 256) {
-      const float4 xv = *reinterpret_cast<const float4 *>(x + c);
-      const float4 yv = *reinterpret_cast<const float4 *>(y + c);
-      const float dx = xv.x - yv.x, dy = xv.y - yv.y, dz = xv.z - yv.z, dw = xv.w - yv.w;
-      s = fmaf(dx, dx, s);
-      s = fmaf(dy, dy, s);
-      s = fmaf(dz, dz, s);
-      s = fmaf(dw, dw, s);
+    if (NV > 0) {
+      float4 xv[NV > 0 ? NV : 1], yv[NV > 0 ? NV : 1];
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        const int c = lane * 4 + 256 * u;
+        xv[u] = c < ds ? *reinterpret_cast<const float4 *>(x + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        const int c = lane * 4 + 256 * u;
+        yv[u] = c < ds ? *reinterpret_cast<const float4 *>(y + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        const float dx = xv[u].x - yv[u].x, dy = xv[u].y - yv[u].y, dz = xv[u].z - yv[u].z, dw = xv[u].w - yv[u].w;
+        s = fmaf(dx, dx, s);
+        s = fmaf(dy, dy, s);
+        s = fmaf(dz, dz, s);
+        s = fmaf(dw, dw, s);
+      }
+    } else {
+      for (int c = lane * 4; c < ds; c += 256) {
+        const float4 xv = *reinterpret_cast<const float4 *>(x + c);
+        const float4 yv = *reinterpret_cast<const float4 *>(y + c);
+        const float dx = xv.x - yv.x, dy = xv.y - yv.y, dz = xv.z - yv.z, dw = xv.w - yv.w;
+        s = fmaf(dx, dx, s);
+        s = fmaf(dy, dy, s);
+        s = fmaf(dz, dz, s);
+        s = fmaf(dw, dw, s);
+      }
     }
     s = wave_sum(s);
     if (lane == 0) {
@@ -62,8 +87,18 @@ hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, 
   int64_t blocks = (n + 3) / 4;
   const int64_t cap = (int64_t)num_cus() * 32;
   if (blocks > cap) blocks = cap;
-  hipLaunchKernelGGL(tau_init_kernel, dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, ds, Y, ldy, assign, tau,
-                     best);
+  const int nv = (ds + 255) / 256;
+#define SKM_TAU_LAUNCH(NV)                                                                                          \
+  hipLaunchKernelGGL(tau_init_kernel<NV>, dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, ds, Y, ldy, assign, \
+                     tau, best)
+  if (nv <= 1) SKM_TAU_LAUNCH(1);
+  else if (nv <= 2) SKM_TAU_LAUNCH(2);
+  else if (nv <= 3) SKM_TAU_LAUNCH(3);
+  else if (nv <= 4) SKM_TAU_LAUNCH(4);
+  else if (nv <= 6) SKM_TAU_LAUNCH(6);
+  else if (nv <= 8) SKM_TAU_LAUNCH(8);
+  else SKM_TAU_LAUNCH(0);
+#undef SKM_TAU_LAUNCH
   return hipGetLastError();
 }
 

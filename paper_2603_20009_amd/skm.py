@@ -22,6 +22,7 @@ class TraceRow(C.Structure):
     _fields_ = [
         ("objective", C.c_double), ("prune_frac", C.c_double), ("recall", C.c_double),
         ("survivors", C.c_int64), ("completed", C.c_int64), ("changed", C.c_int64), ("nempty", C.c_int64),
+        ("dense_dims", C.c_int64), ("dense_pair_blocks", C.c_int64),
         ("dprime", C.c_int32), ("nblocks", C.c_int32),
         ("enter", C.c_int64 * MAX_BLOCKS),
         ("ms_tau", C.c_float), ("ms_gemm", C.c_float), ("ms_prune", C.c_float), ("ms_update", C.c_float),
@@ -158,7 +159,8 @@ class FitResult:
 
 def _row_dict(r: TraceRow) -> dict:
     return dict(objective=r.objective, prune_frac=r.prune_frac, recall=r.recall, survivors=int(r.survivors),
-                completed=int(r.completed), changed=int(r.changed), nempty=int(r.nempty), dprime=int(r.dprime),
+                completed=int(r.completed), changed=int(r.changed), nempty=int(r.nempty),
+                dense_dims=int(r.dense_dims), dense_pair_blocks=int(r.dense_pair_blocks), dprime=int(r.dprime),
                 nblocks=int(r.nblocks), enter=[int(v) for v in r.enter], ms_tau=r.ms_tau, ms_gemm=r.ms_gemm,
                 ms_prune=r.ms_prune, ms_update=r.ms_update, ms_etr=r.ms_etr, ms_step=r.ms_step)
 

@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(skm):
 
 def test_struct_sizes_match_header(skm):
     # sizes implied by include/skm.h on LP64: catches a field added on one side only
-    assert C.sizeof(skm.TraceRow) == 3 * 8 + 4 * 8 + 2 * 4 + 32 * 8 + 6 * 4
+    assert C.sizeof(skm.TraceRow) == 3 * 8 + 6 * 8 + 2 * 4 + 32 * 8 + 6 * 4
     assert C.sizeof(skm.Trace) == 4 * 4 + 6 * 4 + 8
     assert C.sizeof(skm.Params) == 10 * 4 + 2 * 8 + 6 * 4 + 4 * 8 + 8 + 2 * 4
     p = skm.Params()
