@@ -168,7 +168,8 @@ int skm_update(const float *X, int64_t n, int32_t d, const int32_t *assign, int3
                void *stream, float *centroids, int32_t *counts_out);
 
 /* Random orthogonal d x d matrix (Algorithm 1, first line) written to device
- * memory R_out; Haar-distributed (Gram-Schmidt of a seeded Gaussian matrix). */
+ * memory R_out; Haar-distributed (Gram-Schmidt, in fp64 on the device, of a seeded Gaussian
+ * matrix); a function of (d, seed) only, reproducible bit by bit. */
 int skm_make_rotation(int32_t d, uint64_t seed, void *stream, float *R_out);
 
 /* out = X R (n x d), the rotation GEMM (Algorithm 1, second line); with

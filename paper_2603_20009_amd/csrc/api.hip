@@ -10,7 +10,6 @@
 #include <cstring>
 #include <limits>
 #include <string>
-#include <thread>
 #include <vector>
 
 using namespace skm;
@@ -156,80 +155,15 @@ int32_t nprobe_of(int32_t k, double frac) {
   return std::min(std::max(np, 1), k);
 }
 
-// ---------------------------------------------------------------- rotation matrix (host, fp64)
-template <typename F>
-void parallel_for(int n, F f) {
-  unsigned hw = std::thread::hardware_concurrency();
-  int nt = (int)std::min<unsigned>(hw ? hw : 4u, 16u);
-  nt = std::min(nt, n);
-  if (nt <= 1) {
-    for (int i = 0; i < n; ++i) f(i);
-    return;
-  }
-  std::vector<std::thread> th;
-  for (int t = 0; t < nt; ++t)
-    th.emplace_back([=]() {
-      for (int i = t; i < n; i += nt) f(i);
-    });
-  for (auto &x : th) x.join();
-}
-
-double dot4(const double *a, const double *b, int n) {
-  double s0 = 0, s1 = 0, s2 = 0, s3 = 0;
-  int j = 0;
-  for (; j + 4 <= n; j += 4) {
-    s0 += a[j] * b[j];
-    s1 += a[j + 1] * b[j + 1];
-    s2 += a[j + 2] * b[j + 2];
-    s3 += a[j + 3] * b[j + 3];
-  }
-  for (; j < n; ++j) s0 += a[j] * b[j];
-  return (s0 + s1) + (s2 + s3);
-}
-
-// Rows of a seeded Gaussian matrix, orthonormalised by Gram-Schmidt (twice): a Haar-distributed
-// orthogonal matrix.  Panels of rows are first cleared of all finished rows (independent per row,
-// threaded), then orthonormalised among themselves.
-void make_rotation_host(int32_t d, uint64_t seed, std::vector<float> &out) {
-  std::vector<double> Q((size_t)d * d);
-  Rng r = rng_stream(seed, STREAM_ROTATION);
-  for (size_t i = 0; i + 1 < Q.size() + 1; i += 2) {  // Box-Muller pairs
-    double u1 = r.uniform(), u2 = r.uniform();
-    if (u1 < 1e-300) u1 = 1e-300;
-    const double m = std::sqrt(-2.0 * std::log(u1));
-    Q[i] = m * std::cos(6.283185307179586 * u2);
-    if (i + 1 < Q.size()) Q[i + 1] = m * std::sin(6.283185307179586 * u2);
-  }
-  const int PANEL = 32;
-  for (int p0 = 0; p0 < d; p0 += PANEL) {
-    const int p1 = std::min(d, p0 + PANEL);
-    if (p0 > 0)
-      parallel_for(p1 - p0, [&](int ri) {
-        double *v = &Q[(size_t)(p0 + ri) * d];
-        std::vector<double> c((size_t)p0);
-        for (int pass = 0; pass < 2; ++pass) {
-          for (int j = 0; j < p0; ++j) c[(size_t)j] = dot4(&Q[(size_t)j * d], v, d);
-          for (int j = 0; j < p0; ++j) {
-            const double cj = c[(size_t)j];
-            const double *qj = &Q[(size_t)j * d];
-            for (int t = 0; t < d; ++t) v[t] -= cj * qj[t];
-          }
-        }
-      });
-    for (int i = p0; i < p1; ++i) {
-      double *v = &Q[(size_t)i * d];
-      for (int pass = 0; pass < 2; ++pass)
-        for (int j = p0; j < i; ++j) {
-          const double *qj = &Q[(size_t)j * d];
-          const double cj = dot4(qj, v, d);
-          for (int t = 0; t < d; ++t) v[t] -= cj * qj[t];
-        }
-      const double nrm = std::sqrt(dot4(v, v, d));
-      for (int t = 0; t < d; ++t) v[t] /= nrm;
-    }
-  }
-  out.resize((size_t)d * d);
-  for (size_t i = 0; i < out.size(); ++i) out[i] = (float)Q[i];
+// ---------------------------------------------------------------- rotation matrix (device, fp64)
+int make_rotation_dev(Pool &pool, int32_t d, uint64_t seed, hipStream_t st, float *R_out) {
+  double *Qw = nullptr, *Cw = nullptr, *Ww = nullptr, *Lw = nullptr;
+  HIPCHK(pool.get(&Qw, (size_t)d * d + 2));
+  HIPCHK(pool.get(&Cw, std::max<size_t>((size_t)4 * 32 * d, (size_t)((d + 127) / 128) * 32 * 32)));
+  HIPCHK(pool.get(&Ww, (size_t)8 * 32 * d));
+  HIPCHK(pool.get(&Lw, (size_t)32 * 32));
+  HIPCHK(launch_make_rotation(d, rng_stream(seed, STREAM_ROTATION).s, Qw, Cw, Ww, Lw, R_out, st));
+  return SKM_OK;
 }
 
 inline int32_t round_up(int32_t v, int32_t m) { return (v + m - 1) / m * m; }
@@ -244,9 +178,6 @@ int check_shape(const void *X, int64_t n, int32_t d, int32_t k) {
 }
 
 // ---------------------------------------------------------------- one fit / assign context
-// device scalars of one assignment step
-enum { SC_COMPLETED = 0, SC_CHANGED = 1, SC_SURVIVORS = 2, SC_DENSE_DIMS = 3, SC_DENSE_PB = 4, SC_ENTER = 5, SC_COUNT = 5 + kMaxBlocks };
-
 struct Ctx {
   hipStream_t st = nullptr;
   Pool pool;
@@ -261,10 +192,11 @@ struct Ctx {
   unsigned long long *best = nullptr;
   int32_t *assign = nullptr, *prev = nullptr;
   Pair *pairs = nullptr;
-  int64_t pair_cap = 0, chunk_rows = 0;
+  int64_t pair_cap = 0, sub_cap = 0, chunk_rows = 0;
   int32_t nchunks = 0;
   unsigned int emit_max = 0;         // a tile with at most this many alive pairs goes to the gather kernel
-  unsigned int *counters = nullptr;  // [nchunks] pair counts, then [1] error flag (list overflow / unset point)
+  unsigned int *counters = nullptr;  // per chunk the fill counters of the sub-lists, then [1] error flag (overflow / unset point)
+  size_t ncounters = 0;              // words in `counters` before the flag
   float *ratio_dev = nullptr;        // [kMaxBlocks + 1]
   float ratio_host[kMaxBlocks + 1];  // staging for ratio_dev (must outlive the async copy)
   unsigned long long *scal = nullptr;  // [SC_COUNT]
@@ -295,12 +227,16 @@ struct Ctx {
     row_tiles = std::min<int64_t>(row_tiles, std::max<int64_t>(((1 << 24) - 1) / col_tiles, 1));  // launch size limit
     chunk_rows = std::min<int64_t>(row_tiles * 128, (n + 127) / 128 * 128);
     nchunks = (int32_t)((n + chunk_rows - 1) / chunk_rows);
-    pair_cap = progressive_tiles(std::min<int64_t>(chunk_rows, n), k) * per_tile;
+    // each of the kSubLists parts must hold what the tiles of one XCD can hand over
+    const int64_t tiles_chunk = progressive_tiles(std::min<int64_t>(chunk_rows, n), k);
+    sub_cap = ((tiles_chunk + kSubLists - 1) / kSubLists) * per_tile;
+    pair_cap = sub_cap * kSubLists;
     if (pair_cap >= ((int64_t)1 << 32)) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
     HIPCHK(pool.get(&pairs, (size_t)pair_cap));
-    HIPCHK(pool.get(&counters, (size_t)nchunks + 1));
+    ncounters = (size_t)nchunks * kSubLists * kSubListStride;
+    HIPCHK(pool.get(&counters, ncounters + 1));
     HIPCHK(pool.get(&ratio_dev, (size_t)kMaxBlocks + 1));
-    HIPCHK(pool.get(&scal, (size_t)SC_COUNT));
+    HIPCHK(pool.get(&scal, (size_t)SC_COUNT * kStatReplicas));
     HIPCHK(pool.get(&obj_partial, (size_t)finalize_blocks(n)));
     HIPCHK(pool.get(&obj, 1));
     HIPCHK(pool.get(&up.cnt, (size_t)k));
@@ -328,24 +264,24 @@ struct StepStats {
 // Iteration 1 of Algorithm 1: exact assignment over all dims.  Leaves assign, dist, cluster sizes.
 int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
   tm.mark(ST_NONE);
-  HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * ((size_t)c.nchunks + 1), c.st));
+  HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * (c.ncounters + 1), c.st));
   HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, c.ds, c.ynorm, 0, 0, nullptr, c.st));
   HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
   GemmOperands g{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, c.ds};
   HIPCHK(gemm_argmin(g, c.ynorm, c.best, c.st));
   tm.mark(ST_GEMM);
   // winners -> direct squared distances (also the objective of this step)
-  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, nullptr, nullptr, nullptr, nullptr, c.counters + c.nchunks, c.st));
+  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, nullptr, nullptr, nullptr, nullptr, c.counters + c.ncounters, c.st));
   HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.assign, nullptr, c.best, c.st));
   HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
-  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT, c.st));
+  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT * kStatReplicas, c.st));
   HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, nullptr, nullptr, c.st));
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
   double obj = 0;
   unsigned int flag = 0;
   HIPCHK(hipMemcpyAsync(&obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
-  HIPCHK(hipMemcpyAsync(&flag, c.counters + c.nchunks, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(&flag, c.counters + c.ncounters, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipStreamSynchronize(c.st));
   if (flag != 0) return fail(SKM_EINTERNAL, "a point was left without a centroid");
   ss = StepStats();
@@ -367,16 +303,16 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   float *ratio = c.ratio_host;
   for (int m = 0; m <= nb; ++m) ratio[m] = (float)theta_ratio(c.d, std::min(c.d, dprime + kBlockDims * m), eps0);
   HIPCHK(hipMemcpyAsync(c.ratio_dev, ratio, sizeof(float) * ((size_t)nb + 1), hipMemcpyHostToDevice, c.st));
-  HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * ((size_t)c.nchunks + 1), c.st));
+  HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * (c.ncounters + 1), c.st));
   if (!have_prev) {
     HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
     GemmOperands g0{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, dprime};
     HIPCHK(gemm_argmin(g0, c.ynorm, c.best, c.st));
-    HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, nullptr, nullptr, c.counters + c.nchunks, c.st));
+    HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, nullptr, nullptr, c.counters + c.ncounters, c.st));
     tm.mark(ST_GEMM);
   }
   HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st));
-  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT, c.st));
+  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT * kStatReplicas, c.st));
   HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
   tm.mark(ST_TAU);
   for (int32_t ch = 0; ch < c.nchunks; ++ch) {
@@ -387,17 +323,15 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     g.B = c.Y; g.ldb = c.ds; g.N = c.k;
     g.ds = c.ds; g.d = c.d; g.dprime = dprime; g.nb = nb;
     g.ratio = c.ratio_dev; g.tau = c.tau; g.prev = c.prev; g.row_base = r0;
-    g.pairs = c.pairs; g.pair_count = c.counters + ch; g.capacity = (unsigned int)c.pair_cap;
-    g.overflow = c.counters + c.nchunks; g.emit_max = c.emit_max;
-    g.best = c.best; g.survivors = c.scal + SC_SURVIVORS; g.completed = c.scal + SC_COMPLETED;
-    g.enter = c.block_stats ? c.scal + SC_ENTER : nullptr;
-    g.dense_dims = c.scal + SC_DENSE_DIMS;
-    g.dense_pair_blocks = c.scal + SC_DENSE_PB;
+    unsigned int *fill = c.counters + (size_t)ch * kSubLists * kSubListStride;
+    g.pairs = c.pairs; g.pair_count = fill; g.sub_capacity = (unsigned int)c.sub_cap;
+    g.overflow = c.counters + c.ncounters; g.emit_max = c.emit_max;
+    g.best = c.best; g.scal = c.scal; g.block_stats = c.block_stats ? 1 : 0;
     HIPCHK(launch_progressive(g, c.st));
     tm.mark(ST_GEMM);
     if (c.emit_max > 0) {
-      PruneArgs pa{c.pairs, c.counters + ch, c.Xr, c.ldx, c.Ypdx, c.k, dprime, c.ds, nb, c.ratio_dev, c.best,
-                   c.scal + SC_COMPLETED, c.block_stats ? c.scal + SC_ENTER : nullptr};
+      PruneArgs pa{c.pairs, fill, (unsigned int)c.sub_cap, c.Xr, c.ldx, c.Ypdx, c.k, dprime, c.ds, nb, c.ratio_dev,
+                   c.best, c.scal, c.block_stats ? 1 : 0};
       HIPCHK(launch_prune(pa, c.st));
       tm.mark(ST_PRUNE);
     }
@@ -407,13 +341,15 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
   unsigned int overflow = 0;
-  std::vector<unsigned long long> scal_h((size_t)SC_COUNT);
+  std::vector<unsigned long long> scal_h((size_t)SC_COUNT * kStatReplicas);
   double obj = 0;
-  HIPCHK(hipMemcpyAsync(&overflow, c.counters + c.nchunks, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(&overflow, c.counters + c.ncounters, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipMemcpyAsync(scal_h.data(), c.scal, sizeof(unsigned long long) * scal_h.size(), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipMemcpyAsync(&obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipStreamSynchronize(c.st));
   if (overflow != 0) return fail(SKM_EINTERNAL, "hand-over list overflow or a point left without a centroid");
+  for (int r = 1; r < kStatReplicas; ++r)   // fold the replicas into the first
+    for (int q = 0; q < SC_COUNT; ++q) scal_h[(size_t)q] += scal_h[(size_t)r * SC_COUNT + q];
   ss = StepStats();
   ss.survivors = (int64_t)scal_h[SC_SURVIVORS];
   ss.completed = (int64_t)scal_h[SC_COMPLETED];
@@ -503,11 +439,9 @@ struct Rot {
 int setup_rotation(Pool &pool, hipStream_t st, int32_t d, int32_t ds, const float *R_dev, uint64_t seed, Rot &rot) {
   float *Rown = nullptr;
   if (!R_dev) {
-    std::vector<float> Rh;
-    make_rotation_host(d, seed, Rh);
     HIPCHK(pool.get(&Rown, (size_t)d * d));
-    HIPCHK(hipMemcpyAsync(Rown, Rh.data(), sizeof(float) * Rh.size(), hipMemcpyHostToDevice, st));
-    HIPCHK(hipStreamSynchronize(st));
+    int rc = make_rotation_dev(pool, d, seed, st, Rown);
+    if (rc) return rc;
     R_dev = Rown;
   }
   HIPCHK(pool.get(&rot.Rp, (size_t)d * ds));
@@ -945,10 +879,10 @@ int skm_update(const float *X, int64_t n, int32_t d, const int32_t *assign, int3
 int skm_make_rotation(int32_t d, uint64_t seed, void *stream, float *R_out) {
   if (!R_out) return fail(SKM_EINVAL, "null pointer");
   if (d < 1 || d > 16384) return fail(SKM_EINVAL, "d out of range");
-  std::vector<float> Rh;
-  make_rotation_host(d, seed, Rh);
   hipStream_t st = (hipStream_t)stream;
-  HIPCHK(hipMemcpyAsync(R_out, Rh.data(), sizeof(float) * Rh.size(), hipMemcpyHostToDevice, st));
+  Pool pool;
+  int rc = make_rotation_dev(pool, d, seed, st, R_out);
+  if (rc) return rc;
   HIPCHK(hipStreamSynchronize(st));
   return SKM_OK;
 }

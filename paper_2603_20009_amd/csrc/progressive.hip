@@ -14,6 +14,8 @@
 // and the four lanes that share a tile row add up at each checkpoint.
 #include "skm_internal.h"
 
+#include <cstdlib>
+
 namespace skm {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -51,7 +53,7 @@ __device__ inline void tile_of_block(int nrt, int nct, int &rt, int &ct) {
 // Slabs of BK dimensions start at koff = -((BK - d' % BK) % BK), so that slab ends fall on every
 // checkpoint d' + 64 m; dimensions below 0 or past ds are read as zero.
 template <int BK>
-__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) progressive_kernel(ProgArgs g) {
+__device__ __forceinline__ void progressive_body(const ProgArgs &g) {
   constexpr int LS = BK + 4;
   constexpr int F4_ROW = BK / 4;              // lanes per tile row
   constexpr int ROWS_PASS = NT / F4_ROW;      // tile rows staged per pass
@@ -64,6 +66,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ int s_prev[BM];
   __shared__ float s_ratio[kMaxBlocks + 1];
   __shared__ unsigned int s_cnt[2];
+  __shared__ unsigned int s_wcnt[5];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -74,6 +77,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   tile_of_block(nrt, nct, rt, ct);
   const int row0 = rt * BM, col0 = ct * BN;
 
+  unsigned long long *sc = g.scal + (size_t)(blockIdx.x & (kStatReplicas - 1)) * SC_COUNT;
   if (tid < BM) {
     const int gr = row0 + tid;
     const bool ok = gr < g.M;
@@ -235,14 +239,14 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if (tid == 0) {
         s_cnt[(m + 1) & 1] = 0u;   // next checkpoint's counter; nobody reads it before the next barrier
         if (total) {
-          if (m == 0) atomicAdd(g.survivors, (unsigned long long)total);
-          if (!last && g.enter) atomicAdd(g.enter + m, (unsigned long long)total);
-          if (last) atomicAdd(g.completed, (unsigned long long)total);
+          if (m == 0) atomicAdd(sc + SC_SURVIVORS, (unsigned long long)total);
+          if (!last && g.block_stats) atomicAdd(sc + SC_ENTER + m, (unsigned long long)total);
+          if (last) atomicAdd(sc + SC_COMPLETED, (unsigned long long)total);
         }
         if (total == 0u || last || total <= g.emit_max)   // the tile ends here
-          atomicAdd(g.dense_dims, (unsigned long long)(BK * (s + 1)));
+          atomicAdd(sc + SC_DENSE_DIMS, (unsigned long long)(BK * (s + 1)));
         else                                               // the next block of these pairs is done densely
-          atomicAdd(g.dense_pair_blocks, (unsigned long long)total);
+          atomicAdd(sc + SC_DENSE_PB, (unsigned long long)total);
       }
       if (total == 0u) return;
       if (last) {
@@ -288,44 +292,63 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         __builtin_amdgcn_sched_barrier(0);
       }
   } else if (fin_mode == 2) {
-    // sparse enough: hand the alive pairs to the gather kernel, which resumes at block fin_m
+    // sparse enough: hand the alive pairs to the gather kernel, which resumes at block fin_m.
+    // One reservation per tile in the sub-list of this workgroup's XCD.
     int wtot = __popcll(bits);
 #pragma unroll
     for (int sh = 1; sh < 64; sh <<= 1) wtot += __shfl_xor(wtot, sh, 64);
-    if (wtot > 0) {
-      unsigned int base = 0;
-      if (lane == 0) base = atomicAdd(g.pair_count, (unsigned int)wtot);
-      base = __shfl(base, 0, 64);
-      if ((unsigned long long)base + (unsigned long long)wtot > (unsigned long long)g.capacity) {
-        if (lane == 0) *g.overflow = 1u;
+    if (lane == 0) s_wcnt[wave] = (unsigned int)wtot;
+    __syncthreads();
+    if (tid == 0) {
+      const unsigned int tot = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
+      const unsigned int sub = blockIdx.x & (kSubLists - 1);
+      unsigned int base = atomicAdd(g.pair_count + sub * kSubListStride, tot);
+      if ((unsigned long long)base + tot > (unsigned long long)g.sub_capacity) {
+        *g.overflow = 1u;
+        base = 0xffffffffu;
       } else {
-        unsigned int run = base;
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const bool keep = (bits >> ((a * TN + b) * 16 + v)) & 1ull;
-              const unsigned long long mk = __ballot(keep);
-              if (keep) {
-                const int rl = row_of(a, v);
-                const unsigned int pos =
-                    run + __builtin_amdgcn_mbcnt_hi((unsigned int)(mk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mk, 0u));
-                Pair pr;
-                pr.i = (int32_t)(g.row_base + row0 + rl);
-                pr.j = (int32_t)((uint32_t)gc[b] | ((uint32_t)fin_m << 24));
-                const float p = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
-                pr.p = p > 0.f ? p : 0.f;
-                pr.tau = s_tau[rl];
-                g.pairs[pos] = pr;
-              }
-              run += (unsigned int)__popcll(mk);
-              __builtin_amdgcn_sched_barrier(0);
-            }
+        base += sub * g.sub_capacity;
       }
+      s_wcnt[4] = base;
+    }
+    __syncthreads();
+    unsigned int run = s_wcnt[4];
+    if (run != 0xffffffffu && wtot > 0) {
+      for (int w = 0; w < wave; ++w) run += s_wcnt[w];
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const bool keep = (bits >> ((a * TN + b) * 16 + v)) & 1ull;
+            const unsigned long long mk = __ballot(keep);
+            if (keep) {
+              const int rl = row_of(a, v);
+              const unsigned int pos =
+                  run + __builtin_amdgcn_mbcnt_hi((unsigned int)(mk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mk, 0u));
+              Pair pr;
+              pr.i = (int32_t)(g.row_base + row0 + rl);
+              pr.j = (int32_t)((uint32_t)gc[b] | ((uint32_t)fin_m << 24));
+              const float p = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
+              pr.p = p > 0.f ? p : 0.f;
+              pr.tau = s_tau[rl];
+              g.pairs[pos] = pr;
+            }
+            run += (unsigned int)__popcll(mk);
+            __builtin_amdgcn_sched_barrier(0);
+          }
     }
   }
+}
+
+// Two builds of the same body: slabs of 32 dimensions at two wavefronts per SIMD (73.7 KB of LDS), and
+// slabs of 16 at three (40 KB of LDS, 168 registers).
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) progressive_kernel_bk32(ProgArgs g) {
+  progressive_body<32>(g);
+}
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(3, 3))) progressive_kernel_bk16(ProgArgs g) {
+  progressive_body<16>(g);
 }
 
 hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
@@ -334,18 +357,26 @@ hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
       g.nb > kMaxBlocks || (reinterpret_cast<uintptr_t>(g.A) & 15u) || (reinterpret_cast<uintptr_t>(g.B) & 15u) ||
       g.N > (1 << 24))
     return hipErrorInvalidValue;
-  constexpr int BK = 32;
-  constexpr size_t smem = (size_t)2 * (BM + BN) * (BK + 4) * sizeof(float);
+  static const int bk = []() {
+    const char *e = std::getenv("SKM_TEST_PROG_BK");
+    const int v = e ? std::atoi(e) : 0;
+    return v == 16 ? 16 : 32;
+  }();
+  const size_t smem = (size_t)2 * (BM + BN) * (bk + 4) * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel<BK>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel_bk32),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)((size_t)2 * (BM + BN) * 36 * sizeof(float)));
     if (rc != hipSuccess) return rc;
     attr_set = true;
   }
   const int64_t nwg = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (nwg >= (1 << 24)) return hipErrorInvalidValue;   // 2^32 threads per launch at most; the caller chunks rows
-  hipLaunchKernelGGL(progressive_kernel<BK>, dim3((unsigned)nwg), dim3(NT), smem, st, g);
+  if (bk == 32)
+    hipLaunchKernelGGL(progressive_kernel_bk32, dim3((unsigned)nwg), dim3(NT), smem, st, g);
+  else
+    hipLaunchKernelGGL(progressive_kernel_bk16, dim3((unsigned)nwg), dim3(NT), smem, st, g);
   return hipGetLastError();
 }
 

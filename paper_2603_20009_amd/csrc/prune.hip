@@ -37,7 +37,12 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
   if (tid == 0) s_completed = 0u;
   __syncthreads();
 
-  const unsigned int total = *a.count;
+  // the list is kSubLists parts; a flat index p walks them in order
+  unsigned int cum[kSubLists + 1];
+  cum[0] = 0u;
+#pragma unroll
+  for (int sl = 0; sl < kSubLists; ++sl) cum[sl + 1] = cum[sl] + a.count[sl * kSubListStride];
+  const unsigned int total = cum[kSubLists];
   const unsigned int ngroups = gridDim.x * (PRUNE_THREADS / 16);
   const int q = tid & 15;
   unsigned int p = blockIdx.x * (PRUNE_THREADS / 16) + (tid >> 4);
@@ -45,7 +50,10 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
   int i = 0, j = 0, m = 0;
   float acc = 0.f, tau = 0.f;
   auto fetch = [&]() {
-    const Pair pr = a.pairs[p];
+    unsigned int sl = 0;
+#pragma unroll
+    for (int t = 1; t < kSubLists; ++t) sl += (p >= cum[t]);
+    const Pair pr = a.pairs[(size_t)sl * a.sub_capacity + (p - cum[sl])];
     const unsigned int jm = (unsigned int)pr.j;
     i = pr.i;
     j = (int)(jm & 0xffffffu);
@@ -88,10 +96,11 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
     }
   }
   __syncthreads();
-  if (tid == 0 && s_completed) atomicAdd(a.completed, (unsigned long long)s_completed);
-  if (STATS && a.enter) {
+  unsigned long long *sc = a.scal + (size_t)(blockIdx.x & (kStatReplicas - 1)) * SC_COUNT;
+  if (tid == 0 && s_completed) atomicAdd(sc + SC_COMPLETED, (unsigned long long)s_completed);
+  if (STATS) {
     for (int mm = tid; mm < a.nb; mm += PRUNE_THREADS)
-      if (s_enter[mm]) atomicAdd(a.enter + mm, (unsigned long long)s_enter[mm]);
+      if (s_enter[mm]) atomicAdd(sc + SC_ENTER + mm, (unsigned long long)s_enter[mm]);
   }
 }
 
@@ -101,7 +110,7 @@ hipError_t launch_prune(const PruneArgs &a, hipStream_t st) {
   (void)hipGetDevice(&dev);
   (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
   const unsigned grid = (unsigned)cus * 8u;  // 8 workgroups of 4 waves per CU = full occupancy at <= 64 VGPRs
-  if (a.enter)
+  if (a.block_stats)
     hipLaunchKernelGGL(prune_kernel<true>, dim3(grid), dim3(PRUNE_THREADS), 0, st, a);
   else
     hipLaunchKernelGGL(prune_kernel<false>, dim3(grid), dim3(PRUNE_THREADS), 0, st, a);

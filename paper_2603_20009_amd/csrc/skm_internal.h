@@ -55,6 +55,16 @@ hipError_t gemm_store(const GemmOperands &g, float *C, int64_t ldc, int32_t Nsto
 // distance up to the per-row constant ||x_i||^2 (Algorithm 1, iteration 1).
 hipError_t gemm_argmin(const GemmOperands &g, const float *ynorm, unsigned long long *best, hipStream_t st);
 
+// Device scalars of one assignment step.  Every workgroup adds to the replica (blockIdx & (kStatReplicas-1))
+// so that same-address atomics do not serialise; the host sums the replicas.
+enum { SC_COMPLETED = 0, SC_CHANGED = 1, SC_SURVIVORS = 2, SC_DENSE_DIMS = 3, SC_DENSE_PB = 4, SC_ENTER = 5,
+       SC_COUNT = 5 + kMaxBlocks };
+constexpr int kStatReplicas = 32;
+// The hand-over list is split in kSubLists equal parts, one per XCD (workgroup id mod 8), each with its own
+// fill counter (counters are kSubListStride words apart).
+constexpr int kSubLists = 8;
+constexpr int kSubListStride = 16;
+
 // Progressive-pruning GEMM (Algorithm 1, iterations >= 2): a 128 x 128 tile is multiplied densely over
 // d', d'+64, d'+128, ... dimensions; after each step the pairs whose partial distance exceeds
 // theta(t, tau_i) die; the tile stops when nothing is alive, hands its pairs to the gather kernel when
@@ -72,17 +82,14 @@ struct ProgArgs {
   const float *tau;        // [n]
   const int32_t *prev;     // [n] incumbent (never a challenger)
   int64_t row_base;
-  Pair *pairs;
-  unsigned int *pair_count;
-  unsigned int capacity;
+  Pair *pairs;             // kSubLists parts of sub_capacity slots each
+  unsigned int *pair_count;   // [kSubLists * kSubListStride] fill counters of the parts
+  unsigned int sub_capacity;
   unsigned int *overflow;
   unsigned int emit_max;   // a tile with at most this many alive pairs is handed over
   unsigned long long *best;       // [n] packed (distance, centroid)
-  unsigned long long *survivors;  // += pairs alive after the first test
-  unsigned long long *completed;  // += pairs finished over all d dims
-  unsigned long long *enter;      // [nb] += pairs entering trailing block m, or NULL
-  unsigned long long *dense_dims; // += dimensions multiplied, summed over tiles
-  unsigned long long *dense_pair_blocks;  // += (alive pairs) per trailing block that was multiplied densely
+  unsigned long long *scal;       // [kStatReplicas][SC_COUNT] step scalars (SC_SURVIVORS, SC_COMPLETED, SC_DENSE_*, SC_ENTER..)
+  int32_t block_stats;            // also count pairs entering every trailing block (SC_ENTER + m)
 };
 hipError_t launch_progressive(const ProgArgs &g, hipStream_t st);
 int64_t progressive_tiles(int64_t rows, int32_t k);
@@ -90,8 +97,9 @@ int32_t progressive_tile_pairs();
 
 // ---------------------------------------------------------------- pruning
 struct PruneArgs {
-  const Pair *pairs;
-  const unsigned int *count;
+  const Pair *pairs;           // kSubLists parts of sub_capacity slots each
+  const unsigned int *count;   // [kSubLists * kSubListStride] fill counters
+  unsigned int sub_capacity;
   const float *Xr;       // rotated points, row stride ldx, zero padded to ds columns
   int64_t ldx;
   const float *Ypdx;     // [nb][k][64] trailing centroid dimensions, block-major (PDX-style)
@@ -101,8 +109,8 @@ struct PruneArgs {
   int32_t nb;            // trailing blocks
   const float *ratio;    // [nb + 1] theta ratio at checkpoint m, t_m = min(d, d' + 64 m) (device array)
   unsigned long long *best;        // [n] packed (distance, centroid)
-  unsigned long long *completed;   // += pairs completed over all d dims
-  unsigned long long *enter;       // [nb] += pairs entering block m after surviving block m - 1 here, or NULL
+  unsigned long long *scal;        // [kStatReplicas][SC_COUNT]: SC_COMPLETED, and SC_ENTER + m when block_stats
+  int32_t block_stats;
 };
 hipError_t launch_prune(const PruneArgs &a, hipStream_t st);
 
@@ -149,6 +157,12 @@ hipError_t launch_gather_rows(const float *src, int64_t lds, int32_t d, const in
                               int64_t ldd, int32_t dpad, hipStream_t st);
 hipError_t launch_pad_copy(const float *src, int64_t lds, int64_t n, int32_t d, float *dst, int64_t ldd, int32_t dpad,
                            int32_t transpose, hipStream_t st);
+
+// ---------------------------------------------------------------- rotation matrix
+// Haar-distributed orthogonal d x d matrix (fp32) from (d, seed); workspaces in doubles:
+// Qwork d*d + 2, Cwork max(4*32*d, ceil(d/128)*1024), Wwork 8*32*d, Lwork 32*32.
+hipError_t launch_make_rotation(int32_t d, uint64_t seed, double *Qwork, double *Cwork, double *Wwork, double *Lwork,
+                                float *R_out, hipStream_t st);
 
 // ---------------------------------------------------------------- ETR helpers
 // Key lists hold (order-preserving distance bits << 32 | index), ascending; ~0 marks an empty slot.
