@@ -360,3 +360,62 @@ print("banded ok")
     env = dict(os.environ, SKM_TEST_MAX_TILES="7")   # 3 column tiles -> bands of 2 row tiles
     r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=240)
     assert r.returncode == 0 and "banded ok" in r.stdout, r.stderr[-2000:]
+
+
+# ------------------------------------------------------------------ edge and degenerate cases
+def test_single_cluster_and_one_point_per_cluster(skm, orc, dg):
+    X = dg.mixture(700, 48, 5, 3, "linear").numpy()
+    R = orc.random_rotation(48, 1)
+    # k = 1: no challenger exists, nothing survives, the centroid is the global mean
+    got = skm.fit(cuda(X), 1, 3, 5, skm.FitOptions(R=cuda(R)))
+    assert (got.assign.cpu().numpy() == 0).all()
+    assert np.abs(got.centroids.cpu().numpy()[0] - X.astype(np.float64).mean(0)).max() < 1e-6
+    assert all(t["survivors"] == 0 and t["prune_frac"] == 0.0 for t in got.trace)
+    # k = n: every point is its own centroid after iteration 1, all distances 0, nothing moves afterwards
+    Xs = X[:130]
+    got = skm.fit(cuda(Xs), 130, 3, 5, skm.FitOptions(R=cuda(R)))
+    a = got.assign.cpu().numpy()
+    assert sorted(a.tolist()) == list(range(130))
+    assert rel_l2(got.centroids.cpu().numpy()[a], Xs) < 1e-6
+    assert got.trace[-1]["objective"] < 1e-9 and got.trace[-1]["changed"] == 0
+
+
+def test_smallest_shapes(skm, orc):
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((5, 16)).astype(np.float32)      # d = 16 is the smallest d, d' = d
+    ref = orc.fit(X, 2, 3, 1, orc.FitParams(eps0=EPS0), R=None)
+    got = skm.fit(cuda(X), 2, 3, 1, skm.FitOptions(rotate=False))
+    assert (got.assign.cpu().numpy() == ref.assign).all()
+    assert rel_l2(got.centroids.cpu().numpy(), ref.centroids) < 1e-5
+    one = skm.fit(cuda(X[:1]), 1, 1, 1, skm.FitOptions(rotate=False))   # a single point
+    assert one.assign.cpu().numpy().tolist() == [0] and np.allclose(one.centroids.cpu().numpy()[0], X[0])
+
+
+def test_duplicate_points_tie_to_the_lowest_index(skm):
+    X = np.zeros((300, 32), dtype=np.float32)
+    X[:, 0] = 1.0
+    X[150:, 1] = 1.0                                        # two distinct rows, 150 copies each
+    Y = np.stack([X[0], X[0], X[200], X[200]])              # each row twice among the centroids
+    a, dist = skm.assign_exact(cuda(X), cuda(Y))
+    a = a.cpu().numpy()
+    assert (a[:150] == 0).all() and (a[150:] == 2).all() and float(dist.abs().max()) < 1e-6
+    # the pruned step keeps the incumbent on exact ties
+    prev = np.where(np.arange(300) < 150, 1, 3).astype(np.int32)
+    a2, _, _ = skm.assign(cuda(X), cuda(Y), cuda(prev), 16, skm.FitOptions(rotate=False))
+    assert (a2.cpu().numpy() == prev).all()
+
+
+def test_largest_dimension_and_many_blocks(skm, orc, dg):
+    """d = 4096: 60 trailing blocks, more than the per-block counters of the trace hold."""
+    X = dg.mixture(600, 4096, 10, 5, "embed").numpy()
+    R = orc.random_rotation(4096, 2)
+    Y = X[:40] + 0.01
+    Xr, Yr = orc.rotate(X, R), orc.rotate(Y, R)
+    prev = orc.assign_full(Xr, Yr)[0].astype(np.int32)
+    prev[::3] = 7
+    ref = orc.assign_pruned(Xr, Yr, prev, 512, EPS0, 0)
+    for dense in (0.02, 1.0):
+        a, dist, row = skm.assign(cuda(X), cuda(Y), cuda(prev), 512, skm.FitOptions(R=cuda(R), block_stats=True,
+                                                                                     dense_frac=dense))
+        check_assignment(a.cpu().numpy(), ref.assign, Xr, Yr)
+        assert row["nblocks"] == 56 and row["enter"][0] == ref.enter[0]
