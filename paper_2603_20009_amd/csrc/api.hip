@@ -233,7 +233,7 @@ struct Ctx {
     pair_cap = sub_cap * kSubLists;
     if (pair_cap >= ((int64_t)1 << 32)) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
     HIPCHK(pool.get(&pairs, (size_t)pair_cap));
-    ncounters = (size_t)nchunks * kSubLists * kSubListStride;
+    ncounters = (size_t)nchunks * (kSubLists + 8) * kSubListStride;   // list fill counters, then tile counters
     HIPCHK(pool.get(&counters, ncounters + 1));
     HIPCHK(pool.get(&ratio_dev, (size_t)kMaxBlocks + 1));
     HIPCHK(pool.get(&scal, (size_t)SC_COUNT * kStatReplicas));
@@ -324,6 +324,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     g.ds = c.ds; g.d = c.d; g.dprime = dprime; g.nb = nb;
     g.ratio = c.ratio_dev; g.tau = c.tau; g.prev = c.prev; g.row_base = r0;
     unsigned int *fill = c.counters + (size_t)ch * kSubLists * kSubListStride;
+    g.tile_counter = c.counters + ((size_t)c.nchunks * kSubLists + (size_t)ch * 8) * kSubListStride;
     g.pairs = c.pairs; g.pair_count = fill; g.sub_capacity = (unsigned int)c.sub_cap;
     g.overflow = c.counters + c.ncounters; g.emit_max = c.emit_max;
     g.best = c.best; g.scal = c.scal; g.block_stats = c.block_stats ? 1 : 0;

@@ -11,9 +11,14 @@
 //
 // Partial distances come from the norm expansion ||x_t||^2 + ||y_t||^2 - 2 x_t.y_t (Section 3.1).
 // The prefix norms are a by-product of staging: every thread squares the float4 it moves into LDS,
-// and the four lanes that share a tile row add up at each checkpoint.
+// and the lanes that share a tile row add up at each checkpoint.
+//
+// The kernel is persistent: two workgroups per CU take tiles from a per-XCD counter.  When a tile
+// ends, the first slab and the per-row data of the next tile are already being fetched while the
+// finished tile is written out, so the short tiles of a well-pruned step do not drain the pipeline.
 #include "skm_internal.h"
 
+#include <algorithm>
 #include <cstdlib>
 
 namespace skm {
@@ -21,81 +26,77 @@ namespace skm {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 namespace {
-constexpr int BM = 128, BN = 128;
+constexpr int BM = 128, BN = 128, BK = 32;
 constexpr int WTM = 64, WTN = 64, TM = 2, TN = 2;
 constexpr int NT = 256;
+constexpr int LS = BK + 4;
+constexpr int F4_ROW = BK / 4;              // 8 lanes stage one tile row
+constexpr int ROWS_PASS = NT / F4_ROW;      // 32 tile rows per staging pass
+constexpr int A_F4 = BM / ROWS_PASS;        // 4
+constexpr int B_F4 = BN / ROWS_PASS;        // 4
+constexpr int PC = 16;                      // column tiles per panel of the tile walk
 
-// sum over the F4_ROW (4 or 8) consecutive lanes that stage one tile row; all of them get the total
-template <int LANES>
+// sum over the 8 consecutive lanes that stage one tile row; all of them get the total
 __device__ inline float rowgroup_sum(float v) {
   v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
   v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-  if (LANES == 8)
-    v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
   return v;
-}
-
-__device__ inline void tile_of_block(int nrt, int nct, int &rt, int &ct) {
-  const int nwg = gridDim.x, bid = blockIdx.x;
-  const int xcd = bid & 7, q = bid >> 3;
-  const int base = nwg >> 3, rem = nwg & 7;
-  const int logical = xcd * base + (xcd < rem ? xcd : rem) + q;
-  constexpr int PC = 16;
-  const int panel_sz = PC * nrt;
-  const int p = logical / panel_sz;
-  const int r = logical - p * panel_sz;
-  const int pc = (nct - p * PC) < PC ? (nct - p * PC) : PC;
-  rt = r / pc;
-  ct = p * PC + (r - rt * pc);
 }
 }  // namespace
 
 // Slabs of BK dimensions start at koff = -((BK - d' % BK) % BK), so that slab ends fall on every
 // checkpoint d' + 64 m; dimensions below 0 or past ds are read as zero.
-template <int BK>
-__device__ __forceinline__ void progressive_body(const ProgArgs &g) {
-  constexpr int LS = BK + 4;
-  constexpr int F4_ROW = BK / 4;              // lanes per tile row
-  constexpr int ROWS_PASS = NT / F4_ROW;      // tile rows staged per pass
-  constexpr int A_F4 = BM / ROWS_PASS;
-  constexpr int B_F4 = BN / ROWS_PASS;
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) progressive_kernel(ProgArgs g) {
   extern __shared__ __align__(16) float smem[];
   float *As = smem;                  // [2][BM][LS]
   float *Bs = smem + 2 * BM * LS;    // [2][BN][LS]
   __shared__ float s_tau[BM], s_thr[BM], s_xn[BM], s_yn[BN];
   __shared__ int s_prev[BM];
   __shared__ float s_ratio[kMaxBlocks + 1];
+  __shared__ unsigned long long s_dead[NT];   // per thread: accumulator elements that start dead (the incumbent)
   __shared__ unsigned int s_cnt[2];
   __shared__ unsigned int s_wcnt[5];
+  __shared__ int s_next;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int r32 = lane & 31, kh = lane >> 5;
   const int nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
-  int rt, ct;
-  tile_of_block(nrt, nct, rt, ct);
-  const int row0 = rt * BM, col0 = ct * BN;
+  const int ntiles = nrt * nct;
+
+  // This workgroup's share: the contiguous range of logical tile ids of its XCD (workgroups are dealt
+  // round-robin to the 8 XCDs), walked through a per-XCD counter.
+  const int xcd = blockIdx.x & 7;
+  const int tbase = ntiles >> 3, trem = ntiles & 7;
+  const int xstart = xcd * tbase + (xcd < trem ? xcd : trem);
+  const int xcount = tbase + (xcd < trem ? 1 : 0);
+  unsigned int *ctr = g.tile_counter + xcd * kSubListStride;
+  auto tile_rc = [&](int q, int &rt, int &ct) {   // q-th tile of this XCD -> (row tile, column tile)
+    const int logical = xstart + q;
+    const int panel_sz = PC * nrt;
+    const int p = logical / panel_sz;
+    const int r = logical - p * panel_sz;
+    const int pc = (nct - p * PC) < PC ? (nct - p * PC) : PC;
+    rt = r / pc;
+    ct = p * PC + (r - rt * pc);
+  };
 
   unsigned long long *sc = g.scal + (size_t)(blockIdx.x & (kStatReplicas - 1)) * SC_COUNT;
-  if (tid < BM) {
-    const int gr = row0 + tid;
-    const bool ok = gr < g.M;
-    s_tau[tid] = ok ? g.tau[g.row_base + gr] : 0.f;
-    s_prev[tid] = ok ? g.prev[g.row_base + gr] : -1;
-  }
   for (int m = tid; m <= g.nb; m += NT) s_ratio[m] = g.ratio[m];
   if (tid < 2) s_cnt[tid] = 0u;
+  s_dead[tid] = 0ull;
+
+  const int st_row = tid / F4_ROW, st_kq = tid % F4_ROW;  // staging: rows st_row + 32 * s
+  const int koff = -((BK - g.dprime % BK) % BK);
+  const int nslab = (g.ds - koff + BK - 1) / BK;
 
   float4 ra[A_F4], rb[B_F4];
   float na[A_F4], nbv[B_F4];
-#pragma unroll
-  for (int s = 0; s < A_F4; ++s) na[s] = 0.f;
-#pragma unroll
-  for (int s = 0; s < B_F4; ++s) nbv[s] = 0.f;
-  const int st_row = tid / F4_ROW, st_kq = tid % F4_ROW;  // staging: rows st_row + ROWS_PASS * s
-  const int koff = -((BK - g.dprime % BK) % BK);
-  auto gload = [&](int k0) {
+  float tau_reg = 0.f;
+  int prev_reg = -1;
+  auto gload = [&](int row0, int col0, int k0) {
     const int kk = k0 + 4 * st_kq;
     const bool kok = kk >= 0 && kk < g.ds;
 #pragma unroll
@@ -109,6 +110,14 @@ __device__ __forceinline__ void progressive_body(const ProgArgs &g) {
       const int gc = col0 + st_row + ROWS_PASS * s;
       rb[s] = (kok && gc < g.N) ? *reinterpret_cast<const float4 *>(g.B + (int64_t)gc * g.ldb + kk)
                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto load_rows = [&](int row0) {   // per-row data of a tile, one row per thread of the first two wavefronts
+    if (tid < BM) {
+      const int gr = row0 + tid;
+      const bool ok = gr < g.M;
+      tau_reg = ok ? g.tau[g.row_base + gr] : 0.f;
+      prev_reg = ok ? g.prev[g.row_base + gr] : -1;
     }
   };
   auto sstore = [&](int buf) {
@@ -127,7 +136,7 @@ __device__ __forceinline__ void progressive_body(const ProgArgs &g) {
   auto publish_norms = [&](float ratio) {
 #pragma unroll
     for (int s = 0; s < A_F4; ++s) {
-      const float v = rowgroup_sum<F4_ROW>(na[s]);
+      const float v = rowgroup_sum(na[s]);
       if (st_kq == 0) {
         const int rl = st_row + ROWS_PASS * s;
         s_xn[rl] = v;
@@ -136,219 +145,262 @@ __device__ __forceinline__ void progressive_body(const ProgArgs &g) {
     }
 #pragma unroll
     for (int s = 0; s < B_F4; ++s) {
-      const float v = rowgroup_sum<F4_ROW>(nbv[s]);
+      const float v = rowgroup_sum(nbv[s]);
       if (st_kq == 0) s_yn[st_row + ROWS_PASS * s] = v;
     }
   };
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int a = 0; a < TM; ++a)
-#pragma unroll
-    for (int b = 0; b < TN; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
   auto row_of = [&](int a, int v) { return wm * WTM + a * 32 + 8 * (v >> 2) + 4 * kh + (v & 3); };
-  int gc[TN];
-#pragma unroll
-  for (int b = 0; b < TN; ++b) gc[b] = col0 + wn * WTN + b * 32 + r32;
 
-  const int nslab = (g.ds - koff + BK - 1) / BK;
-  gload(koff);
-  sstore(0);
+  // first tile of this workgroup
   __syncthreads();
+  if (tid == 0) s_next = (int)atomicAdd(ctr, 1u);
+  __syncthreads();
+  int q = s_next;
+  if (q >= xcount) return;
+  int rt, ct;
+  tile_rc(q, rt, ct);
+  gload(rt * BM, ct * BN, koff);
+  load_rows(rt * BM);
 
-  // one alive-bit per accumulator element; the incumbent and the padding of ragged tiles start dead
-  unsigned long long bits = 0ull;
+  while (true) {
+    const int row0 = rt * BM, col0 = ct * BN;
+    // ---- commit the prefetched first slab and per-row data of this tile
 #pragma unroll
-  for (int a = 0; a < TM; ++a)
+    for (int s = 0; s < A_F4; ++s) na[s] = 0.f;
 #pragma unroll
-    for (int b = 0; b < TN; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int rl = row_of(a, v);
-        const bool ok = (row0 + rl < g.M) && (gc[b] < g.N) && (gc[b] != s_prev[rl]);
-        bits |= (unsigned long long)ok << ((a * TN + b) * 16 + v);
+    for (int s = 0; s < B_F4; ++s) nbv[s] = 0.f;
+    sstore(0);
+    if (tid < BM) {
+      s_tau[tid] = tau_reg;
+      s_prev[tid] = prev_reg;
+      // the incumbent of this row, if it is a column of this tile, starts dead: find the thread and the
+      // accumulator element that hold (row tid, column prev - col0)
+      const int cl = prev_reg - col0;
+      if (cl >= 0 && cl < BN) {
+        const int rr = tid & 31;
+        const int lane_t = ((rr >> 2) & 1) * 32 + (cl & 31);
+        const int wave_t = (tid >> 6) * 2 + (cl >> 6);
+        const int v_t = 4 * (rr >> 3) + (rr & 3);
+        const int bit = ((((tid & 63) >> 5) * TN) + ((cl & 63) >> 5)) * 16 + v_t;
+        atomicOr(&s_dead[wave_t * 64 + lane_t], 1ull << bit);
       }
-
-  int fin_mode = 0, fin_m = 0;   // how the tile ended: 1 = reached t = d, 2 = handed over at checkpoint fin_m
-  float yn[TN] = {0.f, 0.f};
-  for (int s = 0; s < nslab; ++s) {
-    const int buf = s & 1;
-    if (s + 1 < nslab) gload(koff + (s + 1) * BK);
-    const float *Ab = As + (buf * BM + wm * WTM + r32) * LS + kh * 4;
-    const float *Bb = Bs + (buf * BN + wn * WTN + r32) * LS + kh * 4;
-#pragma unroll
-    for (int kg = 0; kg < BK / 8; ++kg) {
-      float4 af[TM], bf[TN];
-#pragma unroll
-      for (int a = 0; a < TM; ++a) af[a] = *reinterpret_cast<const float4 *>(Ab + a * 32 * LS + kg * 8);
-#pragma unroll
-      for (int b = 0; b < TN; ++b) bf[b] = *reinterpret_cast<const float4 *>(Bb + b * 32 * LS + kg * 8);
-#pragma unroll
-      for (int a = 0; a < TM; ++a)
-#pragma unroll
-        for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].x, bf[b].x, acc[a][b], 0, 0, 0);
-#pragma unroll
-      for (int a = 0; a < TM; ++a)
-#pragma unroll
-        for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].y, bf[b].y, acc[a][b], 0, 0, 0);
-#pragma unroll
-      for (int a = 0; a < TM; ++a)
-#pragma unroll
-        for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].z, bf[b].z, acc[a][b], 0, 0, 0);
-#pragma unroll
-      for (int a = 0; a < TM; ++a)
-#pragma unroll
-        for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].w, bf[b].w, acc[a][b], 0, 0, 0);
     }
-
-    const int tdone = koff + BK * (s + 1);   // dimensions multiplied so far
-    const bool last = (s + 1 == nslab);
-    const bool check = !last && tdone >= g.dprime && tdone < g.d && ((tdone - g.dprime) & (kBlockDims - 1)) == 0;
-    const bool cp = check || last;
-    const int m = last ? g.nb : (tdone - g.dprime) / kBlockDims;   // checkpoint index, t_m = min(d, d' + 64 m)
-    if (cp) publish_norms(s_ratio[m]);      // norms over the slabs multiplied so far (the next slab is added below)
-    if (s + 1 < nslab) sstore(buf ^ 1);
+    unsigned int next_q = 0;
+    if (tid == 0) next_q = atomicAdd(ctr, 1u);   // the tile after this one; consumed below
     __syncthreads();
-    if (cp) {
-#pragma unroll
-      for (int b = 0; b < TN; ++b) yn[b] = s_yn[wn * WTN + b * 32 + r32];
-      if (!last || g.nb == 0) {
-        // test theta(t_m, tau_i): drop the pair when its partial distance exceeds it
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float th = s_thr[row_of(a, v)];
-#pragma unroll
-            for (int b = 0; b < TN; ++b) {
-              const bool keep = (yn[b] - 2.f * acc[a][b][v]) <= th;
-              bits &= ~((unsigned long long)(!keep) << ((a * TN + b) * 16 + v));
-            }
-          }
-      }
-      // alive pairs of the whole tile
-      int cnt = __popcll(bits);
-#pragma unroll
-      for (int sh = 1; sh < 64; sh <<= 1) cnt += __shfl_xor(cnt, sh, 64);
-      if (lane == 0 && cnt) atomicAdd(&s_cnt[m & 1], (unsigned int)cnt);
-      __syncthreads();
-      const unsigned int total = s_cnt[m & 1];
-      if (tid == 0) {
-        s_cnt[(m + 1) & 1] = 0u;   // next checkpoint's counter; nobody reads it before the next barrier
-        if (total) {
-          if (m == 0) atomicAdd(sc + SC_SURVIVORS, (unsigned long long)total);
-          if (!last && g.block_stats) atomicAdd(sc + SC_ENTER + m, (unsigned long long)total);
-          if (last) atomicAdd(sc + SC_COMPLETED, (unsigned long long)total);
-        }
-        if (total == 0u || last || total <= g.emit_max)   // the tile ends here
-          atomicAdd(sc + SC_DENSE_DIMS, (unsigned long long)(BK * (s + 1)));
-        else                                               // the next block of these pairs is done densely
-          atomicAdd(sc + SC_DENSE_PB, (unsigned long long)total);
-      }
-      if (total == 0u) return;
-      if (last) {
-        fin_mode = 1;
-        fin_m = m;
-        break;
-      }
-      if (total <= g.emit_max) {
-        fin_mode = 2;
-        fin_m = m;
-        break;
-      }
-    }
-  }
 
-  if (fin_mode == 1) {
-    // finished distances: offer those below tau_i to the point's packed minimum
+    f32x16 acc[TM][TN];
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int rl = row_of(a, v);
-        unsigned long long key = ~0ull;
+      for (int b = 0; b < TN; ++b)
 #pragma unroll
-        for (int b = 0; b < TN; ++b) {
-          if ((bits >> ((a * TN + b) * 16 + v)) & 1ull) {
-            float dist = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
-            dist = dist > 0.f ? dist : 0.f;
-            if (dist < s_tau[rl]) {
-              const unsigned long long kb = pack_key(dist, gc[b]);
-              key = kb < key ? kb : key;
-            }
-          }
-        }
-        if (__ballot(key != ~0ull)) {
+        for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    int gc[TN];
 #pragma unroll
-          for (int sh = 1; sh < 32; sh <<= 1) {
-            const unsigned long long o = __shfl_xor(key, sh, 64);
-            key = o < key ? o : key;
-          }
-          if (r32 == 0 && key != ~0ull) atomicMin(g.best + g.row_base + row0 + rl, key);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-  } else if (fin_mode == 2) {
-    // sparse enough: hand the alive pairs to the gather kernel, which resumes at block fin_m.
-    // One reservation per tile in the sub-list of this workgroup's XCD.
-    int wtot = __popcll(bits);
-#pragma unroll
-    for (int sh = 1; sh < 64; sh <<= 1) wtot += __shfl_xor(wtot, sh, 64);
-    if (lane == 0) s_wcnt[wave] = (unsigned int)wtot;
-    __syncthreads();
-    if (tid == 0) {
-      const unsigned int tot = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
-      const unsigned int sub = blockIdx.x & (kSubLists - 1);
-      unsigned int base = atomicAdd(g.pair_count + sub * kSubListStride, tot);
-      if ((unsigned long long)base + tot > (unsigned long long)g.sub_capacity) {
-        *g.overflow = 1u;
-        base = 0xffffffffu;
-      } else {
-        base += sub * g.sub_capacity;
-      }
-      s_wcnt[4] = base;
-    }
-    __syncthreads();
-    unsigned int run = s_wcnt[4];
-    if (run != 0xffffffffu && wtot > 0) {
-      for (int w = 0; w < wave; ++w) run += s_wcnt[w];
+    for (int b = 0; b < TN; ++b) gc[b] = col0 + wn * WTN + b * 32 + r32;
+
+    // one alive-bit per accumulator element
+    unsigned long long bits = ~s_dead[tid];
+    s_dead[tid] = 0ull;
+    if (row0 + BM > g.M || col0 + BN > g.N) {   // ragged edge tile: rows / columns past the end start dead
 #pragma unroll
       for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            const bool keep = (bits >> ((a * TN + b) * 16 + v)) & 1ull;
-            const unsigned long long mk = __ballot(keep);
-            if (keep) {
-              const int rl = row_of(a, v);
-              const unsigned int pos =
-                  run + __builtin_amdgcn_mbcnt_hi((unsigned int)(mk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mk, 0u));
-              Pair pr;
-              pr.i = (int32_t)(g.row_base + row0 + rl);
-              pr.j = (int32_t)((uint32_t)gc[b] | ((uint32_t)fin_m << 24));
-              const float p = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
-              pr.p = p > 0.f ? p : 0.f;
-              pr.tau = s_tau[rl];
-              g.pairs[pos] = pr;
-            }
-            run += (unsigned int)__popcll(mk);
-            __builtin_amdgcn_sched_barrier(0);
+            const bool ok = (row0 + row_of(a, v) < g.M) && (gc[b] < g.N);
+            bits &= ~((unsigned long long)(!ok) << ((a * TN + b) * 16 + v));
           }
     }
-  }
-}
 
-// Two builds of the same body: slabs of 32 dimensions at two wavefronts per SIMD (73.7 KB of LDS), and
-// slabs of 16 at three (40 KB of LDS, 168 registers).
-__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) progressive_kernel_bk32(ProgArgs g) {
-  progressive_body<32>(g);
-}
-__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(3, 3))) progressive_kernel_bk16(ProgArgs g) {
-  progressive_body<16>(g);
+    int fin_mode = 0, fin_m = 0;   // how the tile ends: 0 = nothing alive, 1 = reached t = d, 2 = handed over at fin_m
+    float yn[TN] = {0.f, 0.f};
+    for (int s = 0; s < nslab; ++s) {
+      const int buf = s & 1;
+      if (s + 1 < nslab) gload(row0, col0, koff + (s + 1) * BK);
+      const float *Ab = As + (buf * BM + wm * WTM + r32) * LS + kh * 4;
+      const float *Bb = Bs + (buf * BN + wn * WTN + r32) * LS + kh * 4;
+#pragma unroll
+      for (int kg = 0; kg < BK / 8; ++kg) {
+        float4 af[TM], bf[TN];
+#pragma unroll
+        for (int a = 0; a < TM; ++a) af[a] = *reinterpret_cast<const float4 *>(Ab + a * 32 * LS + kg * 8);
+#pragma unroll
+        for (int b = 0; b < TN; ++b) bf[b] = *reinterpret_cast<const float4 *>(Bb + b * 32 * LS + kg * 8);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].x, bf[b].x, acc[a][b], 0, 0, 0);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].y, bf[b].y, acc[a][b], 0, 0, 0);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].z, bf[b].z, acc[a][b], 0, 0, 0);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].w, bf[b].w, acc[a][b], 0, 0, 0);
+      }
+
+      const int tdone = koff + BK * (s + 1);   // dimensions multiplied so far
+      const bool last = (s + 1 == nslab);
+      const bool check = !last && tdone >= g.dprime && tdone < g.d && ((tdone - g.dprime) & (kBlockDims - 1)) == 0;
+      const bool cp = check || last;
+      const int m = last ? g.nb : (tdone - g.dprime) / kBlockDims;   // checkpoint index, t_m = min(d, d' + 64 m)
+      if (cp) publish_norms(s_ratio[m]);      // norms over the slabs multiplied so far (the next slab is added below)
+      if (s + 1 < nslab) sstore(buf ^ 1);
+      if (s == 0 && tid == 0) s_next = (int)next_q;
+      __syncthreads();
+      if (cp) {
+#pragma unroll
+        for (int b = 0; b < TN; ++b) yn[b] = s_yn[wn * WTN + b * 32 + r32];
+        if (!last || g.nb == 0) {
+          // test theta(t_m, tau_i): drop the pair when its partial distance exceeds it
+#pragma unroll
+          for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const float th = s_thr[row_of(a, v)];
+#pragma unroll
+              for (int b = 0; b < TN; ++b) {
+                const bool keep = (yn[b] - 2.f * acc[a][b][v]) <= th;
+                bits &= ~((unsigned long long)(!keep) << ((a * TN + b) * 16 + v));
+              }
+            }
+        }
+        // alive pairs of the whole tile
+        int cnt = __popcll(bits);
+#pragma unroll
+        for (int sh = 1; sh < 64; sh <<= 1) cnt += __shfl_xor(cnt, sh, 64);
+        if (lane == 0 && cnt) atomicAdd(&s_cnt[m & 1], (unsigned int)cnt);
+        __syncthreads();
+        const unsigned int total = s_cnt[m & 1];
+        if (tid == 0) {
+          s_cnt[(m + 1) & 1] = 0u;   // next checkpoint's counter; nobody reads it before the next barrier
+          if (total) {
+            if (m == 0) atomicAdd(sc + SC_SURVIVORS, (unsigned long long)total);
+            if (!last && g.block_stats) atomicAdd(sc + SC_ENTER + m, (unsigned long long)total);
+            if (last) atomicAdd(sc + SC_COMPLETED, (unsigned long long)total);
+          }
+          if (total == 0u || last || total <= g.emit_max)   // the tile ends here
+            atomicAdd(sc + SC_DENSE_DIMS, (unsigned long long)(BK * (s + 1)));
+          else                                               // the next block of these pairs is done densely
+            atomicAdd(sc + SC_DENSE_PB, (unsigned long long)total);
+        }
+        if (total == 0u) break;
+        if (last) {
+          fin_mode = 1;
+          fin_m = m;
+          break;
+        }
+        if (total <= g.emit_max) {
+          fin_mode = 2;
+          fin_m = m;
+          break;
+        }
+      }
+    }
+
+    // ---- start fetching the next tile before this one is written out
+    q = s_next;
+    const bool more = q < xcount;
+    int nrt_ = 0, nct_ = 0;
+    if (more) {
+      tile_rc(q, nrt_, nct_);
+      gload(nrt_ * BM, nct_ * BN, koff);
+      load_rows(nrt_ * BM);
+    }
+
+    if (fin_mode == 1) {
+      // finished distances: offer those below tau_i to the point's packed minimum
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int rl = row_of(a, v);
+          unsigned long long key = ~0ull;
+#pragma unroll
+          for (int b = 0; b < TN; ++b) {
+            if ((bits >> ((a * TN + b) * 16 + v)) & 1ull) {
+              float dist = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
+              dist = dist > 0.f ? dist : 0.f;
+              if (dist < s_tau[rl]) {
+                const unsigned long long kb = pack_key(dist, gc[b]);
+                key = kb < key ? kb : key;
+              }
+            }
+          }
+          if (__ballot(key != ~0ull)) {
+#pragma unroll
+            for (int sh = 1; sh < 32; sh <<= 1) {
+              const unsigned long long o = __shfl_xor(key, sh, 64);
+              key = o < key ? o : key;
+            }
+            if (r32 == 0 && key != ~0ull) atomicMin(g.best + g.row_base + row0 + rl, key);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+    } else if (fin_mode == 2) {
+      // sparse enough: hand the alive pairs to the gather kernel, which resumes at block fin_m.
+      // One reservation per tile in the sub-list of this workgroup's XCD.
+      int wtot = __popcll(bits);
+#pragma unroll
+      for (int sh = 1; sh < 64; sh <<= 1) wtot += __shfl_xor(wtot, sh, 64);
+      if (lane == 0) s_wcnt[wave] = (unsigned int)wtot;
+      __syncthreads();
+      if (tid == 0) {
+        const unsigned int tot = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
+        unsigned int base = atomicAdd(g.pair_count + xcd * kSubListStride, tot);
+        if ((unsigned long long)base + tot > (unsigned long long)g.sub_capacity) {
+          *g.overflow = 1u;
+          base = 0xffffffffu;
+        } else {
+          base += xcd * g.sub_capacity;
+        }
+        s_wcnt[4] = base;
+      }
+      __syncthreads();
+      unsigned int run = s_wcnt[4];
+      if (run != 0xffffffffu && wtot > 0) {
+        for (int w = 0; w < wave; ++w) run += s_wcnt[w];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const bool keep = (bits >> ((a * TN + b) * 16 + v)) & 1ull;
+              const unsigned long long mk = __ballot(keep);
+              if (mk) {   // wave-uniform: most element slots of a sparse tile hold no alive pair
+                if (keep) {
+                  const int rl = row_of(a, v);
+                  const unsigned int pos =
+                      run + __builtin_amdgcn_mbcnt_hi((unsigned int)(mk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mk, 0u));
+                  Pair pr;
+                  pr.i = (int32_t)(g.row_base + row0 + rl);
+                  pr.j = (int32_t)((uint32_t)gc[b] | ((uint32_t)fin_m << 24));
+                  const float p = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
+                  pr.p = p > 0.f ? p : 0.f;
+                  pr.tau = s_tau[rl];
+                  g.pairs[pos] = pr;
+                }
+                run += (unsigned int)__popcll(mk);
+              }
+              __builtin_amdgcn_sched_barrier(0);
+            }
+      }
+    }
+
+    if (!more) break;
+    rt = nrt_;
+    ct = nct_;
+    __syncthreads();   // everyone is done with this tile's LDS before the next one is committed
+  }
 }
 
 hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
@@ -357,26 +409,21 @@ hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
       g.nb > kMaxBlocks || (reinterpret_cast<uintptr_t>(g.A) & 15u) || (reinterpret_cast<uintptr_t>(g.B) & 15u) ||
       g.N > (1 << 24))
     return hipErrorInvalidValue;
-  static const int bk = []() {
-    const char *e = std::getenv("SKM_TEST_PROG_BK");
-    const int v = e ? std::atoi(e) : 0;
-    return v == 16 ? 16 : 32;
-  }();
-  const size_t smem = (size_t)2 * (BM + BN) * (bk + 4) * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel_bk32),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)((size_t)2 * (BM + BN) * 36 * sizeof(float)));
+  constexpr size_t smem = (size_t)2 * (BM + BN) * LS * sizeof(float);
+  static int wgs = 0;
+  if (!wgs) {
+    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (rc != hipSuccess) return rc;
-    attr_set = true;
+    int dev = 0, cus = 256;
+    (void)hipGetDevice(&dev);
+    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    wgs = 2 * cus;   // two workgroups per CU (LDS and registers allow no more)
   }
-  const int64_t nwg = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  if (nwg >= (1 << 24)) return hipErrorInvalidValue;   // 2^32 threads per launch at most; the caller chunks rows
-  if (bk == 32)
-    hipLaunchKernelGGL(progressive_kernel_bk32, dim3((unsigned)nwg), dim3(NT), smem, st, g);
-  else
-    hipLaunchKernelGGL(progressive_kernel_bk16, dim3((unsigned)nwg), dim3(NT), smem, st, g);
+  const int64_t ntiles = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  if (ntiles > 0x7fffffffLL) return hipErrorInvalidValue;
+  const int64_t grid = std::max<int64_t>(8, std::min<int64_t>(wgs, (ntiles + 7) / 8 * 8));
+  hipLaunchKernelGGL(progressive_kernel, dim3((unsigned)grid), dim3(NT), smem, st, g);
   return hipGetLastError();
 }
 

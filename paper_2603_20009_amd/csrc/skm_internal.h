@@ -84,6 +84,7 @@ struct ProgArgs {
   int64_t row_base;
   Pair *pairs;             // kSubLists parts of sub_capacity slots each
   unsigned int *pair_count;   // [kSubLists * kSubListStride] fill counters of the parts
+  unsigned int *tile_counter; // [8 * kSubListStride] next tile of every XCD's range; zero before the launch
   unsigned int sub_capacity;
   unsigned int *overflow;
   unsigned int emit_max;   // a tile with at most this many alive pairs is handed over
