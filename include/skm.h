@@ -111,7 +111,8 @@ typedef struct skm_params {
                             one by the gather kernel.  1 = hand over right after the first test (the paper's
                             split), 0 = dense tiles only.  Execution strategy only: the tests applied to a
                             pair, and so the result, do not depend on it */
-  int32_t reserved;
+  float sample_frac;     /* 0    : in (0, 1): run Algorithm 1 on a uniform sample of round(frac * n) rows (at least k),
+                            then assign every point to the final centroids with the two-phase step (Section 4.4) */
 } skm_params;
 
 void skm_params_default(skm_params *p);

@@ -332,3 +332,29 @@ def fit(X, k: int, iters: int, seed: int, params: FitParams | None = None, R=Non
                          pruned_first=int(r.pruned_first), nempty=int(r.nempty), dprime=int(r.dprime),
                          enter=np.array(list(r.enter), dtype=np.int64)))
     return FitResult(Y, Yr, a, dist, int(run), rows)
+
+
+def fit_sampled(X, k: int, iters: int, seed: int, sample_frac: float, params: FitParams | None = None, R=None):
+    """Sampled fit (Section 4.4): Algorithm 1 on a uniform sample of round(frac * n) rows (at least k; stream 4 of
+    the seed, rows kept in ascending order), then every point is assigned to the final centroids by the two-phase
+    step without a previous assignment.  A composition of the steps above; returns (FitResult of the sample with
+    assign/dist replaced by those of all points, sample indices)."""
+    import dataclasses
+    p = params or FitParams()
+    X = _f32(X)
+    n, d = X.shape
+    s = min(max(int(np.floor(sample_frac * n + 0.5)), k), n)
+    idx = np.sort(sample_rows(seed, n, s, stream=4))
+    inner = fit(X[idx], k, iters, seed, dataclasses.replace(p, final_assign=False), R=R)
+    last = inner.trace[-1]
+    dp = dprime_init(d, p.dprime_frac)
+    if inner.iters_run >= 2:
+        dp = last["dprime"]
+        if p.adjust_dprime and k > 1:
+            dp = dprime_adjust(d, dp, last["prune_frac"], p.adj_lo, p.adj_hi, p.adj_step)
+    Xr = rotate(X, R) if R is not None else X.astype(np.float64)
+    fin = assign_pruned(Xr, inner.centroids_rot, None, dp, p.eps0, p.tau_group)
+    inner.assign, inner.dist = fin.assign, fin.dist
+    inner.trace.append(dict(objective=float(fin.dist.sum()), prune_frac=fin.pruned_first / (n * max(k - 1, 1)),
+                            recall=-1.0, pruned_first=fin.pruned_first, nempty=0, dprime=dp, enter=fin.enter))
+    return inner, idx

@@ -115,7 +115,7 @@ struct Rng {
   double uniform() { return (double)(next() >> 11) * (1.0 / 9007199254740992.0); }
 };
 Rng rng_stream(uint64_t seed, uint64_t stream) { return Rng{seed + stream * 0xD1342543DE82EF95ULL}; }
-enum { STREAM_INIT = 0, STREAM_SPLIT = 1, STREAM_QUERIES = 2, STREAM_ROTATION = 3 };
+enum { STREAM_INIT = 0, STREAM_SPLIT = 1, STREAM_QUERIES = 2, STREAM_ROTATION = 3, STREAM_SAMPLE = 4 };
 
 // k distinct indices of [0, n): the first k steps of a Fisher-Yates shuffle of the identity
 void sample_rows(uint64_t seed, uint64_t stream, int64_t n, int32_t k, int64_t *out) {
@@ -459,8 +459,14 @@ int rotate_into(const float *in, int64_t ldin, int64_t rows, int32_t d, int32_t 
   return SKM_OK;
 }
 
+int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, const int32_t *prev_assign,
+                int32_t dprime_in, const skm_params *pp, int32_t *assign_out, float *dist_out);
+int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params &p,
+                float *centroids_out, int32_t *assign_out, float *dist_out);
+
+// dprime_out (optional) receives the d' the next assignment step would use.
 int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params *pp,
-             float *centroids_out, int32_t *assign_out, float *dist_out) {
+             float *centroids_out, int32_t *assign_out, float *dist_out, int32_t *dprime_out = nullptr) {
   int rc = check_shape(X, n, d, k);
   if (rc) return rc;
   if (!centroids_out) return fail(SKM_EINVAL, "centroids_out is null");
@@ -471,6 +477,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   if (!(p.eps0 >= 0.f)) return fail(SKM_EINVAL, "eps0 must be >= 0");
   skm_trace *tr = p.trace;
   if (tr && (!tr->row || tr->capacity < 1)) return fail(SKM_EINVAL, "trace without rows");
+  if (p.sample_frac > 0.f && p.sample_frac < 1.f)
+    return fit_sampled(X, n, d, k, iters, seed, p, centroids_out, assign_out, dist_out);
 
   Ctx c;
   c.st = (hipStream_t)p.stream;
@@ -669,6 +677,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   }
   HIPCHK(hipEventRecord(e_end, c.st));
   HIPCHK(hipStreamSynchronize(c.st));
+  if (dprime_out) *dprime_out = dprime;
   if (tr) {
     tr->rows = std::min(rows, tr->capacity);
     tr->iters_run = run;
@@ -752,6 +761,108 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
   return SKM_OK;
 }
 
+// Sampled fit (Section 4.4): Algorithm 1 runs on a uniform sample of the rows, then every point is assigned
+// to the resulting centroids by the two-phase step without a previous assignment.
+int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params &p,
+                float *centroids_out, int32_t *assign_out, float *dist_out) {
+  if (p.etr) return fail(SKM_EINVAL, "sample_frac and ETR cannot be combined");
+  if (!p.final_assign) return fail(SKM_EINVAL, "sample_frac needs the final assignment pass");
+  int64_t s = (int64_t)std::llround((double)p.sample_frac * (double)n);
+  s = std::min<int64_t>(std::max<int64_t>(s, k), n);
+  hipStream_t st = (hipStream_t)p.stream;
+  const int32_t ds = round_up(d, 16);
+  Pool pool;
+  Events evs;
+  hipEvent_t e0 = evs.next(), e1 = evs.next();
+  if (!e0 || !e1) return fail(SKM_EHIP, "hipEventCreate failed");
+  HIPCHK(hipEventRecord(e0, st));
+  // rotate everything once: the final pass needs all rows in the rotated space
+  Rot rot;
+  const float *Xr = X;
+  int64_t ldx = d;
+  float *Xr_own = nullptr;
+  if (p.rotate) {
+    int rc = setup_rotation(pool, st, d, ds, p.R, seed, rot);
+    if (rc) return rc;
+    HIPCHK(pool.get(&Xr_own, (size_t)n * ds));
+    rc = rotate_into(X, d, n, d, ds, rot, Xr_own, st);
+    if (rc) return rc;
+    Xr = Xr_own; ldx = ds;
+  }
+  // the sample: s distinct rows, ascending
+  std::vector<int64_t> idx((size_t)s);
+  sample_rows(seed, STREAM_SAMPLE, n, (int32_t)std::min<int64_t>(s, 0x7fffffff), idx.data());
+  std::sort(idx.begin(), idx.end());
+  int64_t *idx_dev = nullptr;
+  float *Xs = nullptr, *Yr = nullptr;
+  HIPCHK(pool.get(&idx_dev, (size_t)s));
+  HIPCHK(pool.get(&Xs, (size_t)s * d));
+  HIPCHK(pool.get(&Yr, (size_t)k * d));
+  HIPCHK(hipMemcpyAsync(idx_dev, idx.data(), sizeof(int64_t) * idx.size(), hipMemcpyHostToDevice, st));
+  HIPCHK(launch_gather_rows(Xr, ldx, d, idx_dev, (int32_t)s, Xs, d, d, st));
+  HIPCHK(hipStreamSynchronize(st));
+  // Algorithm 1 on the sample, in the rotated space
+  skm_params pin = p;
+  pin.sample_frac = 0.f;
+  pin.rotate = 0;
+  pin.R = nullptr;
+  pin.final_assign = 0;
+  skm_trace inner{};
+  skm_trace *tr = p.trace;
+  if (tr) {
+    inner = *tr;
+    pin.trace = &inner;
+  }
+  int32_t dprime = 0;
+  int rc = fit_impl(Xs, s, d, k, iters, seed, &pin, Yr, nullptr, nullptr, &dprime);
+  if (rc) return rc;
+  // every point against the final centroids, no previous assignment
+  skm_params pfin = p;
+  pfin.rotate = 0;
+  pfin.R = nullptr;
+  skm_trace last{};
+  if (tr) {
+    last.capacity = tr->capacity - inner.rows;
+    last.row = tr->row + inner.rows;
+    pfin.trace = last.capacity >= 1 ? &last : nullptr;
+  }
+  if (Xr_own && ds != d) {
+    // the assignment call takes dense n x d rows; the rotated buffer has stride ds when d is no multiple of 16
+    float *Xd = nullptr;
+    HIPCHK(pool.get(&Xd, (size_t)n * d));
+    HIPCHK(hipMemcpy2DAsync(Xd, sizeof(float) * (size_t)d, Xr_own, sizeof(float) * (size_t)ds, sizeof(float) * (size_t)d,
+                            (size_t)n, hipMemcpyDeviceToDevice, st));
+    Xr = Xd;
+  }
+  float *dist_tmp = dist_out;
+  int32_t *assign_tmp = assign_out;
+  if (!assign_tmp) HIPCHK(pool.get(&assign_tmp, (size_t)n));
+  rc = assign_impl(Xr, n, d, Yr, k, nullptr, dprime, &pfin, assign_tmp, dist_tmp);
+  if (rc) return rc;
+  // centroids back in the original space
+  if (p.rotate) {
+    float *Yp = nullptr;
+    HIPCHK(pool.get(&Yp, (size_t)k * ds));
+    HIPCHK(launch_pad_copy(Yr, d, k, d, Yp, ds, ds, 0, st));
+    GemmOperands g{Yp, ds, k, rot.Rp, ds, d, d};
+    HIPCHK(gemm_store(g, centroids_out, d, d, 1.f, 0.f, st));
+  } else {
+    HIPCHK(hipMemcpyAsync(centroids_out, Yr, sizeof(float) * (size_t)k * d, hipMemcpyDeviceToDevice, st));
+  }
+  HIPCHK(hipEventRecord(e1, st));
+  HIPCHK(hipStreamSynchronize(st));
+  if (tr) {
+    tr->rows = inner.rows + ((pfin.trace && last.rows > 0) ? 1 : 0);
+    tr->iters_run = inner.iters_run;
+    tr->ms_rotate = 0.f;
+    tr->ms_init = inner.ms_init;
+    tr->ms_etr_gt = 0.f;
+    tr->ms_unrotate = 0.f;
+    (void)hipEventElapsedTime(&tr->ms_total, e0, e1);
+  }
+  return SKM_OK;
+}
+
 }  // namespace
 
 // ==================================================================== C ABI
@@ -779,6 +890,7 @@ void skm_params_default(skm_params *p) {
   p->etr_patience = 2;
   p->pair_budget = 0;
   p->dense_frac = 0.02f;
+  p->sample_frac = 0.f;
 }
 
 int skm_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, float *centroids_out,

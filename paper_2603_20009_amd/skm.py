@@ -49,7 +49,7 @@ class Params(C.Structure):
         ("probe_frac", C.c_float), ("etr_tol", C.c_float), ("etr_patience", C.c_int32),
         ("queries", C.c_void_p), ("gt", C.c_void_p),
         ("stream", C.c_void_p), ("trace", C.POINTER(Trace)), ("pair_budget", C.c_int64),
-        ("dense_frac", C.c_float), ("reserved", C.c_int32),
+        ("dense_frac", C.c_float), ("sample_frac", C.c_float),
     ]
 
 
@@ -145,6 +145,7 @@ class FitOptions:
     gt: torch.Tensor | None = None           # device nq x topk int64
     pair_budget: int = 0
     dense_frac: float = 0.02
+    sample_frac: float = 0.0
 
 
 @dataclass
@@ -190,6 +191,7 @@ def _params(o: FitOptions, keep: list, trace: Trace | None) -> Params:
         p.trace = C.pointer(trace)
     p.pair_budget = o.pair_budget
     p.dense_frac = o.dense_frac
+    p.sample_frac = o.sample_frac
     return p
 
 

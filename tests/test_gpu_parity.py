@@ -419,3 +419,20 @@ def test_largest_dimension_and_many_blocks(skm, orc, dg):
                                                                                      dense_frac=dense))
         check_assignment(a.cpu().numpy(), ref.assign, Xr, Yr)
         assert row["nblocks"] == 56 and row["enter"][0] == ref.enter[0]
+
+
+# ------------------------------------------------------------------ sampled fit (Section 4.4)
+@pytest.mark.parametrize("n,d,k,frac", [(20_000, 128, 64, 0.25), (6000, 100, 30, 0.5)])
+def test_sampled_fit(skm, orc, dg, n, d, k, frac):
+    X = dg.mixture(n, d, 80, 17, "linear").numpy()
+    R = orc.random_rotation(d, 17)
+    ref, idx = orc.fit_sampled(X, k, 6, 9, frac, orc.FitParams(eps0=EPS0), R=R)
+    got = skm.fit(cuda(X), k, 6, 9, skm.FitOptions(R=cuda(R), sample_frac=frac))
+    assert got.iters_run == 6 and len(got.trace) == 7
+    assert [g["dprime"] for g in got.trace] == [r["dprime"] for r in ref.trace]
+    assert rel_l2(got.centroids.cpu().numpy(), ref.centroids) < 1e-3
+    check_assignment(got.assign.cpu().numpy(), ref.assign, orc.rotate(X, R), ref.centroids_rot)
+    assert got.trace[-1]["objective"] == pytest.approx(ref.trace[-1]["objective"], rel=1e-4)
+    assert got.trace[0]["changed"] == len(idx)          # the loop ran on the sample only
+    with pytest.raises(skm.SkmError):
+        skm.fit(cuda(X), k, 2, 9, skm.FitOptions(R=cuda(R), sample_frac=frac, final_assign=False))

@@ -532,3 +532,19 @@ def test_etr_stops_early_and_reports_recall(orc):
     assert all(0.0 <= r["recall"] <= 1.0 for r in fr.trace[:3])
     p2 = orc.FitParams(etr=True, etr_tol=-1.0, probe_frac=0.1)                   # any change counts as improvement
     assert orc.fit(X, 20, 5, 1, p2, R=None, queries=Q).iters_run == 5
+
+
+def test_sampled_fit_composition(orc):
+    from paper_2603_20009_amd import datagen
+    X = datagen.mixture(3000, 64, 20, 3, "linear").numpy()
+    R = orc.random_rotation(64, 3)
+    fr, idx = orc.fit_sampled(X, 16, 5, 7, 0.3, orc.FitParams(), R=R)
+    assert len(idx) == 900 and len(set(idx.tolist())) == 900 and (np.diff(idx) > 0).all()
+    assert fr.assign.shape == (3000,) and fr.assign.max() < 16
+    # the centroids are the means of the sample under its last in-loop assignment: one exact step from them
+    # moves every centroid little, and the full assignment is one-sided against the exact nearest centroid
+    Xr = orc.rotate(X, R)
+    D = brute_dist(Xr, fr.centroids_rot)
+    assert (fr.dist >= D.min(1) * (1 - 1e-12)).all() and (fr.dist > D.min(1) * (1 + 1e-9)).mean() < 0.01
+    full = orc.fit(X, 16, 5, 7, orc.FitParams(), R=R)
+    assert fr.trace[-1]["objective"] == pytest.approx(full.trace[-1]["objective"], rel=0.2)    # similar quality
