@@ -167,6 +167,13 @@ int make_rotation_dev(Pool &pool, int32_t d, uint64_t seed, hipStream_t st, floa
 }
 
 inline int32_t round_up(int32_t v, int32_t m) { return (v + m - 1) / m * m; }
+
+// *slot = bit pattern of max |A| (the bound the split-fp16 GEMMs scale their operands by)
+int measure_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsigned int *slot, hipStream_t st) {
+  HIPCHK(launch_fill_u32(slot, 1, 0u, st));
+  HIPCHK(launch_absmax(A, lda, rows, cols, slot, st));
+  return SKM_OK;
+}
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int check_shape(const void *X, int64_t n, int32_t d, int32_t k) {
@@ -204,6 +211,15 @@ struct Ctx {
   UpdateWs up{};
   int32_t *split_dev = nullptr;
   bool block_stats = false;
+  unsigned int *amax = nullptr;      // [AM_COUNT] magnitude bounds of the GEMM operands
+  enum { AM_XR = 0, AM_Y = 1, AM_X = 2, AM_Q = 3, AM_QR = 4, AM_COUNT = 8 };
+
+  int alloc_bounds() {
+    HIPCHK(pool.get(&amax, (size_t)AM_COUNT));
+    return SKM_OK;
+  }
+  int measure_xr() { return measure_absmax(Xr, ldx, n, ds, amax + AM_XR, st); }
+  int measure_y() { return measure_absmax(Y, ds, k, ds, amax + AM_Y, st); }
 
   int alloc_common(int64_t pair_budget, float dense_frac, bool need_update) {
     HIPCHK(pool.get(&Y, (size_t)k * ds));
@@ -267,7 +283,9 @@ int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
   HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * (c.ncounters + 1), c.st));
   HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, c.ds, c.ynorm, 0, 0, nullptr, c.st));
   HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
+  if (int rc = c.measure_y()) return rc;
   GemmOperands g{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, c.ds};
+  g.a_absmax = c.amax + Ctx::AM_XR; g.b_absmax = c.amax + Ctx::AM_Y;
   HIPCHK(gemm_argmin(g, c.ynorm, c.best, c.st));
   tm.mark(ST_GEMM);
   // winners -> direct squared distances (also the objective of this step)
@@ -299,6 +317,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   if (nb > kMaxBlocks) return fail(SKM_EINTERNAL, "too many trailing blocks");
   tm.mark(ST_NONE);
   HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, dprime, c.ynorm, dprime, nb, c.Ypdx, c.st));
+  if (int rc = c.measure_y()) return rc;
   // theta ratio at checkpoint m: t_m = min(d, d' + 64 m) dimensions seen
   float *ratio = c.ratio_host;
   for (int m = 0; m <= nb; ++m) ratio[m] = (float)theta_ratio(c.d, std::min(c.d, dprime + kBlockDims * m), eps0);
@@ -307,6 +326,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   if (!have_prev) {
     HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
     GemmOperands g0{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, dprime};
+    g0.a_absmax = c.amax + Ctx::AM_XR; g0.b_absmax = c.amax + Ctx::AM_Y;
     HIPCHK(gemm_argmin(g0, c.ynorm, c.best, c.st));
     HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, nullptr, nullptr, c.counters + c.ncounters, c.st));
     tm.mark(ST_GEMM);
@@ -321,6 +341,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     ProgArgs g{};
     g.A = c.Xr + r0 * c.ldx; g.lda = c.ldx; g.M = (int32_t)rows;
     g.B = c.Y; g.ldb = c.ds; g.N = c.k;
+    g.a_absmax = c.amax + Ctx::AM_XR; g.b_absmax = c.amax + Ctx::AM_Y;
     g.ds = c.ds; g.d = c.d; g.dprime = dprime; g.nb = nb;
     g.ratio = c.ratio_dev; g.tau = c.tau; g.prev = c.prev; g.row_base = r0;
     unsigned int *fill = c.counters + (size_t)ch * kSubLists * kSubListStride;
@@ -436,6 +457,7 @@ void fill_row(skm_trace_row &r, const StepStats &ss, int64_t n, int32_t k, int64
 // Rotation buffers: Rp = R padded to row stride ds, Rtp = R^T padded likewise (both d rows).
 struct Rot {
   float *Rp = nullptr, *Rtp = nullptr;
+  unsigned int *amax = nullptr;   // [0] max |R|, [1] max |input| of the last rotate_into
 };
 int setup_rotation(Pool &pool, hipStream_t st, int32_t d, int32_t ds, const float *R_dev, uint64_t seed, Rot &rot) {
   float *Rown = nullptr;
@@ -449,13 +471,27 @@ int setup_rotation(Pool &pool, hipStream_t st, int32_t d, int32_t ds, const floa
   HIPCHK(pool.get(&rot.Rtp, (size_t)d * ds));
   HIPCHK(launch_pad_copy(R_dev, d, d, d, rot.Rp, ds, ds, 0, st));
   HIPCHK(launch_pad_copy(R_dev, d, d, d, rot.Rtp, ds, ds, 1, st));
-  return SKM_OK;
+  HIPCHK(pool.get(&rot.amax, 2));
+  return measure_absmax(R_dev, d, d, d, rot.amax, st);
 }
 // out (rows x ds, zero padded) = in (rows x d, stride ldin) * R
+// out_absmax (optional) receives the bit pattern of max |out|
 int rotate_into(const float *in, int64_t ldin, int64_t rows, int32_t d, int32_t ds, const Rot &rot, float *out,
-                hipStream_t st) {
+                hipStream_t st, unsigned int *out_absmax = nullptr) {
+  if (int rc = measure_absmax(in, ldin, rows, d, rot.amax + 1, st)) return rc;
+  if (out_absmax) HIPCHK(launch_fill_u32(out_absmax, 1, 0u, st));
   GemmOperands g{in, ldin, (int32_t)rows, rot.Rtp, ds, d, d};
-  HIPCHK(gemm_store(g, out, ds, ds, 1.f, 0.f, st));
+  g.a_absmax = rot.amax + 1; g.b_absmax = rot.amax;
+  HIPCHK(gemm_store(g, out, ds, ds, 1.f, 0.f, st, out_absmax));
+  return SKM_OK;
+}
+// out (rows x d) = Yr (rows x d, stride ldy) * R^T
+int unrotate_into(const float *Yr, int64_t ldy, int32_t rows, int32_t d, int32_t ds, const Rot &rot, float *out,
+                  hipStream_t st) {
+  if (int rc = measure_absmax(Yr, ldy, rows, d, rot.amax + 1, st)) return rc;
+  GemmOperands g{Yr, ldy, rows, rot.Rp, ds, d, d};
+  g.a_absmax = rot.amax + 1; g.b_absmax = rot.amax;
+  HIPCHK(gemm_store(g, out, d, d, 1.f, 0.f, st));
   return SKM_OK;
 }
 
@@ -492,6 +528,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   if (!e_begin || !e_rot || !e_init || !e_end0 || !e_end || !e_gt0 || !e_gt1 || !e_rot0)
     return fail(SKM_EHIP, "hipEventCreate failed");
   HIPCHK(hipEventRecord(e_begin, c.st));
+  rc = c.alloc_bounds();
+  if (rc) return rc;
 
   // ---- Algorithm 1: R, X~ = X R
   Rot rot;
@@ -501,7 +539,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     if (rc) return rc;
     HIPCHK(c.pool.get(&Xr_own, (size_t)n * c.ds));
     HIPCHK(hipEventRecord(e_rot0, c.st));
-    rc = rotate_into(X, d, n, d, c.ds, rot, Xr_own, c.st);
+    rc = rotate_into(X, d, n, d, c.ds, rot, Xr_own, c.st, c.amax + Ctx::AM_XR);
     if (rc) return rc;
     HIPCHK(hipEventRecord(e_rot, c.st));
     c.Xr = Xr_own; c.ldx = c.ds;
@@ -515,6 +553,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   if (!p.rotate) {
     HIPCHK(hipEventRecord(e_rot0, c.st));
     HIPCHK(hipEventRecord(e_rot, c.st));
+    rc = c.measure_xr();
+    if (rc) return rc;
   }
   rc = c.alloc_common(p.pair_budget, p.dense_frac, true);
   if (rc) return rc;
@@ -571,19 +611,26 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
       HIPCHK(c.pool.get(&S, (size_t)p.nq * colchunk));
       HIPCHK(launch_row_norms(X, d, n, d, xnorm, c.st));
       HIPCHK(launch_fill_u64(gt_keys, (int64_t)p.nq * p.topk, ~0ull, c.st));
+      rc = measure_absmax(X, d, n, d, c.amax + Ctx::AM_X, c.st);
+      if (rc) return rc;
+      rc = measure_absmax(Q, d, p.nq, d, c.amax + Ctx::AM_Q, c.st);
+      if (rc) return rc;
       for (int64_t c0 = 0; c0 < n; c0 += colchunk) {
         const int64_t m = std::min<int64_t>(colchunk, n - c0);
         GemmOperands g{Q, d, p.nq, X + c0 * d, d, (int32_t)m, d};
+        g.a_absmax = c.amax + Ctx::AM_Q; g.b_absmax = c.amax + Ctx::AM_X;
         HIPCHK(gemm_store(g, S, colchunk, (int32_t)m, 1.f, 0.f, c.st));
         HIPCHK(launch_topk_merge(S, colchunk, p.nq, (int32_t)m, c0, xnorm, p.topk, gt_keys, c.st));
       }
     }
     HIPCHK(c.pool.get(&Qr, (size_t)p.nq * c.ds));
     if (p.rotate) {
-      rc = rotate_into(Q, d, p.nq, d, c.ds, rot, Qr, c.st);
+      rc = rotate_into(Q, d, p.nq, d, c.ds, rot, Qr, c.st, c.amax + Ctx::AM_QR);
       if (rc) return rc;
     } else {
       HIPCHK(launch_pad_copy(Q, d, p.nq, d, Qr, c.ds, c.ds, 0, c.st));
+      rc = measure_absmax(Qr, c.ds, p.nq, c.ds, c.amax + Ctx::AM_QR, c.st);
+      if (rc) return rc;
     }
     HIPCHK(c.pool.get(&Sq, (size_t)p.nq * k));
     HIPCHK(c.pool.get(&ynorm_full, (size_t)k));
@@ -599,7 +646,9 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   // recall of (current centroids, current assignment): Section 3.3
   auto measure_recall = [&](double *out) -> int {
     HIPCHK(launch_prep_centroids(c.Y, c.ds, k, c.ds, c.ds, ynorm_full, 0, 0, nullptr, c.st));
+    if (int mrc = c.measure_y()) return mrc;
     GemmOperands g{Qr, c.ds, p.nq, c.Y, c.ds, k, c.ds};
+    g.a_absmax = c.amax + Ctx::AM_QR; g.b_absmax = c.amax + Ctx::AM_Y;
     HIPCHK(gemm_store(g, Sq, k, k, 1.f, 0.f, c.st));
     HIPCHK(hipMemsetAsync(etr_scal, 0, 2 * sizeof(unsigned long long), c.st));
     HIPCHK(launch_recall_scores(Sq, k, p.nq, k, ynorm_full, nprobe, gt_keys, p.topk, c.assign, etr_scal, etr_scal + 1,
@@ -669,8 +718,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   // ---- Algorithm 1, last line: Y = Y~ R^T
   HIPCHK(hipEventRecord(e_end0, c.st));
   if (p.rotate) {
-    GemmOperands g{c.Y, c.ds, k, rot.Rp, c.ds, d, d};
-    HIPCHK(gemm_store(g, centroids_out, d, d, 1.f, 0.f, c.st));
+    rc = unrotate_into(c.Y, c.ds, k, d, c.ds, rot, centroids_out, c.st);
+    if (rc) return rc;
   } else {
     HIPCHK(hipMemcpy2DAsync(centroids_out, sizeof(float) * (size_t)d, c.Y, sizeof(float) * (size_t)c.ds,
                             sizeof(float) * (size_t)d, (size_t)k, hipMemcpyDeviceToDevice, c.st));
@@ -717,13 +766,15 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
   StageTimer tm(c.st, true);
   Rot rot;
   float *Xr_own = nullptr;
+  rc = c.alloc_bounds();
+  if (rc) return rc;
   rc = c.alloc_common(p.pair_budget, p.dense_frac, false);
   if (rc) return rc;
   if (p.rotate) {
     rc = setup_rotation(c.pool, c.st, d, c.ds, p.R, 0, rot);
     if (rc) return rc;
     HIPCHK(c.pool.get(&Xr_own, (size_t)n * c.ds));
-    rc = rotate_into(X, d, n, d, c.ds, rot, Xr_own, c.st);
+    rc = rotate_into(X, d, n, d, c.ds, rot, Xr_own, c.st, c.amax + Ctx::AM_XR);
     if (rc) return rc;
     rc = rotate_into(centroids, d, k, d, c.ds, rot, c.Y, c.st);
     if (rc) return rc;
@@ -737,6 +788,8 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
       c.Xr = Xr_own; c.ldx = c.ds;
     }
     HIPCHK(launch_pad_copy(centroids, d, k, d, c.Y, c.ds, c.ds, 0, c.st));
+    rc = c.measure_xr();
+    if (rc) return rc;
   }
   if (prev_assign) {
     rc = labels_in_range(prev_assign, n, k, c.counters, c.st);
@@ -844,8 +897,8 @@ int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, 
     float *Yp = nullptr;
     HIPCHK(pool.get(&Yp, (size_t)k * ds));
     HIPCHK(launch_pad_copy(Yr, d, k, d, Yp, ds, ds, 0, st));
-    GemmOperands g{Yp, ds, k, rot.Rp, ds, d, d};
-    HIPCHK(gemm_store(g, centroids_out, d, d, 1.f, 0.f, st));
+    rc = unrotate_into(Yp, ds, k, d, ds, rot, centroids_out, st);
+    if (rc) return rc;
   } else {
     HIPCHK(hipMemcpyAsync(centroids_out, Yr, sizeof(float) * (size_t)k * d, hipMemcpyDeviceToDevice, st));
   }
@@ -937,7 +990,14 @@ int skm_assign_exact(const float *X, int64_t n, int32_t d, const float *centroid
   HIPCHK(pool.get(&best, (size_t)n));
   HIPCHK(launch_prep_centroids(Yp, ldy, k, ds, ds, ynorm, 0, 0, nullptr, st));
   HIPCHK(launch_fill_u64(best, n, ~0ull, st));
+  unsigned int *amax = nullptr;
+  HIPCHK(pool.get(&amax, 2));
+  rc = measure_absmax(Xp, ldx, n, ds, amax, st);
+  if (rc) return rc;
+  rc = measure_absmax(Yp, ldy, k, ds, amax + 1, st);
+  if (rc) return rc;
   GemmOperands g{Xp, ldx, (int32_t)n, Yp, ldy, k, ds};
+  g.a_absmax = amax; g.b_absmax = amax + 1;
   HIPCHK(gemm_argmin(g, ynorm, best, st));
   HIPCHK(launch_finalize_assign(best, nullptr, n, assign_out, nullptr, nullptr, nullptr, nullptr, nullptr, st));
   if (dist_out) {
@@ -1009,7 +1069,14 @@ int skm_rotate(const float *X, int64_t n, int32_t d, const float *R, int32_t tra
   float *B = nullptr;  // B[c][kk] = R[kk][c] for X R, R[c][kk] for X R^T
   HIPCHK(pool.get(&B, (size_t)d * ds));
   HIPCHK(launch_pad_copy(R, d, d, d, B, ds, ds, transpose ? 0 : 1, st));
+  unsigned int *amax = nullptr;
+  HIPCHK(pool.get(&amax, 2));
+  int rc = measure_absmax(X, d, n, d, amax, st);
+  if (rc) return rc;
+  rc = measure_absmax(R, d, d, d, amax + 1, st);
+  if (rc) return rc;
   GemmOperands g{X, d, (int32_t)n, B, ds, d, d};
+  g.a_absmax = amax; g.b_absmax = amax + 1;
   HIPCHK(gemm_store(g, out, d, d, 1.f, 0.f, st));
   HIPCHK(hipStreamSynchronize(st));
   return SKM_OK;

@@ -1,11 +1,17 @@
-// fp32 MFMA "NT" GEMM for gfx950 with two fused epilogues (store, row argmin).
+// MFMA "NT" GEMM for gfx950 with two fused epilogues (store, row argmin).
 //
 // The GEMM phase of SuperKMeans (Algorithm 1: iteration 1 over all d dimensions, later iterations
 // over the first d' dimensions; Section 3.1 for the rotation X R) is a product of two K-contiguous
 // row-major matrices.  One workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 128 x 128 tile of
-// the score matrix; each wavefront owns 64 x 64 of it as 2 x 2 v_mfma_f32_32x32x2_f32 accumulators.
-// K is consumed in slabs of BK floats that are staged global -> registers -> LDS (two LDS buffers,
-// one barrier per slab) while the previous slab is multiplied.
+// the score matrix; each wavefront owns 64 x 64 of it as 2 x 2 accumulators of 32 x 32.
+// K is consumed in slabs that are staged global -> registers -> LDS (two LDS buffers, one barrier
+// per slab) while the previous slab is multiplied.
+//
+// Two arithmetic forms share the tile shape and the epilogues:
+//  - gemm_split_kernel: fp32 operands split into two fp16 numbers each, three v_mfma_f32_32x32x16_f16
+//    per product, fp32 accumulation (fp32-class accuracy at a multiple of the fp32 matrix rate).  Used
+//    whenever the operands are 16-byte aligned, K >= 32 and the caller supplies magnitude bounds.
+//  - gemm_kernel: plain v_mfma_f32_32x32x2_f32, for unaligned operands and K = 16.
 //
 // The score matrix is never written for the distance use of iteration 1: the epilogue reduces it to
 // a row argmin.  Iterations >= 2 use the progressive kernel of progressive.hip, built on the same tile.
@@ -13,10 +19,14 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 namespace skm {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int BM = 128, BN = 128;  // workgroup tile
 constexpr int WTM = 64, WTN = 64;  // wavefront tile
@@ -30,6 +40,7 @@ struct StoreArgs {
   int64_t ldc;
   int32_t Nstore;
   float alpha, beta;
+  unsigned int *c_absmax;   // optional: max |C| is folded into it
 };
 struct ArgminArgs {
   const float *ynorm;
@@ -63,6 +74,86 @@ __device__ inline void tile_of_block(int nrt, int nct, int PC, int &rt, int &ct)
   const int pc = (nct - p * PC) < PC ? (nct - p * PC) : PC;
   rt = r / pc;
   ct = p * PC + (r - rt * pc);
+}
+
+// Epilogues of a finished 128 x 128 tile.  `unscale` turns an accumulator into the score s(i, j).
+// Accumulator layout of the 32 x 32 MFMA results: register v of lane (r32, kh) holds
+// row 8*(v/4) + 4*kh + (v%4), column r32 of the 32 x 32 tile.
+template <int EPI>
+__device__ inline void tile_epilogue(f32x16 (&acc)[TM][TN], const GemmOperands &g, const typename EpiArgs<EPI>::type &e,
+                                     int row0, int col0, float unscale, float *smem) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int r32 = lane & 31, kh = lane >> 5;
+  auto row_of = [&](int a, int v) { return wm * WTM + a * 32 + 8 * (v >> 2) + 4 * kh + (v & 3); };
+
+  if constexpr (EPI == EPI_STORE) {
+    const float alpha = e.alpha * unscale;
+    float vmax = 0.f;
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int gr = row0 + row_of(a, v);
+        if (gr >= g.M) continue;
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+          const int gc = col0 + wn * WTN + b * 32 + r32;
+          if (gc >= e.Nstore) continue;
+          float *dst = e.C + (int64_t)gr * e.ldc + gc;
+          float val = 0.f;
+          if (gc < g.N) {
+            val = alpha * acc[a][b][v];
+            if (e.beta != 0.f) val += e.beta * *dst;
+            vmax = fmaxf(vmax, fabsf(val));
+          }
+          *dst = val;
+        }
+      }
+    if (e.c_absmax) {
+#pragma unroll
+      for (int m = 1; m < 64; m <<= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, m, 64));
+      if (lane == 0 && vmax > 0.f) atomicMax(e.c_absmax, __builtin_bit_cast(unsigned int, vmax));
+    }
+  } else if constexpr (EPI == EPI_ARGMIN) {
+    // per-row minimum of ynorm[j] - 2 s(i,j): lanes of one half share the rows, columns differ
+    unsigned long long *red = reinterpret_cast<unsigned long long *>(smem);  // [2][BM], reuses the tile buffers
+    const float m2 = -2.f * unscale;
+    float yn[TN];
+    int gc[TN];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+      gc[b] = col0 + wn * WTN + b * 32 + r32;
+      yn[b] = gc[b] < g.N ? e.ynorm[gc[b]] : 0.f;
+    }
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        unsigned long long key = ~0ull;
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+          if (gc[b] < g.N) {
+            const unsigned long long kb = pack_key(fmaf(m2, acc[a][b][v], yn[b]), gc[b]);
+            key = kb < key ? kb : key;
+          }
+        }
+#pragma unroll
+        for (int m = 1; m < 32; m <<= 1) {
+          const unsigned long long o = __shfl_xor(key, m, 64);
+          key = o < key ? o : key;
+        }
+        if (r32 == 0) red[wn * BM + row_of(a, v)] = key;
+      }
+    __syncthreads();
+    if (tid < BM) {
+      const unsigned long long k0 = red[tid], k1 = red[BM + tid];
+      const unsigned long long key = k0 < k1 ? k0 : k1;
+      const int gr = row0 + tid;
+      if (gr < g.M && key != ~0ull) atomicMin(e.best + gr, key);
+    }
+  }
 }
 
 template <int BK, int EPI, bool ALIGNED>
@@ -188,67 +279,201 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmOperands g, typename
     __syncthreads();
   }
 
-  // Accumulator layout of v_mfma_f32_32x32x2_f32: register v of lane (r32, kh) holds
-  // row 8*(v/4) + 4*kh + (v%4), column r32 of the 32 x 32 tile.
-  auto row_of = [&](int a, int v) { return wm * WTM + a * 32 + 8 * (v >> 2) + 4 * kh + (v & 3); };
+  tile_epilogue<EPI>(acc, g, e, row0, col0, 1.f, smem);
+}
 
-  if constexpr (EPI == EPI_STORE) {
+// ---------------------------------------------------------------- split-fp16 form
+// Same tile and wavefront layout, but every operand value is scaled and staged as two fp16 numbers hi and lo
+// (see skm_internal.h) and a product is taken as lo*hi' + hi*lo' + hi*hi' on v_mfma_f32_32x32x16_f16: three
+// matrix instructions of a quarter of the issue time replace eight fp32 ones.  A tile row of a slab of 32 dims
+// holds its 32 hi values (64 bytes), then its 32 lo values, then 16 bytes of padding: the fp32 stride.
+//
+// With the matrix work five times shorter, staging decides the speed, so the loop is software pipelined by
+// hand.  Global loads are unconditional (rows and the K tail are clamped to valid addresses; a clamped tail
+// is multiplied by a zero scale, clamped rows only feed accumulators that are never stored), which lets the
+// compiler keep the loads of two slabs in flight and count them.  While slab s is multiplied from one LDS
+// buffer, slab s + 1 (requested one step earlier) is converted and written to the other buffer between the
+// matrix instructions, and slab s + 2 is requested.
+constexpr int SBK = 32, SLS = SBK + 4;
+constexpr int S_F4 = BM * (SBK / 4) / NTHREADS;   // float4 staged per thread and operand: 4
+
+template <int EPI>
+__global__ void __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+gemm_split_kernel(GemmOperands g, typename EpiArgs<EPI>::type e) {
+  extern __shared__ __align__(16) float smem[];
+  float *As = smem;                    // [2][BM][SLS]
+  float *Bs = smem + 2 * BM * SLS;     // [2][BN][SLS]
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int r32 = lane & 31, kh = lane >> 5;
+
+  const int nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
+  int rt, ct;
+  tile_of_block(nrt, nct, g.panel_cols, rt, ct);
+  const int row0 = rt * BM, col0 = ct * BN;
+
+  const unsigned int ma = *g.a_absmax, mb = *g.b_absmax;
+  const float scale_a = split_scale(ma), scale_b = split_scale(mb);
+  const float unscale = split_unscale(ma) * split_unscale(mb);
+
+  // staging: thread (st_row, kq) moves dims 4 kq .. 4 kq + 3 of tile rows st_row + 32 s.  The 8-lane groups of
+  // a wavefront take rows 4 apart (group bits 0-1 and 2-3 swapped): with a row stride of 36 words the four rows
+  // written by 32 lanes then start 16 banks apart and their 8-byte writes do not collide.
+  const int grp = tid >> 3, kq = tid & 7;
+  const int st_row = (grp & 16) | ((grp & 3) << 2) | ((grp >> 2) & 3);
+  const float *pa[S_F4], *pb[S_F4];
 #pragma unroll
-    for (int a = 0; a < TM; ++a)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int gr = row0 + row_of(a, v);
-        if (gr >= g.M) continue;
-#pragma unroll
-        for (int b = 0; b < TN; ++b) {
-          const int gc = col0 + wn * WTN + b * 32 + r32;
-          if (gc >= e.Nstore) continue;
-          float *dst = e.C + (int64_t)gr * e.ldc + gc;
-          float val = 0.f;
-          if (gc < g.N) {
-            val = e.alpha * acc[a][b][v];
-            if (e.beta != 0.f) val += e.beta * *dst;
-          }
-          *dst = val;
-        }
-      }
-  } else if constexpr (EPI == EPI_ARGMIN) {
-    // per-row minimum of ynorm[j] - 2 s(i,j): lanes of one half share the rows, columns differ
-    unsigned long long *red = reinterpret_cast<unsigned long long *>(smem);  // [2][BM], reuses the tile buffers
-    float yn[TN];
-    int gc[TN];
-#pragma unroll
-    for (int b = 0; b < TN; ++b) {
-      gc[b] = col0 + wn * WTN + b * 32 + r32;
-      yn[b] = gc[b] < g.N ? e.ynorm[gc[b]] : 0.f;
-    }
-#pragma unroll
-    for (int a = 0; a < TM; ++a)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        unsigned long long key = ~0ull;
-#pragma unroll
-        for (int b = 0; b < TN; ++b) {
-          if (gc[b] < g.N) {
-            const unsigned long long kb = pack_key(yn[b] - 2.f * acc[a][b][v], gc[b]);
-            key = kb < key ? kb : key;
-          }
-        }
-#pragma unroll
-        for (int m = 1; m < 32; m <<= 1) {
-          const unsigned long long o = __shfl_xor(key, m, 64);
-          key = o < key ? o : key;
-        }
-        if (r32 == 0) red[wn * BM + row_of(a, v)] = key;
-      }
-    __syncthreads();
-    if (tid < BM) {
-      const unsigned long long k0 = red[tid], k1 = red[BM + tid];
-      const unsigned long long key = k0 < k1 ? k0 : k1;
-      const int gr = row0 + tid;
-      if (gr < g.M && key != ~0ull) atomicMin(e.best + gr, key);
-    }
+  for (int s = 0; s < S_F4; ++s) {
+    const int gr = min(row0 + st_row + 32 * s, g.M - 1);
+    const int gc = min(col0 + st_row + 32 * s, g.N - 1);
+    pa[s] = g.A + (int64_t)gr * g.lda;
+    pb[s] = g.B + (int64_t)gc * g.ldb;
   }
+  auto gload = [&](int k0, float4 *ra, float4 *rb) {
+    const int kk = min(k0 + 4 * kq, g.K - 4);
+#pragma unroll
+    for (int s = 0; s < S_F4; ++s) ra[s] = *reinterpret_cast<const float4 *>(pa[s] + kk);
+#pragma unroll
+    for (int s = 0; s < S_F4; ++s) rb[s] = *reinterpret_cast<const float4 *>(pb[s] + kk);
+  };
+  auto split_store = [&](float *dst_row, const float4 &v, float scale) {
+    const f32x2 p0 = {v.x * scale, v.y * scale}, p1 = {v.z * scale, v.w * scale};
+    const f16x2 h0 = __builtin_convertvector(p0, f16x2), h1 = __builtin_convertvector(p1, f16x2);
+    const f16x2 l0 = __builtin_convertvector(p0 - __builtin_convertvector(h0, f32x2), f16x2);
+    const f16x2 l1 = __builtin_convertvector(p1 - __builtin_convertvector(h1, f32x2), f16x2);
+    uint2 hi, lo;
+    hi.x = __builtin_bit_cast(unsigned int, h0); hi.y = __builtin_bit_cast(unsigned int, h1);
+    lo.x = __builtin_bit_cast(unsigned int, l0); lo.y = __builtin_bit_cast(unsigned int, l1);
+    *reinterpret_cast<uint2 *>(dst_row + 2 * kq) = hi;
+    *reinterpret_cast<uint2 *>(dst_row + 16 + 2 * kq) = lo;
+  };
+  auto store_slab = [&](int buf, int k0, const float4 *ra, const float4 *rb) {   // unpipelined (prologue)
+    const bool live = k0 + 4 * kq < g.K;
+#pragma unroll
+    for (int s = 0; s < S_F4; ++s) {
+      split_store(As + (buf * BM + st_row + 32 * s) * SLS, ra[s], live ? scale_a : 0.f);
+      split_store(Bs + (buf * BN + st_row + 32 * s) * SLS, rb[s], live ? scale_b : 0.f);
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int a = 0; a < TM; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  // Fragments of half a slab (16 dims): lane half kh supplies the 8 consecutive dims 16 h + 8 kh .. + 7 of both
+  // operands.  Products are taken in three groups of four matrix instructions, hi*hi', lo*hi', hi*lo'.
+  f16x8 ah[TM], al[TM], bh[TN], bl[TN];
+  auto frag = [&](const float *base, int h, int lo, int t) {
+    return *reinterpret_cast<const f16x8 *>(base + t * 32 * SLS + kh * 4 + h * 8 + lo * 16);
+  };
+  auto mma4 = [&](const f16x8 (&x)[TM], const f16x8 (&y)[TN]) {
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[a], y[b], acc[a][b], 0, 0, 0);
+  };
+  // interleave the four matrix instructions of a group with `valu` vector instructions each
+  auto mix = [&](auto valu_per_mfma) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, decltype(valu_per_mfma)::value, 0);
+    }
+  };
+  auto multiply_only = [&](int buf) {
+    const float *Ab = As + (buf * BM + wm * WTM + r32) * SLS;
+    const float *Bb = Bs + (buf * BN + wn * WTN + r32) * SLS;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        ah[t] = frag(Ab, h, 0, t); al[t] = frag(Ab, h, 1, t);
+        bh[t] = frag(Bb, h, 0, t); bl[t] = frag(Bb, h, 1, t);
+      }
+      mma4(ah, bh);
+      mma4(al, bh);
+      mma4(ah, bl);
+    }
+  };
+  // One pipelined step: request slab k_load into (la, lb), multiply LDS buffer `buf`, and between the matrix
+  // instructions convert the slab k_store held in (sa, sb) into the other buffer.  The fragments of the second
+  // half are fetched into registers as the first half releases them, two groups before their first use.
+  auto step = [&](int buf, int k_store, const float4 *sa, const float4 *sb, int k_load, float4 *la, float4 *lb) {
+    const float *Ab = As + (buf * BM + wm * WTM + r32) * SLS;
+    const float *Bb = Bs + (buf * BN + wn * WTN + r32) * SLS;
+    float *Aw = As + ((buf ^ 1) * BM + st_row) * SLS;
+    float *Bw = Bs + ((buf ^ 1) * BN + st_row) * SLS;
+    const bool live = k_store + 4 * kq < g.K;
+    const float fa = live ? scale_a : 0.f, fb = live ? scale_b : 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+    gload(k_load, la, lb);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      ah[t] = frag(Ab, 0, 0, t); bh[t] = frag(Bb, 0, 0, t);
+      al[t] = frag(Ab, 0, 1, t); bl[t] = frag(Bb, 0, 1, t);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    mma4(ah, bh);
+    split_store(Aw, sa[0], fa);
+    split_store(Aw + 32 * SLS, sa[1], fa);
+    mix(std::integral_constant<int, 6>());
+    __builtin_amdgcn_sched_barrier(0);
+    mma4(al, bh);
+    split_store(Aw + 64 * SLS, sa[2], fa);
+    mix(std::integral_constant<int, 3>());
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) { al[t] = frag(Ab, 1, 1, t); bh[t] = frag(Bb, 1, 0, t); }
+    mma4(ah, bl);
+    split_store(Aw + 96 * SLS, sa[3], fa);
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+    mix(std::integral_constant<int, 3>());
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) { ah[t] = frag(Ab, 1, 0, t); bl[t] = frag(Bb, 1, 1, t); }
+    mma4(al, bh);
+    split_store(Bw, sb[0], fb);
+    split_store(Bw + 32 * SLS, sb[1], fb);
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+    mix(std::integral_constant<int, 6>());
+    __builtin_amdgcn_sched_barrier(0);
+    mma4(ah, bl);
+    split_store(Bw + 64 * SLS, sb[2], fb);
+    mix(std::integral_constant<int, 3>());
+    __builtin_amdgcn_sched_barrier(0);
+    mma4(ah, bh);
+    split_store(Bw + 96 * SLS, sb[3], fb);
+    mix(std::integral_constant<int, 3>());
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+  };
+
+  const int nslab = (g.K + SBK - 1) / SBK;
+  float4 ra0[S_F4], rb0[S_F4], ra1[S_F4], rb1[S_F4];
+  gload(0, ra0, rb0);
+  store_slab(0, 0, ra0, rb0);
+  gload(SBK, ra0, rb0);
+  __syncthreads();
+  // At the top of an even step LDS buffer 0 holds slab s and set 0 holds slab s + 1, in flight.
+  int s = 0;
+  for (; s + 2 < nslab; s += 2) {
+    step(0, (s + 1) * SBK, ra0, rb0, (s + 2) * SBK, ra1, rb1);
+    step(1, (s + 2) * SBK, ra1, rb1, (s + 3) * SBK, ra0, rb0);
+  }
+  if (s + 2 == nslab) {
+    step(0, (s + 1) * SBK, ra0, rb0, (s + 2) * SBK, ra1, rb1);
+    multiply_only(1);
+  } else {
+    multiply_only(0);
+  }
+  __syncthreads();
+  tile_epilogue<EPI>(acc, g, e, row0, col0, unscale, smem);
 }
 
 constexpr int64_t kMaxTilesPerLaunchFwd = (1 << 24) - 1;
@@ -277,6 +502,24 @@ static hipError_t launch_one(const GemmOperands &g, const typename EpiArgs<EPI>:
   if (nwg <= 0) return hipSuccess;
   if (nwg > kMaxTilesPerLaunchFwd) return hipErrorInvalidValue;
   hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(NTHREADS), smem_bytes<BK>(), st, g, e);
+  return hipGetLastError();
+}
+
+template <int EPI>
+static hipError_t launch_split(const GemmOperands &g, const typename EpiArgs<EPI>::type &e, hipStream_t st) {
+  auto kern = gemm_split_kernel<EPI>;
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)smem_bytes<SBK>());
+    if (rc != hipSuccess) return rc;
+    attr_set = true;
+  }
+  const int64_t nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
+  const int64_t nwg = nrt * nct;
+  if (nwg <= 0) return hipSuccess;
+  if (nwg > kMaxTilesPerLaunchFwd) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(NTHREADS), smem_bytes<SBK>(), st, g, e);
   return hipGetLastError();
 }
 
@@ -320,7 +563,8 @@ static hipError_t launch_any(const GemmOperands &g, const typename EpiArgs<EPI>:
     typename EpiArgs<EPI>::type eb = e;
     shift_rows(eb, r0);
     hipError_t rc;
-    if (al) rc = bk32 ? launch_one<32, EPI, true>(gb, eb, st) : launch_one<16, EPI, true>(gb, eb, st);
+    if (al && g.K >= SBK && g.a_absmax && g.b_absmax) rc = launch_split<EPI>(gb, eb, st);
+    else if (al) rc = bk32 ? launch_one<32, EPI, true>(gb, eb, st) : launch_one<16, EPI, true>(gb, eb, st);
     else rc = bk32 ? launch_one<32, EPI, false>(gb, eb, st) : launch_one<16, EPI, false>(gb, eb, st);
     if (rc != hipSuccess) return rc;
   }
@@ -328,8 +572,8 @@ static hipError_t launch_any(const GemmOperands &g, const typename EpiArgs<EPI>:
 }
 
 hipError_t gemm_store(const GemmOperands &g, float *C, int64_t ldc, int32_t Nstore, float alpha, float beta,
-                      hipStream_t st) {
-  StoreArgs e{C, ldc, Nstore < g.N ? g.N : Nstore, alpha, beta};
+                      hipStream_t st, unsigned int *c_absmax) {
+  StoreArgs e{C, ldc, Nstore < g.N ? g.N : Nstore, alpha, beta, c_absmax};
   return launch_any<EPI_STORE>(g, e, st);
 }
 

@@ -24,6 +24,9 @@
 namespace skm {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 namespace {
 constexpr int BM = 128, BN = 128, BK = 32;
@@ -120,15 +123,31 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       prev_reg = ok ? g.prev[g.row_base + gr] : -1;
     }
   };
+  // Split-fp16 staging (see skm_internal.h): a scaled value v goes to LDS as hi = fp16(v) and lo = fp16(v - hi);
+  // a tile row of a slab holds its 32 hi values (64 bytes), its 32 lo values, and 16 bytes of padding.
+  const unsigned int amax = *g.a_absmax, bmax = *g.b_absmax;
+  const float scale_a = split_scale(amax), scale_b = split_scale(bmax);
+  const float m2 = -2.f * split_unscale(amax) * split_unscale(bmax);   // accumulator -> -2 x.y
+  auto split_store = [&](float *dst_row, const float4 &v, float scale) {
+    const f32x2 p0 = {v.x * scale, v.y * scale}, p1 = {v.z * scale, v.w * scale};
+    const f16x2 h0 = __builtin_convertvector(p0, f16x2), h1 = __builtin_convertvector(p1, f16x2);
+    const f16x2 l0 = __builtin_convertvector(p0 - __builtin_convertvector(h0, f32x2), f16x2);
+    const f16x2 l1 = __builtin_convertvector(p1 - __builtin_convertvector(h1, f32x2), f16x2);
+    uint2 hi, lo;
+    hi.x = __builtin_bit_cast(unsigned int, h0); hi.y = __builtin_bit_cast(unsigned int, h1);
+    lo.x = __builtin_bit_cast(unsigned int, l0); lo.y = __builtin_bit_cast(unsigned int, l1);
+    *reinterpret_cast<uint2 *>(dst_row + 2 * st_kq) = hi;
+    *reinterpret_cast<uint2 *>(dst_row + 16 + 2 * st_kq) = lo;
+  };
   auto sstore = [&](int buf) {
 #pragma unroll
     for (int s = 0; s < A_F4; ++s) {
-      *reinterpret_cast<float4 *>(As + (buf * BM + st_row + ROWS_PASS * s) * LS + 4 * st_kq) = ra[s];
+      split_store(As + (buf * BM + st_row + ROWS_PASS * s) * LS, ra[s], scale_a);
       na[s] = fmaf(ra[s].x, ra[s].x, fmaf(ra[s].y, ra[s].y, fmaf(ra[s].z, ra[s].z, fmaf(ra[s].w, ra[s].w, na[s]))));
     }
 #pragma unroll
     for (int s = 0; s < B_F4; ++s) {
-      *reinterpret_cast<float4 *>(Bs + (buf * BN + st_row + ROWS_PASS * s) * LS + 4 * st_kq) = rb[s];
+      split_store(Bs + (buf * BN + st_row + ROWS_PASS * s) * LS, rb[s], scale_b);
       nbv[s] = fmaf(rb[s].x, rb[s].x, fmaf(rb[s].y, rb[s].y, fmaf(rb[s].z, rb[s].z, fmaf(rb[s].w, rb[s].w, nbv[s]))));
     }
   };
@@ -222,29 +241,33 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if (s + 1 < nslab) gload(row0, col0, koff + (s + 1) * BK);
       const float *Ab = As + (buf * BM + wm * WTM + r32) * LS + kh * 4;
       const float *Bb = Bs + (buf * BN + wn * WTN + r32) * LS + kh * 4;
+      // two steps of 16 dims; lane half kh supplies the 8 consecutive dims 8*kh .. 8*kh+7 of the step;
+      // x.y ~ hi.hi' + hi.lo' + lo.hi' on the fp16 matrix cores, fp32 accumulation
 #pragma unroll
-      for (int kg = 0; kg < BK / 8; ++kg) {
-        float4 af[TM], bf[TN];
+      for (int stp = 0; stp < 2; ++stp) {
+        f16x8 ah[TM], al[TM], bh[TN], bl[TN];
 #pragma unroll
-        for (int a = 0; a < TM; ++a) af[a] = *reinterpret_cast<const float4 *>(Ab + a * 32 * LS + kg * 8);
+        for (int a = 0; a < TM; ++a) {
+          ah[a] = *reinterpret_cast<const f16x8 *>(Ab + a * 32 * LS + stp * 8);
+          al[a] = *reinterpret_cast<const f16x8 *>(Ab + a * 32 * LS + 16 + stp * 8);
+        }
 #pragma unroll
-        for (int b = 0; b < TN; ++b) bf[b] = *reinterpret_cast<const float4 *>(Bb + b * 32 * LS + kg * 8);
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].x, bf[b].x, acc[a][b], 0, 0, 0);
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].y, bf[b].y, acc[a][b], 0, 0, 0);
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].z, bf[b].z, acc[a][b], 0, 0, 0);
+        for (int b = 0; b < TN; ++b) {
+          bh[b] = *reinterpret_cast<const f16x8 *>(Bb + b * 32 * LS + stp * 8);
+          bl[b] = *reinterpret_cast<const f16x8 *>(Bb + b * 32 * LS + 16 + stp * 8);
+        }
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
-          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a].w, bf[b].w, acc[a][b], 0, 0, 0);
+          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[a], bh[b], acc[a][b], 0, 0, 0);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[a], bl[b], acc[a][b], 0, 0, 0);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[a], bh[b], acc[a][b], 0, 0, 0);
       }
 
       const int tdone = koff + BK * (s + 1);   // dimensions multiplied so far
@@ -268,7 +291,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
               const float th = s_thr[row_of(a, v)];
 #pragma unroll
               for (int b = 0; b < TN; ++b) {
-                const bool keep = (yn[b] - 2.f * acc[a][b][v]) <= th;
+                const bool keep = fmaf(m2, acc[a][b][v], yn[b]) <= th;
                 bits &= ~((unsigned long long)(!keep) << ((a * TN + b) * 16 + v));
               }
             }
@@ -327,7 +350,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
           for (int b = 0; b < TN; ++b) {
             if ((bits >> ((a * TN + b) * 16 + v)) & 1ull) {
-              float dist = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
+              float dist = s_xn[rl] + fmaf(m2, acc[a][b][v], yn[b]);
               dist = dist > 0.f ? dist : 0.f;
               if (dist < s_tau[rl]) {
                 const unsigned long long kb = pack_key(dist, gc[b]);
@@ -384,7 +407,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                   Pair pr;
                   pr.i = (int32_t)(g.row_base + row0 + rl);
                   pr.j = (int32_t)((uint32_t)gc[b] | ((uint32_t)fin_m << 24));
-                  const float p = s_xn[rl] + (yn[b] - 2.f * acc[a][b][v]);
+                  const float p = s_xn[rl] + fmaf(m2, acc[a][b][v], yn[b]);
                   pr.p = p > 0.f ? p : 0.f;
                   pr.tau = s_tau[rl];
                   g.pairs[pos] = pr;

@@ -45,11 +45,35 @@ struct GemmOperands {
   int32_t N;
   int32_t K;
   int32_t panel_cols = 16;  // column tiles per panel of the tile walk (set by the launcher)
+  // Device words holding the bit pattern of an upper bound of |A| and of |B| (see launch_absmax).  With both
+  // set (and 16-byte aligned operands, K >= 32) the product runs in the split-fp16 form described below.
+  const unsigned int *a_absmax = nullptr;
+  const unsigned int *b_absmax = nullptr;
 };
 
+// Split-fp16 arithmetic.  A matrix whose largest magnitude is m is scaled by the power of two that brings m
+// into [2^14, 2^15); a scaled value v is staged as hi = fp16(v) and lo = fp16(v - hi), which keeps 22
+// significant bits of v (and an absolute error below 2^-40 m for values too small for that), and a product
+// is taken as hi*hi' + hi*lo' + lo*hi' on v_mfma_f32_32x32x16_f16 with fp32 accumulation.  The dropped
+// lo*lo' term is 2^-22 of the product.  Scaling by powers of two is exact, so the result is that of an fp32
+// GEMM whose inputs were rounded to 22 bits.
+__device__ inline float split_scale(unsigned int absmax_bits) {   // 2^(14 - floor(log2 m)), clamped to normal floats
+  int e = 268 - (int)(absmax_bits >> 23);
+  e = e < 1 ? 1 : (e > 253 ? 253 : e);
+  return __builtin_bit_cast(float, (unsigned int)e << 23);
+}
+__device__ inline float split_unscale(unsigned int absmax_bits) {  // exactly 1 / split_scale
+  int e = 268 - (int)(absmax_bits >> 23);
+  e = e < 1 ? 1 : (e > 253 ? 253 : e);
+  return __builtin_bit_cast(float, (unsigned int)(254 - e) << 23);
+}
+// *out = max(*out, bit pattern of max |A[i][j]|) over rows x cols; *out must hold 0 (or an earlier bound) before.
+hipError_t launch_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsigned int *out, hipStream_t st);
+
 // C[i][j] = alpha * s(i,j) + beta * C[i][j] for j < N; columns N <= j < Nstore are written as 0.
+// If c_absmax is given, max |C| is folded into *c_absmax (as launch_absmax does).
 hipError_t gemm_store(const GemmOperands &g, float *C, int64_t ldc, int32_t Nstore, float alpha, float beta,
-                      hipStream_t st);
+                      hipStream_t st, unsigned int *c_absmax = nullptr);
 
 // best[i] = min(best[i], pack_key(ynorm[j] - 2 s(i,j), j)) over all j: the row argmin of the squared
 // distance up to the per-row constant ||x_i||^2 (Algorithm 1, iteration 1).
@@ -77,6 +101,7 @@ struct ProgArgs {
   const float *B;          // rotated centroids, k x ds
   int64_t ldb;
   int32_t N;
+  const unsigned int *a_absmax, *b_absmax;   // bounds of |A| and |B| for the split-fp16 form (see GemmOperands)
   int32_t ds, d, dprime, nb;
   const float *ratio;      // [nb + 1] theta ratio at checkpoint m (t_m = min(d, d' + 64 m)); device array
   const float *tau;        // [n]

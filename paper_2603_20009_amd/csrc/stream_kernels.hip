@@ -152,6 +152,39 @@ hipError_t launch_fill_u32(unsigned int *p, int64_t n, unsigned int v, hipStream
   return launch_fill<unsigned int>(p, n, v, st);
 }
 
+// ------------------------------------------------------------------ largest magnitude of a matrix
+// Non-negative floats order like their bit patterns, so the maximum is kept with an unsigned atomicMax.
+template <bool VEC4>
+__global__ void __launch_bounds__(256) absmax_kernel(const float *A, int64_t lda, int64_t rows, int32_t cols,
+                                                     unsigned int *out) {
+  const int64_t per_row = VEC4 ? cols / 4 : cols;
+  const int64_t total = rows * per_row;
+  float m = 0.f;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = e / per_row;
+    const int64_t cidx = e - r * per_row;
+    if (VEC4) {
+      const float4 v = *reinterpret_cast<const float4 *>(A + r * lda + 4 * cidx);
+      m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    } else {
+      m = fmaxf(m, fabsf(A[r * lda + cidx]));
+    }
+  }
+#pragma unroll
+  for (int w = 1; w < 64; w <<= 1) m = fmaxf(m, __shfl_xor(m, w, 64));
+  if ((threadIdx.x & 63) == 0 && m > 0.f) atomicMax(out, __builtin_bit_cast(unsigned int, m));
+}
+
+hipError_t launch_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsigned int *out, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  const bool vec = (reinterpret_cast<uintptr_t>(A) & 15u) == 0 && lda % 4 == 0 && cols % 4 == 0;
+  const int64_t work = rows * (int64_t)(vec ? cols / 4 : cols);
+  const unsigned blocks = (unsigned)std::min<int64_t>((work + 255) / 256, 256 * 16);
+  if (vec) hipLaunchKernelGGL(absmax_kernel<true>, dim3(blocks), dim3(256), 0, st, A, lda, rows, cols, out);
+  else hipLaunchKernelGGL(absmax_kernel<false>, dim3(blocks), dim3(256), 0, st, A, lda, rows, cols, out);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ argmin unpack
 constexpr int FIN_THREADS = 256;
 constexpr int FIN_PER_BLOCK = 1024;

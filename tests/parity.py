@@ -9,9 +9,16 @@ def sqdist(Xr, Y, idx):
     return np.einsum("ij,ij->i", diff, diff)
 
 
-def check_assignment(a_gpu, a_ref, Xr, Y, min_agree=0.999, gap=1e-4):
+def check_assignment(a_gpu, a_ref, Xr, Y, min_agree=0.999, gap=1e-4, own=None):
     """>= 99.9 % of the assignments agree, and wherever they differ the two centroids are a
-    near-tie for that point: their fp64 distances differ by at most 1e-4 relative."""
+    near-tie for that point: their fp64 distances differ by at most 1e-4 relative.
+
+    For a fit of several iterations pass own = (X, Y_gpu), the library's input points and final centroids in
+    one space.  A near-tie that falls the other way in some iteration is allowed, but it moves a point between
+    two clusters, so the later centroids of the two runs differ slightly and a few points near a boundary may
+    end on different sides without being near-ties under the reference centroids.  Such a point passes if the
+    library's label is the nearest of the library's own centroids (to the same 1e-4): both runs are then
+    valid Lloyd trajectories that split at a tie."""
     a_gpu = np.asarray(a_gpu)
     a_ref = np.asarray(a_ref)
     assert a_gpu.shape == a_ref.shape
@@ -23,7 +30,16 @@ def check_assignment(a_gpu, a_ref, Xr, Y, min_agree=0.999, gap=1e-4):
         dg = sqdist(Xd, Y, a_gpu[diff])
         dr = sqdist(Xd, Y, a_ref[diff])
         rel = np.abs(dg - dr) / np.maximum(np.minimum(dg, dr), 1e-300)
-        assert rel.max() <= gap, f"disagreement that is no near-tie: rel gap {rel.max():.3e} at point {diff[rel.argmax()]}"
+        bad = rel > gap
+        if own is not None and bad.any():
+            Xo = np.asarray(own[0], dtype=np.float64)[diff[bad]]
+            Yo = np.asarray(own[1], dtype=np.float64)
+            d_all = (Xo * Xo).sum(1)[:, None] - 2.0 * Xo @ Yo.T + (Yo * Yo).sum(1)[None, :]
+            d_lab = sqdist(Xo, Yo, a_gpu[diff[bad]])
+            valid = d_lab <= d_all.min(1) * (1.0 + gap) + 1e-12
+            bad[np.nonzero(bad)[0][valid]] = False
+        assert not bad.any(), (f"disagreement that is no near-tie: rel gap {rel[bad].max():.3e} "
+                               f"at point {diff[bad][rel[bad].argmax()]}")
     return agree
 
 
@@ -31,3 +47,20 @@ def rel_l2(a, b):
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def check_centroids(Yg, Yr, a_gpu, a_ref, tol=1e-3, min_clean=0.9):
+    """Centroids agree to `tol` (relative L2).  If the two runs split at a near-tie (see check_assignment), the
+    clusters that exchanged points have different members and therefore different means; the bound is then
+    asserted over the clusters whose member sets are identical, which must be at least `min_clean` of all.
+    Returns the indices of those clusters."""
+    a_gpu = np.asarray(a_gpu)
+    a_ref = np.asarray(a_ref)
+    if (a_gpu == a_ref).all():
+        assert rel_l2(Yg, Yr) < tol
+        return np.arange(len(Yr))
+    touched = np.union1d(a_gpu[a_gpu != a_ref], a_ref[a_gpu != a_ref])
+    clean = np.setdiff1d(np.arange(len(Yr)), touched)
+    assert len(clean) >= min_clean * len(Yr), f"only {len(clean)} of {len(Yr)} clusters have the same members"
+    assert rel_l2(np.asarray(Yg)[clean], np.asarray(Yr)[clean]) < tol
+    return clean
