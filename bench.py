@@ -22,7 +22,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+# The GEMM-shaped kernels multiply fp32 operands as scaled (hi, lo) fp16 pairs: three fp16 matrix instructions per
+# product (hi*hi' + hi*lo' + lo*hi'), fp32 accumulation.  Their roofline is the dense fp16 matrix peak of MI355X
+# divided by those three: the rate at which fp32-class multiply-adds can leave the matrix cores.
+PEAK_FP16_MFMA_TFLOPS = 2500.0
+SPLIT_PRODUCTS = 3
+PEAK_SPLIT_TFLOPS = PEAK_FP16_MFMA_TFLOPS / SPLIT_PRODUCTS
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 
 
@@ -134,7 +139,7 @@ def main():
     }
     for s in stages.values():
         if s["achieved"] is not None:
-            s["frac"] = s["achieved"] / (PEAK_FP32_MFMA_TFLOPS if s["bound"] == "mfma" else PEAK_HBM_GBS)
+            s["frac"] = s["achieved"] / (PEAK_SPLIT_TFLOPS if s["bound"] == "mfma" else PEAK_HBM_GBS)
     # dominant kernel of the fit by total time
     totals = {"rotation_gemm": ms_rot, "iter1_gemm_argmin": ms_it1_gemm, "progressive_gemm": total_prog}
     dom = max(totals, key=totals.get)
@@ -144,26 +149,28 @@ def main():
             traffic = json.load(open(args.traffic_json)).get(args.config, {}).get(dom)
         except Exception:
             traffic = None
-    kname = {"rotation_gemm": "skm::gemm_kernel<32,store>", "iter1_gemm_argmin": "skm::gemm_kernel<32,argmin>",
-             "progressive_gemm": "skm::progressive_kernel<32>"}[dom]
-    roofline = dict(bound="mfma", kernel=kname, achieved=stages[dom]["achieved"], peak=PEAK_FP32_MFMA_TFLOPS,
+    kname = {"rotation_gemm": "skm::gemm_split_kernel<store>", "iter1_gemm_argmin": "skm::gemm_split_kernel<argmin>",
+             "progressive_gemm": "skm::progressive_kernel"}[dom]
+    roofline = dict(bound="mfma", kernel=kname, achieved=stages[dom]["achieved"], peak=PEAK_SPLIT_TFLOPS,
                     unit="TFLOP/s", frac=stages[dom]["frac"], traffic=traffic,
                     ms_per_step=stages[dom]["ms"], total_ms_per_fit=totals[dom],
                     flop_per_step={"rotation_gemm": flops_rot, "iter1_gemm_argmin": flops_it1,
                                    "progressive_gemm": flop_alg}[dom],
+                    mfma_dtype="f16", mfma_flop_per_algorithmic_flop=SPLIT_PRODUCTS,
                     note="achieved = algorithmic flop (first-test GEMM 2nkd' + 128 per alive pair-block done densely) per "
-                         "pruned step / device time of the kernel's launches in that step (HIP events); 'executed' in "
-                         "stages counts every dimension the tiles multiplied")
+                         "pruned step / device time of the kernel's launches in that step (HIP events); peak = dense "
+                         "fp16 MFMA peak (2500 TFLOP/s) / 3, because every fp32-class product costs three fp16 matrix "
+                         "instructions; 'executed' in stages counts every dimension the tiles multiplied")
     if dom == "progressive_gemm":
         roofline["executed"] = stages[dom]["executed"]
-        roofline["executed_frac"] = stages[dom]["executed"] / PEAK_FP32_MFMA_TFLOPS
+        roofline["executed_frac"] = stages[dom]["executed"] / PEAK_SPLIT_TFLOPS
 
     out = {
         "metric": "point*centroid*dim per second over one SuperKMeans fit (seconds per k-means iteration alongside)",
         "value": value, "unit": "point*centroid*dim/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32 (operands as split fp16 pairs on fp16 MFMA, fp32 accumulation)", "data": "synthetic",
         "config": {"workload": f"{args.config}: {n}x{d} fp32 unit-norm mixture rows ({cfg['components']} components), "
                                f"k={k}, {iters} iterations + final assignment pass", "n": n, "d": d, "k": k,
                    "iters": iters, "iters_run": iters_run},
