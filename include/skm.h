@@ -139,6 +139,41 @@ int skm_fit_ex(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, u
                const skm_params *params, float *centroids_out, int32_t *assign_out, float *dist_out);
 
 /*
+ * skm_fit_hierarchical -- Hierarchical SuperKMeans (Section 6).
+ *   MESO: Algorithm 1 with skm_hier_meso_count(k) = round(sqrt(k)) clusters on
+ *   all points, meso_iters iterations (3 in the paper) and the final
+ *   assignment pass.  FINE: Algorithm 1 inside every meso-cluster (its points
+ *   in ascending row order) with skm_hier_alloc's share of the k clusters,
+ *   fine_iters iterations (5 in the paper), seed `seed + 1 + i` for
+ *   meso-cluster i.  The k fine centroids, in meso order, are the result;
+ *   every point is then assigned to them by the two-phase step without a
+ *   previous assignment.  X is rotated once; both phases run in the rotated
+ *   space.  Not combined with ETR, sample_frac, init_idx or final_assign = 0
+ *   (SKM_EINVAL).
+ *   centroids_out        device k x d fp32, original space
+ *   assign_out, dist_out device n int32 / n fp32 or NULL: the final assignment
+ *   meso_sizes_out_host  HOST int64[round(sqrt(k))] or NULL: points per meso-cluster
+ *   fine_counts_out_host HOST int32[round(sqrt(k))] or NULL: fine clusters per meso-cluster
+ *   params->trace, if set, receives the rows of the meso phase, then the row
+ *   of the final assignment; ms_init = rotation + meso phase, ms_etr_gt = the
+ *   fine phase, ms_total = everything.
+ */
+int skm_fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t meso_iters, int32_t fine_iters,
+                         uint64_t seed, const skm_params *params, float *centroids_out, int32_t *assign_out,
+                         float *dist_out, int64_t *meso_sizes_out_host, int32_t *fine_counts_out_host);
+
+/* Host rules of the hierarchical fit (Section 6).  The paper gives sqrt(k)
+ * meso-clusters and sqrt(n_i) fine clusters in meso-cluster i; so that the
+ * total is exactly k, the k clusters are shared out in proportion to
+ * sqrt(n_i): one to every non-empty meso-cluster, then the floors of the
+ * quotas (k - non-empty) * sqrt(n_i) / sum_j sqrt(n_j), then the rest one by
+ * one by largest fractional part (lowest index on ties); never more clusters
+ * than points.  sizes_host / counts_out_host are HOST arrays of km entries;
+ * SKM_EINVAL unless 1 <= km <= k <= sum of sizes. */
+int32_t skm_hier_meso_count(int32_t k);
+int skm_hier_alloc(const int64_t *sizes_host, int32_t km, int32_t k, int32_t *counts_out_host);
+
+/*
  * skm_assign -- one two-phase assignment step (Section 3.2, "2nd -> n
  * iteration"; Section 3.3, final assignment) of X against given centroids,
  * both in the original space; the rotation is generated from seed 0 unless

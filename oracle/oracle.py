@@ -83,6 +83,10 @@ def lib():
         _lib.orc_dprime_init.argtypes = [C.c_int32, C.c_double]
         _lib.orc_dprime_adjust.restype = C.c_int32
         _lib.orc_dprime_adjust.argtypes = [C.c_int32, C.c_int32] + [C.c_double] * 4
+        _lib.orc_hier_meso_count.restype = C.c_int32
+        _lib.orc_hier_meso_count.argtypes = [C.c_int32]
+        _lib.orc_hier_alloc.restype = None
+        _lib.orc_hier_alloc.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         _lib.orc_nprobe.restype = C.c_int32
         _lib.orc_nprobe.argtypes = [C.c_int32, C.c_double]
         _lib.orc_recall.restype = C.c_double
@@ -358,3 +362,49 @@ def fit_sampled(X, k: int, iters: int, seed: int, sample_frac: float, params: Fi
     inner.trace.append(dict(objective=float(fin.dist.sum()), prune_frac=fin.pruned_first / (n * max(k - 1, 1)),
                             recall=-1.0, pruned_first=fin.pruned_first, nempty=0, dprime=dp, enter=fin.enter))
     return inner, idx
+
+
+def hier_meso_count(k: int) -> int:
+    return int(lib().orc_hier_meso_count(k))
+
+
+def hier_alloc(sizes, k: int) -> np.ndarray:
+    """Fine cluster count of every meso-cluster (Section 6; shares of k in proportion to sqrt(n_i))."""
+    sizes = _i64(sizes)
+    counts = np.zeros(len(sizes), dtype=np.int32)
+    lib().orc_hier_alloc(_p(sizes, C.c_int64), len(sizes), k, _p(counts, C.c_int32))
+    return counts
+
+
+def fit_hierarchical(X, k: int, seed: int, meso_iters: int = 3, fine_iters: int = 5, params: FitParams | None = None,
+                     R=None):
+    """Hierarchical SuperKMeans (Section 6), composed from the steps above.  MESO: Algorithm 1 with sqrt(k) clusters
+    on all (rotated) points, `meso_iters` iterations and the final assignment pass.  FINE: inside meso-cluster i
+    (its points in ascending row order), Algorithm 1 with hier_alloc's count, `fine_iters` iterations, seed
+    `seed + 1 + i`, no final pass.  The k fine centroids, in meso order, are the result; every point is then assigned
+    to them by the two-phase step without a previous assignment.
+    Returns dict(centroids, centroids_rot, assign, dist, meso_assign, meso_sizes, fine_counts, meso)."""
+    import dataclasses
+    p = params or FitParams()
+    X = _f32(X)
+    n, d = X.shape
+    km = hier_meso_count(k)
+    meso = fit(X, km, meso_iters, seed, dataclasses.replace(p, final_assign=True), R=R)
+    Xr = rotate(X, R) if R is not None else X.astype(np.float64)
+    sizes = np.bincount(meso.assign, minlength=km).astype(np.int64)
+    counts = hier_alloc(sizes, k)
+    Y = np.zeros((k, d), dtype=np.float64)
+    off = 0
+    for i in range(km):
+        if counts[i] == 0:
+            continue
+        rows = np.nonzero(meso.assign == i)[0]
+        sub = fit(Xr[rows], int(counts[i]), fine_iters, (seed + 1 + i) & 0xFFFFFFFFFFFFFFFF,
+                  dataclasses.replace(p, final_assign=False), R=None)
+        Y[off:off + counts[i]] = sub.centroids_rot
+        off += int(counts[i])
+    assert off == k
+    fin = assign_pruned(Xr, Y, None, dprime_init(d, p.dprime_frac), p.eps0, p.tau_group)
+    return dict(centroids=unrotate(Y, R) if R is not None else Y.copy(), centroids_rot=Y, assign=fin.assign, dist=fin.dist,
+                meso_assign=meso.assign, meso_sizes=sizes, fine_counts=counts, meso=meso,
+                objective=float(fin.dist.sum()), prune_frac=fin.pruned_first / (n * max(k - 1, 1)))

@@ -465,6 +465,78 @@ int32_t orc_nprobe(int32_t k, double probe_frac) {
 }
 
 /* ------------------------------------------------------------------ */
+/* Hierarchical SuperKMeans (Section 6): how many clusters each phase   */
+/* makes.  The meso phase makes sqrt(k) clusters (rounded to nearest).  */
+/* The fine phase runs k-means inside meso-cluster i with a number of   */
+/* clusters that follows sqrt(n_i); so that the total is exactly k, the */
+/* k clusters are shared out in proportion to sqrt(n_i): every          */
+/* non-empty meso-cluster gets one, the other r = k - (non-empty) are   */
+/* split by quota q_i = r sqrt(n_i) / sum_j sqrt(n_j): floor(q_i) each, */
+/* the rest one by one in the order of the largest fractional part      */
+/* (lowest index first on ties).  No meso-cluster gets more clusters    */
+/* than it has points; what it cannot take goes on down the same order. */
+/* ------------------------------------------------------------------ */
+int32_t orc_hier_meso_count(int32_t k) {
+  int32_t km = (int32_t)floor(sqrt((double)k) + 0.5);
+  if (km < 1) km = 1;
+  if (km > k) km = k;
+  return km;
+}
+
+void orc_hier_alloc(const int64_t *sizes, int32_t km, int32_t k,
+                    int32_t *counts) {
+  double *frac = (double *)malloc(sizeof(double) * (size_t)km);
+  int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)km);
+  double W = 0.0;
+  int64_t given = 0, r, left;
+  int32_t i, a, b;
+  for (i = 0; i < km; i++) {
+    counts[i] = sizes[i] > 0 ? 1 : 0;
+    given += counts[i];
+    W += sqrt((double)sizes[i]);
+  }
+  r = (int64_t)k - given;
+  if (r < 0) r = 0;
+  for (i = 0; i < km; i++) {
+    double q = W > 0.0 ? (double)r * sqrt((double)sizes[i]) / W : 0.0;
+    double fl = floor(q);
+    int64_t room = sizes[i] - counts[i];
+    int64_t g = (int64_t)fl;
+    if (g > room) g = room;
+    counts[i] += (int32_t)g;
+    given += g;
+    frac[i] = q - fl;
+    order[i] = i;
+  }
+  /* order by fractional part, largest first; equal parts keep index order
+   * (insertion sort: km is small) */
+  for (a = 1; a < km; a++) {
+    int32_t v = order[a];
+    b = a - 1;
+    while (b >= 0 && frac[order[b]] < frac[v]) {
+      order[b + 1] = order[b];
+      b--;
+    }
+    order[b + 1] = v;
+  }
+  left = (int64_t)k - given;
+  while (left > 0) {
+    int progress = 0;
+    for (a = 0; a < km && left > 0; a++) {
+      i = order[a];
+      if ((int64_t)counts[i] < sizes[i]) {
+        counts[i]++;
+        left--;
+        progress = 1;
+      }
+    }
+    if (!progress) break;
+  }
+  free(frac);
+  free(order);
+}
+
+/* ------------------------------------------------------------------ */
 /* The whole fit, Algorithm 1 top to bottom.                            */
 /* ------------------------------------------------------------------ */
 typedef struct orc_params {

@@ -33,15 +33,47 @@ int fail_hip(hipError_t e, const char *where) {
   } while (0)
 
 // device allocations released when the call ends, whichever way it ends
+// A preallocated slab that Pools of nested calls carve their buffers from (the hierarchical fit runs hundreds of small
+// fits; a hipMalloc per buffer would dominate them).  A Pool constructed while an arena is current takes memory from it
+// and gives it back, stack-like, when it is destroyed; what does not fit falls back to hipMalloc.
+struct Arena {
+  char *base = nullptr;
+  size_t cap = 0, off = 0;
+  ~Arena() {
+    if (base) (void)hipFree(base);
+  }
+  hipError_t init(size_t bytes) {
+    cap = bytes;
+    return hipMalloc(reinterpret_cast<void **>(&base), bytes);
+  }
+};
+thread_local Arena *tl_arena = nullptr;
+struct ArenaScope {
+  Arena *saved;
+  explicit ArenaScope(Arena *a) : saved(tl_arena) { tl_arena = a; }
+  ~ArenaScope() { tl_arena = saved; }
+};
+
 struct Pool {
   std::vector<void *> ptrs;
+  Arena *arena = tl_arena;
+  size_t mark = tl_arena ? tl_arena->off : 0;
   ~Pool() {
     for (void *p : ptrs) (void)hipFree(p);
+    if (arena) arena->off = mark;
   }
   template <typename T>
   hipError_t get(T **out, size_t count) {
     void *p = nullptr;
     size_t bytes = std::max<size_t>(count, 1) * sizeof(T);
+    if (arena) {
+      const size_t at = (arena->off + 255) & ~(size_t)255;
+      if (at + bytes <= arena->cap) {
+        arena->off = at + bytes;
+        *out = reinterpret_cast<T *>(arena->base + at);
+        return hipSuccess;
+      }
+    }
     hipError_t e = hipMalloc(&p, bytes);
     if (e != hipSuccess) {
       *out = nullptr;
@@ -149,6 +181,49 @@ int32_t dprime_adjust(int32_t d, int32_t dp, double f, double lo, double hi, dou
   if (f > hi) return std::min(snap16((double)dp - step * (double)dp, d), snap16((double)dp - 16.0, d));
   if (f < lo) return std::max(snap16((double)dp + step * (double)dp, d), snap16((double)dp + 16.0, d));
   return dp;
+}
+// Section 6: sqrt(k) meso-clusters; the k fine clusters are shared out in proportion to sqrt(n_i), one to every
+// non-empty meso-cluster first, floors of the quotas next, the rest by largest fractional part (lowest index on ties),
+// never more clusters than points.
+int32_t hier_meso_count(int32_t k) {
+  const int32_t km = (int32_t)std::floor(std::sqrt((double)k) + 0.5);
+  return std::min(std::max(km, 1), k);
+}
+void hier_alloc(const int64_t *sizes, int32_t km, int32_t k, int32_t *counts) {
+  std::vector<double> root((size_t)km), frac((size_t)km);
+  double W = 0.0;
+  int64_t given = 0;
+  for (int32_t i = 0; i < km; ++i) {
+    root[(size_t)i] = std::sqrt((double)sizes[i]);
+    W += root[(size_t)i];
+    counts[i] = sizes[i] > 0 ? 1 : 0;
+    given += counts[i];
+  }
+  const int64_t r = std::max<int64_t>((int64_t)k - given, 0);
+  for (int32_t i = 0; i < km; ++i) {
+    const double q = W > 0.0 ? (double)r * root[(size_t)i] / W : 0.0;
+    const double whole = std::floor(q);
+    const int64_t g = std::min<int64_t>((int64_t)whole, sizes[i] - counts[i]);
+    counts[i] += (int32_t)g;
+    given += g;
+    frac[(size_t)i] = q - whole;
+  }
+  std::vector<int32_t> order((size_t)km);
+  for (int32_t i = 0; i < km; ++i) order[(size_t)i] = i;
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return frac[(size_t)a] > frac[(size_t)b]; });
+  int64_t left = (int64_t)k - given;
+  while (left > 0) {
+    bool progress = false;
+    for (int32_t a = 0; a < km && left > 0; ++a) {
+      const int32_t i = order[(size_t)a];
+      if ((int64_t)counts[i] < sizes[i]) {
+        ++counts[i];
+        --left;
+        progress = true;
+      }
+    }
+    if (!progress) break;
+  }
 }
 int32_t nprobe_of(int32_t k, double frac) {
   int32_t np = (int32_t)std::floor(frac * (double)k + 0.5);
@@ -499,10 +574,12 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
                 int32_t dprime_in, const skm_params *pp, int32_t *assign_out, float *dist_out);
 int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params &p,
                 float *centroids_out, int32_t *assign_out, float *dist_out);
+int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params *pp,
+             float *centroids_out, int32_t *assign_out, float *dist_out, int32_t *dprime_out);
 
 // dprime_out (optional) receives the d' the next assignment step would use.
 int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params *pp,
-             float *centroids_out, int32_t *assign_out, float *dist_out, int32_t *dprime_out = nullptr) {
+             float *centroids_out, int32_t *assign_out, float *dist_out, int32_t *dprime_out) {
   int rc = check_shape(X, n, d, k);
   if (rc) return rc;
   if (!centroids_out) return fail(SKM_EINVAL, "centroids_out is null");
@@ -916,6 +993,158 @@ int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, 
   return SKM_OK;
 }
 
+// Hierarchical SuperKMeans (Section 6): Algorithm 1 with sqrt(k) clusters on all points (MESO), then Algorithm 1 inside
+// every meso-cluster with its share of the k clusters (FINE), then the two-phase assignment of every point to the k
+// fine centroids.  Everything runs in the rotated space; X is rotated once.
+int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t meso_iters, int32_t fine_iters, uint64_t seed,
+                     const skm_params *pp, float *centroids_out, int32_t *assign_out, float *dist_out,
+                     int64_t *meso_sizes_out, int32_t *fine_counts_out) {
+  int rc = check_shape(X, n, d, k);
+  if (rc) return rc;
+  if (!centroids_out) return fail(SKM_EINVAL, "centroids_out is null");
+  if (meso_iters < 1 || fine_iters < 1) return fail(SKM_EINVAL, "meso_iters and fine_iters must be >= 1");
+  skm_params p;
+  if (pp) p = *pp; else skm_params_default(&p);
+  if (p.etr) return fail(SKM_EINVAL, "the hierarchical fit does not take ETR");
+  if (p.sample_frac > 0.f && p.sample_frac < 1.f) return fail(SKM_EINVAL, "the hierarchical fit does not take sample_frac");
+  if (p.init_idx) return fail(SKM_EINVAL, "the hierarchical fit draws its initial rows from the seed");
+  if (!p.final_assign) return fail(SKM_EINVAL, "the hierarchical fit needs the final assignment pass");
+  skm_trace *tr = p.trace;
+  if (tr && (!tr->row || tr->capacity < 1)) return fail(SKM_EINVAL, "trace without rows");
+  hipStream_t st = (hipStream_t)p.stream;
+  const int32_t ds = round_up(d, 16);
+  Pool pool;
+  Events evs;
+  hipEvent_t e0 = evs.next(), e1 = evs.next(), e_meso = evs.next(), e_fine = evs.next();
+  if (!e0 || !e1 || !e_meso || !e_fine) return fail(SKM_EHIP, "hipEventCreate failed");
+  HIPCHK(hipEventRecord(e0, st));
+  Rot rot;
+  const float *Xr = X;   // dense n x d rows in the rotated space
+  if (p.rotate) {
+    rc = setup_rotation(pool, st, d, ds, p.R, seed, rot);
+    if (rc) return rc;
+    float *Xp = nullptr;
+    HIPCHK(pool.get(&Xp, (size_t)n * ds));
+    rc = rotate_into(X, d, n, d, ds, rot, Xp, st);
+    if (rc) return rc;
+    Xr = Xp;
+    if (ds != d) {
+      float *Xd = nullptr;
+      HIPCHK(pool.get(&Xd, (size_t)n * d));
+      HIPCHK(hipMemcpy2DAsync(Xd, sizeof(float) * (size_t)d, Xp, sizeof(float) * (size_t)ds, sizeof(float) * (size_t)d,
+                              (size_t)n, hipMemcpyDeviceToDevice, st));
+      Xr = Xd;
+    }
+  }
+  skm_params pin = p;
+  pin.rotate = 0;
+  pin.R = nullptr;
+  pin.trace = nullptr;
+
+  // ---- MESO
+  const int32_t km = hier_meso_count(k);
+  float *Ymeso = nullptr, *Yr = nullptr;
+  int32_t *meso_assign = nullptr;
+  HIPCHK(pool.get(&Ymeso, (size_t)km * d));
+  HIPCHK(pool.get(&Yr, (size_t)k * d));
+  HIPCHK(pool.get(&meso_assign, (size_t)n));
+  skm_params pm = pin;
+  skm_trace inner{};
+  if (tr) {
+    inner = *tr;
+    pm.trace = &inner;
+  }
+  rc = fit_impl(Xr, n, d, km, meso_iters, seed, &pm, Ymeso, meso_assign, nullptr, nullptr);
+  if (rc) return rc;
+  HIPCHK(hipEventRecord(e_meso, st));
+  // members of every meso-cluster in ascending row order (counting sort on the host)
+  std::vector<int32_t> ma((size_t)n);
+  HIPCHK(hipMemcpyAsync(ma.data(), meso_assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost, st));
+  HIPCHK(hipStreamSynchronize(st));
+  std::vector<int64_t> sizes((size_t)km, 0), start((size_t)km + 1, 0);
+  for (int64_t i = 0; i < n; ++i) {
+    if (ma[(size_t)i] < 0 || ma[(size_t)i] >= km) return fail(SKM_EINTERNAL, "meso assignment out of range");
+    ++sizes[(size_t)ma[(size_t)i]];
+  }
+  for (int32_t c = 0; c < km; ++c) start[(size_t)c + 1] = start[(size_t)c] + sizes[(size_t)c];
+  std::vector<int64_t> order((size_t)n), cursor(start.begin(), start.end() - 1);
+  for (int64_t i = 0; i < n; ++i) order[(size_t)cursor[(size_t)ma[(size_t)i]]++] = i;
+  std::vector<int32_t> counts((size_t)km, 0);
+  hier_alloc(sizes.data(), km, k, counts.data());
+  if (meso_sizes_out) std::copy(sizes.begin(), sizes.end(), meso_sizes_out);
+  if (fine_counts_out) std::copy(counts.begin(), counts.end(), fine_counts_out);
+
+  // ---- FINE
+  const int64_t nmax = *std::max_element(sizes.begin(), sizes.end());
+  const int32_t kmax = *std::max_element(counts.begin(), counts.end());
+  int64_t *order_dev = nullptr;
+  float *Xs = nullptr;
+  HIPCHK(pool.get(&order_dev, (size_t)n));
+  HIPCHK(pool.get(&Xs, (size_t)std::max<int64_t>(nmax, 1) * d));
+  HIPCHK(hipMemcpyAsync(order_dev, order.data(), sizeof(int64_t) * (size_t)n, hipMemcpyHostToDevice, st));
+  {
+    // workspace of the largest fine fit, generously: per point the padded row copy and the per-point arrays,
+    // per centroid three padded rows, plus the hand-over list of a small problem
+    Arena arena;
+    const size_t want = (size_t)nmax * ((size_t)ds * 4 + 96) + (size_t)kmax * (size_t)ds * 24 + ((size_t)256 << 20);
+    if (arena.init(want) != hipSuccess) {
+      (void)hipGetLastError();
+      arena.base = nullptr;
+      arena.cap = 0;   // every buffer then comes from hipMalloc
+    }
+    ArenaScope scope(arena.base ? &arena : nullptr);
+    skm_params pfine = pin;
+    pfine.final_assign = 0;   // only the centroids of a fine fit are used
+    int32_t koff = 0;
+    for (int32_t c = 0; c < km; ++c) {
+      const int32_t kc = counts[(size_t)c];
+      if (kc == 0) continue;
+      const int64_t nc = sizes[(size_t)c];
+      HIPCHK(launch_gather_rows(Xr, d, d, order_dev + start[(size_t)c], (int32_t)nc, Xs, d, d, st));
+      rc = fit_impl(Xs, nc, d, kc, fine_iters, seed + 1 + (uint64_t)c, &pfine, Yr + (size_t)koff * d, nullptr, nullptr,
+                    nullptr);
+      if (rc) return rc;
+      koff += kc;
+    }
+    if (koff != k) return fail(SKM_EINTERNAL, "fine cluster counts do not add up to k");
+  }
+  HIPCHK(hipEventRecord(e_fine, st));
+
+  // ---- every point against the k fine centroids, no previous assignment
+  skm_params pfin = pin;
+  skm_trace last{};
+  if (tr) {
+    last.capacity = tr->capacity - inner.rows;
+    last.row = tr->row + inner.rows;
+    pfin.trace = last.capacity >= 1 ? &last : nullptr;
+  }
+  int32_t *assign_tmp = assign_out;
+  if (!assign_tmp) HIPCHK(pool.get(&assign_tmp, (size_t)n));
+  rc = assign_impl(Xr, n, d, Yr, k, nullptr, 0, &pfin, assign_tmp, dist_out);
+  if (rc) return rc;
+  if (p.rotate) {
+    float *Yp = nullptr;
+    HIPCHK(pool.get(&Yp, (size_t)k * ds));
+    HIPCHK(launch_pad_copy(Yr, d, k, d, Yp, ds, ds, 0, st));
+    rc = unrotate_into(Yp, ds, k, d, ds, rot, centroids_out, st);
+    if (rc) return rc;
+  } else {
+    HIPCHK(hipMemcpyAsync(centroids_out, Yr, sizeof(float) * (size_t)k * d, hipMemcpyDeviceToDevice, st));
+  }
+  HIPCHK(hipEventRecord(e1, st));
+  HIPCHK(hipStreamSynchronize(st));
+  if (tr) {
+    tr->rows = inner.rows + ((pfin.trace && last.rows > 0) ? 1 : 0);
+    tr->iters_run = inner.iters_run;
+    tr->ms_rotate = 0.f;
+    (void)hipEventElapsedTime(&tr->ms_init, e0, e_meso);      // rotation + the whole meso phase
+    (void)hipEventElapsedTime(&tr->ms_etr_gt, e_meso, e_fine);  // the whole fine phase
+    tr->ms_unrotate = 0.f;
+    (void)hipEventElapsedTime(&tr->ms_total, e0, e1);
+  }
+  return SKM_OK;
+}
+
 }  // namespace
 
 // ==================================================================== C ABI
@@ -948,12 +1177,33 @@ void skm_params_default(skm_params *p) {
 
 int skm_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, float *centroids_out,
             int32_t *assign_out) {
-  return fit_impl(X, n, d, k, iters, seed, nullptr, centroids_out, assign_out, nullptr);
+  return fit_impl(X, n, d, k, iters, seed, nullptr, centroids_out, assign_out, nullptr, nullptr);
 }
 
 int skm_fit_ex(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params *params,
                float *centroids_out, int32_t *assign_out, float *dist_out) {
-  return fit_impl(X, n, d, k, iters, seed, params, centroids_out, assign_out, dist_out);
+  return fit_impl(X, n, d, k, iters, seed, params, centroids_out, assign_out, dist_out, nullptr);
+}
+
+int skm_fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t meso_iters, int32_t fine_iters,
+                         uint64_t seed, const skm_params *params, float *centroids_out, int32_t *assign_out,
+                         float *dist_out, int64_t *meso_sizes_out_host, int32_t *fine_counts_out_host) {
+  return fit_hierarchical(X, n, d, k, meso_iters, fine_iters, seed, params, centroids_out, assign_out, dist_out,
+                          meso_sizes_out_host, fine_counts_out_host);
+}
+
+int32_t skm_hier_meso_count(int32_t k) { return k >= 1 ? hier_meso_count(k) : 0; }
+
+int skm_hier_alloc(const int64_t *sizes_host, int32_t km, int32_t k, int32_t *counts_out_host) {
+  if (!sizes_host || !counts_out_host || km < 1 || k < km) return fail(SKM_EINVAL, "bad arguments");
+  int64_t total = 0;
+  for (int32_t i = 0; i < km; ++i) {
+    if (sizes_host[i] < 0) return fail(SKM_EINVAL, "negative size");
+    total += sizes_host[i];
+  }
+  if (total < k) return fail(SKM_EINVAL, "fewer points than clusters");
+  hier_alloc(sizes_host, km, k, counts_out_host);
+  return SKM_OK;
 }
 
 int skm_assign(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, const int32_t *prev_assign,

@@ -207,6 +207,10 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     unsigned int next_q = 0;
     if (tid == 0) next_q = atomicAdd(ctr, 1u);   // the tile after this one; consumed below
     __syncthreads();
+    // The alive counter of checkpoint 0 may still hold the last total of the previous tile (a tile that ends at an
+    // even checkpoint leaves it behind).  Every thread has read that total before the barrier above, and the first
+    // add of this tile comes after the barrier of its first slab.
+    if (tid == 0) s_cnt[0] = 0u;
 
     f32x16 acc[TM][TN];
 #pragma unroll

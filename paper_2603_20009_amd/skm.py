@@ -56,7 +56,7 @@ class Params(C.Structure):
 EXPORTS = [
     "skm_params_default", "skm_fit", "skm_fit_ex", "skm_assign", "skm_assign_ex", "skm_assign_exact", "skm_update",
     "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_theta_ratio", "skm_dprime_init", "skm_dprime_adjust",
-    "skm_strerror", "skm_last_error", "skm_version",
+    "skm_strerror", "skm_last_error", "skm_version", "skm_fit_hierarchical", "skm_hier_meso_count", "skm_hier_alloc",
 ]
 
 _lib = None
@@ -81,8 +81,12 @@ def lib():
         L.skm_make_rotation.argtypes = [i32, u64, vp, vp]
         L.skm_rotate.argtypes = [vp, i64, i32, vp, i32, vp, vp]
         L.skm_sample_rows.argtypes = [u64, i64, i32, vp]
+        L.skm_fit_hierarchical.argtypes = [vp, i64, i32, i32, i32, i32, u64, C.POINTER(Params), vp, vp, vp, vp, vp]
+        L.skm_hier_meso_count.argtypes = [i32]
+        L.skm_hier_meso_count.restype = i32
+        L.skm_hier_alloc.argtypes = [vp, i32, i32, vp]
         for f in ("skm_fit", "skm_fit_ex", "skm_assign", "skm_assign_ex", "skm_assign_exact", "skm_update",
-                  "skm_make_rotation", "skm_rotate", "skm_sample_rows"):
+                  "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_fit_hierarchical", "skm_hier_alloc"):
             getattr(L, f).restype = C.c_int
         L.skm_theta_ratio.argtypes = [i32, i32, f32]
         L.skm_theta_ratio.restype = f32
@@ -223,6 +227,30 @@ def fit(X: torch.Tensor, k: int, iters: int, seed: int, opts: FitOptions | None 
     return FitResult(cent, assign, dist, int(tr.iters_run), rows, timing)
 
 
+def fit_hierarchical(X: torch.Tensor, k: int, seed: int, meso_iters: int = 3, fine_iters: int = 5,
+                     opts: FitOptions | None = None):
+    """skm_fit_hierarchical (Section 6).  Returns (FitResult, meso_sizes, fine_counts); the trace holds the rows of
+    the meso phase and the row of the final assignment."""
+    o = opts or FitOptions()
+    n, d = X.shape
+    km = hier_meso_count(k)
+    keep: list = []
+    tr = _new_trace(meso_iters + 2, keep)
+    p = _params(o, keep, tr)
+    cent = torch.empty((k, d), device=X.device, dtype=torch.float32)
+    assign = torch.empty(n, device=X.device, dtype=torch.int32)
+    dist = torch.empty(n, device=X.device, dtype=torch.float32)
+    sizes = (C.c_int64 * km)()
+    counts = (C.c_int32 * km)()
+    rc = lib().skm_fit_hierarchical(_dev(X, torch.float32, "X"), n, d, k, meso_iters, fine_iters, C.c_uint64(seed),
+                                    C.byref(p), C.c_void_p(cent.data_ptr()), C.c_void_p(assign.data_ptr()),
+                                    C.c_void_p(dist.data_ptr()), C.cast(sizes, C.c_void_p), C.cast(counts, C.c_void_p))
+    _check(rc)
+    rows = [_row_dict(tr.row[i]) for i in range(tr.rows)]
+    timing = dict(ms_meso=tr.ms_init, ms_fine=tr.ms_etr_gt, ms_total=tr.ms_total)
+    return FitResult(cent, assign, dist, int(tr.iters_run), rows, timing), list(sizes), list(counts)
+
+
 def fit_default(X: torch.Tensor, k: int, iters: int, seed: int):
     """skm_fit: default parameters, default stream."""
     n, d = X.shape
@@ -303,6 +331,18 @@ def sample_rows(seed: int, n: int, k: int):
     arr = (C.c_int64 * k)()
     _check(lib().skm_sample_rows(C.c_uint64(seed), n, k, C.cast(arr, C.c_void_p)))
     return list(arr)
+
+
+def hier_meso_count(k: int) -> int:
+    return int(lib().skm_hier_meso_count(k))
+
+
+def hier_alloc(sizes, k: int):
+    km = len(sizes)
+    arr = (C.c_int64 * km)(*[int(v) for v in sizes])
+    out = (C.c_int32 * km)()
+    _check(lib().skm_hier_alloc(C.cast(arr, C.c_void_p), km, k, C.cast(out, C.c_void_p)))
+    return list(out)
 
 
 def theta_ratio(d: int, t: int, eps0: float) -> float:

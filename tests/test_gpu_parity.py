@@ -439,3 +439,50 @@ def test_sampled_fit(skm, orc, dg, n, d, k, frac):
     assert got.trace[0]["changed"] == len(idx)          # the loop ran on the sample only
     with pytest.raises(skm.SkmError):
         skm.fit(cuda(X), k, 2, 9, skm.FitOptions(R=cuda(R), sample_frac=frac, final_assign=False))
+
+
+@pytest.mark.parametrize("n,d,k", [(20_000, 128, 64), (9000, 100, 30)])
+def test_hierarchical_fit(skm, orc, dg, n, d, k):
+    """Section 6: meso phase, shares of k, fine phase per meso-cluster, final assignment, against the oracle's
+    composition of the same steps."""
+    X = dg.mixture(n, d, 80, 21, "linear").numpy()
+    R = orc.random_rotation(d, 21)
+    ref = orc.fit_hierarchical(X, k, 13, 3, 5, orc.FitParams(eps0=EPS0), R=R)
+    got, sizes, counts = skm.fit_hierarchical(cuda(X), k, 13, 3, 5, skm.FitOptions(R=cuda(R), eps0=EPS0))
+    assert sizes == ref["meso_sizes"].tolist() and counts == ref["fine_counts"].tolist() and sum(counts) == k
+    assert len(got.trace) == 3 + 2 and got.iters_run == 3
+    for g, r in zip(got.trace[:4], ref["meso"].trace):
+        assert g["objective"] == pytest.approx(r["objective"], rel=1e-4) and g["dprime"] == r["dprime"]
+    a = got.assign.cpu().numpy()
+    Y = got.centroids.cpu().numpy()
+    check_assignment(a, ref["assign"], orc.rotate(X, R), ref["centroids_rot"], own=(X, Y))
+    check_centroids(Y, ref["centroids"], a, ref["assign"])
+    assert got.trace[-1]["objective"] == pytest.approx(ref["objective"], rel=1e-4)
+    assert float(got.dist.sum()) == pytest.approx(ref["objective"], rel=1e-4)
+    with pytest.raises(skm.SkmError):
+        skm.fit_hierarchical(cuda(X), k, 13, 3, 5, skm.FitOptions(R=cuda(R), sample_frac=0.5))
+
+
+@pytest.mark.parametrize("d,dp", [(144, 16), (208, 16), (272, 80)])
+def test_pruned_step_counters_when_workgroups_take_many_tiles(skm, orc, dg, d, dp):
+    """More row tiles than resident workgroups, so the persistent kernel walks several tiles per workgroup; the
+    step counters (survivors, completed pairs, pairs entering each block) must still match the oracle exactly.
+    The shapes give an even and an odd number of trailing blocks (a tile can end at either kind of checkpoint)."""
+    n, k = 90_000, 24
+    X = dg.mixture(n, d, 40, 31, "linear").numpy()
+    R = orc.random_rotation(d, 31)
+    Xr = orc.rotate(X, R)
+    Y0 = Xr[orc.sample_rows(31, n, k)]
+    a0, _ = orc.assign_full(Xr, Y0)
+    Yr, _ = orc.update(Xr, a0, Y0)
+    ref = orc.assign_pruned(Xr, Yr, a0, dp, EPS0)
+    for dense in (0.02, 1.0):
+        a, dist, row = skm.assign(cuda(Xr.astype(np.float32)), cuda(Yr.astype(np.float32)), cuda(a0.astype(np.int32)), dp,
+                                  skm.FitOptions(rotate=False, eps0=EPS0, dense_frac=dense, block_stats=True))
+        check_assignment(a.cpu().numpy(), ref.assign, Xr, Yr)
+        surv_ref = n * (k - 1) - ref.pruned_first
+        assert abs(row["survivors"] - surv_ref) <= max(2, 1e-3 * surv_ref)
+        assert row["nblocks"] == len(ref.enter) - 1
+        for m in range(row["nblocks"]):
+            assert abs(row["enter"][m] - ref.enter[m]) <= max(2, 1e-3 * ref.enter[m])
+        assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])

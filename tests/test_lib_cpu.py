@@ -55,6 +55,17 @@ def test_host_rules_agree_with_the_oracle(skm, orc):
                 assert skm.dprime_adjust(d, dp, f) == orc.dprime_adjust(d, dp, f)
     for seed, n, k in ((42, 20_000, 100), (1, 1000, 1000), (7, 10**6, 1024), (2**63 + 5, 333, 17)):
         assert skm.sample_rows(seed, n, k) == orc.sample_rows(seed, n, k).tolist()
+    # hierarchical fit: number of meso-clusters and the shares of k
+    for k in (1, 2, 3, 10, 99, 1024, 16384, 32768, 2**24):
+        assert skm.hier_meso_count(k) == orc.hier_meso_count(k)
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        km = int(rng.integers(1, 200))
+        sizes = rng.integers(0, 50_000, km) * (rng.random(km) > 0.05)
+        sizes[int(rng.integers(0, km))] += km + 5
+        k = int(rng.integers(km, min(int(sizes.sum()), 40 * km) + 1))
+        assert skm.hier_alloc(sizes.tolist(), k) == orc.hier_alloc(sizes, k).tolist()
+    assert skm.lib().skm_hier_alloc(None, 3, 5, None) == -1
 
 
 def test_argument_errors_are_codes_not_crashes(skm):

@@ -548,3 +548,99 @@ def test_sampled_fit_composition(orc):
     assert (fr.dist >= D.min(1) * (1 - 1e-12)).all() and (fr.dist > D.min(1) * (1 + 1e-9)).mean() < 0.01
     full = orc.fit(X, 16, 5, 7, orc.FitParams(), R=R)
     assert fr.trace[-1]["objective"] == pytest.approx(full.trace[-1]["objective"], rel=0.2)    # similar quality
+
+
+# ---------------------------------------------------------------- hierarchical fit (Section 6)
+def hamilton(sizes, k):
+    """Largest-remainder apportionment written independently with exact rational comparisons where possible:
+    one seat to every non-empty party, the rest by quota on sqrt(size)."""
+    sizes = [int(s) for s in sizes]
+    counts = [1 if s > 0 else 0 for s in sizes]
+    r = k - sum(counts)
+    w = [math.sqrt(s) for s in sizes]
+    W = 0.0
+    for v in w:
+        W += v
+    q = [r * v / W for v in w]
+    for i, v in enumerate(q):
+        counts[i] += min(int(math.floor(v)), sizes[i] - counts[i])
+    order = sorted(range(len(sizes)), key=lambda i: (-(q[i] - math.floor(q[i])), i))
+    left = k - sum(counts)
+    while left > 0:
+        moved = False
+        for i in order:
+            if left > 0 and counts[i] < sizes[i]:
+                counts[i] += 1
+                left -= 1
+                moved = True
+        if not moved:
+            break
+    return counts
+
+
+def test_hier_counts_closed_forms(orc):
+    assert [orc.hier_meso_count(k) for k in (1, 2, 3, 4, 10, 100, 1000, 1024, 16384, 32768)] == \
+        [1, 1, 2, 2, 3, 10, 32, 32, 128, 181]
+    # equal meso-clusters share k equally; sqrt weighting: sizes 400 : 100 : 25 weigh 4 : 2 : 1
+    assert orc.hier_alloc([500] * 8, 64).tolist() == [8] * 8
+    assert orc.hier_alloc([400, 100, 0, 25], 10).tolist() == [5, 3, 0, 2]
+    # never more clusters than points; what a small meso-cluster cannot take goes to the others
+    assert orc.hier_alloc([2, 1000, 3], 12).tolist() == [1, 9, 2]
+    assert orc.hier_alloc([1, 1, 1, 97], 50).tolist() == [1, 1, 1, 47]
+    assert orc.hier_alloc([5, 5], 10).tolist() == [5, 5]
+
+
+def test_hier_alloc_against_independent_apportionment(orc):
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        km = int(rng.integers(1, 40))
+        sizes = rng.integers(0, 2000, km) * (rng.random(km) > 0.1)
+        if sizes.sum() == 0:
+            sizes[0] = 7
+        k = int(rng.integers(max(km, 1), max(int(sizes.sum()), km) + 1))
+        if k > sizes.sum():
+            continue
+        got = orc.hier_alloc(sizes, k)
+        assert got.sum() == k and (got <= sizes).all() and ((got > 0) == (sizes > 0)).all()
+        assert got.tolist() == hamilton(sizes, k)
+        # more points never means fewer clusters
+        o = np.argsort(sizes, kind="stable")
+        assert (np.diff(got[o]) >= -1).all()
+
+
+def test_hierarchical_fit_composition(orc):
+    from paper_2603_20009_amd import datagen
+    X = datagen.mixture(4000, 64, 30, 4, "linear").numpy()
+    R = orc.random_rotation(64, 4)
+    k = 36
+    h = orc.fit_hierarchical(X, k, 9, 3, 5, orc.FitParams(eps0=float("inf")), R=R)
+    Xr = orc.rotate(X, R)
+    km = orc.hier_meso_count(k)
+    assert km == 6 and h["meso_sizes"].sum() == 4000 and h["fine_counts"].sum() == k
+    assert h["fine_counts"].tolist() == hamilton(h["meso_sizes"], k)
+    # with exact Lloyd steps the final assignment is the nearest of all k centroids
+    D = brute_dist(Xr, h["centroids_rot"])
+    assert (h["assign"] == D.argmin(1)).mean() > 0.9999 and np.allclose(h["dist"], D.min(1), rtol=1e-9, atol=1e-12)
+    # block c of the centroids belongs to meso-cluster c: every fine centroid is a mean of some of its points, so
+    # it lies inside their bounding box, and the block's centroids, weighted by their member counts, average to the
+    # mean of the meso-cluster (Lloyd's update keeps the total sum)
+    off = 0
+    for c in range(km):
+        kc = int(h["fine_counts"][c])
+        rows = np.nonzero(h["meso_assign"] == c)[0]
+        P = Xr[rows]
+        Yc = h["centroids_rot"][off:off + kc]
+        assert (Yc >= P.min(0) - 1e-9).all() and (Yc <= P.max(0) + 1e-9).all()
+        lab = brute_dist(P, Yc).argmin(1)        # members under the next exact step
+        # one more exact step from Yc moves it little: Yc are fixed points up to the 5-iteration budget
+        moved = np.stack([P[lab == j].mean(0) if (lab == j).any() else Yc[j] for j in range(kc)])
+        assert np.linalg.norm(moved - Yc) / np.linalg.norm(Yc) < 0.2
+        off += kc
+    # k = 1: one meso-cluster, one fine cluster, the global mean
+    one = orc.fit_hierarchical(X, 1, 9, 3, 5, orc.FitParams(), R=R)
+    assert np.allclose(one["centroids_rot"][0], Xr.mean(0), atol=1e-9)
+    # the unrotated centroids are the rotated ones times R^T
+    assert np.allclose(h["centroids"], h["centroids_rot"] @ R.astype(np.float64).T, atol=1e-9)
+    # quality: within a modest factor of the flat fit with the same k (the paper reports a small recall loss only)
+    flat = orc.fit(X, k, 8, 9, orc.FitParams(), R=R)
+    assert h["objective"] < 1.25 * flat.trace[-1]["objective"]
