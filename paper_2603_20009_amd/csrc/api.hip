@@ -5,6 +5,10 @@
 #include "skm_internal.h"
 
 #include <algorithm>
+#include <atomic>
+#include <thread>
+#include <system_error>
+#include <functional>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -1074,39 +1078,98 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
   if (meso_sizes_out) std::copy(sizes.begin(), sizes.end(), meso_sizes_out);
   if (fine_counts_out) std::copy(counts.begin(), counts.end(), fine_counts_out);
 
-  // ---- FINE
+  // ---- FINE: the meso-clusters are independent small problems; a few host threads, each with its own stream and
+  // workspace arena, take them from a shared counter so that their short kernels overlap on the device.  The result
+  // does not depend on who runs what: every fit writes its own block of Yr and draws from its own seed.
   const int64_t nmax = *std::max_element(sizes.begin(), sizes.end());
   const int32_t kmax = *std::max_element(counts.begin(), counts.end());
+  std::vector<int32_t> koffs((size_t)km + 1, 0);
+  for (int32_t c = 0; c < km; ++c) koffs[(size_t)c + 1] = koffs[(size_t)c] + counts[(size_t)c];
+  if (koffs[(size_t)km] != k) return fail(SKM_EINTERNAL, "fine cluster counts do not add up to k");
   int64_t *order_dev = nullptr;
-  float *Xs = nullptr;
   HIPCHK(pool.get(&order_dev, (size_t)n));
-  HIPCHK(pool.get(&Xs, (size_t)std::max<int64_t>(nmax, 1) * d));
   HIPCHK(hipMemcpyAsync(order_dev, order.data(), sizeof(int64_t) * (size_t)n, hipMemcpyHostToDevice, st));
+  HIPCHK(hipStreamSynchronize(st));
   {
+    struct Worker {
+      hipStream_t st = nullptr;
+      Arena arena;
+      float *Xs = nullptr;
+      int rc = SKM_OK;
+      std::string err;
+    };
+    const int nworkers = (int)std::min<int32_t>(4, km);   // the device exposes four hardware queues to a process
+    std::vector<Worker> workers((size_t)nworkers);
     // workspace of the largest fine fit, generously: per point the padded row copy and the per-point arrays,
     // per centroid three padded rows, plus the hand-over list of a small problem
-    Arena arena;
     const size_t want = (size_t)nmax * ((size_t)ds * 4 + 96) + (size_t)kmax * (size_t)ds * 24 + ((size_t)256 << 20);
-    if (arena.init(want) != hipSuccess) {
-      (void)hipGetLastError();
-      arena.base = nullptr;
-      arena.cap = 0;   // every buffer then comes from hipMalloc
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    struct StreamGuard {
+      std::vector<Worker> &w;
+      ~StreamGuard() {
+        for (Worker &x : w)
+          if (x.st) (void)hipStreamDestroy(x.st);
+      }
+    } guard{workers};
+    for (Worker &w : workers) {
+      HIPCHK(hipStreamCreateWithFlags(&w.st, hipStreamNonBlocking));
+      HIPCHK(pool.get(&w.Xs, (size_t)std::max<int64_t>(nmax, 1) * d));
+      if (w.arena.init(want) != hipSuccess) {
+        (void)hipGetLastError();
+        w.arena.base = nullptr;
+        w.arena.cap = 0;   // every buffer of this worker then comes from hipMalloc
+      }
     }
-    ArenaScope scope(arena.base ? &arena : nullptr);
-    skm_params pfine = pin;
-    pfine.final_assign = 0;   // only the centroids of a fine fit are used
-    int32_t koff = 0;
-    for (int32_t c = 0; c < km; ++c) {
-      const int32_t kc = counts[(size_t)c];
-      if (kc == 0) continue;
-      const int64_t nc = sizes[(size_t)c];
-      HIPCHK(launch_gather_rows(Xr, d, d, order_dev + start[(size_t)c], (int32_t)nc, Xs, d, d, st));
-      rc = fit_impl(Xs, nc, d, kc, fine_iters, seed + 1 + (uint64_t)c, &pfine, Yr + (size_t)koff * d, nullptr, nullptr,
-                    nullptr);
-      if (rc) return rc;
-      koff += kc;
+    std::atomic<int32_t> next_cluster{0};
+    auto body = [&](Worker &w) {
+      if (hipSetDevice(dev) != hipSuccess) {
+        w.rc = fail(SKM_EHIP, "hipSetDevice failed in a worker thread");
+        w.err = g_last_error;
+        return;
+      }
+      ArenaScope scope(w.arena.base ? &w.arena : nullptr);
+      skm_params pfine = pin;
+      pfine.final_assign = 0;   // only the centroids of a fine fit are used
+      pfine.stream = (void *)w.st;
+      for (;;) {
+        const int32_t c = next_cluster.fetch_add(1);
+        if (c >= km) break;
+        const int32_t kc = counts[(size_t)c];
+        if (kc == 0) continue;
+        const int64_t nc = sizes[(size_t)c];
+        hipError_t e = launch_gather_rows(Xr, d, d, order_dev + start[(size_t)c], (int32_t)nc, w.Xs, d, d, w.st);
+        int rcw = e == hipSuccess ? SKM_OK : fail_hip(e, "launch_gather_rows");
+        if (!rcw)
+          rcw = fit_impl(w.Xs, nc, d, kc, fine_iters, seed + 1 + (uint64_t)c, &pfine, Yr + (size_t)koffs[(size_t)c] * d,
+                         nullptr, nullptr, nullptr);
+        if (rcw) {
+          w.rc = rcw;
+          w.err = g_last_error;
+          next_cluster.store(km);   // stop handing out work
+          break;
+        }
+      }
+    };
+    std::vector<std::thread> threads;
+    for (int t = 1; t < nworkers; ++t) {
+      try {
+        threads.emplace_back(body, std::ref(workers[(size_t)t]));
+      } catch (const std::system_error &) {
+        break;   // fewer threads: the others take the work
+      }
     }
-    if (koff != k) return fail(SKM_EINTERNAL, "fine cluster counts do not add up to k");
+    body(workers[0]);
+    for (std::thread &t : threads) t.join();
+    for (Worker &w : workers) {
+      if (w.st) (void)hipStreamSynchronize(w.st);
+    }
+    for (Worker &w : workers) {
+      if (w.rc) {
+        g_last_error = w.err;
+        return w.rc;
+      }
+    }
   }
   HIPCHK(hipEventRecord(e_fine, st));
 
