@@ -60,7 +60,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ unsigned long long s_dead[NT];   // per thread: accumulator elements that start dead (the incumbent)
   __shared__ unsigned int s_cnt[2];
   __shared__ unsigned int s_wcnt[5];
-  __shared__ int s_next;
+  __shared__ int s_q[4];   // ring of tile numbers drawn from the XCD's counter, two tiles ahead of the one in work
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -172,16 +172,19 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   // first tile of this workgroup
   __syncthreads();
-  if (tid == 0) s_next = (int)atomicAdd(ctr, 1u);
+  if (tid == 0) {
+    s_q[0] = (int)atomicAdd(ctr, 1u);
+    s_q[1] = (int)atomicAdd(ctr, 1u);
+  }
   __syncthreads();
-  int q = s_next;
+  int q = s_q[0];
   if (q >= xcount) return;
   int rt, ct;
   tile_rc(q, rt, ct);
   gload(rt * BM, ct * BN, koff);
   load_rows(rt * BM);
 
-  while (true) {
+  for (int tile_no = 0;; ++tile_no) {
     const int row0 = rt * BM, col0 = ct * BN;
     // ---- commit the prefetched first slab and per-row data of this tile
 #pragma unroll
@@ -204,8 +207,10 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         atomicOr(&s_dead[wave_t * 64 + lane_t], 1ull << bit);
       }
     }
-    unsigned int next_q = 0;
-    if (tid == 0) next_q = atomicAdd(ctr, 1u);   // the tile after this one; consumed below
+    // Draw the number of the tile after next now; the answer of the counter is stored at the end of this tile, so
+    // its round trip never stalls the workgroup.
+    unsigned int drawn = 0;
+    if (tid == 0) drawn = atomicAdd(ctr, 1u);
     __syncthreads();
     // The alive counter of checkpoint 0 may still hold the last total of the previous tile (a tile that ends at an
     // even checkpoint leaves it behind).  Every thread has read that total before the barrier above, and the first
@@ -281,7 +286,6 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const int m = last ? g.nb : (tdone - g.dprime) / kBlockDims;   // checkpoint index, t_m = min(d, d' + 64 m)
       if (cp) publish_norms(s_ratio[m]);      // norms over the slabs multiplied so far (the next slab is added below)
       if (s + 1 < nslab) sstore(buf ^ 1);
-      if (s == 0 && tid == 0) s_next = (int)next_q;
       __syncthreads();
       if (cp) {
 #pragma unroll
@@ -334,7 +338,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
 
     // ---- start fetching the next tile before this one is written out
-    q = s_next;
+    q = s_q[(tile_no + 1) & 3];
     const bool more = q < xcount;
     int nrt_ = 0, nct_ = 0;
     if (more) {
@@ -426,6 +430,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     if (!more) break;
     rt = nrt_;
     ct = nct_;
+    if (tid == 0) s_q[(tile_no + 2) & 3] = (int)drawn;
     __syncthreads();   // everyone is done with this tile's LDS before the next one is committed
   }
 }
