@@ -113,6 +113,12 @@ typedef struct skm_params {
                             pair, and so the result, do not depend on it */
   float sample_frac;     /* 0    : in (0, 1): run Algorithm 1 on a uniform sample of round(frac * n) rows (at least k),
                             then assign every point to the final centroids with the two-phase step (Section 4.4) */
+  int32_t angular;       /* 0    : 1 = angular metric (Section 2, "Determining Assignments"): the rotated points are scaled
+                            to unit length and every centroid is scaled back to unit length after each update, so
+                            the nearest centroid by L2 is the one of smallest angle; centroids_out are unit vectors and
+                            dist_out is 2 - 2 cos.  skm_fit_ex only (not with ETR, sample_frac, the hierarchical fit
+                            or skm_assign_ex: SKM_EINVAL) */
+  int32_t reserved3;
 } skm_params;
 
 void skm_params_default(skm_params *p);

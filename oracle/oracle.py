@@ -50,6 +50,7 @@ class _Params(C.Structure):
         ("probe_frac", C.c_double),
         ("etr_tol", C.c_double),
         ("etr_patience", C.c_int32),
+        ("angular", C.c_int32),
     ]
 
 
@@ -288,6 +289,7 @@ class FitParams:
     probe_frac: float = 0.01
     etr_tol: float = 0.005
     etr_patience: int = 2
+    angular: bool = False          # spherical k-means: unit points, centroids renormalised after every update
 
 
 @dataclass
@@ -311,7 +313,7 @@ def fit(X, k: int, iters: int, seed: int, params: FitParams | None = None, R=Non
     Rm = None if R is None else _f32(R)
     cp = _Params(p.dprime_frac, p.eps0, p.tau_group, int(p.adjust_dprime), p.adj_lo, p.adj_hi, p.adj_step,
                  p.split_eps, int(p.final_assign), int(p.etr), 0 if queries is None else int(len(queries)), p.topk,
-                 p.probe_frac, p.etr_tol, p.etr_patience)
+                 p.probe_frac, p.etr_tol, p.etr_patience, int(p.angular))
     Q = None
     G = None
     if p.etr:

@@ -553,6 +553,13 @@ typedef struct orc_params {
   double probe_frac;     /* 0.01 */
   double etr_tol;        /* 0.005 */
   int32_t etr_patience;  /* 2 */
+  /* angular metric (Section 2, "Determining Assignments"): cluster directions,
+   * not positions.  Points are scaled to unit length before anything else and
+   * every centroid is scaled back to unit length after each update (and
+   * split): on the unit sphere ||x - y||^2 = 2 - 2 x.y, so the nearest
+   * centroid by L2 is the one of largest inner product / smallest angle, and
+   * the rest of Algorithm 1 runs unchanged. */
+  int32_t angular;       /* 0 */
 } orc_params;
 
 typedef struct orc_trace_row {
@@ -583,6 +590,21 @@ void orc_params_default(orc_params *p) {
   p->probe_frac = 0.01;
   p->etr_tol = 0.005;
   p->etr_patience = 2;
+}
+
+/* scale every non-zero row to unit Euclidean length */
+void orc_normalize_rows(double *A, int64_t rows, int32_t d) {
+  int64_t i;
+#pragma omp parallel for schedule(static)
+  for (i = 0; i < rows; ++i) {
+    double s = 0.0;
+    int32_t j;
+    for (j = 0; j < d; ++j) s += A[i * d + j] * A[i * d + j];
+    if (s > 0.0) {
+      double inv = 1.0 / sqrt(s);
+      for (j = 0; j < d; ++j) A[i * d + j] *= inv;
+    }
+  }
 }
 
 static double sum_d(const double *v, int64_t n) {
@@ -625,6 +647,7 @@ int32_t orc_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters,
   } else {
     for (i = 0; i < n * d; ++i) Xr[i] = (double)X[i];
   }
+  if (p->angular) orc_normalize_rows(Xr, n, d);
   for (c = 0; c < k; ++c)
     for (j = 0; j < d; ++j)
       Yr[(int64_t)c * d + j] = Xr[init_idx[c] * d + j];
@@ -673,6 +696,7 @@ int32_t orc_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters,
       if (counts[c] == 0) nempty++;
     nsplit = orc_split_empty(Yr, counts, k, d, &split_rng, p->split_eps, NULL);
     (void)nsplit;
+    if (p->angular) orc_normalize_rows(Yr, k, d);
     if (tr) tr->nempty = nempty;
     run = t;
     /* adjust d' (only after an iteration that pruned) */

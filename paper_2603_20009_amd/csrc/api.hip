@@ -594,8 +594,11 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   if (!(p.eps0 >= 0.f)) return fail(SKM_EINVAL, "eps0 must be >= 0");
   skm_trace *tr = p.trace;
   if (tr && (!tr->row || tr->capacity < 1)) return fail(SKM_EINVAL, "trace without rows");
-  if (p.sample_frac > 0.f && p.sample_frac < 1.f)
+  if (p.angular && p.etr) return fail(SKM_EINVAL, "the angular metric is not combined with ETR");
+  if (p.sample_frac > 0.f && p.sample_frac < 1.f) {
+    if (p.angular) return fail(SKM_EINVAL, "the angular metric is not combined with sample_frac");
     return fit_sampled(X, n, d, k, iters, seed, p, centroids_out, assign_out, dist_out);
+  }
 
   Ctx c;
   c.st = (hipStream_t)p.stream;
@@ -624,16 +627,19 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     if (rc) return rc;
     HIPCHK(hipEventRecord(e_rot, c.st));
     c.Xr = Xr_own; c.ldx = c.ds;
-  } else if (d == c.ds && aligned16(X)) {
+  } else if (d == c.ds && aligned16(X) && !p.angular) {
     c.Xr = X; c.ldx = d;
   } else {
     HIPCHK(c.pool.get(&Xr_own, (size_t)n * c.ds));
     HIPCHK(launch_pad_copy(X, d, n, d, Xr_own, c.ds, c.ds, 0, c.st));
     c.Xr = Xr_own; c.ldx = c.ds;
   }
-  if (!p.rotate) {
-    HIPCHK(hipEventRecord(e_rot0, c.st));
-    HIPCHK(hipEventRecord(e_rot, c.st));
+  if (p.angular) HIPCHK(launch_normalize_rows(Xr_own, c.ds, n, c.ds, c.st));   // the library's own copy, in place
+  if (!p.rotate || p.angular) {
+    if (!p.rotate) {
+      HIPCHK(hipEventRecord(e_rot0, c.st));
+      HIPCHK(hipEventRecord(e_rot, c.st));
+    }
     rc = c.measure_xr();
     if (rc) return rc;
   }
@@ -759,6 +765,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     int64_t nempty = 0;
     rc = step_update(c, tm, split_rng, p.split_eps, &nempty);
     if (rc) return rc;
+    if (p.angular) HIPCHK(launch_normalize_rows(c.Y, c.ds, k, c.ds, c.st));
     HIPCHK(hipStreamSynchronize(c.st));
     float ms[ST_COUNT], total;
     tm.collect(ms, &total);
@@ -838,6 +845,7 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
   if (!centroids || !assign_out) return fail(SKM_EINVAL, "null pointer");
   skm_params p;
   if (pp) p = *pp; else skm_params_default(&p);
+  if (p.angular) return fail(SKM_EINVAL, "the angular metric is a fit option: normalise the inputs for a single step");
   skm_trace *tr = p.trace;
   Ctx c;
   c.st = (hipStream_t)p.stream;
@@ -1010,6 +1018,7 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
   skm_params p;
   if (pp) p = *pp; else skm_params_default(&p);
   if (p.etr) return fail(SKM_EINVAL, "the hierarchical fit does not take ETR");
+  if (p.angular) return fail(SKM_EINVAL, "the hierarchical fit does not take the angular metric");
   if (p.sample_frac > 0.f && p.sample_frac < 1.f) return fail(SKM_EINVAL, "the hierarchical fit does not take sample_frac");
   if (p.init_idx) return fail(SKM_EINVAL, "the hierarchical fit draws its initial rows from the seed");
   if (!p.final_assign) return fail(SKM_EINVAL, "the hierarchical fit needs the final assignment pass");

@@ -150,6 +150,9 @@ hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, 
 hipError_t launch_prep_centroids(const float *Y, int64_t ldy, int32_t k, int32_t ds, int32_t dn, float *ynorm,
                                  int32_t dprime, int32_t nb, float *Ypdx, hipStream_t st);
 
+// every non-zero row of A scaled to unit Euclidean length, in place (cols, lda multiples of 4; A 16-byte aligned)
+hipError_t launch_normalize_rows(float *A, int64_t lda, int64_t rows, int32_t cols, hipStream_t st);
+
 hipError_t launch_fill_u64(unsigned long long *p, int64_t n, unsigned long long v, hipStream_t st);
 hipError_t launch_fill_u32(unsigned int *p, int64_t n, unsigned int v, hipStream_t st);
 

@@ -185,6 +185,40 @@ hipError_t launch_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ unit-length rows (angular metric)
+// One wavefront per row: sum of squares in fp32 over float4 loads, then the row is scaled in place.
+// Rows of zeros are left alone.
+__global__ void __launch_bounds__(256) normalize_rows_kernel(float *A, int64_t lda, int64_t rows, int32_t cols) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  float *row = A + r * lda;
+  float s = 0.f;
+  for (int c = 4 * lane; c < cols; c += 256) {
+    const float4 v = *reinterpret_cast<const float4 *>(row + c);
+    s = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, s))));
+  }
+#pragma unroll
+  for (int w = 1; w < 64; w <<= 1) s += __shfl_xor(s, w, 64);
+  if (!(s > 0.f)) return;
+  const float inv = 1.0f / sqrtf(s);
+  for (int c = 4 * lane; c < cols; c += 256) {
+    float4 v = *reinterpret_cast<const float4 *>(row + c);
+    v.x *= inv; v.y *= inv; v.z *= inv; v.w *= inv;
+    *reinterpret_cast<float4 *>(row + c) = v;
+  }
+}
+
+// cols and lda multiples of 4, A 16-byte aligned (the padded buffers of the library)
+hipError_t launch_normalize_rows(float *A, int64_t lda, int64_t rows, int32_t cols, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  if ((reinterpret_cast<uintptr_t>(A) & 15u) || lda % 4 || cols % 4) return hipErrorInvalidValue;
+  const int64_t blocks = (rows + 3) / 4;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(normalize_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, A, lda, rows, cols);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ argmin unpack
 constexpr int FIN_THREADS = 256;
 constexpr int FIN_PER_BLOCK = 1024;

@@ -49,7 +49,7 @@ class Params(C.Structure):
         ("probe_frac", C.c_float), ("etr_tol", C.c_float), ("etr_patience", C.c_int32),
         ("queries", C.c_void_p), ("gt", C.c_void_p),
         ("stream", C.c_void_p), ("trace", C.POINTER(Trace)), ("pair_budget", C.c_int64),
-        ("dense_frac", C.c_float), ("sample_frac", C.c_float),
+        ("dense_frac", C.c_float), ("sample_frac", C.c_float), ("angular", C.c_int32), ("reserved3", C.c_int32),
     ]
 
 
@@ -150,6 +150,7 @@ class FitOptions:
     pair_budget: int = 0
     dense_frac: float = 0.02
     sample_frac: float = 0.0
+    angular: bool = False
 
 
 @dataclass
@@ -196,6 +197,7 @@ def _params(o: FitOptions, keep: list, trace: Trace | None) -> Params:
     p.pair_budget = o.pair_budget
     p.dense_frac = o.dense_frac
     p.sample_frac = o.sample_frac
+    p.angular = int(o.angular)
     return p
 
 

@@ -486,3 +486,24 @@ def test_pruned_step_counters_when_workgroups_take_many_tiles(skm, orc, dg, d, d
         for m in range(row["nblocks"]):
             assert abs(row["enter"][m] - ref.enter[m]) <= max(2, 1e-3 * ref.enter[m])
         assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])
+
+
+def test_angular_fit(skm, orc, dg):
+    """Angular metric: unit points, centroids renormalised after every update; against the oracle's option."""
+    rng = np.random.default_rng(3)
+    X = dg.mixture(15_000, 100, 60, 23, "linear").numpy() * rng.uniform(0.2, 5.0, (15_000, 1)).astype(np.float32)
+    R = orc.random_rotation(100, 23)
+    ref, got = fit_pair(skm, orc, X, 40, 6, 3, R, angular=True)
+    Xu = orc.rotate(X, R)
+    Xu /= np.linalg.norm(Xu, axis=1, keepdims=True)
+    Y = got.centroids.cpu().numpy()
+    assert np.abs(np.linalg.norm(Y, axis=1) - 1.0).max() < 1e-5
+    Xo = X.astype(np.float64) / np.linalg.norm(X.astype(np.float64), axis=1, keepdims=True)
+    check_assignment(got.assign.cpu().numpy(), ref.assign, Xu, ref.centroids_rot, own=(Xo, Y))
+    check_centroids(Y, ref.centroids, got.assign.cpu().numpy(), ref.assign)
+    for g, r in zip(got.trace, ref.trace):
+        assert g["objective"] == pytest.approx(r["objective"], rel=1e-4) and g["dprime"] == r["dprime"]
+    with pytest.raises(skm.SkmError):
+        skm.fit(cuda(X), 40, 3, 3, skm.FitOptions(R=cuda(R), angular=True, sample_frac=0.5))
+    with pytest.raises(skm.SkmError):
+        skm.assign(cuda(X), cuda(Y), None, 0, skm.FitOptions(R=cuda(R), angular=True))

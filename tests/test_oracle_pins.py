@@ -644,3 +644,36 @@ def test_hierarchical_fit_composition(orc):
     # quality: within a modest factor of the flat fit with the same k (the paper reports a small recall loss only)
     flat = orc.fit(X, k, 8, 9, orc.FitParams(), R=R)
     assert h["objective"] < 1.25 * flat.trace[-1]["objective"]
+
+
+# ---------------------------------------------------------------- angular metric (spherical k-means)
+def test_angular_fit_pins(orc):
+    from paper_2603_20009_amd import datagen
+    rng = np.random.default_rng(8)
+    X = datagen.mixture(3000, 48, 25, 6, "linear").numpy() * rng.uniform(0.2, 5.0, (3000, 1)).astype(np.float32)
+    R = orc.random_rotation(48, 6)
+    k = 12
+    fr = orc.fit(X, k, 6, 5, orc.FitParams(eps0=float("inf"), angular=True), R=R)
+    U = orc.rotate(X, R)
+    U /= np.linalg.norm(U, axis=1, keepdims=True)
+    Y = fr.centroids_rot
+    # centroids are unit vectors; with exact steps every point sits with the centroid of largest cosine
+    assert np.allclose(np.linalg.norm(Y, axis=1), 1.0, atol=1e-12)
+    cos = U @ Y.T
+    assert (fr.assign == cos.argmax(1)).mean() > 0.9999
+    assert np.allclose(fr.dist, 2.0 - 2.0 * cos.max(1), atol=1e-10)
+    # a centroid is the direction of the mean of its (unit) members under the last in-loop assignment; after the
+    # final pass the members changed little, so the direction of the new mean is close to it
+    for c in range(k):
+        m = U[fr.assign == c].mean(0)
+        assert m @ Y[c] / np.linalg.norm(m) > 0.999
+    # only directions matter: rescaling every point changes nothing
+    fr2 = orc.fit(X * rng.uniform(0.5, 2.0, (3000, 1)).astype(np.float32), k, 6, 5,
+                  orc.FitParams(eps0=float("inf"), angular=True), R=R)
+    assert (fr2.assign == fr.assign).mean() > 0.999 and np.allclose(fr2.centroids_rot, Y, atol=1e-5)
+    # and it is not the L2 clustering of the raw points
+    l2 = orc.fit(X, k, 6, 5, orc.FitParams(eps0=float("inf")), R=R)
+    assert (l2.assign != fr.assign).mean() > 0.05
+    # pruning on: same trajectory up to the rare false prune
+    pr = orc.fit(X, k, 6, 5, orc.FitParams(angular=True), R=R)
+    assert (pr.assign == fr.assign).mean() > 0.995
