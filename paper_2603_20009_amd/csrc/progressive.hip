@@ -20,6 +20,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 namespace skm {
 
@@ -91,36 +92,51 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   if (tid < 2) s_cnt[tid] = 0u;
   s_dead[tid] = 0ull;
 
-  const int st_row = tid / F4_ROW, st_kq = tid % F4_ROW;  // staging: rows st_row + 32 * s
+  // staging: thread (st_row, st_kq) moves dims 4 st_kq .. + 3 of tile rows st_row + 32 s.  The 8-lane groups of a
+  // wavefront take rows 4 apart (group bits 0-1 and 2-3 swapped): with a row stride of 36 words the rows written by
+  // 32 lanes then start 16 banks apart and their 8-byte LDS writes do not collide.
+  const int grp = tid / F4_ROW, st_kq = tid % F4_ROW;
+  const int st_row = (grp & 16) | ((grp & 3) << 2) | ((grp >> 2) & 3);
   const int koff = -((BK - g.dprime % BK) % BK);
   const int nslab = (g.ds - koff + BK - 1) / BK;
 
+  // Global loads are unconditional: rows past the end are clamped to the last row (their accumulator elements start
+  // dead), dimensions outside [0, ds) are clamped into the row and multiplied by zero when staged.  With nothing
+  // conditional around them the compiler can keep the loads of a whole slab in flight across a multiply step.
   float4 ra[A_F4], rb[B_F4];
   float na[A_F4], nbv[B_F4];
   float tau_reg = 0.f;
   int prev_reg = -1;
-  auto gload = [&](int row0, int col0, int k0) {
-    const int kk = k0 + 4 * st_kq;
-    const bool kok = kk >= 0 && kk < g.ds;
+  const float *baseA = g.A, *baseB = g.B;   // first row / column of the tile being loaded (uniform)
+  int limA = 0, limB = 0;                   // last valid row / column of that tile, relative to its first (uniform)
+  auto aim = [&](int row0, int col0) {
+    baseA = g.A + (int64_t)row0 * g.lda;
+    baseB = g.B + (int64_t)col0 * g.ldb;
+    limA = g.M - 1 - row0;
+    limB = g.N - 1 - col0;
+  };
+  auto kclamp = [&](int k0) { return (unsigned int)min(max(k0 + 4 * st_kq, 0), g.ds - 4); };
+  auto klive = [&](int k0) { return k0 + 4 * st_kq >= 0 && k0 + 4 * st_kq < g.ds; };
+  auto load_a = [&](int j, unsigned int kk) {
+    const unsigned int off = (unsigned int)(min(st_row + ROWS_PASS * j, limA) * (int)g.lda) + kk;
+    ra[j] = *reinterpret_cast<const float4 *>(baseA + off);
+  };
+  auto load_b = [&](int j, unsigned int kk) {
+    const unsigned int off = (unsigned int)(min(st_row + ROWS_PASS * j, limB) * (int)g.ldb) + kk;
+    rb[j] = *reinterpret_cast<const float4 *>(baseB + off);
+  };
+  auto gload = [&](int k0) {
+    const unsigned int kk = kclamp(k0);
 #pragma unroll
-    for (int s = 0; s < A_F4; ++s) {
-      const int gr = row0 + st_row + ROWS_PASS * s;
-      ra[s] = (kok && gr < g.M) ? *reinterpret_cast<const float4 *>(g.A + (int64_t)gr * g.lda + kk)
-                                : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int j = 0; j < A_F4; ++j) load_a(j, kk);
 #pragma unroll
-    for (int s = 0; s < B_F4; ++s) {
-      const int gc = col0 + st_row + ROWS_PASS * s;
-      rb[s] = (kok && gc < g.N) ? *reinterpret_cast<const float4 *>(g.B + (int64_t)gc * g.ldb + kk)
-                                : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int j = 0; j < B_F4; ++j) load_b(j, kk);
   };
   auto load_rows = [&](int row0) {   // per-row data of a tile, one row per thread of the first two wavefronts
     if (tid < BM) {
-      const int gr = row0 + tid;
-      const bool ok = gr < g.M;
-      tau_reg = ok ? g.tau[g.row_base + gr] : 0.f;
-      prev_reg = ok ? g.prev[g.row_base + gr] : -1;
+      const int gr = min(row0 + tid, g.M - 1);
+      tau_reg = g.tau[g.row_base + gr];
+      prev_reg = row0 + tid < g.M ? g.prev[g.row_base + gr] : -1;
     }
   };
   // Split-fp16 staging (see skm_internal.h): a scaled value v goes to LDS as hi = fp16(v) and lo = fp16(v - hi);
@@ -139,17 +155,18 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     *reinterpret_cast<uint2 *>(dst_row + 2 * st_kq) = hi;
     *reinterpret_cast<uint2 *>(dst_row + 16 + 2 * st_kq) = lo;
   };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int s = 0; s < A_F4; ++s) {
-      split_store(As + (buf * BM + st_row + ROWS_PASS * s) * LS, ra[s], scale_a);
-      na[s] = fmaf(ra[s].x, ra[s].x, fmaf(ra[s].y, ra[s].y, fmaf(ra[s].z, ra[s].z, fmaf(ra[s].w, ra[s].w, na[s]))));
-    }
-#pragma unroll
-    for (int s = 0; s < B_F4; ++s) {
-      split_store(Bs + (buf * BN + st_row + ROWS_PASS * s) * LS, rb[s], scale_b);
-      nbv[s] = fmaf(rb[s].x, rb[s].x, fmaf(rb[s].y, rb[s].y, fmaf(rb[s].z, rb[s].z, fmaf(rb[s].w, rb[s].w, nbv[s]))));
-    }
+  auto sumsq = [](const float4 &v) { return fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, v.w * v.w))); };
+  // float4 j of the staged slab -> LDS buffer `buf` (prefix norms updated), then the same registers are aimed at the
+  // slab after it (element offset kk2), so that one register set carries two slabs: one being used, one in flight
+  auto stage_a = [&](int j, int buf, float fa, float fz, unsigned int kk2) {
+    split_store(As + (buf * BM + st_row + ROWS_PASS * j) * LS, ra[j], fa);
+    na[j] = fmaf(sumsq(ra[j]), fz, na[j]);
+    load_a(j, kk2);
+  };
+  auto stage_b = [&](int j, int buf, float fb, float fz, unsigned int kk2) {
+    split_store(Bs + (buf * BN + st_row + ROWS_PASS * j) * LS, rb[j], fb);
+    nbv[j] = fmaf(sumsq(rb[j]), fz, nbv[j]);
+    load_b(j, kk2);
   };
   // prefix norms of the rows / columns of this tile over the dimensions staged so far
   auto publish_norms = [&](float ratio) {
@@ -181,7 +198,10 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   if (q >= xcount) return;
   int rt, ct;
   tile_rc(q, rt, ct);
-  gload(rt * BM, ct * BN, koff);
+  rt = __builtin_amdgcn_readfirstlane(rt);
+  ct = __builtin_amdgcn_readfirstlane(ct);
+  aim(rt * BM, ct * BN);
+  gload(koff);
   load_rows(rt * BM);
 
   for (int tile_no = 0;; ++tile_no) {
@@ -191,7 +211,16 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     for (int s = 0; s < A_F4; ++s) na[s] = 0.f;
 #pragma unroll
     for (int s = 0; s < B_F4; ++s) nbv[s] = 0.f;
-    sstore(0);
+    {
+      // slab 0 of this tile arrived while the previous tile was written out; slab 1 is requested as slab 0 is staged
+      const bool live0 = klive(koff);
+      const float fz = live0 ? 1.f : 0.f;
+      const unsigned int kk1 = kclamp(koff + BK);
+#pragma unroll
+      for (int j = 0; j < A_F4; ++j) stage_a(j, 0, live0 ? scale_a : 0.f, fz, kk1);
+#pragma unroll
+      for (int j = 0; j < B_F4; ++j) stage_b(j, 0, live0 ? scale_b : 0.f, fz, kk1);
+    }
     if (tid < BM) {
       s_tau[tid] = tau_reg;
       s_prev[tid] = prev_reg;
@@ -245,47 +274,83 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
     int fin_mode = 0, fin_m = 0;   // how the tile ends: 0 = nothing alive, 1 = reached t = d, 2 = handed over at fin_m
     float yn[TN] = {0.f, 0.f};
+    // Fragments of half a slab (16 dims): lane half kh supplies the 8 consecutive dims 16 h + 8 kh .. + 7 of both
+    // operands.  x.y ~ hi.hi' + lo.hi' + hi.lo' on the fp16 matrix cores, fp32 accumulation, in groups of four
+    // matrix instructions between which the next slab is converted and the one after it requested.
+    f16x8 ah[TM], al[TM], bh[TN], bl[TN];
+    auto frag = [&](const float *base, int h, int lo, int t) {
+      return *reinterpret_cast<const f16x8 *>(base + t * 32 * LS + kh * 4 + h * 8 + lo * 16);
+    };
+    auto mma4 = [&](const f16x8 (&x)[TM], const f16x8 (&y)[TN]) {
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[a], y[b], acc[a][b], 0, 0, 0);
+    };
+    auto mix = [&](auto valu_per_mfma) {   // spread `valu` vector instructions behind each of the four matrix ones
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, decltype(valu_per_mfma)::value, 0);
+      }
+    };
     for (int s = 0; s < nslab; ++s) {
       const int buf = s & 1;
-      if (s + 1 < nslab) gload(row0, col0, koff + (s + 1) * BK);
-      const float *Ab = As + (buf * BM + wm * WTM + r32) * LS + kh * 4;
-      const float *Bb = Bs + (buf * BN + wn * WTN + r32) * LS + kh * 4;
-      // two steps of 16 dims; lane half kh supplies the 8 consecutive dims 8*kh .. 8*kh+7 of the step;
-      // x.y ~ hi.hi' + hi.lo' + lo.hi' on the fp16 matrix cores, fp32 accumulation
-#pragma unroll
-      for (int stp = 0; stp < 2; ++stp) {
-        f16x8 ah[TM], al[TM], bh[TN], bl[TN];
-#pragma unroll
-        for (int a = 0; a < TM; ++a) {
-          ah[a] = *reinterpret_cast<const f16x8 *>(Ab + a * 32 * LS + stp * 8);
-          al[a] = *reinterpret_cast<const f16x8 *>(Ab + a * 32 * LS + 16 + stp * 8);
-        }
-#pragma unroll
-        for (int b = 0; b < TN; ++b) {
-          bh[b] = *reinterpret_cast<const f16x8 *>(Bb + b * 32 * LS + stp * 8);
-          bl[b] = *reinterpret_cast<const f16x8 *>(Bb + b * 32 * LS + 16 + stp * 8);
-        }
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[a], bh[b], acc[a][b], 0, 0, 0);
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[a], bl[b], acc[a][b], 0, 0, 0);
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[a], bh[b], acc[a][b], 0, 0, 0);
-      }
-
-      const int tdone = koff + BK * (s + 1);   // dimensions multiplied so far
+      const int tdone = koff + BK * (s + 1);   // dimensions multiplied after this step
       const bool last = (s + 1 == nslab);
       const bool check = !last && tdone >= g.dprime && tdone < g.d && ((tdone - g.dprime) & (kBlockDims - 1)) == 0;
       const bool cp = check || last;
       const int m = last ? g.nb : (tdone - g.dprime) / kBlockDims;   // checkpoint index, t_m = min(d, d' + 64 m)
-      if (cp) publish_norms(s_ratio[m]);      // norms over the slabs multiplied so far (the next slab is added below)
-      if (s + 1 < nslab) sstore(buf ^ 1);
+      // the prefix norms cover slabs 0..s here (slab s was staged during the previous step): what the checkpoint
+      // after this step needs; they are published before this step adds slab s + 1
+      if (cp) publish_norms(s_ratio[m]);
+      const float *Ab = As + (buf * BM + wm * WTM + r32) * LS;
+      const float *Bb = Bs + (buf * BN + wn * WTN + r32) * LS;
+      {
+        // (the last step of a tile stages a slab past the end: all zeros, into a buffer nobody reads again)
+        const bool live1 = klive(koff + (s + 1) * BK);
+        const float fa = live1 ? scale_a : 0.f, fb = live1 ? scale_b : 0.f, fz = live1 ? 1.f : 0.f;
+        const unsigned int kk2 = kclamp(koff + (s + 2) * BK);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          ah[t] = frag(Ab, 0, 0, t); bh[t] = frag(Bb, 0, 0, t);
+          al[t] = frag(Ab, 0, 1, t); bl[t] = frag(Bb, 0, 1, t);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mma4(ah, bh);
+        stage_a(0, buf ^ 1, fa, fz, kk2);
+        mix(std::integral_constant<int, 5>());
+        __builtin_amdgcn_sched_barrier(0);
+        mma4(al, bh);
+        stage_a(1, buf ^ 1, fa, fz, kk2);
+        mix(std::integral_constant<int, 5>());
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) { al[t] = frag(Ab, 1, 1, t); bh[t] = frag(Bb, 1, 0, t); }
+        mma4(ah, bl);
+        stage_a(2, buf ^ 1, fa, fz, kk2);
+        stage_a(3, buf ^ 1, fa, fz, kk2);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+        mix(std::integral_constant<int, 9>());
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) { ah[t] = frag(Ab, 1, 0, t); bl[t] = frag(Bb, 1, 1, t); }
+        mma4(al, bh);
+        stage_b(0, buf ^ 1, fb, fz, kk2);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+        mix(std::integral_constant<int, 5>());
+        __builtin_amdgcn_sched_barrier(0);
+        mma4(ah, bl);
+        stage_b(1, buf ^ 1, fb, fz, kk2);
+        mix(std::integral_constant<int, 5>());
+        __builtin_amdgcn_sched_barrier(0);
+        mma4(ah, bh);
+        stage_b(2, buf ^ 1, fb, fz, kk2);
+        stage_b(3, buf ^ 1, fb, fz, kk2);
+        mix(std::integral_constant<int, 9>());
+        __builtin_amdgcn_sched_barrier(0);
+      }
       __syncthreads();
       if (cp) {
 #pragma unroll
@@ -343,7 +408,10 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     int nrt_ = 0, nct_ = 0;
     if (more) {
       tile_rc(q, nrt_, nct_);
-      gload(nrt_ * BM, nct_ * BN, koff);
+      nrt_ = __builtin_amdgcn_readfirstlane(nrt_);
+      nct_ = __builtin_amdgcn_readfirstlane(nct_);
+      aim(nrt_ * BM, nct_ * BN);
+      gload(koff);
       load_rows(nrt_ * BM);
     }
 
