@@ -238,8 +238,8 @@ int32_t nprobe_of(int32_t k, double frac) {
 int make_rotation_dev(Pool &pool, int32_t d, uint64_t seed, hipStream_t st, float *R_out) {
   double *Qw = nullptr, *Cw = nullptr, *Ww = nullptr, *Lw = nullptr;
   HIPCHK(pool.get(&Qw, (size_t)d * d + 2));
-  HIPCHK(pool.get(&Cw, std::max<size_t>((size_t)4 * 32 * d, (size_t)((d + 127) / 128) * 32 * 32)));
-  HIPCHK(pool.get(&Ww, (size_t)8 * 32 * d));
+  HIPCHK(pool.get(&Cw, std::max<size_t>((size_t)12 * 32 * d, (size_t)((d + 127) / 128) * 32 * 32)));
+  HIPCHK(pool.get(&Ww, (size_t)((d + 63) / 64) * 32 * d));
   HIPCHK(pool.get(&Lw, (size_t)32 * 32));
   HIPCHK(launch_make_rotation(d, rng_stream(seed, STREAM_ROTATION).s, Qw, Cw, Ww, Lw, R_out, st));
   return SKM_OK;

@@ -42,8 +42,8 @@ __device__ inline double wave_sum_f64(double v) {
 
 // C = W Q_done^T as a small tiled product: workgroup (jt, ks) owns 32 finished rows j0 .. j0+31 and the
 // ks-th quarter of the columns; Cpart[ks][r][j] holds its share of <W_r, Q_j>.
-constexpr int KS = 4;    // column splits of the coefficient product
-constexpr int JS = 8;    // row splits of the update
+constexpr int KS = 12;   // column splits of the coefficient product
+constexpr int JR = 64;   // finished rows per workgroup of the update (the row range is split into ceil(p0 / JR) parts)
 __global__ void __launch_bounds__(256) coeff_kernel(const double *Q, int d, int p0, int nr, double *Cpart) {
   __shared__ double s_w[PB][65], s_q[32][65];
   const int j0 = blockIdx.x * 32, ks = blockIdx.y;
@@ -76,7 +76,7 @@ __global__ void __launch_bounds__(256) coeff_kernel(const double *Q, int d, int 
   if (j0 + jg + 3 < p0) dst[3] = a3;
 }
 
-// Wpart[js][r][c] = sum over the js-th share of the finished rows j of C[r][j] Q[j][c], with
+// Wpart[js][r][c] = sum over the js-th JR rows of the finished rows j of C[r][j] Q[j][c], with
 // C[r][j] = sum_ks Cpart[ks][r][j].  Thread = (column, group of 8 panel rows).
 __global__ void __launch_bounds__(256) apply_kernel(const double *Q, int d, int p0, int nr, const double *Cpart,
                                                     double *Wpart) {
@@ -84,8 +84,7 @@ __global__ void __launch_bounds__(256) apply_kernel(const double *Q, int d, int 
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
   const int rg = threadIdx.x >> 6;  // rows rg*8 .. rg*8+7
   const int js = blockIdx.y;
-  const int jchunk = ((p0 + JS - 1) / JS + 63) / 64 * 64;
-  const int jbeg = js * jchunk, jend = min(p0, jbeg + jchunk);
+  const int jbeg = js * JR, jend = min(p0, jbeg + JR);
   double acc[8];
 #pragma unroll
   for (int u = 0; u < 8; ++u) acc[u] = 0.0;
@@ -101,12 +100,12 @@ __global__ void __launch_bounds__(256) apply_kernel(const double *Q, int d, int 
     __syncthreads();
     if (c < d) {
       const int jn = min(64, jend - j0);
-      for (int jb = 0; jb < jn; jb += 4) {
-        double qv[4];
+      for (int jb = 0; jb < jn; jb += 8) {
+        double qv[8];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) qv[w] = (jb + w < jn) ? Q[(int64_t)(j0 + jb + w) * d + c] : 0.0;
+        for (int w = 0; w < 8; ++w) qv[w] = (jb + w < jn) ? Q[(int64_t)(j0 + jb + w) * d + c] : 0.0;
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
+        for (int w = 0; w < 8; ++w)
 #pragma unroll
           for (int u = 0; u < 8; ++u) acc[u] = fma(s_c[rg * 8 + u][(jb + w) & 63], qv[w], acc[u]);
       }
@@ -118,13 +117,12 @@ __global__ void __launch_bounds__(256) apply_kernel(const double *Q, int d, int 
 }
 
 // W[r][c] -= sum_js Wpart[js][r][c] (fixed order)
-__global__ void __launch_bounds__(256) subtract_kernel(double *Q, int d, int p0, int nr, const double *Wpart) {
+__global__ void __launch_bounds__(256) subtract_kernel(double *Q, int d, int p0, int nr, const double *Wpart, int njs) {
   const int c = blockIdx.x * 256 + threadIdx.x;
   const int r = blockIdx.y;
   if (c >= d || r >= nr) return;
   double s = 0.0;
-#pragma unroll
-  for (int js = 0; js < JS; ++js) s += Wpart[((int64_t)js * PB + r) * d + c];
+  for (int js = 0; js < njs; ++js) s += Wpart[((int64_t)js * PB + r) * d + c];
   Q[(int64_t)(p0 + r) * d + c] -= s;
 }
 
@@ -221,7 +219,7 @@ __global__ void to_float_kernel(const double *Q, int64_t n, float *R) {
 }
 }  // namespace
 
-// Qwork: d*d + 2 doubles; Cwork: max(4 * 32 * d, ceil(d/128) * 32 * 32); Wwork: 8 * 32 * d; Lwork: 32 * 32.
+// Qwork: d*d + 2 doubles; Cwork: max(12 * 32 * d, ceil(d/128) * 32 * 32); Wwork: ceil(d/64) * 32 * d; Lwork: 32 * 32.
 hipError_t launch_make_rotation(int32_t d, uint64_t seed, double *Qwork, double *Cwork, double *Wwork, double *Lwork,
                                 float *R_out, hipStream_t st) {
   const int64_t nel = (int64_t)d * d;
@@ -229,16 +227,21 @@ hipError_t launch_make_rotation(int32_t d, uint64_t seed, double *Qwork, double 
   hipLaunchKernelGGL(gauss_fill_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, st, Qwork, pairs, seed);
   for (int p0 = 0; p0 < d; p0 += PB) {
     const int nr = d - p0 < PB ? d - p0 : PB;
+    // The rows are Gaussian: what a panel keeps after the projection has norm sqrt((d - p0) / d) of what it had, so one
+    // projection and one Cholesky-QR already leave errors near fp64 rounding while the complement is large.  In the
+    // last 256 rows, where the complement gets small and the panel ill-conditioned, both steps are done twice.
+    const int passes = d - p0 <= 8 * PB ? 2 : 1;
     if (p0 > 0) {
-      for (int pass = 0; pass < 2; ++pass) {
+      for (int pass = 0; pass < passes; ++pass) {
         hipLaunchKernelGGL(coeff_kernel, dim3((unsigned)((p0 + 31) / 32), KS), dim3(256), 0, st, Qwork, d, p0, nr, Cwork);
-        hipLaunchKernelGGL(apply_kernel, dim3((unsigned)((d + 63) / 64), JS), dim3(256), 0, st, Qwork, d, p0, nr, Cwork,
-                           Wwork);
+        const int njs = (p0 + JR - 1) / JR;
+        hipLaunchKernelGGL(apply_kernel, dim3((unsigned)((d + 63) / 64), (unsigned)njs), dim3(256), 0, st, Qwork, d, p0, nr,
+                           Cwork, Wwork);
         hipLaunchKernelGGL(subtract_kernel, dim3((unsigned)((d + 255) / 256), PB), dim3(256), 0, st, Qwork, d, p0, nr,
-                           Wwork);
+                           Wwork, njs);
       }
     }
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = 0; pass < passes; ++pass) {
       const int nchunks = (d + GC - 1) / GC;
       hipLaunchKernelGGL(gram_partial_kernel, dim3((unsigned)nchunks), dim3(256), 0, st, Qwork, d, p0, nr, Cwork);
       hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(64), 0, st, Cwork, nchunks, nr, Lwork);

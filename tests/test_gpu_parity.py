@@ -55,6 +55,10 @@ def test_library_rotation_is_orthogonal_and_seeded(skm):
         R = skm.make_rotation(d, 5).cpu().numpy().astype(np.float64)
         assert np.abs(R @ R.T - np.eye(d)).max() < 1e-6
         assert np.abs(np.linalg.det(R)) == pytest.approx(1.0, abs=1e-4)
+    # at the benchmark's size, several seeds: the error is that of rounding the fp64 matrix to fp32
+    for seed in (0, 1, 2):
+        R = skm.make_rotation(1536, seed).cpu().numpy().astype(np.float64)
+        assert np.abs(R @ R.T - np.eye(1536)).max() < 1e-7 and np.abs(R.T @ R - np.eye(1536)).max() < 1e-7
     a = skm.make_rotation(64, 1).cpu().numpy()
     b = skm.make_rotation(64, 1).cpu().numpy()
     c = skm.make_rotation(64, 2).cpu().numpy()
