@@ -50,6 +50,36 @@ def test_rotation_gemm(skm, orc, dg, n, d):
     assert np.abs(skm.rotate(cuda(X), cuda(R), True).cpu().numpy() - want_t).max() < 2e-6
 
 
+@pytest.mark.parametrize("scale", [1e-30, 1e-6, 1.0, 1e6, 1e30])
+def test_split_gemm_keeps_fp32_accuracy_over_the_dynamic_range(skm, orc, scale):
+    """The GEMMs multiply fp32 operands as scaled pairs of fp16 numbers.  The error against fp64 must stay at the
+    fp32 level relative to the largest output whatever the magnitude of the inputs, also when a few columns are a
+    thousand times larger than the rest, and zero inputs must give exact zeros."""
+    rng = np.random.default_rng(7)
+    n, d = 700, 256
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    X[:, :5] *= 1000.0                      # a few dominant columns
+    X[::7] *= 1e-3                          # and some tiny rows
+    X = (X * np.float32(scale)).astype(np.float32)
+    R = orc.random_rotation(d, 9)
+    want = X.astype(np.float64) @ R.astype(np.float64)
+    got = skm.rotate(cuda(X), cuda(R)).cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= 2e-6 * np.abs(want).max()
+    # the tiny rows keep a relative accuracy of their own largest entry: 22-bit operands, not a global absolute error
+    tiny = np.arange(n)[::7]
+    assert (np.abs(got[tiny] - want[tiny]).max(1) <= 1e-4 * np.abs(want[tiny]).max(1)).all()
+    Z = np.zeros((n, d), dtype=np.float32)
+    assert not skm.rotate(cuda(Z), cuda(R)).cpu().numpy().any()
+    # exact assignment on the same data agrees with fp64 except at near-ties (where squared distances fit fp32 at all)
+    if not 1e-7 < scale < 1e7:
+        return
+    Y = X[rng.choice(n, 40, replace=False)]
+    a, _ = skm.assign_exact(cuda(X), cuda(Y))
+    ao, _ = orc.assign_full(X.astype(np.float64), Y.astype(np.float64))
+    check_assignment(a.cpu().numpy(), ao, X, Y, min_agree=0.995)
+
+
 def test_library_rotation_is_orthogonal_and_seeded(skm):
     for d in (16, 100, 384):
         R = skm.make_rotation(d, 5).cpu().numpy().astype(np.float64)
