@@ -528,14 +528,16 @@ static hipError_t launch_split(const GemmOperands &g, const typename EpiArgs<EPI
 constexpr int64_t kMaxTilesPerLaunch = (1 << 24) - 1;
 
 // Column tiles per panel of the tile walk.  Measured on MI355X (rotation and iteration-1 GEMMs of the
-// 1M x 1536 workload, widths 1..12): no effect on the run time, the kernel is bound by the matrix pipe;
-// SKM_TEST_PANEL_COLS overrides the width for experiments.
-static int panel_cols_for(int) {
+// 1M x 1536 workload): the width moves the run time by less than the noise, but the bytes fetched from beyond L2
+// drop by a quarter at 4 (the four centroid tiles of a panel then stay in one XCD's L2 while the point tiles
+// stream past; every point tile is read once per panel).  With many column tiles the point tiles would be re-read
+// too often, so wide problems keep 16.  SKM_TEST_PANEL_COLS overrides the width for experiments.
+static int panel_cols_for(int64_t nct) {
   static const int forced = []() {
     const char *e = std::getenv("SKM_TEST_PANEL_COLS");
     return e ? std::atoi(e) : 0;
   }();
-  return forced > 0 ? forced : 16;
+  return forced > 0 ? forced : (nct <= 16 ? 4 : 16);
 }
 
 inline void shift_rows(StoreArgs &e, int64_t r0) { e.C += r0 * e.ldc; }
@@ -557,7 +559,7 @@ static hipError_t launch_any(const GemmOperands &g, const typename EpiArgs<EPI>:
   const int64_t band_rows = std::max<int64_t>(max_tiles / nct, 1) * BM;
   for (int64_t r0 = 0; r0 < g.M; r0 += band_rows) {
     GemmOperands gb = g;
-    gb.panel_cols = panel_cols_for(g.K);
+    gb.panel_cols = panel_cols_for(nct);
     gb.A = g.A + r0 * g.lda;
     gb.M = (int32_t)std::min<int64_t>(band_rows, g.M - r0);
     typename EpiArgs<EPI>::type eb = e;

@@ -38,7 +38,6 @@ constexpr int F4_ROW = BK / 4;              // 8 lanes stage one tile row
 constexpr int ROWS_PASS = NT / F4_ROW;      // 32 tile rows per staging pass
 constexpr int A_F4 = BM / ROWS_PASS;        // 4
 constexpr int B_F4 = BN / ROWS_PASS;        // 4
-constexpr int PC = 16;                      // column tiles per panel of the tile walk
 
 // sum over the 8 consecutive lanes that stage one tile row; all of them get the total
 __device__ inline float rowgroup_sum(float v) {
@@ -69,6 +68,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int r32 = lane & 31, kh = lane >> 5;
   const int nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
   const int ntiles = nrt * nct;
+  const int PC = nct <= 16 ? 4 : 16;   // column tiles per panel of the tile walk (see gemm.hip)
 
   // This workgroup's share: the contiguous range of logical tile ids of its XCD (workgroups are dealt
   // round-robin to the 8 XCDs), walked through a per-XCD counter.
