@@ -68,7 +68,9 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int r32 = lane & 31, kh = lane >> 5;
   const int nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
   const int ntiles = nrt * nct;
-  const int PC = nct <= 16 ? 4 : 16;   // column tiles per panel of the tile walk (see gemm.hip)
+  // column tiles per panel of the tile walk: in the steady state only d' + a few blocks of every centroid are read,
+  // so a panel of 16 column tiles fits one XCD's L2 and every point tile is read once per 16 column tiles
+  constexpr int PC = 16;
 
   // This workgroup's share: the contiguous range of logical tile ids of its XCD (workgroups are dealt
   // round-robin to the 8 XCDs), walked through a per-XCD counter.
