@@ -170,7 +170,9 @@ def main():
         "value": value, "unit": "point*centroid*dim/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 (operands as split fp16 pairs on fp16 MFMA, fp32 accumulation)", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
+        "arithmetic": "fp32 in, fp32 accumulation and fp32 out; GEMM-shaped products run on the fp16 matrix cores with "
+                      "every operand as a scaled (hi, lo) fp16 pair, 22 significant bits (three MFMAs per product)",
         "config": {"workload": f"{args.config}: {n}x{d} fp32 unit-norm mixture rows ({cfg['components']} components), "
                                f"k={k}, {iters} iterations + final assignment pass", "n": n, "d": d, "k": k,
                    "iters": iters, "iters_run": iters_run},
