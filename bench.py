@@ -125,6 +125,13 @@ def main():
     flop_alg = float(np.mean([2.0 * n * k * t["dprime"] + 128.0 * t["dense_pair_blocks"] for t in steps2])) if steps2 else 0.0
     flop_exec = float(np.mean([tile_flop * t["dense_dims"] for t in steps2])) if steps2 else 0.0
     total_prog = float(np.sum([t["ms_gemm"] for t in steps2]))
+    # algorithmic bytes of an update: every row once (full), or the rows of the points that changed cluster, twice
+    # (joined + left), when the library takes the incremental path (at most one point in eight changed)
+    def update_bytes(t, first):
+        if not first and 8 * t["changed"] <= n:
+            return 2.0 * t["changed"] * ds * 4.0 + 8.0 * n + k * ds * 20.0
+        return n * ds * 4.0 + 8.0 * n + 2.0 * k * ds * 4.0
+    upd_bytes = float(np.mean([update_bytes(t, i == 0) for i, t in enumerate(last.trace[:last.iters_run])]))
     flops_rot = 2.0 * n * d * d
     flops_it1 = 2.0 * n * k * ds
     stages = {
@@ -134,8 +141,8 @@ def main():
                                  executed=flop_exec / ms_prog / 1e9),
         "tau_init": dict(bound="hbm", ms=ms_tau, achieved=(n * ds * 4.0 + 12.0 * n) / ms_tau / 1e6, unit="GB/s"),
         "gather_prune": dict(bound="hbm", ms=ms_prune, achieved=None, unit="GB/s"),
-        "update": dict(bound="hbm", ms=ms_update, achieved=(n * ds * 4.0 + 8.0 * n + 2.0 * k * ds * 4.0) / ms_update / 1e6,
-                       unit="GB/s"),
+        "update": dict(bound="hbm", ms=ms_update, achieved=upd_bytes / ms_update / 1e6, unit="GB/s",
+                       incremental_updates=int(last.timing.get("inc_updates", 0))),
     }
     for s in stages.values():
         if s["achieved"] is not None:

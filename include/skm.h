@@ -66,7 +66,7 @@ typedef struct skm_trace {
   int32_t capacity;    /* in : rows available in `row` (iters + 1 is enough) */
   int32_t rows;        /* out: rows written */
   int32_t iters_run;   /* out: update steps performed */
-  int32_t reserved;
+  int32_t inc_updates; /* out: update steps done incrementally (from the points that changed cluster only) */
   float ms_rotate;     /* out: the X~ = X R GEMM alone (events around its launch) */
   float ms_init;       /* out: everything before iteration 1: workspace, R, rotation, initial centroids, ETR set-up */
   float ms_etr_gt;     /* out: ETR ground truth (0 when supplied or ETR off) */
@@ -118,7 +118,9 @@ typedef struct skm_params {
                             the nearest centroid by L2 is the one of smallest angle; centroids_out are unit vectors and
                             dist_out is 2 - 2 cos.  skm_fit_ex only (not with ETR, sample_frac, the hierarchical fit
                             or skm_assign_ex: SKM_EINVAL) */
-  int32_t reserved3;
+  int32_t full_update;   /* 0    : 1 = recompute every cluster sum from all points in every update.  By default, once at most
+                            one point in eight changes its cluster, the fp64 sums of the previous update are
+                            corrected by the rows that joined and left (the same means up to fp64 rounding) */
 } skm_params;
 
 void skm_params_default(skm_params *p);

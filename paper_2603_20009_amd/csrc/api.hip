@@ -288,6 +288,10 @@ struct Ctx {
   unsigned long long *scal = nullptr;  // [SC_COUNT]
   double *obj_partial = nullptr, *obj = nullptr;
   UpdateWs up{};
+  IncUpdateWs inc{};                 // workspace of the incremental update
+  double *S = nullptr;               // [k][ds] cluster sums of the last update (fp64), valid once S_valid
+  bool S_valid = false;
+  int32_t inc_updates = 0;           // update steps that took the incremental path
   int32_t *split_dev = nullptr;
   bool block_stats = false;
   unsigned int *amax = nullptr;      // [AM_COUNT] magnitude bounds of the GEMM operands
@@ -343,6 +347,19 @@ struct Ctx {
       up.max_segments = update_max_segments(n, k);
       HIPCHK(pool.get(&up.partial, (size_t)up.max_segments * ds));
       HIPCHK(pool.get(&split_dev, (size_t)2 * k));
+      // the incremental update is used while at most one point in eight changes its label
+      HIPCHK(pool.get(&S, (size_t)k * ds));
+      inc.capacity = 2 * (n / 8) + 2;
+      inc.max_segments = update_max_segments(inc.capacity, k);
+      HIPCHK(pool.get(&inc.ent_id, (size_t)inc.capacity));
+      HIPCHK(pool.get(&inc.ent_lab, (size_t)inc.capacity));
+      HIPCHK(pool.get(&inc.order, (size_t)inc.capacity));
+      HIPCHK(pool.get(&inc.cnt, (size_t)k));
+      HIPCHK(pool.get(&inc.off, (size_t)k + 1));
+      HIPCHK(pool.get(&inc.cursor, (size_t)k));
+      HIPCHK(pool.get(&inc.segoff, (size_t)k + 1));
+      HIPCHK(pool.get(&inc.counter, 1));
+      HIPCHK(pool.get(&inc.partial, (size_t)inc.max_segments * ds));
     }
     return SKM_OK;
   }
@@ -466,8 +483,19 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
 }
 
 // Update + split of empty clusters (Section 3.2).  c.up.cnt must hold the cluster sizes of c.assign.
-int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t *nempty_out) {
-  HIPCHK(launch_update(c.Xr, c.ldx, c.n, c.ds, c.assign, c.k, c.up, c.Y, c.ds, c.st));
+// `changed` = points whose label differs from c.prev (c.n after the exact step).  While few points move, the cluster
+// sums of the previous update are corrected by the rows that joined and left instead of being recomputed from all
+// points (full = true forces the recomputation).
+int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t *nempty_out, int64_t changed,
+                bool full) {
+  if (!full && c.S_valid && 2 * changed <= c.inc.capacity - 2) {
+    ++c.inc_updates;
+    HIPCHK(launch_update_incremental(c.Xr, c.ldx, c.n, c.ds, c.assign, c.prev, changed, c.k, c.up, c.inc, c.S, c.Y, c.ds,
+                                     c.st));
+  } else {
+    HIPCHK(launch_update(c.Xr, c.ldx, c.n, c.ds, c.assign, c.k, c.up, c.Y, c.ds, c.st, c.S));
+    c.S_valid = true;
+  }
   std::vector<int32_t> cnt((size_t)c.k);
   HIPCHK(hipMemcpyAsync(cnt.data(), c.up.cnt, sizeof(int32_t) * cnt.size(), hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipStreamSynchronize(c.st));
@@ -763,7 +791,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
       tm.mark(ST_ETR);
     }
     int64_t nempty = 0;
-    rc = step_update(c, tm, split_rng, p.split_eps, &nempty);
+    rc = step_update(c, tm, split_rng, p.split_eps, &nempty, ss.changed, p.full_update != 0);
     if (rc) return rc;
     if (p.angular) HIPCHK(launch_normalize_rows(c.Y, c.ds, k, c.ds, c.st));
     HIPCHK(hipStreamSynchronize(c.st));
@@ -818,6 +846,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   if (tr) {
     tr->rows = std::min(rows, tr->capacity);
     tr->iters_run = run;
+    tr->inc_updates = c.inc_updates;
     (void)hipEventElapsedTime(&tr->ms_rotate, e_rot0, e_rot);
     (void)hipEventElapsedTime(&tr->ms_init, e_begin, e_init);
     (void)hipEventElapsedTime(&tr->ms_etr_gt, e_gt0, e_gt1);

@@ -177,8 +177,25 @@ struct UpdateWs {
   int64_t max_segments;
 };
 int64_t update_max_segments(int64_t n, int32_t k);
+// S (optional, [k][ds] fp64) receives the sum of every cluster.
 hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign, int32_t k,
-                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st);
+                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st, double *S = nullptr);
+
+// Workspace of the incremental update: room for 2 * (points that changed label) entries.
+struct IncUpdateWs {
+  int32_t *ent_id;     // [capacity] point id, or ~id for a point that left the cluster
+  int32_t *ent_lab;    // [capacity] cluster of the entry
+  int32_t *order;      // [capacity]
+  int32_t *cnt, *off, *cursor, *segoff;   // [k], [k+1], [k], [k+1]
+  unsigned int *counter;
+  double *partial;     // [max_segments][ds]
+  int64_t capacity, max_segments;
+};
+// Centroids from the cluster sums S of the previous update and the points whose label changed since
+// (Section 3.2, the same means computed from the difference).
+hipError_t launch_update_incremental(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign,
+                                     const int32_t *prev, int64_t changed, int32_t k, const UpdateWs &w,
+                                     const IncUpdateWs &inc, double *S, float *Y, int64_t ldy, hipStream_t st);
 
 hipError_t launch_split(float *Y, int64_t ldy, int32_t d, const int32_t *pairs_dev, int32_t nsplit, float eps,
                         hipStream_t st);

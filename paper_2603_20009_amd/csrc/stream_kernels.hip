@@ -356,12 +356,13 @@ __global__ void __launch_bounds__(1024) scan_counts_kernel(const int32_t *cnt, i
   if (threadIdx.x == 0) { off[k] = carry_a; segoff[k] = carry_b; }
 }
 
+// order[...] = i (or ids[i] when the labelled items are a list of ids), grouped by label
 __global__ void scatter_order_kernel(const int32_t *assign, int64_t n, const int32_t *off, int32_t *cursor,
-                                     int32_t *order) {
+                                     int32_t *order, const int32_t *ids) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
     const int a = assign[i];
     const int pos = off[a] + atomicAdd(cursor + a, 1);
-    order[pos] = (int32_t)i;
+    order[pos] = ids ? ids[i] : (int32_t)i;
   }
 }
 
@@ -397,6 +398,8 @@ __global__ void __launch_bounds__(256) sort_segments_kernel(const int32_t *off, 
 
 // One workgroup per (segment of <= kSegPoints points of one cluster, slice of 1024 dims):
 // rows are gathered through `order` (each a contiguous row read), summed in fp64 per thread.
+// SIGNED: an entry i >= 0 adds row i, an entry ~i < 0 subtracts row i (a point that left the cluster).
+template <bool SIGNED>
 __global__ void __launch_bounds__(256) segment_sum_kernel(const float *Xr, int64_t ldx, int32_t ds, int32_t k,
                                                           const int32_t *off, const int32_t *segoff,
                                                           const int32_t *order, double *partial) {
@@ -416,6 +419,15 @@ __global__ void __launch_bounds__(256) segment_sum_kernel(const float *Xr, int64
   if (col >= ds) return;
   double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
   int p = p0;
+  if (SIGNED) {
+    for (; p < p1; ++p) {
+      const int raw = order[p];
+      const int i = raw < 0 ? ~raw : raw;
+      const double sg = raw < 0 ? -1.0 : 1.0;
+      const float4 v = *reinterpret_cast<const float4 *>(Xr + (int64_t)i * ldx + col);
+      a0 += sg * (double)v.x; a1 += sg * (double)v.y; a2 += sg * (double)v.z; a3 += sg * (double)v.w;
+    }
+  }
   for (; p + 4 <= p1; p += 4) {
     const int i0 = order[p], i1 = order[p + 1], i2 = order[p + 2], i3 = order[p + 3];
     const float4 v0 = *reinterpret_cast<const float4 *>(Xr + (int64_t)i0 * ldx + col);
@@ -436,31 +448,95 @@ __global__ void __launch_bounds__(256) segment_sum_kernel(const float *Xr, int64
 }
 
 // One workgroup per (cluster, slice): partial sums added in segment order, divided by the size.
+// S (optional, [k][ds] fp64) keeps the sum of every cluster between updates: it is overwritten by the total of the
+// partials, or, with `accumulate`, the total (a signed change) is added to it.
 __global__ void __launch_bounds__(256) centroid_mean_kernel(const double *partial, int32_t ds, const int32_t *cnt,
-                                                            const int32_t *segoff, float *Y, int64_t ldy) {
+                                                            const int32_t *segoff, float *Y, int64_t ldy, double *S,
+                                                            int accumulate) {
   const int c = blockIdx.x;
   const int n_c = cnt[c];
-  if (n_c == 0) return;  // an empty cluster keeps its centroid until the split
   const int col = blockIdx.y * 256 + threadIdx.x;
   if (col >= ds) return;
   double s = 0.0;
   for (int seg = segoff[c]; seg < segoff[c + 1]; ++seg) s += partial[(int64_t)seg * ds + col];
+  if (S) {
+    if (accumulate) s += S[(int64_t)c * ds + col];
+    S[(int64_t)c * ds + col] = s;
+  }
+  if (n_c == 0) return;  // an empty cluster keeps its centroid until the split
   Y[(int64_t)c * ldy + col] = (float)(s / (double)n_c);
 }
 
+// Points whose label changed: entry (i, new label) and entry (~i, old label), in any order (the segments are
+// sorted afterwards).  *counter must be 0; entries past `cap` are dropped and show in the final *counter.
+__global__ void __launch_bounds__(256) compact_changes_kernel(const int32_t *assign, const int32_t *prev, int64_t n,
+                                                              int32_t *ent_id, int32_t *ent_lab, unsigned int *counter,
+                                                              unsigned int cap) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const int a = assign[i], b = prev[i];
+    if (a != b) {
+      const unsigned int e = atomicAdd(counter, 2u);
+      if (e + 2u <= cap) {
+        ent_id[e] = (int32_t)i;
+        ent_lab[e] = a;
+        ent_id[e + 1] = ~(int32_t)i;
+        ent_lab[e + 1] = b;
+      }
+    }
+  }
+}
+
 hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign, int32_t k,
-                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st) {
+                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st, double *S) {
   hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, st, w.cnt, k, w.off, w.cursor, w.segoff);
   int64_t blocks = (n + 255) / 256;
   if (blocks > 16384) blocks = 16384;
   hipLaunchKernelGGL(scatter_order_kernel, dim3((unsigned)blocks), dim3(256), 0, st, assign, n, w.off, w.cursor,
-                     w.order);
+                     w.order, (const int32_t *)nullptr);
   hipLaunchKernelGGL(sort_segments_kernel, dim3(k), dim3(256), 0, st, w.off, w.order);
   const unsigned slices4 = (unsigned)((ds + 1023) / 1024);
-  hipLaunchKernelGGL(segment_sum_kernel, dim3((unsigned)w.max_segments, slices4), dim3(256), 0, st, Xr, ldx, ds, k,
+  hipLaunchKernelGGL(segment_sum_kernel<false>, dim3((unsigned)w.max_segments, slices4), dim3(256), 0, st, Xr, ldx, ds, k,
                      w.off, w.segoff, w.order, w.partial);
   const unsigned slices1 = (unsigned)((ds + 255) / 256);
-  hipLaunchKernelGGL(centroid_mean_kernel, dim3(k, slices1), dim3(256), 0, st, w.partial, ds, w.cnt, w.segoff, Y, ldy);
+  hipLaunchKernelGGL(centroid_mean_kernel, dim3(k, slices1), dim3(256), 0, st, w.partial, ds, w.cnt, w.segoff, Y, ldy, S,
+                     0);
+  return hipGetLastError();
+}
+
+// The same update from the points that changed label only: S (the cluster sums of the previous update) takes the
+// rows of the points that joined minus those of the points that left, and every centroid is S / size again.
+// w.cnt holds the new cluster sizes; `changed` is the number of points with assign != prev (known to the host from
+// the assignment step), inc is a workspace for 2 * changed entries.
+hipError_t launch_update_incremental(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign,
+                                     const int32_t *prev, int64_t changed, int32_t k, const UpdateWs &w,
+                                     const IncUpdateWs &inc, double *S, float *Y, int64_t ldy, hipStream_t st) {
+  const int64_t m2 = 2 * changed;
+  if (m2 > inc.capacity || !S) return hipErrorInvalidValue;
+  hipError_t rc = hipMemsetAsync(inc.counter, 0, sizeof(unsigned int), st);
+  if (rc != hipSuccess) return rc;
+  rc = hipMemsetAsync(inc.cnt, 0, sizeof(int32_t) * (size_t)k, st);
+  if (rc != hipSuccess) return rc;
+  int64_t blocks = std::min<int64_t>((n + 255) / 256, 16384);
+  hipLaunchKernelGGL(compact_changes_kernel, dim3((unsigned)blocks), dim3(256), 0, st, assign, prev, n, inc.ent_id,
+                     inc.ent_lab, inc.counter, (unsigned int)inc.capacity);
+  if (m2 > 0) {
+    rc = launch_histogram(inc.ent_lab, m2, inc.cnt, st);
+    if (rc != hipSuccess) return rc;
+  }
+  hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, st, inc.cnt, k, inc.off, inc.cursor, inc.segoff);
+  if (m2 > 0) {
+    blocks = std::min<int64_t>((m2 + 255) / 256, 16384);
+    hipLaunchKernelGGL(scatter_order_kernel, dim3((unsigned)blocks), dim3(256), 0, st, inc.ent_lab, m2, inc.off, inc.cursor,
+                       inc.order, (const int32_t *)inc.ent_id);
+    hipLaunchKernelGGL(sort_segments_kernel, dim3(k), dim3(256), 0, st, inc.off, inc.order);
+    const unsigned slices4 = (unsigned)((ds + 1023) / 1024);
+    const int64_t segs = std::min<int64_t>(inc.max_segments, (int64_t)k + m2 / kSegPoints + 1);
+    hipLaunchKernelGGL(segment_sum_kernel<true>, dim3((unsigned)segs, slices4), dim3(256), 0, st, Xr, ldx, ds, k, inc.off,
+                       inc.segoff, inc.order, inc.partial);
+  }
+  const unsigned slices1 = (unsigned)((ds + 255) / 256);
+  hipLaunchKernelGGL(centroid_mean_kernel, dim3(k, slices1), dim3(256), 0, st, inc.partial, ds, w.cnt, inc.segoff, Y, ldy,
+                     S, 1);
   return hipGetLastError();
 }
 

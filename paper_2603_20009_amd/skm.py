@@ -32,7 +32,7 @@ class TraceRow(C.Structure):
 
 class Trace(C.Structure):
     _fields_ = [
-        ("capacity", C.c_int32), ("rows", C.c_int32), ("iters_run", C.c_int32), ("reserved", C.c_int32),
+        ("capacity", C.c_int32), ("rows", C.c_int32), ("iters_run", C.c_int32), ("inc_updates", C.c_int32),
         ("ms_rotate", C.c_float), ("ms_init", C.c_float), ("ms_etr_gt", C.c_float), ("ms_unrotate", C.c_float),
         ("ms_total", C.c_float), ("reserved2", C.c_float),
         ("row", C.POINTER(TraceRow)),
@@ -49,7 +49,7 @@ class Params(C.Structure):
         ("probe_frac", C.c_float), ("etr_tol", C.c_float), ("etr_patience", C.c_int32),
         ("queries", C.c_void_p), ("gt", C.c_void_p),
         ("stream", C.c_void_p), ("trace", C.POINTER(Trace)), ("pair_budget", C.c_int64),
-        ("dense_frac", C.c_float), ("sample_frac", C.c_float), ("angular", C.c_int32), ("reserved3", C.c_int32),
+        ("dense_frac", C.c_float), ("sample_frac", C.c_float), ("angular", C.c_int32), ("full_update", C.c_int32),
     ]
 
 
@@ -151,6 +151,7 @@ class FitOptions:
     dense_frac: float = 0.02
     sample_frac: float = 0.0
     angular: bool = False
+    full_update: bool = False
 
 
 @dataclass
@@ -198,6 +199,7 @@ def _params(o: FitOptions, keep: list, trace: Trace | None) -> Params:
     p.dense_frac = o.dense_frac
     p.sample_frac = o.sample_frac
     p.angular = int(o.angular)
+    p.full_update = int(o.full_update)
     return p
 
 
@@ -225,7 +227,7 @@ def fit(X: torch.Tensor, k: int, iters: int, seed: int, opts: FitOptions | None 
     _check(rc)
     rows = [_row_dict(tr.row[i]) for i in range(tr.rows)]
     timing = dict(ms_rotate=tr.ms_rotate, ms_init=tr.ms_init, ms_etr_gt=tr.ms_etr_gt, ms_unrotate=tr.ms_unrotate,
-                  ms_total=tr.ms_total)
+                  ms_total=tr.ms_total, inc_updates=int(tr.inc_updates))
     return FitResult(cent, assign, dist, int(tr.iters_run), rows, timing)
 
 

@@ -541,3 +541,29 @@ def test_angular_fit(skm, orc, dg):
         skm.fit(cuda(X), 40, 3, 3, skm.FitOptions(R=cuda(R), angular=True, sample_frac=0.5))
     with pytest.raises(skm.SkmError):
         skm.assign(cuda(X), cuda(Y), None, 0, skm.FitOptions(R=cuda(R), angular=True))
+
+
+def test_incremental_update_matches_the_full_one(skm, orc, dg):
+    """Once few points change cluster, the centroid update corrects the cluster sums of the previous update by the
+    rows that joined and left.  The result must be that of recomputing every sum from all points (fp64 sums, so
+    equal up to the last bit of the fp32 mean), and it must still match the oracle."""
+    X = dg.mixture(40_000, 96, 50, 41, "linear").numpy()
+    R = orc.random_rotation(96, 41)
+    k, iters = 64, 9
+    a = skm.fit(cuda(X), k, iters, 4, skm.FitOptions(R=cuda(R), eps0=EPS0))
+    b = skm.fit(cuda(X), k, iters, 4, skm.FitOptions(R=cuda(R), eps0=EPS0, full_update=True))
+    assert a.timing["inc_updates"] >= 3 and b.timing["inc_updates"] == 0
+    assert [r["changed"] for r in a.trace] == [r["changed"] for r in b.trace]
+    assert torch.equal(a.assign, b.assign)
+    assert rel_l2(a.centroids.cpu().numpy(), b.centroids.cpu().numpy()) < 1e-6
+    ref = orc.fit(X, k, iters, 4, orc.FitParams(eps0=EPS0), R=R)
+    check_assignment(a.assign.cpu().numpy(), ref.assign, orc.rotate(X, R), ref.centroids_rot,
+                     own=(X, a.centroids.cpu().numpy()))
+    check_centroids(a.centroids.cpu().numpy(), ref.centroids, a.assign.cpu().numpy(), ref.assign)
+    # an empty cluster that is re-seeded by a split must be handled by both paths alike
+    idx = orc.sample_rows(2, len(X), k)
+    idx[1] = idx[0]
+    c = skm.fit(cuda(X), k, iters, 4, skm.FitOptions(R=cuda(R), eps0=EPS0, init_idx=list(idx)))
+    d = skm.fit(cuda(X), k, iters, 4, skm.FitOptions(R=cuda(R), eps0=EPS0, init_idx=list(idx), full_update=True))
+    assert c.trace[0]["nempty"] == 1 and torch.equal(c.assign, d.assign)
+    assert rel_l2(c.centroids.cpu().numpy(), d.centroids.cpu().numpy()) < 1e-6
