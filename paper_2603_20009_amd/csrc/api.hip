@@ -279,7 +279,6 @@ struct Ctx {
   int32_t *assign = nullptr, *prev = nullptr;
   Pair *pairs = nullptr;
   int64_t pair_cap = 0, sub_cap = 0, chunk_rows = 0;
-  uint32_t page_shift = 12, pages_part = 0;   // the list parts are cut into pages of 2^page_shift slots
   int32_t nchunks = 0;
   unsigned int emit_max = 0;         // a tile with at most this many alive pairs goes to the gather kernel
   unsigned int *counters = nullptr;  // per chunk the fill counters of the sub-lists, then [1] error flag (overflow / unset point)
@@ -323,28 +322,17 @@ struct Ctx {
     const int64_t per_tile = std::max<int64_t>(emit_max, 1);
     if (pair_budget <= 0) pair_budget = (int64_t)1 << 29;
     const int64_t col_tiles = progressive_tiles(1, k);
-    // A workgroup appends to a page of the list that it owns and draws a new page when the next tile does not fit, so a
-    // page (a power of two, at least emit_max) may stay partly empty: two consecutive pages of a workgroup always hold
-    // more than one page of pairs, hence the factor 2 below.
-    page_shift = 12;
-    while (((int64_t)1 << page_shift) < per_tile) ++page_shift;
-    const int64_t page = (int64_t)1 << page_shift;
-    int64_t row_tiles = std::max<int64_t>(pair_budget / (2 * per_tile * col_tiles), 1);
+    int64_t row_tiles = std::max<int64_t>(pair_budget / (per_tile * col_tiles), 1);
     row_tiles = std::min<int64_t>(row_tiles, std::max<int64_t>(((1 << 24) - 1) / col_tiles, 1));  // launch size limit
     chunk_rows = std::min<int64_t>(row_tiles * 128, (n + 127) / 128 * 128);
     nchunks = (int32_t)((n + chunk_rows - 1) / chunk_rows);
     // each of the kSubLists parts must hold what the tiles of one XCD can hand over
     const int64_t tiles_chunk = progressive_tiles(std::min<int64_t>(chunk_rows, n), k);
-    const int64_t tiles_part = (tiles_chunk + kSubLists - 1) / kSubLists;
-    const int64_t wgs_part = (progressive_workgroups(tiles_chunk) + kSubLists - 1) / kSubLists;
-    const int64_t pages = std::min<int64_t>(tiles_part, (2 * tiles_part * per_tile + page - 1) / page) + wgs_part + 1;
-    pages_part = (uint32_t)pages;
-    sub_cap = pages * page;
+    sub_cap = ((tiles_chunk + kSubLists - 1) / kSubLists) * per_tile;
     pair_cap = sub_cap * kSubLists;
     if (pair_cap >= ((int64_t)1 << 32)) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
     HIPCHK(pool.get(&pairs, (size_t)pair_cap));
-    // per chunk of rows: pages drawn per part, tile counters per XCD, slots used per page
-    ncounters = (size_t)nchunks * ((kSubLists + 8) * kSubListStride + (size_t)kSubLists * pages_part);
+    ncounters = (size_t)nchunks * (kSubLists + 8) * kSubListStride;   // list fill counters, then tile counters
     HIPCHK(pool.get(&counters, ncounters + 1));
     HIPCHK(pool.get(&ratio_dev, (size_t)kMaxBlocks + 1));
     HIPCHK(pool.get(&scal, (size_t)SC_COUNT * kStatReplicas));
@@ -454,16 +442,13 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     g.ratio = c.ratio_dev; g.tau = c.tau; g.prev = c.prev; g.row_base = r0;
     unsigned int *fill = c.counters + (size_t)ch * kSubLists * kSubListStride;
     g.tile_counter = c.counters + ((size_t)c.nchunks * kSubLists + (size_t)ch * 8) * kSubListStride;
-    unsigned int *page_fill = c.counters + (size_t)c.nchunks * (kSubLists + 8) * kSubListStride +
-                              (size_t)ch * kSubLists * c.pages_part;
     g.pairs = c.pairs; g.pair_count = fill; g.sub_capacity = (unsigned int)c.sub_cap;
-    g.page_fill = page_fill; g.page_shift = c.page_shift; g.pages_per_part = c.pages_part;
     g.overflow = c.counters + c.ncounters; g.emit_max = c.emit_max;
     g.best = c.best; g.scal = c.scal; g.block_stats = c.block_stats ? 1 : 0;
     HIPCHK(launch_progressive(g, c.st));
     tm.mark(ST_GEMM);
     if (c.emit_max > 0) {
-      PruneArgs pa{c.pairs, fill, page_fill, c.page_shift, c.pages_part, (unsigned int)c.sub_cap, c.Xr, c.ldx, c.Ypdx, c.k, dprime, c.ds, nb, c.ratio_dev,
+      PruneArgs pa{c.pairs, fill, (unsigned int)c.sub_cap, c.Xr, c.ldx, c.Ypdx, c.k, dprime, c.ds, nb, c.ratio_dev,
                    c.best, c.scal, c.block_stats ? 1 : 0};
       HIPCHK(launch_prune(pa, c.st));
       tm.mark(ST_PRUNE);

@@ -60,7 +60,6 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ unsigned long long s_dead[NT];   // per thread: accumulator elements that start dead (the incumbent)
   __shared__ unsigned int s_cnt[2];
   __shared__ unsigned int s_wcnt[5];
-  __shared__ unsigned int s_page[3];   // hand-over list page of this workgroup: page number, next free slot, end
   __shared__ int s_q[4];   // ring of tile numbers drawn from the XCD's counter, two tiles ahead of the one in work
 
   const int tid = threadIdx.x;
@@ -93,7 +92,6 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   unsigned long long *sc = g.scal + (size_t)(blockIdx.x & (kStatReplicas - 1)) * SC_COUNT;
   for (int m = tid; m <= g.nb; m += NT) s_ratio[m] = g.ratio[m];
   if (tid < 2) s_cnt[tid] = 0u;
-  if (tid == 0) { s_page[0] = 0xffffffffu; s_page[1] = 0u; s_page[2] = 0u; }
   s_dead[tid] = 0ull;
 
   // staging: thread (st_row, st_kq) moves dims 4 st_kq .. + 3 of tile rows st_row + 32 s.  The 8-lane groups of a
@@ -172,20 +170,6 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     nbv[j] = fmaf(sumsq(rb[j]), fz, nbv[j]);
     load_b(j, kk2);
   };
-  // First slab of a tile (already requested) -> LDS buffer 0, prefix norms restarted, second slab requested.
-  auto commit_slab0 = [&]() {
-#pragma unroll
-    for (int j = 0; j < A_F4; ++j) na[j] = 0.f;
-#pragma unroll
-    for (int j = 0; j < B_F4; ++j) nbv[j] = 0.f;
-    const bool live0 = klive(koff);
-    const float fz = live0 ? 1.f : 0.f;
-    const unsigned int kk1 = kclamp(koff + BK);
-#pragma unroll
-    for (int j = 0; j < A_F4; ++j) stage_a(j, 0, live0 ? scale_a : 0.f, fz, kk1);
-#pragma unroll
-    for (int j = 0; j < B_F4; ++j) stage_b(j, 0, live0 ? scale_b : 0.f, fz, kk1);
-  };
   // prefix norms of the rows / columns of this tile over the dimensions staged so far
   auto publish_norms = [&](float ratio) {
 #pragma unroll
@@ -221,12 +205,24 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   aim(rt * BM, ct * BN);
   gload(koff);
   load_rows(rt * BM);
-  commit_slab0();
 
   for (int tile_no = 0;; ++tile_no) {
     const int row0 = rt * BM, col0 = ct * BN;
-    // ---- per-row data of this tile (its first slab was staged, and its second requested, while the previous tile
-    // was being written out: see the end of the loop)
+    // ---- commit the prefetched first slab and per-row data of this tile
+#pragma unroll
+    for (int s = 0; s < A_F4; ++s) na[s] = 0.f;
+#pragma unroll
+    for (int s = 0; s < B_F4; ++s) nbv[s] = 0.f;
+    {
+      // slab 0 of this tile arrived while the previous tile was written out; slab 1 is requested as slab 0 is staged
+      const bool live0 = klive(koff);
+      const float fz = live0 ? 1.f : 0.f;
+      const unsigned int kk1 = kclamp(koff + BK);
+#pragma unroll
+      for (int j = 0; j < A_F4; ++j) stage_a(j, 0, live0 ? scale_a : 0.f, fz, kk1);
+#pragma unroll
+      for (int j = 0; j < B_F4; ++j) stage_b(j, 0, live0 ? scale_b : 0.f, fz, kk1);
+    }
     if (tid < BM) {
       s_tau[tid] = tau_reg;
       s_prev[tid] = prev_reg;
@@ -412,7 +408,6 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     q = s_q[(tile_no + 1) & 3];
     const bool more = q < xcount;
     int nrt_ = 0, nct_ = 0;
-    bool committed = false;
     if (more) {
       tile_rc(q, nrt_, nct_);
       nrt_ = __builtin_amdgcn_readfirstlane(nrt_);
@@ -452,50 +447,23 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
           __builtin_amdgcn_sched_barrier(0);
         }
     } else if (fin_mode == 2) {
-      // sparse enough: hand the alive pairs to the gather kernel, which resumes at block fin_m.  They go to the
-      // list part of this workgroup's XCD, into a page that this workgroup owns; only when the page cannot take
-      // them is the next page drawn from the part's counter, so most tiles need no round trip to memory here.
+      // sparse enough: hand the alive pairs to the gather kernel, which resumes at block fin_m.
+      // One reservation per tile in the sub-list of this workgroup's XCD.
       int wtot = __popcll(bits);
 #pragma unroll
       for (int sh = 1; sh < 64; sh <<= 1) wtot += __shfl_xor(wtot, sh, 64);
       if (lane == 0) s_wcnt[wave] = (unsigned int)wtot;
       __syncthreads();
-      unsigned int fresh = 0u;
-      bool need_page = false;
       if (tid == 0) {
         const unsigned int tot = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
-        need_page = s_page[1] + tot > s_page[2];
-        if (need_page) {
-          // close the page in use (the gather kernel reads how far it was filled) and draw the next one
-          if (s_page[0] != 0xffffffffu)
-            g.page_fill[xcd * g.pages_per_part + s_page[0]] = s_page[1] - (s_page[0] << g.page_shift);
-          fresh = atomicAdd(g.pair_count + xcd * kSubListStride, 1u);
-        }
-      }
-      if (more) {
-        commit_slab0();   // the next tile's first slab, while the page number (if one was drawn) is on its way
-        committed = true;
-      }
-      if (tid == 0) {
-        const unsigned int tot = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
-        if (need_page) {
-          if (fresh >= g.pages_per_part) {
-            *g.overflow = 1u;
-            s_page[0] = 0xffffffffu;
-            s_page[1] = 0u;
-            s_page[2] = 0u;
-          } else {
-            s_page[0] = fresh;
-            s_page[1] = fresh << g.page_shift;
-            s_page[2] = (fresh + 1u) << g.page_shift;
-          }
-        }
-        if (s_page[1] + tot > s_page[2]) {
-          s_wcnt[4] = 0xffffffffu;
+        unsigned int base = atomicAdd(g.pair_count + xcd * kSubListStride, tot);
+        if ((unsigned long long)base + tot > (unsigned long long)g.sub_capacity) {
+          *g.overflow = 1u;
+          base = 0xffffffffu;
         } else {
-          s_wcnt[4] = xcd * g.sub_capacity + s_page[1];
-          s_page[1] += tot;
+          base += xcd * g.sub_capacity;
         }
+        s_wcnt[4] = base;
       }
       __syncthreads();
       unsigned int run = s_wcnt[4];
@@ -529,14 +497,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
     }
 
-    if (more && !committed) commit_slab0();
-    if (!more) {
-      // the page in use is closed here: the barrier orders the last update of its fill before this read
-      __syncthreads();
-      if (tid == 0 && s_page[0] != 0xffffffffu)
-        g.page_fill[xcd * g.pages_per_part + s_page[0]] = s_page[1] - (s_page[0] << g.page_shift);
-      break;
-    }
+    if (!more) break;
     rt = nrt_;
     ct = nct_;
     if (tid == 0) s_q[(tile_no + 2) & 3] = (int)drawn;
@@ -551,28 +512,21 @@ hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
       g.N > (1 << 24))
     return hipErrorInvalidValue;
   constexpr size_t smem = (size_t)2 * (BM + BN) * LS * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
+  static int wgs = 0;
+  if (!wgs) {
     hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (rc != hipSuccess) return rc;
-    attr_set = true;
+    int dev = 0, cus = 256;
+    (void)hipGetDevice(&dev);
+    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    wgs = 2 * cus;   // two workgroups per CU (LDS and registers allow no more)
   }
   const int64_t ntiles = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (ntiles > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (g.emit_max > (1u << g.page_shift) || (uint64_t)g.pages_per_part << g.page_shift != g.sub_capacity)
-    return hipErrorInvalidValue;
-  const int64_t grid = progressive_workgroups(ntiles);   // two workgroups per CU (LDS and registers allow no more)
+  const int64_t grid = std::max<int64_t>(8, std::min<int64_t>(wgs, (ntiles + 7) / 8 * 8));
   hipLaunchKernelGGL(progressive_kernel, dim3((unsigned)grid), dim3(NT), smem, st, g);
   return hipGetLastError();
-}
-
-// workgroups of a launch over `tiles` tiles (two per CU, in multiples of the 8 XCDs)
-int64_t progressive_workgroups(int64_t tiles) {
-  int dev = 0, cus = 256;
-  (void)hipGetDevice(&dev);
-  (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-  return std::max<int64_t>(8, std::min<int64_t>(2 * (int64_t)cus, (tiles + 7) / 8 * 8));
 }
 
 int64_t progressive_tiles(int64_t rows, int32_t k) { return ((rows + BM - 1) / BM) * (int64_t)((k + BN - 1) / BN); }

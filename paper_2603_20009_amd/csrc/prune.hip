@@ -45,20 +45,11 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
   // the part of its own XCD, so those rows and blocks are fetched into one L2 only and found there again.
   static_assert(kSubLists == 8, "one part per XCD");
   const unsigned int part = blockIdx.x & 7u;
-  // the part is a run of pages, each filled from its start by the one workgroup that owned it
-  const unsigned int total = a.count[part * kSubListStride] << a.page_shift;
+  const unsigned int total = a.count[part * kSubListStride];
   const Pair *list = a.pairs + (size_t)part * a.sub_capacity;
-  const unsigned int *fill = a.page_fill + (size_t)part * a.pages_per_part;
-  const unsigned int page_mask = (1u << a.page_shift) - 1u;
-  auto used = [&](unsigned int slot) { return (slot & page_mask) < fill[slot >> a.page_shift]; };
-  // next used slot at or after `slot` on this group's stride (slots past the fill of a page are skipped)
-  auto seek = [&](unsigned int slot, unsigned int stride) {
-    while (slot < total && !used(slot)) slot += stride;
-    return slot;
-  };
   const unsigned int ngroups = (gridDim.x >> 3) * (PRUNE_THREADS / PAIR_LANES);
   const int q = tid & (PAIR_LANES - 1);
-  unsigned int p = seek((blockIdx.x >> 3) * (PRUNE_THREADS / PAIR_LANES) + (tid / PAIR_LANES), ngroups);
+  unsigned int p = (blockIdx.x >> 3) * (PRUNE_THREADS / PAIR_LANES) + (tid / PAIR_LANES);
   bool active = p < total;
   int i = 0, j = 0, m = 0;
   float acc = 0.f, tau = 0.f;
@@ -71,7 +62,7 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
     tau = pr.tau;
   };
   if (active) unpack(list[p]);
-  unsigned int pn = active ? seek(p + ngroups, ngroups) : total;   // the entry after this one, requested ahead of its use
+  unsigned int pn = p + ngroups;   // the entry after this one, requested ahead of its use
   Pair nx = {0, 0, 0.f, 0.f};
   if (pn < total) nx = list[pn];
   while (__any(active)) {
@@ -115,7 +106,7 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
         active = p < total;
         if (active) {
           unpack(nx);
-          pn = seek(p + ngroups, ngroups);
+          pn = p + ngroups;
           if (pn < total) nx = list[pn];
         }
       }

@@ -107,10 +107,8 @@ struct ProgArgs {
   const float *tau;        // [n]
   const int32_t *prev;     // [n] incumbent (never a challenger)
   int64_t row_base;
-  Pair *pairs;             // kSubLists parts of sub_capacity slots each, every part cut into pages of 2^page_shift slots
-  unsigned int *pair_count;   // [kSubLists * kSubListStride] pages drawn from every part; zero before the launch
-  unsigned int *page_fill;    // [kSubLists][pages_per_part] slots used in every page; zero before the launch
-  unsigned int page_shift, pages_per_part;   // a page holds at least emit_max slots; sub_capacity = pages_per_part << page_shift
+  Pair *pairs;             // kSubLists parts of sub_capacity slots each
+  unsigned int *pair_count;   // [kSubLists * kSubListStride] fill counters of the parts
   unsigned int *tile_counter; // [8 * kSubListStride] next tile of every XCD's range; zero before the launch
   unsigned int sub_capacity;
   unsigned int *overflow;
@@ -121,15 +119,12 @@ struct ProgArgs {
 };
 hipError_t launch_progressive(const ProgArgs &g, hipStream_t st);
 int64_t progressive_tiles(int64_t rows, int32_t k);
-int64_t progressive_workgroups(int64_t tiles);
 int32_t progressive_tile_pairs();
 
 // ---------------------------------------------------------------- pruning
 struct PruneArgs {
-  const Pair *pairs;           // kSubLists parts of sub_capacity slots each, in pages of 2^page_shift slots
-  const unsigned int *count;   // [kSubLists * kSubListStride] pages drawn from every part
-  const unsigned int *page_fill;   // [kSubLists][pages_per_part] slots used in every page
-  unsigned int page_shift, pages_per_part;
+  const Pair *pairs;           // kSubLists parts of sub_capacity slots each
+  const unsigned int *count;   // [kSubLists * kSubListStride] fill counters
   unsigned int sub_capacity;
   const float *Xr;       // rotated points, row stride ldx, zero padded to ds columns
   int64_t ldx;
