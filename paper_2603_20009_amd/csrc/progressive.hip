@@ -469,15 +469,26 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       unsigned int run = s_wcnt[4];
       if (run != 0xffffffffu && wtot > 0) {
         for (int w = 0; w < wave; ++w) run += s_wcnt[w];
+        // element slots in which any lane of this wavefront holds an alive pair (a sparse tile has few): the 64
+        // slots below are then skipped by a scalar test each
+        unsigned int any_lo = (unsigned int)bits, any_hi = (unsigned int)(bits >> 32);
+#pragma unroll
+        for (int sh = 1; sh < 64; sh <<= 1) {
+          any_lo |= __shfl_xor(any_lo, sh, 64);
+          any_hi |= __shfl_xor(any_hi, sh, 64);
+        }
+        const unsigned long long any = ((unsigned long long)__builtin_amdgcn_readfirstlane(any_hi) << 32) |
+                                       (unsigned long long)__builtin_amdgcn_readfirstlane(any_lo);
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
           for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
+              if (!((any >> ((a * TN + b) * 16 + v)) & 1ull)) continue;
               const bool keep = (bits >> ((a * TN + b) * 16 + v)) & 1ull;
               const unsigned long long mk = __ballot(keep);
-              if (mk) {   // wave-uniform: most element slots of a sparse tile hold no alive pair
+              if (mk) {
                 if (keep) {
                   const int rl = row_of(a, v);
                   const unsigned int pos =
