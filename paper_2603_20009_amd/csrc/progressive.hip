@@ -163,11 +163,13 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   auto stage_a = [&](int j, int buf, float fa, float fz, unsigned int kk2) {
     split_store(As + (buf * BM + st_row + ROWS_PASS * j) * LS, ra[j], fa);
     na[j] = fmaf(sumsq(ra[j]), fz, na[j]);
+    asm volatile("" : "+v"(na[j]));   // the sum is taken here, before the registers are re-aimed (not sunk to the loop end)
     load_a(j, kk2);
   };
   auto stage_b = [&](int j, int buf, float fb, float fz, unsigned int kk2) {
     split_store(Bs + (buf * BN + st_row + ROWS_PASS * j) * LS, rb[j], fb);
     nbv[j] = fmaf(sumsq(rb[j]), fz, nbv[j]);
+    asm volatile("" : "+v"(nbv[j]));
     load_b(j, kk2);
   };
   // prefix norms of the rows / columns of this tile over the dimensions staged so far
@@ -322,11 +324,11 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         __builtin_amdgcn_sched_barrier(0);
         mma4(ah, bh);
         stage_a(0, buf ^ 1, fa, fz, kk2);
-        mix(std::integral_constant<int, 5>());
+        mix(std::integral_constant<int, 6>());
         __builtin_amdgcn_sched_barrier(0);
         mma4(al, bh);
         stage_a(1, buf ^ 1, fa, fz, kk2);
-        mix(std::integral_constant<int, 5>());
+        mix(std::integral_constant<int, 6>());
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < 2; ++t) { al[t] = frag(Ab, 1, 1, t); bh[t] = frag(Bb, 1, 0, t); }
@@ -334,23 +336,23 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         stage_a(2, buf ^ 1, fa, fz, kk2);
         stage_a(3, buf ^ 1, fa, fz, kk2);
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-        mix(std::integral_constant<int, 9>());
+        mix(std::integral_constant<int, 11>());
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < 2; ++t) { ah[t] = frag(Ab, 1, 0, t); bl[t] = frag(Bb, 1, 1, t); }
         mma4(al, bh);
         stage_b(0, buf ^ 1, fb, fz, kk2);
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-        mix(std::integral_constant<int, 5>());
+        mix(std::integral_constant<int, 6>());
         __builtin_amdgcn_sched_barrier(0);
         mma4(ah, bl);
         stage_b(1, buf ^ 1, fb, fz, kk2);
-        mix(std::integral_constant<int, 5>());
+        mix(std::integral_constant<int, 6>());
         __builtin_amdgcn_sched_barrier(0);
         mma4(ah, bh);
         stage_b(2, buf ^ 1, fb, fz, kk2);
         stage_b(3, buf ^ 1, fb, fz, kk2);
-        mix(std::integral_constant<int, 9>());
+        mix(std::integral_constant<int, 11>());
         __builtin_amdgcn_sched_barrier(0);
       }
       __syncthreads();
