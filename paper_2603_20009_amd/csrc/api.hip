@@ -273,6 +273,9 @@ struct Ctx {
   int64_t ldx = 0;
   float *Y = nullptr;         // centroids k x ds (rotated space)
   float *Ypdx = nullptr;
+  float *xnp = nullptr;       // [ds / 16][n] prefix norms of the points at every multiple of 16 dims, written by the
+  bool xnp_valid = false;     // first pruned step (the points of a context never change)
+  float *ynp = nullptr;       // [nb + 1][k] prefix norms of the centroids at the checkpoints of the current step
   float *ynorm = nullptr;
   float *tau = nullptr, *dist = nullptr;
   unsigned long long *best = nullptr;
@@ -308,6 +311,8 @@ struct Ctx {
     HIPCHK(pool.get(&Y, (size_t)k * ds));
     const int32_t nbmax = (ds - 16 + kBlockDims - 1) / kBlockDims + 1;
     HIPCHK(pool.get(&Ypdx, (size_t)nbmax * k * kBlockDims));
+    HIPCHK(pool.get(&xnp, (size_t)(ds / 16) * n));
+    HIPCHK(pool.get(&ynp, (size_t)nbmax * k));
     HIPCHK(pool.get(&ynorm, (size_t)k));
     HIPCHK(pool.get(&tau, (size_t)n));
     HIPCHK(pool.get(&dist, (size_t)n));
@@ -412,7 +417,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   const int32_t nb = (c.d - dprime + kBlockDims - 1) / kBlockDims;
   if (nb > kMaxBlocks) return fail(SKM_EINTERNAL, "too many trailing blocks");
   tm.mark(ST_NONE);
-  HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, dprime, c.ynorm, dprime, nb, c.Ypdx, c.st));
+  HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, dprime, c.ynorm, dprime, nb, c.Ypdx, c.st, c.ynp));
   if (int rc = c.measure_y()) return rc;
   // theta ratio at checkpoint m: t_m = min(d, d' + 64 m) dimensions seen
   float *ratio = c.ratio_host;
@@ -427,7 +432,8 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, nullptr, nullptr, c.counters + c.ncounters, c.st));
     tm.mark(ST_GEMM);
   }
-  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st));
+  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st, c.xnp_valid ? nullptr : c.xnp));
+  c.xnp_valid = true;
   HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT * kStatReplicas, c.st));
   HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
   tm.mark(ST_TAU);
@@ -440,6 +446,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     g.a_absmax = c.amax + Ctx::AM_XR; g.b_absmax = c.amax + Ctx::AM_Y;
     g.ds = c.ds; g.d = c.d; g.dprime = dprime; g.nb = nb;
     g.ratio = c.ratio_dev; g.tau = c.tau; g.prev = c.prev; g.row_base = r0;
+    g.xnp = c.xnp; g.xn_stride = c.n; g.ynp = c.ynp;
     unsigned int *fill = c.counters + (size_t)ch * kSubLists * kSubListStride;
     g.tile_counter = c.counters + ((size_t)c.nchunks * kSubLists + (size_t)ch * 8) * kSubListStride;
     g.pairs = c.pairs; g.pair_count = fill; g.sub_capacity = (unsigned int)c.sub_cap;
@@ -1138,9 +1145,9 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
     };
     const int nworkers = (int)std::min<int32_t>(4, km);   // the device exposes four hardware queues to a process
     std::vector<Worker> workers((size_t)nworkers);
-    // workspace of the largest fine fit, generously: per point the padded row copy and the per-point arrays,
-    // per centroid three padded rows, plus the hand-over list of a small problem
-    const size_t want = (size_t)nmax * ((size_t)ds * 4 + 96) + (size_t)kmax * (size_t)ds * 24 + ((size_t)256 << 20);
+    // workspace of the largest fine fit, generously: per point the padded row copy, its table of prefix norms and
+    // the per-point arrays, per centroid three padded rows, plus the hand-over list of a small problem
+    const size_t want = (size_t)nmax * ((size_t)ds * 4 + (size_t)ds / 4 + 96) + (size_t)kmax * (size_t)ds * 24 + ((size_t)256 << 20);
     int dev = 0;
     HIPCHK(hipGetDevice(&dev));
     struct StreamGuard {

@@ -10,8 +10,9 @@
 // (distance, centroid) minimum if it beats tau_i.
 //
 // Partial distances come from the norm expansion ||x_t||^2 + ||y_t||^2 - 2 x_t.y_t (Section 3.1).
-// The prefix norms are a by-product of staging: every thread squares the float4 it moves into LDS,
-// and the lanes that share a tile row add up at each checkpoint.
+// The prefix norms at the checkpoints are inputs (xnp, ynp): passes that read every point and every
+// centroid anyway write them, so that this kernel, whose vector unit is the busy one, only
+// fetches one number per row and column and checkpoint.
 //
 // The kernel is persistent: two workgroups per CU take tiles from a per-XCD counter.  When a tile
 // ends, the first slab and the per-row data of the next tile are already being fetched while the
@@ -39,13 +40,6 @@ constexpr int ROWS_PASS = NT / F4_ROW;      // 32 tile rows per staging pass
 constexpr int A_F4 = BM / ROWS_PASS;        // 4
 constexpr int B_F4 = BN / ROWS_PASS;        // 4
 
-// sum over the 8 consecutive lanes that stage one tile row; all of them get the total
-__device__ inline float rowgroup_sum(float v) {
-  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
-  return v;
-}
 }  // namespace
 
 // Slabs of BK dimensions start at koff = -((BK - d' % BK) % BK), so that slab ends fall on every
@@ -106,16 +100,29 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // dead), dimensions outside [0, ds) are clamped into the row and multiplied by zero when staged.  With nothing
   // conditional around them the compiler can keep the loads of a whole slab in flight across a multiply step.
   float4 ra[A_F4], rb[B_F4];
-  float na[A_F4], nbv[B_F4];
   float tau_reg = 0.f;
   int prev_reg = -1;
   const float *baseA = g.A, *baseB = g.B;   // first row / column of the tile being loaded (uniform)
   int limA = 0, limB = 0;                   // last valid row / column of that tile, relative to its first (uniform)
+  // prefix norms: threads 0..127 fetch those of the tile's rows, threads 128..255 those of its columns
+  const float *npre = g.xnp;                // &norm[0][this thread's row or column]
+  const int64_t npre_stride = tid < BM ? g.xn_stride : (int64_t)g.N;
+  float nreg = 0.f;
   auto aim = [&](int row0, int col0) {
     baseA = g.A + (int64_t)row0 * g.lda;
     baseB = g.B + (int64_t)col0 * g.ldb;
     limA = g.M - 1 - row0;
     limB = g.N - 1 - col0;
+    npre = tid < BM ? g.xnp + g.row_base + row0 + min(tid, limA) : g.ynp + col0 + min(tid - BM, limB);
+  };
+  // Row of the norm tables that multiply step s needs if it ends on a checkpoint (any valid row otherwise): the
+  // points' table has a row per 16 dimensions, the centroids' a row per checkpoint of this step.
+  auto load_norm = [&](int s) {
+    const int td = koff + BK * (s + 1);
+    const bool end = s + 1 >= nslab;
+    const int px = ((end ? g.ds : min(max(td, 16), g.ds)) >> 4) - 1;
+    const int py = end ? g.nb : min(max((td - g.dprime) / kBlockDims, 0), g.nb);
+    nreg = npre[(int64_t)(tid < BM ? px : py) * npre_stride];
   };
   auto kclamp = [&](int k0) { return (unsigned int)min(max(k0 + 4 * st_kq, 0), g.ds - 4); };
   auto klive = [&](int k0) { return k0 + 4 * st_kq >= 0 && k0 + 4 * st_kq < g.ds; };
@@ -157,36 +164,23 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     *reinterpret_cast<uint2 *>(dst_row + 2 * st_kq) = hi;
     *reinterpret_cast<uint2 *>(dst_row + 16 + 2 * st_kq) = lo;
   };
-  auto sumsq = [](const float4 &v) { return fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, v.w * v.w))); };
-  // float4 j of the staged slab -> LDS buffer `buf` (prefix norms updated), then the same registers are aimed at the
-  // slab after it (element offset kk2), so that one register set carries two slabs: one being used, one in flight
-  auto stage_a = [&](int j, int buf, float fa, float fz, unsigned int kk2) {
+  // float4 j of the staged slab -> LDS buffer `buf`, then the same registers are aimed at the slab after it (element
+  // offset kk2), so that one register set carries two slabs: one being used, one in flight
+  auto stage_a = [&](int j, int buf, float fa, unsigned int kk2) {
     split_store(As + (buf * BM + st_row + ROWS_PASS * j) * LS, ra[j], fa);
-    na[j] = fmaf(sumsq(ra[j]), fz, na[j]);
-    asm volatile("" : "+v"(na[j]));   // the sum is taken here, before the registers are re-aimed (not sunk to the loop end)
     load_a(j, kk2);
   };
-  auto stage_b = [&](int j, int buf, float fb, float fz, unsigned int kk2) {
+  auto stage_b = [&](int j, int buf, float fb, unsigned int kk2) {
     split_store(Bs + (buf * BN + st_row + ROWS_PASS * j) * LS, rb[j], fb);
-    nbv[j] = fmaf(sumsq(rb[j]), fz, nbv[j]);
-    asm volatile("" : "+v"(nbv[j]));
     load_b(j, kk2);
   };
-  // prefix norms of the rows / columns of this tile over the dimensions staged so far
+  // the prefix norms fetched during the previous step -> LDS, with the row's threshold theta(t_m, tau) - ||x_t||^2
   auto publish_norms = [&](float ratio) {
-#pragma unroll
-    for (int s = 0; s < A_F4; ++s) {
-      const float v = rowgroup_sum(na[s]);
-      if (st_kq == 0) {
-        const int rl = st_row + ROWS_PASS * s;
-        s_xn[rl] = v;
-        s_thr[rl] = ratio * s_tau[rl] - v;
-      }
-    }
-#pragma unroll
-    for (int s = 0; s < B_F4; ++s) {
-      const float v = rowgroup_sum(nbv[s]);
-      if (st_kq == 0) s_yn[st_row + ROWS_PASS * s] = v;
+    if (tid < BM) {
+      s_xn[tid] = nreg;
+      s_thr[tid] = ratio * tau_reg - nreg;
+    } else {
+      s_yn[tid - BM] = nreg;
     }
   };
   auto row_of = [&](int a, int v) { return wm * WTM + a * 32 + 8 * (v >> 2) + 4 * kh + (v & 3); };
@@ -205,25 +199,21 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   rt = __builtin_amdgcn_readfirstlane(rt);
   ct = __builtin_amdgcn_readfirstlane(ct);
   aim(rt * BM, ct * BN);
+  load_norm(0);
   gload(koff);
   load_rows(rt * BM);
 
   for (int tile_no = 0;; ++tile_no) {
     const int row0 = rt * BM, col0 = ct * BN;
     // ---- commit the prefetched first slab and per-row data of this tile
-#pragma unroll
-    for (int s = 0; s < A_F4; ++s) na[s] = 0.f;
-#pragma unroll
-    for (int s = 0; s < B_F4; ++s) nbv[s] = 0.f;
     {
       // slab 0 of this tile arrived while the previous tile was written out; slab 1 is requested as slab 0 is staged
       const bool live0 = klive(koff);
-      const float fz = live0 ? 1.f : 0.f;
       const unsigned int kk1 = kclamp(koff + BK);
 #pragma unroll
-      for (int j = 0; j < A_F4; ++j) stage_a(j, 0, live0 ? scale_a : 0.f, fz, kk1);
+      for (int j = 0; j < A_F4; ++j) stage_a(j, 0, live0 ? scale_a : 0.f, kk1);
 #pragma unroll
-      for (int j = 0; j < B_F4; ++j) stage_b(j, 0, live0 ? scale_b : 0.f, fz, kk1);
+      for (int j = 0; j < B_F4; ++j) stage_b(j, 0, live0 ? scale_b : 0.f, kk1);
     }
     if (tid < BM) {
       s_tau[tid] = tau_reg;
@@ -305,15 +295,16 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const bool check = !last && tdone >= g.dprime && tdone < g.d && ((tdone - g.dprime) & (kBlockDims - 1)) == 0;
       const bool cp = check || last;
       const int m = last ? g.nb : (tdone - g.dprime) / kBlockDims;   // checkpoint index, t_m = min(d, d' + 64 m)
-      // the prefix norms cover slabs 0..s here (slab s was staged during the previous step): what the checkpoint
-      // after this step needs; they are published before this step adds slab s + 1
+      // the norms of checkpoint m were requested one step ago (or with the tile's first slab); every step requests
+      // those of the step after it, needed or not, so that the request is never behind a branch
       if (cp) publish_norms(s_ratio[m]);
+      load_norm(s + 1);
       const float *Ab = As + (buf * BM + wm * WTM + r32) * LS;
       const float *Bb = Bs + (buf * BN + wn * WTN + r32) * LS;
       {
         // (the last step of a tile stages a slab past the end: all zeros, into a buffer nobody reads again)
         const bool live1 = klive(koff + (s + 1) * BK);
-        const float fa = live1 ? scale_a : 0.f, fb = live1 ? scale_b : 0.f, fz = live1 ? 1.f : 0.f;
+        const float fa = live1 ? scale_a : 0.f, fb = live1 ? scale_b : 0.f;
         const unsigned int kk2 = kclamp(koff + (s + 2) * BK);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -323,35 +314,35 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
         __builtin_amdgcn_sched_barrier(0);
         mma4(ah, bh);
-        stage_a(0, buf ^ 1, fa, fz, kk2);
+        stage_a(0, buf ^ 1, fa, kk2);
         mix(std::integral_constant<int, 6>());
         __builtin_amdgcn_sched_barrier(0);
         mma4(al, bh);
-        stage_a(1, buf ^ 1, fa, fz, kk2);
+        stage_a(1, buf ^ 1, fa, kk2);
         mix(std::integral_constant<int, 6>());
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < 2; ++t) { al[t] = frag(Ab, 1, 1, t); bh[t] = frag(Bb, 1, 0, t); }
         mma4(ah, bl);
-        stage_a(2, buf ^ 1, fa, fz, kk2);
-        stage_a(3, buf ^ 1, fa, fz, kk2);
+        stage_a(2, buf ^ 1, fa, kk2);
+        stage_a(3, buf ^ 1, fa, kk2);
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
         mix(std::integral_constant<int, 11>());
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < 2; ++t) { ah[t] = frag(Ab, 1, 0, t); bl[t] = frag(Bb, 1, 1, t); }
         mma4(al, bh);
-        stage_b(0, buf ^ 1, fb, fz, kk2);
+        stage_b(0, buf ^ 1, fb, kk2);
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
         mix(std::integral_constant<int, 6>());
         __builtin_amdgcn_sched_barrier(0);
         mma4(ah, bl);
-        stage_b(1, buf ^ 1, fb, fz, kk2);
+        stage_b(1, buf ^ 1, fb, kk2);
         mix(std::integral_constant<int, 6>());
         __builtin_amdgcn_sched_barrier(0);
         mma4(ah, bh);
-        stage_b(2, buf ^ 1, fb, fz, kk2);
-        stage_b(3, buf ^ 1, fb, fz, kk2);
+        stage_b(2, buf ^ 1, fb, kk2);
+        stage_b(3, buf ^ 1, fb, kk2);
         mix(std::integral_constant<int, 11>());
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -415,6 +406,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       nrt_ = __builtin_amdgcn_readfirstlane(nrt_);
       nct_ = __builtin_amdgcn_readfirstlane(nct_);
       aim(nrt_ * BM, nct_ * BN);
+      load_norm(0);
       gload(koff);
       load_rows(nrt_ * BM);
     }

@@ -107,6 +107,9 @@ struct ProgArgs {
   const float *tau;        // [n]
   const int32_t *prev;     // [n] incumbent (never a challenger)
   int64_t row_base;
+  const float *xnp;        // [ds / 16][xn_stride] ||x_i[0 : 16 (p + 1))||^2, indexed like tau (row_base + tile row)
+  int64_t xn_stride;
+  const float *ynp;        // [nb + 1][N] ||y_c[0 : t_m)||^2
   Pair *pairs;             // kSubLists parts of sub_capacity slots each
   unsigned int *pair_count;   // [kSubLists * kSubListStride] fill counters of the parts
   unsigned int *tile_counter; // [8 * kSubListStride] next tile of every XCD's range; zero before the launch
@@ -143,12 +146,16 @@ hipError_t launch_prune(const PruneArgs &a, hipStream_t st);
 // ---------------------------------------------------------------- streaming kernels
 // tau_i = ||x_i - y_{a_i}||^2 over all dims, best_i = pack(tau_i, a_i)
 // (Algorithm 1, "Initial pruning threshold").  Either output may be NULL.
+// With xnp ([ds / 16][n], ds a multiple of 16) the same pass writes the table of prefix norms
+// xnp[p][i] = ||x_i[0 : 16 (p + 1))||^2 that the progressive kernel reads at its checkpoints.
 hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
-                           const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st);
+                           const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st,
+                           float *xnp = nullptr);
 
 // ynorm[c] = ||Y[c][0:dn)||^2 and (if Ypdx) the block-major copy of the dims from dprime on.
+// ynp (optional, [nb + 1][k]): prefix norms of the centroids at the same checkpoints.
 hipError_t launch_prep_centroids(const float *Y, int64_t ldy, int32_t k, int32_t ds, int32_t dn, float *ynorm,
-                                 int32_t dprime, int32_t nb, float *Ypdx, hipStream_t st);
+                                 int32_t dprime, int32_t nb, float *Ypdx, hipStream_t st, float *ynp = nullptr);
 
 // every non-zero row of A scaled to unit Euclidean length, in place (cols, lda multiples of 4; A 16-byte aligned)
 hipError_t launch_normalize_rows(float *A, int64_t lda, int64_t rows, int32_t cols, hipStream_t st);

@@ -31,10 +31,45 @@ static int num_cus() {
 // float4 per lane (1 KiB per wavefront load); squared differences over all dims give tau_i.
 // NV = float4 loads per lane and operand (rows of up to 256 * NV floats): all loads of a row pair are
 // issued before the first use, so that a wavefront keeps 2 * NV KiB in flight.
+//
+// The same pass can emit the prefix norms of the point that the progressive kernel tests against: every
+// checkpoint t = d' + 64 m is a multiple of 16, so the table xnp[p][i] = ||x_i[0 : 16 (p + 1))||^2 serves any d',
+// and the points do not change during a fit, so it is written once (PrefixOut), by the first pass that has the rows
+// in registers anyway.  Lane l holds dims 4 l + 256 u .. + 3; a quad of lanes holds a 16-dim piece, and an
+// inclusive scan over the 16 quads of the wavefront (then over u) gives every quad the norm of the row up to the
+// end of its piece.
+struct PrefixOut {
+  float *xnp;        // [ds / 16][n] or NULL
+  int64_t n;
+  int32_t ds;
+};
+
+// inclusive scan over the 16 quads of a wavefront of a value that is equal within each quad
+__device__ inline float quad_scan64(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x114, 0xF, 0xF, false));  // row_shr:4
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x118, 0xF, 0xF, false));  // row_shr:8
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false));  // row_bcast:15 -> rows 1, 3
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false));  // row_bcast:31 -> rows 2, 3
+  return v;
+}
+__device__ inline float quad_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  return v;
+}
+// q = sum of squares of this lane's float4 at column c0 = 4 lane + 256 u; base = norm of the row before column 256 u.
+// Returns the norm of the row up to column 256 (u + 1).
+__device__ inline float emit_prefix(const PrefixOut &po, int64_t i, int lane, int u, float q, float base) {
+  const float upto = base + quad_scan64(quad_sum(q));   // norm up to the end of this quad's 16-dim piece
+  const int t = 256 * u + 16 * (lane >> 2) + 16;          // that end
+  if ((lane & 3) == 0 && t <= po.ds) po.xnp[(int64_t)((t >> 4) - 1) * po.n + i] = upto;
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, upto), 63));
+}
+
 template <int NV>
 __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t ldx, int64_t n, int32_t ds,
                                                        const float *Y, int64_t ldy, const int32_t *assign, float *tau,
-                                                       unsigned long long *best) {
+                                                       unsigned long long *best, PrefixOut po) {
   const int lane = threadIdx.x & 63;
   const int64_t nwaves = (int64_t)gridDim.x * 4;
   for (int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); i < n; i += nwaves) {
@@ -62,15 +97,33 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
         s = fmaf(dz, dz, s);
         s = fmaf(dw, dw, s);
       }
+      if (po.xnp) {
+        float base = 0.f;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+          if (256 * u >= ds) break;
+          const float q = fmaf(xv[u].x, xv[u].x, fmaf(xv[u].y, xv[u].y, fmaf(xv[u].z, xv[u].z, xv[u].w * xv[u].w)));
+          base = emit_prefix(po, i, lane, u, q, base);
+        }
+      }
     } else {
-      for (int c = lane * 4; c < ds; c += 256) {
-        const float4 xv = *reinterpret_cast<const float4 *>(x + c);
-        const float4 yv = *reinterpret_cast<const float4 *>(y + c);
+      float base = 0.f;
+      for (int c0 = 0; c0 < ds; c0 += 256) {
+        const int c = c0 + lane * 4;
+        float4 xv = make_float4(0.f, 0.f, 0.f, 0.f), yv = xv;
+        if (c < ds) {
+          xv = *reinterpret_cast<const float4 *>(x + c);
+          yv = *reinterpret_cast<const float4 *>(y + c);
+        }
         const float dx = xv.x - yv.x, dy = xv.y - yv.y, dz = xv.z - yv.z, dw = xv.w - yv.w;
         s = fmaf(dx, dx, s);
         s = fmaf(dy, dy, s);
         s = fmaf(dz, dz, s);
         s = fmaf(dw, dw, s);
+        if (po.xnp) {
+          const float q = fmaf(xv.x, xv.x, fmaf(xv.y, xv.y, fmaf(xv.z, xv.z, xv.w * xv.w)));
+          base = emit_prefix(po, i, lane, c0 >> 8, q, base);
+        }
       }
     }
     s = wave_sum(s);
@@ -82,15 +135,16 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
 }
 
 hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
-                           const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st) {
+                           const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st, float *xnp) {
   if (n <= 0) return hipSuccess;
   int64_t blocks = (n + 3) / 4;
   const int64_t cap = (int64_t)num_cus() * 32;
   if (blocks > cap) blocks = cap;
   const int nv = (ds + 255) / 256;
+  const PrefixOut po{xnp, n, ds};
 #define SKM_TAU_LAUNCH(NV)                                                                                          \
   hipLaunchKernelGGL(tau_init_kernel<NV>, dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, ds, Y, ldy, assign, \
-                     tau, best)
+                     tau, best, po)
   if (nv <= 1) SKM_TAU_LAUNCH(1);
   else if (nv <= 2) SKM_TAU_LAUNCH(2);
   else if (nv <= 3) SKM_TAU_LAUNCH(3);
@@ -107,8 +161,9 @@ hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, 
 // copied to Ypdx[m][c][0..63] (block m = dims dprime+64m ..), zero filled past the row.
 __global__ void __launch_bounds__(256) prep_centroids_kernel(const float *Y, int64_t ldy, int32_t k, int32_t ds,
                                                              int32_t dn, float *ynorm, int32_t dprime, int32_t nb,
-                                                             float *Ypdx) {
+                                                             float *Ypdx, float *ynp) {
   __shared__ float red[4];
+  __shared__ float piece[1024];   // ds <= 16384
   const int c = blockIdx.x;
   const float *y = Y + (int64_t)c * ldy;
   float s = 0.f;
@@ -117,6 +172,23 @@ __global__ void __launch_bounds__(256) prep_centroids_kernel(const float *Y, int
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
   __syncthreads();
   if (threadIdx.x == 0 && ynorm) ynorm[c] = (red[0] + red[1]) + (red[2] + red[3]);
+  if (ynp) {
+    // ||y[0 : t_m)||^2 at the checkpoints t_m = min(ds, d' + 64 m): sums of squares of the 16-dim pieces of the row
+    // in LDS, then thread m adds up the pieces below its checkpoint (d' is a multiple of 16; rows are short)
+    const int np = (ds + 15) / 16;
+    for (int p = threadIdx.x; p < np; p += 256) {
+      float acc = 0.f;
+      for (int j = 16 * p; j < min(ds, 16 * p + 16); ++j) acc = fmaf(y[j], y[j], acc);
+      piece[p] = acc;
+    }
+    __syncthreads();
+    for (int m = threadIdx.x; m <= nb; m += 256) {
+      const int t = m == nb ? ds : min(ds, dprime + kBlockDims * m);
+      float acc = 0.f;
+      for (int p = 0; p < (t + 15) / 16; ++p) acc += piece[p];
+      ynp[(int64_t)m * k + c] = acc;
+    }
+  }
   if (Ypdx) {
     for (int t = threadIdx.x; t < nb * kBlockDims; t += 256) {
       const int m = t / kBlockDims, qd = t % kBlockDims;
@@ -127,8 +199,8 @@ __global__ void __launch_bounds__(256) prep_centroids_kernel(const float *Y, int
 }
 
 hipError_t launch_prep_centroids(const float *Y, int64_t ldy, int32_t k, int32_t ds, int32_t dn, float *ynorm,
-                                 int32_t dprime, int32_t nb, float *Ypdx, hipStream_t st) {
-  hipLaunchKernelGGL(prep_centroids_kernel, dim3(k), dim3(256), 0, st, Y, ldy, k, ds, dn, ynorm, dprime, nb, Ypdx);
+                                 int32_t dprime, int32_t nb, float *Ypdx, hipStream_t st, float *ynp) {
+  hipLaunchKernelGGL(prep_centroids_kernel, dim3(k), dim3(256), 0, st, Y, ldy, k, ds, dn, ynorm, dprime, nb, Ypdx, ynp);
   return hipGetLastError();
 }
 
