@@ -89,6 +89,37 @@ struct Pool {
   }
 };
 
+// Page-locked host memory for the few numbers that every step reports to the host: copies into it are asynchronous,
+// so one wait per step covers all of them (a copy into pageable memory waits for its own staging).  Blocks are kept
+// in a per-thread cache and reused by later calls on that thread (the hierarchical fit runs hundreds of small fits);
+// worker threads release their cache before they end, that of a caller's thread stays until the process ends.
+struct PinnedCache {
+  std::vector<std::pair<void *, size_t>> idle;
+  void *take(size_t bytes, size_t *cap) {
+    for (size_t i = 0; i < idle.size(); ++i)
+      if (idle[i].second >= bytes) {
+        void *p = idle[i].first;
+        *cap = idle[i].second;
+        idle.erase(idle.begin() + (std::ptrdiff_t)i);
+        return p;
+      }
+    void *p = nullptr;
+    const size_t want = std::max<size_t>(bytes, (size_t)1 << 16);
+    if (hipHostMalloc(&p, want, hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    *cap = want;
+    return p;
+  }
+  void give(void *p, size_t cap) { idle.emplace_back(p, cap); }
+  void release() {
+    for (auto &b : idle) (void)hipHostFree(b.first);
+    idle.clear();
+  }
+};
+thread_local PinnedCache tl_pinned;
+
 struct Events {
   std::vector<hipEvent_t> ev;
   ~Events() {
@@ -300,14 +331,47 @@ struct Ctx {
   unsigned int *amax = nullptr;      // [AM_COUNT] magnitude bounds of the GEMM operands
   enum { AM_XR = 0, AM_Y = 1, AM_X = 2, AM_Q = 3, AM_QR = 4, AM_COUNT = 8 };
 
+  // what a step reports (page-locked, see PinnedCache): the step scalars, the objective, the error flag, the
+  // cluster sizes
+  void *rb_block = nullptr;
+  size_t rb_cap = 0;
+  Ctx() = default;
+  Ctx(const Ctx &) = delete;
+  Ctx &operator=(const Ctx &) = delete;
+  ~Ctx() {
+    if (rb_block) tl_pinned.give(rb_block, rb_cap);   // a context lives and dies on one thread
+  }
+  unsigned long long *rb_scal = nullptr;   // [SC_COUNT * kStatReplicas]
+  double *rb_obj = nullptr;
+  unsigned int *rb_flag = nullptr;
+  int32_t *rb_cnt = nullptr;               // [k]
+  bool rb_cnt_valid = false;               // rb_cnt holds the sizes of c.assign's clusters
+  int alloc_readback() {
+    const size_t nscal = (size_t)SC_COUNT * kStatReplicas;
+    if (!rb_block) rb_block = tl_pinned.take(nscal * 8 + 16 + sizeof(int32_t) * (size_t)k, &rb_cap);
+    char *h = static_cast<char *>(rb_block);
+    if (!h) return fail(SKM_EHIP, "hipHostMalloc failed for the step read-back block");
+    rb_scal = reinterpret_cast<unsigned long long *>(h);
+    rb_obj = reinterpret_cast<double *>(h + nscal * 8);
+    rb_flag = reinterpret_cast<unsigned int *>(h + nscal * 8 + 8);
+    rb_cnt = reinterpret_cast<int32_t *>(h + nscal * 8 + 16);
+    return SKM_OK;
+  }
+
   int alloc_bounds() {
     HIPCHK(pool.get(&amax, (size_t)AM_COUNT));
     return SKM_OK;
   }
   int measure_xr() { return measure_absmax(Xr, ldx, n, ds, amax + AM_XR, st); }
-  int measure_y() { return measure_absmax(Y, ds, k, ds, amax + AM_Y, st); }
+  bool y_amax_valid = false;   // amax[AM_Y] bounds the current Y (the update writes it; other changes of Y clear this)
+  int measure_y() {
+    if (y_amax_valid) return SKM_OK;
+    y_amax_valid = true;
+    return measure_absmax(Y, ds, k, ds, amax + AM_Y, st);
+  }
 
   int alloc_common(int64_t pair_budget, float dense_frac, bool need_update) {
+    if (int rc = alloc_readback()) return rc;
     HIPCHK(pool.get(&Y, (size_t)k * ds));
     const int32_t nbmax = (ds - 16 + kBlockDims - 1) / kBlockDims + 1;
     HIPCHK(pool.get(&Ypdx, (size_t)nbmax * k * kBlockDims));
@@ -397,14 +461,14 @@ int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
   HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, nullptr, nullptr, c.st));
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
-  double obj = 0;
-  unsigned int flag = 0;
-  HIPCHK(hipMemcpyAsync(&obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
-  HIPCHK(hipMemcpyAsync(&flag, c.counters + c.ncounters, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(c.rb_obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(c.rb_flag, c.counters + c.ncounters, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(c.rb_cnt, c.up.cnt, sizeof(int32_t) * (size_t)c.k, hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipStreamSynchronize(c.st));
-  if (flag != 0) return fail(SKM_EINTERNAL, "a point was left without a centroid");
+  c.rb_cnt_valid = true;
+  if (*c.rb_flag != 0) return fail(SKM_EINTERNAL, "a point was left without a centroid");
   ss = StepStats();
-  ss.objective = obj;
+  ss.objective = *c.rb_obj;
   ss.dprime = c.d;
   ss.changed = c.n;
   return SKM_OK;
@@ -465,14 +529,16 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
                                 nullptr, c.st));
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
-  unsigned int overflow = 0;
-  std::vector<unsigned long long> scal_h((size_t)SC_COUNT * kStatReplicas);
-  double obj = 0;
-  HIPCHK(hipMemcpyAsync(&overflow, c.counters + c.ncounters, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
-  HIPCHK(hipMemcpyAsync(scal_h.data(), c.scal, sizeof(unsigned long long) * scal_h.size(), hipMemcpyDeviceToHost, c.st));
-  HIPCHK(hipMemcpyAsync(&obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
+  const size_t nscal = (size_t)SC_COUNT * kStatReplicas;
+  HIPCHK(hipMemcpyAsync(c.rb_flag, c.counters + c.ncounters, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(c.rb_scal, c.scal, sizeof(unsigned long long) * nscal, hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(c.rb_obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipMemcpyAsync(c.rb_cnt, c.up.cnt, sizeof(int32_t) * (size_t)c.k, hipMemcpyDeviceToHost, c.st));
   HIPCHK(hipStreamSynchronize(c.st));
-  if (overflow != 0) return fail(SKM_EINTERNAL, "hand-over list overflow or a point left without a centroid");
+  c.rb_cnt_valid = true;
+  if (*c.rb_flag != 0) return fail(SKM_EINTERNAL, "hand-over list overflow or a point left without a centroid");
+  std::vector<unsigned long long> scal_h(c.rb_scal, c.rb_scal + nscal);
+  const double obj = *c.rb_obj;
   for (int r = 1; r < kStatReplicas; ++r)   // fold the replicas into the first
     for (int q = 0; q < SC_COUNT; ++q) scal_h[(size_t)q] += scal_h[(size_t)r * SC_COUNT + q];
   ss = StepStats();
@@ -498,14 +564,19 @@ int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t
   if (!full && c.S_valid && 2 * changed <= c.inc.capacity - 2) {
     ++c.inc_updates;
     HIPCHK(launch_update_incremental(c.Xr, c.ldx, c.n, c.ds, c.assign, c.prev, changed, c.k, c.up, c.inc, c.S, c.Y, c.ds,
-                                     c.st));
+                                     c.st, c.amax + Ctx::AM_Y));
   } else {
-    HIPCHK(launch_update(c.Xr, c.ldx, c.n, c.ds, c.assign, c.k, c.up, c.Y, c.ds, c.st, c.S));
+    HIPCHK(launch_update(c.Xr, c.ldx, c.n, c.ds, c.assign, c.k, c.up, c.Y, c.ds, c.st, c.S, c.amax + Ctx::AM_Y));
     c.S_valid = true;
   }
-  std::vector<int32_t> cnt((size_t)c.k);
-  HIPCHK(hipMemcpyAsync(cnt.data(), c.up.cnt, sizeof(int32_t) * cnt.size(), hipMemcpyDeviceToHost, c.st));
-  HIPCHK(hipStreamSynchronize(c.st));
+  c.y_amax_valid = true;
+  // the cluster sizes came back with the step's scalars; neither update changes them
+  if (!c.rb_cnt_valid) {
+    HIPCHK(hipMemcpyAsync(c.rb_cnt, c.up.cnt, sizeof(int32_t) * (size_t)c.k, hipMemcpyDeviceToHost, c.st));
+    HIPCHK(hipStreamSynchronize(c.st));
+  }
+  c.rb_cnt_valid = false;
+  std::vector<int32_t> cnt(c.rb_cnt, c.rb_cnt + c.k);
   int64_t nempty = 0;
   for (int32_t v : cnt) nempty += (v == 0);
   *nempty_out = nempty;
@@ -538,6 +609,7 @@ int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t
     if (!pairs.empty()) {
       HIPCHK(hipMemcpyAsync(c.split_dev, pairs.data(), sizeof(int32_t) * pairs.size(), hipMemcpyHostToDevice, c.st));
       HIPCHK(launch_split(c.Y, c.ds, c.d, c.split_dev, (int32_t)(pairs.size() / 2), split_eps, c.st));
+      c.y_amax_valid = false;
       HIPCHK(hipStreamSynchronize(c.st));  // `pairs` must outlive the copy
     }
   }
@@ -800,7 +872,10 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     int64_t nempty = 0;
     rc = step_update(c, tm, split_rng, p.split_eps, &nempty, ss.changed, p.full_update != 0);
     if (rc) return rc;
-    if (p.angular) HIPCHK(launch_normalize_rows(c.Y, c.ds, k, c.ds, c.st));
+    if (p.angular) {
+      HIPCHK(launch_normalize_rows(c.Y, c.ds, k, c.ds, c.st));
+      c.y_amax_valid = false;
+    }
     HIPCHK(hipStreamSynchronize(c.st));
     float ms[ST_COUNT], total;
     tm.collect(ms, &total);
@@ -1199,7 +1274,12 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
     std::vector<std::thread> threads;
     for (int t = 1; t < nworkers; ++t) {
       try {
-        threads.emplace_back(body, std::ref(workers[(size_t)t]));
+        threads.emplace_back(
+            [&body](Worker &w) {
+              body(w);
+              tl_pinned.release();   // this thread's page-locked blocks go with it
+            },
+            std::ref(workers[(size_t)t]));
       } catch (const std::system_error &) {
         break;   // fewer threads: the others take the work
       }

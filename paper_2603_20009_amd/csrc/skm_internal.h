@@ -184,9 +184,11 @@ struct UpdateWs {
   int64_t max_segments;
 };
 int64_t update_max_segments(int64_t n, int32_t k);
-// S (optional, [k][ds] fp64) receives the sum of every cluster.
+// S (optional, [k][ds] fp64) receives the sum of every cluster; y_absmax (optional) the bit pattern of max |Y| of
+// the new centroids (the launcher clears it first).
 hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign, int32_t k,
-                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st, double *S = nullptr);
+                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st, double *S = nullptr,
+                         unsigned int *y_absmax = nullptr);
 
 // Workspace of the incremental update: room for 2 * (points that changed label) entries.
 struct IncUpdateWs {
@@ -202,7 +204,8 @@ struct IncUpdateWs {
 // (Section 3.2, the same means computed from the difference).
 hipError_t launch_update_incremental(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign,
                                      const int32_t *prev, int64_t changed, int32_t k, const UpdateWs &w,
-                                     const IncUpdateWs &inc, double *S, float *Y, int64_t ldy, hipStream_t st);
+                                     const IncUpdateWs &inc, double *S, float *Y, int64_t ldy, hipStream_t st,
+                                     unsigned int *y_absmax = nullptr);
 
 hipError_t launch_split(float *Y, int64_t ldy, int32_t d, const int32_t *pairs_dev, int32_t nsplit, float eps,
                         hipStream_t st);

@@ -66,6 +66,13 @@ __device__ inline float emit_prefix(const PrefixOut &po, int64_t i, int lane, in
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, upto), 63));
 }
 
+// 16-byte load with the non-temporal hint (data read once)
+__device__ inline float4 load_stream4(const float *p) {
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
 template <int NV>
 __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t ldx, int64_t n, int32_t ds,
                                                        const float *Y, int64_t ldy, const int32_t *assign, float *tau,
@@ -82,7 +89,8 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
 #pragma unroll
       for (int u = 0; u < NV; ++u) {
         const int c = lane * 4 + 256 * u;
-        xv[u] = c < ds ? *reinterpret_cast<const float4 *>(x + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        // the points stream through once per step: keep them from displacing the centroids in the L2
+        xv[u] = c < ds ? load_stream4(x + c) : make_float4(0.f, 0.f, 0.f, 0.f);
       }
 #pragma unroll
       for (int u = 0; u < NV; ++u) {
@@ -522,21 +530,37 @@ __global__ void __launch_bounds__(256) segment_sum_kernel(const float *Xr, int64
 // One workgroup per (cluster, slice): partial sums added in segment order, divided by the size.
 // S (optional, [k][ds] fp64) keeps the sum of every cluster between updates: it is overwritten by the total of the
 // partials, or, with `accumulate`, the total (a signed change) is added to it.
+// y_absmax (optional, zero before the launch) receives the bit pattern of max |Y| over all centroids, the bound
+// that the split-fp16 GEMMs of the next step scale the centroids by.
 __global__ void __launch_bounds__(256) centroid_mean_kernel(const double *partial, int32_t ds, const int32_t *cnt,
                                                             const int32_t *segoff, float *Y, int64_t ldy, double *S,
-                                                            int accumulate) {
+                                                            int accumulate, unsigned int *y_absmax) {
   const int c = blockIdx.x;
   const int n_c = cnt[c];
   const int col = blockIdx.y * 256 + threadIdx.x;
-  if (col >= ds) return;
-  double s = 0.0;
-  for (int seg = segoff[c]; seg < segoff[c + 1]; ++seg) s += partial[(int64_t)seg * ds + col];
-  if (S) {
-    if (accumulate) s += S[(int64_t)c * ds + col];
-    S[(int64_t)c * ds + col] = s;
+  float y = 0.f;
+  if (col < ds) {
+    double s = 0.0;
+    for (int seg = segoff[c]; seg < segoff[c + 1]; ++seg) s += partial[(int64_t)seg * ds + col];
+    if (S) {
+      if (accumulate) s += S[(int64_t)c * ds + col];
+      S[(int64_t)c * ds + col] = s;
+    }
+    if (n_c == 0) {   // an empty cluster keeps its centroid until the split
+      y = Y[(int64_t)c * ldy + col];
+    } else {
+      y = (float)(s / (double)n_c);
+      Y[(int64_t)c * ldy + col] = y;
+    }
   }
-  if (n_c == 0) return;  // an empty cluster keeps its centroid until the split
-  Y[(int64_t)c * ldy + col] = (float)(s / (double)n_c);
+  if (y_absmax) {
+    float m = fabsf(y);
+#pragma unroll
+    for (int w = 1; w < 64; w <<= 1) m = fmaxf(m, __shfl_xor(m, w, 64));
+    // thousands of wavefronts share this one word: only those that would raise it take the atomic
+    const unsigned int mb = __builtin_bit_cast(unsigned int, m);
+    if ((threadIdx.x & 63) == 0 && mb > __atomic_load_n(y_absmax, __ATOMIC_RELAXED)) atomicMax(y_absmax, mb);
+  }
 }
 
 // Points whose label changed: entry (i, new label) and entry (~i, old label), in any order (the segments are
@@ -559,7 +583,11 @@ __global__ void __launch_bounds__(256) compact_changes_kernel(const int32_t *ass
 }
 
 hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign, int32_t k,
-                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st, double *S) {
+                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st, double *S, unsigned int *y_absmax) {
+  if (y_absmax) {
+    hipError_t rc = hipMemsetAsync(y_absmax, 0, sizeof(unsigned int), st);
+    if (rc != hipSuccess) return rc;
+  }
   hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, st, w.cnt, k, w.off, w.cursor, w.segoff);
   int64_t blocks = (n + 255) / 256;
   if (blocks > 16384) blocks = 16384;
@@ -571,7 +599,7 @@ hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, co
                      w.off, w.segoff, w.order, w.partial);
   const unsigned slices1 = (unsigned)((ds + 255) / 256);
   hipLaunchKernelGGL(centroid_mean_kernel, dim3(k, slices1), dim3(256), 0, st, w.partial, ds, w.cnt, w.segoff, Y, ldy, S,
-                     0);
+                     0, y_absmax);
   return hipGetLastError();
 }
 
@@ -581,11 +609,16 @@ hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, co
 // the assignment step), inc is a workspace for 2 * changed entries.
 hipError_t launch_update_incremental(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign,
                                      const int32_t *prev, int64_t changed, int32_t k, const UpdateWs &w,
-                                     const IncUpdateWs &inc, double *S, float *Y, int64_t ldy, hipStream_t st) {
+                                     const IncUpdateWs &inc, double *S, float *Y, int64_t ldy, hipStream_t st,
+                                     unsigned int *y_absmax) {
   const int64_t m2 = 2 * changed;
   if (m2 > inc.capacity || !S) return hipErrorInvalidValue;
   hipError_t rc = hipMemsetAsync(inc.counter, 0, sizeof(unsigned int), st);
   if (rc != hipSuccess) return rc;
+  if (y_absmax) {
+    rc = hipMemsetAsync(y_absmax, 0, sizeof(unsigned int), st);
+    if (rc != hipSuccess) return rc;
+  }
   rc = hipMemsetAsync(inc.cnt, 0, sizeof(int32_t) * (size_t)k, st);
   if (rc != hipSuccess) return rc;
   int64_t blocks = std::min<int64_t>((n + 255) / 256, 16384);
@@ -608,7 +641,7 @@ hipError_t launch_update_incremental(const float *Xr, int64_t ldx, int64_t n, in
   }
   const unsigned slices1 = (unsigned)((ds + 255) / 256);
   hipLaunchKernelGGL(centroid_mean_kernel, dim3(k, slices1), dim3(256), 0, st, inc.partial, ds, w.cnt, inc.segoff, Y, ldy,
-                     S, 1);
+                     S, 1, y_absmax);
   return hipGetLastError();
 }
 
