@@ -147,6 +147,33 @@ int skm_fit_ex(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, u
                const skm_params *params, float *centroids_out, int32_t *assign_out, float *dist_out);
 
 /*
+ * skm_fit_host -- Algorithm 1 on points that stay in HOST memory (Section 7.1:
+ *   the points pass through the device in batches; copies and kernels overlap).
+ *   For data larger than the device memory.  Every pass over the data (an
+ *   iteration, or the final assignment) copies the rows to the device in batches
+ *   of batch_rows rows through two buffers, rotates the batch there, assigns it,
+ *   and adds its cluster sums (fp64) to those of the pass; the means are taken
+ *   when the pass is complete.  The result is that of skm_fit_ex with
+ *   params->full_update = 1, up to the rounding of sums taken in another order.
+ *   X_host          HOST n x d fp32.  Page-locked memory (hipHostMalloc) lets the
+ *                   copies run beside the kernels; pageable memory works, each
+ *                   copy then holds the calling thread until it is done.
+ *   batch_rows      rows per batch, rounded up to a multiple of 128; 0 = 131072.
+ *                   Device memory in use: about 3 * batch_rows * d * 4 bytes for the
+ *                   batches plus 8 (12 with dist_out_host) bytes per point.
+ *   centroids_out   DEVICE k x d fp32, original space
+ *   assign_out_host HOST n int32 or NULL; dist_out_host HOST n fp32 or NULL
+ *   params->R, if set, is a DEVICE pointer as elsewhere; params->init_idx a host
+ *   array.  Not combined with ETR, the angular metric or sample_frac
+ *   (SKM_EINVAL).  params->trace: one row per pass, stage times summed over
+ *   the batches (time spent waiting for a copy shows in ms_step only).
+ *   The call returns after its last copy has completed.
+ */
+int skm_fit_host(const float *X_host, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed,
+                 const skm_params *params, int64_t batch_rows, float *centroids_out, int32_t *assign_out_host,
+                 float *dist_out_host);
+
+/*
  * skm_fit_hierarchical -- Hierarchical SuperKMeans (Section 6).
  *   MESO: Algorithm 1 with skm_hier_meso_count(k) = round(sqrt(k)) clusters on
  *   all points, meso_iters iterations (3 in the paper) and the final

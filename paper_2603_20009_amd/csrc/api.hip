@@ -559,6 +559,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
 // `changed` = points whose label differs from c.prev (c.n after the exact step).  While few points move, the cluster
 // sums of the previous update are corrected by the rows that joined and left instead of being recomputed from all
 // points (full = true forces the recomputation).
+int split_empty(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t *nempty_out);
 int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t *nempty_out, int64_t changed,
                 bool full) {
   if (!full && c.S_valid && 2 * changed <= c.inc.capacity - 2) {
@@ -570,6 +571,11 @@ int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t
     c.S_valid = true;
   }
   c.y_amax_valid = true;
+  return split_empty(c, tm, split_rng, split_eps, nempty_out);
+}
+
+// Empty clusters after an update (Section 3.2): c.rb_cnt (if rb_cnt_valid) or c.up.cnt holds the cluster sizes.
+int split_empty(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t *nempty_out) {
   // the cluster sizes came back with the step's scalars; neither update changes them
   if (!c.rb_cnt_valid) {
     HIPCHK(hipMemcpyAsync(c.rb_cnt, c.up.cnt, sizeof(int32_t) * (size_t)c.k, hipMemcpyDeviceToHost, c.st));
@@ -932,6 +938,218 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     (void)hipEventElapsedTime(&tr->ms_rotate, e_rot0, e_rot);
     (void)hipEventElapsedTime(&tr->ms_init, e_begin, e_init);
     (void)hipEventElapsedTime(&tr->ms_etr_gt, e_gt0, e_gt1);
+    (void)hipEventElapsedTime(&tr->ms_unrotate, e_end0, e_end);
+    (void)hipEventElapsedTime(&tr->ms_total, e_begin, e_end);
+  }
+  return SKM_OK;
+}
+
+
+// Algorithm 1 on points that stay in host memory (Section 7.1: batches of X pass through the device, copies and kernels
+// overlap).  Every pass over the data (an iteration, or the final assignment) sends the rows through two device buffers
+// of `W` rows: while batch g is rotated and assigned, batch g + 1 is already there and batch g + 2 follows as soon as the
+// rotation has released its buffer.  A batch is rotated again in every pass (a d x d product per row, small next to the
+// transfer), so nothing of size n x d is kept on the device: per point only its label, and its distance if asked for.
+// An update adds the batch's cluster sums (fp64) to S; the means are taken once the pass is complete.
+int fit_host_impl(const float *Xh, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params *pp,
+                  int64_t batch_rows, float *centroids_out, int32_t *assign_out_host, float *dist_out_host) {
+  int rc = check_shape(Xh, n, d, k);
+  if (rc) return rc;
+  if (!centroids_out) return fail(SKM_EINVAL, "centroids_out is null");
+  if (iters < 1) return fail(SKM_EINVAL, "iters must be >= 1");
+  if (batch_rows < 0) return fail(SKM_EINVAL, "batch_rows must be >= 0");
+  skm_params p;
+  if (pp) p = *pp; else skm_params_default(&p);
+  if (!(p.dprime_frac > 0.f && p.dprime_frac <= 1.f)) return fail(SKM_EINVAL, "dprime_frac out of (0, 1]");
+  if (!(p.eps0 >= 0.f)) return fail(SKM_EINVAL, "eps0 must be >= 0");
+  if (p.etr || p.angular || (p.sample_frac > 0.f && p.sample_frac < 1.f))
+    return fail(SKM_EINVAL, "the host-resident fit is not combined with ETR, the angular metric or sample_frac");
+  skm_trace *tr = p.trace;
+  if (tr && (!tr->row || tr->capacity < 1)) return fail(SKM_EINVAL, "trace without rows");
+
+  // rows per batch: a multiple of 128 (whole tiles; the per-point arrays of a batch then start 512-byte aligned)
+  int64_t W = batch_rows > 0 ? batch_rows : (int64_t)131072;
+  W = std::min<int64_t>((W + 127) / 128 * 128, (n + 127) / 128 * 128);
+  const int64_t nbatch = (n + W - 1) / W;
+  const int npass = iters + (p.final_assign ? 1 : 0);
+
+  Ctx c;
+  c.st = (hipStream_t)p.stream;
+  c.n = W; c.d = d; c.k = k;
+  c.ds = round_up(d, 16);
+  c.block_stats = p.block_stats != 0;
+  StageTimer tm(c.st, true);
+  Events evs;
+  hipEvent_t e_begin = evs.next(), e_init = evs.next(), e_end0 = evs.next(), e_end = evs.next();
+  hipEvent_t ev_copied[2] = {evs.next(), evs.next()}, ev_free[2] = {evs.next(), evs.next()};
+  if (!e_begin || !e_init || !e_end0 || !e_end || !ev_copied[0] || !ev_copied[1] || !ev_free[0] || !ev_free[1])
+    return fail(SKM_EHIP, "hipEventCreate failed");
+  struct CopyStream {
+    hipStream_t s = nullptr;
+    ~CopyStream() {
+      if (s) (void)hipStreamDestroy(s);
+    }
+  } cs;
+  HIPCHK(hipStreamCreateWithFlags(&cs.s, hipStreamNonBlocking));
+  HIPCHK(hipEventRecord(e_begin, c.st));
+  rc = c.alloc_bounds();
+  if (rc) return rc;
+  rc = c.alloc_common(p.pair_budget, p.dense_frac, true);
+  if (rc) return rc;
+  const int64_t tile_rows = c.chunk_rows;   // rows per launch of the tile kernel inside a batch
+
+  Rot rot;
+  if (p.rotate) {
+    rc = setup_rotation(c.pool, c.st, d, c.ds, p.R, seed, rot);
+    if (rc) return rc;
+  }
+  float *raw[2] = {nullptr, nullptr}, *Xr_buf = nullptr, *dist_all = nullptr;
+  int32_t *lab[2] = {nullptr, nullptr};
+  HIPCHK(c.pool.get(&raw[0], (size_t)W * d));
+  HIPCHK(c.pool.get(&raw[1], (size_t)W * d));
+  HIPCHK(c.pool.get(&Xr_buf, (size_t)W * c.ds));
+  HIPCHK(c.pool.get(&lab[0], (size_t)nbatch * W));
+  HIPCHK(c.pool.get(&lab[1], (size_t)nbatch * W));
+  if (dist_out_host) HIPCHK(c.pool.get(&dist_all, (size_t)nbatch * W));
+  float *dist_batch = c.dist;
+  int32_t *cnt_dev = c.up.cnt;
+
+  // ---- InitCentroids: k distinct rows of X, rotated like the points
+  {
+    std::vector<int64_t> idx((size_t)k);
+    if (p.init_idx) {
+      for (int32_t i = 0; i < k; ++i) {
+        idx[(size_t)i] = p.init_idx[i];
+        if (idx[(size_t)i] < 0 || idx[(size_t)i] >= n) return fail(SKM_EINVAL, "init_idx out of range");
+      }
+    } else {
+      sample_rows(seed, STREAM_INIT, n, k, idx.data());
+    }
+    std::vector<float> rows_h((size_t)k * d);
+    for (int32_t i = 0; i < k; ++i)
+      std::memcpy(rows_h.data() + (size_t)i * d, Xh + (size_t)idx[(size_t)i] * d, sizeof(float) * (size_t)d);
+    float *rows_dev = nullptr;
+    HIPCHK(c.pool.get(&rows_dev, (size_t)k * d));
+    HIPCHK(hipMemcpyAsync(rows_dev, rows_h.data(), sizeof(float) * rows_h.size(), hipMemcpyHostToDevice, c.st));
+    if (p.rotate) {
+      rc = rotate_into(rows_dev, d, k, d, c.ds, rot, c.Y, c.st);
+      if (rc) return rc;
+    } else {
+      HIPCHK(launch_pad_copy(rows_dev, d, k, d, c.Y, c.ds, c.ds, 0, c.st));
+    }
+    HIPCHK(hipStreamSynchronize(c.st));   // rows_h must outlive the copy
+  }
+  HIPCHK(hipEventRecord(e_init, c.st));
+
+  // ---- the stream of batches: batch number g = pass * nbatch + b uses device buffer g & 1
+  const int64_t gtotal = (int64_t)npass * nbatch;
+  auto send = [&](int64_t g) -> int {   // enqueue the copy of batch g on the copy stream
+    if (g >= gtotal) return SKM_OK;
+    const int64_t b = g % nbatch, r0 = b * W, rows = std::min<int64_t>(W, n - r0);
+    if (g >= 2) HIPCHK(hipStreamWaitEvent(cs.s, ev_free[g & 1], 0));
+    HIPCHK(hipMemcpyAsync(raw[g & 1], Xh + (size_t)r0 * d, sizeof(float) * (size_t)rows * d, hipMemcpyHostToDevice, cs.s));
+    HIPCHK(hipEventRecord(ev_copied[g & 1], cs.s));
+    return SKM_OK;
+  };
+  if ((rc = send(0))) return rc;
+  if ((rc = send(1))) return rc;
+
+  int32_t dprime = dprime_init(d, p.dprime_frac);
+  Rng split_rng = rng_stream(seed, STREAM_SPLIT);
+  int32_t rows_out = 0;
+  int cur = 0;   // lab[cur] receives the labels of the pass in work, lab[cur ^ 1] holds those of the pass before
+  std::vector<int64_t> cnt_total((size_t)k);
+  for (int pass = 0; pass < npass; ++pass) {
+    const bool final_pass = pass >= iters;
+    StepStats tot;
+    tot.pruned = pass > 0;
+    std::fill(cnt_total.begin(), cnt_total.end(), 0);
+    if (!final_pass) HIPCHK(hipMemsetAsync(c.S, 0, sizeof(double) * (size_t)k * c.ds, c.st));
+    for (int64_t b = 0; b < nbatch; ++b) {
+      const int64_t g = (int64_t)pass * nbatch + b, r0 = b * W, rows = std::min<int64_t>(W, n - r0);
+      HIPCHK(hipStreamWaitEvent(c.st, ev_copied[g & 1], 0));
+      if (p.rotate) {
+        rc = rotate_into(raw[g & 1], d, rows, d, c.ds, rot, Xr_buf, c.st, c.amax + Ctx::AM_XR);
+        if (rc) return rc;
+      } else {
+        HIPCHK(launch_pad_copy(raw[g & 1], d, rows, d, Xr_buf, c.ds, c.ds, 0, c.st));
+      }
+      HIPCHK(hipEventRecord(ev_free[g & 1], c.st));
+      if ((rc = send(g + 2))) return rc;
+      c.n = rows;
+      c.nchunks = (int32_t)((rows + tile_rows - 1) / tile_rows);
+      c.Xr = Xr_buf; c.ldx = c.ds;
+      c.xnp_valid = false;
+      c.assign = lab[cur] + r0;
+      c.prev = lab[cur ^ 1] + r0;
+      c.dist = dist_all ? dist_all + r0 : dist_batch;
+      if (!p.rotate) {
+        rc = c.measure_xr();
+        if (rc) return rc;
+      }
+      StepStats ss;
+      rc = pass == 0 ? step_exact(c, tm, ss) : step_pruned(c, tm, dprime, (double)p.eps0, true, ss);
+      if (rc) return rc;
+      for (int32_t j = 0; j < k; ++j) cnt_total[(size_t)j] += c.rb_cnt[j];
+      tot.objective += ss.objective;
+      tot.survivors += ss.survivors;
+      tot.completed += ss.completed;
+      tot.changed += ss.changed;
+      tot.dense_dims += ss.dense_dims;
+      tot.dense_pair_blocks += ss.dense_pair_blocks;
+      for (int m = 0; m < SKM_MAX_BLOCKS; ++m) tot.enter[m] += ss.enter[m];
+      tot.dprime = ss.dprime;
+      tot.nblocks = ss.nblocks;
+      if (!final_pass) {
+        HIPCHK(launch_update(c.Xr, c.ldx, rows, c.ds, c.assign, k, c.up, nullptr, c.ds, c.st, c.S, nullptr, 1));
+        tm.mark(ST_UPDATE);
+      }
+    }
+    int64_t nempty = 0;
+    if (!final_pass) {
+      // means of the whole pass, then the split of empty clusters on the total sizes
+      for (int32_t j = 0; j < k; ++j) c.rb_cnt[j] = (int32_t)cnt_total[(size_t)j];
+      HIPCHK(hipMemcpyAsync(cnt_dev, c.rb_cnt, sizeof(int32_t) * (size_t)k, hipMemcpyHostToDevice, c.st));
+      HIPCHK(launch_means_from_sums(c.S, cnt_dev, k, c.ds, c.Y, c.ds, c.amax + Ctx::AM_Y, c.st));
+      c.y_amax_valid = true;
+      c.rb_cnt_valid = true;
+      rc = split_empty(c, tm, split_rng, p.split_eps, &nempty);
+      if (rc) return rc;
+    }
+    HIPCHK(hipStreamSynchronize(c.st));
+    float ms[ST_COUNT], total;
+    tm.collect(ms, &total);
+    if (tr && rows_out < tr->capacity) fill_row(tr->row[rows_out], tot, n, k, nempty, -1.0, ms, total);
+    ++rows_out;
+    if (pass > 0 && !final_pass && p.adjust_dprime && k > 1) {
+      const double f = 1.0 - (double)tot.survivors / ((double)n * (double)(k - 1));
+      dprime = dprime_adjust(d, dprime, f, p.adj_lo, p.adj_hi, p.adj_step);
+    }
+    cur ^= 1;
+  }
+  const int last = cur ^ 1;   // labels of the last pass
+  if (assign_out_host)
+    HIPCHK(hipMemcpyAsync(assign_out_host, lab[last], sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost, c.st));
+  if (dist_out_host)
+    HIPCHK(hipMemcpyAsync(dist_out_host, dist_all, sizeof(float) * (size_t)n, hipMemcpyDeviceToHost, c.st));
+  HIPCHK(hipEventRecord(e_end0, c.st));
+  if (p.rotate) {
+    rc = unrotate_into(c.Y, c.ds, k, d, c.ds, rot, centroids_out, c.st);
+    if (rc) return rc;
+  } else {
+    HIPCHK(hipMemcpy2DAsync(centroids_out, sizeof(float) * (size_t)d, c.Y, sizeof(float) * (size_t)c.ds,
+                            sizeof(float) * (size_t)d, (size_t)k, hipMemcpyDeviceToDevice, c.st));
+  }
+  HIPCHK(hipEventRecord(e_end, c.st));
+  HIPCHK(hipStreamSynchronize(c.st));
+  HIPCHK(hipStreamSynchronize(cs.s));
+  if (tr) {
+    tr->rows = std::min(rows_out, tr->capacity);
+    tr->iters_run = iters;
+    tr->inc_updates = 0;
+    tr->ms_rotate = 0.f;
+    tr->ms_etr_gt = 0.f;
+    (void)hipEventElapsedTime(&tr->ms_init, e_begin, e_init);
     (void)hipEventElapsedTime(&tr->ms_unrotate, e_end0, e_end);
     (void)hipEventElapsedTime(&tr->ms_total, e_begin, e_end);
   }
@@ -1371,6 +1589,12 @@ int skm_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint
 int skm_fit_ex(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params *params,
                float *centroids_out, int32_t *assign_out, float *dist_out) {
   return fit_impl(X, n, d, k, iters, seed, params, centroids_out, assign_out, dist_out, nullptr);
+}
+
+int skm_fit_host(const float *X_host, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed,
+                 const skm_params *params, int64_t batch_rows, float *centroids_out, int32_t *assign_out_host,
+                 float *dist_out_host) {
+  return fit_host_impl(X_host, n, d, k, iters, seed, params, batch_rows, centroids_out, assign_out_host, dist_out_host);
 }
 
 int skm_fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t meso_iters, int32_t fine_iters,

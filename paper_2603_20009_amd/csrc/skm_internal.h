@@ -185,10 +185,13 @@ struct UpdateWs {
 };
 int64_t update_max_segments(int64_t n, int32_t k);
 // S (optional, [k][ds] fp64) receives the sum of every cluster; y_absmax (optional) the bit pattern of max |Y| of
-// the new centroids (the launcher clears it first).
+// the new centroids (the launcher clears it first).  With `accumulate` the sums of these n points are added to S
+// instead (one batch of a larger update); Y may then be NULL, and launch_means_from_sums finishes the update.
 hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign, int32_t k,
                          const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st, double *S = nullptr,
-                         unsigned int *y_absmax = nullptr);
+                         unsigned int *y_absmax = nullptr, int accumulate = 0);
+hipError_t launch_means_from_sums(const double *S, const int32_t *cnt, int32_t k, int32_t ds, float *Y, int64_t ldy,
+                                  unsigned int *y_absmax, hipStream_t st);
 
 // Workspace of the incremental update: room for 2 * (points that changed label) entries.
 struct IncUpdateWs {

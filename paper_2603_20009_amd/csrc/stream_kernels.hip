@@ -546,7 +546,9 @@ __global__ void __launch_bounds__(256) centroid_mean_kernel(const double *partia
       if (accumulate) s += S[(int64_t)c * ds + col];
       S[(int64_t)c * ds + col] = s;
     }
-    if (n_c == 0) {   // an empty cluster keeps its centroid until the split
+    if (!Y) {
+      // sums only (a batch of a larger update: the means follow once all batches are in)
+    } else if (n_c == 0) {   // an empty cluster keeps its centroid until the split
       y = Y[(int64_t)c * ldy + col];
     } else {
       y = (float)(s / (double)n_c);
@@ -561,6 +563,40 @@ __global__ void __launch_bounds__(256) centroid_mean_kernel(const double *partia
     const unsigned int mb = __builtin_bit_cast(unsigned int, m);
     if ((threadIdx.x & 63) == 0 && mb > __atomic_load_n(y_absmax, __ATOMIC_RELAXED)) atomicMax(y_absmax, mb);
   }
+}
+
+// Y = S / size for every cluster with points (an empty one keeps its row), max |Y| into *y_absmax (zero before).
+__global__ void __launch_bounds__(256) means_from_sums_kernel(const double *S, const int32_t *cnt, int32_t ds, float *Y,
+                                                              int64_t ldy, unsigned int *y_absmax) {
+  const int c = blockIdx.x;
+  const int n_c = cnt[c];
+  const int col = blockIdx.y * 256 + threadIdx.x;
+  float y = 0.f;
+  if (col < ds) {
+    if (n_c == 0) {
+      y = Y[(int64_t)c * ldy + col];
+    } else {
+      y = (float)(S[(int64_t)c * ds + col] / (double)n_c);
+      Y[(int64_t)c * ldy + col] = y;
+    }
+  }
+  if (y_absmax) {
+    float m = fabsf(y);
+#pragma unroll
+    for (int w = 1; w < 64; w <<= 1) m = fmaxf(m, __shfl_xor(m, w, 64));
+    const unsigned int mb = __builtin_bit_cast(unsigned int, m);
+    if ((threadIdx.x & 63) == 0 && mb > __atomic_load_n(y_absmax, __ATOMIC_RELAXED)) atomicMax(y_absmax, mb);
+  }
+}
+hipError_t launch_means_from_sums(const double *S, const int32_t *cnt, int32_t k, int32_t ds, float *Y, int64_t ldy,
+                                  unsigned int *y_absmax, hipStream_t st) {
+  if (y_absmax) {
+    hipError_t rc = hipMemsetAsync(y_absmax, 0, sizeof(unsigned int), st);
+    if (rc != hipSuccess) return rc;
+  }
+  hipLaunchKernelGGL(means_from_sums_kernel, dim3(k, (unsigned)((ds + 255) / 256)), dim3(256), 0, st, S, cnt, ds, Y, ldy,
+                     y_absmax);
+  return hipGetLastError();
 }
 
 // Points whose label changed: entry (i, new label) and entry (~i, old label), in any order (the segments are
@@ -583,7 +619,9 @@ __global__ void __launch_bounds__(256) compact_changes_kernel(const int32_t *ass
 }
 
 hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const int32_t *assign, int32_t k,
-                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st, double *S, unsigned int *y_absmax) {
+                         const UpdateWs &w, float *Y, int64_t ldy, hipStream_t st, double *S, unsigned int *y_absmax,
+                         int accumulate) {
+  if ((accumulate && !S) || (!Y && y_absmax)) return hipErrorInvalidValue;
   if (y_absmax) {
     hipError_t rc = hipMemsetAsync(y_absmax, 0, sizeof(unsigned int), st);
     if (rc != hipSuccess) return rc;
@@ -599,7 +637,7 @@ hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, co
                      w.off, w.segoff, w.order, w.partial);
   const unsigned slices1 = (unsigned)((ds + 255) / 256);
   hipLaunchKernelGGL(centroid_mean_kernel, dim3(k, slices1), dim3(256), 0, st, w.partial, ds, w.cnt, w.segoff, Y, ldy, S,
-                     0, y_absmax);
+                     accumulate, y_absmax);
   return hipGetLastError();
 }
 

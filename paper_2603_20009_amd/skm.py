@@ -57,6 +57,7 @@ EXPORTS = [
     "skm_params_default", "skm_fit", "skm_fit_ex", "skm_assign", "skm_assign_ex", "skm_assign_exact", "skm_update",
     "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_theta_ratio", "skm_dprime_init", "skm_dprime_adjust",
     "skm_strerror", "skm_last_error", "skm_version", "skm_fit_hierarchical", "skm_hier_meso_count", "skm_hier_alloc",
+    "skm_fit_host",
 ]
 
 _lib = None
@@ -82,11 +83,13 @@ def lib():
         L.skm_rotate.argtypes = [vp, i64, i32, vp, i32, vp, vp]
         L.skm_sample_rows.argtypes = [u64, i64, i32, vp]
         L.skm_fit_hierarchical.argtypes = [vp, i64, i32, i32, i32, i32, u64, C.POINTER(Params), vp, vp, vp, vp, vp]
+        L.skm_fit_host.argtypes = [vp, i64, i32, i32, i32, u64, C.POINTER(Params), i64, vp, vp, vp]
         L.skm_hier_meso_count.argtypes = [i32]
         L.skm_hier_meso_count.restype = i32
         L.skm_hier_alloc.argtypes = [vp, i32, i32, vp]
         for f in ("skm_fit", "skm_fit_ex", "skm_assign", "skm_assign_ex", "skm_assign_exact", "skm_update",
-                  "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_fit_hierarchical", "skm_hier_alloc"):
+                  "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_fit_hierarchical", "skm_hier_alloc",
+                  "skm_fit_host"):
             getattr(L, f).restype = C.c_int
         L.skm_theta_ratio.argtypes = [i32, i32, f32]
         L.skm_theta_ratio.restype = f32
@@ -253,6 +256,29 @@ def fit_hierarchical(X: torch.Tensor, k: int, seed: int, meso_iters: int = 3, fi
     rows = [_row_dict(tr.row[i]) for i in range(tr.rows)]
     timing = dict(ms_meso=tr.ms_init, ms_fine=tr.ms_etr_gt, ms_total=tr.ms_total)
     return FitResult(cent, assign, dist, int(tr.iters_run), rows, timing), list(sizes), list(counts)
+
+
+def fit_host(X_host: torch.Tensor, k: int, iters: int, seed: int, batch_rows: int = 0, opts: FitOptions | None = None,
+             device: str = "cuda") -> FitResult:
+    """skm_fit_host (Section 7.1): Algorithm 1 on points that stay in host memory (a CPU tensor, page-locked for
+    copies that overlap the kernels) and pass through the device in batches of `batch_rows` rows.  The centroids come
+    back on the device, the labels and distances as CPU tensors."""
+    o = opts or FitOptions()
+    if X_host.device.type != "cpu" or X_host.dtype != torch.float32 or not X_host.is_contiguous():
+        raise ValueError("X_host must be a contiguous fp32 CPU tensor")
+    n, d = X_host.shape
+    keep: list = []
+    tr = _new_trace(iters + 1, keep)
+    p = _params(o, keep, tr)
+    cent = torch.empty((k, d), device=device, dtype=torch.float32)
+    assign = torch.empty(n, dtype=torch.int32, pin_memory=True)
+    dist = torch.empty(n, dtype=torch.float32, pin_memory=True)
+    rc = lib().skm_fit_host(C.c_void_p(X_host.data_ptr()), n, d, k, iters, C.c_uint64(seed), C.byref(p), batch_rows,
+                            C.c_void_p(cent.data_ptr()), C.c_void_p(assign.data_ptr()), C.c_void_p(dist.data_ptr()))
+    _check(rc)
+    rows = [_row_dict(tr.row[i]) for i in range(tr.rows)]
+    timing = dict(ms_init=tr.ms_init, ms_unrotate=tr.ms_unrotate, ms_total=tr.ms_total)
+    return FitResult(cent, assign, dist, int(tr.iters_run), rows, timing)
 
 
 def fit_default(X: torch.Tensor, k: int, iters: int, seed: int):

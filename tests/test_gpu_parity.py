@@ -567,3 +567,66 @@ def test_incremental_update_matches_the_full_one(skm, orc, dg):
     d = skm.fit(cuda(X), k, iters, 4, skm.FitOptions(R=cuda(R), eps0=EPS0, init_idx=list(idx), full_update=True))
     assert c.trace[0]["nempty"] == 1 and torch.equal(c.assign, d.assign)
     assert rel_l2(c.centroids.cpu().numpy(), d.centroids.cpu().numpy()) < 1e-6
+
+
+# ------------------------------------------------------------------ points that stay in host memory
+@pytest.mark.parametrize("pinned", [True, False])
+@pytest.mark.parametrize("n,d,k,batch", [(20_000, 128, 64, 4096),      # 5 batches, ragged last one (3616 rows)
+                                         (5000, 100, 24, 1536),        # padded dims, 4 batches, tail of 392 rows
+                                         (3000, 64, 16, 0)])           # one batch holds everything
+def test_host_resident_fit(skm, orc, dg, n, d, k, batch, pinned):
+    """Section 7.1: the points stay in host memory and pass through the device in batches, every iteration.
+    The result must be Algorithm 1's, i.e. the oracle's, and that of the device-resident fit."""
+    X = dg.mixture(n, d, 40, 17, "linear").numpy()
+    R = orc.random_rotation(d, 17)
+    iters = 6
+    Xh = torch.from_numpy(X)
+    if pinned:
+        Xh = Xh.pin_memory()
+    opts = skm.FitOptions(R=cuda(R), eps0=EPS0, adjust_dprime=False, block_stats=True)
+    got = skm.fit_host(Xh, k, iters, 3, batch_rows=batch, opts=opts)
+    ref = orc.fit(X, k, iters, 3, orc.FitParams(eps0=EPS0, adjust_dprime=False), R=R)
+    a = got.assign.numpy()
+    check_assignment(a, ref.assign, orc.rotate(X, R), ref.centroids_rot, own=(X, got.centroids.cpu().numpy()))
+    check_centroids(got.centroids.cpu().numpy(), ref.centroids, a, ref.assign)
+    assert len(got.trace) == len(ref.trace) == iters + 1
+    for g, r in zip(got.trace, ref.trace):
+        assert g["objective"] == pytest.approx(r["objective"], rel=1e-4)
+        assert g["dprime"] == r["dprime"] and g["nempty"] == r["nempty"]
+        assert g["prune_frac"] == pytest.approx(r["prune_frac"], abs=1e-3)
+    # the same fit with the points on the device, every cluster sum recomputed in every update
+    dev = skm.fit(cuda(X), k, iters, 3, skm.FitOptions(R=cuda(R), eps0=EPS0, adjust_dprime=False, full_update=True))
+    assert (dev.assign.cpu().numpy() == a).mean() >= 0.999
+    assert rel_l2(got.centroids.cpu().numpy(), dev.centroids.cpu().numpy()) < 1e-3
+    same = dev.assign.cpu().numpy() == a
+    assert np.abs(got.dist.numpy()[same] - dev.dist.cpu().numpy()[same]).max() < 1e-5
+
+
+def test_host_resident_fit_options(skm, orc, dg):
+    """d' adjustment, no rotation, no final pass, empty clusters: the host-resident fit follows the same rules."""
+    X = dg.mixture(12_000, 256, 64, 8, "embed").numpy()
+    R = orc.random_rotation(256, 8)
+    got = skm.fit_host(torch.from_numpy(X).pin_memory(), 64, 8, 5, batch_rows=5120,
+                       opts=skm.FitOptions(R=cuda(R), eps0=EPS0))
+    ref = orc.fit(X, 64, 8, 5, orc.FitParams(eps0=EPS0), R=R)
+    assert [g["dprime"] for g in got.trace] == [r["dprime"] for r in ref.trace]
+    assert got.trace[-1]["objective"] == pytest.approx(ref.trace[-1]["objective"], rel=1e-4)
+    assert rel_l2(got.centroids.cpu().numpy(), ref.centroids) < 1e-3
+    # repeated initial rows leave clusters empty after iteration 1; no rotation; labels of the last in-loop step
+    X = dg.mixture(6000, 64, 24, 10, "linear").numpy()
+    idx = orc.sample_rows(1, 6000, 12)
+    idx[1] = idx[0]
+    idx[2] = idx[0]
+    got = skm.fit_host(torch.from_numpy(X), 12, 5, 1, batch_rows=2048,
+                       opts=skm.FitOptions(rotate=False, eps0=EPS0, adjust_dprime=False, final_assign=False,
+                                           init_idx=list(idx)))
+    ref = orc.fit(X, 12, 5, 1, orc.FitParams(eps0=EPS0, adjust_dprime=False, final_assign=False), R=None, init_idx=idx)
+    assert [g["nempty"] for g in got.trace] == [r["nempty"] for r in ref.trace] and ref.trace[0]["nempty"] == 2
+    check_assignment(got.assign.numpy(), ref.assign, X, ref.centroids_rot, own=(X, got.centroids.cpu().numpy()))
+    assert rel_l2(got.centroids.cpu().numpy(), ref.centroids) < 1e-3
+    a = got.assign.numpy()
+    S = np.zeros((12, 64))
+    np.add.at(S, a, X.astype(np.float64))
+    assert np.abs(got.centroids.cpu().numpy() - S / np.bincount(a, minlength=12)[:, None]).max() < 1e-6
+    with pytest.raises(RuntimeError):
+        skm.fit_host(torch.from_numpy(X), 12, 5, 1, opts=skm.FitOptions(angular=True))
