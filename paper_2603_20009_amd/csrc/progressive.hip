@@ -40,6 +40,26 @@ constexpr int ROWS_PASS = NT / F4_ROW;      // 32 tile rows per staging pass
 constexpr int A_F4 = BM / ROWS_PASS;        // 4
 constexpr int B_F4 = BN / ROWS_PASS;        // 4
 
+// Sum / bitwise OR over the 64 lanes of a wavefront through the data-parallel lane moves: within quads, mirrored
+// within half rows and rows, then the row totals handed on to the following rows; lane 63 ends with the result.
+#define SKM_WAVE_REDUCE(v, OP)                                                                \
+  do {                                                                                        \
+    v = v OP __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);  /* quad_perm [1,0,3,2] */ \
+    v = v OP __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);  /* quad_perm [2,3,0,1] */ \
+    v = v OP __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false); /* row_half_mirror */      \
+    v = v OP __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, false); /* row_mirror */           \
+    v = v OP __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false); /* row_bcast:15 */         \
+    v = v OP __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false); /* row_bcast:31 */         \
+  } while (0)
+__device__ inline int wave_sum_i32(int v) {
+  SKM_WAVE_REDUCE(v, +);
+  return __builtin_amdgcn_readlane(v, 63);
+}
+__device__ inline int wave_or_i32(int v) {
+  SKM_WAVE_REDUCE(v, |);
+  return __builtin_amdgcn_readlane(v, 63);
+}
+
 }  // namespace
 
 // Slabs of BK dimensions start at koff = -((BK - d' % BK) % BK), so that slab ends fall on every
@@ -48,12 +68,13 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   extern __shared__ __align__(16) float smem[];
   float *As = smem;                  // [2][BM][LS]
   float *Bs = smem + 2 * BM * LS;    // [2][BN][LS]
-  __shared__ float s_tau[BM], s_thr[BM], s_xn[BM], s_yn[BN];
+  __shared__ __align__(16) float s_tau[BM], s_thr[BM], s_xn[BM], s_yn[BN];
   __shared__ int s_prev[BM];
   __shared__ float s_ratio[kMaxBlocks + 1];
   __shared__ unsigned long long s_dead[NT];   // per thread: accumulator elements that start dead (the incumbent)
   __shared__ unsigned int s_cnt[2];
-  __shared__ unsigned int s_wcnt[5];
+  __shared__ unsigned int s_wcnt[2][4];   // alive pairs of every wavefront at the last checkpoint (by checkpoint parity)
+  __shared__ unsigned int s_base;         // first list slot of a tile that hands its pairs over
   __shared__ int s_q[4];   // ring of tile numbers drawn from the XCD's counter, two tiles ahead of the one in work
 
   const int tid = threadIdx.x;
@@ -267,6 +288,8 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
 
     int fin_mode = 0, fin_m = 0;   // how the tile ends: 0 = nothing alive, 1 = reached t = d, 2 = handed over at fin_m
+    int wave_alive = 0;            // alive pairs of this wavefront at the last checkpoint
+    unsigned int slot0 = 0;        // thread 0: reply of the list reservation
     float yn[TN] = {0.f, 0.f};
     // Fragments of half a slab (16 dims): lane half kh supplies the 8 consecutive dims 16 h + 8 kh .. + 7 of both
     // operands.  x.y ~ hi.hi' + lo.hi' + hi.lo' on the fp16 matrix cores, fp32 accumulation, in groups of four
@@ -364,15 +387,19 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
               }
             }
         }
-        // alive pairs of the whole tile
-        int cnt = __popcll(bits);
-#pragma unroll
-        for (int sh = 1; sh < 64; sh <<= 1) cnt += __shfl_xor(cnt, sh, 64);
-        if (lane == 0 && cnt) atomicAdd(&s_cnt[m & 1], (unsigned int)cnt);
+        // alive pairs of this wavefront and of the whole tile
+        wave_alive = wave_sum_i32(__popcll(bits));
+        if (lane == 0) {
+          s_wcnt[m & 1][wave] = (unsigned int)wave_alive;
+          if (wave_alive) atomicAdd(&s_cnt[m & 1], (unsigned int)wave_alive);
+        }
         __syncthreads();
         const unsigned int total = s_cnt[m & 1];
         if (tid == 0) {
           s_cnt[(m + 1) & 1] = 0u;   // next checkpoint's counter; nobody reads it before the next barrier
+          // a tile that hands its pairs over reserves their slots now (one reservation per tile in the sub-list of
+          // this workgroup's XCD): the answer is not needed before the next tile's loads have been requested
+          if (!last && total != 0u && total <= g.emit_max) slot0 = atomicAdd(g.pair_count + xcd * kSubListStride, total);
           if (total) {
             if (m == 0) atomicAdd(sc + SC_SURVIVORS, (unsigned long long)total);
             if (!last && g.block_stats) atomicAdd(sc + SC_ENTER + m, (unsigned long long)total);
@@ -441,40 +468,36 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
           __builtin_amdgcn_sched_barrier(0);
         }
     } else if (fin_mode == 2) {
-      // sparse enough: hand the alive pairs to the gather kernel, which resumes at block fin_m.
-      // One reservation per tile in the sub-list of this workgroup's XCD.
-      int wtot = __popcll(bits);
-#pragma unroll
-      for (int sh = 1; sh < 64; sh <<= 1) wtot += __shfl_xor(wtot, sh, 64);
-      if (lane == 0) s_wcnt[wave] = (unsigned int)wtot;
-      __syncthreads();
+      // sparse enough: hand the alive pairs to the gather kernel, which resumes at block fin_m
       if (tid == 0) {
-        const unsigned int tot = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
-        unsigned int base = atomicAdd(g.pair_count + xcd * kSubListStride, tot);
+        const unsigned int tot = s_wcnt[fin_m & 1][0] + s_wcnt[fin_m & 1][1] + s_wcnt[fin_m & 1][2] + s_wcnt[fin_m & 1][3];
+        unsigned int base = slot0;
         if ((unsigned long long)base + tot > (unsigned long long)g.sub_capacity) {
           *g.overflow = 1u;
           base = 0xffffffffu;
         } else {
           base += xcd * g.sub_capacity;
         }
-        s_wcnt[4] = base;
+        s_base = base;
       }
+      // element slots in which any lane of this wavefront holds an alive pair (a sparse tile has few): the others
+      // are skipped by a scalar test each
+      const unsigned long long any = ((unsigned long long)(unsigned int)wave_or_i32((int)(bits >> 32)) << 32) |
+                                     (unsigned long long)(unsigned int)wave_or_i32((int)bits);
       __syncthreads();
-      unsigned int run = s_wcnt[4];
-      if (run != 0xffffffffu && wtot > 0) {
-        for (int w = 0; w < wave; ++w) run += s_wcnt[w];
-        // element slots in which any lane of this wavefront holds an alive pair (a sparse tile has few): the 64
-        // slots below are then skipped by a scalar test each
-        unsigned int any_lo = (unsigned int)bits, any_hi = (unsigned int)(bits >> 32);
+      unsigned int run = s_base;
+      if (run != 0xffffffffu && wave_alive > 0) {
+        for (int w = 0; w < wave; ++w) run += s_wcnt[fin_m & 1][w];
 #pragma unroll
-        for (int sh = 1; sh < 64; sh <<= 1) {
-          any_lo |= __shfl_xor(any_lo, sh, 64);
-          any_hi |= __shfl_xor(any_hi, sh, 64);
-        }
-        const unsigned long long any = ((unsigned long long)__builtin_amdgcn_readfirstlane(any_hi) << 32) |
-                                       (unsigned long long)__builtin_amdgcn_readfirstlane(any_lo);
+        for (int a = 0; a < TM; ++a) {
+          // per-row data of the 16 rows this lane holds in accumulator row block a: four aligned groups of four rows
+          float4 xn4[4], tau4[4];
 #pragma unroll
-        for (int a = 0; a < TM; ++a)
+          for (int q4 = 0; q4 < 4; ++q4) {
+            xn4[q4] = *reinterpret_cast<const float4 *>(&s_xn[wm * WTM + a * 32 + 8 * q4 + 4 * kh]);
+            tau4[q4] = *reinterpret_cast<const float4 *>(&s_tau[wm * WTM + a * 32 + 8 * q4 + 4 * kh]);
+          }
+          auto pick = [](const float4 &f, int i) { return i == 0 ? f.x : i == 1 ? f.y : i == 2 ? f.z : f.w; };
 #pragma unroll
           for (int b = 0; b < TN; ++b)
 #pragma unroll
@@ -482,23 +505,21 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
               if (!((any >> ((a * TN + b) * 16 + v)) & 1ull)) continue;
               const bool keep = (bits >> ((a * TN + b) * 16 + v)) & 1ull;
               const unsigned long long mk = __ballot(keep);
-              if (mk) {
-                if (keep) {
-                  const int rl = row_of(a, v);
-                  const unsigned int pos =
-                      run + __builtin_amdgcn_mbcnt_hi((unsigned int)(mk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mk, 0u));
-                  Pair pr;
-                  pr.i = (int32_t)(g.row_base + row0 + rl);
-                  pr.j = (int32_t)((uint32_t)gc[b] | ((uint32_t)fin_m << 24));
-                  const float p = s_xn[rl] + fmaf(m2, acc[a][b][v], yn[b]);
-                  pr.p = p > 0.f ? p : 0.f;
-                  pr.tau = s_tau[rl];
-                  g.pairs[pos] = pr;
-                }
-                run += (unsigned int)__popcll(mk);
+              if (keep) {
+                const unsigned int pos =
+                    run + __builtin_amdgcn_mbcnt_hi((unsigned int)(mk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mk, 0u));
+                Pair pr;
+                pr.i = (int32_t)(g.row_base + row0 + row_of(a, v));
+                pr.j = (int32_t)((uint32_t)gc[b] | ((uint32_t)fin_m << 24));
+                const float p = pick(xn4[v >> 2], v & 3) + fmaf(m2, acc[a][b][v], yn[b]);
+                pr.p = p > 0.f ? p : 0.f;
+                pr.tau = pick(tau4[v >> 2], v & 3);
+                g.pairs[pos] = pr;
               }
+              run += (unsigned int)__popcll(mk);
               __builtin_amdgcn_sched_barrier(0);
             }
+        }
       }
     }
 
