@@ -304,6 +304,8 @@ struct Ctx {
   int64_t ldx = 0;
   float *Y = nullptr;         // centroids k x ds (rotated space)
   float *Ypdx = nullptr;
+  uint32_t *Xs = nullptr;     // [n][ds + 32] split-fp16 copy of Xr for the progressive kernel, made with xnp
+  uint32_t *Ys = nullptr;     // [k][ds + 32] the same of Y, remade in every pruned step
   float *xnp = nullptr;       // [ds / 16][n] prefix norms of the points at every multiple of 16 dims, written by the
   bool xnp_valid = false;     // first pruned step (the points of a context never change)
   float *ynp = nullptr;       // [nb + 1][k] prefix norms of the centroids at the checkpoints of the current step
@@ -376,6 +378,8 @@ struct Ctx {
     const int32_t nbmax = (ds - 16 + kBlockDims - 1) / kBlockDims + 1;
     HIPCHK(pool.get(&Ypdx, (size_t)nbmax * k * kBlockDims));
     HIPCHK(pool.get(&xnp, (size_t)(ds / 16) * n));
+    HIPCHK(pool.get(&Xs, (size_t)n * (ds + 32)));
+    HIPCHK(pool.get(&Ys, (size_t)k * (ds + 32)));
     HIPCHK(pool.get(&ynp, (size_t)nbmax * k));
     HIPCHK(pool.get(&ynorm, (size_t)k));
     HIPCHK(pool.get(&tau, (size_t)n));
@@ -496,8 +500,11 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, nullptr, nullptr, c.counters + c.ncounters, c.st));
     tm.mark(ST_GEMM);
   }
-  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st, c.xnp_valid ? nullptr : c.xnp));
+  // the first pruned step of a context also writes the tables that depend on the points only
+  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st, c.xnp_valid ? nullptr : c.xnp,
+                         c.xnp_valid ? nullptr : c.Xs, c.amax + Ctx::AM_XR));
   c.xnp_valid = true;
+  HIPCHK(launch_split_rows(c.Y, c.ds, c.k, c.ds, c.amax + Ctx::AM_Y, c.Ys, c.st));
   HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT * kStatReplicas, c.st));
   HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
   tm.mark(ST_TAU);
@@ -505,8 +512,8 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     const int64_t r0 = (int64_t)ch * c.chunk_rows;
     const int64_t rows = std::min<int64_t>(c.chunk_rows, c.n - r0);
     ProgArgs g{};
-    g.A = c.Xr + r0 * c.ldx; g.lda = c.ldx; g.M = (int32_t)rows;
-    g.B = c.Y; g.ldb = c.ds; g.N = c.k;
+    g.A = c.Xs + r0 * (c.ds + 32); g.lda = c.ds + 32; g.M = (int32_t)rows;
+    g.B = c.Ys; g.ldb = c.ds + 32; g.N = c.k;
     g.a_absmax = c.amax + Ctx::AM_XR; g.b_absmax = c.amax + Ctx::AM_Y;
     g.ds = c.ds; g.d = c.d; g.dprime = dprime; g.nb = nb;
     g.ratio = c.ratio_dev; g.tau = c.tau; g.prev = c.prev; g.row_base = r0;
@@ -1438,9 +1445,9 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
     };
     const int nworkers = (int)std::min<int32_t>(4, km);   // the device exposes four hardware queues to a process
     std::vector<Worker> workers((size_t)nworkers);
-    // workspace of the largest fine fit, generously: per point the padded row copy, its table of prefix norms and
+    // workspace of the largest fine fit, generously: per point the padded row copy, its split-fp16 copy, its table of prefix norms and
     // the per-point arrays, per centroid three padded rows, plus the hand-over list of a small problem
-    const size_t want = (size_t)nmax * ((size_t)ds * 4 + (size_t)ds / 4 + 96) + (size_t)kmax * (size_t)ds * 24 + ((size_t)256 << 20);
+    const size_t want = (size_t)nmax * ((size_t)ds * 8 + (size_t)ds / 4 + 256) + (size_t)kmax * (size_t)ds * 24 + ((size_t)256 << 20);
     int dev = 0;
     HIPCHK(hipGetDevice(&dev));
     struct StreamGuard {

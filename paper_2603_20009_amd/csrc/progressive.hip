@@ -14,6 +14,10 @@
 // centroid anyway write them, so that this kernel, whose vector unit is the busy one, only
 // fetches one number per row and column and checkpoint.
 //
+// Operands arrive already split into fp16 pairs (split_rows_kernel: once per fit for the points, once per
+// step for the centroids), in the very byte order of the LDS tiles, so staging is a copy: every lane moves
+// 16 bytes from global memory straight into LDS and the vector unit is left to the tests.
+//
 // The kernel is persistent: two workgroups per CU take tiles from a per-XCD counter.  When a tile
 // ends, the first slab and the per-row data of the next tile are already being fetched while the
 // finished tile is written out, so the short tiles of a well-pruned step do not drain the pipeline.
@@ -30,15 +34,58 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
+// ---------------------------------------------------------------- split-fp16 copies of the operands
+// Row r of a matrix scaled by split_scale(*absmax): granule g (dims 16 g .. 16 g + 15) is 16 words at word
+// 16 (g + 1) of the row: 8 words of hi halves (fp16 of the scaled value, two per word), then 8 words of lo
+// halves (fp16 of the remainder).  Granule positions 0 and ds / 16 + 1 are zero, so that a 32-dimension slab
+// starting 16 dimensions before the row or ending 16 after it reads zeros.  Row stride ds + 32 words.
+__global__ void __launch_bounds__(256) split_rows_kernel(const float *A, int64_t lda, int64_t rows, int32_t ds,
+                                                         const unsigned int *absmax, uint32_t *out) {
+  const float scale = split_scale(*absmax);
+  const int per_row = ds / 4 + 8;   // float4 pieces per output row, pads included
+  const int64_t total = rows * per_row;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = e / per_row;
+    const int piece = (int)(e - r * per_row);      // 4 dims each; pieces 0..3 and the last 4 are padding
+    const int gpos = piece >> 2, q = piece & 3;    // granule position, quarter of the granule
+    uint2 hi = make_uint2(0u, 0u), lo = hi;
+    if (gpos >= 1 && gpos <= ds / 16) {
+      const float4 v = *reinterpret_cast<const float4 *>(A + r * lda + 16 * (gpos - 1) + 4 * q);
+      const f32x2 p0 = {v.x * scale, v.y * scale}, p1 = {v.z * scale, v.w * scale};
+      const f16x2 h0 = __builtin_convertvector(p0, f16x2), h1 = __builtin_convertvector(p1, f16x2);
+      const f16x2 l0 = __builtin_convertvector(p0 - __builtin_convertvector(h0, f32x2), f16x2);
+      const f16x2 l1 = __builtin_convertvector(p1 - __builtin_convertvector(h1, f32x2), f16x2);
+      hi.x = __builtin_bit_cast(unsigned int, h0); hi.y = __builtin_bit_cast(unsigned int, h1);
+      lo.x = __builtin_bit_cast(unsigned int, l0); lo.y = __builtin_bit_cast(unsigned int, l1);
+    }
+    uint32_t *dst = out + r * (int64_t)(ds + 32) + 16 * gpos;
+    *reinterpret_cast<uint2 *>(dst + 2 * q) = hi;
+    *reinterpret_cast<uint2 *>(dst + 8 + 2 * q) = lo;
+  }
+}
+hipError_t launch_split_rows(const float *A, int64_t lda, int64_t rows, int32_t ds, const unsigned int *absmax,
+                             uint32_t *out, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  if (ds % 16 != 0 || lda % 4 != 0 || (reinterpret_cast<uintptr_t>(A) & 15u) || (reinterpret_cast<uintptr_t>(out) & 15u))
+    return hipErrorInvalidValue;
+  const int64_t total = rows * (ds / 4 + 8);
+  const int64_t blocks = std::min<int64_t>((total + 255) / 256, 1 << 16);
+  hipLaunchKernelGGL(split_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, A, lda, rows, ds, absmax, out);
+  return hipGetLastError();
+}
+
 namespace {
 constexpr int BM = 128, BN = 128, BK = 32;
 constexpr int WTM = 64, WTN = 64, TM = 2, TN = 2;
 constexpr int NT = 256;
-constexpr int LS = BK + 4;
-constexpr int F4_ROW = BK / 4;              // 8 lanes stage one tile row
-constexpr int ROWS_PASS = NT / F4_ROW;      // 32 tile rows per staging pass
-constexpr int A_F4 = BM / ROWS_PASS;        // 4
-constexpr int B_F4 = BN / ROWS_PASS;        // 4
+constexpr int ROW_WORDS = BK;                       // a tile row of a slab: 32 hi + 32 lo halves = 128 bytes
+constexpr int STAGE_WORDS = (BM + BN) * ROW_WORDS;  // one slab of both operands: 32 KB
+constexpr int ROWS_PASS = NT / 8;                   // 8 lanes move one tile row: 32 rows per load instruction
+constexpr int A_LD = BM / ROWS_PASS;                // 4 load instructions per thread, slab and operand
+constexpr int B_LD = BN / ROWS_PASS;
+
+// wait until at most n of this wavefront's vector memory operations are outstanding (LDS and export counters untouched)
+#define SKM_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
 // Sum / bitwise OR over the 64 lanes of a wavefront through the data-parallel lane moves: within quads, mirrored
 // within half rows and rows, then the row totals handed on to the following rows; lane 63 ends with the result.
@@ -63,11 +110,10 @@ __device__ inline int wave_or_i32(int v) {
 }  // namespace
 
 // Slabs of BK dimensions start at koff = -((BK - d' % BK) % BK), so that slab ends fall on every
-// checkpoint d' + 64 m; dimensions below 0 or past ds are read as zero.
+// checkpoint d' + 64 m; the zero granules around every row of the split operands cover dimensions below 0
+// or past ds.
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) progressive_kernel(ProgArgs g) {
-  extern __shared__ __align__(16) float smem[];
-  float *As = smem;                  // [2][BM][LS]
-  float *Bs = smem + 2 * BM * LS;    // [2][BN][LS]
+  extern __shared__ __align__(16) uint32_t smem[];   // [2 stages][A: BM rows | B: BN rows][ROW_WORDS]
   __shared__ __align__(16) float s_tau[BM], s_thr[BM], s_xn[BM], s_yn[BN];
   __shared__ int s_prev[BM];
   __shared__ float s_ratio[kMaxBlocks + 1];
@@ -81,6 +127,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int r32 = lane & 31, kh = lane >> 5;
+  const int swz = (r32 >> 1) & 7;   // position swizzle of the tile rows this lane reads fragments from
   const int nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
   const int ntiles = nrt * nct;
   // column tiles per panel of the tile walk: in the steady state only d' + a few blocks of every centroid are read,
@@ -109,22 +156,25 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   if (tid < 2) s_cnt[tid] = 0u;
   s_dead[tid] = 0ull;
 
-  // staging: thread (st_row, st_kq) moves dims 4 st_kq .. + 3 of tile rows st_row + 32 s.  The 8-lane groups of a
-  // wavefront take rows 4 apart (group bits 0-1 and 2-3 swapped): with a row stride of 36 words the rows written by
-  // 32 lanes then start 16 banks apart and their 8-byte LDS writes do not collide.
-  const int grp = tid / F4_ROW, st_kq = tid % F4_ROW;
-  const int st_row = (grp & 16) | ((grp & 3) << 2) | ((grp >> 2) & 3);
+  // Staging: load instruction j of wavefront w moves tile rows 32 j + 8 w .. + 7 of a slab, 8 lanes per row and 16
+  // bytes per lane, from global memory straight into LDS, where the lanes' pieces land one after the other: LDS rows
+  // are 128 bytes without padding.  Piece c of a row (c = 4 h + 2 lo + kh: half-slab, hi or lo halves, dims 8 kh ..
+  // + 7 of the half-slab) is kept at position c ^ swz(row), swz = (row >> 1) & 7, so that the 16-byte fragment reads
+  // of 16 consecutive rows fall into 16 different bank groups; a lane therefore fetches the piece that belongs at
+  // its own position.
+  const int lrow = lane >> 3, lpos = lane & 7;
+  const int ld_row = 8 * wave + lrow;                        // + 32 j
+  const int ld_piece = lpos ^ ((ld_row >> 1) & 7);
   const int koff = -((BK - g.dprime % BK) % BK);
   const int nslab = (g.ds - koff + BK - 1) / BK;
+  const int kw0 = 16 + koff;                                 // word of a split row where slab 0 starts (one zero granule leads)
 
-  // Global loads are unconditional: rows past the end are clamped to the last row (their accumulator elements start
-  // dead), dimensions outside [0, ds) are clamped into the row and multiplied by zero when staged.  With nothing
-  // conditional around them the compiler can keep the loads of a whole slab in flight across a multiply step.
-  float4 ra[A_F4], rb[B_F4];
+  // Rows past the end are clamped to the last row (their accumulator elements start dead).
+  unsigned int offA[A_LD], offB[B_LD];      // word offset of this lane's piece from the tile's first row / column
   float tau_reg = 0.f;
   int prev_reg = -1;
-  const float *baseA = g.A, *baseB = g.B;   // first row / column of the tile being loaded (uniform)
-  int limA = 0, limB = 0;                   // last valid row / column of that tile, relative to its first (uniform)
+  const uint32_t *baseA = g.A, *baseB = g.B;   // first row / column of the tile being loaded (uniform)
+  int limA = 0, limB = 0;                      // last valid row / column of that tile, relative to its first (uniform)
   // prefix norms: threads 0..127 fetch those of the tile's rows, threads 128..255 those of its columns
   const float *npre = g.xnp;                // &norm[0][this thread's row or column]
   const int64_t npre_stride = tid < BM ? g.xn_stride : (int64_t)g.N;
@@ -134,7 +184,26 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     baseB = g.B + (int64_t)col0 * g.ldb;
     limA = g.M - 1 - row0;
     limB = g.N - 1 - col0;
+#pragma unroll
+    for (int j = 0; j < A_LD; ++j)
+      offA[j] = (unsigned int)(min(ld_row + ROWS_PASS * j, limA) * (int)g.lda + 4 * ld_piece);
+#pragma unroll
+    for (int j = 0; j < B_LD; ++j)
+      offB[j] = (unsigned int)(min(ld_row + ROWS_PASS * j, limB) * (int)g.ldb + 4 * ld_piece);
     npre = tid < BM ? g.xnp + g.row_base + row0 + min(tid, limA) : g.ynp + col0 + min(tid - BM, limB);
+  };
+  // slab s of the aimed tile -> LDS stage `stage` (asynchronous: SKM_VMCNT(0) and a barrier before it is read)
+  auto issue = [&](int stage, int s) {
+    uint32_t *sb = smem + stage * STAGE_WORDS + 8 * wave * ROW_WORDS;
+    const int kw = kw0 + BK * s;
+#pragma unroll
+    for (int j = 0; j < A_LD; ++j)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(baseA + offA[j] + kw),
+                                       (__attribute__((address_space(3))) void *)(sb + ROWS_PASS * j * ROW_WORDS), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < B_LD; ++j)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(baseB + offB[j] + kw),
+                                       (__attribute__((address_space(3))) void *)(sb + (BM + ROWS_PASS * j) * ROW_WORDS), 16, 0, 0);
   };
   // Row of the norm tables that multiply step s needs if it ends on a checkpoint (any valid row otherwise): the
   // points' table has a row per 16 dimensions, the centroids' a row per checkpoint of this step.
@@ -145,23 +214,6 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int py = end ? g.nb : min(max((td - g.dprime) / kBlockDims, 0), g.nb);
     nreg = npre[(int64_t)(tid < BM ? px : py) * npre_stride];
   };
-  auto kclamp = [&](int k0) { return (unsigned int)min(max(k0 + 4 * st_kq, 0), g.ds - 4); };
-  auto klive = [&](int k0) { return k0 + 4 * st_kq >= 0 && k0 + 4 * st_kq < g.ds; };
-  auto load_a = [&](int j, unsigned int kk) {
-    const unsigned int off = (unsigned int)(min(st_row + ROWS_PASS * j, limA) * (int)g.lda) + kk;
-    ra[j] = *reinterpret_cast<const float4 *>(baseA + off);
-  };
-  auto load_b = [&](int j, unsigned int kk) {
-    const unsigned int off = (unsigned int)(min(st_row + ROWS_PASS * j, limB) * (int)g.ldb) + kk;
-    rb[j] = *reinterpret_cast<const float4 *>(baseB + off);
-  };
-  auto gload = [&](int k0) {
-    const unsigned int kk = kclamp(k0);
-#pragma unroll
-    for (int j = 0; j < A_F4; ++j) load_a(j, kk);
-#pragma unroll
-    for (int j = 0; j < B_F4; ++j) load_b(j, kk);
-  };
   auto load_rows = [&](int row0) {   // per-row data of a tile, one row per thread of the first two wavefronts
     if (tid < BM) {
       const int gr = min(row0 + tid, g.M - 1);
@@ -169,32 +221,8 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       prev_reg = row0 + tid < g.M ? g.prev[g.row_base + gr] : -1;
     }
   };
-  // Split-fp16 staging (see skm_internal.h): a scaled value v goes to LDS as hi = fp16(v) and lo = fp16(v - hi);
-  // a tile row of a slab holds its 32 hi values (64 bytes), its 32 lo values, and 16 bytes of padding.
   const unsigned int amax = *g.a_absmax, bmax = *g.b_absmax;
-  const float scale_a = split_scale(amax), scale_b = split_scale(bmax);
   const float m2 = -2.f * split_unscale(amax) * split_unscale(bmax);   // accumulator -> -2 x.y
-  auto split_store = [&](float *dst_row, const float4 &v, float scale) {
-    const f32x2 p0 = {v.x * scale, v.y * scale}, p1 = {v.z * scale, v.w * scale};
-    const f16x2 h0 = __builtin_convertvector(p0, f16x2), h1 = __builtin_convertvector(p1, f16x2);
-    const f16x2 l0 = __builtin_convertvector(p0 - __builtin_convertvector(h0, f32x2), f16x2);
-    const f16x2 l1 = __builtin_convertvector(p1 - __builtin_convertvector(h1, f32x2), f16x2);
-    uint2 hi, lo;
-    hi.x = __builtin_bit_cast(unsigned int, h0); hi.y = __builtin_bit_cast(unsigned int, h1);
-    lo.x = __builtin_bit_cast(unsigned int, l0); lo.y = __builtin_bit_cast(unsigned int, l1);
-    *reinterpret_cast<uint2 *>(dst_row + 2 * st_kq) = hi;
-    *reinterpret_cast<uint2 *>(dst_row + 16 + 2 * st_kq) = lo;
-  };
-  // float4 j of the staged slab -> LDS buffer `buf`, then the same registers are aimed at the slab after it (element
-  // offset kk2), so that one register set carries two slabs: one being used, one in flight
-  auto stage_a = [&](int j, int buf, float fa, unsigned int kk2) {
-    split_store(As + (buf * BM + st_row + ROWS_PASS * j) * LS, ra[j], fa);
-    load_a(j, kk2);
-  };
-  auto stage_b = [&](int j, int buf, float fb, unsigned int kk2) {
-    split_store(Bs + (buf * BN + st_row + ROWS_PASS * j) * LS, rb[j], fb);
-    load_b(j, kk2);
-  };
   // the prefix norms fetched during the previous step -> LDS, with the row's threshold theta(t_m, tau) - ||x_t||^2
   auto publish_norms = [&](float ratio) {
     if (tid < BM) {
@@ -220,22 +248,15 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   rt = __builtin_amdgcn_readfirstlane(rt);
   ct = __builtin_amdgcn_readfirstlane(ct);
   aim(rt * BM, ct * BN);
+  int stg = 0;   // LDS stage that holds (or is receiving) the slab of the multiply step in work
   load_norm(0);
-  gload(koff);
+  issue(stg, 0);
   load_rows(rt * BM);
 
   for (int tile_no = 0;; ++tile_no) {
     const int row0 = rt * BM, col0 = ct * BN;
-    // ---- commit the prefetched first slab and per-row data of this tile
-    {
-      // slab 0 of this tile arrived while the previous tile was written out; slab 1 is requested as slab 0 is staged
-      const bool live0 = klive(koff);
-      const unsigned int kk1 = kclamp(koff + BK);
-#pragma unroll
-      for (int j = 0; j < A_F4; ++j) stage_a(j, 0, live0 ? scale_a : 0.f, kk1);
-#pragma unroll
-      for (int j = 0; j < B_F4; ++j) stage_b(j, 0, live0 ? scale_b : 0.f, kk1);
-    }
+    // ---- slab 0 and the per-row data of this tile were requested while the previous tile was written out
+    SKM_VMCNT(0);
     if (tid < BM) {
       s_tau[tid] = tau_reg;
       s_prev[tid] = prev_reg;
@@ -293,10 +314,10 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     float yn[TN] = {0.f, 0.f};
     // Fragments of half a slab (16 dims): lane half kh supplies the 8 consecutive dims 16 h + 8 kh .. + 7 of both
     // operands.  x.y ~ hi.hi' + lo.hi' + hi.lo' on the fp16 matrix cores, fp32 accumulation, in groups of four
-    // matrix instructions between which the next slab is converted and the one after it requested.
+    // matrix instructions; the fragments of the second half-slab are fetched as the first half releases registers.
     f16x8 ah[TM], al[TM], bh[TN], bl[TN];
-    auto frag = [&](const float *base, int h, int lo, int t) {
-      return *reinterpret_cast<const f16x8 *>(base + t * 32 * LS + kh * 4 + h * 8 + lo * 16);
+    auto frag = [&](const uint32_t *base, int h, int lo, int t) {
+      return *reinterpret_cast<const f16x8 *>(base + t * 32 * ROW_WORDS + (((4 * h + 2 * lo + kh) ^ swz) << 2));
     };
     auto mma4 = [&](const f16x8 (&x)[TM], const f16x8 (&y)[TN]) {
 #pragma unroll
@@ -304,15 +325,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
         for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[a], y[b], acc[a][b], 0, 0, 0);
     };
-    auto mix = [&](auto valu_per_mfma) {   // spread `valu` vector instructions behind each of the four matrix ones
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, decltype(valu_per_mfma)::value, 0);
-      }
-    };
     for (int s = 0; s < nslab; ++s) {
-      const int buf = s & 1;
       const int tdone = koff + BK * (s + 1);   // dimensions multiplied after this step
       const bool last = (s + 1 == nslab);
       const bool check = !last && tdone >= g.dprime && tdone < g.d && ((tdone - g.dprime) & (kBlockDims - 1)) == 0;
@@ -322,13 +335,12 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       // those of the step after it, needed or not, so that the request is never behind a branch
       if (cp) publish_norms(s_ratio[m]);
       load_norm(s + 1);
-      const float *Ab = As + (buf * BM + wm * WTM + r32) * LS;
-      const float *Bb = Bs + (buf * BN + wn * WTN + r32) * LS;
+      // the next slab goes straight into the other stage, which every wavefront has finished reading (the barrier
+      // that ended the previous step); it is complete, and visible, after the wait and the barrier below
+      if (!last) issue(stg ^ 1, s + 1);
+      const uint32_t *Ab = smem + stg * STAGE_WORDS + (wm * WTM + r32) * ROW_WORDS;
+      const uint32_t *Bb = smem + stg * STAGE_WORDS + (BM + wn * WTN + r32) * ROW_WORDS;
       {
-        // (the last step of a tile stages a slab past the end: all zeros, into a buffer nobody reads again)
-        const bool live1 = klive(koff + (s + 1) * BK);
-        const float fa = live1 ? scale_a : 0.f, fb = live1 ? scale_b : 0.f;
-        const unsigned int kk2 = kclamp(koff + (s + 2) * BK);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -337,38 +349,22 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
         __builtin_amdgcn_sched_barrier(0);
         mma4(ah, bh);
-        stage_a(0, buf ^ 1, fa, kk2);
-        mix(std::integral_constant<int, 6>());
-        __builtin_amdgcn_sched_barrier(0);
         mma4(al, bh);
-        stage_a(1, buf ^ 1, fa, kk2);
-        mix(std::integral_constant<int, 6>());
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < 2; ++t) { al[t] = frag(Ab, 1, 1, t); bh[t] = frag(Bb, 1, 0, t); }
         mma4(ah, bl);
-        stage_a(2, buf ^ 1, fa, kk2);
-        stage_a(3, buf ^ 1, fa, kk2);
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-        mix(std::integral_constant<int, 11>());
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < 2; ++t) { ah[t] = frag(Ab, 1, 0, t); bl[t] = frag(Bb, 1, 1, t); }
         mma4(al, bh);
-        stage_b(0, buf ^ 1, fb, kk2);
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-        mix(std::integral_constant<int, 6>());
         __builtin_amdgcn_sched_barrier(0);
         mma4(ah, bl);
-        stage_b(1, buf ^ 1, fb, kk2);
-        mix(std::integral_constant<int, 6>());
-        __builtin_amdgcn_sched_barrier(0);
         mma4(ah, bh);
-        stage_b(2, buf ^ 1, fb, kk2);
-        stage_b(3, buf ^ 1, fb, kk2);
-        mix(std::integral_constant<int, 11>());
         __builtin_amdgcn_sched_barrier(0);
       }
+      stg ^= 1;
+      SKM_VMCNT(0);
       __syncthreads();
       if (cp) {
 #pragma unroll
@@ -434,7 +430,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       nct_ = __builtin_amdgcn_readfirstlane(nct_);
       aim(nrt_ * BM, nct_ * BN);
       load_norm(0);
-      gload(koff);
+      issue(stg, 0);   // both stages are free: every wavefront has passed the barrier of the last multiply step
       load_rows(nrt_ * BM);
     }
 
@@ -533,11 +529,11 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
-  if (g.ds % 16 != 0 || g.dprime % 16 != 0 || g.dprime < 16 || g.dprime > g.ds || g.lda % 4 != 0 || g.ldb % 4 != 0 ||
+  if (g.ds % 16 != 0 || g.dprime % 16 != 0 || g.dprime < 16 || g.dprime > g.ds || g.lda != g.ds + 32 || g.ldb != g.ds + 32 ||
       g.nb > kMaxBlocks || (reinterpret_cast<uintptr_t>(g.A) & 15u) || (reinterpret_cast<uintptr_t>(g.B) & 15u) ||
       g.N > (1 << 24))
     return hipErrorInvalidValue;
-  constexpr size_t smem = (size_t)2 * (BM + BN) * LS * sizeof(float);
+  constexpr size_t smem = (size_t)2 * STAGE_WORDS * sizeof(uint32_t);
   static int wgs = 0;
   if (!wgs) {
     hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel),

@@ -94,14 +94,20 @@ constexpr int kSubListStride = 16;
 // theta(t, tau_i) die; the tile stops when nothing is alive, hands its pairs to the gather kernel when
 // at most emit_max are alive, and offers finished distances below tau_i to best[] at t = d.
 // Rows are local to the chunk: global row = row_base + i; tau/prev/best are indexed by global row.
+// Split-fp16 copy of a matrix in the byte order of the progressive kernel's LDS tiles (launch_split_rows): row stride
+// ds + 32 words; dims 16 g .. 16 g + 15 of a row are the 16 words at 16 (g + 1): 8 words of hi halves, 8 of lo halves
+// of the values scaled by split_scale(*absmax); the 16 words before and after the row's data are zero.
+hipError_t launch_split_rows(const float *A, int64_t lda, int64_t rows, int32_t ds, const unsigned int *absmax,
+                             uint32_t *out, hipStream_t st);
+
 struct ProgArgs {
-  const float *A;          // rotated points of the chunk, zero padded to ds columns
-  int64_t lda;
+  const uint32_t *A;       // split-fp16 copy of the rotated points of the chunk (launch_split_rows)
+  int64_t lda;             // ds + 32 words
   int32_t M;
-  const float *B;          // rotated centroids, k x ds
+  const uint32_t *B;       // split-fp16 copy of the rotated centroids
   int64_t ldb;
   int32_t N;
-  const unsigned int *a_absmax, *b_absmax;   // bounds of |A| and |B| for the split-fp16 form (see GemmOperands)
+  const unsigned int *a_absmax, *b_absmax;   // the bounds the copies were scaled by
   int32_t ds, d, dprime, nb;
   const float *ratio;      // [nb + 1] theta ratio at checkpoint m (t_m = min(d, d' + 64 m)); device array
   const float *tau;        // [n]
@@ -147,10 +153,11 @@ hipError_t launch_prune(const PruneArgs &a, hipStream_t st);
 // tau_i = ||x_i - y_{a_i}||^2 over all dims, best_i = pack(tau_i, a_i)
 // (Algorithm 1, "Initial pruning threshold").  Either output may be NULL.
 // With xnp ([ds / 16][n], ds a multiple of 16) the same pass writes the table of prefix norms
-// xnp[p][i] = ||x_i[0 : 16 (p + 1))||^2 that the progressive kernel reads at its checkpoints.
+// xnp[p][i] = ||x_i[0 : 16 (p + 1))||^2 that the progressive kernel reads at its checkpoints; with xs also the
+// split-fp16 copy of the points (the layout of launch_split_rows, scaled by the bound *x_absmax).
 hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
                            const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st,
-                           float *xnp = nullptr);
+                           float *xnp = nullptr, uint32_t *xs = nullptr, const unsigned int *x_absmax = nullptr);
 
 // ynorm[c] = ||Y[c][0:dn)||^2 and (if Ypdx) the block-major copy of the dims from dprime on.
 // ynp (optional, [nb + 1][k]): prefix norms of the centroids at the same checkpoints.

@@ -38,11 +38,36 @@ static int num_cus() {
 // in registers anyway.  Lane l holds dims 4 l + 256 u .. + 3; a quad of lanes holds a 16-dim piece, and an
 // inclusive scan over the 16 quads of the wavefront (then over u) gives every quad the norm of the row up to the
 // end of its piece.
+// With `xs` the pass also writes the split-fp16 copy of the row that the progressive kernel multiplies (the layout
+// of launch_split_rows: row stride ds + 32 words, zero granules around the data).
 struct PrefixOut {
   float *xnp;        // [ds / 16][n] or NULL
   int64_t n;
   int32_t ds;
+  uint32_t *xs;      // [n][ds + 32] or NULL
+  const unsigned int *absmax;   // bound of |X| (bit pattern) that fixes the scale of xs
+  float scale;       // split_scale(*absmax), set by the kernel
 };
+
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+// this lane's float4 at column c (a quarter of granule c / 16) -> hi and lo halves in the split copy of row i
+__device__ inline void emit_split(const PrefixOut &po, int64_t i, int c, const float4 &v) {
+  const f32x2_t p0 = {v.x * po.scale, v.y * po.scale}, p1 = {v.z * po.scale, v.w * po.scale};
+  const f16x2_t h0 = __builtin_convertvector(p0, f16x2_t), h1 = __builtin_convertvector(p1, f16x2_t);
+  const f16x2_t l0 = __builtin_convertvector(p0 - __builtin_convertvector(h0, f32x2_t), f16x2_t);
+  const f16x2_t l1 = __builtin_convertvector(p1 - __builtin_convertvector(h1, f32x2_t), f16x2_t);
+  uint32_t *dst = po.xs + i * (int64_t)(po.ds + 32) + 16 * (c / 16 + 1) + 2 * ((c / 4) & 3);
+  *reinterpret_cast<uint2 *>(dst) = make_uint2(__builtin_bit_cast(unsigned int, h0), __builtin_bit_cast(unsigned int, h1));
+  *reinterpret_cast<uint2 *>(dst + 8) = make_uint2(__builtin_bit_cast(unsigned int, l0), __builtin_bit_cast(unsigned int, l1));
+}
+// the zero granules before and after the data of row i (lanes 0..3 and 4..7, 16 bytes each)
+__device__ inline void emit_split_pads(const PrefixOut &po, int64_t i, int lane) {
+  if (lane < 8) {
+    uint32_t *dst = po.xs + i * (int64_t)(po.ds + 32) + (lane < 4 ? 4 * lane : po.ds + 16 + 4 * (lane - 4));
+    *reinterpret_cast<uint4 *>(dst) = make_uint4(0u, 0u, 0u, 0u);
+  }
+}
 
 // inclusive scan over the 16 quads of a wavefront of a value that is equal within each quad
 __device__ inline float quad_scan64(float v) {
@@ -77,6 +102,7 @@ template <int NV>
 __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t ldx, int64_t n, int32_t ds,
                                                        const float *Y, int64_t ldy, const int32_t *assign, float *tau,
                                                        unsigned long long *best, PrefixOut po) {
+  if (po.xs) po.scale = split_scale(*po.absmax);
   const int lane = threadIdx.x & 63;
   const int64_t nwaves = (int64_t)gridDim.x * 4;
   for (int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); i < n; i += nwaves) {
@@ -114,6 +140,12 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
           base = emit_prefix(po, i, lane, u, q, base);
         }
       }
+      if (po.xs) {
+        emit_split_pads(po, i, lane);
+#pragma unroll
+        for (int u = 0; u < NV; ++u)
+          if (lane * 4 + 256 * u < ds) emit_split(po, i, lane * 4 + 256 * u, xv[u]);
+      }
     } else {
       float base = 0.f;
       for (int c0 = 0; c0 < ds; c0 += 256) {
@@ -132,6 +164,10 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
           const float q = fmaf(xv.x, xv.x, fmaf(xv.y, xv.y, fmaf(xv.z, xv.z, xv.w * xv.w)));
           base = emit_prefix(po, i, lane, c0 >> 8, q, base);
         }
+        if (po.xs) {
+          if (c0 == 0) emit_split_pads(po, i, lane);
+          if (c < ds) emit_split(po, i, c, xv);
+        }
       }
     }
     s = wave_sum(s);
@@ -143,13 +179,15 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
 }
 
 hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
-                           const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st, float *xnp) {
+                           const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st, float *xnp,
+                           uint32_t *xs, const unsigned int *x_absmax) {
   if (n <= 0) return hipSuccess;
   int64_t blocks = (n + 3) / 4;
   const int64_t cap = (int64_t)num_cus() * 32;
   if (blocks > cap) blocks = cap;
   const int nv = (ds + 255) / 256;
-  const PrefixOut po{xnp, n, ds};
+  if (xs && (ds % 16 != 0 || !x_absmax)) return hipErrorInvalidValue;
+  const PrefixOut po{xnp, n, ds, xs, x_absmax, 0.f};
 #define SKM_TAU_LAUNCH(NV)                                                                                          \
   hipLaunchKernelGGL(tau_init_kernel<NV>, dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, ds, Y, ldy, assign, \
                      tau, best, po)
