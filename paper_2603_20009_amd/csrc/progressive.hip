@@ -141,15 +141,26 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int xstart = xcd * tbase + (xcd < trem ? xcd : trem);
   const int xcount = tbase + (xcd < trem ? 1 : 0);
   unsigned int *ctr = g.tile_counter + xcd * kSubListStride;
+  const int panel_sz = PC * nrt;
+  const float inv_panel = 1.0f / (float)panel_sz;
   auto tile_rc = [&](int q, int &rt, int &ct) {   // q-th tile of this XCD -> (row tile, column tile)
     const int logical = xstart + q;
-    const int panel_sz = PC * nrt;
-    const int p = logical / panel_sz;
-    const int r = logical - p * panel_sz;
+    // panel = logical / panel_sz without an integer division: the float estimate is within one of the quotient
+    // (fewer than 2^20 panels), and the remainder says which way
+    int p = (int)((float)logical * inv_panel);
+    int r = logical - p * panel_sz;
+    if (r < 0) {
+      --p;
+      r += panel_sz;
+    } else if (r >= panel_sz) {
+      ++p;
+      r -= panel_sz;
+    }
     const int pc = (nct - p * PC) < PC ? (nct - p * PC) : PC;
-    rt = r / pc;
+    rt = pc == PC ? r >> 4 : r / pc;   // only the last panel can be narrower
     ct = p * PC + (r - rt * pc);
   };
+  static_assert(PC == 16, "the shift above");
 
   unsigned long long *sc = g.scal + (size_t)(blockIdx.x & (kStatReplicas - 1)) * SC_COUNT;
   for (int m = tid; m <= g.nb; m += NT) s_ratio[m] = g.ratio[m];
@@ -241,7 +252,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     s_q[1] = (int)atomicAdd(ctr, 1u);
   }
   __syncthreads();
-  int q = s_q[0];
+  int q = __builtin_amdgcn_readfirstlane(s_q[0]);
   if (q >= xcount) return;
   int rt, ct;
   tile_rc(q, rt, ct);
@@ -421,7 +432,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
 
     // ---- start fetching the next tile before this one is written out
-    q = s_q[(tile_no + 1) & 3];
+    q = __builtin_amdgcn_readfirstlane(s_q[(tile_no + 1) & 3]);
     const bool more = q < xcount;
     int nrt_ = 0, nct_ = 0;
     if (more) {
@@ -484,6 +495,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       unsigned int run = s_base;
       if (run != 0xffffffffu && wave_alive > 0) {
         for (int w = 0; w < wave; ++w) run += s_wcnt[fin_m & 1][w];
+        const int irow = (int)g.row_base + row0 + wm * WTM + 4 * kh;   // + a * 32 + 8 * (v >> 2) + (v & 3)
 #pragma unroll
         for (int a = 0; a < TM; ++a) {
           // per-row data of the 16 rows this lane holds in accumulator row block a: four aligned groups of four rows
@@ -505,7 +517,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 const unsigned int pos =
                     run + __builtin_amdgcn_mbcnt_hi((unsigned int)(mk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mk, 0u));
                 Pair pr;
-                pr.i = (int32_t)(g.row_base + row0 + row_of(a, v));
+                pr.i = irow + a * 32 + 8 * (v >> 2) + (v & 3);
                 pr.j = (int32_t)((uint32_t)gc[b] | ((uint32_t)fin_m << 24));
                 const float p = pick(xn4[v >> 2], v & 3) + fmaf(m2, acc[a][b][v], yn[b]);
                 pr.p = p > 0.f ? p : 0.f;
