@@ -118,8 +118,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ int s_prev[BM];
   __shared__ float s_ratio[kMaxBlocks + 1];
   __shared__ unsigned long long s_dead[NT];   // per thread: accumulator elements that start dead (the incumbent)
-  __shared__ unsigned int s_cnt[2];
-  __shared__ unsigned int s_wcnt[2][4];   // alive pairs of every wavefront at the last checkpoint (by checkpoint parity)
+  __shared__ __align__(16) unsigned int s_wcnt[2][4];   // alive pairs of every wavefront at the last checkpoint (by checkpoint parity)
   __shared__ unsigned int s_base;         // first list slot of a tile that hands its pairs over
   __shared__ int s_q[4];   // ring of tile numbers drawn from the XCD's counter, two tiles ahead of the one in work
 
@@ -164,7 +163,6 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   unsigned long long *sc = g.scal + (size_t)(blockIdx.x & (kStatReplicas - 1)) * SC_COUNT;
   for (int m = tid; m <= g.nb; m += NT) s_ratio[m] = g.ratio[m];
-  if (tid < 2) s_cnt[tid] = 0u;
   s_dead[tid] = 0ull;
 
   // Staging: load instruction j of wavefront w moves tile rows 32 j + 8 w .. + 7 of a slab, 8 lanes per row and 16
@@ -288,10 +286,6 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     unsigned int drawn = 0;
     if (tid == 0) drawn = atomicAdd(ctr, 1u);
     __syncthreads();
-    // The alive counter of checkpoint 0 may still hold the last total of the previous tile (a tile that ends at an
-    // even checkpoint leaves it behind).  Every thread has read that total before the barrier above, and the first
-    // add of this tile comes after the barrier of its first slab.
-    if (tid == 0) s_cnt[0] = 0u;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -396,14 +390,12 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
         // alive pairs of this wavefront and of the whole tile
         wave_alive = wave_sum_i32(__popcll(bits));
-        if (lane == 0) {
-          s_wcnt[m & 1][wave] = (unsigned int)wave_alive;
-          if (wave_alive) atomicAdd(&s_cnt[m & 1], (unsigned int)wave_alive);
-        }
+        if (lane == 0) s_wcnt[m & 1][wave] = (unsigned int)wave_alive;
         __syncthreads();
-        const unsigned int total = s_cnt[m & 1];
+        // (the counts of checkpoint m + 1 go to the other row: a wavefront that is already there cannot disturb this read)
+        const uint4 wc = *reinterpret_cast<const uint4 *>(s_wcnt[m & 1]);
+        const unsigned int total = wc.x + wc.y + wc.z + wc.w;
         if (tid == 0) {
-          s_cnt[(m + 1) & 1] = 0u;   // next checkpoint's counter; nobody reads it before the next barrier
           // a tile that hands its pairs over reserves their slots now (one reservation per tile in the sub-list of
           // this workgroup's XCD): the answer is not needed before the next tile's loads have been requested
           if (!last && total != 0u && total <= g.emit_max) slot0 = atomicAdd(g.pair_count + xcd * kSubListStride, total);

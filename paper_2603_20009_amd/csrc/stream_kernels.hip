@@ -565,6 +565,21 @@ __global__ void __launch_bounds__(256) segment_sum_kernel(const float *Xr, int64
   dst[0] = a0; dst[1] = a1; dst[2] = a2; dst[3] = a3;
 }
 
+// max |v| over a workgroup of 256 threads into *out (bit pattern, unsigned order): one atomic per workgroup, and
+// only if it would raise the word that thousands of workgroups share
+__device__ inline void block_absmax(float v, unsigned int *out) {
+  __shared__ unsigned int s_m[4];
+  float m = fabsf(v);
+#pragma unroll
+  for (int w = 1; w < 64; w <<= 1) m = fmaxf(m, __shfl_xor(m, w, 64));
+  if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = __builtin_bit_cast(unsigned int, m);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned int mb = max(max(s_m[0], s_m[1]), max(s_m[2], s_m[3]));
+    if (mb > __atomic_load_n(out, __ATOMIC_RELAXED)) atomicMax(out, mb);
+  }
+}
+
 // One workgroup per (cluster, slice): partial sums added in segment order, divided by the size.
 // S (optional, [k][ds] fp64) keeps the sum of every cluster between updates: it is overwritten by the total of the
 // partials, or, with `accumulate`, the total (a signed change) is added to it.
@@ -593,14 +608,7 @@ __global__ void __launch_bounds__(256) centroid_mean_kernel(const double *partia
       Y[(int64_t)c * ldy + col] = y;
     }
   }
-  if (y_absmax) {
-    float m = fabsf(y);
-#pragma unroll
-    for (int w = 1; w < 64; w <<= 1) m = fmaxf(m, __shfl_xor(m, w, 64));
-    // thousands of wavefronts share this one word: only those that would raise it take the atomic
-    const unsigned int mb = __builtin_bit_cast(unsigned int, m);
-    if ((threadIdx.x & 63) == 0 && mb > __atomic_load_n(y_absmax, __ATOMIC_RELAXED)) atomicMax(y_absmax, mb);
-  }
+  if (y_absmax) block_absmax(y, y_absmax);
 }
 
 // Y = S / size for every cluster with points (an empty one keeps its row), max |Y| into *y_absmax (zero before).
@@ -618,13 +626,7 @@ __global__ void __launch_bounds__(256) means_from_sums_kernel(const double *S, c
       Y[(int64_t)c * ldy + col] = y;
     }
   }
-  if (y_absmax) {
-    float m = fabsf(y);
-#pragma unroll
-    for (int w = 1; w < 64; w <<= 1) m = fmaxf(m, __shfl_xor(m, w, 64));
-    const unsigned int mb = __builtin_bit_cast(unsigned int, m);
-    if ((threadIdx.x & 63) == 0 && mb > __atomic_load_n(y_absmax, __ATOMIC_RELAXED)) atomicMax(y_absmax, mb);
-  }
+  if (y_absmax) block_absmax(y, y_absmax);
 }
 hipError_t launch_means_from_sums(const double *S, const int32_t *cnt, int32_t k, int32_t ds, float *Y, int64_t ldy,
                                   unsigned int *y_absmax, hipStream_t st) {
