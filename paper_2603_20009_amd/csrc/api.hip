@@ -62,6 +62,8 @@ struct Pool {
   std::vector<void *> ptrs;
   Arena *arena = tl_arena;
   size_t mark = tl_arena ? tl_arena->off : 0;
+  bool count_only = false;   // plan mode: add up what would be taken (256-byte granules), hand out nothing
+  size_t counted = 0;
   ~Pool() {
     for (void *p : ptrs) (void)hipFree(p);
     if (arena) arena->off = mark;
@@ -70,6 +72,11 @@ struct Pool {
   hipError_t get(T **out, size_t count) {
     void *p = nullptr;
     size_t bytes = std::max<size_t>(count, 1) * sizeof(T);
+    if (count_only) {
+      counted += (bytes + 255) & ~(size_t)255;
+      *out = nullptr;
+      return hipSuccess;
+    }
     if (arena) {
       const size_t at = (arena->off + 255) & ~(size_t)255;
       if (at + bytes <= arena->cap) {
@@ -438,6 +445,41 @@ struct Ctx {
   }
 };
 
+// Bytes that a context of this shape takes from its pool (alloc_bounds + alloc_common), counted without allocating.
+size_t plan_common_bytes(int64_t n, int32_t d, int32_t k, int64_t pair_budget, float dense_frac, bool need_update) {
+  Ctx t;
+  t.pool.count_only = true;
+  t.n = n; t.d = d; t.k = k;
+  t.ds = (d + 15) / 16 * 16;
+  if (t.alloc_bounds() != SKM_OK || t.alloc_common(pair_budget, dense_frac, need_update) != SKM_OK) return 0;
+  return t.pool.counted;
+}
+
+// One device allocation for the whole workspace of a top-level call instead of some forty (3.4 ms of allocation and
+// release per fit of 1M x 1536 become 0.8 ms).  Declared before the context, so that the context's pool carves from it.
+// A nested call (a worker of the hierarchical fit, the steps of the sampled fit) finds an arena in place and adds none;
+// whatever does not fit, or the whole workspace if this allocation fails, comes from hipMalloc as before.
+struct CallArena {
+  Arena arena;
+  bool on = false;
+  explicit CallArena(size_t bytes) {
+    if (tl_arena || bytes == 0) return;
+    if (arena.init(bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      arena.base = nullptr;
+      arena.cap = 0;
+      return;
+    }
+    tl_arena = &arena;
+    on = true;
+  }
+  ~CallArena() {
+    if (on) tl_arena = nullptr;
+  }
+  CallArena(const CallArena &) = delete;
+  CallArena &operator=(const CallArena &) = delete;
+};
+
 struct StepStats {
   double objective = 0;
   int64_t survivors = 0, completed = 0, changed = 0, dense_dims = 0, dense_pair_blocks = 0;
@@ -720,6 +762,11 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     return fit_sampled(X, n, d, k, iters, seed, p, centroids_out, assign_out, dist_out);
   }
 
+  // the workspace in one piece: the context's buffers, the rotated points, the rotation matrices and their generator
+  const size_t ds0 = (size_t)round_up(d, 16);
+  const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, true);
+  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 7 * (size_t)d * ds0 * 4 + (size_t)d * 8192 + (size_t)k * 16 + ((size_t)32 << 20)
+                    : 0);
   Ctx c;
   c.st = (hipStream_t)p.stream;
   c.n = n; c.d = d; c.k = k;
