@@ -1230,6 +1230,9 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
   if (pp) p = *pp; else skm_params_default(&p);
   if (p.angular) return fail(SKM_EINVAL, "the angular metric is a fit option: normalise the inputs for a single step");
   skm_trace *tr = p.trace;
+  const size_t ds0 = (size_t)round_up(d, 16);
+  const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, false);
+  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 7 * (size_t)d * ds0 * 4 + (size_t)d * 8192 + ((size_t)32 << 20) : 0);
   Ctx c;
   c.st = (hipStream_t)p.stream;
   c.n = n; c.d = d; c.k = k;
