@@ -500,11 +500,11 @@ int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
   HIPCHK(gemm_argmin(g, c.ynorm, c.best, c.st));
   tm.mark(ST_GEMM);
   // winners -> direct squared distances (also the objective of this step)
-  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, nullptr, nullptr, nullptr, nullptr, c.counters + c.ncounters, c.st));
+  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, nullptr, nullptr, c.k, nullptr, nullptr, c.counters + c.ncounters, c.st));
   HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.assign, nullptr, c.best, c.st));
   HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
   HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT * kStatReplicas, c.st));
-  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, nullptr, nullptr, c.st));
+  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.k, c.obj_partial, nullptr, nullptr, c.st));
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
   HIPCHK(hipMemcpyAsync(c.rb_obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
@@ -539,7 +539,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     GemmOperands g0{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, dprime};
     g0.a_absmax = c.amax + Ctx::AM_XR; g0.b_absmax = c.amax + Ctx::AM_Y;
     HIPCHK(gemm_argmin(g0, c.ynorm, c.best, c.st));
-    HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, nullptr, nullptr, c.counters + c.ncounters, c.st));
+    HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, c.k, nullptr, nullptr, c.counters + c.ncounters, c.st));
     tm.mark(ST_GEMM);
   }
   // the first pruned step of a context also writes the tables that depend on the points only
@@ -574,7 +574,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
       tm.mark(ST_PRUNE);
     }
   }
-  HIPCHK(launch_finalize_assign(c.best, c.prev, c.n, c.assign, c.dist, c.up.cnt, c.obj_partial, c.scal + SC_CHANGED,
+  HIPCHK(launch_finalize_assign(c.best, c.prev, c.n, c.assign, c.dist, c.up.cnt, c.k, c.obj_partial, c.scal + SC_CHANGED,
                                 nullptr, c.st));
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
@@ -1718,7 +1718,7 @@ int skm_assign_exact(const float *X, int64_t n, int32_t d, const float *centroid
   GemmOperands g{Xp, ldx, (int32_t)n, Yp, ldy, k, ds};
   g.a_absmax = amax; g.b_absmax = amax + 1;
   HIPCHK(gemm_argmin(g, ynorm, best, st));
-  HIPCHK(launch_finalize_assign(best, nullptr, n, assign_out, nullptr, nullptr, nullptr, nullptr, nullptr, st));
+  HIPCHK(launch_finalize_assign(best, nullptr, n, assign_out, nullptr, nullptr, k, nullptr, nullptr, nullptr, st));
   if (dist_out) {
     HIPCHK(launch_tau_init(Xp, ldx, n, ds, Yp, ldy, assign_out, dist_out, nullptr, st));
   }

@@ -170,11 +170,11 @@ hipError_t launch_normalize_rows(float *A, int64_t lda, int64_t rows, int32_t co
 hipError_t launch_fill_u64(unsigned long long *p, int64_t n, unsigned long long v, hipStream_t st);
 hipError_t launch_fill_u32(unsigned int *p, int64_t n, unsigned int v, hipStream_t st);
 
-// Unpack best -> assign/dist, count cluster sizes, changed assignments, per-block objective partials.
+// Unpack best -> assign/dist, count cluster sizes (cnt[k], optional), changed assignments, per-block objective partials.
 // *unset is set to 1 if some point still holds the "no centroid yet" key (an internal error).
 hipError_t launch_finalize_assign(const unsigned long long *best, const int32_t *prev, int64_t n, int32_t *assign,
-                                  float *dist, int32_t *cnt, double *obj_partial, unsigned long long *changed,
-                                  unsigned int *unset, hipStream_t st);
+                                  float *dist, int32_t *cnt, int32_t k, double *obj_partial,
+                                  unsigned long long *changed, unsigned int *unset, hipStream_t st);
 int64_t finalize_blocks(int64_t n);
 hipError_t launch_sum_partials(const double *part, int64_t m, double *out, hipStream_t st);
 hipError_t launch_histogram(const int32_t *assign, int64_t n, int32_t *cnt, hipStream_t st);
