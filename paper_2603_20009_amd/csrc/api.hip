@@ -611,7 +611,10 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
 int split_empty(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t *nempty_out);
 int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t *nempty_out, int64_t changed,
                 bool full) {
-  if (!full && c.S_valid && 2 * changed <= c.inc.capacity - 2) {
+  if (!full && c.S_valid && changed == 0) {
+    // no point changed its cluster: sums, sizes and therefore the means are those of the previous update
+    ++c.inc_updates;
+  } else if (!full && c.S_valid && 2 * changed <= c.inc.capacity - 2) {
     ++c.inc_updates;
     HIPCHK(launch_update_incremental(c.Xr, c.ldx, c.n, c.ds, c.assign, c.prev, changed, c.k, c.up, c.inc, c.S, c.Y, c.ds,
                                      c.st, c.amax + Ctx::AM_Y));
