@@ -1030,6 +1030,13 @@ int fit_host_impl(const float *Xh, int64_t n, int32_t d, int32_t k, int32_t iter
   const int64_t nbatch = (n + W - 1) / W;
   const int npass = iters + (p.final_assign ? 1 : 0);
 
+  // the workspace in one piece: the context of a batch, two raw batches and the rotated one, labels (and distances)
+  // of all points, the rotation matrices and their generator, the initial rows
+  const size_t ds0 = (size_t)round_up(d, 16);
+  const size_t plan = plan_common_bytes(W, d, k, p.pair_budget, p.dense_frac, true);
+  CallArena ws(plan ? plan + (size_t)W * (2 * (size_t)d + ds0) * 4 + 3 * (size_t)nbatch * W * 4 + 7 * (size_t)d * ds0 * 4 +
+                          (size_t)d * 8192 + (size_t)k * d * 4 + ((size_t)32 << 20)
+                    : 0);
   Ctx c;
   c.st = (hipStream_t)p.stream;
   c.n = W; c.d = d; c.k = k;

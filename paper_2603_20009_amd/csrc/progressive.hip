@@ -1,7 +1,7 @@
 // Progressive-pruning GEMM (Algorithm 1, iterations >= 2; Section 3.4 "Progressive Pruning").
 //
 // The paper multiplies only the first d' dimensions densely and finishes survivors one by one.
-// On MI355X a 64-dimension step of a dense 128 x 128 tile on the fp32 matrix cores costs about as
+// On MI355X a 64-dimension step of a dense 128 x 128 tile on the matrix cores costs about as
 // much as gathering the same step for 2 % of the tile's pairs, so this kernel keeps multiplying a
 // tile densely, 64 dimensions at a time, while more than a small share of its pairs is alive, and
 // hands the pairs over to the gather kernel (prune.hip) only once the tile is sparse.  The tests are
@@ -11,12 +11,11 @@
 //
 // Partial distances come from the norm expansion ||x_t||^2 + ||y_t||^2 - 2 x_t.y_t (Section 3.1).
 // The prefix norms at the checkpoints are inputs (xnp, ynp): passes that read every point and every
-// centroid anyway write them, so that this kernel, whose vector unit is the busy one, only
-// fetches one number per row and column and checkpoint.
+// centroid anyway write them, and this kernel fetches one number per row and column and checkpoint.
 //
-// Operands arrive already split into fp16 pairs (split_rows_kernel: once per fit for the points, once per
-// step for the centroids), in the very byte order of the LDS tiles, so staging is a copy: every lane moves
-// 16 bytes from global memory straight into LDS and the vector unit is left to the tests.
+// Operands arrive already split into fp16 pairs (the points once per fit, by the first threshold pass; the
+// centroids once per step, by split_rows_kernel), in the very byte order of the LDS tiles, so staging is a
+// copy: every lane moves 16 bytes from global memory straight into LDS and the vector unit is left to the tests.
 //
 // The kernel is persistent: two workgroups per CU take tiles from a per-XCD counter.  When a tile
 // ends, the first slab and the per-row data of the next tile are already being fetched while the
@@ -25,7 +24,6 @@
 
 #include <algorithm>
 #include <cstdlib>
-#include <type_traits>
 
 namespace skm {
 
