@@ -106,7 +106,7 @@ typedef struct skm_params {
   int64_t pair_budget;   /* 0 = default (2^29): capacity, in (point, centroid) pairs, of the list that carries pairs
                             from the dense tiles to the gather kernel; points are processed in chunks of rows
                             sized so that the list cannot overflow */
-  float dense_frac;      /* 0.02 : a 128 x 128 tile keeps multiplying densely, 64 dimensions at a time, while more
+  float dense_frac;      /* 0.0125 : a 128 x 128 tile keeps multiplying densely, 64 dimensions at a time, while more
                             than this share of its pairs is alive; below it the alive pairs are finished one by
                             one by the gather kernel.  1 = hand over right after the first test (the paper's
                             split), 0 = dense tiles only.  Execution strategy only: the tests applied to a

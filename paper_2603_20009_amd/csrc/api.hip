@@ -1644,7 +1644,7 @@ void skm_params_default(skm_params *p) {
   p->etr_tol = 0.005f;
   p->etr_patience = 2;
   p->pair_budget = 0;
-  p->dense_frac = 0.02f;
+  p->dense_frac = 0.0125f;
   p->sample_frac = 0.f;
 }
 

@@ -151,7 +151,7 @@ class FitOptions:
     queries: torch.Tensor | None = None      # device nq x d
     gt: torch.Tensor | None = None           # device nq x topk int64
     pair_budget: int = 0
-    dense_frac: float = 0.02
+    dense_frac: float = 0.0125
     sample_frac: float = 0.0
     angular: bool = False
     full_update: bool = False

@@ -126,7 +126,7 @@ def pruned_case(orc, dg, n, d, k, seed, recipe):
     return X, R, Y, Xr, Yr, prev.astype(np.int32)
 
 
-@pytest.mark.parametrize("dense", [0.02, 1.0, 0.0, 0.3])   # default, hand-over after the first test, dense tiles only
+@pytest.mark.parametrize("dense", [0.0125, 1.0, 0.0, 0.3])   # default, hand-over after the first test, dense tiles only
 @pytest.mark.parametrize("n,d,k,dp,budget", [
     (2000, 128, 100, 0, 0),
     (3000, 208, 257, 0, 0),          # d' = 32, trailing 176 = 2 x 64 + 48 (short tail block)
