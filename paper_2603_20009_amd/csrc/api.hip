@@ -286,9 +286,10 @@ int make_rotation_dev(Pool &pool, int32_t d, uint64_t seed, hipStream_t st, floa
 inline int32_t round_up(int32_t v, int32_t m) { return (v + m - 1) / m * m; }
 
 // *slot = bit pattern of max |A| (the bound the split-fp16 GEMMs scale their operands by)
-int measure_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsigned int *slot, hipStream_t st) {
+int measure_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsigned int *slot, hipStream_t st,
+                   int max_blocks = 0) {
   HIPCHK(launch_fill_u32(slot, 1, 0u, st));
-  HIPCHK(launch_absmax(A, lda, rows, cols, slot, st));
+  HIPCHK(launch_absmax(A, lda, rows, cols, slot, st, max_blocks));
   return SKM_OK;
 }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -715,14 +716,16 @@ int setup_rotation(Pool &pool, hipStream_t st, int32_t d, int32_t ds, const floa
   HIPCHK(pool.get(&rot.Rtp, (size_t)d * ds));
   HIPCHK(launch_pad_copy(R_dev, d, d, d, rot.Rp, ds, ds, 0, st));
   HIPCHK(launch_pad_copy(R_dev, d, d, d, rot.Rtp, ds, ds, 1, st));
-  HIPCHK(pool.get(&rot.amax, 2));
+  if (!rot.amax) HIPCHK(pool.get(&rot.amax, 2));
   return measure_absmax(R_dev, d, d, d, rot.amax, st);
 }
 // out (rows x ds, zero padded) = in (rows x d, stride ldin) * R
 // out_absmax (optional) receives the bit pattern of max |out|
+// (in_measured: rot.amax[1] already bounds |in|)
 int rotate_into(const float *in, int64_t ldin, int64_t rows, int32_t d, int32_t ds, const Rot &rot, float *out,
-                hipStream_t st, unsigned int *out_absmax = nullptr) {
-  if (int rc = measure_absmax(in, ldin, rows, d, rot.amax + 1, st)) return rc;
+                hipStream_t st, unsigned int *out_absmax = nullptr, bool in_measured = false) {
+  if (!in_measured)
+    if (int rc = measure_absmax(in, ldin, rows, d, rot.amax + 1, st)) return rc;
   if (out_absmax) HIPCHK(launch_fill_u32(out_absmax, 1, 0u, st));
   GemmOperands g{in, ldin, (int32_t)rows, rot.Rtp, ds, d, d};
   g.a_absmax = rot.amax + 1; g.b_absmax = rot.amax;
@@ -789,12 +792,36 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   Rot rot;
   float *Xr_own = nullptr;
   if (p.rotate) {
+    // The rotation matrix is made by a chain of small kernels that leaves most of the device idle: the pass over X
+    // that bounds its magnitude (the scale of the split-fp16 product) runs beside it on a second stream.
+    struct SideStream {
+      hipStream_t s = nullptr;
+      ~SideStream() {
+        if (s) (void)hipStreamDestroy(s);
+      }
+    } side;
+    hipEvent_t e_fork = nullptr, e_join = nullptr;
+    const bool beside = !p.R && (int64_t)n * d >= ((int64_t)1 << 26);
+    if (beside) {
+      e_fork = evs.next();
+      e_join = evs.next();
+      if (!e_fork || !e_join) return fail(SKM_EHIP, "hipEventCreate failed");
+      HIPCHK(hipStreamCreateWithFlags(&side.s, hipStreamNonBlocking));
+      HIPCHK(c.pool.get(&rot.amax, 2));
+      HIPCHK(hipEventRecord(e_fork, c.st));   // X is ready where the caller's stream stands now
+      HIPCHK(hipStreamWaitEvent(side.s, e_fork, 0));
+      rc = measure_absmax(X, d, n, d, rot.amax + 1, side.s, 1024);   // four workgroups per CU: the generator's kernels find room
+      if (rc) return rc;
+      HIPCHK(hipEventRecord(e_join, side.s));
+    }
     rc = setup_rotation(c.pool, c.st, d, c.ds, p.R, seed, rot);
     if (rc) return rc;
     HIPCHK(c.pool.get(&Xr_own, (size_t)n * c.ds));
+    if (beside) HIPCHK(hipStreamWaitEvent(c.st, e_join, 0));
     HIPCHK(hipEventRecord(e_rot0, c.st));
-    rc = rotate_into(X, d, n, d, c.ds, rot, Xr_own, c.st, c.amax + Ctx::AM_XR);
+    rc = rotate_into(X, d, n, d, c.ds, rot, Xr_own, c.st, c.amax + Ctx::AM_XR, beside);
     if (rc) return rc;
+    if (beside) HIPCHK(hipStreamSynchronize(side.s));   // nothing is left on the side stream when it is destroyed
     HIPCHK(hipEventRecord(e_rot, c.st));
     c.Xr = Xr_own; c.ldx = c.ds;
   } else if (d == c.ds && aligned16(X) && !p.angular) {

@@ -68,7 +68,9 @@ __device__ inline float split_unscale(unsigned int absmax_bits) {  // exactly 1 
   return __builtin_bit_cast(float, (unsigned int)(254 - e) << 23);
 }
 // *out = max(*out, bit pattern of max |A[i][j]|) over rows x cols; *out must hold 0 (or an earlier bound) before.
-hipError_t launch_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsigned int *out, hipStream_t st);
+// max_blocks > 0 limits the grid (a pass that shares the device with other work should not take every wavefront slot).
+hipError_t launch_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsigned int *out, hipStream_t st,
+                         int max_blocks = 0);
 
 // C[i][j] = alpha * s(i,j) + beta * C[i][j] for j < N; columns N <= j < Nstore are written as 0.
 // If c_absmax is given, max |C| is folded into *c_absmax (as launch_absmax does).

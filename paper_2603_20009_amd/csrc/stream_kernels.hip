@@ -293,11 +293,12 @@ __global__ void __launch_bounds__(256) absmax_kernel(const float *A, int64_t lda
   if ((threadIdx.x & 63) == 0 && m > 0.f) atomicMax(out, __builtin_bit_cast(unsigned int, m));
 }
 
-hipError_t launch_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsigned int *out, hipStream_t st) {
+hipError_t launch_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsigned int *out, hipStream_t st,
+                         int max_blocks) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
   const bool vec = (reinterpret_cast<uintptr_t>(A) & 15u) == 0 && lda % 4 == 0 && cols % 4 == 0;
   const int64_t work = rows * (int64_t)(vec ? cols / 4 : cols);
-  const unsigned blocks = (unsigned)std::min<int64_t>((work + 255) / 256, 256 * 16);
+  const unsigned blocks = (unsigned)std::min<int64_t>((work + 255) / 256, max_blocks > 0 ? max_blocks : 256 * 16);
   if (vec) hipLaunchKernelGGL(absmax_kernel<true>, dim3(blocks), dim3(256), 0, st, A, lda, rows, cols, out);
   else hipLaunchKernelGGL(absmax_kernel<false>, dim3(blocks), dim3(256), 0, st, A, lda, rows, cols, out);
   return hipGetLastError();
