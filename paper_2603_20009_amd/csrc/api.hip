@@ -778,13 +778,20 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   c.n = n; c.d = d; c.k = k;
   c.ds = round_up(d, 16);
   c.block_stats = p.block_stats != 0;
-  StageTimer tm(c.st, true);
+  // stage times are taken only for a caller that asked for the trace (a small fit inside the hierarchical fit spends
+  // a third of its host time creating and reading events otherwise)
+  const bool timed = tr != nullptr;
+  StageTimer tm(c.st, timed);
   Events evs;
-  hipEvent_t e_begin = evs.next(), e_rot = evs.next(), e_init = evs.next(), e_end0 = evs.next(), e_end = evs.next();
-  hipEvent_t e_gt0 = evs.next(), e_gt1 = evs.next(), e_rot0 = evs.next();
-  if (!e_begin || !e_rot || !e_init || !e_end0 || !e_end || !e_gt0 || !e_gt1 || !e_rot0)
-    return fail(SKM_EHIP, "hipEventCreate failed");
-  HIPCHK(hipEventRecord(e_begin, c.st));
+  hipEvent_t e_begin = nullptr, e_rot = nullptr, e_init = nullptr, e_end0 = nullptr, e_end = nullptr;
+  hipEvent_t e_gt0 = nullptr, e_gt1 = nullptr, e_rot0 = nullptr;
+  if (timed) {
+    e_begin = evs.next(); e_rot = evs.next(); e_init = evs.next(); e_end0 = evs.next(); e_end = evs.next();
+    e_gt0 = evs.next(); e_gt1 = evs.next(); e_rot0 = evs.next();
+    if (!e_begin || !e_rot || !e_init || !e_end0 || !e_end || !e_gt0 || !e_gt1 || !e_rot0)
+      return fail(SKM_EHIP, "hipEventCreate failed");
+  }
+  if (timed) HIPCHK(hipEventRecord(e_begin, c.st));
   rc = c.alloc_bounds();
   if (rc) return rc;
 
@@ -818,11 +825,11 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     if (rc) return rc;
     HIPCHK(c.pool.get(&Xr_own, (size_t)n * c.ds));
     if (beside) HIPCHK(hipStreamWaitEvent(c.st, e_join, 0));
-    HIPCHK(hipEventRecord(e_rot0, c.st));
+    if (timed) HIPCHK(hipEventRecord(e_rot0, c.st));
     rc = rotate_into(X, d, n, d, c.ds, rot, Xr_own, c.st, c.amax + Ctx::AM_XR, beside);
     if (rc) return rc;
     if (beside) HIPCHK(hipStreamSynchronize(side.s));   // nothing is left on the side stream when it is destroyed
-    HIPCHK(hipEventRecord(e_rot, c.st));
+    if (timed) HIPCHK(hipEventRecord(e_rot, c.st));
     c.Xr = Xr_own; c.ldx = c.ds;
   } else if (d == c.ds && aligned16(X) && !p.angular) {
     c.Xr = X; c.ldx = d;
@@ -834,8 +841,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   if (p.angular) HIPCHK(launch_normalize_rows(Xr_own, c.ds, n, c.ds, c.st));   // the library's own copy, in place
   if (!p.rotate || p.angular) {
     if (!p.rotate) {
-      HIPCHK(hipEventRecord(e_rot0, c.st));
-      HIPCHK(hipEventRecord(e_rot, c.st));
+      if (timed) HIPCHK(hipEventRecord(e_rot0, c.st));
+      if (timed) HIPCHK(hipEventRecord(e_rot, c.st));
     }
     rc = c.measure_xr();
     if (rc) return rc;
@@ -865,7 +872,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   float *Qr = nullptr, *Sq = nullptr, *ynorm_full = nullptr;
   unsigned long long *gt_keys = nullptr, *etr_scal = nullptr;
   int32_t nprobe = 0;
-  HIPCHK(hipEventRecord(e_gt0, c.st));
+  if (timed) HIPCHK(hipEventRecord(e_gt0, c.st));
   if (p.etr) {
     if (p.nq < 1 || p.topk < 1 || p.topk > 256) return fail(SKM_EINVAL, "ETR: nq >= 1 and 1 <= topk <= 256 required");
     nprobe = nprobe_of(k, p.probe_frac);
@@ -920,8 +927,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     HIPCHK(c.pool.get(&ynorm_full, (size_t)k));
     HIPCHK(c.pool.get(&etr_scal, 2));
   }
-  HIPCHK(hipEventRecord(e_gt1, c.st));
-  HIPCHK(hipEventRecord(e_init, c.st));
+  if (timed) HIPCHK(hipEventRecord(e_gt1, c.st));
+  if (timed) HIPCHK(hipEventRecord(e_init, c.st));
 
   int32_t dprime = dprime_init(d, p.dprime_frac);
   Rng split_rng = rng_stream(seed, STREAM_SPLIT);
@@ -1004,7 +1011,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   if (dist_out) HIPCHK(hipMemcpyAsync(dist_out, c.dist, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
 
   // ---- Algorithm 1, last line: Y = Y~ R^T
-  HIPCHK(hipEventRecord(e_end0, c.st));
+  if (timed) HIPCHK(hipEventRecord(e_end0, c.st));
   if (p.rotate) {
     rc = unrotate_into(c.Y, c.ds, k, d, c.ds, rot, centroids_out, c.st);
     if (rc) return rc;
@@ -1012,7 +1019,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     HIPCHK(hipMemcpy2DAsync(centroids_out, sizeof(float) * (size_t)d, c.Y, sizeof(float) * (size_t)c.ds,
                             sizeof(float) * (size_t)d, (size_t)k, hipMemcpyDeviceToDevice, c.st));
   }
-  HIPCHK(hipEventRecord(e_end, c.st));
+  if (timed) HIPCHK(hipEventRecord(e_end, c.st));
   HIPCHK(hipStreamSynchronize(c.st));
   if (dprime_out) *dprime_out = dprime;
   if (tr) {
