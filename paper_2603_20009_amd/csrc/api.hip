@@ -328,7 +328,7 @@ struct Ctx {
   unsigned int *counters = nullptr;  // per chunk the fill counters of the sub-lists, then [1] error flag (overflow / unset point)
   size_t ncounters = 0;              // words in `counters` before the flag
   float *ratio_dev = nullptr;        // [kMaxBlocks + 1]
-  float ratio_host[kMaxBlocks + 1];  // staging for ratio_dev (must outlive the async copy)
+  float *ratio_host = nullptr;       // [kMaxBlocks + 1] page-locked staging for ratio_dev (behind the read-back block)
   unsigned long long *scal = nullptr;  // [SC_COUNT]
   double *obj_partial = nullptr, *obj = nullptr;
   UpdateWs up{};
@@ -356,15 +356,28 @@ struct Ctx {
   unsigned int *rb_flag = nullptr;
   int32_t *rb_cnt = nullptr;               // [k]
   bool rb_cnt_valid = false;               // rb_cnt holds the sizes of c.assign's clusters
-  int alloc_readback() {
-    const size_t nscal = (size_t)SC_COUNT * kStatReplicas;
-    if (!rb_block) rb_block = tl_pinned.take(nscal * 8 + 16 + sizeof(int32_t) * (size_t)k, &rb_cap);
+  char *zblock = nullptr;                  // device: counters | flag | scal | obj | up.cnt (see alloc_common)
+  size_t zbytes = 0, rb_off = 0;           // the part from rb_off on is what comes back to the host
+  // start of a step: everything it counts into is cleared
+  int clear_step_block() {
+    HIPCHK(hipMemsetAsync(zblock, 0, zbytes, st));
+    return SKM_OK;
+  }
+  // end of a step: flag, scalars, objective and cluster sizes in one copy; the caller waits on the stream
+  int fetch_step_block() {
+    HIPCHK(hipMemcpyAsync(rb_block, zblock + rb_off, zbytes - rb_off, hipMemcpyDeviceToHost, st));
+    return SKM_OK;
+  }
+  int alloc_readback(size_t o_scal, size_t o_obj, size_t o_cnt) {
+    const size_t o_ratio = (zbytes - rb_off + 15) & ~(size_t)15;
+    if (!rb_block) rb_block = tl_pinned.take(o_ratio + sizeof(float) * ((size_t)kMaxBlocks + 1), &rb_cap);
     char *h = static_cast<char *>(rb_block);
     if (!h) return fail(SKM_EHIP, "hipHostMalloc failed for the step read-back block");
-    rb_scal = reinterpret_cast<unsigned long long *>(h);
-    rb_obj = reinterpret_cast<double *>(h + nscal * 8);
-    rb_flag = reinterpret_cast<unsigned int *>(h + nscal * 8 + 8);
-    rb_cnt = reinterpret_cast<int32_t *>(h + nscal * 8 + 16);
+    rb_flag = reinterpret_cast<unsigned int *>(h);
+    rb_scal = reinterpret_cast<unsigned long long *>(h + o_scal);
+    rb_obj = reinterpret_cast<double *>(h + o_obj);
+    rb_cnt = reinterpret_cast<int32_t *>(h + o_cnt);
+    ratio_host = reinterpret_cast<float *>(h + o_ratio);
     return SKM_OK;
   }
 
@@ -381,7 +394,6 @@ struct Ctx {
   }
 
   int alloc_common(int64_t pair_budget, float dense_frac, bool need_update) {
-    if (int rc = alloc_readback()) return rc;
     HIPCHK(pool.get(&Y, (size_t)k * ds));
     const int32_t nbmax = (ds - 16 + kBlockDims - 1) / kBlockDims + 1;
     HIPCHK(pool.get(&Ypdx, (size_t)nbmax * k * kBlockDims));
@@ -414,12 +426,27 @@ struct Ctx {
     if (pair_cap >= ((int64_t)1 << 32)) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
     HIPCHK(pool.get(&pairs, (size_t)pair_cap));
     ncounters = (size_t)nchunks * (kSubLists + 8) * kSubListStride;   // list fill counters, then tile counters
-    HIPCHK(pool.get(&counters, ncounters + 1));
+    // Everything a step clears at its start and reports at its end is one block: counters | flag | step scalars |
+    // objective | cluster sizes.  One memset, and one copy (from the flag on) into the page-locked mirror.
+    {
+      const size_t nscal = (size_t)SC_COUNT * kStatReplicas;
+      const size_t off_flag = ncounters * sizeof(unsigned int);
+      const size_t off_scal = (off_flag + sizeof(unsigned int) + 7) & ~(size_t)7;
+      const size_t off_obj = off_scal + nscal * sizeof(unsigned long long);
+      const size_t off_cnt = off_obj + sizeof(double);
+      zbytes = off_cnt + sizeof(int32_t) * (size_t)k;
+      HIPCHK(pool.get(&zblock, zbytes));
+      rb_off = off_flag;
+      if (zblock) {
+        counters = reinterpret_cast<unsigned int *>(zblock);
+        scal = reinterpret_cast<unsigned long long *>(zblock + off_scal);
+        obj = reinterpret_cast<double *>(zblock + off_obj);
+        up.cnt = reinterpret_cast<int32_t *>(zblock + off_cnt);
+      }
+      if (int rc = alloc_readback(off_scal - off_flag, off_obj - off_flag, off_cnt - off_flag)) return rc;
+    }
     HIPCHK(pool.get(&ratio_dev, (size_t)kMaxBlocks + 1));
-    HIPCHK(pool.get(&scal, (size_t)SC_COUNT * kStatReplicas));
     HIPCHK(pool.get(&obj_partial, (size_t)finalize_blocks(n)));
-    HIPCHK(pool.get(&obj, 1));
-    HIPCHK(pool.get(&up.cnt, (size_t)k));
     if (need_update) {
       HIPCHK(pool.get(&up.off, (size_t)k + 1));
       HIPCHK(pool.get(&up.cursor, (size_t)k));
@@ -492,7 +519,7 @@ struct StepStats {
 // Iteration 1 of Algorithm 1: exact assignment over all dims.  Leaves assign, dist, cluster sizes.
 int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
   tm.mark(ST_NONE);
-  HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * (c.ncounters + 1), c.st));
+  if (int rc = c.clear_step_block()) return rc;
   HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, c.ds, c.ynorm, 0, 0, nullptr, c.st));
   HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
   if (int rc = c.measure_y()) return rc;
@@ -503,14 +530,10 @@ int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
   // winners -> direct squared distances (also the objective of this step)
   HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, nullptr, nullptr, c.k, nullptr, nullptr, c.counters + c.ncounters, c.st));
   HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.assign, nullptr, c.best, c.st));
-  HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
-  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT * kStatReplicas, c.st));
   HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.k, c.obj_partial, nullptr, nullptr, c.st));
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
-  HIPCHK(hipMemcpyAsync(c.rb_obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
-  HIPCHK(hipMemcpyAsync(c.rb_flag, c.counters + c.ncounters, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
-  HIPCHK(hipMemcpyAsync(c.rb_cnt, c.up.cnt, sizeof(int32_t) * (size_t)c.k, hipMemcpyDeviceToHost, c.st));
+  if (int rc = c.fetch_step_block()) return rc;
   HIPCHK(hipStreamSynchronize(c.st));
   c.rb_cnt_valid = true;
   if (*c.rb_flag != 0) return fail(SKM_EINTERNAL, "a point was left without a centroid");
@@ -534,7 +557,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   float *ratio = c.ratio_host;
   for (int m = 0; m <= nb; ++m) ratio[m] = (float)theta_ratio(c.d, std::min(c.d, dprime + kBlockDims * m), eps0);
   HIPCHK(hipMemcpyAsync(c.ratio_dev, ratio, sizeof(float) * ((size_t)nb + 1), hipMemcpyHostToDevice, c.st));
-  HIPCHK(hipMemsetAsync(c.counters, 0, sizeof(unsigned int) * (c.ncounters + 1), c.st));
+  if (int rc = c.clear_step_block()) return rc;
   if (!have_prev) {
     HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
     GemmOperands g0{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, dprime};
@@ -548,8 +571,6 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
                          c.xnp_valid ? nullptr : c.Xs, c.amax + Ctx::AM_XR));
   c.xnp_valid = true;
   HIPCHK(launch_split_rows(c.Y, c.ds, c.k, c.ds, c.amax + Ctx::AM_Y, c.Ys, c.st));
-  HIPCHK(hipMemsetAsync(c.scal, 0, sizeof(unsigned long long) * (size_t)SC_COUNT * kStatReplicas, c.st));
-  HIPCHK(hipMemsetAsync(c.up.cnt, 0, sizeof(int32_t) * (size_t)c.k, c.st));
   tm.mark(ST_TAU);
   for (int32_t ch = 0; ch < c.nchunks; ++ch) {
     const int64_t r0 = (int64_t)ch * c.chunk_rows;
@@ -580,10 +601,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
   tm.mark(ST_TAU);
   const size_t nscal = (size_t)SC_COUNT * kStatReplicas;
-  HIPCHK(hipMemcpyAsync(c.rb_flag, c.counters + c.ncounters, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
-  HIPCHK(hipMemcpyAsync(c.rb_scal, c.scal, sizeof(unsigned long long) * nscal, hipMemcpyDeviceToHost, c.st));
-  HIPCHK(hipMemcpyAsync(c.rb_obj, c.obj, sizeof(double), hipMemcpyDeviceToHost, c.st));
-  HIPCHK(hipMemcpyAsync(c.rb_cnt, c.up.cnt, sizeof(int32_t) * (size_t)c.k, hipMemcpyDeviceToHost, c.st));
+  if (int rc = c.fetch_step_block()) return rc;
   HIPCHK(hipStreamSynchronize(c.st));
   c.rb_cnt_valid = true;
   if (*c.rb_flag != 0) return fail(SKM_EINTERNAL, "hand-over list overflow or a point left without a centroid");
