@@ -272,25 +272,43 @@ hipError_t launch_fill_u32(unsigned int *p, int64_t n, unsigned int v, hipStream
 
 // ------------------------------------------------------------------ largest magnitude of a matrix
 // Non-negative floats order like their bit patterns, so the maximum is kept with an unsigned atomicMax.
+// max |v| over a workgroup of 256 threads into *out (bit pattern, unsigned order): one atomic per workgroup, and
+// only if it would raise the word that thousands of workgroups share
+__device__ inline void block_absmax(float v, unsigned int *out) {
+  __shared__ unsigned int s_m[4];
+  float m = fabsf(v);
+#pragma unroll
+  for (int w = 1; w < 64; w <<= 1) m = fmaxf(m, __shfl_xor(m, w, 64));
+  if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = __builtin_bit_cast(unsigned int, m);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned int mb = max(max(s_m[0], s_m[1]), max(s_m[2], s_m[3]));
+    if (mb > __atomic_load_n(out, __ATOMIC_RELAXED)) atomicMax(out, mb);
+  }
+}
+
+// Rows without gaps (lda == cols) are read as one array; otherwise an element index is split into row and column.
 template <bool VEC4>
 __global__ void __launch_bounds__(256) absmax_kernel(const float *A, int64_t lda, int64_t rows, int32_t cols,
                                                      unsigned int *out) {
   const int64_t per_row = VEC4 ? cols / 4 : cols;
   const int64_t total = rows * per_row;
+  const bool flat = lda == cols;
   float m = 0.f;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t r = e / per_row;
-    const int64_t cidx = e - r * per_row;
+    int64_t at = e * (VEC4 ? 4 : 1);
+    if (!flat) {
+      const int64_t r = e / per_row;
+      at = r * lda + (e - r * per_row) * (VEC4 ? 4 : 1);
+    }
     if (VEC4) {
-      const float4 v = *reinterpret_cast<const float4 *>(A + r * lda + 4 * cidx);
+      const float4 v = *reinterpret_cast<const float4 *>(A + at);
       m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
     } else {
-      m = fmaxf(m, fabsf(A[r * lda + cidx]));
+      m = fmaxf(m, fabsf(A[at]));
     }
   }
-#pragma unroll
-  for (int w = 1; w < 64; w <<= 1) m = fmaxf(m, __shfl_xor(m, w, 64));
-  if ((threadIdx.x & 63) == 0 && m > 0.f) atomicMax(out, __builtin_bit_cast(unsigned int, m));
+  block_absmax(m, out);
 }
 
 hipError_t launch_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsigned int *out, hipStream_t st,
@@ -298,7 +316,8 @@ hipError_t launch_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols
   if (rows <= 0 || cols <= 0) return hipSuccess;
   const bool vec = (reinterpret_cast<uintptr_t>(A) & 15u) == 0 && lda % 4 == 0 && cols % 4 == 0;
   const int64_t work = rows * (int64_t)(vec ? cols / 4 : cols);
-  const unsigned blocks = (unsigned)std::min<int64_t>((work + 255) / 256, max_blocks > 0 ? max_blocks : 256 * 16);
+  // at least four elements per thread where there are that many: fewer workgroups meet at the one result word
+  const unsigned blocks = (unsigned)std::min<int64_t>((work + 1023) / 1024, max_blocks > 0 ? max_blocks : 256 * 16);
   if (vec) hipLaunchKernelGGL(absmax_kernel<true>, dim3(blocks), dim3(256), 0, st, A, lda, rows, cols, out);
   else hipLaunchKernelGGL(absmax_kernel<false>, dim3(blocks), dim3(256), 0, st, A, lda, rows, cols, out);
   return hipGetLastError();
@@ -533,13 +552,16 @@ __global__ void __launch_bounds__(256) sort_segments_kernel(const int32_t *off, 
   for (int t = threadIdx.x; t < len; t += 256) order[lo + t] = s[t];
 }
 
-// One workgroup per (segment of <= kSegPoints points of one cluster, slice of 1024 dims):
-// rows are gathered through `order` (each a contiguous row read), summed in fp64 per thread.
+// One workgroup per (segment of <= kSegPoints points of one cluster, slice of 256 dims): rows are gathered through
+// `order` (each a contiguous row read).  Wavefront w takes the points p0 + w, p0 + w + 4, ... of the segment, four
+// rows in flight per thread, fp64 sums per thread; the four wavefronts' sums are added in a fixed order, so the
+// result depends on the segment only.
 // SIGNED: an entry i >= 0 adds row i, an entry ~i < 0 subtracts row i (a point that left the cluster).
 template <bool SIGNED>
 __global__ void __launch_bounds__(256) segment_sum_kernel(const float *Xr, int64_t ldx, int32_t ds, int32_t k,
                                                           const int32_t *off, const int32_t *segoff,
                                                           const int32_t *order, double *partial) {
+  __shared__ double red[3][64][4];
   const int seg = blockIdx.x;
   if (seg >= segoff[k]) return;
   // cluster of this segment: last c with segoff[c] <= seg
@@ -552,50 +574,53 @@ __global__ void __launch_bounds__(256) segment_sum_kernel(const float *Xr, int64
   const int s_in = seg - segoff[c];
   const int p0 = off[c] + s_in * kSegPoints;
   const int p1 = min(off[c + 1], p0 + kSegPoints);
-  const int col = (blockIdx.y * 256 + threadIdx.x) * 4;
-  if (col >= ds) return;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int col = (blockIdx.y * 64 + lane) * 4;
+  const bool live = col < ds;
   double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
-  int p = p0;
-  if (SIGNED) {
-    for (; p < p1; ++p) {
-      const int raw = order[p];
-      const int i = raw < 0 ? ~raw : raw;
-      const double sg = raw < 0 ? -1.0 : 1.0;
-      const float4 v = *reinterpret_cast<const float4 *>(Xr + (int64_t)i * ldx + col);
+  auto row = [&](int raw, float4 &v, double &sg) {
+    const int i = SIGNED && raw < 0 ? ~raw : raw;
+    sg = SIGNED && raw < 0 ? -1.0 : 1.0;
+    v = *reinterpret_cast<const float4 *>(Xr + (int64_t)i * ldx + col);
+  };
+  auto add = [&](const float4 &v, double sg) {
+    if (SIGNED) {
       a0 += sg * (double)v.x; a1 += sg * (double)v.y; a2 += sg * (double)v.z; a3 += sg * (double)v.w;
+    } else {
+      a0 += (double)v.x; a1 += (double)v.y; a2 += (double)v.z; a3 += (double)v.w;
+    }
+  };
+  if (live) {
+    int p = p0 + w;
+    for (; p + 12 < p1; p += 16) {
+      float4 v0, v1, v2, v3;
+      double s0, s1, s2, s3;
+      row(order[p], v0, s0);
+      row(order[p + 4], v1, s1);
+      row(order[p + 8], v2, s2);
+      row(order[p + 12], v3, s3);
+      add(v0, s0);
+      add(v1, s1);
+      add(v2, s2);
+      add(v3, s3);
+    }
+    for (; p < p1; p += 4) {
+      float4 v;
+      double sg;
+      row(order[p], v, sg);
+      add(v, sg);
     }
   }
-  for (; p + 4 <= p1; p += 4) {
-    const int i0 = order[p], i1 = order[p + 1], i2 = order[p + 2], i3 = order[p + 3];
-    const float4 v0 = *reinterpret_cast<const float4 *>(Xr + (int64_t)i0 * ldx + col);
-    const float4 v1 = *reinterpret_cast<const float4 *>(Xr + (int64_t)i1 * ldx + col);
-    const float4 v2 = *reinterpret_cast<const float4 *>(Xr + (int64_t)i2 * ldx + col);
-    const float4 v3 = *reinterpret_cast<const float4 *>(Xr + (int64_t)i3 * ldx + col);
-    a0 += (double)v0.x; a1 += (double)v0.y; a2 += (double)v0.z; a3 += (double)v0.w;
-    a0 += (double)v1.x; a1 += (double)v1.y; a2 += (double)v1.z; a3 += (double)v1.w;
-    a0 += (double)v2.x; a1 += (double)v2.y; a2 += (double)v2.z; a3 += (double)v2.w;
-    a0 += (double)v3.x; a1 += (double)v3.y; a2 += (double)v3.z; a3 += (double)v3.w;
+  if (w > 0) {
+    red[w - 1][lane][0] = a0; red[w - 1][lane][1] = a1; red[w - 1][lane][2] = a2; red[w - 1][lane][3] = a3;
   }
-  for (; p < p1; ++p) {
-    const float4 v = *reinterpret_cast<const float4 *>(Xr + (int64_t)order[p] * ldx + col);
-    a0 += (double)v.x; a1 += (double)v.y; a2 += (double)v.z; a3 += (double)v.w;
-  }
-  double *dst = partial + (int64_t)seg * ds + col;
-  dst[0] = a0; dst[1] = a1; dst[2] = a2; dst[3] = a3;
-}
-
-// max |v| over a workgroup of 256 threads into *out (bit pattern, unsigned order): one atomic per workgroup, and
-// only if it would raise the word that thousands of workgroups share
-__device__ inline void block_absmax(float v, unsigned int *out) {
-  __shared__ unsigned int s_m[4];
-  float m = fabsf(v);
-#pragma unroll
-  for (int w = 1; w < 64; w <<= 1) m = fmaxf(m, __shfl_xor(m, w, 64));
-  if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = __builtin_bit_cast(unsigned int, m);
   __syncthreads();
-  if (threadIdx.x == 0) {
-    const unsigned int mb = max(max(s_m[0], s_m[1]), max(s_m[2], s_m[3]));
-    if (mb > __atomic_load_n(out, __ATOMIC_RELAXED)) atomicMax(out, mb);
+  if (w == 0 && live) {
+    double *dst = partial + (int64_t)seg * ds + col;
+    dst[0] = (a0 + red[0][lane][0]) + (red[1][lane][0] + red[2][lane][0]);
+    dst[1] = (a1 + red[0][lane][1]) + (red[1][lane][1] + red[2][lane][1]);
+    dst[2] = (a2 + red[0][lane][2]) + (red[1][lane][2] + red[2][lane][2]);
+    dst[3] = (a3 + red[0][lane][3]) + (red[1][lane][3] + red[2][lane][3]);
   }
 }
 
@@ -691,7 +716,7 @@ hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, co
   hipLaunchKernelGGL(scatter_order_kernel, dim3((unsigned)blocks), dim3(256), 0, st, assign, n, w.off, w.cursor,
                      w.order, (const int32_t *)nullptr);
   hipLaunchKernelGGL(sort_segments_kernel, dim3(k), dim3(256), 0, st, w.off, w.order);
-  const unsigned slices4 = (unsigned)((ds + 1023) / 1024);
+  const unsigned slices4 = (unsigned)((ds + 255) / 256);   // 64 lanes x 4 dims per workgroup
   hipLaunchKernelGGL(segment_sum_kernel<false>, dim3((unsigned)w.max_segments, slices4), dim3(256), 0, st, Xr, ldx, ds, k,
                      w.off, w.segoff, w.order, w.partial);
   const unsigned slices1 = (unsigned)((ds + 255) / 256);
@@ -731,7 +756,7 @@ hipError_t launch_update_incremental(const float *Xr, int64_t ldx, int64_t n, in
     hipLaunchKernelGGL(scatter_order_kernel, dim3((unsigned)blocks), dim3(256), 0, st, inc.ent_lab, m2, inc.off, inc.cursor,
                        inc.order, (const int32_t *)inc.ent_id);
     hipLaunchKernelGGL(sort_segments_kernel, dim3(k), dim3(256), 0, st, inc.off, inc.order);
-    const unsigned slices4 = (unsigned)((ds + 1023) / 1024);
+    const unsigned slices4 = (unsigned)((ds + 255) / 256);   // 64 lanes x 4 dims per workgroup
     const int64_t segs = std::min<int64_t>(inc.max_segments, (int64_t)k + m2 / kSegPoints + 1);
     hipLaunchKernelGGL(segment_sum_kernel<true>, dim3((unsigned)segs, slices4), dim3(256), 0, st, Xr, ldx, ds, k, inc.off,
                        inc.segoff, inc.order, inc.partial);
