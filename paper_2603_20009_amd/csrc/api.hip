@@ -446,7 +446,7 @@ struct Ctx {
       if (int rc = alloc_readback(off_scal - off_flag, off_obj - off_flag, off_cnt - off_flag)) return rc;
     }
     HIPCHK(pool.get(&ratio_dev, (size_t)kMaxBlocks + 1));
-    HIPCHK(pool.get(&obj_partial, (size_t)finalize_blocks(n)));
+    HIPCHK(pool.get(&obj_partial, (size_t)(n + 1023) / 1024));   // at least finalize_blocks(m) for every m <= n
     if (need_update) {
       HIPCHK(pool.get(&up.off, (size_t)k + 1));
       HIPCHK(pool.get(&up.cursor, (size_t)k));

@@ -361,28 +361,30 @@ hipError_t launch_normalize_rows(float *A, int64_t lda, int64_t rows, int32_t co
 // A workgroup takes 8192 consecutive points.  The cluster sizes are counted in LDS first when the k counters fit
 // (k <= FIN_LDS_BINS) and flushed once per workgroup: a million atomic increments on the 64 cache lines that hold 1024
 // counters took 0.2 ms per step; larger k spreads them over more lines and goes to memory directly.
+// Small inputs (one small fit of many, as in the hierarchical fit) take 1024 points per workgroup instead: the
+// launch is then a few workgroups side by side rather than one long loop.
 constexpr int FIN_THREADS = 256;
-constexpr int FIN_PER_BLOCK = 8192;
 constexpr int FIN_LDS_BINS = 8192;
-int64_t finalize_blocks(int64_t n) { return (n + FIN_PER_BLOCK - 1) / FIN_PER_BLOCK; }
+static int finalize_per_block(int64_t n) { return n >= (int64_t)1 << 18 ? 8192 : 1024; }
+int64_t finalize_blocks(int64_t n) { return (n + finalize_per_block(n) - 1) / finalize_per_block(n); }
 
 __global__ void __launch_bounds__(FIN_THREADS) finalize_assign_kernel(const unsigned long long *best,
                                                                       const int32_t *prev, int64_t n, int32_t *assign,
                                                                       float *dist, int32_t *cnt, int32_t k,
                                                                       double *obj_partial, unsigned long long *changed,
-                                                                      unsigned int *unset) {
+                                                                      unsigned int *unset, int per_block) {
   __shared__ double red[4];
   __shared__ unsigned int redc[4];
   __shared__ int s_hist[FIN_LDS_BINS];
-  const bool in_lds = cnt && k <= FIN_LDS_BINS;
+  const bool in_lds = cnt && k <= FIN_LDS_BINS && per_block > 1024;
   if (in_lds) {
     for (int b = threadIdx.x; b < k; b += FIN_THREADS) s_hist[b] = 0;
     __syncthreads();
   }
   double s = 0.0;
   unsigned int ch = 0;
-  const int64_t base = (int64_t)blockIdx.x * FIN_PER_BLOCK;
-  for (int t = threadIdx.x; t < FIN_PER_BLOCK; t += FIN_THREADS) {
+  const int64_t base = (int64_t)blockIdx.x * per_block;
+  for (int t = threadIdx.x; t < per_block; t += FIN_THREADS) {
     const int64_t i = base + t;
     if (i < n) {
       const unsigned long long key = best[i];
@@ -426,7 +428,7 @@ hipError_t launch_finalize_assign(const unsigned long long *best, const int32_t 
                                   unsigned long long *changed, unsigned int *unset, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(finalize_assign_kernel, dim3((unsigned)finalize_blocks(n)), dim3(FIN_THREADS), 0, st, best, prev, n,
-                     assign, dist, cnt, k, obj_partial, changed, unset);
+                     assign, dist, cnt, k, obj_partial, changed, unset, finalize_per_block(n));
   return hipGetLastError();
 }
 

@@ -573,7 +573,8 @@ def test_incremental_update_matches_the_full_one(skm, orc, dg):
 @pytest.mark.parametrize("pinned", [True, False])
 @pytest.mark.parametrize("n,d,k,batch", [(20_000, 128, 64, 4096),      # 5 batches, ragged last one (3616 rows)
                                          (5000, 100, 24, 1536),        # padded dims, 4 batches, tail of 392 rows
-                                         (3000, 64, 16, 0)])           # one batch holds everything
+                                         (3000, 64, 16, 0),            # one batch holds everything
+                                         (300_000, 32, 8, 262_144)])   # a large batch, then a tail an eighth its size
 def test_host_resident_fit(skm, orc, dg, n, d, k, batch, pinned):
     """Section 7.1: the points stay in host memory and pass through the device in batches, every iteration.
     The result must be Algorithm 1's, i.e. the oracle's, and that of the device-resident fit."""
