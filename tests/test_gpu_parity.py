@@ -372,6 +372,38 @@ def test_c2_full_size_sampled_parity(skm, orc, dg):
     torch.cuda.empty_cache()
 
 
+def test_c4_full_size_sampled_parity(skm, orc, dg):
+    """Workload C4 (1 000 000 x 1536, k = 16 384): the large-k regime, where a step is a million tiles of one to
+    three slabs.  Pruned steps at d' = 192 and at d' = 64 (what the d' rule reaches on this workload), checked by
+    the oracle on a sample of the rows one by one."""
+    torch.cuda.empty_cache()
+    n, d, k = 1_000_000, 1536, 16_384
+    say("generating C4")
+    X = dg.config_data("C4", device="cuda")
+    Rn = orc.random_rotation(d, 42)
+    R = cuda(Rn)
+    say("fit 3 iterations")
+    fr = skm.fit(X, k, 3, 42, skm.FitOptions(R=R, final_assign=False, adjust_dprime=False))
+    rng = np.random.default_rng(1)
+    rows = np.sort(rng.choice(n, 3072, replace=False))
+    Xr = orc.rotate(X[torch.from_numpy(rows).cuda()].cpu().numpy(), Rn)
+    say("rotating the centroids on the host")
+    Yr = orc.rotate(fr.centroids.cpu().numpy(), Rn)
+    prev = fr.assign.cpu().numpy()[rows]
+    for dp in (192, 64):
+        say("assign step at d' =", dp)
+        a, dist, row = skm.assign(X, fr.centroids, fr.assign, dp, skm.FitOptions(R=R))
+        ref = orc.assign_pruned(Xr, Yr, prev, dp, EPS0, 0)
+        check_assignment(a.cpu().numpy()[rows], ref.assign, Xr, Yr, min_agree=0.995)
+        same = a.cpu().numpy()[rows] == ref.assign
+        assert np.abs(dist.cpu().numpy()[rows][same] - ref.dist[same]).max() < 1e-5
+        surv_ref = len(rows) * (k - 1) - ref.pruned_first
+        assert row["survivors"] / n == pytest.approx(surv_ref / len(rows), rel=0.2)    # same survivor density (a heavy-tailed count per point)
+        assert row["dprime"] == dp
+    del X, fr
+    torch.cuda.empty_cache()
+
+
 def test_tall_problems_are_cut_into_bands_of_row_tiles(orc, dg):
     """A launch holds at most 2^24 - 1 tiles; the limit is lowered through the environment in a child
     process so that the banding of the GEMM launches runs on a small input."""
