@@ -22,20 +22,45 @@ __device__ inline unsigned long long block_min_u64(unsigned long long v, unsigne
 // Keys are (order-preserving distance bits << 32 | index); the running list of each query and the new
 // score row are treated as one candidate set, from which the K smallest keys are drawn one at a time
 // (each round takes the smallest key above the previous one: ties resolve to the lowest index).
+// Once the running list is full, a column can only enter it with a key below the list's largest: one pass over the
+// row collects those columns in LDS (after the first chunks there are few) and the K rounds run over them instead of
+// over the whole row; a row with more candidates than the buffer holds falls back to rounds over the row.
+constexpr int TOPK_CAND = 4096;
 __global__ void __launch_bounds__(256) topk_merge_kernel(const float *S, int64_t lds, int32_t m, int64_t col_base,
                                                          const float *colnorm, int32_t K, unsigned long long *top) {
   __shared__ unsigned long long red[4];
   __shared__ unsigned long long s_new[256];
+  __shared__ unsigned long long s_cand[TOPK_CAND];
+  __shared__ unsigned int s_ncand;
   const int q = blockIdx.x;
   const float *row = S + (int64_t)q * lds;
   unsigned long long *mine = top + (int64_t)q * K;
+  auto key_of = [&](int c) {
+    const float v = colnorm[col_base + c] - 2.f * row[c];
+    return ((unsigned long long)f2ord(v) << 32) | (unsigned long long)(uint32_t)(col_base + c);
+  };
+  const unsigned long long kth = mine[K - 1];   // ~0 while the list is not full: then every column is a candidate
+  if (threadIdx.x == 0) s_ncand = 0u;
+  __syncthreads();
+  bool filtered = false;
+  if (kth != ~0ull) {
+    for (int c = threadIdx.x; c < m; c += 256) {
+      const unsigned long long key = key_of(c);
+      if (key < kth) {
+        const unsigned int pos = atomicAdd(&s_ncand, 1u);
+        if (pos < (unsigned int)TOPK_CAND) s_cand[pos] = key;
+      }
+    }
+    __syncthreads();
+    filtered = s_ncand <= (unsigned int)TOPK_CAND;
+  }
+  const int ncand = filtered ? (int)s_ncand : m;
   unsigned long long last = 0ull;
   bool first = true;
   for (int r = 0; r < K; ++r) {
     unsigned long long best = ~0ull;
-    for (int c = threadIdx.x; c < m; c += 256) {
-      const float v = colnorm[col_base + c] - 2.f * row[c];
-      const unsigned long long key = ((unsigned long long)f2ord(v) << 32) | (unsigned long long)(uint32_t)(col_base + c);
+    for (int c = threadIdx.x; c < ncand; c += 256) {
+      const unsigned long long key = filtered ? s_cand[c] : key_of(c);
       if ((first || key > last) && key < best) best = key;
     }
     if ((int)threadIdx.x < K) {
