@@ -151,7 +151,9 @@ __device__ inline void tile_epilogue(f32x16 (&acc)[TM][TN], const GemmOperands &
       const unsigned long long k0 = red[tid], k1 = red[BM + tid];
       const unsigned long long key = k0 < k1 ? k0 : k1;
       const int gr = row0 + tid;
-      if (gr < g.M && key != ~0ull) atomicMin(e.best + gr, key);
+      // The minimum only goes down, so a key that does not beat what is there now never will: most tiles after the
+      // first few column tiles of a row are settled by this plain read instead of an atomic.
+      if (gr < g.M && key != ~0ull && key < __atomic_load_n(e.best + gr, __ATOMIC_RELAXED)) atomicMin(e.best + gr, key);
     }
   }
 }
