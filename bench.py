@@ -158,8 +158,10 @@ def main():
             traffic = None
     kname = {"rotation_gemm": "skm::gemm_split_kernel<store>", "iter1_gemm_argmin": "skm::gemm_split_kernel<argmin>",
              "progressive_gemm": "skm::progressive_kernel"}[dom]
+    # traffic: HBM bytes per launch of that kernel (scaled FETCH_SIZE + WRITE_SIZE of the committed counter runs)
     roofline = dict(bound="mfma", kernel=kname, achieved=stages[dom]["achieved"], peak=PEAK_SPLIT_TFLOPS,
-                    unit="TFLOP/s", frac=stages[dom]["frac"], traffic=traffic,
+                    unit="TFLOP/s", frac=stages[dom]["frac"],
+                    traffic=None if traffic is None else traffic.get("total_bytes"), traffic_detail=traffic,
                     ms_per_step=stages[dom]["ms"], total_ms_per_fit=totals[dom],
                     flop_per_step={"rotation_gemm": flops_rot, "iter1_gemm_argmin": flops_it1,
                                    "progressive_gemm": flop_alg}[dom],
