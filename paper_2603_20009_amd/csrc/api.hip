@@ -525,6 +525,7 @@ int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
   if (int rc = c.measure_y()) return rc;
   GemmOperands g{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, c.ds};
   g.a_absmax = c.amax + Ctx::AM_XR; g.b_absmax = c.amax + Ctx::AM_Y;
+  g.b_split = c.Ys;   // every pruned step remakes it: free here
   HIPCHK(gemm_argmin(g, c.ynorm, c.best, c.st));
   tm.mark(ST_GEMM);
   // winners -> direct squared distances (also the objective of this step)
@@ -562,6 +563,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
     GemmOperands g0{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, dprime};
     g0.a_absmax = c.amax + Ctx::AM_XR; g0.b_absmax = c.amax + Ctx::AM_Y;
+    g0.b_split = c.Ys;   // rewritten for all dimensions below
     HIPCHK(gemm_argmin(g0, c.ynorm, c.best, c.st));
     HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, c.k, nullptr, nullptr, c.counters + c.ncounters, c.st));
     tm.mark(ST_GEMM);
@@ -721,6 +723,7 @@ void fill_row(skm_trace_row &r, const StepStats &ss, int64_t n, int32_t k, int64
 struct Rot {
   float *Rp = nullptr, *Rtp = nullptr;
   unsigned int *amax = nullptr;   // [0] max |R|, [1] max |input| of the last rotate_into
+  uint32_t *Rs = nullptr;         // workspace for the split-fp16 copy of R^T (tall rotations)
 };
 int setup_rotation(Pool &pool, hipStream_t st, int32_t d, int32_t ds, const float *R_dev, uint64_t seed, Rot &rot) {
   float *Rown = nullptr;
@@ -735,6 +738,7 @@ int setup_rotation(Pool &pool, hipStream_t st, int32_t d, int32_t ds, const floa
   HIPCHK(launch_pad_copy(R_dev, d, d, d, rot.Rp, ds, ds, 0, st));
   HIPCHK(launch_pad_copy(R_dev, d, d, d, rot.Rtp, ds, ds, 1, st));
   if (!rot.amax) HIPCHK(pool.get(&rot.amax, 2));
+  if (d % 32 == 0) HIPCHK(pool.get(&rot.Rs, (size_t)d * ((size_t)d + 32)));
   return measure_absmax(R_dev, d, d, d, rot.amax, st);
 }
 // out (rows x ds, zero padded) = in (rows x d, stride ldin) * R
@@ -747,6 +751,7 @@ int rotate_into(const float *in, int64_t ldin, int64_t rows, int32_t d, int32_t 
   if (out_absmax) HIPCHK(launch_fill_u32(out_absmax, 1, 0u, st));
   GemmOperands g{in, ldin, (int32_t)rows, rot.Rtp, ds, d, d};
   g.a_absmax = rot.amax + 1; g.b_absmax = rot.amax;
+  g.b_split = rot.Rs;
   HIPCHK(gemm_store(g, out, ds, ds, 1.f, 0.f, st, out_absmax));
   return SKM_OK;
 }
@@ -789,7 +794,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   // the workspace in one piece: the context's buffers, the rotated points, the rotation matrices and their generator
   const size_t ds0 = (size_t)round_up(d, 16);
   const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, true);
-  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 7 * (size_t)d * ds0 * 4 + (size_t)d * 8192 + (size_t)k * 16 + ((size_t)32 << 20)
+  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 9 * (size_t)d * ds0 * 4 + (size_t)d * 8192 + (size_t)k * 16 + ((size_t)32 << 20)
                     : 0);
   Ctx c;
   c.st = (hipStream_t)p.stream;
@@ -1086,7 +1091,7 @@ int fit_host_impl(const float *Xh, int64_t n, int32_t d, int32_t k, int32_t iter
   // of all points, the rotation matrices and their generator, the initial rows
   const size_t ds0 = (size_t)round_up(d, 16);
   const size_t plan = plan_common_bytes(W, d, k, p.pair_budget, p.dense_frac, true);
-  CallArena ws(plan ? plan + (size_t)W * (2 * (size_t)d + ds0) * 4 + 3 * (size_t)nbatch * W * 4 + 7 * (size_t)d * ds0 * 4 +
+  CallArena ws(plan ? plan + (size_t)W * (2 * (size_t)d + ds0) * 4 + 3 * (size_t)nbatch * W * 4 + 9 * (size_t)d * ds0 * 4 +
                           (size_t)d * 8192 + (size_t)k * d * 4 + ((size_t)32 << 20)
                     : 0);
   Ctx c;
@@ -1294,7 +1299,7 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
   skm_trace *tr = p.trace;
   const size_t ds0 = (size_t)round_up(d, 16);
   const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, false);
-  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 7 * (size_t)d * ds0 * 4 + (size_t)d * 8192 + ((size_t)32 << 20) : 0);
+  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 9 * (size_t)d * ds0 * 4 + (size_t)d * 8192 + ((size_t)32 << 20) : 0);
   Ctx c;
   c.st = (hipStream_t)p.stream;
   c.n = n; c.d = d; c.k = k;
@@ -1782,6 +1787,7 @@ int skm_assign_exact(const float *X, int64_t n, int32_t d, const float *centroid
   if (rc) return rc;
   GemmOperands g{Xp, ldx, (int32_t)n, Yp, ldy, k, ds};
   g.a_absmax = amax; g.b_absmax = amax + 1;
+  if (ds % 32 == 0) HIPCHK(pool.get(&g.b_split, (size_t)k * ((size_t)ds + 32)));
   HIPCHK(gemm_argmin(g, ynorm, best, st));
   HIPCHK(launch_finalize_assign(best, nullptr, n, assign_out, nullptr, nullptr, k, nullptr, nullptr, nullptr, st));
   if (dist_out) {
@@ -1861,6 +1867,7 @@ int skm_rotate(const float *X, int64_t n, int32_t d, const float *R, int32_t tra
   if (rc) return rc;
   GemmOperands g{X, d, (int32_t)n, B, ds, d, d};
   g.a_absmax = amax; g.b_absmax = amax + 1;
+  if (d % 32 == 0) HIPCHK(pool.get(&g.b_split, (size_t)d * ((size_t)d + 32)));
   HIPCHK(gemm_store(g, out, d, d, 1.f, 0.f, st));
   HIPCHK(hipStreamSynchronize(st));
   return SKM_OK;

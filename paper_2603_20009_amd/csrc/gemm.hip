@@ -76,15 +76,16 @@ __device__ inline void tile_of_block(int nrt, int nct, int PC, int &rt, int &ct)
   ct = p * PC + (r - rt * pc);
 }
 
-// Epilogues of a finished 128 x 128 tile.  `unscale` turns an accumulator into the score s(i, j).
-// Accumulator layout of the 32 x 32 MFMA results: register v of lane (r32, kh) holds
+// Epilogues of a finished TB x TB tile (TB / 64 wavefronts each way).  `unscale` turns an accumulator into the
+// score s(i, j).  Accumulator layout of the 32 x 32 MFMA results: register v of lane (r32, kh) holds
 // row 8*(v/4) + 4*kh + (v%4), column r32 of the 32 x 32 tile.
-template <int EPI>
+template <int EPI, int TB = BM>
 __device__ inline void tile_epilogue(f32x16 (&acc)[TM][TN], const GemmOperands &g, const typename EpiArgs<EPI>::type &e,
                                      int row0, int col0, float unscale, float *smem) {
+  constexpr int NWN = TB / WTN;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / NWN, wn = wave % NWN;
   const int r32 = lane & 31, kh = lane >> 5;
   auto row_of = [&](int a, int v) { return wm * WTM + a * 32 + 8 * (v >> 2) + 4 * kh + (v & 3); };
 
@@ -118,7 +119,7 @@ __device__ inline void tile_epilogue(f32x16 (&acc)[TM][TN], const GemmOperands &
     }
   } else if constexpr (EPI == EPI_ARGMIN) {
     // per-row minimum of ynorm[j] - 2 s(i,j): lanes of one half share the rows, columns differ
-    unsigned long long *red = reinterpret_cast<unsigned long long *>(smem);  // [2][BM], reuses the tile buffers
+    unsigned long long *red = reinterpret_cast<unsigned long long *>(smem);  // [NWN][TB], reuses the tile buffers
     const float m2 = -2.f * unscale;
     float yn[TN];
     int gc[TN];
@@ -144,12 +145,16 @@ __device__ inline void tile_epilogue(f32x16 (&acc)[TM][TN], const GemmOperands &
           const unsigned long long o = __shfl_xor(key, m, 64);
           key = o < key ? o : key;
         }
-        if (r32 == 0) red[wn * BM + row_of(a, v)] = key;
+        if (r32 == 0) red[wn * TB + row_of(a, v)] = key;
       }
     __syncthreads();
-    if (tid < BM) {
-      const unsigned long long k0 = red[tid], k1 = red[BM + tid];
-      const unsigned long long key = k0 < k1 ? k0 : k1;
+    if (tid < TB) {
+      unsigned long long key = red[tid];
+#pragma unroll
+      for (int w = 1; w < NWN; ++w) {
+        const unsigned long long o = red[w * TB + tid];
+        key = o < key ? o : key;
+      }
       const int gr = row0 + tid;
       // The minimum only goes down, so a key that does not beat what is there now never will: most tiles after the
       // first few column tiles of a row are settled by this plain read instead of an atomic.
@@ -478,6 +483,152 @@ gemm_split_kernel(GemmOperands g, typename EpiArgs<EPI>::type e) {
   tile_epilogue<EPI>(acc, g, e, row0, col0, unscale, smem);
 }
 
+
+// ---------------------------------------------------------------- split-fp16 form, 256 x 256 tile
+// For tall products whose B operand is small enough to be split ahead of the multiply (the centroids of iteration 1,
+// the rotation matrix).  One workgroup of 1024 threads (16 wavefronts, 4 x 4, 64 x 64 pairs each) owns 256 x 256
+// scores: per matrix instruction half as many operand bytes travel from L2 to LDS as with the 128 x 128 tile, and
+// half as many slabs' worth of barriers are crossed.  With 128 registers per lane the staging must be lean:
+//  - B comes from a copy already split into fp16 pairs in the LDS byte order (split_rows_kernel), so every lane moves
+//    16 bytes per load straight from global memory into LDS;
+//  - A is fp32: a lane fetches 2 x 4 values of the next slab at the top of a step and converts them after the second
+//    group of matrix instructions.
+// LDS rows are 128 bytes, unpadded; the 16-byte piece c of a row (c = 4 h + 2 lo + kh: half-slab, hi or lo halves,
+// dims 8 kh .. + 7 of the half-slab) sits at position c ^ ((row >> 1) & 7), which spreads the fragment reads of 16
+// consecutive rows over all bank groups.  K must be a multiple of 32.
+constexpr int T2 = 256, NT2 = 1024;
+constexpr int T2_STAGE = 2 * T2 * 32;   // words of one slab of both operands (A rows, then B rows)
+#define SKM_GEMM_VMCNT0() __builtin_amdgcn_s_waitcnt((0x7 << 4) | (0xF << 8))   // all vector memory operations done
+
+template <int EPI>
+__global__ void __launch_bounds__(NT2) gemm_split256_kernel(GemmOperands g, const uint32_t *Bsplit, int64_t ldbs,
+                                                            typename EpiArgs<EPI>::type e) {
+  extern __shared__ __align__(16) float smem[];
+  uint32_t *lds = reinterpret_cast<uint32_t *>(smem);   // [2 stages][A 256 rows | B 256 rows][32 words]
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int r32 = lane & 31, kh = lane >> 5;
+
+  const int nrt = (g.M + T2 - 1) / T2, nct = (g.N + T2 - 1) / T2;
+  int rt, ct;
+  tile_of_block(nrt, nct, g.panel_cols, rt, ct);
+  const int row0 = rt * T2, col0 = ct * T2;
+
+  const unsigned int ma = *g.a_absmax, mb = *g.b_absmax;
+  const float scale_a = split_scale(ma);
+  const float unscale = split_unscale(ma) * split_unscale(mb);
+
+  // B: load instruction j of wavefront w fills tile rows 128 j + 8 w .. + 7, 8 lanes a row; a lane fetches the piece
+  // that belongs at its own position.  A: thread (arow, kq) converts dims 4 kq .. + 3 of tile rows arow and arow + 128.
+  const int lrow = lane >> 3, lpos = lane & 7;
+  const int kq = tid & 7, arow = tid >> 3;
+  const int c_hi = 4 * (kq >> 2) + ((kq >> 1) & 1);   // piece that holds the hi halves of these four dims
+  const uint32_t *gb[2];
+  const float *ga[2];
+  uint32_t *wa[2];
+  int lo_off[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int rb = 8 * wave + 128 * j + lrow;
+    gb[j] = Bsplit + (int64_t)min(col0 + rb, g.N - 1) * ldbs + 16 + 4 * (lpos ^ ((rb >> 1) & 7));   // one zero granule leads a row
+    const int ra_ = arow + 128 * j, sw = (ra_ >> 1) & 7;
+    ga[j] = g.A + (int64_t)min(row0 + ra_, g.M - 1) * g.lda + 4 * kq;
+    wa[j] = lds + ra_ * 32 + ((c_hi ^ sw) << 2) + 2 * (kq & 1);
+    lo_off[j] = (((c_hi + 2) ^ sw) - (c_hi ^ sw)) << 2;   // the lo halves: piece c_hi + 2
+  }
+  auto issue_b = [&](int stage, int k0) {
+    uint32_t *sb = lds + stage * T2_STAGE + T2 * 32 + 8 * wave * 32;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gb[j] + k0),
+                                       (__attribute__((address_space(3))) void *)(sb + 128 * j * 32), 16, 0, 0);
+  };
+  float4 ra[2];
+  auto load_a = [&](int k0) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) ra[j] = *reinterpret_cast<const float4 *>(ga[j] + k0);
+  };
+  auto convert_a = [&](int stage) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const float4 v = ra[j];
+      const f32x2 p0 = {v.x * scale_a, v.y * scale_a}, p1 = {v.z * scale_a, v.w * scale_a};
+      const f16x2 h0 = __builtin_convertvector(p0, f16x2), h1 = __builtin_convertvector(p1, f16x2);
+      const f16x2 l0 = __builtin_convertvector(p0 - __builtin_convertvector(h0, f32x2), f16x2);
+      const f16x2 l1 = __builtin_convertvector(p1 - __builtin_convertvector(h1, f32x2), f16x2);
+      uint2 hi, lo;
+      hi.x = __builtin_bit_cast(unsigned int, h0); hi.y = __builtin_bit_cast(unsigned int, h1);
+      lo.x = __builtin_bit_cast(unsigned int, l0); lo.y = __builtin_bit_cast(unsigned int, l1);
+      uint32_t *dst = wa[j] + stage * T2_STAGE;
+      *reinterpret_cast<uint2 *>(dst) = hi;
+      *reinterpret_cast<uint2 *>(dst + lo_off[j]) = lo;
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int a = 0; a < TM; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  const int swz = (r32 >> 1) & 7;
+  const int fa = (wm * WTM + r32) * 32, fb = (T2 + wn * WTN + r32) * 32;
+  auto frag = [&](const uint32_t *sb, int rowbase, int t, int h, int lo) {
+    return *reinterpret_cast<const f16x8 *>(sb + rowbase + t * 32 * 32 + (((4 * h + 2 * lo + kh) ^ swz) << 2));
+  };
+  auto mma4 = [&](const f16x8 (&x)[TM], const f16x8 (&y)[TN]) {
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int b = 0; b < TN; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x[a], y[b], acc[a][b], 0, 0, 0);
+  };
+
+  const int nslab = g.K / 32;
+  issue_b(0, 0);
+  load_a(0);
+  convert_a(0);
+  SKM_GEMM_VMCNT0();
+  __syncthreads();
+  for (int s = 0; s < nslab; ++s) {
+    const uint32_t *sb = lds + (s & 1) * T2_STAGE;
+    const bool more = s + 1 < nslab;
+    // the other stage was last read in the previous step, which ended with a barrier
+    if (more) {
+      issue_b((s + 1) & 1, (s + 1) * 32);
+      load_a((s + 1) * 32);
+    }
+    f16x8 ah[TM], al[TM], bh[TN], bl[TN];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      ah[t] = frag(sb, fa, t, 0, 0); bh[t] = frag(sb, fb, t, 0, 0);
+      al[t] = frag(sb, fa, t, 0, 1); bl[t] = frag(sb, fb, t, 0, 1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    mma4(ah, bh);
+    mma4(al, bh);
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) convert_a((s + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) { al[t] = frag(sb, fa, t, 1, 1); bh[t] = frag(sb, fb, t, 1, 0); }
+    mma4(ah, bl);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) { ah[t] = frag(sb, fa, t, 1, 0); bl[t] = frag(sb, fb, t, 1, 1); }
+    mma4(al, bh);
+    __builtin_amdgcn_sched_barrier(0);
+    mma4(ah, bl);
+    mma4(ah, bh);
+    __builtin_amdgcn_sched_barrier(0);
+    SKM_GEMM_VMCNT0();
+    __syncthreads();
+  }
+  tile_epilogue<EPI, T2>(acc, g, e, row0, col0, unscale, smem);
+}
+
 constexpr int64_t kMaxTilesPerLaunchFwd = (1 << 24) - 1;
 template <int BK>
 constexpr size_t smem_bytes() {
@@ -525,6 +676,38 @@ static hipError_t launch_split(const GemmOperands &g, const typename EpiArgs<EPI
   return hipGetLastError();
 }
 
+
+// The 256 x 256 form pays when the tall operand fills the device several times over and B can be split ahead.
+static bool wants_split256(const GemmOperands &g) {
+  static const int forced = []() {
+    const char *e = std::getenv("SKM_TEST_GEMM256");   // 0: never, 1: whenever the operands allow it
+    return e ? std::atoi(e) : -1;
+  }();
+  if (!g.b_split || !g.a_absmax || !g.b_absmax || g.K % 32 != 0 || g.K < 64 || forced == 0) return false;
+  if (!aligned16(g.A) || !aligned16(g.B) || !aligned16(g.b_split) || g.lda % 4 != 0 || g.ldb % 4 != 0) return false;
+  const int64_t tiles = (int64_t)((g.M + T2 - 1) / T2) * ((g.N + T2 - 1) / T2);
+  // narrow B: a last column tile that is mostly padding costs more than the larger tile gains
+  const int64_t ncols = (int64_t)((g.N + T2 - 1) / T2) * T2;
+  return forced == 1 || (tiles >= 512 && ncols * 4 <= (int64_t)g.N * 5);
+}
+
+template <int EPI>
+static hipError_t launch_split256(const GemmOperands &g, const typename EpiArgs<EPI>::type &e, hipStream_t st) {
+  auto kern = gemm_split256_kernel<EPI>;
+  constexpr size_t smem = (size_t)2 * T2_STAGE * sizeof(uint32_t);
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (rc != hipSuccess) return rc;
+    attr_set = true;
+  }
+  const int64_t nwg = (int64_t)((g.M + T2 - 1) / T2) * ((g.N + T2 - 1) / T2);
+  if (nwg <= 0) return hipSuccess;
+  if (nwg > (1 << 22) - 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(NT2), smem, st, g, (const uint32_t *)g.b_split, (int64_t)g.K + 32, e);
+  return hipGetLastError();
+}
+
 // A launch may not exceed 2^32 threads in total: at 256 threads per tile that is 2^24 - 1 tiles, so
 // tall problems are cut into bands of row tiles (the epilogue pointers move with the band).
 constexpr int64_t kMaxTilesPerLaunch = (1 << 24) - 1;
@@ -551,14 +734,20 @@ static hipError_t launch_any(const GemmOperands &g, const typename EpiArgs<EPI>:
   const bool al = operands_aligned(g);
   // slabs of 32 for long K; slabs of 16 when K is short or not a multiple of 32 (d' is a multiple of 16)
   const bool bk32 = (g.K % 32 == 0) && g.K >= 256;
-  const int64_t nct = (g.N + BN - 1) / BN;
+  const bool big = wants_split256(g);
+  const int edge = big ? T2 : BM;
+  const int64_t nct = (g.N + edge - 1) / edge;
+  if (big) {   // B, split into fp16 pairs, K + 32 words a row
+    hipError_t rc = launch_split_rows(g.B, g.ldb, g.N, g.K, g.b_absmax, g.b_split, st);
+    if (rc != hipSuccess) return rc;
+  }
   // SKM_TEST_MAX_TILES lowers the limit so that the banding can be exercised on small inputs
   static const int64_t max_tiles = []() {
     const char *e = std::getenv("SKM_TEST_MAX_TILES");
     const int64_t v = e ? std::atoll(e) : 0;
     return (v > 0 && v < kMaxTilesPerLaunch) ? v : kMaxTilesPerLaunch;
   }();
-  const int64_t band_rows = std::max<int64_t>(max_tiles / nct, 1) * BM;
+  const int64_t band_rows = std::max<int64_t>((big ? std::min<int64_t>(max_tiles, (1 << 22) - 1) : max_tiles) / nct, 1) * edge;
   for (int64_t r0 = 0; r0 < g.M; r0 += band_rows) {
     GemmOperands gb = g;
     gb.panel_cols = panel_cols_for(nct);
@@ -567,7 +756,8 @@ static hipError_t launch_any(const GemmOperands &g, const typename EpiArgs<EPI>:
     typename EpiArgs<EPI>::type eb = e;
     shift_rows(eb, r0);
     hipError_t rc;
-    if (al && g.K >= SBK && g.a_absmax && g.b_absmax) rc = launch_split<EPI>(gb, eb, st);
+    if (big) rc = launch_split256<EPI>(gb, eb, st);
+    else if (al && g.K >= SBK && g.a_absmax && g.b_absmax) rc = launch_split<EPI>(gb, eb, st);
     else if (al) rc = bk32 ? launch_one<32, EPI, true>(gb, eb, st) : launch_one<16, EPI, true>(gb, eb, st);
     else rc = bk32 ? launch_one<32, EPI, false>(gb, eb, st) : launch_one<16, EPI, false>(gb, eb, st);
     if (rc != hipSuccess) return rc;

@@ -49,6 +49,9 @@ struct GemmOperands {
   // set (and 16-byte aligned operands, K >= 32) the product runs in the split-fp16 form described below.
   const unsigned int *a_absmax = nullptr;
   const unsigned int *b_absmax = nullptr;
+  // Optional workspace of N * (K + 32) words, 16-byte aligned: with it (and the bounds above, K a multiple of 32) a
+  // tall product splits B into fp16 pairs there first and runs on 256 x 256 tiles.
+  uint32_t *b_split = nullptr;
 };
 
 // Split-fp16 arithmetic.  A matrix whose largest magnitude is m is scaled by the power of two that brings m

@@ -430,6 +430,48 @@ print("banded ok")
     assert r.returncode == 0 and "banded ok" in r.stdout, r.stderr[-2000:]
 
 
+@pytest.mark.parametrize("max_tiles", [None, "5"])
+def test_wide_tile_gemm_on_small_ragged_inputs(max_tiles):
+    """Tall products run on 256 x 256 tiles with the second operand split ahead.  The form is forced through the
+    environment in a child process, so that ragged row and column tiles, several slabs and (with the tile limit
+    lowered) the banding run on inputs the oracle finishes in seconds: exact assignment, rotation, a whole fit."""
+    import subprocess
+    import sys
+    import os
+    code = r'''
+import sys, numpy as np, torch
+sys.path.insert(0, %r)
+from paper_2603_20009_amd import skm, datagen
+from oracle import oracle as orc
+for (n, d, k) in ((3000, 64, 300), (1001, 96, 257), (700, 160, 5)):
+    X = datagen.mixture(n, d, 20, 2, "linear").numpy()
+    Y = X[:k].copy() + np.float32(0.01)
+    a, dist = skm.assign_exact(torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda())
+    ao, do = orc.assign_full(X.astype(np.float64), Y.astype(np.float64))
+    same = a.cpu().numpy() == ao
+    assert same.mean() > 0.999, (n, d, k, same.mean())
+    assert np.abs(dist.cpu().numpy()[same] - do[same]).max() < 1e-5 * max(1.0, do.max())
+    R = orc.random_rotation(d, 1)
+    out = skm.rotate(torch.from_numpy(X).cuda(), torch.from_numpy(R).cuda()).cpu().numpy()
+    assert np.abs(out - orc.rotate(X, R)).max() < 2e-6 * max(1.0, np.abs(X).max())
+X = datagen.mixture(4096, 128, 40, 11, "linear")
+R = orc.random_rotation(128, 7)
+idx = orc.sample_rows(7, 4096, 32)
+eps0 = float(np.float32(2.1))
+ref = orc.fit(X.numpy(), 32, 4, 7, orc.FitParams(eps0=eps0, adjust_dprime=False), R=R, init_idx=idx)
+got = skm.fit(X.cuda(), 32, 4, 7, skm.FitOptions(R=torch.from_numpy(R).cuda(), adjust_dprime=False))
+assert (got.assign.cpu().numpy() == ref.assign).mean() >= 0.999
+assert np.linalg.norm(got.centroids.cpu().numpy() - ref.centroids) / np.linalg.norm(ref.centroids) < 1e-3
+assert abs(got.trace[-1]["objective"] - ref.trace[-1]["objective"]) / ref.trace[-1]["objective"] < 1e-4
+print("wide tiles ok")
+''' % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, SKM_TEST_GEMM256="1")
+    if max_tiles:
+        env["SKM_TEST_MAX_TILES"] = max_tiles
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "wide tiles ok" in r.stdout, r.stderr[-2000:]
+
+
 # ------------------------------------------------------------------ edge and degenerate cases
 def test_single_cluster_and_one_point_per_cluster(skm, orc, dg):
     X = dg.mixture(700, 48, 5, 3, "linear").numpy()
