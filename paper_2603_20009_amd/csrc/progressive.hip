@@ -373,18 +373,23 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
         for (int b = 0; b < TN; ++b) yn[b] = s_yn[wn * WTN + b * 32 + r32];
         if (!last || g.nb == 0) {
-          // test theta(t_m, tau_i): drop the pair when its partial distance exceeds it
+          // test theta(t_m, tau_i): drop the pair when its partial distance exceeds it.  The sign of threshold minus
+          // distance is the verdict (a difference of two floats is negative exactly when the second is larger); the
+          // signs of the 32 elements of an accumulator row block are shifted into one word, last element first, one
+          // funnel shift each.
 #pragma unroll
-          for (int a = 0; a < TM; ++a)
+          for (int a = 0; a < TM; ++a) {
+            unsigned int dropped = 0u;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const float th = s_thr[row_of(a, v)];
+            for (int b = TN - 1; b >= 0; --b)
 #pragma unroll
-              for (int b = 0; b < TN; ++b) {
-                const bool keep = fmaf(m2, acc[a][b][v], yn[b]) <= th;
-                bits &= ~((unsigned long long)(!keep) << ((a * TN + b) * 16 + v));
+              for (int v = 15; v >= 0; --v) {
+                const float margin = s_thr[row_of(a, v)] - fmaf(m2, acc[a][b][v], yn[b]);
+                dropped = __builtin_amdgcn_alignbit(dropped, __builtin_bit_cast(unsigned int, margin), 31);
               }
-            }
+            bits &= ~((unsigned long long)dropped << (32 * a));
+          }
+          static_assert(TN * 16 == 32, "one word per accumulator row block");
         }
         // alive pairs of this wavefront and of the whole tile
         wave_alive = wave_sum_i32(__popcll(bits));
