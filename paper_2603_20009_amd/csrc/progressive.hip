@@ -85,7 +85,7 @@ constexpr int B_LD = BN / ROWS_PASS;
 // wait until at most n of this wavefront's vector memory operations are outstanding (LDS and export counters untouched)
 #define SKM_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
-// Sum / bitwise OR over the 64 lanes of a wavefront through the data-parallel lane moves: within quads, mirrored
+// Sum over the 64 lanes of a wavefront through the data-parallel lane moves: within quads, mirrored
 // within half rows and rows, then the row totals handed on to the following rows; lane 63 ends with the result.
 #define SKM_WAVE_REDUCE(v, OP)                                                                \
   do {                                                                                        \
@@ -98,10 +98,6 @@ constexpr int B_LD = BN / ROWS_PASS;
   } while (0)
 __device__ inline int wave_sum_i32(int v) {
   SKM_WAVE_REDUCE(v, +);
-  return __builtin_amdgcn_readlane(v, 63);
-}
-__device__ inline int wave_or_i32(int v) {
-  SKM_WAVE_REDUCE(v, |);
   return __builtin_amdgcn_readlane(v, 63);
 }
 
@@ -482,46 +478,45 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
         s_base = base;
       }
-      // element slots in which any lane of this wavefront holds an alive pair (a sparse tile has few): the others
-      // are skipped by a scalar test each
-      const unsigned long long any = ((unsigned long long)(unsigned int)wave_or_i32((int)(bits >> 32)) << 32) |
-                                     (unsigned long long)(unsigned int)wave_or_i32((int)bits);
       __syncthreads();
       unsigned int run = s_base;
       if (run != 0xffffffffu && wave_alive > 0) {
         for (int w = 0; w < wave; ++w) run += s_wcnt[fin_m & 1][w];
-        const int irow = (int)g.row_base + row0 + wm * WTM + 4 * kh;   // + a * 32 + 8 * (v >> 2) + (v & 3)
+        // A sparse tile holds one or two alive pairs per lane.  Every lane walks its own alive bits; the accumulator
+        // element behind a bit is found through LDS, where the lane parks its 32 values of a row block (a register
+        // cannot be chosen per lane): the stage the last multiply step read is free, 8 KB per wavefront as [32][64].
+        // List slots: the wavefront's range, then lane by lane (prefix sum of the lanes' counts), then bit by bit.
+        int upto = __popcll(bits);
+        const int mine = upto;
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x111, 0xF, 0xF, false);   // row_shr:1
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x112, 0xF, 0xF, false);   // row_shr:2
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x114, 0xF, 0xF, false);   // row_shr:4
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x118, 0xF, 0xF, false);   // row_shr:8
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x142, 0xA, 0xF, false);   // row_bcast:15
+        upto += __builtin_amdgcn_update_dpp(0, upto, 0x143, 0xC, 0xF, false);   // row_bcast:31
+        unsigned int pos = run + (unsigned int)(upto - mine);
+        float *park = reinterpret_cast<float *>(smem + (stg ^ 1) * STAGE_WORDS + wave * (32 * 64)) + lane;
+        const int irow = wm * WTM + 4 * kh;   // + a * 32 + 8 * (v >> 2) + (v & 3)
 #pragma unroll
         for (int a = 0; a < TM; ++a) {
-          // per-row data of the 16 rows this lane holds in accumulator row block a: four aligned groups of four rows
-          float4 xn4[4], tau4[4];
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            xn4[q4] = *reinterpret_cast<const float4 *>(&s_xn[wm * WTM + a * 32 + 8 * q4 + 4 * kh]);
-            tau4[q4] = *reinterpret_cast<const float4 *>(&s_tau[wm * WTM + a * 32 + 8 * q4 + 4 * kh]);
-          }
-          auto pick = [](const float4 &f, int i) { return i == 0 ? f.x : i == 1 ? f.y : i == 2 ? f.z : f.w; };
 #pragma unroll
           for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              if (!((any >> ((a * TN + b) * 16 + v)) & 1ull)) continue;
-              const bool keep = (bits >> ((a * TN + b) * 16 + v)) & 1ull;
-              const unsigned long long mk = __ballot(keep);
-              if (keep) {
-                const unsigned int pos =
-                    run + __builtin_amdgcn_mbcnt_hi((unsigned int)(mk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mk, 0u));
-                Pair pr;
-                pr.i = irow + a * 32 + 8 * (v >> 2) + (v & 3);
-                pr.j = (int32_t)((uint32_t)gc[b] | ((uint32_t)fin_m << 24));
-                const float p = pick(xn4[v >> 2], v & 3) + fmaf(m2, acc[a][b][v], yn[b]);
-                pr.p = p > 0.f ? p : 0.f;
-                pr.tau = pick(tau4[v >> 2], v & 3);
-                g.pairs[pos] = pr;
-              }
-              run += (unsigned int)__popcll(mk);
-              __builtin_amdgcn_sched_barrier(0);
-            }
+            for (int v = 0; v < 16; ++v) park[(b * 16 + v) * 64] = acc[a][b][v];
+          unsigned int left = (unsigned int)(bits >> (32 * a));
+          while (left) {
+            const int e = __builtin_ctz(left);   // b * 16 + v
+            left &= left - 1u;
+            const int v = e & 15, b = e >> 4;
+            const int rl = irow + a * 32 + 8 * (v >> 2) + (v & 3);
+            Pair pr;
+            pr.i = (int32_t)g.row_base + row0 + rl;
+            pr.j = (int32_t)((uint32_t)gc[b ? 1 : 0] | ((uint32_t)fin_m << 24));
+            const float p = s_xn[rl] + fmaf(m2, park[e * 64], b ? yn[1] : yn[0]);
+            pr.p = p > 0.f ? p : 0.f;
+            pr.tau = s_tau[rl];
+            g.pairs[pos++] = pr;
+          }
         }
       }
     }
