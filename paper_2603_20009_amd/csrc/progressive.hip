@@ -108,8 +108,7 @@ __device__ inline int wave_sum_i32(int v) {
 // or past ds.
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) progressive_kernel(ProgArgs g) {
   extern __shared__ __align__(16) uint32_t smem[];   // [2 stages][A: BM rows | B: BN rows][ROW_WORDS]
-  __shared__ __align__(16) float s_tau[BM], s_thr[BM], s_xn[BM], s_yn[BN];
-  __shared__ int s_prev[BM];
+  __shared__ __align__(16) float s_tau[2][BM], s_thr[BM], s_xn[BM], s_yn[BN];   // s_tau: by tile parity
   __shared__ float s_ratio[kMaxBlocks + 1];
   __shared__ unsigned long long s_dead[NT];   // per thread: accumulator elements that start dead (the incumbent)
   __shared__ __align__(16) unsigned int s_wcnt[2][4];   // alive pairs of every wavefront at the last checkpoint (by checkpoint parity)
@@ -255,16 +254,18 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   load_norm(0);
   issue(stg, 0);
   load_rows(rt * BM);
-
-  for (int tile_no = 0;; ++tile_no) {
-    const int row0 = rt * BM, col0 = ct * BN;
-    // ---- slab 0 and the per-row data of this tile were requested while the previous tile was written out
+  // A tile is committed once its first slab and its per-row data have arrived: the thresholds go to LDS (two copies by
+  // tile parity: the previous tile may still be handing pairs over), the incumbents are marked, and the number of the
+  // tile after next is drawn (the counter's answer is stored at the end of the tile, so its round trip never stalls
+  // the workgroup).  One barrier separates two tiles.
+  unsigned int drawn = 0;
+  auto commit = [&](int col0, int par) {
     SKM_VMCNT(0);
     if (tid < BM) {
-      s_tau[tid] = tau_reg;
-      s_prev[tid] = prev_reg;
+      s_tau[par][tid] = tau_reg;
       // the incumbent of this row, if it is a column of this tile, starts dead: find the thread and the
-      // accumulator element that hold (row tid, column prev - col0)
+      // accumulator element that hold (row tid, column prev - col0).  (Every thread emptied its own marks right
+      // after the previous commit's barrier, and has crossed a multiply step's barrier since.)
       const int cl = prev_reg - col0;
       if (cl >= 0 && cl < BN) {
         const int rr = tid & 31;
@@ -275,11 +276,14 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         atomicOr(&s_dead[wave_t * 64 + lane_t], 1ull << bit);
       }
     }
-    // Draw the number of the tile after next now; the answer of the counter is stored at the end of this tile, so
-    // its round trip never stalls the workgroup.
-    unsigned int drawn = 0;
     if (tid == 0) drawn = atomicAdd(ctr, 1u);
     __syncthreads();
+  };
+  commit(ct * BN, 0);
+
+  for (int tile_no = 0;; ++tile_no) {
+    const int row0 = rt * BM, col0 = ct * BN;
+    const int par = tile_no & 1;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -449,7 +453,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
             if ((bits >> ((a * TN + b) * 16 + v)) & 1ull) {
               float dist = s_xn[rl] + fmaf(m2, acc[a][b][v], yn[b]);
               dist = dist > 0.f ? dist : 0.f;
-              if (dist < s_tau[rl]) {
+              if (dist < s_tau[par][rl]) {
                 const unsigned long long kb = pack_key(dist, gc[b]);
                 key = kb < key ? kb : key;
               }
@@ -514,7 +518,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
             pr.j = (int32_t)((uint32_t)gc[b ? 1 : 0] | ((uint32_t)fin_m << 24));
             const float p = s_xn[rl] + fmaf(m2, park[e * 64], b ? yn[1] : yn[0]);
             pr.p = p > 0.f ? p : 0.f;
-            pr.tau = s_tau[rl];
+            pr.tau = s_tau[par][rl];
             g.pairs[pos++] = pr;
           }
         }
@@ -525,7 +529,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     rt = nrt_;
     ct = nct_;
     if (tid == 0) s_q[(tile_no + 2) & 3] = (int)drawn;
-    __syncthreads();   // everyone is done with this tile's LDS before the next one is committed
+    commit(ct * BN, par ^ 1);   // its barrier also ends this tile: everyone is done with the tile's LDS
   }
 }
 
