@@ -454,9 +454,9 @@ for (n, d, k) in ((3000, 64, 300), (1001, 96, 257), (700, 160, 5)):
     R = orc.random_rotation(d, 1)
     out = skm.rotate(torch.from_numpy(X).cuda(), torch.from_numpy(R).cuda()).cpu().numpy()
     assert np.abs(out - orc.rotate(X, R)).max() < 2e-6 * max(1.0, np.abs(X).max())
-X = datagen.mixture(4096, 128, 40, 11, "linear")
+X = datagen.mixture(4000, 128, 40, 11, "linear")   # a ragged last row tile
 R = orc.random_rotation(128, 7)
-idx = orc.sample_rows(7, 4096, 32)
+idx = orc.sample_rows(7, 4000, 32)
 eps0 = float(np.float32(2.1))
 ref = orc.fit(X.numpy(), 32, 4, 7, orc.FitParams(eps0=eps0, adjust_dprime=False), R=R, init_idx=idx)
 got = skm.fit(X.cuda(), 32, 4, 7, skm.FitOptions(R=torch.from_numpy(R).cuda(), adjust_dprime=False))
