@@ -293,6 +293,30 @@ def test_fit_splits_empty_clusters_like_the_oracle(skm, orc, dg):
     assert (np.bincount(got.assign.cpu().numpy(), minlength=12) > 0).all()
 
 
+@pytest.mark.parametrize("case", range(8))
+def test_fit_over_seeded_shapes(skm, orc, dg, case):
+    """Whole fits on shapes drawn from a seed: d not a multiple of 16 or 64, k below, at and above one tile, row
+    counts that leave ragged tiles, with and without rotation and d' adjustment."""
+    rng = np.random.default_rng(1000 + case)
+    n = int(rng.integers(150, 6000))
+    d = int(rng.choice([16, 24, 40, 72, 100, 129, 200, 333]))
+    k = int(min(rng.choice([2, 7, 31, 127, 128, 129, 260]), n // 3))
+    iters = int(rng.integers(2, 6))
+    kind = ["linear", "embed"][case % 2]
+    rotate = case % 3 != 2
+    X = dg.mixture(n, d, max(k // 2, 3), 50 + case, kind).numpy()
+    R = orc.random_rotation(d, case) if rotate else None
+    say("fit shape", case, n, d, k, iters, kind, "rotate" if rotate else "plain")
+    ref, got = fit_pair(skm, orc, X, k, iters, 77 + case, R, adjust_dprime=case % 2 == 0)
+    Xr = orc.rotate(X, R) if rotate else X
+    check_assignment(got.assign.cpu().numpy(), ref.assign, Xr, ref.centroids_rot, own=(X, got.centroids.cpu().numpy()))
+    check_centroids(got.centroids.cpu().numpy(), ref.centroids, got.assign.cpu().numpy(), ref.assign)
+    assert [g["dprime"] for g in got.trace] == [r["dprime"] for r in ref.trace]
+    assert got.trace[-1]["objective"] == pytest.approx(ref.trace[-1]["objective"], rel=1e-4)
+    assert np.array_equal(np.bincount(got.assign.cpu().numpy(), minlength=k) == 0,
+                          np.bincount(ref.assign, minlength=k) == 0)
+
+
 def test_fit_is_bitwise_reproducible(skm, orc, dg):
     X = cuda(dg.mixture(30_000, 128, 64, 12, "linear").numpy())
     R = cuda(orc.random_rotation(128, 2))
