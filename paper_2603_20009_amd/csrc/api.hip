@@ -276,9 +276,9 @@ int32_t nprobe_of(int32_t k, double frac) {
 int make_rotation_dev(Pool &pool, int32_t d, uint64_t seed, hipStream_t st, float *R_out) {
   double *Qw = nullptr, *Cw = nullptr, *Ww = nullptr, *Lw = nullptr;
   HIPCHK(pool.get(&Qw, (size_t)d * d + 2));
-  HIPCHK(pool.get(&Cw, std::max<size_t>((size_t)12 * 32 * d, (size_t)((d + 127) / 128) * 32 * 32)));
-  HIPCHK(pool.get(&Ww, (size_t)((d + 63) / 64) * 32 * d));
-  HIPCHK(pool.get(&Lw, (size_t)32 * 32));
+  HIPCHK(pool.get(&Cw, std::max<size_t>((size_t)12 * 64 * d, (size_t)((d + 63) / 64) * 64 * 64)));
+  HIPCHK(pool.get(&Ww, (size_t)((d + 63) / 64) * 64 * d));
+  HIPCHK(pool.get(&Lw, (size_t)64 * 64));
   HIPCHK(launch_make_rotation(d, rng_stream(seed, STREAM_ROTATION).s, Qw, Cw, Ww, Lw, R_out, st));
   return SKM_OK;
 }
@@ -794,7 +794,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   // the workspace in one piece: the context's buffers, the rotated points, the rotation matrices and their generator
   const size_t ds0 = (size_t)round_up(d, 16);
   const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, true);
-  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 9 * (size_t)d * ds0 * 4 + (size_t)d * 8192 + (size_t)k * 16 + ((size_t)32 << 20)
+  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + (size_t)k * 16 + ((size_t)32 << 20)
                     : 0);
   Ctx c;
   c.st = (hipStream_t)p.stream;
@@ -1091,8 +1091,8 @@ int fit_host_impl(const float *Xh, int64_t n, int32_t d, int32_t k, int32_t iter
   // of all points, the rotation matrices and their generator, the initial rows
   const size_t ds0 = (size_t)round_up(d, 16);
   const size_t plan = plan_common_bytes(W, d, k, p.pair_budget, p.dense_frac, true);
-  CallArena ws(plan ? plan + (size_t)W * (2 * (size_t)d + ds0) * 4 + 3 * (size_t)nbatch * W * 4 + 9 * (size_t)d * ds0 * 4 +
-                          (size_t)d * 8192 + (size_t)k * d * 4 + ((size_t)32 << 20)
+  CallArena ws(plan ? plan + (size_t)W * (2 * (size_t)d + ds0) * 4 + 3 * (size_t)nbatch * W * 4 + 10 * (size_t)d * ds0 * 4 +
+                          (size_t)d * 16384 + (size_t)k * d * 4 + ((size_t)32 << 20)
                     : 0);
   Ctx c;
   c.st = (hipStream_t)p.stream;
@@ -1299,7 +1299,7 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
   skm_trace *tr = p.trace;
   const size_t ds0 = (size_t)round_up(d, 16);
   const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, false);
-  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 9 * (size_t)d * ds0 * 4 + (size_t)d * 8192 + ((size_t)32 << 20) : 0);
+  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + ((size_t)32 << 20) : 0);
   Ctx c;
   c.st = (hipStream_t)p.stream;
   c.n = n; c.d = d; c.k = k;
