@@ -84,10 +84,16 @@ __device__ inline float quad_sum(float v) {
 }
 // q = sum of squares of this lane's float4 at column c0 = 4 lane + 256 u; base = norm of the row before column 256 u.
 // Returns the norm of the row up to column 256 (u + 1).
-__device__ inline float emit_prefix(const PrefixOut &po, int64_t i, int lane, int u, float q, float base) {
+// With `stage` (LDS, [ds / 16][64]) the value goes to column `slot` of it instead of the table: the caller writes the
+// table 64 points at a time.
+__device__ inline float emit_prefix(const PrefixOut &po, int64_t i, int lane, int u, float q, float base,
+                                    float *stage = nullptr, int slot = 0) {
   const float upto = base + quad_scan64(quad_sum(q));   // norm up to the end of this quad's 16-dim piece
   const int t = 256 * u + 16 * (lane >> 2) + 16;          // that end
-  if ((lane & 3) == 0 && t <= po.ds) po.xnp[(int64_t)((t >> 4) - 1) * po.n + i] = upto;
+  if ((lane & 3) == 0 && t <= po.ds) {
+    if (stage) stage[((t >> 4) - 1) * 64 + slot] = upto;
+    else po.xnp[(int64_t)((t >> 4) - 1) * po.n + i] = upto;
+  }
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, upto), 63));
 }
 
@@ -98,14 +104,17 @@ __device__ inline float4 load_stream4(const float *p) {
   return make_float4(v.x, v.y, v.z, v.w);
 }
 
-template <int NV>
+// BATCH (with po.xnp, NV > 0): a workgroup takes 64 consecutive points at a time and writes their prefix norms through
+// LDS, 256 contiguous bytes per table row, instead of one 4-byte store per point and row.
+constexpr int kPrefixStageRows = 128;   // ds <= 2048 in the batched form
+template <int NV, bool BATCH>
 __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t ldx, int64_t n, int32_t ds,
                                                        const float *Y, int64_t ldy, const int32_t *assign, float *tau,
                                                        unsigned long long *best, PrefixOut po) {
+  __shared__ float s_np[BATCH ? kPrefixStageRows * 64 : 1];
   if (po.xs) po.scale = split_scale(*po.absmax);
   const int lane = threadIdx.x & 63;
-  const int64_t nwaves = (int64_t)gridDim.x * 4;
-  for (int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); i < n; i += nwaves) {
+  auto point = [&](int64_t i, int slot) {
     const int a = assign[i];
     const float *x = Xr + i * ldx;
     const float *y = Y + (int64_t)a * ldy;
@@ -137,7 +146,7 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
         for (int u = 0; u < NV; ++u) {
           if (256 * u >= ds) break;
           const float q = fmaf(xv[u].x, xv[u].x, fmaf(xv[u].y, xv[u].y, fmaf(xv[u].z, xv[u].z, xv[u].w * xv[u].w)));
-          base = emit_prefix(po, i, lane, u, q, base);
+          base = emit_prefix(po, i, lane, u, q, base, BATCH ? s_np : nullptr, slot);
         }
       }
       if (po.xs) {
@@ -175,6 +184,22 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
       if (tau) tau[i] = s;
       if (best) best[i] = pack_key(s, a);
     }
+  };
+  if (BATCH) {
+    const int wave = threadIdx.x >> 6, rows = ds >> 4;
+    for (int64_t b0 = (int64_t)blockIdx.x * 64; b0 < n; b0 += (int64_t)gridDim.x * 64) {
+      for (int it = 0; it < 16; ++it) {
+        const int slot = it * 4 + wave;
+        if (b0 + slot < n) point(b0 + slot, slot);
+      }
+      __syncthreads();
+      if (b0 + lane < n)
+        for (int p = wave; p < rows; p += 4) po.xnp[(int64_t)p * po.n + b0 + lane] = s_np[p * 64 + lane];
+      __syncthreads();
+    }
+  } else {
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); i < n; i += nwaves) point(i, 0);
   }
 }
 
@@ -182,15 +207,22 @@ hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, 
                            const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st, float *xnp,
                            uint32_t *xs, const unsigned int *x_absmax) {
   if (n <= 0) return hipSuccess;
-  int64_t blocks = (n + 3) / 4;
+  const int nv = (ds + 255) / 256;
+  const bool batch = xnp != nullptr && nv <= 8 && ds / 16 <= kPrefixStageRows;
+  int64_t blocks = batch ? (n + 63) / 64 : (n + 3) / 4;
   const int64_t cap = (int64_t)num_cus() * 32;
   if (blocks > cap) blocks = cap;
-  const int nv = (ds + 255) / 256;
   if (xs && (ds % 16 != 0 || !x_absmax)) return hipErrorInvalidValue;
   const PrefixOut po{xnp, n, ds, xs, x_absmax, 0.f};
-#define SKM_TAU_LAUNCH(NV)                                                                                          \
-  hipLaunchKernelGGL(tau_init_kernel<NV>, dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, ds, Y, ldy, assign, \
-                     tau, best, po)
+#define SKM_TAU_LAUNCH(NV)                                                                                      \
+  do {                                                                                                          \
+    if (batch && NV > 0)                                                                                        \
+      hipLaunchKernelGGL((tau_init_kernel<NV, (NV > 0)>), dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, ds, Y, \
+                         ldy, assign, tau, best, po);                                                           \
+    else                                                                                                        \
+      hipLaunchKernelGGL((tau_init_kernel<NV, false>), dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, ds, Y,   \
+                         ldy, assign, tau, best, po);                                                           \
+  } while (0)
   if (nv <= 1) SKM_TAU_LAUNCH(1);
   else if (nv <= 2) SKM_TAU_LAUNCH(2);
   else if (nv <= 3) SKM_TAU_LAUNCH(3);
