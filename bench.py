@@ -8,7 +8,10 @@ and the un-rotation of the centroids.  Inputs are generated once, seeded, on the
 resident in HBM when the timed region starts.  Every fit makes its own rotation matrix R on the device
 (fp64 Gram-Schmidt of a seeded Gaussian matrix), inside the timed region.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (point*centroid*dim per second over whole fits), ms_per_step, the workload in
+config, per-iteration seconds, `roofline` for the dominant kernel (algorithmic flop per launch over its HIP-event
+time, against the dense fp16 matrix peak divided by the three products of the split arithmetic), `stages` with the
+same figures for every kernel family, and `cpu_baseline` (the CPU oracle timed on a bounded sample of the workload).
 """
 from __future__ import annotations
 
