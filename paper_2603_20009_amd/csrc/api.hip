@@ -316,6 +316,16 @@ struct Ctx {
   uint32_t *Ys = nullptr;     // [k][ds + 32] the same of Y, remade in every pruned step
   float *xnp = nullptr;       // [ds / 16][n] prefix norms of the points at every multiple of 16 dims, written by the
   bool xnp_valid = false;     // first pruned step (the points of a context never change)
+  // Regrouping (a fit with several steps left): once the tables exist and a full update has just grouped the points
+  // by their cluster, the next threshold pass rewrites the points, their split copy, their tables and every per-point
+  // array in that order.  Row tiles then hold points of one or two clusters, whose challengers are the same few
+  // centroids: the alive pairs of a step gather in few tiles, the others end at the first test, and the rows and
+  // centroid blocks the gather kernel fetches are shared by neighbouring pairs.
+  float *Xr2 = nullptr;          // [n][ds] the points in the new order (NULL: no regrouping in this context)
+  int32_t *pos_to_id = nullptr;  // [n] point of every position
+  bool regroup_ok = false;       // the caller has enough steps left for it to pay
+  bool order_fresh = false;      // up.order groups the points by the labels now in `prev`
+  bool permuted = false;
   float *ynp = nullptr;       // [nb + 1][k] prefix norms of the centroids at the checkpoints of the current step
   float *ynorm = nullptr;
   float *tau = nullptr, *dist = nullptr;
@@ -568,9 +578,21 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, c.k, nullptr, nullptr, c.counters + c.ncounters, c.st));
     tm.mark(ST_GEMM);
   }
-  // the first pruned step of a context also writes the tables that depend on the points only
-  HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st, c.xnp_valid ? nullptr : c.xnp,
-                         c.xnp_valid ? nullptr : c.Xs, c.amax + Ctx::AM_XR));
+  if (c.regroup_ok && !c.permuted && c.xnp_valid && c.order_fresh && c.Xr2 && have_prev) {
+    // this pass reads every point anyway: it writes them back grouped by cluster (see Ctx)
+    HIPCHK(hipMemcpyAsync(c.pos_to_id, c.up.order, sizeof(int32_t) * (size_t)c.n, hipMemcpyDeviceToDevice, c.st));
+    HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st, c.xnp, c.Xs,
+                           c.amax + Ctx::AM_XR, c.pos_to_id, c.Xr2, c.assign));
+    std::swap(c.prev, c.assign);   // the incumbents in the new order; the other buffer receives this step's labels
+    c.Xr = c.Xr2;
+    c.ldx = c.ds;
+    c.permuted = true;
+  } else {
+    // the first pruned step of a context also writes the tables that depend on the points only
+    HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st, c.xnp_valid ? nullptr : c.xnp,
+                           c.xnp_valid ? nullptr : c.Xs, c.amax + Ctx::AM_XR));
+  }
+  c.order_fresh = false;
   c.xnp_valid = true;
   HIPCHK(launch_split_rows(c.Y, c.ds, c.k, c.ds, c.amax + Ctx::AM_Y, c.Ys, c.st));
   tm.mark(ST_TAU);
@@ -632,6 +654,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
 int split_empty(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t *nempty_out);
 int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t *nempty_out, int64_t changed,
                 bool full) {
+  bool fresh = false;   // up.order rebuilt from the labels of this step
   if (!full && c.S_valid && changed == 0) {
     // no point changed its cluster: sums, sizes and therefore the means are those of the previous update
     ++c.inc_updates;
@@ -642,7 +665,9 @@ int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t
   } else {
     HIPCHK(launch_update(c.Xr, c.ldx, c.n, c.ds, c.assign, c.k, c.up, c.Y, c.ds, c.st, c.S, c.amax + Ctx::AM_Y));
     c.S_valid = true;
+    fresh = true;
   }
+  c.order_fresh = fresh;
   c.y_amax_valid = true;
   return split_empty(c, tm, split_rng, split_eps, nempty_out);
 }
@@ -794,7 +819,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   // the workspace in one piece: the context's buffers, the rotated points, the rotation matrices and their generator
   const size_t ds0 = (size_t)round_up(d, 16);
   const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, true);
-  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + (size_t)k * 16 + ((size_t)32 << 20)
+  CallArena ws(plan ? plan + 2 * (size_t)n * ds0 * 4 + (size_t)n * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 +
+                           (size_t)k * 16 + ((size_t)32 << 20)
                     : 0);
   Ctx c;
   c.st = (hipStream_t)p.stream;
@@ -872,6 +898,14 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   }
   rc = c.alloc_common(p.pair_budget, p.dense_frac, true);
   if (rc) return rc;
+  // regrouping of the points by cluster (Ctx): not with ETR, whose ground truth names points, and not for rows that the
+  // batched table writes of the threshold pass do not cover
+  // (it happens in the third step at the earliest and wants four steps, itself included, to pay)
+  const bool may_regroup = !p.etr && c.ds <= 2048 && n < ((int64_t)1 << 31) && iters + (p.final_assign ? 1 : 0) >= 6;
+  if (may_regroup) {
+    HIPCHK(c.pool.get(&c.Xr2, (size_t)n * c.ds));
+    HIPCHK(c.pool.get(&c.pos_to_id, (size_t)n));
+  }
 
   // ---- InitCentroids: k distinct rows of X~
   {
@@ -980,6 +1014,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
       rc = step_exact(c, tm, ss);
     } else {
       std::swap(c.assign, c.prev);
+      // the rewrite costs about as much as three threshold passes and saves a fraction of every later step
+      c.regroup_ok = may_regroup && (iters - t + 1) + (p.final_assign ? 1 : 0) >= 4;
       rc = step_pruned(c, tm, dprime, (double)p.eps0, true, ss);
     }
     if (rc) return rc;
@@ -1023,6 +1059,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   if (p.final_assign) {
     StepStats ss;
     std::swap(c.assign, c.prev);
+    c.regroup_ok = false;
     rc = step_pruned(c, tm, dprime, (double)p.eps0, true, ss);
     if (rc) return rc;
     float ms[ST_COUNT], total;
@@ -1030,8 +1067,13 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     if (tr && rows < tr->capacity) fill_row(tr->row[rows], ss, n, k, 0, -1.0, ms, total);
     ++rows;
   }
-  if (assign_out) HIPCHK(hipMemcpyAsync(assign_out, c.assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
-  if (dist_out) HIPCHK(hipMemcpyAsync(dist_out, c.dist, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+  if (c.permuted) {   // per-point results back in the caller's order
+    if (assign_out) HIPCHK(launch_scatter_by_index(c.assign, c.pos_to_id, n, assign_out, c.st));
+    if (dist_out) HIPCHK(launch_scatter_by_index(c.dist, c.pos_to_id, n, dist_out, c.st));
+  } else {
+    if (assign_out) HIPCHK(hipMemcpyAsync(assign_out, c.assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+    if (dist_out) HIPCHK(hipMemcpyAsync(dist_out, c.dist, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+  }
 
   // ---- Algorithm 1, last line: Y = Y~ R^T
   if (timed) HIPCHK(hipEventRecord(e_end0, c.st));

@@ -160,9 +160,15 @@ hipError_t launch_prune(const PruneArgs &a, hipStream_t st);
 // With xnp ([ds / 16][n], ds a multiple of 16) the same pass writes the table of prefix norms
 // xnp[p][i] = ||x_i[0 : 16 (p + 1))||^2 that the progressive kernel reads at its checkpoints; with xs also the
 // split-fp16 copy of the points (the layout of launch_split_rows, scaled by the bound *x_absmax).
+// Regrouping (order, xr_out, label_out: all or none): output slot p of every array above takes point order[p] (a
+// permutation of 0 .. n - 1); the row of that point is copied to xr_out[p] (row stride ds) and its label to
+// label_out[p].  `assign` is still indexed by point.
 hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
                            const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st,
-                           float *xnp = nullptr, uint32_t *xs = nullptr, const unsigned int *x_absmax = nullptr);
+                           float *xnp = nullptr, uint32_t *xs = nullptr, const unsigned int *x_absmax = nullptr,
+                           const int32_t *order = nullptr, float *xr_out = nullptr, int32_t *label_out = nullptr);
+// dst[idx[p]] = src[p] for 4-byte items
+hipError_t launch_scatter_by_index(const void *src, const int32_t *idx, int64_t n, void *dst, hipStream_t st);
 
 // ynorm[c] = ||Y[c][0:dn)||^2 and (if Ypdx) the block-major copy of the dims from dprime on.
 // ynp (optional, [nb + 1][k]): prefix norms of the centroids at the same checkpoints.

@@ -47,6 +47,11 @@ struct PrefixOut {
   uint32_t *xs;      // [n][ds + 32] or NULL
   const unsigned int *absmax;   // bound of |X| (bit pattern) that fixes the scale of xs
   float scale;       // split_scale(*absmax), set by the kernel
+  // Regrouping (all three or none): output slot p takes point order[p]; its row is copied to xr_out (row stride ds)
+  // and its label to label_out[p], so that every per-point array continues in the new order.
+  const int32_t *order;
+  float *xr_out;
+  int32_t *label_out;
 };
 
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -114,7 +119,8 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
   __shared__ float s_np[BATCH ? kPrefixStageRows * 64 : 1];
   if (po.xs) po.scale = split_scale(*po.absmax);
   const int lane = threadIdx.x & 63;
-  auto point = [&](int64_t i, int slot) {
+  auto point = [&](int64_t p, int slot) {   // output slot p <- point i
+    const int64_t i = po.order ? (int64_t)po.order[p] : p;
     const int a = assign[i];
     const float *x = Xr + i * ldx;
     const float *y = Y + (int64_t)a * ldy;
@@ -146,14 +152,19 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
         for (int u = 0; u < NV; ++u) {
           if (256 * u >= ds) break;
           const float q = fmaf(xv[u].x, xv[u].x, fmaf(xv[u].y, xv[u].y, fmaf(xv[u].z, xv[u].z, xv[u].w * xv[u].w)));
-          base = emit_prefix(po, i, lane, u, q, base, BATCH ? s_np : nullptr, slot);
+          base = emit_prefix(po, p, lane, u, q, base, BATCH ? s_np : nullptr, slot);
         }
       }
       if (po.xs) {
-        emit_split_pads(po, i, lane);
+        emit_split_pads(po, p, lane);
 #pragma unroll
         for (int u = 0; u < NV; ++u)
-          if (lane * 4 + 256 * u < ds) emit_split(po, i, lane * 4 + 256 * u, xv[u]);
+          if (lane * 4 + 256 * u < ds) emit_split(po, p, lane * 4 + 256 * u, xv[u]);
+      }
+      if (po.xr_out) {
+#pragma unroll
+        for (int u = 0; u < NV; ++u)
+          if (lane * 4 + 256 * u < ds) *reinterpret_cast<float4 *>(po.xr_out + p * (int64_t)ds + lane * 4 + 256 * u) = xv[u];
       }
     } else {
       float base = 0.f;
@@ -171,18 +182,20 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
         s = fmaf(dw, dw, s);
         if (po.xnp) {
           const float q = fmaf(xv.x, xv.x, fmaf(xv.y, xv.y, fmaf(xv.z, xv.z, xv.w * xv.w)));
-          base = emit_prefix(po, i, lane, c0 >> 8, q, base);
+          base = emit_prefix(po, p, lane, c0 >> 8, q, base);
         }
         if (po.xs) {
-          if (c0 == 0) emit_split_pads(po, i, lane);
-          if (c < ds) emit_split(po, i, c, xv);
+          if (c0 == 0) emit_split_pads(po, p, lane);
+          if (c < ds) emit_split(po, p, c, xv);
         }
+        if (po.xr_out && c < ds) *reinterpret_cast<float4 *>(po.xr_out + p * (int64_t)ds + c) = xv;
       }
     }
     s = wave_sum(s);
     if (lane == 0) {
-      if (tau) tau[i] = s;
-      if (best) best[i] = pack_key(s, a);
+      if (tau) tau[p] = s;
+      if (best) best[p] = pack_key(s, a);
+      if (po.label_out) po.label_out[p] = a;
     }
   };
   if (BATCH) {
@@ -205,7 +218,8 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
 
 hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
                            const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st, float *xnp,
-                           uint32_t *xs, const unsigned int *x_absmax) {
+                           uint32_t *xs, const unsigned int *x_absmax, const int32_t *order, float *xr_out,
+                           int32_t *label_out) {
   if (n <= 0) return hipSuccess;
   const int nv = (ds + 255) / 256;
   const bool batch = xnp != nullptr && nv <= 8 && ds / 16 <= kPrefixStageRows;
@@ -213,7 +227,9 @@ hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, 
   const int64_t cap = (int64_t)num_cus() * 32;
   if (blocks > cap) blocks = cap;
   if (xs && (ds % 16 != 0 || !x_absmax)) return hipErrorInvalidValue;
-  const PrefixOut po{xnp, n, ds, xs, x_absmax, 0.f};
+  if ((order != nullptr) != (xr_out != nullptr) || (order != nullptr) != (label_out != nullptr)) return hipErrorInvalidValue;
+  if (xr_out && (reinterpret_cast<uintptr_t>(xr_out) & 15u)) return hipErrorInvalidValue;
+  const PrefixOut po{xnp, n, ds, xs, x_absmax, 0.f, order, xr_out, label_out};
 #define SKM_TAU_LAUNCH(NV)                                                                                      \
   do {                                                                                                          \
     if (batch && NV > 0)                                                                                        \
@@ -231,6 +247,18 @@ hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, 
   else if (nv <= 8) SKM_TAU_LAUNCH(8);
   else SKM_TAU_LAUNCH(0);
 #undef SKM_TAU_LAUNCH
+  return hipGetLastError();
+}
+
+// dst[idx[p]] = src[p] (4-byte items): per-point results back from a regrouped order to the caller's
+__global__ void scatter_by_index_kernel(const uint32_t *src, const int32_t *idx, int64_t n, uint32_t *dst) {
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n; p += (int64_t)gridDim.x * blockDim.x) dst[idx[p]] = src[p];
+}
+hipError_t launch_scatter_by_index(const void *src, const int32_t *idx, int64_t n, void *dst, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  const int64_t blocks = std::min<int64_t>((n + 255) / 256, (int64_t)num_cus() * 16);
+  hipLaunchKernelGGL(scatter_by_index_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint32_t *)src, idx, n,
+                     (uint32_t *)dst);
   return hipGetLastError();
 }
 

@@ -696,8 +696,13 @@ def test_host_resident_fit(skm, orc, dg, n, d, k, batch, pinned):
     # the same fit with the points on the device, every cluster sum recomputed in every update
     dev = skm.fit(cuda(X), k, iters, 3, skm.FitOptions(R=cuda(R), eps0=EPS0, adjust_dprime=False, full_update=True))
     assert (dev.assign.cpu().numpy() == a).mean() >= 0.999
-    assert rel_l2(got.centroids.cpu().numpy(), dev.centroids.cpu().numpy()) < 1e-3
-    same = dev.assign.cpu().numpy() == a
+    # (the two fits visit the points in different orders and tile them differently: a near-tie may fall the other way,
+    # which moves a point between two clusters; the clusters with the same members must agree)
+    check_assignment(dev.assign.cpu().numpy(), ref.assign, orc.rotate(X, R), ref.centroids_rot,
+                     own=(X, dev.centroids.cpu().numpy()))
+    clean = check_centroids(got.centroids.cpu().numpy(), dev.centroids.cpu().numpy(), a, dev.assign.cpu().numpy())
+    same = (dev.assign.cpu().numpy() == a) & np.isin(a, clean)          # clusters with the same members in both fits
+    assert same.mean() > 0.9
     assert np.abs(got.dist.numpy()[same] - dev.dist.cpu().numpy()[same]).max() < 1e-5
 
 
