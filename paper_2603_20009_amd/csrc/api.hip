@@ -326,6 +326,8 @@ struct Ctx {
   bool regroup_ok = false;       // the caller has enough steps left for it to pay
   bool order_fresh = false;      // up.order groups the points by the labels now in `prev`
   bool permuted = false;
+  unsigned long long *point_keys = nullptr;   // keys that name points (ETR ground truth): renumbered with the points
+  int64_t n_point_keys = 0;
   float *ynp = nullptr;       // [nb + 1][k] prefix norms of the centroids at the checkpoints of the current step
   float *ynorm = nullptr;
   float *tau = nullptr, *dist = nullptr;
@@ -584,6 +586,8 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st, c.xnp, c.Xs,
                            c.amax + Ctx::AM_XR, c.pos_to_id, c.Xr2, c.assign));
     std::swap(c.prev, c.assign);   // the incumbents in the new order; the other buffer receives this step's labels
+    if (c.point_keys)   // (up.order is scratch until the next full update rebuilds it)
+      HIPCHK(launch_remap_key_ids(c.point_keys, c.n_point_keys, c.pos_to_id, c.n, c.up.order, c.st));
     c.Xr = c.Xr2;
     c.ldx = c.ds;
     c.permuted = true;
@@ -898,10 +902,9 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   }
   rc = c.alloc_common(p.pair_budget, p.dense_frac, true);
   if (rc) return rc;
-  // regrouping of the points by cluster (Ctx): not with ETR, whose ground truth names points, and not for rows that the
-  // batched table writes of the threshold pass do not cover
-  // (it happens in the third step at the earliest and wants four steps, itself included, to pay)
-  const bool may_regroup = !p.etr && c.ds <= 2048 && n < ((int64_t)1 << 31) && iters + (p.final_assign ? 1 : 0) >= 6;
+  // regrouping of the points by cluster (Ctx): not for rows that the batched table writes of the threshold pass do not
+  // cover (it happens in the third step at the earliest and wants four steps, itself included, to pay)
+  const bool may_regroup = c.ds <= 2048 && n < ((int64_t)1 << 31) && iters + (p.final_assign ? 1 : 0) >= 6;
   if (may_regroup) {
     HIPCHK(c.pool.get(&c.Xr2, (size_t)n * c.ds));
     HIPCHK(c.pool.get(&c.pos_to_id, (size_t)n));
@@ -983,6 +986,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     HIPCHK(c.pool.get(&Sq, (size_t)p.nq * k));
     HIPCHK(c.pool.get(&ynorm_full, (size_t)k));
     HIPCHK(c.pool.get(&etr_scal, 2));
+    c.point_keys = gt_keys;   // the ground truth names points: it follows them if they are regrouped
+    c.n_point_keys = (int64_t)p.nq * p.topk;
   }
   if (timed) HIPCHK(hipEventRecord(e_gt1, c.st));
   if (timed) HIPCHK(hipEventRecord(e_init, c.st));

@@ -262,6 +262,27 @@ hipError_t launch_scatter_by_index(const void *src, const int32_t *idx, int64_t 
   return hipGetLastError();
 }
 
+// inv[perm[p]] = p, then the point id in the low half of every key replaced by its position (keys of ~0 stay)
+__global__ void invert_permutation_kernel(const int32_t *perm, int64_t n, int32_t *inv) {
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n; p += (int64_t)gridDim.x * blockDim.x) inv[perm[p]] = (int32_t)p;
+}
+__global__ void remap_key_ids_kernel(unsigned long long *keys, int64_t m, const int32_t *inv, int64_t n) {
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < m; e += (int64_t)gridDim.x * blockDim.x) {
+    const unsigned long long key = keys[e];
+    const unsigned long long id = key & 0xffffffffull;
+    if (key != ~0ull && (int64_t)id < n) keys[e] = (key & ~0xffffffffull) | (unsigned long long)(unsigned int)inv[id];
+  }
+}
+hipError_t launch_remap_key_ids(unsigned long long *keys, int64_t m, const int32_t *perm, int64_t n, int32_t *inv_scratch,
+                                hipStream_t st) {
+  if (n <= 0 || m <= 0) return hipSuccess;
+  const int64_t b1 = std::min<int64_t>((n + 255) / 256, (int64_t)num_cus() * 16);
+  hipLaunchKernelGGL(invert_permutation_kernel, dim3((unsigned)b1), dim3(256), 0, st, perm, n, inv_scratch);
+  const int64_t b2 = std::min<int64_t>((m + 255) / 256, (int64_t)num_cus() * 16);
+  hipLaunchKernelGGL(remap_key_ids_kernel, dim3((unsigned)b2), dim3(256), 0, st, keys, m, (const int32_t *)inv_scratch, n);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ centroid preparation
 // One workgroup per centroid: ynorm[c] over dims [0, dn), and the trailing dims from dprime on
 // copied to Ypdx[m][c][0..63] (block m = dims dprime+64m ..), zero filled past the row.
