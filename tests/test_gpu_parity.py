@@ -317,6 +317,31 @@ def test_fit_over_seeded_shapes(skm, orc, dg, case):
                           np.bincount(ref.assign, minlength=k) == 0)
 
 
+def test_fit_regroups_points_across_row_chunks(skm, orc, dg):
+    """From the third step on a long fit works on the points grouped by cluster (labels and distances come back in the
+    caller's order).  With a small pair budget the rows are also processed in several chunks; the result must follow
+    the oracle like any other fit, and must not depend on the budget beyond near-ties."""
+    X = dg.mixture(9000, 100, 60, 31, "embed").numpy()
+    R = orc.random_rotation(100, 4)
+    idx = orc.sample_rows(19, 9000, 70)
+    ref = orc.fit(X, 70, 7, 19, orc.FitParams(eps0=EPS0, adjust_dprime=True), R=R, init_idx=idx)
+    Xr = orc.rotate(X, R)
+    fits = []
+    for budget in (0, 150_000):     # default, and about 2000 rows (16 row tiles) per chunk
+        got = skm.fit(cuda(X), 70, 7, 19, skm.FitOptions(R=cuda(R), eps0=EPS0, adjust_dprime=True, pair_budget=budget))
+        a = got.assign.cpu().numpy()
+        check_assignment(a, ref.assign, Xr, ref.centroids_rot, own=(X, got.centroids.cpu().numpy()))
+        clean = check_centroids(got.centroids.cpu().numpy(), ref.centroids, a, ref.assign)
+        assert [g["dprime"] for g in got.trace] == [r["dprime"] for r in ref.trace]
+        assert got.trace[-1]["objective"] == pytest.approx(ref.trace[-1]["objective"], rel=1e-4)
+        same = (a == ref.assign) & np.isin(ref.assign, clean)
+        assert same.mean() > 0.9
+        assert np.abs(got.dist.cpu().numpy()[same] - ref.dist[same]).max() < 1e-5      # distances sit with their points
+        assert float(got.dist.sum()) == pytest.approx(got.trace[-1]["objective"], rel=1e-5)
+        fits.append(a)
+    assert (fits[0] == fits[1]).mean() >= 0.999
+
+
 def test_fit_is_bitwise_reproducible(skm, orc, dg):
     X = cuda(dg.mixture(30_000, 128, 64, 12, "linear").numpy())
     R = cuda(orc.random_rotation(128, 2))
