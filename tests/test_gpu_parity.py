@@ -421,6 +421,36 @@ def test_c2_full_size_sampled_parity(skm, orc, dg):
     torch.cuda.empty_cache()
 
 
+def test_c2_full_fit_as_benchmarked_keeps_labels_with_their_points(skm, orc, dg):
+    """The whole C2 fit as bench.py times it (10 iterations + final pass, points regrouped by cluster from the third
+    step on).  On sampled rows the returned label must be the nearest of the returned centroids (up to near-ties and
+    the pruning's rare losses), the returned distance the direct one, and the distances must add up to the objective
+    of the final pass: a label or a distance that came back at the wrong row would break all three."""
+    torch.cuda.empty_cache()
+    n, d, k = 1_000_000, 1536, 1024
+    X = dg.config_data("C2", device="cuda")
+    Rn = orc.random_rotation(d, 42)
+    say("full C2 fit")
+    fr = skm.fit(X, k, 10, 42, skm.FitOptions(R=cuda(Rn)))
+    assert fr.iters_run == 10 and len(fr.trace) == 11
+    a = fr.assign.cpu().numpy()
+    dist = fr.dist.cpu().numpy()
+    assert np.bincount(a, minlength=k).sum() == n and a.min() >= 0 and a.max() < k
+    assert float(dist.astype(np.float64).sum()) == pytest.approx(fr.trace[-1]["objective"], rel=1e-5)
+    rng = np.random.default_rng(5)
+    rows = np.sort(rng.choice(n, 1536, replace=False))
+    Xs = X[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    Y = fr.centroids.cpu().numpy().astype(np.float64)
+    ao, do = orc.assign_full(Xs, Y)
+    check_assignment(a[rows], ao, Xs, Y, min_agree=0.998)
+    direct = ((Xs - Y[a[rows]]) ** 2).sum(1)
+    assert np.abs(dist[rows] - direct).max() < 1e-5
+    obj = [t["objective"] for t in fr.trace]
+    assert all(b <= x * (1 + 1e-6) for x, b in zip(obj, obj[1:]))
+    del X, fr
+    torch.cuda.empty_cache()
+
+
 def test_c4_full_size_sampled_parity(skm, orc, dg):
     """Workload C4 (1 000 000 x 1536, k = 16 384): the large-k regime, where a step is a million tiles of one to
     three slabs.  Pruned steps at d' = 192 and at d' = 64 (what the d' rule reaches on this workload), checked by
