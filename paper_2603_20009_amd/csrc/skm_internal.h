@@ -169,6 +169,10 @@ hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, 
                            const int32_t *order = nullptr, float *xr_out = nullptr, int32_t *label_out = nullptr);
 // dst[idx[p]] = src[p] for 4-byte items
 hipError_t launch_scatter_by_index(const void *src, const int32_t *idx, int64_t n, void *dst, hipStream_t st);
+// order_out = order_in (points grouped by cluster, segment c = [off[c], off[c+1])) with every segment stably sorted by
+// the signs of the first four dimensions of its points.  key_scratch: n bytes.
+hipError_t launch_suborder(const float *Xr, int64_t ldx, int64_t n, int32_t k, const int32_t *off, const int32_t *order_in,
+                           unsigned char *key_scratch, int32_t *order_out, hipStream_t st);
 // keys hold a point id in their low 32 bits (packed (distance, point) keys; ~0 = none): every id becomes the position
 // p with perm[p] = id.  inv_scratch: n ints.
 hipError_t launch_remap_key_ids(unsigned long long *keys, int64_t m, const int32_t *perm, int64_t n, int32_t *inv_scratch,

@@ -262,6 +262,65 @@ hipError_t launch_scatter_by_index(const void *src, const int32_t *idx, int64_t 
   return hipGetLastError();
 }
 
+// Sub-order of the points inside a cluster for the regrouping.  key[i] = the signs of the first four (rotated)
+// dimensions of point i: four random hyperplanes through the origin cut every cluster into up to 16 pieces that are
+// compact in space, and points of one piece share their challengers more than points of the whole cluster do.
+__global__ void sign_key_kernel(const float *Xr, int64_t ldx, int64_t n, unsigned char *key) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const float4 v = *reinterpret_cast<const float4 *>(Xr + i * ldx);
+    key[i] = (unsigned char)((v.x > 0.f) | ((v.y > 0.f) << 1) | ((v.z > 0.f) << 2) | ((v.w > 0.f) << 3));
+  }
+}
+// order_out = order_in with every cluster's segment [off[c], off[c+1]) stably sorted by key (16 values): one
+// workgroup per cluster, thread t takes the t-th contiguous part of the segment, so that the order inside a key is kept.
+__global__ void __launch_bounds__(256) suborder_kernel(const int32_t *off, const int32_t *order_in, const unsigned char *key,
+                                                       int32_t *order_out) {
+  __shared__ int s_cnt[16][256];   // [key][thread]: count, then first output slot
+  __shared__ int s_tot[16];
+  const int c = blockIdx.x, t = threadIdx.x;
+  const int lo = off[c], len = off[c + 1] - lo;
+  const int part = (len + 255) / 256;
+  const int p0 = min(t * part, len), p1 = min(p0 + part, len);
+  for (int b = 0; b < 16; ++b) s_cnt[b][t] = 0;
+  for (int p = p0; p < p1; ++p) s_cnt[key[order_in[lo + p]]][t] += 1;
+  __syncthreads();
+  if (t < 16) {   // exclusive scan of this key's counts over the threads
+    int run = 0;
+    for (int u = 0; u < 256; ++u) {
+      const int v = s_cnt[t][u];
+      s_cnt[t][u] = run;
+      run += v;
+    }
+    s_tot[t] = run;
+  }
+  __syncthreads();
+  if (t == 0) {   // first slot of every key
+    int run = 0;
+    for (int b = 0; b < 16; ++b) {
+      const int v = s_tot[b];
+      s_tot[b] = run;
+      run += v;
+    }
+  }
+  __syncthreads();
+  for (int p = p0; p < p1; ++p) {
+    const int id = order_in[lo + p];
+    const int b = key[id];
+    order_out[lo + s_tot[b] + s_cnt[b][t]] = id;
+    s_cnt[b][t] += 1;
+  }
+}
+hipError_t launch_suborder(const float *Xr, int64_t ldx, int64_t n, int32_t k, const int32_t *off, const int32_t *order_in,
+                           unsigned char *key_scratch, int32_t *order_out, hipStream_t st) {
+  if (n <= 0 || k <= 0) return hipSuccess;
+  if ((reinterpret_cast<uintptr_t>(Xr) & 15u) || ldx % 4 != 0) return hipErrorInvalidValue;
+  const int64_t blocks = std::min<int64_t>((n + 255) / 256, (int64_t)num_cus() * 16);
+  hipLaunchKernelGGL(sign_key_kernel, dim3((unsigned)blocks), dim3(256), 0, st, Xr, ldx, n, key_scratch);
+  hipLaunchKernelGGL(suborder_kernel, dim3((unsigned)k), dim3(256), 0, st, off, order_in, (const unsigned char *)key_scratch,
+                     order_out);
+  return hipGetLastError();
+}
+
 // inv[perm[p]] = p, then the point id in the low half of every key replaced by its position (keys of ~0 stay)
 __global__ void invert_permutation_kernel(const int32_t *perm, int64_t n, int32_t *inv) {
   for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n; p += (int64_t)gridDim.x * blockDim.x) inv[perm[p]] = (int32_t)p;

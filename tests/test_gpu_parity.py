@@ -261,7 +261,9 @@ def test_fit_with_dprime_adjustment(skm, orc, dg):
     assert [g["dprime"] for g in got.trace] == [r["dprime"] for r in ref.trace]
     assert len({g["dprime"] for g in got.trace[1:]}) > 1                    # the controller did move d'
     assert got.trace[-1]["objective"] == pytest.approx(ref.trace[-1]["objective"], rel=1e-4)
-    assert rel_l2(got.centroids.cpu().numpy(), ref.centroids) < 1e-3
+    check_assignment(got.assign.cpu().numpy(), ref.assign, orc.rotate(X, R), ref.centroids_rot,
+                     own=(X, got.centroids.cpu().numpy()))
+    check_centroids(got.centroids.cpu().numpy(), ref.centroids, got.assign.cpu().numpy(), ref.assign)
 
 
 def test_fit_without_rotation_or_final_pass(skm, orc, dg):
