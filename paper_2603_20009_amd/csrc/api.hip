@@ -581,7 +581,18 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, c.k, nullptr, nullptr, c.counters + c.ncounters, c.st));
     tm.mark(ST_GEMM);
   }
-  if (c.regroup_ok && !c.permuted && c.xnp_valid && c.order_fresh && c.Xr2 && have_prev) {
+  bool regroup = c.regroup_ok && !c.permuted && c.xnp_valid && c.order_fresh && c.Xr2 && have_prev;
+  if (regroup) {
+    // The update leaves the members of a cluster sorted by index only up to a size (larger clusters keep the order in
+    // which the scatter placed them, which depends on scheduling): with such a cluster the new order, and with it the
+    // rounding of the results, would differ from run to run.  Those fits keep the input order.
+    std::vector<int32_t> off((size_t)c.k + 1);
+    HIPCHK(hipMemcpyAsync(off.data(), c.up.off, sizeof(int32_t) * off.size(), hipMemcpyDeviceToHost, c.st));
+    HIPCHK(hipStreamSynchronize(c.st));
+    for (int32_t j = 0; j < c.k && regroup; ++j) regroup = off[(size_t)j + 1] - off[(size_t)j] <= update_sort_cap();
+    if (!regroup) c.regroup_ok = false;
+  }
+  if (regroup) {
     // this pass reads every point anyway: it writes them back grouped by cluster (see Ctx)
     // Inside a cluster that spans several row tiles the points follow the signs of their first four dimensions, then
     // their index: which points of a cluster share a tile matters (measured: -3 % on a fit with 1000 points per

@@ -210,6 +210,8 @@ struct UpdateWs {
   int64_t max_segments;
 };
 int64_t update_max_segments(int64_t n, int32_t k);
+// largest cluster whose members launch_update leaves sorted by index in w.order (larger ones: any order)
+int32_t update_sort_cap();
 // S (optional, [k][ds] fp64) receives the sum of every cluster; y_absmax (optional) the bit pattern of max |Y| of
 // the new centroids (the launcher clears it first).  With `accumulate` the sums of these n points are added to S
 // instead (one batch of a larger update); Y may then be NULL, and launch_means_from_sums finishes the update.

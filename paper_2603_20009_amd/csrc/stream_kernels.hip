@@ -670,6 +670,7 @@ __global__ void scatter_order_kernel(const int32_t *assign, int64_t n, const int
 // fp64 in whatever order they were scattered (the fp64 sum of fp32 values then differs from the
 // sorted-order sum by at most a few ulps of fp64, far below the fp32 rounding of the mean).
 constexpr int SORT_CAP = 8192;
+int32_t update_sort_cap() { return SORT_CAP; }
 __global__ void __launch_bounds__(256) sort_segments_kernel(const int32_t *off, int32_t *order) {
   __shared__ int32_t s[SORT_CAP];
   const int c = blockIdx.x;
