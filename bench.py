@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--config", default="C2", help="workload name in paper_2603_20009_amd.datagen.CONFIGS")
     ap.add_argument("--n", type=int, default=0, help="override the number of points (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--own-workspace", action="store_true",
+                    help="let the library allocate and free its workspace inside every call (default: the caller lends it)")
     ap.add_argument("--cpu-sample", type=int, default=12288)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 1 GiB device copy first (a kernel of known traffic for scaling rocprofv3 --pmc counters)")
@@ -87,7 +89,8 @@ def main():
     X = datagen.config_data(args.config, device="cuda", n=n)
     queries = datagen.config_queries(args.config, device="cuda") if cfg.get("etr") else None
     torch.cuda.synchronize()
-    opts = skm.FitOptions(etr=bool(cfg.get("etr")), queries=queries)   # R = None: made by the fit from the seed
+    # R = None: made by the fit from the seed
+    opts = skm.FitOptions(etr=bool(cfg.get("etr")), queries=queries, own_workspace=args.own_workspace)
 
     def step():
         return skm.fit(X, k, iters, seed, opts)
@@ -191,6 +194,12 @@ def main():
         "s_per_iteration": {"iteration_1": ms_iter1 * 1e-3, "iterations_2_plus_median": ms_iter_rest * 1e-3,
                             "fit_total_device": avg(lambda r: r.timing["ms_total"]) * 1e-3},
         "ms_before_iteration_1": avg(lambda r: r.timing["ms_init"]),
+        "host": {"ms_call_wall": avg(lambda r: r.timing["ms_host_total"]),
+                 "ms_workspace_alloc": avg(lambda r: r.timing["ms_host_alloc"]),
+                 "ms_workspace_free": avg(lambda r: r.timing["ms_host_free"]),
+                 "ms_wall_minus_device": ms_per_step - avg(lambda r: r.timing["ms_total"]),
+                 "workspace": "lent by the caller (a torch tensor; skm_workspace_bytes)" if not args.own_workspace
+                              else "allocated and freed by the library inside every call"},
         "dprime_per_step": dprimes,
         "prune_frac_per_step": [round(t["prune_frac"], 5) for t in results[-1].trace],
         "objective_final": results[-1].trace[-1]["objective"],

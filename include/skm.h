@@ -8,12 +8,16 @@
  *     declared, unless the comment says "host".  The params / trace structs
  *     themselves live in host memory.
  *   - The caller owns every buffer it passes.  The library allocates and
- *     frees its own workspace inside the call.
+ *     frees its own workspace inside the call, unless the caller lends it one
+ *     (params->workspace, see skm_workspace_bytes).
  *   - Work is enqueued on `params->stream` (a hipStream_t, NULL = the default
  *     stream) and the call returns after that stream has been synchronised,
  *     so outputs are complete on return.
- *   - Return value: 0 on success, a negative SKM_E* code otherwise.  On error
- *     outputs are unspecified.  No exception crosses this boundary.
+ *   - Return value: 0 on success, a negative SKM_E* code otherwise.  An
+ *     argument error (SKM_EINVAL, or SKM_ENOMEM for a workspace that is too
+ *     small) is found before any work is enqueued and leaves the outputs
+ *     untouched; after any other error their contents are unspecified.  No
+ *     exception crosses this boundary.
  *   - Thread-compatible, not thread-safe: concurrent calls must use distinct
  *     streams and distinct buffers.
  *   - Limits: 16 <= d <= 16384, 1 <= k <= min(n, 2^24), n < 2^31.
@@ -32,6 +36,9 @@ extern "C" {
 #define SKM_ENOMEM (-2)    /* workspace allocation failed */
 #define SKM_EHIP (-3)      /* a HIP call failed; see skm_last_error() */
 #define SKM_EINTERNAL (-4) /* an internal invariant was violated */
+#define SKM_EOVERFLOW (-5) /* the list that carries pairs from the dense tiles to the gather kernel overflowed
+                              (cannot happen with the capacities the library derives from pair_budget; reported
+                              instead of a wrong result if it ever does) */
 
 #define SKM_MAX_BLOCKS 32 /* counters kept for at most this many trailing blocks */
 
@@ -71,8 +78,10 @@ typedef struct skm_trace {
   float ms_init;       /* out: everything before iteration 1: workspace, R, rotation, initial centroids, ETR set-up */
   float ms_etr_gt;     /* out: ETR ground truth (0 when supplied or ETR off) */
   float ms_unrotate;   /* out: Y = Y~ R^T */
-  float ms_total;      /* out: whole call, device time */
-  float reserved2;
+  float ms_total;      /* out: whole call, device time (HIP events on the call's stream) */
+  float ms_host_total; /* out: whole call on the host clock, entry to return (skm_fit_ex, skm_assign_ex) */
+  float ms_host_alloc; /* out: of that, getting the workspace (0 with params->workspace) */
+  float ms_host_free;  /* out: of that, releasing it */
   skm_trace_row *row;  /* host array, caller-allocated */
 } skm_trace;
 
@@ -121,9 +130,26 @@ typedef struct skm_params {
   int32_t full_update;   /* 0    : 1 = recompute every cluster sum from all points in every update.  By default, once at most
                             one point in eight changes its cluster, the fp64 sums of the previous update are
                             corrected by the rows that joined and left (the same means up to fp64 rounding) */
+  void *workspace;       /* NULL : device memory, 256-byte aligned, of at least skm_workspace_bytes(n, d, k, params)
+                            bytes that skm_fit_ex / skm_assign_ex use instead of allocating their own.  With it the
+                            call makes no device allocation at all; a workspace that is too small is refused with
+                            SKM_ENOMEM before any work is enqueued.  Contents are undefined afterwards.  The other
+                            entry points ignore it */
+  int64_t workspace_bytes; /* 0  : size of `workspace` */
+  float conv_tol;        /* 0    : > 0 = also stop (Section 3.3, the second termination condition) after an iteration
+                            t >= 2 in which at most this share of the points changed its cluster */
+  int32_t tau_group;     /* 0    : centroids after which a point's threshold tau is refreshed inside a step.  0 (= k):
+                            tau keeps its initial value for the whole step, the only form this library runs (the
+                            result is then independent of the order in which tiles are processed); any other value
+                            but k is refused with SKM_EINVAL */
 } skm_params;
 
 void skm_params_default(skm_params *p);
+
+/* Device bytes that skm_fit_ex (and skm_assign_ex) of this shape and these parameters take as workspace: what the
+ * call allocates itself when params->workspace is NULL, and what a caller-owned workspace must hold.  params may be
+ * NULL (defaults).  Returns a negative SKM_E* code for an invalid shape. */
+int64_t skm_workspace_bytes(int64_t n, int32_t d, int32_t k, const skm_params *params);
 
 /*
  * skm_fit -- Algorithm 1 with default parameters.

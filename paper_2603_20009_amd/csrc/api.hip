@@ -6,7 +6,10 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
+#include <mutex>
 #include <thread>
+#include <unordered_map>
 #include <system_error>
 #include <functional>
 #include <cmath>
@@ -28,7 +31,7 @@ int fail(int rc, const char *what) {
 }
 int fail_hip(hipError_t e, const char *where) {
   g_last_error = std::string(where) + ": " + hipGetErrorString(e);
-  return SKM_EHIP;
+  return e == hipErrorOutOfMemory ? SKM_ENOMEM : SKM_EHIP;
 }
 #define HIPCHK(expr)                                              \
   do {                                                            \
@@ -43,12 +46,20 @@ int fail_hip(hipError_t e, const char *where) {
 struct Arena {
   char *base = nullptr;
   size_t cap = 0, off = 0;
+  bool owned = true;     // false: the caller's memory (params->workspace)
+  bool strict = false;   // true: what does not fit is an error, never a hipMalloc
   ~Arena() {
-    if (base) (void)hipFree(base);
+    if (base && owned) (void)hipFree(base);
   }
   hipError_t init(size_t bytes) {
     cap = bytes;
     return hipMalloc(reinterpret_cast<void **>(&base), bytes);
+  }
+  void lend(void *mem, size_t bytes) {
+    base = static_cast<char *>(mem);
+    cap = bytes;
+    owned = false;
+    strict = true;
   }
 };
 thread_local Arena *tl_arena = nullptr;
@@ -83,6 +94,10 @@ struct Pool {
         arena->off = at + bytes;
         *out = reinterpret_cast<T *>(arena->base + at);
         return hipSuccess;
+      }
+      if (arena->strict) {   // a caller-owned workspace: the call allocates nothing
+        *out = nullptr;
+        return hipErrorOutOfMemory;
       }
     }
     hipError_t e = hipMalloc(&p, bytes);
@@ -193,13 +208,28 @@ enum { STREAM_INIT = 0, STREAM_SPLIT = 1, STREAM_QUERIES = 2, STREAM_ROTATION = 
 
 // k distinct indices of [0, n): the first k steps of a Fisher-Yates shuffle of the identity
 void sample_rows(uint64_t seed, uint64_t stream, int64_t n, int32_t k, int64_t *out) {
-  std::vector<int64_t> perm((size_t)n);
-  for (int64_t i = 0; i < n; ++i) perm[(size_t)i] = i;
   Rng r = rng_stream(seed, stream);
+  if ((int64_t)k * 8 >= n) {
+    std::vector<int64_t> perm((size_t)n);
+    for (int64_t i = 0; i < n; ++i) perm[(size_t)i] = i;
+    for (int32_t i = 0; i < k; ++i) {
+      const int64_t j = i + (int64_t)(r.next() % (uint64_t)(n - i));
+      std::swap(perm[(size_t)i], perm[(size_t)j]);
+      out[i] = perm[(size_t)i];
+    }
+    return;
+  }
+  // few draws from many rows: the same shuffle, keeping only the entries that no longer hold their own index (step i
+  // reads positions i and j >= i and never looks at a position below i again, so position i itself need not be kept)
+  std::unordered_map<int64_t, int64_t> moved;
+  moved.reserve((size_t)k * 2);
   for (int32_t i = 0; i < k; ++i) {
     const int64_t j = i + (int64_t)(r.next() % (uint64_t)(n - i));
-    std::swap(perm[(size_t)i], perm[(size_t)j]);
-    out[i] = perm[(size_t)i];
+    const auto it_i = moved.find(i);
+    const int64_t vi = it_i == moved.end() ? (int64_t)i : it_i->second;
+    const auto it_j = moved.find(j);
+    out[i] = it_j == moved.end() ? j : it_j->second;
+    moved[j] = vi;
   }
 }
 
@@ -348,6 +378,7 @@ struct Ctx {
   IncUpdateWs inc{};                 // workspace of the incremental update
   double *S = nullptr;               // [k][ds] cluster sums of the last update (fp64), valid once S_valid
   bool S_valid = false;
+  bool split_last = false;           // the last update re-seeded empty clusters (their donors' rows are perturbed)
   int32_t inc_updates = 0;           // update steps that took the incremental path
   int32_t *split_dev = nullptr;
   bool block_stats = false;
@@ -503,8 +534,22 @@ size_t plan_common_bytes(int64_t n, int32_t d, int32_t k, int64_t pair_budget, f
 struct CallArena {
   Arena arena;
   bool on = false;
-  explicit CallArena(size_t bytes) {
+  bool too_small = false;   // a caller's workspace that cannot hold `bytes`
+  explicit CallArena(size_t bytes, void *lent = nullptr, int64_t lent_bytes = 0) {
     if (tl_arena || bytes == 0) return;
+    if (lent) {
+      // the caller's memory: aligned up to the 256-byte granule of the pools
+      const uintptr_t a = (reinterpret_cast<uintptr_t>(lent) + 255) & ~(uintptr_t)255;
+      const size_t lost = (size_t)(a - reinterpret_cast<uintptr_t>(lent));
+      if (lent_bytes < 0 || (size_t)lent_bytes < bytes + lost) {
+        too_small = true;
+        return;
+      }
+      arena.lend(reinterpret_cast<void *>(a), (size_t)lent_bytes - lost);
+      tl_arena = &arena;
+      on = true;
+      return;
+    }
     if (arena.init(bytes) != hipSuccess) {
       (void)hipGetLastError();
       arena.base = nullptr;
@@ -520,6 +565,46 @@ struct CallArena {
   CallArena(const CallArena &) = delete;
   CallArena &operator=(const CallArena &) = delete;
 };
+
+// Host-clock readings of one call: entry, workspace ready, body done; the destructor (declared before the arena, so it
+// runs after the arena's release) writes them to the caller's trace.
+struct HostTimes {
+  using clk = std::chrono::steady_clock;
+  clk::time_point t0 = clk::now(), t_ws = t0, t_done = t0;
+  skm_trace *tr = nullptr;
+  bool done = false;
+  static float ms(clk::time_point a, clk::time_point b) { return std::chrono::duration<float, std::milli>(b - a).count(); }
+  void workspace_ready() { t_ws = clk::now(); }
+  void body_done(skm_trace *t) {
+    tr = t;
+    t_done = clk::now();
+    done = true;
+  }
+  ~HostTimes() {
+    if (!tr || !done) return;
+    const auto t1 = clk::now();
+    tr->ms_host_alloc = ms(t0, t_ws);
+    tr->ms_host_free = ms(t_done, t1);
+    tr->ms_host_total = ms(t0, t1);
+  }
+};
+
+// Upper bound of the device bytes one plain fit (or one assignment call) of this shape carves from its arena: the
+// context's buffers, the rotated points and their regrouped copy, the rotation matrices and their generator, the ETR
+// buffers.  What skm_workspace_bytes reports.
+size_t fit_workspace_need(int64_t n, int32_t d, int32_t k, const skm_params &p) {
+  const size_t ds0 = (size_t)((d + 15) / 16 * 16);
+  const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, true);
+  if (!plan) return 0;
+  size_t need = plan + 2 * (size_t)n * ds0 * 4 + (size_t)n * 5 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 +
+                (size_t)k * 16 + ((size_t)32 << 20);
+  if (p.etr && p.nq > 0 && p.topk > 0) {
+    const size_t nq = (size_t)p.nq;
+    need += (size_t)n * 4 + nq * (size_t)std::min<int64_t>(n, 1 << 16) * 4 + nq * (size_t)p.topk * 8 + nq * (ds0 + d) * 4 +
+            nq * 8 + nq * (size_t)k * 4 + (size_t)k * 4 + ((size_t)1 << 16);
+  }
+  return need;
+}
 
 struct StepStats {
   double objective = 0;
@@ -650,7 +735,8 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   if (int rc = c.fetch_step_block()) return rc;
   HIPCHK(hipStreamSynchronize(c.st));
   c.rb_cnt_valid = true;
-  if (*c.rb_flag != 0) return fail(SKM_EINTERNAL, "hand-over list overflow or a point left without a centroid");
+  if (*c.rb_flag & 1u) return fail(SKM_EOVERFLOW, "the hand-over list of the dense tiles overflowed");
+  if (*c.rb_flag != 0) return fail(SKM_EINTERNAL, "a point was left without a centroid");
   std::vector<unsigned long long> scal_h(c.rb_scal, c.rb_scal + nscal);
   const double obj = *c.rb_obj;
   for (int r = 1; r < kStatReplicas; ++r)   // fold the replicas into the first
@@ -678,8 +764,13 @@ int step_update(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t
                 bool full) {
   bool fresh = false;   // up.order rebuilt from the labels of this step
   if (!full && c.S_valid && changed == 0) {
-    // no point changed its cluster: sums, sizes and therefore the means are those of the previous update
+    // no point changed its cluster: sums, sizes and therefore the means are those of the previous update.  If that
+    // update was followed by a split, the donor's row still holds its perturbed copy: Algorithm 1's update puts the
+    // mean of its members back before the next split, so the means are rewritten from the sums.
     ++c.inc_updates;
+    if (c.split_last) {
+      HIPCHK(launch_means_from_sums(c.S, c.up.cnt, c.k, c.ds, c.Y, c.ds, c.amax + Ctx::AM_Y, c.st));
+    }
   } else if (!full && c.S_valid && 2 * changed <= c.inc.capacity - 2) {
     ++c.inc_updates;
     HIPCHK(launch_update_incremental(c.Xr, c.ldx, c.n, c.ds, c.assign, c.prev, changed, c.k, c.up, c.inc, c.S, c.Y, c.ds,
@@ -706,6 +797,7 @@ int split_empty(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t
   int64_t nempty = 0;
   for (int32_t v : cnt) nempty += (v == 0);
   *nempty_out = nempty;
+  c.split_last = false;
   if (nempty > 0) {
     // empty clusters in increasing index; donor drawn with probability proportional to its size
     // among clusters of at least two points; the donor's points are shared floor(n/2) / rest
@@ -736,6 +828,7 @@ int split_empty(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t
       HIPCHK(hipMemcpyAsync(c.split_dev, pairs.data(), sizeof(int32_t) * pairs.size(), hipMemcpyHostToDevice, c.st));
       HIPCHK(launch_split(c.Y, c.ds, c.d, c.split_dev, (int32_t)(pairs.size() / 2), split_eps, c.st));
       c.y_amax_valid = false;
+      c.split_last = true;
       HIPCHK(hipStreamSynchronize(c.st));  // `pairs` must outlive the copy
     }
   }
@@ -826,10 +919,14 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   if (rc) return rc;
   if (!centroids_out) return fail(SKM_EINVAL, "centroids_out is null");
   if (iters < 1) return fail(SKM_EINVAL, "iters must be >= 1");
+  HostTimes host;   // before the arena: its destructor runs after the workspace has been released
   skm_params p;
   if (pp) p = *pp; else skm_params_default(&p);
   if (!(p.dprime_frac > 0.f && p.dprime_frac <= 1.f)) return fail(SKM_EINVAL, "dprime_frac out of (0, 1]");
   if (!(p.eps0 >= 0.f)) return fail(SKM_EINVAL, "eps0 must be >= 0");
+  if (p.tau_group != 0 && p.tau_group != k)
+    return fail(SKM_EINVAL, "tau_group: only 0 (= k, the threshold frozen for the whole step) is implemented");
+  if (!(p.conv_tol >= 0.f && p.conv_tol <= 1.f)) return fail(SKM_EINVAL, "conv_tol out of [0, 1]");
   skm_trace *tr = p.trace;
   if (tr && (!tr->row || tr->capacity < 1)) return fail(SKM_EINVAL, "trace without rows");
   if (p.angular && p.etr) return fail(SKM_EINVAL, "the angular metric is not combined with ETR");
@@ -838,12 +935,11 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     return fit_sampled(X, n, d, k, iters, seed, p, centroids_out, assign_out, dist_out);
   }
 
-  // the workspace in one piece: the context's buffers, the rotated points, the rotation matrices and their generator
-  const size_t ds0 = (size_t)round_up(d, 16);
-  const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, true);
-  CallArena ws(plan ? plan + 2 * (size_t)n * ds0 * 4 + (size_t)n * 5 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 +
-                           (size_t)k * 16 + ((size_t)32 << 20)
-                    : 0);
+  // the workspace in one piece (the caller's, if it lends one): the context's buffers, the rotated points, the rotation
+  // matrices and their generator, the ETR buffers
+  CallArena ws(fit_workspace_need(n, d, k, p), p.workspace, p.workspace_bytes);
+  if (ws.too_small) return fail(SKM_ENOMEM, "params->workspace is smaller than skm_workspace_bytes() for this call");
+  host.workspace_ready();
   Ctx c;
   c.st = (hipStream_t)p.stream;
   c.n = n; c.d = d; c.k = k;
@@ -1076,6 +1172,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
         if (streak >= p.etr_patience) stop = true;
       }
     }
+    // Section 3.3, second condition (convergence): hardly any point changed its cluster
+    if (p.conv_tol > 0.f && t > 1 && (double)ss.changed <= (double)p.conv_tol * (double)n) stop = true;
     if (stop) break;
   }
 
@@ -1121,6 +1219,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     (void)hipEventElapsedTime(&tr->ms_unrotate, e_end0, e_end);
     (void)hipEventElapsedTime(&tr->ms_total, e_begin, e_end);
   }
+  host.body_done(tr);
   return SKM_OK;
 }
 
@@ -1362,10 +1461,16 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
   skm_params p;
   if (pp) p = *pp; else skm_params_default(&p);
   if (p.angular) return fail(SKM_EINVAL, "the angular metric is a fit option: normalise the inputs for a single step");
+  if (p.tau_group != 0 && p.tau_group != k)
+    return fail(SKM_EINVAL, "tau_group: only 0 (= k, the threshold frozen for the whole step) is implemented");
   skm_trace *tr = p.trace;
+  HostTimes host;
   const size_t ds0 = (size_t)round_up(d, 16);
   const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, false);
-  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + ((size_t)32 << 20) : 0);
+  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + ((size_t)32 << 20) : 0,
+               p.workspace, p.workspace_bytes);
+  if (ws.too_small) return fail(SKM_ENOMEM, "params->workspace is smaller than skm_workspace_bytes() for this call");
+  host.workspace_ready();
   Ctx c;
   c.st = (hipStream_t)p.stream;
   c.n = n; c.d = d; c.k = k;
@@ -1418,6 +1523,7 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
     tr->rows = 1;
     tr->iters_run = 0;
     tr->ms_total = total;
+    host.body_done(tr);
   }
   return SKM_OK;
 }
@@ -1468,6 +1574,8 @@ int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, 
   pin.rotate = 0;
   pin.R = nullptr;
   pin.final_assign = 0;
+  pin.workspace = nullptr;   // the nested calls allocate their own
+  pin.workspace_bytes = 0;
   skm_trace inner{};
   skm_trace *tr = p.trace;
   if (tr) {
@@ -1481,6 +1589,8 @@ int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, 
   skm_params pfin = p;
   pfin.rotate = 0;
   pfin.R = nullptr;
+  pfin.workspace = nullptr;
+  pfin.workspace_bytes = 0;
   skm_trace last{};
   if (tr) {
     last.capacity = tr->capacity - inner.rows;
@@ -1572,6 +1682,8 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
   pin.rotate = 0;
   pin.R = nullptr;
   pin.trace = nullptr;
+  pin.workspace = nullptr;   // the nested calls allocate their own
+  pin.workspace_bytes = 0;
 
   // ---- MESO
   const int32_t km = hier_meso_count(k);
@@ -1772,6 +1884,20 @@ void skm_params_default(skm_params *p) {
   p->pair_budget = 0;
   p->dense_frac = 0.0125f;
   p->sample_frac = 0.f;
+  p->workspace = nullptr;
+  p->workspace_bytes = 0;
+  p->conv_tol = 0.f;
+  p->tau_group = 0;
+}
+
+int64_t skm_workspace_bytes(int64_t n, int32_t d, int32_t k, const skm_params *params) {
+  if (n < 1 || n >= (int64_t)1 << 31 || d < 16 || d > 16384 || k < 1 || k > n || k > (1 << 24))
+    return fail(SKM_EINVAL, "shape out of range");
+  skm_params p;
+  if (params) p = *params; else skm_params_default(&p);
+  const size_t need = fit_workspace_need(n, d, k, p);
+  if (!need) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
+  return (int64_t)need + 256;   // room to align the caller's pointer
 }
 
 int skm_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, float *centroids_out,
@@ -1958,11 +2084,12 @@ const char *skm_strerror(int rc) {
     case SKM_ENOMEM: return "out of memory";
     case SKM_EHIP: return "HIP runtime error";
     case SKM_EINTERNAL: return "internal error";
+    case SKM_EOVERFLOW: return "hand-over list overflow";
     default: return "unknown error";
   }
 }
 const char *skm_last_error(void) { return g_last_error.c_str(); }
-const char *skm_version(void) { return "skm 0.1 (gfx950)"; }
+const char *skm_version(void) { return "skm 0.2 (gfx950)"; }
 
 #pragma GCC visibility pop
 }  // extern "C"

@@ -475,7 +475,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const unsigned int tot = s_wcnt[fin_m & 1][0] + s_wcnt[fin_m & 1][1] + s_wcnt[fin_m & 1][2] + s_wcnt[fin_m & 1][3];
         unsigned int base = slot0;
         if ((unsigned long long)base + tot > (unsigned long long)g.sub_capacity) {
-          *g.overflow = 1u;
+          atomicOr(g.overflow, 1u);
           base = 0xffffffffu;
         } else {
           base += xcd * g.sub_capacity;

@@ -533,7 +533,7 @@ __global__ void __launch_bounds__(FIN_THREADS) finalize_assign_kernel(const unsi
       if (key == ~0ull) {   // a point no kernel offered a centroid for: reported through `unset`, kept in range
         a = 0;
         dv = 0.f;
-        if (unset) *unset = 1u;
+        if (unset) atomicOr(unset, 2u);   // bit 1: unset point (bit 0 is the hand-over list's overflow)
       }
       assign[i] = a;
       if (dist) dist[i] = dv;

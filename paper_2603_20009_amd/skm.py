@@ -34,7 +34,7 @@ class Trace(C.Structure):
     _fields_ = [
         ("capacity", C.c_int32), ("rows", C.c_int32), ("iters_run", C.c_int32), ("inc_updates", C.c_int32),
         ("ms_rotate", C.c_float), ("ms_init", C.c_float), ("ms_etr_gt", C.c_float), ("ms_unrotate", C.c_float),
-        ("ms_total", C.c_float), ("reserved2", C.c_float),
+        ("ms_total", C.c_float), ("ms_host_total", C.c_float), ("ms_host_alloc", C.c_float), ("ms_host_free", C.c_float),
         ("row", C.POINTER(TraceRow)),
     ]
 
@@ -50,6 +50,7 @@ class Params(C.Structure):
         ("queries", C.c_void_p), ("gt", C.c_void_p),
         ("stream", C.c_void_p), ("trace", C.POINTER(Trace)), ("pair_budget", C.c_int64),
         ("dense_frac", C.c_float), ("sample_frac", C.c_float), ("angular", C.c_int32), ("full_update", C.c_int32),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64), ("conv_tol", C.c_float), ("tau_group", C.c_int32),
     ]
 
 
@@ -57,7 +58,7 @@ EXPORTS = [
     "skm_params_default", "skm_fit", "skm_fit_ex", "skm_assign", "skm_assign_ex", "skm_assign_exact", "skm_update",
     "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_theta_ratio", "skm_dprime_init", "skm_dprime_adjust",
     "skm_strerror", "skm_last_error", "skm_version", "skm_fit_hierarchical", "skm_hier_meso_count", "skm_hier_alloc",
-    "skm_fit_host",
+    "skm_fit_host", "skm_workspace_bytes",
 ]
 
 _lib = None
@@ -87,6 +88,8 @@ def lib():
         L.skm_hier_meso_count.argtypes = [i32]
         L.skm_hier_meso_count.restype = i32
         L.skm_hier_alloc.argtypes = [vp, i32, i32, vp]
+        L.skm_workspace_bytes.argtypes = [i64, i32, i32, C.POINTER(Params)]
+        L.skm_workspace_bytes.restype = i64
         for f in ("skm_fit", "skm_fit_ex", "skm_assign", "skm_assign_ex", "skm_assign_exact", "skm_update",
                   "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_fit_hierarchical", "skm_hier_alloc",
                   "skm_fit_host"):
@@ -155,6 +158,9 @@ class FitOptions:
     sample_frac: float = 0.0
     angular: bool = False
     full_update: bool = False
+    conv_tol: float = 0.0
+    tau_group: int = 0
+    own_workspace: bool = False              # True: the library allocates and frees its workspace inside the call
 
 
 @dataclass
@@ -203,7 +209,29 @@ def _params(o: FitOptions, keep: list, trace: Trace | None) -> Params:
     p.sample_frac = o.sample_frac
     p.angular = int(o.angular)
     p.full_update = int(o.full_update)
+    p.conv_tol = o.conv_tol
+    p.tau_group = o.tau_group
     return p
+
+
+def workspace_bytes(n: int, d: int, k: int, p: Params | None = None) -> int:
+    """skm_workspace_bytes: device bytes a fit / assignment call of this shape needs as workspace."""
+    nbytes = int(lib().skm_workspace_bytes(n, d, k, None if p is None else C.byref(p)))
+    if nbytes < 0:
+        _check(nbytes)
+    return nbytes
+
+
+def _lend_workspace(p: Params, o: FitOptions, n: int, d: int, k: int, device, keep: list):
+    """The workspace as a torch tensor (device memory is torch's business: its caching allocator hands the same block
+    to the next call, so repeated fits allocate nothing).  Skipped for the variants that do not take one."""
+    if o.own_workspace or (0.0 < o.sample_frac < 1.0):
+        return
+    nbytes = workspace_bytes(n, d, k, p)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    keep.append(ws)
+    p.workspace = ws.data_ptr()
+    p.workspace_bytes = nbytes
 
 
 def _new_trace(rows: int, keep: list) -> Trace:
@@ -222,6 +250,7 @@ def fit(X: torch.Tensor, k: int, iters: int, seed: int, opts: FitOptions | None 
     keep: list = []
     tr = _new_trace(iters + 1, keep)
     p = _params(o, keep, tr)
+    _lend_workspace(p, o, n, d, k, X.device, keep)
     cent = torch.empty((k, d), device=X.device, dtype=torch.float32)
     assign = torch.empty(n, device=X.device, dtype=torch.int32)
     dist = torch.empty(n, device=X.device, dtype=torch.float32)
@@ -230,7 +259,8 @@ def fit(X: torch.Tensor, k: int, iters: int, seed: int, opts: FitOptions | None 
     _check(rc)
     rows = [_row_dict(tr.row[i]) for i in range(tr.rows)]
     timing = dict(ms_rotate=tr.ms_rotate, ms_init=tr.ms_init, ms_etr_gt=tr.ms_etr_gt, ms_unrotate=tr.ms_unrotate,
-                  ms_total=tr.ms_total, inc_updates=int(tr.inc_updates))
+                  ms_total=tr.ms_total, inc_updates=int(tr.inc_updates), ms_host_total=tr.ms_host_total,
+                  ms_host_alloc=tr.ms_host_alloc, ms_host_free=tr.ms_host_free)
     return FitResult(cent, assign, dist, int(tr.iters_run), rows, timing)
 
 
@@ -301,6 +331,7 @@ def assign(X: torch.Tensor, centroids: torch.Tensor, prev: torch.Tensor | None =
     keep: list = []
     tr = _new_trace(1, keep)
     p = _params(o, keep, tr)
+    _lend_workspace(p, o, n, d, k, X.device, keep)
     a = torch.empty(n, device=X.device, dtype=torch.int32)
     dist = torch.empty(n, device=X.device, dtype=torch.float32)
     pv = None if prev is None else _dev(prev, torch.int32, "prev")

@@ -35,8 +35,8 @@ def test_every_declared_symbol_is_exported(skm):
 def test_struct_sizes_match_header(skm):
     # sizes implied by include/skm.h on LP64: catches a field added on one side only
     assert C.sizeof(skm.TraceRow) == 3 * 8 + 6 * 8 + 2 * 4 + 32 * 8 + 6 * 4
-    assert C.sizeof(skm.Trace) == 4 * 4 + 6 * 4 + 8
-    assert C.sizeof(skm.Params) == 10 * 4 + 2 * 8 + 6 * 4 + 4 * 8 + 8 + 2 * 4 + 2 * 4
+    assert C.sizeof(skm.Trace) == 4 * 4 + 8 * 4 + 8
+    assert C.sizeof(skm.Params) == 10 * 4 + 2 * 8 + 6 * 4 + 4 * 8 + 8 + 2 * 4 + 2 * 4 + 2 * 8 + 2 * 4
     p = skm.Params()
     skm.lib().skm_params_default(C.byref(p))
     assert (p.dprime_frac, p.adjust_dprime, p.final_assign, p.rotate, p.etr) == (0.125, 1, 1, 1, 0)
@@ -82,3 +82,17 @@ def test_argument_errors_are_codes_not_crashes(skm):
     assert L.skm_sample_rows(1, 5, 6, one) == -1
     assert b"invalid" in L.skm_strerror(-1) and L.skm_last_error() != b""
     assert L.skm_strerror(0) == b"ok"
+
+
+def test_workspace_size_query(skm):
+    L = skm.lib()
+    assert L.skm_workspace_bytes(0, 16, 1, None) == -1 and L.skm_workspace_bytes(10, 8, 2, None) == -1
+    assert L.skm_workspace_bytes(10, 16, 11, None) == -1
+    small = skm.workspace_bytes(1000, 64, 10)
+    big = skm.workspace_bytes(1_000_000, 1536, 1024)
+    # two copies of the rotated points, their split-fp16 copy and the prefix-norm table dominate
+    assert small > 0 and 3 * 1_000_000 * 1536 * 4 < big < 6 * 1_000_000 * 1536 * 4
+    p = skm.Params()
+    L.skm_params_default(C.byref(p))
+    p.etr, p.nq, p.topk = 1, 1000, 10
+    assert skm.workspace_bytes(1_000_000, 1536, 1024, p) > big
