@@ -487,7 +487,8 @@ struct Ctx {
         obj = reinterpret_cast<double *>(zblock + off_obj);
         up.cnt = reinterpret_cast<int32_t *>(zblock + off_cnt);
       }
-      if (int rc = alloc_readback(off_scal - off_flag, off_obj - off_flag, off_cnt - off_flag)) return rc;
+      if (!pool.count_only)   // (a size query touches no device and no page-locked memory)
+        if (int rc = alloc_readback(off_scal - off_flag, off_obj - off_flag, off_cnt - off_flag)) return rc;
     }
     HIPCHK(pool.get(&ratio_dev, (size_t)kMaxBlocks + 1));
     HIPCHK(pool.get(&obj_partial, (size_t)(n + 1023) / 1024));   // at least finalize_blocks(m) for every m <= n
