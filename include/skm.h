@@ -285,6 +285,13 @@ float skm_theta_ratio(int32_t d, int32_t t, float eps0);
 int32_t skm_dprime_init(int32_t d, float frac);
 int32_t skm_dprime_adjust(int32_t d, int32_t dprime, double prune_frac, float lo, float hi, float step);
 
+/* Launch choices of the GEMM kernels, for tests (Algorithm 1's products are the same whatever is chosen; only tile
+ * shape and launch banding change).  Process-wide, takes effect for later calls, not synchronised with running ones.
+ *   tile256    -1 = chosen by shape (default), 0 = never the 256 x 256 tiles, 1 = whenever the operands allow them
+ *   panel_cols 0 = default, > 0 = column tiles per panel of the tile walk
+ *   max_tiles  0 = default, > 0 = tiles per launch (a tall product is cut into bands of row tiles) */
+void skm_debug_gemm_config(int32_t tile256, int32_t panel_cols, int64_t max_tiles);
+
 const char *skm_strerror(int rc);
 const char *skm_last_error(void); /* text of the last failure on this thread */
 const char *skm_version(void);

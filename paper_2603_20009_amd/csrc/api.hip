@@ -2078,6 +2078,10 @@ int32_t skm_dprime_adjust(int32_t d, int32_t dprime, double prune_frac, float lo
   return dprime_adjust(d, dprime, prune_frac, (double)lo, (double)hi, (double)step);
 }
 
+void skm_debug_gemm_config(int32_t tile256, int32_t panel_cols, int64_t max_tiles) {
+  gemm_debug_config(tile256, panel_cols, max_tiles);
+}
+
 const char *skm_strerror(int rc) {
   switch (rc) {
     case SKM_OK: return "ok";

@@ -18,6 +18,7 @@
 #include "skm_internal.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 
@@ -643,13 +644,10 @@ static bool operands_aligned(const GemmOperands &g) {
 template <int BK, int EPI, bool ALIGNED>
 static hipError_t launch_one(const GemmOperands &g, const typename EpiArgs<EPI>::type &e, hipStream_t st) {
   auto kern = gemm_kernel<BK, EPI, ALIGNED>;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)smem_bytes<BK>());
-    if (rc != hipSuccess) return rc;
-    attr_set = true;
-  }
+  // once per instantiation; the initialisation of a function-local static is synchronised between threads
+  static const hipError_t attr_rc = hipFuncSetAttribute(
+      reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BK>());
+  if (attr_rc != hipSuccess) return attr_rc;
   const int64_t nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
   const int64_t nwg = nrt * nct;
   if (nwg <= 0) return hipSuccess;
@@ -661,13 +659,9 @@ static hipError_t launch_one(const GemmOperands &g, const typename EpiArgs<EPI>:
 template <int EPI>
 static hipError_t launch_split(const GemmOperands &g, const typename EpiArgs<EPI>::type &e, hipStream_t st) {
   auto kern = gemm_split_kernel<EPI>;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)smem_bytes<SBK>());
-    if (rc != hipSuccess) return rc;
-    attr_set = true;
-  }
+  static const hipError_t attr_rc = hipFuncSetAttribute(
+      reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<SBK>());
+  if (attr_rc != hipSuccess) return attr_rc;
   const int64_t nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
   const int64_t nwg = nrt * nct;
   if (nwg <= 0) return hipSuccess;
@@ -677,12 +671,18 @@ static hipError_t launch_split(const GemmOperands &g, const typename EpiArgs<EPI
 }
 
 
+// Launch choices a test can force (gemm_debug_config): nothing here changes what is computed.
+static std::atomic<int> g_tile256{-1}, g_panel_cols{0};
+static std::atomic<int64_t> g_max_tiles{0};
+void gemm_debug_config(int tile256, int panel_cols, int64_t max_tiles) {
+  g_tile256.store(tile256 < 0 ? -1 : (tile256 ? 1 : 0));
+  g_panel_cols.store(panel_cols > 0 ? panel_cols : 0);
+  g_max_tiles.store(max_tiles > 0 ? max_tiles : 0);
+}
+
 // The 256 x 256 form pays when the tall operand fills the device several times over and B can be split ahead.
 static bool wants_split256(const GemmOperands &g) {
-  static const int forced = []() {
-    const char *e = std::getenv("SKM_TEST_GEMM256");   // 0: never, 1: whenever the operands allow it
-    return e ? std::atoi(e) : -1;
-  }();
+  const int forced = g_tile256.load(std::memory_order_relaxed);   // -1: by shape, 0: never, 1: whenever the operands allow it
   if (!g.b_split || !g.a_absmax || !g.b_absmax || g.K % 32 != 0 || g.K < 64 || forced == 0) return false;
   if (!aligned16(g.A) || !aligned16(g.B) || !aligned16(g.b_split) || g.lda % 4 != 0 || g.ldb % 4 != 0) return false;
   const int64_t tiles = (int64_t)((g.M + T2 - 1) / T2) * ((g.N + T2 - 1) / T2);
@@ -695,12 +695,9 @@ template <int EPI>
 static hipError_t launch_split256(const GemmOperands &g, const typename EpiArgs<EPI>::type &e, hipStream_t st) {
   auto kern = gemm_split256_kernel<EPI>;
   constexpr size_t smem = (size_t)2 * T2_STAGE * sizeof(uint32_t);
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (rc != hipSuccess) return rc;
-    attr_set = true;
-  }
+  static const hipError_t attr_rc =
+      hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr_rc != hipSuccess) return attr_rc;
   const int64_t nwg = (int64_t)((g.M + T2 - 1) / T2) * ((g.N + T2 - 1) / T2);
   if (nwg <= 0) return hipSuccess;
   if (nwg > (1 << 22) - 1) return hipErrorInvalidValue;
@@ -716,12 +713,9 @@ constexpr int64_t kMaxTilesPerLaunch = (1 << 24) - 1;
 // 1M x 1536 workload): the width moves the run time by less than the noise, but the bytes fetched from beyond L2
 // drop by a quarter at 4 (the four centroid tiles of a panel then stay in one XCD's L2 while the point tiles
 // stream past; every point tile is read once per panel).  With many column tiles the point tiles would be re-read
-// too often, so wide problems keep 16.  SKM_TEST_PANEL_COLS overrides the width for experiments.
+// too often, so wide problems keep 16.  gemm_debug_config overrides the width for experiments.
 static int panel_cols_for(int64_t nct) {
-  static const int forced = []() {
-    const char *e = std::getenv("SKM_TEST_PANEL_COLS");
-    return e ? std::atoi(e) : 0;
-  }();
+  const int forced = g_panel_cols.load(std::memory_order_relaxed);
   return forced > 0 ? forced : (nct <= 16 ? 4 : 16);
 }
 
@@ -741,12 +735,9 @@ static hipError_t launch_any(const GemmOperands &g, const typename EpiArgs<EPI>:
     hipError_t rc = launch_split_rows(g.B, g.ldb, g.N, g.K, g.b_absmax, g.b_split, st);
     if (rc != hipSuccess) return rc;
   }
-  // SKM_TEST_MAX_TILES lowers the limit so that the banding can be exercised on small inputs
-  static const int64_t max_tiles = []() {
-    const char *e = std::getenv("SKM_TEST_MAX_TILES");
-    const int64_t v = e ? std::atoll(e) : 0;
-    return (v > 0 && v < kMaxTilesPerLaunch) ? v : kMaxTilesPerLaunch;
-  }();
+  // gemm_debug_config lowers the limit so that the banding can be exercised on small inputs
+  const int64_t forced_tiles = g_max_tiles.load(std::memory_order_relaxed);
+  const int64_t max_tiles = (forced_tiles > 0 && forced_tiles < kMaxTilesPerLaunch) ? forced_tiles : kMaxTilesPerLaunch;
   const int64_t band_rows = std::max<int64_t>((big ? std::min<int64_t>(max_tiles, (1 << 22) - 1) : max_tiles) / nct, 1) * edge;
   for (int64_t r0 = 0; r0 < g.M; r0 += band_rows) {
     GemmOperands gb = g;

@@ -540,16 +540,23 @@ hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
       g.N > (1 << 24))
     return hipErrorInvalidValue;
   constexpr size_t smem = (size_t)2 * STAGE_WORDS * sizeof(uint32_t);
-  static int wgs = 0;
-  if (!wgs) {
-    hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (rc != hipSuccess) return rc;
-    int dev = 0, cus = 256;
-    (void)hipGetDevice(&dev);
-    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    wgs = 2 * cus;   // two workgroups per CU (LDS and registers allow no more)
-  }
+  // once per process (the initialisation of a function-local static is synchronised between threads): the kernel's LDS
+  // size, and two workgroups per CU (LDS and registers allow no more)
+  struct Setup {
+    hipError_t rc;
+    int wgs = 0;
+    Setup() {
+      rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      int dev = 0, cus = 256;
+      (void)hipGetDevice(&dev);
+      (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+      wgs = 2 * cus;
+    }
+  };
+  static const Setup setup;
+  if (setup.rc != hipSuccess) return setup.rc;
+  const int wgs = setup.wgs;
   const int64_t ntiles = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (ntiles > 0x7fffffffLL) return hipErrorInvalidValue;
   const int64_t grid = std::max<int64_t>(8, std::min<int64_t>(wgs, (ntiles + 7) / 8 * 8));

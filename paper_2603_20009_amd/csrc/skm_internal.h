@@ -84,6 +84,11 @@ hipError_t gemm_store(const GemmOperands &g, float *C, int64_t ldc, int32_t Nsto
 // distance up to the per-row constant ||x_i||^2 (Algorithm 1, iteration 1).
 hipError_t gemm_argmin(const GemmOperands &g, const float *ynorm, unsigned long long *best, hipStream_t st);
 
+// Launch choices of the GEMM family that tests force (process-wide; nothing here changes what is computed):
+// tile256 -1 = by shape, 0 = never the 256 x 256 form, 1 = whenever the operands allow it; panel_cols > 0 = width of
+// the tile walk's panels; max_tiles > 0 = tiles per launch (tall problems are cut into bands of row tiles).
+void gemm_debug_config(int tile256, int panel_cols, int64_t max_tiles);
+
 // Device scalars of one assignment step.  Every workgroup adds to the replica (blockIdx & (kStatReplicas-1))
 // so that same-address atomics do not serialise; the host sums the replicas.
 enum { SC_COMPLETED = 0, SC_CHANGED = 1, SC_SURVIVORS = 2, SC_DENSE_DIMS = 3, SC_DENSE_PB = 4, SC_ENTER = 5,

@@ -17,12 +17,12 @@ __device__ inline double wave_sum(double v) {
 }
 
 static int num_cus() {
-  static int cus = 0;
-  if (!cus) {
-    int dev = 0;
+  static const int cus = []() {   // (initialised once, synchronised between threads)
+    int dev = 0, v = 0;
     (void)hipGetDevice(&dev);
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-  }
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    return v;
+  }();
   return cus;
 }
 

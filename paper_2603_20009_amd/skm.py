@@ -58,7 +58,7 @@ EXPORTS = [
     "skm_params_default", "skm_fit", "skm_fit_ex", "skm_assign", "skm_assign_ex", "skm_assign_exact", "skm_update",
     "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_theta_ratio", "skm_dprime_init", "skm_dprime_adjust",
     "skm_strerror", "skm_last_error", "skm_version", "skm_fit_hierarchical", "skm_hier_meso_count", "skm_hier_alloc",
-    "skm_fit_host", "skm_workspace_bytes",
+    "skm_fit_host", "skm_workspace_bytes", "skm_debug_gemm_config",
 ]
 
 _lib = None
@@ -90,6 +90,8 @@ def lib():
         L.skm_hier_alloc.argtypes = [vp, i32, i32, vp]
         L.skm_workspace_bytes.argtypes = [i64, i32, i32, C.POINTER(Params)]
         L.skm_workspace_bytes.restype = i64
+        L.skm_debug_gemm_config.argtypes = [i32, i32, i64]
+        L.skm_debug_gemm_config.restype = None
         for f in ("skm_fit", "skm_fit_ex", "skm_assign", "skm_assign_ex", "skm_assign_exact", "skm_update",
                   "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_fit_hierarchical", "skm_hier_alloc",
                   "skm_fit_host"):
@@ -416,6 +418,11 @@ def dprime_init(d: int, frac: float = 0.125) -> int:
 
 def dprime_adjust(d: int, dprime: int, f: float, lo=0.95, hi=0.97, step=0.20) -> int:
     return int(lib().skm_dprime_adjust(d, dprime, f, lo, hi, step))
+
+
+def debug_gemm_config(tile256: int = -1, panel_cols: int = 0, max_tiles: int = 0):
+    """skm_debug_gemm_config: force launch choices of the GEMM kernels (tests); no arguments = defaults."""
+    lib().skm_debug_gemm_config(tile256, panel_cols, max_tiles)
 
 
 def version() -> str:

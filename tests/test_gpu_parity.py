@@ -485,72 +485,51 @@ def test_c4_full_size_sampled_parity(skm, orc, dg):
     torch.cuda.empty_cache()
 
 
-def test_tall_problems_are_cut_into_bands_of_row_tiles(orc, dg):
-    """A launch holds at most 2^24 - 1 tiles; the limit is lowered through the environment in a child
-    process so that the banding of the GEMM launches runs on a small input."""
-    import subprocess
-    import sys
-    import os
-    code = r'''
-import sys, numpy as np, torch
-sys.path.insert(0, %r)
-from paper_2603_20009_amd import skm, datagen
-from oracle import oracle as orc
-X = datagen.mixture(3000, 64, 20, 2, "linear").numpy()
-Y = X[:300].copy()
-a, dist = skm.assign_exact(torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda())
-ao, do = orc.assign_full(X.astype(np.float64), Y.astype(np.float64))
-assert (a.cpu().numpy() == ao).mean() > 0.999, (a.cpu().numpy() == ao).mean()
-R = orc.random_rotation(64, 1)
-out = skm.rotate(torch.from_numpy(X).cuda(), torch.from_numpy(R).cuda()).cpu().numpy()
-assert np.abs(out - orc.rotate(X, R)).max() < 2e-6
-print("banded ok")
-''' % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    env = dict(os.environ, SKM_TEST_MAX_TILES="7")   # 3 column tiles -> bands of 2 row tiles
-    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=240)
-    assert r.returncode == 0 and "banded ok" in r.stdout, r.stderr[-2000:]
-
-
-@pytest.mark.parametrize("max_tiles", [None, "5"])
-def test_wide_tile_gemm_on_small_ragged_inputs(max_tiles):
-    """Tall products run on 256 x 256 tiles with the second operand split ahead.  The form is forced through the
-    environment in a child process, so that ragged row and column tiles, several slabs and (with the tile limit
-    lowered) the banding run on inputs the oracle finishes in seconds: exact assignment, rotation, a whole fit."""
-    import subprocess
-    import sys
-    import os
-    code = r'''
-import sys, numpy as np, torch
-sys.path.insert(0, %r)
-from paper_2603_20009_amd import skm, datagen
-from oracle import oracle as orc
-for (n, d, k) in ((3000, 64, 300), (1001, 96, 257), (700, 160, 5)):
-    X = datagen.mixture(n, d, 20, 2, "linear").numpy()
-    Y = X[:k].copy() + np.float32(0.01)
-    a, dist = skm.assign_exact(torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda())
+def test_tall_problems_are_cut_into_bands_of_row_tiles(skm, orc, dg):
+    """A launch holds at most 2^24 - 1 tiles; with the limit lowered (skm_debug_gemm_config) the banding of the GEMM
+    launches runs on a small input."""
+    X = dg.mixture(3000, 64, 20, 2, "linear").numpy()
+    Y = X[:300].copy()
+    R = orc.random_rotation(64, 1)
+    skm.debug_gemm_config(max_tiles=7)   # 3 column tiles -> bands of 2 row tiles
+    try:
+        a, dist = skm.assign_exact(cuda(X), cuda(Y))
+        out = skm.rotate(cuda(X), cuda(R)).cpu().numpy()
+    finally:
+        skm.debug_gemm_config()
     ao, do = orc.assign_full(X.astype(np.float64), Y.astype(np.float64))
-    same = a.cpu().numpy() == ao
-    assert same.mean() > 0.999, (n, d, k, same.mean())
-    assert np.abs(dist.cpu().numpy()[same] - do[same]).max() < 1e-5 * max(1.0, do.max())
-    R = orc.random_rotation(d, 1)
-    out = skm.rotate(torch.from_numpy(X).cuda(), torch.from_numpy(R).cuda()).cpu().numpy()
-    assert np.abs(out - orc.rotate(X, R)).max() < 2e-6 * max(1.0, np.abs(X).max())
-X = datagen.mixture(4000, 128, 40, 11, "linear")   # a ragged last row tile
-R = orc.random_rotation(128, 7)
-idx = orc.sample_rows(7, 4000, 32)
-eps0 = float(np.float32(2.1))
-ref = orc.fit(X.numpy(), 32, 4, 7, orc.FitParams(eps0=eps0, adjust_dprime=False), R=R, init_idx=idx)
-got = skm.fit(X.cuda(), 32, 4, 7, skm.FitOptions(R=torch.from_numpy(R).cuda(), adjust_dprime=False))
-assert (got.assign.cpu().numpy() == ref.assign).mean() >= 0.999
-assert np.linalg.norm(got.centroids.cpu().numpy() - ref.centroids) / np.linalg.norm(ref.centroids) < 1e-3
-assert abs(got.trace[-1]["objective"] - ref.trace[-1]["objective"]) / ref.trace[-1]["objective"] < 1e-4
-print("wide tiles ok")
-''' % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    env = dict(os.environ, SKM_TEST_GEMM256="1")
-    if max_tiles:
-        env["SKM_TEST_MAX_TILES"] = max_tiles
-    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
-    assert r.returncode == 0 and "wide tiles ok" in r.stdout, r.stderr[-2000:]
+    assert (a.cpu().numpy() == ao).mean() > 0.999
+    assert np.abs(out - orc.rotate(X, R)).max() < 2e-6
+
+
+@pytest.mark.parametrize("max_tiles", [0, 5])
+def test_wide_tile_gemm_on_small_ragged_inputs(skm, orc, dg, max_tiles):
+    """Tall products run on 256 x 256 tiles with the second operand split ahead.  The form is forced
+    (skm_debug_gemm_config), so that ragged row and column tiles, several slabs and (with the tile limit lowered) the
+    banding run on inputs the oracle finishes in seconds: exact assignment, rotation, a whole fit."""
+    skm.debug_gemm_config(tile256=1, max_tiles=max_tiles)
+    try:
+        for (n, d, k) in ((3000, 64, 300), (1001, 96, 257), (700, 160, 5)):
+            X = dg.mixture(n, d, 20, 2, "linear").numpy()
+            Y = X[:k].copy() + np.float32(0.01)
+            a, dist = skm.assign_exact(cuda(X), cuda(Y))
+            ao, do = orc.assign_full(X.astype(np.float64), Y.astype(np.float64))
+            same = a.cpu().numpy() == ao
+            assert same.mean() > 0.999, (n, d, k, same.mean())
+            assert np.abs(dist.cpu().numpy()[same] - do[same]).max() < 1e-5 * max(1.0, do.max())
+            R = orc.random_rotation(d, 1)
+            out = skm.rotate(cuda(X), cuda(R)).cpu().numpy()
+            assert np.abs(out - orc.rotate(X, R)).max() < 2e-6 * max(1.0, np.abs(X).max())
+        X = dg.mixture(4000, 128, 40, 11, "linear").numpy()   # a ragged last row tile
+        R = orc.random_rotation(128, 7)
+        idx = orc.sample_rows(7, 4000, 32)
+        ref = orc.fit(X, 32, 4, 7, orc.FitParams(eps0=EPS0, adjust_dprime=False), R=R, init_idx=idx)
+        got = skm.fit(cuda(X), 32, 4, 7, skm.FitOptions(R=cuda(R), adjust_dprime=False))
+    finally:
+        skm.debug_gemm_config()
+    assert (got.assign.cpu().numpy() == ref.assign).mean() >= 0.999
+    assert rel_l2(got.centroids.cpu().numpy(), ref.centroids) < 1e-3
+    assert got.trace[-1]["objective"] == pytest.approx(ref.trace[-1]["objective"], rel=1e-4)
 
 
 # ------------------------------------------------------------------ edge and degenerate cases
