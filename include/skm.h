@@ -259,6 +259,17 @@ int skm_assign_ex(const float *X, int64_t n, int32_t d, const float *centroids, 
 int skm_assign_exact(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k,
                      void *stream, int32_t *assign_out, float *dist_out);
 
+/* skm_assign_exact for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same kernels, the same results, but the call's working memory (packed
+ * minima, centroid norms, operand bounds, the split-fp16 copy of the centroids) is a fixed 16 MiB array in device
+ * memory that every GPU the library runs on holds until the process ends.  No hipMalloc, hipFree or allocating
+ * library routine is called.  Limits (SKM_EINVAL beyond them): 1 <= n <= 1 048 576, 1 <= k <= min(n, 16 384), d a
+ * multiple of 16 in [16, 16384], X and centroids 16-byte aligned.  All calls on one GPU share that array: calls
+ * that overlap on one GPU (other threads, other streams) race; calls one after the other do not, whatever their
+ * sizes.  The call returns after `stream` has been synchronised. */
+int skm_assign_exact_static(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, void *stream,
+                            int32_t *assign_out, float *dist_out);
+
 /* Centroid update (Section 3.2): per-cluster mean of the assigned rows; empty
  * clusters keep the row already in `centroids`.  counts_out: device k int32. */
 int skm_update(const float *X, int64_t n, int32_t d, const int32_t *assign, int32_t k,

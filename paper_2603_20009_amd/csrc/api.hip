@@ -1859,6 +1859,11 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
 
 }  // namespace
 
+namespace skm {
+int report_error(int rc, const char *what) { return fail(rc, what); }
+int report_hip_error(hipError_t e, const char *where) { return fail_hip(e, where); }
+}  // namespace skm
+
 // ==================================================================== C ABI
 extern "C" {
 #pragma GCC visibility push(default)

@@ -20,6 +20,11 @@ struct __attribute__((aligned(16))) Pair {
   float tau;   // the point's pruning threshold for this step
 };
 
+// Error reporting shared by the translation units that hold entry points: records the text skm_last_error() returns
+// on this thread and gives back the code (SKM_ENOMEM for an out-of-memory HIP error, SKM_EHIP for any other).
+int report_error(int rc, const char *what);
+int report_hip_error(hipError_t e, const char *where);
+
 // ---- order-preserving float <-> uint32 map (for packed 64-bit atomic min) ----
 __host__ __device__ inline uint32_t f2ord(float f) {
   uint32_t u = __builtin_bit_cast(uint32_t, f);

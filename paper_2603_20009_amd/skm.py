@@ -59,6 +59,7 @@ EXPORTS = [
     "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_theta_ratio", "skm_dprime_init", "skm_dprime_adjust",
     "skm_strerror", "skm_last_error", "skm_version", "skm_fit_hierarchical", "skm_hier_meso_count", "skm_hier_alloc",
     "skm_fit_host", "skm_workspace_bytes", "skm_debug_gemm_config",
+    "skm_assign_exact_static",
 ]
 
 _lib = None
@@ -79,6 +80,8 @@ def lib():
         L.skm_assign.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp]
         L.skm_assign_ex.argtypes = [vp, i64, i32, vp, i32, vp, i32, C.POINTER(Params), vp, vp]
         L.skm_assign_exact.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp]
+        L.skm_assign_exact_static.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp]
+        L.skm_assign_exact_static.restype = C.c_int
         L.skm_update.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp]
         L.skm_make_rotation.argtypes = [i32, u64, vp, vp]
         L.skm_rotate.argtypes = [vp, i64, i32, vp, i32, vp, vp]
@@ -363,6 +366,17 @@ def assign_exact(X: torch.Tensor, centroids: torch.Tensor):
     dist = torch.empty(n, device=X.device, dtype=torch.float32)
     _check(lib().skm_assign_exact(_dev(X, torch.float32, "X"), n, d, _dev(centroids, torch.float32, "centroids"), k,
                                   _stream(), C.c_void_p(a.data_ptr()), C.c_void_p(dist.data_ptr())))
+    return a, dist
+
+
+def assign_exact_static(X: torch.Tensor, centroids: torch.Tensor, out=None):
+    """skm_assign_exact_static: the exact step with no device allocation inside the call (outputs are the caller's)."""
+    n, d = X.shape
+    k = centroids.shape[0]
+    a, dist = out if out is not None else (torch.empty(n, device=X.device, dtype=torch.int32),
+                                           torch.empty(n, device=X.device, dtype=torch.float32))
+    _check(lib().skm_assign_exact_static(_dev(X, torch.float32, "X"), n, d, _dev(centroids, torch.float32, "centroids"),
+                                         k, _stream(), C.c_void_p(a.data_ptr()), C.c_void_p(dist.data_ptr())))
     return a, dist
 
 
