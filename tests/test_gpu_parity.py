@@ -250,7 +250,7 @@ def test_fit_c1_full_parity(skm, orc, dg):
     obj = [g["objective"] for g in got.trace]
     assert all(b <= a * (1 + 1e-6) for a, b in zip(obj, obj[1:]))          # Lloyd objective never increases
     same = (got.assign.cpu().numpy() == ref.assign) & np.isin(ref.assign, clean)   # clusters with the same members
-    assert same.mean() > 0.9
+    assert same.mean() > 0.97
     assert np.abs(got.dist.cpu().numpy()[same] - ref.dist[same]).max() < 1e-5
 
 
@@ -337,7 +337,7 @@ def test_fit_regroups_points_across_row_chunks(skm, orc, dg):
         assert [g["dprime"] for g in got.trace] == [r["dprime"] for r in ref.trace]
         assert got.trace[-1]["objective"] == pytest.approx(ref.trace[-1]["objective"], rel=1e-4)
         same = (a == ref.assign) & np.isin(ref.assign, clean)
-        assert same.mean() > 0.9
+        assert same.mean() > 0.97
         assert np.abs(got.dist.cpu().numpy()[same] - ref.dist[same]).max() < 1e-5      # distances sit with their points
         assert float(got.dist.sum()) == pytest.approx(got.trace[-1]["objective"], rel=1e-5)
         fits.append(a)
@@ -738,7 +738,7 @@ def test_host_resident_fit(skm, orc, dg, n, d, k, batch, pinned):
                      own=(X, dev.centroids.cpu().numpy()))
     clean = check_centroids(got.centroids.cpu().numpy(), dev.centroids.cpu().numpy(), a, dev.assign.cpu().numpy())
     same = (dev.assign.cpu().numpy() == a) & np.isin(a, clean)          # clusters with the same members in both fits
-    assert same.mean() > 0.9
+    assert same.mean() > 0.97
     assert np.abs(got.dist.numpy()[same] - dev.dist.cpu().numpy()[same]).max() < 1e-5
 
 
@@ -770,3 +770,107 @@ def test_host_resident_fit_options(skm, orc, dg):
     assert np.abs(got.centroids.cpu().numpy() - S / np.bincount(a, minlength=12)[:, None]).max() < 1e-6
     with pytest.raises(RuntimeError):
         skm.fit_host(torch.from_numpy(X), 12, 5, 1, opts=skm.FitOptions(angular=True))
+
+
+# ------------------------------------------------------------------ whole fit in lock step: the strict contract
+def _witness(orc, Xr, Yr, i, j, tau, d, dprime):
+    """True if centroid j's partial distance to point i comes within fp32 rounding of the pruning threshold at some
+    checkpoint (then the statistical test may fall either way in fp32 and in fp64)."""
+    diff2 = (Xr[i] - Yr[j]) ** 2
+    t = dprime
+    while t < d:
+        p = diff2[:t].sum()
+        thr = orc.theta_ratio(d, t, EPS0) * tau
+        if abs(p - thr) <= 2e-5 * max(thr, 1e-30):
+            return True
+        t = min(d, t + 64)
+    return abs(diff2.sum() - tau) <= 2e-5 * max(tau, 1e-30)
+
+
+def lockstep_fit(skm, orc, X, R, k, iters, seed, adjust):
+    """Algorithm 1 driven by the oracle; at every iteration the library's step calls (skm_assign_exact /
+    skm_assign_ex, skm_update) get the oracle's state (centroids Y_t and labels a_t, rounded to fp32 once and used by
+    both sides) and must meet the contract with no relaxation: >= 99.9 % of the labels equal, every other one a
+    near-tie of <= 1e-4 (or a pair whose partial distance sits on the pruning threshold to fp32 rounding, counted and
+    bounded), centroids of ALL clusters within 1e-3 relative L2, objective within 1e-4, survivor counters within
+    0.1 %, the same d' decision."""
+    n, d = X.shape
+    Xr = orc.rotate(X, R).astype(np.float32)          # the rotated points both sides work on
+    Xr64 = Xr.astype(np.float64)
+    Xg = cuda(Xr)
+    plain = dict(rotate=False, eps0=EPS0, block_stats=True)
+    Y = Xr[orc.sample_rows(seed, n, k)].copy()         # fp32 centroids, the state handed from step to step
+    rng_state = orc.rng_stream(seed, 1)
+    dp = orc.dprime_init(d)
+    prev = None
+    on_threshold = 0
+    for t in range(1, iters + 2):                       # iterations 1..iters, then the final assignment pass
+        Y64 = Y.astype(np.float64)
+        if t == 1:
+            a_ref, d_ref = orc.assign_full(Xr64, Y64)
+            a, dist = skm.assign_exact(Xg, cuda(Y))
+            row = None
+        else:
+            ref = orc.assign_pruned(Xr64, Y64, prev, dp, EPS0, 0)
+            a_ref, d_ref = ref.assign, ref.dist
+            a, dist, row = skm.assign(Xg, cuda(Y), cuda(prev), dp, skm.FitOptions(**plain))
+        a = a.cpu().numpy()
+        diff = np.nonzero(a != a_ref)[0]
+        assert len(diff) <= 1e-3 * n, (t, len(diff))
+        far = 0
+        for i in diff:
+            dg = ((Xr64[i] - Y64[a[i]]) ** 2).sum()
+            dr = ((Xr64[i] - Y64[a_ref[i]]) ** 2).sum()
+            if abs(dg - dr) <= 1e-4 * min(dg, dr):
+                continue
+            # not a near-tie: only possible in a pruned step, when the statistical test of the better centroid sat on
+            # its threshold (the side that pruned it keeps a farther centroid)
+            assert t > 1, (t, i, dg, dr)
+            tau = ((Xr64[i] - Y64[prev[i]]) ** 2).sum()
+            loser = a_ref[i] if dr < dg else a[i]
+            assert _witness(orc, Xr64, Y64, i, loser, tau, d, dp), (t, i, dg, dr)
+            far += 1
+        on_threshold += far
+        say(f"lockstep t={t} d'={dp if t > 1 else d} disagreements {len(diff)} (on a threshold: {far})")
+        same = a == a_ref
+        assert np.abs(dist.cpu().numpy()[same] - d_ref[same]).max() < 2e-5 * max(1.0, d_ref.max())
+        if row is not None:
+            assert row["objective"] == pytest.approx(d_ref.sum(), rel=1e-4)
+            surv_ref = n * (k - 1) - ref.pruned_first
+            assert abs(row["survivors"] - surv_ref) <= max(2, 1e-3 * surv_ref)
+            for m in range(min(row["nblocks"], 32)):
+                assert abs(row["enter"][m] - ref.enter[m]) <= max(2, 1e-3 * ref.enter[m])
+            assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])
+        if t == iters + 1:
+            break
+        # update on the oracle's labels, both sides; every cluster is compared
+        Yn, cnt = orc.update(Xr64, a_ref, Y64)
+        Yg = cuda(Y)
+        cg = skm.update(Xg, cuda(a_ref), Yg).cpu().numpy()
+        assert (cg == cnt).all()
+        assert rel_l2(Yg.cpu().numpy(), Yn) < 1e-6 and np.abs(Yg.cpu().numpy() - Yn).max() < 1e-6
+        if (cnt == 0).any():
+            Yn, cnt, _, rng_state = orc.split_empty(Yn, cnt, rng_state)
+        if t > 1 and adjust:
+            f_ref = ref.pruned_first / (n * (k - 1))
+            new_dp = orc.dprime_adjust(d, dp, f_ref)
+            assert skm.dprime_adjust(d, dp, row["prune_frac"]) == new_dp
+            dp = new_dp
+        Y = Yn.astype(np.float32)
+        prev = a_ref.astype(np.int32)
+    return on_threshold
+
+
+def test_lockstep_fit_c1(skm, orc, dg):
+    """Workload C1, all 10 iterations and the final pass, the strict contract at every step."""
+    X = dg.config_data("C1").numpy()
+    on_thr = lockstep_fit(skm, orc, X, orc.random_rotation(128, 42), 100, 10, 42, adjust=True)
+    assert on_thr <= 2
+
+
+def test_lockstep_fit_scaled_c2(skm, orc, dg):
+    """The first 131 072 rows of workload C2 (d = 1536, k = 1024), all 10 iterations and the final pass."""
+    torch.cuda.empty_cache()
+    X = dg.config_data("C2", device="cuda", n=131_072).cpu().numpy()
+    on_thr = lockstep_fit(skm, orc, X, orc.random_rotation(1536, 42), 1024, 10, 42, adjust=True)
+    assert on_thr <= 4
