@@ -20,7 +20,8 @@
  *     exception crosses this boundary.
  *   - Thread-compatible, not thread-safe: concurrent calls must use distinct
  *     streams and distinct buffers.
- *   - Limits: 16 <= d <= 16384, 1 <= k <= min(n, 2^24), n < 2^31.
+ *   - Limits: 16 <= d <= 16384, 1 <= k <= 2^24, n < 2^31; a fit needs k <= n
+ *     (an assignment step may have more centroids than points).
  */
 #ifndef SKM_H_
 #define SKM_H_
@@ -263,7 +264,7 @@ int skm_assign_exact(const float *X, int64_t n, int32_t d, const float *centroid
  * loops, harnesses that forbid hipMalloc): the same kernels, the same results, but the call's working memory (packed
  * minima, centroid norms, operand bounds, the split-fp16 copy of the centroids) is a fixed 16 MiB array in device
  * memory that every GPU the library runs on holds until the process ends.  No hipMalloc, hipFree or allocating
- * library routine is called.  Limits (SKM_EINVAL beyond them): 1 <= n <= 1 048 576, 1 <= k <= min(n, 16 384), d a
+ * library routine is called.  Limits (SKM_EINVAL beyond them): 1 <= n <= 1 048 576, 1 <= k <= 16 384, d a
  * multiple of 16 in [16, 16384], X and centroids 16-byte aligned.  All calls on one GPU share that array: calls
  * that overlap on one GPU (other threads, other streams) race; calls one after the other do not, whatever their
  * sizes.  The call returns after `stream` has been synchronised. */
@@ -274,6 +275,13 @@ int skm_assign_exact_static(const float *X, int64_t n, int32_t d, const float *c
  * clusters keep the row already in `centroids`.  counts_out: device k int32. */
 int skm_update(const float *X, int64_t n, int32_t d, const int32_t *assign, int32_t k,
                void *stream, float *centroids, int32_t *counts_out);
+
+/* Ground truth of Early Termination by Recall (Section 3.3): for every query (device nq x d, original space) the
+ * indices of its topk nearest points of X by L2, nearest first, lowest index on equal distances; -1 where fewer than
+ * topk points exist.  gt_out: device nq x topk int64.  This is what skm_fit_ex computes when params->etr is set and
+ * params->gt is NULL; 1 <= topk <= 256. */
+int skm_etr_ground_truth(const float *X, int64_t n, int32_t d, const float *queries, int32_t nq, int32_t topk,
+                         void *stream, int64_t *gt_out);
 
 /* Random orthogonal d x d matrix (Algorithm 1, first line) written to device
  * memory R_out; Haar-distributed (Gram-Schmidt, in fp64 on the device, of a seeded Gaussian

@@ -324,11 +324,12 @@ int measure_absmax(const float *A, int64_t lda, int64_t rows, int32_t cols, unsi
 }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int check_shape(const void *X, int64_t n, int32_t d, int32_t k) {
+// fit = false: an assignment of n points to k given centroids, where k may exceed n
+int check_shape(const void *X, int64_t n, int32_t d, int32_t k, bool fit = true) {
   if (!X) return fail(SKM_EINVAL, "null input pointer");
   if (n < 1 || n >= (int64_t)1 << 31) return fail(SKM_EINVAL, "n out of range [1, 2^31)");
   if (d < 16 || d > 16384) return fail(SKM_EINVAL, "d out of range [16, 16384]");
-  if (k < 1 || k > n || k > (1 << 24)) return fail(SKM_EINVAL, "k out of range [1, min(n, 2^24)]");
+  if (k < 1 || (fit && k > n) || k > (1 << 24)) return fail(SKM_EINVAL, "k out of range [1, min(n, 2^24)]");
   return SKM_OK;
 }
 
@@ -906,6 +907,30 @@ int unrotate_into(const float *Yr, int64_t ldy, int32_t rows, int32_t d, int32_t
   return SKM_OK;
 }
 
+// Ground truth of ETR (Section 3.3): the K nearest points of every query by L2 over X (original space, lowest index
+// on ties) as packed (distance, index) keys, ascending.  The scores q . x come from the GEMM in chunks of 65 536
+// points; each chunk is merged into the running lists.  amax_x / amax_q: one word each for the operand bounds.
+constexpr int64_t kGtChunk = 1 << 16;
+int ground_truth_keys(Pool &pool, const float *X, int64_t n, int32_t d, const float *Q, int32_t nq, int32_t K,
+                      unsigned int *amax_x, unsigned int *amax_q, unsigned long long *gt_keys, hipStream_t st) {
+  float *xnorm = nullptr, *S = nullptr;
+  const int64_t colchunk = std::min<int64_t>(n, kGtChunk);
+  HIPCHK(pool.get(&xnorm, (size_t)n));
+  HIPCHK(pool.get(&S, (size_t)nq * colchunk));
+  HIPCHK(launch_row_norms(X, d, n, d, xnorm, st));
+  HIPCHK(launch_fill_u64(gt_keys, (int64_t)nq * K, ~0ull, st));
+  if (int rc = measure_absmax(X, d, n, d, amax_x, st)) return rc;
+  if (int rc = measure_absmax(Q, d, nq, d, amax_q, st)) return rc;
+  for (int64_t c0 = 0; c0 < n; c0 += colchunk) {
+    const int64_t m = std::min<int64_t>(colchunk, n - c0);
+    GemmOperands g{Q, d, nq, X + c0 * d, d, (int32_t)m, d};
+    g.a_absmax = amax_q; g.b_absmax = amax_x;
+    HIPCHK(gemm_store(g, S, colchunk, (int32_t)m, 1.f, 0.f, st));
+    HIPCHK(launch_topk_merge(S, colchunk, nq, (int32_t)m, c0, xnorm, K, gt_keys, st));
+  }
+  return SKM_OK;
+}
+
 int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, const int32_t *prev_assign,
                 int32_t dprime_in, const skm_params *pp, int32_t *assign_out, float *dist_out);
 int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params &p,
@@ -1071,24 +1096,8 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
     if (p.gt) {
       HIPCHK(launch_index_to_keys(p.gt, (int64_t)p.nq * p.topk, gt_keys, c.st));
     } else {
-      // exact top-K of every query over X (original space): score GEMM in column chunks + selection
-      float *xnorm = nullptr, *S = nullptr;
-      const int64_t colchunk = std::min<int64_t>(n, 1 << 16);
-      HIPCHK(c.pool.get(&xnorm, (size_t)n));
-      HIPCHK(c.pool.get(&S, (size_t)p.nq * colchunk));
-      HIPCHK(launch_row_norms(X, d, n, d, xnorm, c.st));
-      HIPCHK(launch_fill_u64(gt_keys, (int64_t)p.nq * p.topk, ~0ull, c.st));
-      rc = measure_absmax(X, d, n, d, c.amax + Ctx::AM_X, c.st);
+      rc = ground_truth_keys(c.pool, X, n, d, Q, p.nq, p.topk, c.amax + Ctx::AM_X, c.amax + Ctx::AM_Q, gt_keys, c.st);
       if (rc) return rc;
-      rc = measure_absmax(Q, d, p.nq, d, c.amax + Ctx::AM_Q, c.st);
-      if (rc) return rc;
-      for (int64_t c0 = 0; c0 < n; c0 += colchunk) {
-        const int64_t m = std::min<int64_t>(colchunk, n - c0);
-        GemmOperands g{Q, d, p.nq, X + c0 * d, d, (int32_t)m, d};
-        g.a_absmax = c.amax + Ctx::AM_Q; g.b_absmax = c.amax + Ctx::AM_X;
-        HIPCHK(gemm_store(g, S, colchunk, (int32_t)m, 1.f, 0.f, c.st));
-        HIPCHK(launch_topk_merge(S, colchunk, p.nq, (int32_t)m, c0, xnorm, p.topk, gt_keys, c.st));
-      }
     }
     HIPCHK(c.pool.get(&Qr, (size_t)p.nq * c.ds));
     if (p.rotate) {
@@ -1456,7 +1465,7 @@ int labels_in_range(const int32_t *a, int64_t n, int32_t k, unsigned int *flag_d
 
 int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, const int32_t *prev_assign,
                 int32_t dprime_in, const skm_params *pp, int32_t *assign_out, float *dist_out) {
-  int rc = check_shape(X, n, d, k);
+  int rc = check_shape(X, n, d, k, false);
   if (rc) return rc;
   if (!centroids || !assign_out) return fail(SKM_EINVAL, "null pointer");
   skm_params p;
@@ -1897,7 +1906,7 @@ void skm_params_default(skm_params *p) {
 }
 
 int64_t skm_workspace_bytes(int64_t n, int32_t d, int32_t k, const skm_params *params) {
-  if (n < 1 || n >= (int64_t)1 << 31 || d < 16 || d > 16384 || k < 1 || k > n || k > (1 << 24))
+  if (n < 1 || n >= (int64_t)1 << 31 || d < 16 || d > 16384 || k < 1 || k > (1 << 24))
     return fail(SKM_EINVAL, "shape out of range");
   skm_params p;
   if (params) p = *params; else skm_params_default(&p);
@@ -1955,7 +1964,7 @@ int skm_assign_ex(const float *X, int64_t n, int32_t d, const float *centroids, 
 
 int skm_assign_exact(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, void *stream,
                      int32_t *assign_out, float *dist_out) {
-  int rc = check_shape(X, n, d, k);
+  int rc = check_shape(X, n, d, k, false);
   if (rc) return rc;
   if (!centroids || !assign_out) return fail(SKM_EINVAL, "null pointer");
   hipStream_t st = (hipStream_t)stream;
@@ -2033,6 +2042,23 @@ int skm_update(const float *X, int64_t n, int32_t d, const int32_t *assign, int3
     HIPCHK(hipMemcpy2DAsync(centroids, sizeof(float) * (size_t)d, Yp, sizeof(float) * (size_t)ds,
                             sizeof(float) * (size_t)d, (size_t)k, hipMemcpyDeviceToDevice, st));
   if (counts_out) HIPCHK(hipMemcpyAsync(counts_out, w.cnt, sizeof(int32_t) * (size_t)k, hipMemcpyDeviceToDevice, st));
+  HIPCHK(hipStreamSynchronize(st));
+  return SKM_OK;
+}
+
+int skm_etr_ground_truth(const float *X, int64_t n, int32_t d, const float *queries, int32_t nq, int32_t topk,
+                         void *stream, int64_t *gt_out) {
+  if (!X || !queries || !gt_out) return fail(SKM_EINVAL, "null pointer");
+  if (n < 1 || n >= (int64_t)1 << 31 || d < 1 || d > 16384) return fail(SKM_EINVAL, "shape out of range");
+  if (nq < 1 || topk < 1 || topk > 256) return fail(SKM_EINVAL, "nq >= 1 and 1 <= topk <= 256 required");
+  hipStream_t st = (hipStream_t)stream;
+  Pool pool;
+  unsigned int *amax = nullptr;
+  unsigned long long *keys = nullptr;
+  HIPCHK(pool.get(&amax, 2));
+  HIPCHK(pool.get(&keys, (size_t)nq * topk));
+  if (int rc = ground_truth_keys(pool, X, n, d, queries, nq, topk, amax, amax + 1, keys, st)) return rc;
+  HIPCHK(launch_keys_to_index(keys, (int64_t)nq * topk, gt_out, st));
   HIPCHK(hipStreamSynchronize(st));
   return SKM_OK;
 }

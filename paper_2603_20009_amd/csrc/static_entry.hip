@@ -61,8 +61,7 @@ int skm_assign_exact_static(const float *X, int64_t n, int32_t d, const float *c
   using namespace skm;
   if (!X || !centroids || !assign_out) return report_error(SKM_EINVAL, "null pointer");
   if (n < 1 || n > kMaxPoints) return report_error(SKM_EINVAL, "skm_assign_exact_static: n out of range [1, 1048576]");
-  if (k < 1 || k > kMaxCentroids || k > n)
-    return report_error(SKM_EINVAL, "skm_assign_exact_static: k out of range [1, min(n, 16384)]");
+  if (k < 1 || k > kMaxCentroids) return report_error(SKM_EINVAL, "skm_assign_exact_static: k out of range [1, 16384]");
   if (d < 16 || d > 16384 || d % 16 != 0)
     return report_error(SKM_EINVAL, "skm_assign_exact_static: d must be a multiple of 16 in [16, 16384]");
   if ((reinterpret_cast<uintptr_t>(X) & 15u) || (reinterpret_cast<uintptr_t>(centroids) & 15u))

@@ -59,7 +59,7 @@ EXPORTS = [
     "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_theta_ratio", "skm_dprime_init", "skm_dprime_adjust",
     "skm_strerror", "skm_last_error", "skm_version", "skm_fit_hierarchical", "skm_hier_meso_count", "skm_hier_alloc",
     "skm_fit_host", "skm_workspace_bytes", "skm_debug_gemm_config",
-    "skm_assign_exact_static",
+    "skm_assign_exact_static", "skm_etr_ground_truth",
 ]
 
 _lib = None
@@ -93,6 +93,8 @@ def lib():
         L.skm_hier_alloc.argtypes = [vp, i32, i32, vp]
         L.skm_workspace_bytes.argtypes = [i64, i32, i32, C.POINTER(Params)]
         L.skm_workspace_bytes.restype = i64
+        L.skm_etr_ground_truth.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp]
+        L.skm_etr_ground_truth.restype = C.c_int
         L.skm_debug_gemm_config.argtypes = [i32, i32, i64]
         L.skm_debug_gemm_config.restype = None
         for f in ("skm_fit", "skm_fit_ex", "skm_assign", "skm_assign_ex", "skm_assign_exact", "skm_update",
@@ -388,6 +390,16 @@ def update(X: torch.Tensor, assign_: torch.Tensor, centroids: torch.Tensor):
     _check(lib().skm_update(_dev(X, torch.float32, "X"), n, d, _dev(assign_, torch.int32, "assign"), k, _stream(),
                             _dev(centroids, torch.float32, "centroids"), C.c_void_p(counts.data_ptr())))
     return counts
+
+
+def etr_ground_truth(X: torch.Tensor, queries: torch.Tensor, topk: int) -> torch.Tensor:
+    """skm_etr_ground_truth: nq x topk int64 indices of the nearest points of every query."""
+    n, d = X.shape
+    nq = queries.shape[0]
+    gt = torch.empty((nq, topk), device=X.device, dtype=torch.int64)
+    _check(lib().skm_etr_ground_truth(_dev(X, torch.float32, "X"), n, d, _dev(queries, torch.float32, "queries"), nq,
+                                      topk, _stream(), C.c_void_p(gt.data_ptr())))
+    return gt
 
 
 def make_rotation(d: int, seed: int, device="cuda") -> torch.Tensor:

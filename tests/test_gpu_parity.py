@@ -377,7 +377,129 @@ def test_etr_ground_truth_recall_and_stop(skm, orc, dg):
     assert all(g["recall"] >= 0.9 for g in got3.trace[:3])
 
 
+def check_ground_truth(gt, ref, X, Q, tol=2e-6):
+    """Index by index; where the two lists differ, the fp64 distances of the two points named at that rank must tie to
+    the rounding of an fp32 score (the library orders by ||x||^2 - 2 q.x computed in fp32)."""
+    gt = np.asarray(gt)
+    ref = np.asarray(ref)
+    assert gt.shape == ref.shape and gt.min() >= 0 and gt.max() < len(X)
+    assert all(len(set(r.tolist())) == len(r) for r in gt)          # no point twice in a list
+    qs, ranks = np.nonzero(gt != ref)
+    say(f"ground truth: {gt.size} entries, {len(qs)} differ")
+    assert len(qs) <= 0.01 * gt.size
+    for q, r in zip(qs, ranks):
+        dq = Q[q].astype(np.float64)
+        a = ((dq - X[gt[q, r]].astype(np.float64)) ** 2).sum()
+        b = ((dq - X[ref[q, r]].astype(np.float64)) ** 2).sum()
+        scale = (dq ** 2).sum() + (X[ref[q, r]].astype(np.float64) ** 2).sum()
+        assert abs(a - b) <= tol * scale, (q, r, a, b)
+
+
+def test_etr_ground_truth_merges_score_chunks(skm, orc, dg):
+    """The ground truth is selected from scores computed 65 536 points at a time.  150 000 points are three chunks
+    (the last one ragged): the running lists are full after the first, so the later chunks go through the filtered
+    merge (only columns below the list's largest key are candidates)."""
+    n, d, nq, K = 150_000, 64, 64, 10
+    X = dg.mixture(n, d, 30, 3, "linear").numpy()
+    Q = dg.mixture(nq, d, 30, 3, "linear", sample_seed=99).numpy()
+    gt = skm.etr_ground_truth(cuda(X), cuda(Q), K).cpu().numpy()
+    check_ground_truth(gt, orc.ground_truth(X, Q, K), X, Q)
+    # K = 1 and K larger than a wavefront
+    for K2 in (1, 100):
+        gt2 = skm.etr_ground_truth(cuda(X[:70_000]), cuda(Q[:8]), K2).cpu().numpy()
+        check_ground_truth(gt2, orc.ground_truth(X[:70_000], Q[:8], K2), X, Q[:8])
+
+
+def test_etr_ground_truth_when_a_chunk_floods_the_candidate_buffer(skm, orc):
+    """The filtered merge keeps at most 4096 candidate columns; a chunk with more columns below the running list's
+    largest key must fall back to selecting over the whole chunk.  First chunk: far points; second chunk: 60 000 points
+    all nearer to every query than anything before."""
+    rng = np.random.default_rng(5)
+    d, nq, K = 32, 16, 10
+    far = (rng.standard_normal((65_536, d)) * 0.1 + 3.0).astype(np.float32)
+    near = (rng.standard_normal((60_000, d)) * 0.1).astype(np.float32)
+    X = np.concatenate([far, near])
+    Q = (rng.standard_normal((nq, d)) * 0.1).astype(np.float32)
+    gt = skm.etr_ground_truth(cuda(X), cuda(Q), K).cpu().numpy()
+    assert gt.min() >= 65_536                                   # every neighbour comes from the second chunk
+    check_ground_truth(gt, orc.ground_truth(X, Q, K), X, Q)
+    # fewer points than K: the lists end with -1
+    gt3 = skm.etr_ground_truth(cuda(X[:4]), cuda(Q[:2]), K).cpu().numpy()
+    assert (gt3[:, 4:] == -1).all() and (np.sort(gt3[:, :4], axis=1) == np.arange(4)).all()
+
+
+def test_c3_full_size_etr(skm, orc, dg):
+    """Workload C3 (1 000 000 x 768, k = 4096, 1000 held-out queries, top-10, 41 probed centroids) as the fit runs it:
+    the ground truth over 16 score chunks against the oracle (a sample of the queries, index by index), and the recall
+    of every step against the oracle's recall formula on all 1000 queries."""
+    torch.cuda.empty_cache()
+    n, d, k, nq, K = 1_000_000, 768, 4096, 1000, 10
+    say("generating C3")
+    X = dg.config_data("C3", device="cuda")
+    Q = dg.config_queries("C3", device="cuda")
+    Rn = orc.random_rotation(d, 42)
+    R = cuda(Rn)
+    say("ground truth")
+    gt = skm.etr_ground_truth(X, Q, K)
+    rng = np.random.default_rng(2)
+    qs = np.sort(rng.choice(nq, 96, replace=False))
+    Xn = X.cpu().numpy()
+    Qn = Q.cpu().numpy()
+    say("oracle ground truth of 96 queries")
+    check_ground_truth(gt.cpu().numpy()[qs], orc.ground_truth(Xn, Qn[qs], K), Xn, Qn[qs])
+    nprobe = orc.nprobe(k, 0.01)
+    assert nprobe == 41
+    Qr = orc.rotate(Qn, Rn)
+    say("fits")
+    base = dict(R=R, etr=True, queries=Q, adjust_dprime=True)
+    full = skm.fit(X, k, 10, 42, skm.FitOptions(**base))                      # the library computes the ground truth
+    given = skm.fit(X, k, 10, 42, skm.FitOptions(gt=gt, **base))              # ... or is handed it
+    assert [r["recall"] for r in full.trace] == [r["recall"] for r in given.trace]
+    assert 2 <= full.iters_run <= 10 and len(full.trace) == full.iters_run + 1
+    gtn = gt.cpu().numpy()
+    for t in range(1, full.iters_run + 1):
+        # recall of step t: centroids Y_(t-1) (a fit of t - 1 iterations returns them; t = 1: the initial rows) and the
+        # labels a_t (a fit of t iterations without the final pass returns them); fits are reproducible bit by bit
+        if t == 1:
+            Yprev = Xn[orc.sample_rows(42, n, k)]
+        else:
+            Yprev = skm.fit(X, k, t - 1, 42, skm.FitOptions(etr_tol=-1.0, final_assign=False, **base)).centroids.cpu().numpy()
+        a_t = skm.fit(X, k, t, 42, skm.FitOptions(etr_tol=-1.0, final_assign=False, **base)).assign.cpu().numpy()
+        want = orc.recall(Qr, orc.rotate(Yprev, Rn), nprobe, gtn, a_t)
+        say(f"C3 step {t}: recall {full.trace[t - 1]['recall']:.5f} oracle {want:.5f}")
+        assert full.trace[t - 1]["recall"] == pytest.approx(want, abs=3.0 / (nq * K))
+    # the stop rule on the recalls it saw
+    rec = [r["recall"] for r in full.trace[: full.iters_run]]
+    best, streak, stop_at = rec[0], 0, None
+    for t in range(2, len(rec) + 1):
+        streak = streak + 1 if rec[t - 1] - best <= 0.005 else 0
+        best = max(best, rec[t - 1])
+        if streak >= 2:
+            stop_at = t
+            break
+    if full.iters_run < 10:
+        assert stop_at == full.iters_run
+    else:
+        assert stop_at in (None, 10)
+    del X, Q, full, given
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ full size, bench launch configuration
+def check_counters_on_rows(skm, ref, Xs, Y, prev_s, dp, R):
+    """The same pruned step on the sampled rows alone, with per-block statistics: every counter within 0.1 % of the
+    oracle's for those rows (the full-size run can only be compared in density: it counts over other points)."""
+    a, dist, row = skm.assign(Xs, Y, prev_s, dp, skm.FitOptions(R=R, block_stats=True))
+    ns, k = Xs.shape[0], Y.shape[0]
+    surv_ref = ns * (k - 1) - ref.pruned_first
+    assert abs(row["survivors"] - surv_ref) <= max(2, 1e-3 * surv_ref), (row["survivors"], surv_ref)
+    for m in range(min(row["nblocks"], 32)):
+        assert abs(row["enter"][m] - ref.enter[m]) <= max(2, 1e-3 * ref.enter[m]), (m, row["enter"][m], ref.enter[m])
+    assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])
+    assert (a.cpu().numpy() != ref.assign).sum() <= max(1, 1e-3 * ns)
+    return row
+
+
 def test_c2_full_size_sampled_parity(skm, orc, dg):
     """Workload C2 (1 000 000 x 1536, k = 1024) exactly as bench.py runs it; the oracle checks
     a sample of the rows one by one (pruned step and exact step) and a sample of the clusters."""
@@ -404,7 +526,9 @@ def test_c2_full_size_sampled_parity(skm, orc, dg):
     same = a3.cpu().numpy()[rows] == ref.assign
     assert np.abs(d3.cpu().numpy()[rows][same] - ref.dist[same]).max() < 1e-5
     surv_ref = len(rows) * (k - 1) - ref.pruned_first
-    assert row["survivors"] / n == pytest.approx(surv_ref / len(rows), rel=0.1)     # same survivor density
+    assert row["survivors"] / n == pytest.approx(surv_ref / len(rows), rel=0.1)     # same survivor density (sampling error)
+    ridx = torch.from_numpy(rows).cuda()
+    check_counters_on_rows(skm, ref, X[ridx].contiguous(), fr.centroids, fr.assign[ridx].contiguous(), orc.dprime_init(d), R)
     say("exact step on the sample")
     ae, de = skm.assign_exact(X, fr.centroids)
     ao, do = orc.assign_full(Xs.astype(np.float64), Y.astype(np.float64))
@@ -481,6 +605,57 @@ def test_c4_full_size_sampled_parity(skm, orc, dg):
         surv_ref = len(rows) * (k - 1) - ref.pruned_first
         assert row["survivors"] / n == pytest.approx(surv_ref / len(rows), rel=0.2)    # same survivor density (a heavy-tailed count per point)
         assert row["dprime"] == dp
+        ridx = torch.from_numpy(rows).cuda()
+        check_counters_on_rows(skm, ref, X[ridx].contiguous(), fr.centroids, fr.assign[ridx].contiguous(), dp, R)
+    del X, fr
+    torch.cuda.empty_cache()
+
+
+def test_c5_full_size_sampled_parity(skm, orc, dg):
+    """Workload C5 (10 000 000 x 384, k = 32 768): the large-N regime.  Three iterations as the fit runs them (at the
+    default pair budget the rows of a pruned step go through the tile kernel in eight chunks), then pruned steps at
+    d' = 48 (the initial value: the last trailing block holds 16 dimensions) and d' = 64, checked by the oracle on a
+    sample of the rows one by one."""
+    torch.cuda.empty_cache()
+    n, d, k = 10_000_000, 384, 32_768
+    say("generating C5")
+    X = dg.config_data("C5", device="cuda")
+    Rn = orc.random_rotation(d, 42)
+    R = cuda(Rn)
+    say("fit 3 iterations")
+    fr = skm.fit(X, k, 3, 42, skm.FitOptions(R=R, final_assign=False, adjust_dprime=False))
+    assert fr.trace[1]["dprime"] == 48 and fr.trace[1]["nblocks"] == 6
+    cnt = torch.bincount(fr.assign.long(), minlength=k)
+    assert int(cnt.sum()) == n
+    rng = np.random.default_rng(4)
+    rows = np.sort(rng.choice(n, 3072, replace=False))
+    ridx = torch.from_numpy(rows).cuda()
+    Xs = X[ridx].contiguous()
+    Xr = orc.rotate(Xs.cpu().numpy(), Rn)
+    Yr = orc.rotate(fr.centroids.cpu().numpy(), Rn)
+    prev = fr.assign.cpu().numpy()[rows]
+    for dp in (48, 64):
+        say("assign step at d' =", dp)
+        a, dist, row = skm.assign(X, fr.centroids, fr.assign, dp, skm.FitOptions(R=R))
+        ref = orc.assign_pruned(Xr, Yr, prev, dp, EPS0, 0)
+        check_assignment(a.cpu().numpy()[rows], ref.assign, Xr, Yr, min_agree=0.995)
+        same = a.cpu().numpy()[rows] == ref.assign
+        assert np.abs(dist.cpu().numpy()[rows][same] - ref.dist[same]).max() < 1e-5
+        surv_ref = len(rows) * (k - 1) - ref.pruned_first
+        # survivors per point are heavy-tailed here (a few points with a poor incumbent keep thousands of pairs), so
+        # 3072 rows estimate the density of ten million only roughly; the exact comparison is on the rows themselves
+        assert 0.5 < (row["survivors"] / n) / (surv_ref / len(rows)) < 2.0
+        assert row["dprime"] == dp and row["changed"] == int((a != fr.assign).sum())
+        check_counters_on_rows(skm, ref, Xs, fr.centroids, fr.assign[ridx].contiguous(), dp, R)
+    say("update on sampled clusters")
+    Yn = fr.centroids.clone()
+    cnt2 = skm.update(X, a, Yn).cpu().numpy()
+    assert cnt2.sum() == n
+    for c in rng.choice(k, 6, replace=False):
+        members = torch.nonzero(a == int(c)).flatten()
+        if len(members):
+            mean = X[members].cpu().numpy().astype(np.float64).mean(0)
+            assert np.abs(Yn[int(c)].cpu().numpy() - mean).max() < 1e-6
     del X, fr
     torch.cuda.empty_cache()
 

@@ -87,7 +87,7 @@ def test_argument_errors_are_codes_not_crashes(skm):
 def test_workspace_size_query(skm):
     L = skm.lib()
     assert L.skm_workspace_bytes(0, 16, 1, None) == -1 and L.skm_workspace_bytes(10, 8, 2, None) == -1
-    assert L.skm_workspace_bytes(10, 16, 11, None) == -1
+    assert L.skm_workspace_bytes(10, 16, 11, None) > 0      # an assignment step may have k > n
     small = skm.workspace_bytes(1000, 64, 10)
     big = skm.workspace_bytes(1_000_000, 1536, 1024)
     # two copies of the rotated points, their split-fp16 copy and the prefix-norm table dominate
