@@ -51,6 +51,7 @@ class _Params(C.Structure):
         ("etr_tol", C.c_double),
         ("etr_patience", C.c_int32),
         ("angular", C.c_int32),
+        ("conv_tol", C.c_double),
     ]
 
 
@@ -290,6 +291,7 @@ class FitParams:
     etr_tol: float = 0.005
     etr_patience: int = 2
     angular: bool = False          # spherical k-means: unit points, centroids renormalised after every update
+    conv_tol: float = 0.0          # > 0: stop after an iteration t >= 2 in which <= conv_tol * n labels changed
 
 
 @dataclass
@@ -313,7 +315,7 @@ def fit(X, k: int, iters: int, seed: int, params: FitParams | None = None, R=Non
     Rm = None if R is None else _f32(R)
     cp = _Params(p.dprime_frac, p.eps0, p.tau_group, int(p.adjust_dprime), p.adj_lo, p.adj_hi, p.adj_step,
                  p.split_eps, int(p.final_assign), int(p.etr), 0 if queries is None else int(len(queries)), p.topk,
-                 p.probe_frac, p.etr_tol, p.etr_patience, int(p.angular))
+                 p.probe_frac, p.etr_tol, p.etr_patience, int(p.angular), p.conv_tol)
     Q = None
     G = None
     if p.etr:

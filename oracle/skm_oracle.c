@@ -36,7 +36,9 @@
  * witnesses for every false prune, no-regress / monotone objective, centroid
  * means, rotation invariance, closed-form theta values, ETR closed form.
  * Unpinned by the paper (fixed by this build's reading only): eps0's default,
- * the split constants, d' rounding, ETR stop-rule details.
+ * the split constants, d' rounding, ETR stop-rule details, the convergence
+ * criterion (conv_tol: share of changed labels; its mechanics are pinned
+ * against textbook Lloyd's label changes, the choice of criterion is not).
  */
 #include <math.h>
 #include <stdint.h>
@@ -560,6 +562,11 @@ typedef struct orc_params {
    * centroid by L2 is the one of largest inner product / smallest angle, and
    * the rest of Algorithm 1 runs unchanged. */
   int32_t angular;       /* 0 */
+  /* Section 3.3, second termination condition ("reaching convergence"; the
+   * paper gives no criterion).  Reading: after an iteration t >= 2 in which
+   * at most conv_tol * n points changed their cluster, stop (the update of
+   * that iteration is still done).  0 = off. */
+  double conv_tol;       /* 0 */
 } orc_params;
 
 typedef struct orc_trace_row {
@@ -666,6 +673,7 @@ int32_t orc_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters,
     int64_t pf = 0;
     int64_t enter[33];
     int32_t nsplit, nempty = 0, stop = 0;
+    int64_t changed = n;
     double recall = -1.0;
     memset(enter, 0, sizeof(enter));
     if (t == 1) {
@@ -675,6 +683,8 @@ int32_t orc_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters,
       memcpy(prev, assign, sizeof(int32_t) * (size_t)n);
       orc_assign_pruned(Xr, n, d, Yr, k, prev, dprime, p->eps0, G, assign,
                         dist, &pf, enter, NULL);
+      changed = 0;
+      for (i = 0; i < n; ++i) changed += (assign[i] != prev[i]);
       free(prev);
     }
     if (p->etr)
@@ -718,6 +728,10 @@ int32_t orc_fit(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters,
         if (streak >= p->etr_patience) stop = 1;
       }
     }
+    /* convergence stop rule */
+    if (p->conv_tol > 0.0 && t > 1 &&
+        (double)changed <= p->conv_tol * (double)n)
+      stop = 1;
     if (stop) break;
   }
 

@@ -344,6 +344,52 @@ def test_fit_regroups_points_across_row_chunks(skm, orc, dg):
     assert (fits[0] == fits[1]).mean() >= 0.999
 
 
+def test_fit_stops_at_convergence_like_the_oracle(skm, orc, dg):
+    """conv_tol: the fit stops after the first iteration t >= 2 in which at most that share of the labels changed."""
+    X = dg.mixture(8000, 64, 12, 6, "linear").numpy()
+    R = orc.random_rotation(64, 6)
+    for tol in (0.01, 1e-4, 1.0):
+        ref, got = fit_pair(skm, orc, X, 12, 40, 6, R, conv_tol=tol)
+        assert got.iters_run == ref.iters_run and len(got.trace) == len(ref.trace) == ref.iters_run + 1
+        assert ref.iters_run < 40 and (tol < 1.0 or ref.iters_run == 2)
+        assert got.trace[got.iters_run - 1]["changed"] <= tol * len(X)
+        check_assignment(got.assign.cpu().numpy(), ref.assign, orc.rotate(X, R), ref.centroids_rot,
+                         own=(X, got.centroids.cpu().numpy()))
+        check_centroids(got.centroids.cpu().numpy(), ref.centroids, got.assign.cpu().numpy(), ref.assign)
+    with pytest.raises(skm.SkmError):
+        skm.fit(cuda(X), 12, 3, 6, skm.FitOptions(R=cuda(R), tau_group=5))      # only the frozen threshold is built
+    skm.fit(cuda(X), 12, 2, 6, skm.FitOptions(R=cuda(R), tau_group=12))         # ... which is what G = k says
+
+
+def test_update_after_a_split_that_moved_no_point(skm, orc, dg):
+    """Ten distinct points, fifty copies each, twelve centroids: two clusters are empty after iteration 1 and every
+    split re-seeds them next to a donor whose members are all equidistant from the two perturbed rows (exact ties:
+    which way they fall is rounding, so the labels are not compared with the oracle here).  Whenever no label changes
+    in the step after a split, the update must still put the donor back on the mean of its members before the next
+    split perturbs it again (Algorithm 1 updates, then splits): at the end every cluster with members sits on their
+    mean, or on the mean perturbed once, never twice."""
+    eps = 1.0 / 1024.0
+    base = dg.mixture(10, 32, 4, 2, "linear").numpy()
+    X = np.repeat(base, 50, axis=0)
+    idx = list(range(0, 500, 50)) + [101, 102]                # all ten points, and two more copies of the third
+    # seven iterations: in this run the seventh is one that changes no label after the split of the sixth, so the
+    # centroids returned are those of the update in question
+    got = skm.fit(cuda(X), 12, 7, 5, skm.FitOptions(rotate=False, init_idx=idx, adjust_dprime=False,
+                                                     final_assign=False))
+    assert got.trace[0]["nempty"] == 2 and got.trace[-1]["changed"] == 0 and got.trace[-2]["nempty"] > 0
+    quiet_after_split = [t for t in range(1, len(got.trace)) if got.trace[t]["changed"] == 0 and got.trace[t - 1]["nempty"] > 0]
+    say("steps without a label change after a split:", quiet_after_split, [(g["changed"], g["nempty"]) for g in got.trace])
+    assert quiet_after_split, "the scenario did not occur in this run (pick other points)"
+    a = got.assign.cpu().numpy()
+    Y = got.centroids.cpu().numpy().astype(np.float64)
+    s = np.where(np.arange(32) % 2 == 0, 1.0, -1.0)
+    for c in range(12):
+        if (a == c).any():
+            mean = X[a == c].astype(np.float64).mean(0)
+            errs = [np.abs(Y[c] - mean * f).max() for f in (1.0, 1.0 + eps * s, 1.0 - eps * s)]
+            assert min(errs) < 1e-6, (c, errs)
+
+
 def test_fit_is_bitwise_reproducible(skm, orc, dg):
     X = cuda(dg.mixture(30_000, 128, 64, 12, "linear").numpy())
     R = cuda(orc.random_rotation(128, 2))

@@ -414,6 +414,34 @@ def test_fit_without_rotation_and_test_is_textbook_lloyd(orc):
     assert np.allclose([r["objective"] for r in fr.trace], objs, rtol=1e-10)
 
 
+def test_convergence_stop_follows_textbook_label_changes(orc):
+    """conv_tol (Section 3.3, second condition): with the statistical test off the fit is textbook Lloyd, so the
+    iteration at which it stops is the first t >= 2 at which numpy's Lloyd changes at most conv_tol * n labels."""
+    rng = np.random.default_rng(12)
+    n, d, k, iters = 1500, 32, 6, 30
+    X = unit_rows(rng, n, d)
+    idx = orc.sample_rows(3, n, k)
+    # label changes per iteration of the textbook algorithm
+    Y = X[idx].astype(np.float64).copy()
+    prev, changes = None, []
+    for _ in range(iters):
+        D = ((X[:, None, :].astype(np.float64) - Y[None, :, :]) ** 2).sum(2)
+        a = D.argmin(1)
+        changes.append(n if prev is None else int((a != prev).sum()))
+        prev = a
+        for c in range(k):
+            if (a == c).any():
+                Y[c] = X[a == c].mean(0)
+    assert changes[-1] == 0 and changes[1] > 0.02 * n            # the run does converge, and not at once
+    for tol in (0.02, 0.002, 1e-9, 1.0):
+        want = next(t for t in range(2, iters + 1) if changes[t - 1] <= tol * n)
+        p = orc.FitParams(eps0=float("inf"), adjust_dprime=False, final_assign=False, conv_tol=tol)
+        fr = orc.fit(X, k, iters, 3, p, R=None, init_idx=idx)
+        assert fr.iters_run == want, (tol, fr.iters_run, want)
+    off = orc.fit(X, k, 8, 3, orc.FitParams(eps0=float("inf"), adjust_dprime=False, final_assign=False), R=None, init_idx=idx)
+    assert off.iters_run == 8                                    # 0 = no convergence stop
+
+
 def test_fit_rotation_invariance_and_unrotation(orc):
     rng = np.random.default_rng(8)
     n, d, k, iters = 800, 48, 8, 5
