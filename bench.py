@@ -1,17 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the SuperKMeans hot path on one MI355X.
 
-One *step* is one whole fit (``skm_fit_ex``) of the named workload: rotation GEMM, centroid
-initialisation, iteration 1 (full GEMM + argmin), iterations 2..n (initial threshold, partial GEMM +
-first test, progressive pruning, argmin, update, d' adjustment), the final two-phase assignment pass
-and the un-rotation of the centroids.  Inputs are generated once, seeded, on the GPU and are
-resident in HBM when the timed region starts.  Every fit makes its own rotation matrix R on the device
-(fp64 Gram-Schmidt of a seeded Gaussian matrix), inside the timed region.
+One *step* is one whole fit (``skm_fit_ex``) of the headline workload C2 (1M x 1536, k = 1024): rotation GEMM,
+centroid initialisation, iteration 1 (full GEMM + argmin), iterations 2..n (initial threshold, partial GEMM + first
+test, progressive pruning, argmin, update, d' adjustment), the final two-phase assignment pass and the un-rotation of
+the centroids.  Inputs are generated once, seeded, on the GPU and are resident in HBM when the timed region starts.
+Every fit makes its own rotation matrix R on the device (fp64 Gram-Schmidt of a seeded Gaussian matrix) inside the
+timed region.  The fit's workspace is lent by the caller (a torch tensor sized by ``skm_workspace_bytes``), so a fit
+allocates nothing; ``--own-workspace`` lets the library allocate and free it inside every call instead.
 
 Prints ONE JSON line: metric, value (point*centroid*dim per second over whole fits), ms_per_step, the workload in
-config, per-iteration seconds, `roofline` for the dominant kernel (algorithmic flop per launch over its HIP-event
-time, against the dense fp16 matrix peak divided by the three products of the split arithmetic), `stages` with the
-same figures for every kernel family, and `cpu_baseline` (the CPU oracle timed on a bounded sample of the workload).
+config, per-iteration seconds, host-clock figures (wall time of a call, wall minus device time), `roofline` for the
+dominant kernel (algorithmic flop per launch over its HIP-event time, against the dense fp16 matrix peak divided by
+the three products of the split arithmetic), `stages` with the same figures for every kernel family,
+`other_workloads` (the rest of the metric's range, k = 4096 ... 32 768: C4, C3, C5, a few timed fits each, same
+figures) and `cpu_baseline` (the CPU oracle timed on a bounded sample of the headline workload).
 """
 from __future__ import annotations
 
@@ -51,60 +54,35 @@ def cpu_baseline(X_sample, k, iters, seed, R, cores):
                 seconds=dt)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="C2", help="workload name in paper_2603_20009_amd.datagen.CONFIGS")
-    ap.add_argument("--n", type=int, default=0, help="override the number of points (testing only)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--own-workspace", action="store_true",
-                    help="let the library allocate and free its workspace inside every call (default: the caller lends it)")
-    ap.add_argument("--cpu-sample", type=int, default=12288)
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="run one 1 GiB device copy first (a kernel of known traffic for scaling rocprofv3 --pmc counters)")
-    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
-                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (optional)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(name, steps, warmup, own_workspace, traffic_json, n_override=0):
+    """`warmup` untimed and `steps` timed fits of one workload; returns (summary dict, X, results)."""
     import numpy as np
     import torch
     from paper_2603_20009_amd import skm, datagen
 
-    cfg = dict(datagen.CONFIGS[args.config])
-    n = args.n or cfg["n"]
+    cfg = dict(datagen.CONFIGS[name])
+    n = n_override or cfg["n"]
     d, k, iters = cfg["d"], cfg["k"], cfg["iters"]
     seed = datagen.SEED_FIT
-    torch.cuda.set_device(0)
-    if args.calibrate_copy:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-    X = datagen.config_data(args.config, device="cuda", n=n)
-    queries = datagen.config_queries(args.config, device="cuda") if cfg.get("etr") else None
+    X = datagen.config_data(name, device="cuda", n=n)
+    queries = datagen.config_queries(name, device="cuda") if cfg.get("etr") else None
     torch.cuda.synchronize()
     # R = None: made by the fit from the seed
-    opts = skm.FitOptions(etr=bool(cfg.get("etr")), queries=queries, own_workspace=args.own_workspace)
+    opts = skm.FitOptions(etr=bool(cfg.get("etr")), queries=queries, own_workspace=own_workspace)
 
     def step():
         return skm.fit(X, k, iters, seed, opts)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     results = []
     t0 = time.time()
-    for _ in range(args.steps):
+    for _ in range(steps):
         results.append(step())
     torch.cuda.synchronize()
     wall = time.time() - t0
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step = wall * 1e3 / steps
     iters_run = results[-1].iters_run
     value = n * k * d * iters_run / (ms_per_step * 1e-3)
 
@@ -131,6 +109,9 @@ def main():
     flop_alg = float(np.mean([2.0 * n * k * t["dprime"] + 128.0 * t["dense_pair_blocks"] for t in steps2])) if steps2 else 0.0
     flop_exec = float(np.mean([tile_flop * t["dense_dims"] for t in steps2])) if steps2 else 0.0
     total_prog = float(np.sum([t["ms_gemm"] for t in steps2]))
+    # algorithmic bytes of the gather kernel per pruned step: a (pair, block) step reads one 256-byte block of the
+    # point's row and one of the centroid's block-major copy; every pair is a 16-byte list entry
+    prune_bytes = float(np.mean([512.0 * t["gather_pair_blocks"] + 16.0 * t["gather_pairs"] for t in steps2])) if steps2 else 0.0
     # algorithmic bytes of an update: every row once (full), or the rows of the points that changed cluster, twice
     # (joined + left), when the library takes the incremental path (at most one point in eight changed)
     def update_bytes(t, first):
@@ -146,7 +127,10 @@ def main():
         "progressive_gemm": dict(bound="mfma", ms=ms_prog, achieved=flop_alg / ms_prog / 1e9, unit="TFLOP/s",
                                  executed=flop_exec / ms_prog / 1e9),
         "tau_init": dict(bound="hbm", ms=ms_tau, achieved=(n * ds * 4.0 + 12.0 * n) / ms_tau / 1e6, unit="GB/s"),
-        "gather_prune": dict(bound="hbm", ms=ms_prune, achieved=None, unit="GB/s"),
+        "gather_prune": dict(bound="hbm", ms=ms_prune, achieved=(prune_bytes / ms_prune / 1e6) if ms_prune > 0 else None,
+                             unit="GB/s", bytes_per_step=prune_bytes,
+                             note="algorithmic bytes the gather kernel requests (512 B per gathered pair-block step + "
+                                  "16 B per pair); most are served by the XCD's L2, not by HBM"),
         "update": dict(bound="hbm", ms=ms_update, achieved=upd_bytes / ms_update / 1e6, unit="GB/s",
                        incremental_updates=int(last.timing.get("inc_updates", 0))),
     }
@@ -157,17 +141,22 @@ def main():
     totals = {"rotation_gemm": ms_rot, "iter1_gemm_argmin": ms_it1_gemm, "progressive_gemm": total_prog}
     dom = max(totals, key=totals.get)
     traffic = None
-    if os.path.exists(args.traffic_json):
+    traffic_source = None
+    if traffic_json and os.path.exists(traffic_json):
         try:
-            traffic = json.load(open(args.traffic_json)).get(args.config, {}).get(dom)
+            traffic = json.load(open(traffic_json)).get(name, {}).get(dom)
+            if traffic is not None:
+                traffic_source = (f"{os.path.relpath(traffic_json, ROOT)} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
+                                  f"this command, committed; NOT measured in this run)")
         except Exception:
             traffic = None
-    kname = {"rotation_gemm": "skm::gemm_split_kernel<store>", "iter1_gemm_argmin": "skm::gemm_split_kernel<argmin>",
+    kname = {"rotation_gemm": "skm::gemm_split256_kernel<store>", "iter1_gemm_argmin": "skm::gemm_split256_kernel<argmin>",
              "progressive_gemm": "skm::progressive_kernel"}[dom]
     # traffic: HBM bytes per launch of that kernel (scaled FETCH_SIZE + WRITE_SIZE of the committed counter runs)
     roofline = dict(bound="mfma", kernel=kname, achieved=stages[dom]["achieved"], peak=PEAK_SPLIT_TFLOPS,
                     unit="TFLOP/s", frac=stages[dom]["frac"],
-                    traffic=None if traffic is None else traffic.get("total_bytes"), traffic_detail=traffic,
+                    traffic=None if traffic is None else traffic.get("total_bytes"), traffic_source=traffic_source,
+                    traffic_detail=traffic,
                     ms_per_step=stages[dom]["ms"], total_ms_per_fit=totals[dom],
                     flop_per_step={"rotation_gemm": flops_rot, "iter1_gemm_argmin": flops_it1,
                                    "progressive_gemm": flop_alg}[dom],
@@ -179,38 +168,96 @@ def main():
     if dom == "progressive_gemm":
         roofline["executed"] = stages[dom]["executed"]
         roofline["executed_frac"] = stages[dom]["executed"] / PEAK_SPLIT_TFLOPS
-
+    device_ms = avg(lambda r: r.timing["ms_total"])
     out = {
-        "metric": "point*centroid*dim per second over one SuperKMeans fit (seconds per k-means iteration alongside)",
-        "value": value, "unit": "point*centroid*dim/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "arithmetic": "fp32 in, fp32 accumulation and fp32 out; GEMM-shaped products run on the fp16 matrix cores with "
-                      "every operand as a scaled (hi, lo) fp16 pair, 22 significant bits (three MFMAs per product)",
-        "config": {"workload": f"{args.config}: {n}x{d} fp32 unit-norm mixture rows ({cfg['components']} components), "
-                               f"k={k}, {iters} iterations + final assignment pass", "n": n, "d": d, "k": k,
-                   "iters": iters, "iters_run": iters_run},
+        "value": value, "unit": "point*centroid*dim/s", "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "config": {"workload": f"{name}: {n}x{d} fp32 unit-norm mixture rows ({cfg['components']} components), "
+                               f"k={k}, {iters} iterations + final assignment pass" + (", ETR on 1000 held-out queries" if cfg.get("etr") else ""),
+                   "n": n, "d": d, "k": k, "iters": iters, "iters_run": iters_run},
         "s_per_iteration": {"iteration_1": ms_iter1 * 1e-3, "iterations_2_plus_median": ms_iter_rest * 1e-3,
-                            "fit_total_device": avg(lambda r: r.timing["ms_total"]) * 1e-3},
+                            "fit_total_device": device_ms * 1e-3},
         "ms_before_iteration_1": avg(lambda r: r.timing["ms_init"]),
         "host": {"ms_call_wall": avg(lambda r: r.timing["ms_host_total"]),
                  "ms_workspace_alloc": avg(lambda r: r.timing["ms_host_alloc"]),
                  "ms_workspace_free": avg(lambda r: r.timing["ms_host_free"]),
-                 "ms_wall_minus_device": ms_per_step - avg(lambda r: r.timing["ms_total"]),
-                 "workspace": "lent by the caller (a torch tensor; skm_workspace_bytes)" if not args.own_workspace
+                 "ms_wall_minus_device": ms_per_step - device_ms,
+                 "workspace": "lent by the caller (a torch tensor; skm_workspace_bytes)" if not own_workspace
                               else "allocated and freed by the library inside every call"},
         "dprime_per_step": dprimes,
-        "prune_frac_per_step": [round(t["prune_frac"], 5) for t in results[-1].trace],
-        "objective_final": results[-1].trace[-1]["objective"],
+        "prune_frac_per_step": [round(t["prune_frac"], 5) for t in last.trace],
+        "objective_final": last.trace[-1]["objective"],
         "roofline": roofline,
         "stages": stages,
     }
+    if cfg.get("etr"):
+        out["recall_per_step"] = [round(t["recall"], 5) for t in last.trace[:iters_run]]
+        out["ms_etr_ground_truth"] = avg(lambda r: r.timing["ms_etr_gt"])
+    return out, X, results
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C2", help="headline workload (a name in paper_2603_20009_amd.datagen.CONFIGS)")
+    ap.add_argument("--others", default="C4,C3,C5",
+                    help="further workloads timed in the same run (comma separated, '' for none): 1 untimed + 3 timed fits each")
+    ap.add_argument("--n", type=int, default=0, help="override the number of points of the headline workload (testing only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--own-workspace", action="store_true",
+                    help="let the library allocate and free its workspace inside every call (default: the caller lends it)")
+    ap.add_argument("--cpu-sample", type=int, default=12288)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one 1 GiB device copy first (a kernel of known traffic for scaling rocprofv3 --pmc counters)")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
+                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (optional)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_20009_amd import skm, datagen
+
+    torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    head, X, results = run_workload(args.config, args.steps, args.warmup, args.own_workspace, args.traffic_json, args.n)
+    out = {
+        "metric": "point*centroid*dim per second over one SuperKMeans fit (seconds per k-means iteration alongside)",
+        "value": head["value"], "unit": head["unit"],
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "arithmetic": "fp32 in, fp32 accumulation and fp32 out; GEMM-shaped products run on the fp16 matrix cores with "
+                      "every operand as a scaled (hi, lo) fp16 pair, 22 significant bits (three MFMAs per product)",
+    }
+    for key in ("config", "s_per_iteration", "ms_before_iteration_1", "host", "dprime_per_step", "prune_frac_per_step",
+                "objective_final", "roofline", "stages"):
+        out[key] = head[key]
+    cfg = datagen.CONFIGS[args.config]
     if not args.no_cpu_baseline:
-        ns = min(n, max(args.cpu_sample, k))
+        ns = min(X.shape[0], max(args.cpu_sample, cfg["k"]))
         cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-        R = skm.make_rotation(d, seed)   # the matrix the fits above used (a function of d and the seed only)
-        out["cpu_baseline"] = cpu_baseline(X[:ns].cpu().numpy(), k, iters, seed, R.cpu().numpy(), cores)
+        R = skm.make_rotation(cfg["d"], datagen.SEED_FIT)   # the matrix the fits above used (a function of d and the seed only)
+        Xs = X[:ns].cpu().numpy()
+        Rn = R.cpu().numpy()
+    del X, results
+    torch.cuda.empty_cache()
+    others = {}
+    for name in [s for s in args.others.split(",") if s and s != args.config]:
+        o, Xo, ro = run_workload(name, 3, 1, args.own_workspace, args.traffic_json)
+        others[name] = o
+        del Xo, ro
+        torch.cuda.empty_cache()
+    out["other_workloads"] = others
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(Xs, cfg["k"], cfg["iters"], datagen.SEED_FIT, Rn, cores)
     print(json.dumps(out))
 
 

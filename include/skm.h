@@ -58,6 +58,13 @@ typedef struct skm_trace_row {
                           (x 2*128*128 = executed MFMA flop of the progressive kernel) */
   int64_t dense_pair_blocks; /* (pair, trailing block) steps of alive pairs that were done inside dense tiles
                                 (the rest of the steps went through the gather kernel) */
+  int64_t gather_pair_blocks; /* (pair, trailing block) steps done by the gather kernel: each reads 256 bytes of the
+                                 point's row and 256 bytes of the centroid's block */
+  int64_t gather_pairs; /* pairs handed from the dense tiles to the gather kernel (16-byte list entries) */
+  int64_t screen_dims; /* dimensions multiplied by the low-precision first filter (one fp16 product), summed over
+                          its 128 x 128 tiles; 0 when the step ran without it */
+  int64_t listed_tiles; /* tiles of 128 listed centroids that the exact kernel then processed (0 without the filter:
+                           the exact kernel then takes every (row tile, column tile) pair) */
   int32_t dprime;      /* d' used by this step (d for iteration 1) */
   int32_t nblocks;     /* trailing 64-dim blocks (the last may be shorter) */
   int64_t enter[SKM_MAX_BLOCKS]; /* pairs that entered trailing block m (only when
@@ -139,6 +146,13 @@ typedef struct skm_params {
   int64_t workspace_bytes; /* 0  : size of `workspace` */
   float conv_tol;        /* 0    : > 0 = also stop (Section 3.3, the second termination condition) after an iteration
                             t >= 2 in which at most this share of the points changed its cluster */
+  int32_t screen;        /* 0    : low-precision first filter (Section 4.14, closing remark): before the exact tile
+                            kernel, one fp16 product on the first d' dimensions and the first test theta(d', tau)
+                            widened by the rounding bound find, per tile of 128 points, the centroids that can still
+                            pass; the exact kernel (three products, exact tests and counters) then runs on those
+                            only.  0 = in steps that follow a step which cut at least 90 % of the pairs at the first
+                            test, 1 = in every pruned step, -1 = never.  Execution strategy only: a pair cut by the
+                            widened test is cut by the exact one as well */
   int32_t tau_group;     /* 0    : centroids after which a point's threshold tau is refreshed inside a step.  0 (= k):
                             tau keeps its initial value for the whole step, the only form this library runs (the
                             result is then independent of the order in which tiles are processed); any other value

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libskm.so")
-SOURCES = ["gemm.hip", "progressive.hip", "prune.hip", "stream_kernels.hip", "rotation.hip", "etr.hip", "api.hip", "static_entry.hip"]
+SOURCES = ["gemm.hip", "progressive.hip", "screen.hip", "prune.hip", "stream_kernels.hip", "rotation.hip", "etr.hip", "api.hip", "static_entry.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-Wall", "-Wno-unused-function",

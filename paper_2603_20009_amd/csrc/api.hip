@@ -383,6 +383,12 @@ struct Ctx {
   int32_t inc_updates = 0;           // update steps that took the incremental path
   int32_t *split_dev = nullptr;
   bool block_stats = false;
+  // low-precision first filter (screen.hip): mode as params->screen; buffers for one chunk of rows
+  int32_t screen_mode = 0;
+  double last_prune_frac = -1.0;     // of the previous pruned step of this context (-1: none yet)
+  uint32_t *colmask = nullptr;
+  float *scr_arow = nullptr, *scr_ycol = nullptr;
+  int32_t *scr_cnt = nullptr, *scr_first = nullptr, *scr_ntiles = nullptr, *scr_cols = nullptr, *scr_tile_rt = nullptr;
   unsigned int *amax = nullptr;      // [AM_COUNT] magnitude bounds of the GEMM operands
   enum { AM_XR = 0, AM_Y = 1, AM_X = 2, AM_Q = 3, AM_QR = 4, AM_COUNT = 8 };
 
@@ -470,7 +476,19 @@ struct Ctx {
     pair_cap = sub_cap * kSubLists;
     if (pair_cap >= ((int64_t)1 << 32)) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
     HIPCHK(pool.get(&pairs, (size_t)pair_cap));
-    ncounters = (size_t)nchunks * (kSubLists + 8) * kSubListStride;   // list fill counters, then tile counters
+    ncounters = (size_t)nchunks * (kSubLists + 16) * kSubListStride;   // list fill counters, tile counters of the two tile kernels
+    if (screen_mode > 0 || (screen_mode == 0 && k >= 2 * progressive_tile_cols())) {   // (unless forced: of no use below two column tiles)
+      // one bit per (row tile, centroid); at most one tile of listed columns per (row tile, column tile) of the chunk
+      const int64_t nrt_chunk = (std::min<int64_t>(chunk_rows, n) + 127) / 128;
+      HIPCHK(pool.get(&colmask, (size_t)nrt_chunk * 4 * (size_t)col_tiles));
+      HIPCHK(pool.get(&scr_cnt, (size_t)nrt_chunk));
+      HIPCHK(pool.get(&scr_first, (size_t)nrt_chunk));
+      HIPCHK(pool.get(&scr_ntiles, 2));   // the tile count, then a float scalar of the filter
+      HIPCHK(pool.get(&scr_arow, (size_t)std::min<int64_t>(chunk_rows, n)));
+      HIPCHK(pool.get(&scr_ycol, (size_t)k));
+      HIPCHK(pool.get(&scr_cols, (size_t)tiles_chunk * 128));
+      HIPCHK(pool.get(&scr_tile_rt, (size_t)tiles_chunk));
+    }
     // Everything a step clears at its start and reports at its end is one block: counters | flag | step scalars |
     // objective | cluster sizes.  One memset, and one copy (from the flag on) into the page-locked mirror.
     {
@@ -611,6 +629,7 @@ size_t fit_workspace_need(int64_t n, int32_t d, int32_t k, const skm_params &p) 
 struct StepStats {
   double objective = 0;
   int64_t survivors = 0, completed = 0, changed = 0, dense_dims = 0, dense_pair_blocks = 0;
+  int64_t gather_pair_blocks = 0, gather_pairs = 0, screen_dims = 0, listed_tiles = 0;
   int64_t enter[SKM_MAX_BLOCKS] = {0};
   int32_t dprime = 0, nblocks = 0;
   bool pruned = false;  // false for the exact step of iteration 1
@@ -703,6 +722,10 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   }
   c.order_fresh = false;
   c.xnp_valid = true;
+  // Low-precision first filter: worth its pass over the front dimensions when most columns of a tile die at the
+  // first test, which the previous step's prune fraction predicts.
+  const bool screen = c.colmask && nb > 0 &&
+                      (c.screen_mode > 0 || (c.screen_mode == 0 && c.last_prune_frac >= 0.90));
   HIPCHK(launch_split_rows(c.Y, c.ds, c.k, c.ds, c.amax + Ctx::AM_Y, c.Ys, c.st));
   tm.mark(ST_TAU);
   for (int32_t ch = 0; ch < c.nchunks; ++ch) {
@@ -720,6 +743,22 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     g.pairs = c.pairs; g.pair_count = fill; g.sub_capacity = (unsigned int)c.sub_cap;
     g.overflow = c.counters + c.ncounters; g.emit_max = c.emit_max;
     g.best = c.best; g.scal = c.scal; g.block_stats = c.block_stats ? 1 : 0;
+    if (screen) {
+      ScreenLaunch sl{};
+      sl.A = g.A; sl.lda = g.lda; sl.M = g.M; sl.B = g.B; sl.ldb = g.ldb; sl.N = g.N;
+      sl.a_absmax = g.a_absmax; sl.b_absmax = g.b_absmax;
+      sl.ds = c.ds; sl.dprime = dprime; sl.ratio0 = ratio[0];
+      sl.tau = c.tau; sl.row_base = r0;
+      sl.xn = c.xnp + (int64_t)(dprime / 16 - 1) * c.n;
+      sl.yn = c.ynp;
+      sl.arow = c.scr_arow; sl.ycol = c.scr_ycol;
+      sl.colmask = c.colmask; sl.cnt = c.scr_cnt; sl.first = c.scr_first; sl.ntiles = c.scr_ntiles;
+      sl.col_list = c.scr_cols; sl.tile_rt = c.scr_tile_rt;
+      sl.tile_counter = c.counters + ((size_t)c.nchunks * (kSubLists + 8) + (size_t)ch * 8) * kSubListStride;
+      sl.scal = c.scal;
+      HIPCHK(launch_screen(sl, c.st));
+      g.tile_rt = c.scr_tile_rt; g.col_list = c.scr_cols; g.ntiles = c.scr_ntiles;
+    }
     HIPCHK(launch_progressive(g, c.st));
     tm.mark(ST_GEMM);
     if (c.emit_max > 0) {
@@ -749,6 +788,11 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   ss.changed = (int64_t)scal_h[SC_CHANGED];
   ss.dense_dims = (int64_t)scal_h[SC_DENSE_DIMS];
   ss.dense_pair_blocks = (int64_t)scal_h[SC_DENSE_PB];
+  ss.gather_pair_blocks = (int64_t)scal_h[SC_GATHER_PB];
+  ss.gather_pairs = (int64_t)scal_h[SC_GATHER_PAIRS];
+  ss.screen_dims = (int64_t)scal_h[SC_SCREEN_DIMS];
+  ss.listed_tiles = (int64_t)scal_h[SC_LISTED_TILES];
+  c.last_prune_frac = c.k > 1 ? 1.0 - (double)ss.survivors / ((double)c.n * (double)(c.k - 1)) : -1.0;
   for (int m = 0; m < std::min<int>(nb, SKM_MAX_BLOCKS); ++m) ss.enter[m] = (int64_t)scal_h[SC_ENTER + (size_t)m];
   ss.objective = obj;
   ss.dprime = dprime;
@@ -849,6 +893,10 @@ void fill_row(skm_trace_row &r, const StepStats &ss, int64_t n, int32_t k, int64
   r.changed = ss.changed;
   r.dense_dims = ss.dense_dims;
   r.dense_pair_blocks = ss.dense_pair_blocks;
+  r.gather_pair_blocks = ss.gather_pair_blocks;
+  r.gather_pairs = ss.gather_pairs;
+  r.screen_dims = ss.screen_dims;
+  r.listed_tiles = ss.listed_tiles;
   r.nempty = nempty;
   r.dprime = ss.dprime;
   r.nblocks = ss.nblocks;
@@ -971,6 +1019,7 @@ int fit_impl(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uin
   c.n = n; c.d = d; c.k = k;
   c.ds = round_up(d, 16);
   c.block_stats = p.block_stats != 0;
+  c.screen_mode = p.screen;
   // stage times are taken only for a caller that asked for the trace (a small fit inside the hierarchical fit spends
   // a third of its host time creating and reading events otherwise)
   const bool timed = tr != nullptr;
@@ -1274,6 +1323,7 @@ int fit_host_impl(const float *Xh, int64_t n, int32_t d, int32_t k, int32_t iter
   c.n = W; c.d = d; c.k = k;
   c.ds = round_up(d, 16);
   c.block_stats = p.block_stats != 0;
+  c.screen_mode = p.screen;
   StageTimer tm(c.st, true);
   Events evs;
   hipEvent_t e_begin = evs.next(), e_init = evs.next(), e_end0 = evs.next(), e_end = evs.next();
@@ -1393,6 +1443,10 @@ int fit_host_impl(const float *Xh, int64_t n, int32_t d, int32_t k, int32_t iter
       tot.changed += ss.changed;
       tot.dense_dims += ss.dense_dims;
       tot.dense_pair_blocks += ss.dense_pair_blocks;
+      tot.gather_pair_blocks += ss.gather_pair_blocks;
+      tot.gather_pairs += ss.gather_pairs;
+      tot.screen_dims += ss.screen_dims;
+      tot.listed_tiles += ss.listed_tiles;
       for (int m = 0; m < SKM_MAX_BLOCKS; ++m) tot.enter[m] += ss.enter[m];
       tot.dprime = ss.dprime;
       tot.nblocks = ss.nblocks;
@@ -1486,6 +1540,7 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
   c.n = n; c.d = d; c.k = k;
   c.ds = round_up(d, 16);
   c.block_stats = p.block_stats != 0;
+  c.screen_mode = p.screen;
   StageTimer tm(c.st, true);
   Rot rot;
   float *Xr_own = nullptr;
@@ -1902,6 +1957,7 @@ void skm_params_default(skm_params *p) {
   p->workspace = nullptr;
   p->workspace_bytes = 0;
   p->conv_tol = 0.f;
+  p->screen = 0;
   p->tau_group = 0;
 }
 

@@ -106,6 +106,7 @@ __device__ inline int wave_sum_i32(int v) {
 // Slabs of BK dimensions start at koff = -((BK - d' % BK) % BK), so that slab ends fall on every
 // checkpoint d' + 64 m; the zero granules around every row of the split operands cover dimensions below 0
 // or past ds.
+template <bool LISTED>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) progressive_kernel(ProgArgs g) {
   extern __shared__ __align__(16) uint32_t smem[];   // [2 stages][A: BM rows | B: BN rows][ROW_WORDS]
   __shared__ __align__(16) float s_tau[2][BM], s_thr[BM], s_xn[BM], s_yn[BN];   // s_tau: by tile parity
@@ -114,6 +115,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ __align__(16) unsigned int s_wcnt[2][4];   // alive pairs of every wavefront at the last checkpoint (by checkpoint parity)
   __shared__ unsigned int s_base;         // first list slot of a tile that hands its pairs over
   __shared__ int s_q[4];   // ring of tile numbers drawn from the XCD's counter, two tiles ahead of the one in work
+  __shared__ int s_cid[BN];   // listed columns: the centroid ids of the tile being committed (INT_MAX = none)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -121,7 +123,10 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int r32 = lane & 31, kh = lane >> 5;
   const int swz = (r32 >> 1) & 7;   // position swizzle of the tile rows this lane reads fragments from
   const int nrt = (g.M + BM - 1) / BM, nct = (g.N + BN - 1) / BN;
-  const int ntiles = nrt * nct;
+  // Listed columns (after the low-precision first filter): tile t is row tile tile_rt[t] against the 128 centroids
+  // col_list[128 t ..]; the "column tile" of such a tile is its own number.
+  constexpr bool listed = LISTED;
+  const int ntiles = listed ? *g.ntiles : nrt * nct;
   // column tiles per panel of the tile walk: in the steady state only d' + a few blocks of every centroid are read,
   // so a panel of 16 column tiles fits one XCD's L2 and every point tile is read once per 16 column tiles
   constexpr int PC = 16;
@@ -137,6 +142,11 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const float inv_panel = 1.0f / (float)panel_sz;
   auto tile_rc = [&](int q, int &rt, int &ct) {   // q-th tile of this XCD -> (row tile, column tile)
     const int logical = xstart + q;
+    if (listed) {
+      rt = g.tile_rt[logical];
+      ct = logical;
+      return;
+    }
     // panel = logical / panel_sz without an integer division: the float estimate is within one of the quotient
     // (fewer than 2^20 panels), and the remainder says which way
     int p = (int)((float)logical * inv_panel);
@@ -181,14 +191,29 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const float *npre = g.xnp;                // &norm[0][this thread's row or column]
   const int64_t npre_stride = tid < BM ? g.xn_stride : (int64_t)g.N;
   float nreg = 0.f;
+  int cid_reg = 0;   // listed columns, threads BM..: the centroid id of column tid - BM of the tile being loaded
   auto aim = [&](int row0, int col0) {
     baseA = g.A + (int64_t)row0 * g.lda;
-    baseB = g.B + (int64_t)col0 * g.ldb;
     limA = g.M - 1 - row0;
-    limB = g.N - 1 - col0;
 #pragma unroll
     for (int j = 0; j < A_LD; ++j)
       offA[j] = (unsigned int)(min(ld_row + ROWS_PASS * j, limA) * (int)g.lda + 4 * ld_piece);
+    if (listed) {
+      // col0 is the tile's number: its columns are listed ids (a missing one loads centroid 0 and starts dead)
+      const int32_t *ids = g.col_list + (int64_t)col0 * BN;
+      baseB = g.B;
+      limB = BN - 1;
+#pragma unroll
+      for (int j = 0; j < B_LD; ++j) {
+        const int id = ids[ld_row + ROWS_PASS * j];
+        offB[j] = (unsigned int)(max(id, 0) * (int)g.ldb + 4 * ld_piece);
+      }
+      cid_reg = tid >= BM ? ids[tid - BM] : 0;
+      npre = tid < BM ? g.xnp + g.row_base + row0 + min(tid, limA) : g.ynp + max(cid_reg, 0);
+      return;
+    }
+    baseB = g.B + (int64_t)col0 * g.ldb;
+    limB = g.N - 1 - col0;
 #pragma unroll
     for (int j = 0; j < B_LD; ++j)
       offB[j] = (unsigned int)(min(ld_row + ROWS_PASS * j, limB) * (int)g.ldb + 4 * ld_piece);
@@ -249,7 +274,9 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   tile_rc(q, rt, ct);
   rt = __builtin_amdgcn_readfirstlane(rt);
   ct = __builtin_amdgcn_readfirstlane(ct);
-  aim(rt * BM, ct * BN);
+  // (listed columns: a tile's "first column" is its number, see aim and commit)
+  auto col_arg = [&](int c) { return listed ? c : c * BN; };
+  aim(rt * BM, col_arg(ct));
   int stg = 0;   // LDS stage that holds (or is receiving) the slab of the multiply step in work
   load_norm(0);
   issue(stg, 0);
@@ -261,12 +288,23 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   unsigned int drawn = 0;
   auto commit = [&](int col0, int par) {
     SKM_VMCNT(0);
+    if (listed) {   // the tile's centroid ids, ascending, for the search below
+      if (tid >= BM) s_cid[tid - BM] = cid_reg < 0 ? 0x7fffffff : cid_reg;
+      __syncthreads();
+    }
     if (tid < BM) {
       s_tau[par][tid] = tau_reg;
       // the incumbent of this row, if it is a column of this tile, starts dead: find the thread and the
       // accumulator element that hold (row tid, column prev - col0).  (Every thread emptied its own marks right
       // after the previous commit's barrier, and has crossed a multiply step's barrier since.)
-      const int cl = prev_reg - col0;
+      int cl = prev_reg - col0;
+      if (listed) {   // position of the incumbent among the listed ids, if it is one of them
+        int lo = 0;
+#pragma unroll
+        for (int step = BN / 2; step > 0; step >>= 1)
+          if (s_cid[lo + step] <= prev_reg) lo += step;
+        cl = (prev_reg >= 0 && s_cid[lo] == prev_reg) ? lo : -1;
+      }
       if (cl >= 0 && cl < BN) {
         const int rr = tid & 31;
         const int lane_t = ((rr >> 2) & 1) * 32 + (cl & 31);
@@ -279,10 +317,10 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     if (tid == 0) drawn = atomicAdd(ctr, 1u);
     __syncthreads();
   };
-  commit(ct * BN, 0);
+  commit(col_arg(ct), 0);
 
   for (int tile_no = 0;; ++tile_no) {
-    const int row0 = rt * BM, col0 = ct * BN;
+    const int row0 = rt * BM, col0 = col_arg(ct);
     const int par = tile_no & 1;
 
     f32x16 acc[TM][TN];
@@ -292,14 +330,15 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int b = 0; b < TN; ++b)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-    int gc[TN];
+    int gc[TN];   // centroid of this lane's accumulator columns (listed columns: from the committed ids, INT_MAX = none)
 #pragma unroll
-    for (int b = 0; b < TN; ++b) gc[b] = col0 + wn * WTN + b * 32 + r32;
+    for (int b = 0; b < TN; ++b) gc[b] = listed ? s_cid[wn * WTN + b * 32 + r32] : col0 + wn * WTN + b * 32 + r32;
 
     // one alive-bit per accumulator element
     unsigned long long bits = ~s_dead[tid];
     s_dead[tid] = 0ull;
-    if (row0 + BM > g.M || col0 + BN > g.N) {   // ragged edge tile: rows / columns past the end start dead
+    if (row0 + BM > g.M || (listed ? (gc[0] >= g.N || gc[1] >= g.N) : col0 + BN > g.N)) {
+      // ragged edge tile: rows / columns past the end (or not listed) start dead
 #pragma unroll
       for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -434,7 +473,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       tile_rc(q, nrt_, nct_);
       nrt_ = __builtin_amdgcn_readfirstlane(nrt_);
       nct_ = __builtin_amdgcn_readfirstlane(nct_);
-      aim(nrt_ * BM, nct_ * BN);
+      aim(nrt_ * BM, col_arg(nct_));
       load_norm(0);
       issue(stg, 0);   // both stages are free: every wavefront has passed the barrier of the last multiply step
       load_rows(nrt_ * BM);
@@ -529,7 +568,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
     rt = nrt_;
     ct = nct_;
     if (tid == 0) s_q[(tile_no + 2) & 3] = (int)drawn;
-    commit(ct * BN, par ^ 1);   // its barrier also ends this tile: everyone is done with the tile's LDS
+    commit(col_arg(ct), par ^ 1);   // its barrier also ends this tile: everyone is done with the tile's LDS
   }
 }
 
@@ -546,8 +585,11 @@ hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
     hipError_t rc;
     int wgs = 0;
     Setup() {
-      rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel),
+      rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel<false>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (rc == hipSuccess)
+        rc = hipFuncSetAttribute(reinterpret_cast<const void *>(progressive_kernel<true>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       int dev = 0, cus = 256;
       (void)hipGetDevice(&dev);
       (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -557,14 +599,20 @@ hipError_t launch_progressive(const ProgArgs &g, hipStream_t st) {
   static const Setup setup;
   if (setup.rc != hipSuccess) return setup.rc;
   const int wgs = setup.wgs;
+  if ((g.col_list != nullptr) != (g.tile_rt != nullptr) || (g.col_list != nullptr) != (g.ntiles != nullptr))
+    return hipErrorInvalidValue;
   const int64_t ntiles = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (ntiles > 0x7fffffffLL) return hipErrorInvalidValue;
   const int64_t grid = std::max<int64_t>(8, std::min<int64_t>(wgs, (ntiles + 7) / 8 * 8));
-  hipLaunchKernelGGL(progressive_kernel, dim3((unsigned)grid), dim3(NT), smem, st, g);
+  if (g.col_list)
+    hipLaunchKernelGGL(progressive_kernel<true>, dim3((unsigned)grid), dim3(NT), smem, st, g);
+  else
+    hipLaunchKernelGGL(progressive_kernel<false>, dim3((unsigned)grid), dim3(NT), smem, st, g);
   return hipGetLastError();
 }
 
 int64_t progressive_tiles(int64_t rows, int32_t k) { return ((rows + BM - 1) / BM) * (int64_t)((k + BN - 1) / BN); }
 int32_t progressive_tile_pairs() { return BM * BN; }
+int32_t progressive_tile_cols() { return BN; }
 
 }  // namespace skm

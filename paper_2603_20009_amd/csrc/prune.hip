@@ -31,14 +31,19 @@ template <bool STATS>
 __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
   __shared__ float s_ratio[kMaxBlocks + 1];
   __shared__ unsigned int s_enter[kMaxBlocks + 1];
-  __shared__ unsigned int s_completed;
+  __shared__ unsigned int s_completed, s_steps, s_pairs;
   const int tid = threadIdx.x;
   for (int m = tid; m <= a.nb; m += PRUNE_THREADS) {
     s_ratio[m] = a.ratio[m];
     s_enter[m] = 0u;
   }
-  if (tid == 0) s_completed = 0u;
+  if (tid == 0) {
+    s_completed = 0u;
+    s_steps = 0u;
+    s_pairs = 0u;
+  }
   __syncthreads();
+  unsigned int my_steps = 0u, my_pairs = 0u;   // (lane 0 of a group) block steps gathered and pairs taken: the kernel's traffic
 
   // The list is kSubLists parts, one per XCD of the kernel that made it (workgroup id mod 8), each in the order in
   // which that XCD walked its tiles: neighbouring entries share point rows and centroid blocks.  A workgroup reads
@@ -61,7 +66,10 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
     acc = pr.p;
     tau = pr.tau;
   };
-  if (active) unpack(list[p]);
+  if (active) {
+    unpack(list[p]);
+    ++my_pairs;
+  }
   unsigned int pn = p + ngroups;   // the entry after this one, requested ahead of its use
   Pair nx = {0, 0, 0.f, 0.f};
   if (pn < total) nx = list[pn];
@@ -89,6 +97,7 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
         s = fmaf(dw, dw, s);
         acc += row8_sum(s);
         ++m;
+        ++my_steps;
       }
       const bool done = m >= a.nb;
       bool drop = false;
@@ -106,15 +115,22 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
         active = p < total;
         if (active) {
           unpack(nx);
+          ++my_pairs;
           pn = p + ngroups;
           if (pn < total) nx = list[pn];
         }
       }
     }
   }
+  if (q == 0) {
+    if (my_steps) atomicAdd(&s_steps, my_steps);
+    if (my_pairs) atomicAdd(&s_pairs, my_pairs);
+  }
   __syncthreads();
   unsigned long long *sc = a.scal + (size_t)(blockIdx.x & (kStatReplicas - 1)) * SC_COUNT;
   if (tid == 0 && s_completed) atomicAdd(sc + SC_COMPLETED, (unsigned long long)s_completed);
+  if (tid == 0 && s_steps) atomicAdd(sc + SC_GATHER_PB, (unsigned long long)s_steps);
+  if (tid == 0 && s_pairs) atomicAdd(sc + SC_GATHER_PAIRS, (unsigned long long)s_pairs);
   if (STATS) {
     for (int mm = tid; mm < a.nb; mm += PRUNE_THREADS)
       if (s_enter[mm]) atomicAdd(sc + SC_ENTER + mm, (unsigned long long)s_enter[mm]);

@@ -96,8 +96,8 @@ void gemm_debug_config(int tile256, int panel_cols, int64_t max_tiles);
 
 // Device scalars of one assignment step.  Every workgroup adds to the replica (blockIdx & (kStatReplicas-1))
 // so that same-address atomics do not serialise; the host sums the replicas.
-enum { SC_COMPLETED = 0, SC_CHANGED = 1, SC_SURVIVORS = 2, SC_DENSE_DIMS = 3, SC_DENSE_PB = 4, SC_ENTER = 5,
-       SC_COUNT = 5 + kMaxBlocks };
+enum { SC_COMPLETED = 0, SC_CHANGED = 1, SC_SURVIVORS = 2, SC_DENSE_DIMS = 3, SC_DENSE_PB = 4, SC_GATHER_PB = 5,
+       SC_GATHER_PAIRS = 6, SC_SCREEN_DIMS = 7, SC_LISTED_TILES = 8, SC_ENTER = 9, SC_COUNT = 9 + kMaxBlocks };
 constexpr int kStatReplicas = 32;
 // The hand-over list is split in kSubLists equal parts, one per XCD (workgroup id mod 8), each with its own
 // fill counter (counters are kSubListStride words apart).
@@ -140,10 +140,37 @@ struct ProgArgs {
   unsigned long long *best;       // [n] packed (distance, centroid)
   unsigned long long *scal;       // [kStatReplicas][SC_COUNT] step scalars (SC_SURVIVORS, SC_COMPLETED, SC_DENSE_*, SC_ENTER..)
   int32_t block_stats;            // also count pairs entering every trailing block (SC_ENTER + m)
+  // Listed columns (after launch_screen; all NULL otherwise): tile t is row tile tile_rt[t] against the 128 centroids
+  // col_list[128 t ..] (ascending ids, -1 = none); *ntiles tiles in all.
+  const int32_t *tile_rt = nullptr, *col_list = nullptr, *ntiles = nullptr;
 };
 hipError_t launch_progressive(const ProgArgs &g, hipStream_t st);
+
+// Low-precision first filter (screen.hip): one fp16 product on the first d' dimensions and the first test
+// theta(d', tau) widened by the error bound of the dropped halves; then, per row tile of 128 points, the centroids
+// that some point of the tile may still pass, as an ascending id list padded with -1 to a multiple of 128.
+// Outputs: cnt[row tiles], first[row tiles] (first tile of 128 listed columns of every row tile), *ntiles,
+// col_list[128 * ntiles], tile_rt[ntiles]; capacity needed: one tile per (row tile, column tile) of the full problem.
+struct ScreenLaunch {
+  const uint32_t *A; int64_t lda; int32_t M;
+  const uint32_t *B; int64_t ldb; int32_t N;
+  const unsigned int *a_absmax, *b_absmax;
+  int32_t ds, dprime;
+  float ratio0;              // theta(d', tau) / tau
+  const float *tau;          // [n], indexed by row_base + row
+  int64_t row_base;
+  const float *xn;           // [n] ||x_i[0 : d')||^2, indexed like tau
+  const float *yn;           // [N] ||y_j[0 : d')||^2
+  float *arow, *ycol;        // scratch: [M] and [N] (the test's per-point and per-centroid terms)
+  uint32_t *colmask;         // scratch: [row tiles][4 * column tiles]
+  int32_t *cnt, *first, *ntiles, *col_list, *tile_rt;   // (ntiles: two words, the second is scratch)
+  unsigned int *tile_counter;   // [8 * kSubListStride], zero before the launch
+  unsigned long long *scal;     // step scalars (SC_SCREEN_DIMS)
+};
+hipError_t launch_screen(const ScreenLaunch &a, hipStream_t st);
 int64_t progressive_tiles(int64_t rows, int32_t k);
 int32_t progressive_tile_pairs();
+int32_t progressive_tile_cols();
 
 // ---------------------------------------------------------------- pruning
 struct PruneArgs {
@@ -159,7 +186,7 @@ struct PruneArgs {
   int32_t nb;            // trailing blocks
   const float *ratio;    // [nb + 1] theta ratio at checkpoint m, t_m = min(d, d' + 64 m) (device array)
   unsigned long long *best;        // [n] packed (distance, centroid)
-  unsigned long long *scal;        // [kStatReplicas][SC_COUNT]: SC_COMPLETED, and SC_ENTER + m when block_stats
+  unsigned long long *scal;        // [kStatReplicas][SC_COUNT]: SC_COMPLETED, SC_GATHER_*, and SC_ENTER + m when block_stats
   int32_t block_stats;
 };
 hipError_t launch_prune(const PruneArgs &a, hipStream_t st);

@@ -23,6 +23,8 @@ class TraceRow(C.Structure):
         ("objective", C.c_double), ("prune_frac", C.c_double), ("recall", C.c_double),
         ("survivors", C.c_int64), ("completed", C.c_int64), ("changed", C.c_int64), ("nempty", C.c_int64),
         ("dense_dims", C.c_int64), ("dense_pair_blocks", C.c_int64),
+        ("gather_pair_blocks", C.c_int64), ("gather_pairs", C.c_int64),
+        ("screen_dims", C.c_int64), ("listed_tiles", C.c_int64),
         ("dprime", C.c_int32), ("nblocks", C.c_int32),
         ("enter", C.c_int64 * MAX_BLOCKS),
         ("ms_tau", C.c_float), ("ms_gemm", C.c_float), ("ms_prune", C.c_float), ("ms_update", C.c_float),
@@ -50,7 +52,8 @@ class Params(C.Structure):
         ("queries", C.c_void_p), ("gt", C.c_void_p),
         ("stream", C.c_void_p), ("trace", C.POINTER(Trace)), ("pair_budget", C.c_int64),
         ("dense_frac", C.c_float), ("sample_frac", C.c_float), ("angular", C.c_int32), ("full_update", C.c_int32),
-        ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64), ("conv_tol", C.c_float), ("tau_group", C.c_int32),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64), ("conv_tol", C.c_float), ("screen", C.c_int32),
+        ("tau_group", C.c_int32),
     ]
 
 
@@ -167,6 +170,7 @@ class FitOptions:
     full_update: bool = False
     conv_tol: float = 0.0
     tau_group: int = 0
+    screen: int = 0                          # low-precision first filter: 0 = by the previous step's prune fraction, 1 = always, -1 = never
     own_workspace: bool = False              # True: the library allocates and frees its workspace inside the call
 
 
@@ -183,7 +187,9 @@ class FitResult:
 def _row_dict(r: TraceRow) -> dict:
     return dict(objective=r.objective, prune_frac=r.prune_frac, recall=r.recall, survivors=int(r.survivors),
                 completed=int(r.completed), changed=int(r.changed), nempty=int(r.nempty),
-                dense_dims=int(r.dense_dims), dense_pair_blocks=int(r.dense_pair_blocks), dprime=int(r.dprime),
+                dense_dims=int(r.dense_dims), dense_pair_blocks=int(r.dense_pair_blocks),
+                gather_pair_blocks=int(r.gather_pair_blocks), gather_pairs=int(r.gather_pairs),
+                screen_dims=int(r.screen_dims), listed_tiles=int(r.listed_tiles), dprime=int(r.dprime),
                 nblocks=int(r.nblocks), enter=[int(v) for v in r.enter], ms_tau=r.ms_tau, ms_gemm=r.ms_gemm,
                 ms_prune=r.ms_prune, ms_update=r.ms_update, ms_etr=r.ms_etr, ms_step=r.ms_step)
 
@@ -218,6 +224,7 @@ def _params(o: FitOptions, keep: list, trace: Trace | None) -> Params:
     p.full_update = int(o.full_update)
     p.conv_tol = o.conv_tol
     p.tau_group = o.tau_group
+    p.screen = o.screen
     return p
 
 

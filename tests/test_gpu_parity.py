@@ -156,6 +156,55 @@ def test_pruned_step(skm, orc, dg, n, d, k, dp, budget, dense):
     assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])
     assert row["objective"] == pytest.approx(ref.dist.sum(), rel=1e-5)
     assert row["changed"] == int((a != prev).sum())
+    # every (pair, block) step ran either inside a dense tile or in the gather kernel
+    if row["nblocks"] <= 32:
+        assert row["dense_pair_blocks"] + row["gather_pair_blocks"] == sum(row["enter"][: row["nblocks"]])
+    assert (row["gather_pairs"] == 0) == (row["gather_pair_blocks"] == 0) and row["gather_pairs"] <= row["survivors"]
+    if dense == 0.0:
+        assert row["gather_pairs"] == 0
+    if dense == 1.0 and row["nblocks"] > 0:
+        assert row["gather_pairs"] == row["survivors"] and row["dense_pair_blocks"] == 0
+
+
+@pytest.mark.parametrize("dense", [0.0125, 1.0])
+@pytest.mark.parametrize("n,d,k,dp,budget", [
+    (2000, 128, 100, 0, 0),
+    (3000, 208, 257, 0, 0),          # d' = 32; three column tiles, the last with one centroid
+    (1000, 1536, 64, 0, 0),
+    (1500, 1536, 300, 160, 0),       # d' = 160: the first slab starts 16 dimensions before the row
+    (4000, 100, 50, 48, 0),          # padded rows
+    (5000, 128, 129, 0, 5248),       # 5 chunks of rows
+    (6000, 64, 1100, 16, 0),         # nine column tiles: most are dead for a row tile
+])
+def test_pruned_step_with_low_precision_filter(skm, orc, dg, n, d, k, dp, budget, dense):
+    """The same step with the one-product first filter in front (params->screen = 1): the exact kernel then only sees
+    the centroids that filter lists for a row tile.  Nothing that Algorithm 1's first test keeps may be lost: labels,
+    distances and every counter must match the oracle exactly as without the filter."""
+    say("screened", n, d, k, dp, budget, dense)
+    X, R, Y, Xr, Yr, prev = pruned_case(orc, dg, n, d, k, n + k, "linear" if d < 512 else "embed")
+    dp = dp or orc.dprime_init(d)
+    ref = orc.assign_pruned(Xr, Yr, prev, dp, EPS0, 0)
+    opts = skm.FitOptions(R=cuda(R), block_stats=True, pair_budget=budget, dense_frac=dense, screen=1)
+    a, dist, row = skm.assign(cuda(X), cuda(Y), cuda(prev), dp, opts)
+    a = a.cpu().numpy()
+    check_assignment(a, ref.assign, Xr, Yr)
+    same = a == ref.assign
+    assert np.abs(dist.cpu().numpy()[same] - ref.dist[same]).max() < 2e-5 * max(1.0, ref.dist.max())
+    surv_ref = n * (k - 1) - ref.pruned_first
+    assert abs(row["survivors"] - surv_ref) <= max(2, 1e-3 * surv_ref)
+    for m in range(row["nblocks"]):
+        assert abs(row["enter"][m] - ref.enter[m]) <= max(2, 1e-3 * ref.enter[m])
+    assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])
+    assert row["objective"] == pytest.approx(ref.dist.sum(), rel=1e-5)
+    assert row["changed"] == int((a != prev).sum())
+    nrt, nct = -(-n // 128), -(-k // 128)
+    assert row["screen_dims"] > 0 and 0 < row["listed_tiles"] <= nrt * nct
+    # without the filter the step gives the same labels (the tests applied to a pair are the same)
+    b, _, row0 = skm.assign(cuda(X), cuda(Y), cuda(prev), dp, skm.FitOptions(R=cuda(R), block_stats=True,
+                                                                              pair_budget=budget, dense_frac=dense, screen=-1))
+    assert row0["screen_dims"] == 0 and row0["listed_tiles"] == 0
+    assert row0["survivors"] == row["survivors"] and row0["enter"] == row["enter"] and row0["completed"] == row["completed"]
+    assert (b.cpu().numpy() != a).sum() <= 1
 
 
 def test_pruned_step_without_previous_assignment(skm, orc, dg):
@@ -1008,7 +1057,7 @@ def _witness(orc, Xr, Yr, i, j, tau, d, dprime):
     return abs(diff2.sum() - tau) <= 2e-5 * max(tau, 1e-30)
 
 
-def lockstep_fit(skm, orc, X, R, k, iters, seed, adjust):
+def lockstep_fit(skm, orc, X, R, k, iters, seed, adjust, screen=0):
     """Algorithm 1 driven by the oracle; at every iteration the library's step calls (skm_assign_exact /
     skm_assign_ex, skm_update) get the oracle's state (centroids Y_t and labels a_t, rounded to fp32 once and used by
     both sides) and must meet the contract with no relaxation: >= 99.9 % of the labels equal, every other one a
@@ -1019,7 +1068,7 @@ def lockstep_fit(skm, orc, X, R, k, iters, seed, adjust):
     Xr = orc.rotate(X, R).astype(np.float32)          # the rotated points both sides work on
     Xr64 = Xr.astype(np.float64)
     Xg = cuda(Xr)
-    plain = dict(rotate=False, eps0=EPS0, block_stats=True)
+    plain = dict(rotate=False, eps0=EPS0, block_stats=True, screen=screen)
     Y = Xr[orc.sample_rows(seed, n, k)].copy()         # fp32 centroids, the state handed from step to step
     rng_state = orc.rng_stream(seed, 1)
     dp = orc.dprime_init(d)
@@ -1082,16 +1131,19 @@ def lockstep_fit(skm, orc, X, R, k, iters, seed, adjust):
     return on_threshold
 
 
-def test_lockstep_fit_c1(skm, orc, dg):
-    """Workload C1, all 10 iterations and the final pass, the strict contract at every step."""
+@pytest.mark.parametrize("screen", [-1, 1])
+def test_lockstep_fit_c1(skm, orc, dg, screen):
+    """Workload C1, all 10 iterations and the final pass, the strict contract at every step; without and with the
+    low-precision first filter in front of every pruned step."""
     X = dg.config_data("C1").numpy()
-    on_thr = lockstep_fit(skm, orc, X, orc.random_rotation(128, 42), 100, 10, 42, adjust=True)
+    on_thr = lockstep_fit(skm, orc, X, orc.random_rotation(128, 42), 100, 10, 42, adjust=True, screen=screen)
     assert on_thr <= 2
 
 
-def test_lockstep_fit_scaled_c2(skm, orc, dg):
+@pytest.mark.parametrize("screen", [-1, 1])
+def test_lockstep_fit_scaled_c2(skm, orc, dg, screen):
     """The first 131 072 rows of workload C2 (d = 1536, k = 1024), all 10 iterations and the final pass."""
     torch.cuda.empty_cache()
     X = dg.config_data("C2", device="cuda", n=131_072).cpu().numpy()
-    on_thr = lockstep_fit(skm, orc, X, orc.random_rotation(1536, 42), 1024, 10, 42, adjust=True)
+    on_thr = lockstep_fit(skm, orc, X, orc.random_rotation(1536, 42), 1024, 10, 42, adjust=True, screen=screen)
     assert on_thr <= 4

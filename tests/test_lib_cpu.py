@@ -34,9 +34,9 @@ def test_every_declared_symbol_is_exported(skm):
 
 def test_struct_sizes_match_header(skm):
     # sizes implied by include/skm.h on LP64: catches a field added on one side only
-    assert C.sizeof(skm.TraceRow) == 3 * 8 + 6 * 8 + 2 * 4 + 32 * 8 + 6 * 4
+    assert C.sizeof(skm.TraceRow) == 3 * 8 + 10 * 8 + 2 * 4 + 32 * 8 + 6 * 4
     assert C.sizeof(skm.Trace) == 4 * 4 + 8 * 4 + 8
-    assert C.sizeof(skm.Params) == 10 * 4 + 2 * 8 + 6 * 4 + 4 * 8 + 8 + 2 * 4 + 2 * 4 + 2 * 8 + 2 * 4
+    assert C.sizeof(skm.Params) == 10 * 4 + 2 * 8 + 6 * 4 + 4 * 8 + 8 + 2 * 4 + 2 * 4 + 2 * 8 + 4 * 4
     p = skm.Params()
     skm.lib().skm_params_default(C.byref(p))
     assert (p.dprime_frac, p.adjust_dprime, p.final_assign, p.rotate, p.etr) == (0.125, 1, 1, 1, 0)
