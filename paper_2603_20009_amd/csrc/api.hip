@@ -388,6 +388,7 @@ struct Ctx {
   double last_prune_frac = -1.0;     // of the previous pruned step of this context (-1: none yet)
   uint32_t *colmask = nullptr;
   float *scr_arow = nullptr, *scr_ycol = nullptr;
+  uint32_t *Xh = nullptr, *Yh = nullptr;   // [n][ds / 2 + 16], [k][ds / 2 + 16]: the hi halves of Xs, Ys as planes of their own
   int32_t *scr_cnt = nullptr, *scr_first = nullptr, *scr_ntiles = nullptr, *scr_cols = nullptr, *scr_tile_rt = nullptr;
   unsigned int *amax = nullptr;      // [AM_COUNT] magnitude bounds of the GEMM operands
   enum { AM_XR = 0, AM_Y = 1, AM_X = 2, AM_Q = 3, AM_QR = 4, AM_COUNT = 8 };
@@ -486,6 +487,8 @@ struct Ctx {
       HIPCHK(pool.get(&scr_ntiles, 2));   // the tile count, then a float scalar of the filter
       HIPCHK(pool.get(&scr_arow, (size_t)std::min<int64_t>(chunk_rows, n)));
       HIPCHK(pool.get(&scr_ycol, (size_t)k));
+      HIPCHK(pool.get(&Xh, (size_t)n * (ds / 2 + 16)));
+      HIPCHK(pool.get(&Yh, (size_t)k * (ds / 2 + 16)));
       HIPCHK(pool.get(&scr_cols, (size_t)tiles_chunk * 128));
       HIPCHK(pool.get(&scr_tile_rt, (size_t)tiles_chunk));
     }
@@ -708,7 +711,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     else
       HIPCHK(hipMemcpyAsync(c.pos_to_id, c.up.order, sizeof(int32_t) * (size_t)c.n, hipMemcpyDeviceToDevice, c.st));
     HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st, c.xnp, c.Xs,
-                           c.amax + Ctx::AM_XR, c.pos_to_id, c.Xr2, c.assign));
+                           c.amax + Ctx::AM_XR, c.pos_to_id, c.Xr2, c.assign, c.Xh));
     std::swap(c.prev, c.assign);   // the incumbents in the new order; the other buffer receives this step's labels
     if (c.point_keys)   // (up.order is scratch until the next full update rebuilds it)
       HIPCHK(launch_remap_key_ids(c.point_keys, c.n_point_keys, c.pos_to_id, c.n, c.up.order, c.st));
@@ -718,7 +721,8 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   } else {
     // the first pruned step of a context also writes the tables that depend on the points only
     HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, c.best, c.st, c.xnp_valid ? nullptr : c.xnp,
-                           c.xnp_valid ? nullptr : c.Xs, c.amax + Ctx::AM_XR));
+                           c.xnp_valid ? nullptr : c.Xs, c.amax + Ctx::AM_XR, nullptr, nullptr, nullptr,
+                           c.xnp_valid ? nullptr : c.Xh));
   }
   c.order_fresh = false;
   c.xnp_valid = true;
@@ -726,7 +730,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   // first test, which the previous step's prune fraction predicts.
   const bool screen = c.colmask && nb > 0 &&
                       (c.screen_mode > 0 || (c.screen_mode == 0 && c.last_prune_frac >= 0.90));
-  HIPCHK(launch_split_rows(c.Y, c.ds, c.k, c.ds, c.amax + Ctx::AM_Y, c.Ys, c.st));
+  HIPCHK(launch_split_rows(c.Y, c.ds, c.k, c.ds, c.amax + Ctx::AM_Y, c.Ys, c.st, screen ? c.Yh : nullptr));
   tm.mark(ST_TAU);
   for (int32_t ch = 0; ch < c.nchunks; ++ch) {
     const int64_t r0 = (int64_t)ch * c.chunk_rows;
@@ -745,7 +749,8 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     g.best = c.best; g.scal = c.scal; g.block_stats = c.block_stats ? 1 : 0;
     if (screen) {
       ScreenLaunch sl{};
-      sl.A = g.A; sl.lda = g.lda; sl.M = g.M; sl.B = g.B; sl.ldb = g.ldb; sl.N = g.N;
+      sl.A = c.Xh + r0 * (c.ds / 2 + 16); sl.lda = c.ds / 2 + 16; sl.M = g.M;
+      sl.B = c.Yh; sl.ldb = c.ds / 2 + 16; sl.N = g.N;
       sl.a_absmax = g.a_absmax; sl.b_absmax = g.b_absmax;
       sl.ds = c.ds; sl.dprime = dprime; sl.ratio0 = ratio[0];
       sl.tau = c.tau; sl.row_base = r0;

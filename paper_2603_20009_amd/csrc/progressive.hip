@@ -37,8 +37,10 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 // 16 (g + 1) of the row: 8 words of hi halves (fp16 of the scaled value, two per word), then 8 words of lo
 // halves (fp16 of the remainder).  Granule positions 0 and ds / 16 + 1 are zero, so that a 32-dimension slab
 // starting 16 dimensions before the row or ending 16 after it reads zeros.  Row stride ds + 32 words.
+// out_hi (optional): the hi halves once more as a plane of their own, ds / 2 + 16 words a row (8 zero words, the row two
+// dimensions a word, 8 zero words): what the low-precision first filter reads, 64 contiguous bytes per row and slab.
 __global__ void __launch_bounds__(256) split_rows_kernel(const float *A, int64_t lda, int64_t rows, int32_t ds,
-                                                         const unsigned int *absmax, uint32_t *out) {
+                                                         const unsigned int *absmax, uint32_t *out, uint32_t *out_hi) {
   const float scale = split_scale(*absmax);
   const int per_row = ds / 4 + 8;   // float4 pieces per output row, pads included
   const int64_t total = rows * per_row;
@@ -59,16 +61,18 @@ __global__ void __launch_bounds__(256) split_rows_kernel(const float *A, int64_t
     uint32_t *dst = out + r * (int64_t)(ds + 32) + 16 * gpos;
     *reinterpret_cast<uint2 *>(dst + 2 * q) = hi;
     *reinterpret_cast<uint2 *>(dst + 8 + 2 * q) = lo;
+    if (out_hi) *reinterpret_cast<uint2 *>(out_hi + r * (int64_t)(ds / 2 + 16) + 2 * piece) = hi;
   }
 }
 hipError_t launch_split_rows(const float *A, int64_t lda, int64_t rows, int32_t ds, const unsigned int *absmax,
-                             uint32_t *out, hipStream_t st) {
+                             uint32_t *out, hipStream_t st, uint32_t *out_hi) {
   if (rows <= 0) return hipSuccess;
   if (ds % 16 != 0 || lda % 4 != 0 || (reinterpret_cast<uintptr_t>(A) & 15u) || (reinterpret_cast<uintptr_t>(out) & 15u))
     return hipErrorInvalidValue;
   const int64_t total = rows * (ds / 4 + 8);
   const int64_t blocks = std::min<int64_t>((total + 255) / 256, 1 << 16);
-  hipLaunchKernelGGL(split_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, A, lda, rows, ds, absmax, out);
+  if (reinterpret_cast<uintptr_t>(out_hi) & 15u) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(split_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, A, lda, rows, ds, absmax, out, out_hi);
   return hipGetLastError();
 }
 

@@ -49,7 +49,7 @@ constexpr int DEPTH = 3, NSTAGE = 4;              // slabs requested ahead of th
 }  // namespace
 
 struct ScreenArgs {
-  const uint32_t *A;   // split-fp16 copy of the points of the chunk (launch_split_rows layout), row stride lda words
+  const uint32_t *A;   // hi halves of the split-fp16 copy of the chunk's points (launch_split_rows' out_hi), row stride lda words
   int64_t lda;
   int32_t M;
   const uint32_t *B;   // the same of the centroids
@@ -70,8 +70,8 @@ struct ScreenArgs {
 // LDS rows are 64 bytes (four 16-byte pieces: dims 8 c .. 8 c + 7 of the slab, c = 2 h + kh for half-slab h and lane
 // half kh); piece c of row r sits at position c ^ ((r >> 2) & 3), so that the 16-byte fragment reads of 16 consecutive
 // rows fall into 16 different bank groups.  Staging is global -> LDS directly, 16 bytes per lane, four lanes per row:
-// the lane that fills a position fetches the piece that belongs there.  In global memory the hi halves of half-slab h
-// are the first 8 words of a 16-word granule (see launch_split_rows).  The kernel is persistent: every XCD walks a
+// the lane that fills a position fetches the piece that belongs there.  In global memory the hi halves of a row are
+// one contiguous plane (see launch_split_rows): a slab row is 64 contiguous bytes.  The kernel is persistent: every XCD walks a
 // contiguous range of tiles (column tile fastest inside panels of 8 column tiles), its workgroups take every n-th;
 // the first slab of a workgroup's next tile is requested before the finished tile is tested.
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) screen_kernel(ScreenArgs g) {
@@ -105,10 +105,10 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int lrow = lane >> 2, lpos = lane & 3;
   const int ld_row = 16 * wave + lrow;                        // + 128 j
   const int ld_c = lpos ^ ((ld_row >> 2) & 3);                // piece that belongs at this lane's position
-  const int ld_words = 16 * (ld_c >> 1) + 4 * (ld_c & 1);     // its word offset inside the slab's 32 words
+  const int ld_words = 4 * ld_c;                              // its word offset inside the slab's 16 hi words
   const int koff = -((BK - g.dprime % BK) % BK);
   const int nslab = (g.dprime - koff) / BK;                   // slabs [koff, d')
-  const int kw0 = 16 + koff;
+  const int kw0 = 8 + koff / 2;                               // word of the hi plane where slab 0 starts
 
   // ---- the loading side runs DEPTH slabs ahead of the multiplying side, across tile boundaries (a tile of a
   // well-pruned step is two or three slabs: one tile's worth of loads in flight would leave the matrix cores waiting
@@ -142,7 +142,7 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       ++ltile;
     }
     uint32_t *sb = smem + (ljob & (NSTAGE - 1)) * STAGE_WORDS + 16 * wave * ROW_WORDS;
-    const int kw = kw0 + BK * ls;
+    const int kw = kw0 + (BK / 2) * ls;
 #pragma unroll
     for (int j = 0; j < A_LD; ++j)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(baseA + offA[j] + kw),
@@ -366,7 +366,7 @@ __global__ void __launch_bounds__(1024) max_value_kernel(const float *v, int32_t
 
 hipError_t launch_screen(const ScreenLaunch &a, hipStream_t st) {
   if (a.M <= 0 || a.N <= 0) return hipSuccess;
-  if (a.dprime % 16 != 0 || a.dprime < 16 || a.dprime > a.ds || a.lda != a.ds + 32 || a.ldb != a.ds + 32 ||
+  if (a.dprime % 16 != 0 || a.dprime < 16 || a.dprime > a.ds || a.lda != a.ds / 2 + 16 || a.ldb != a.ds / 2 + 16 ||
       (reinterpret_cast<uintptr_t>(a.A) & 15u) || (reinterpret_cast<uintptr_t>(a.B) & 15u) || a.N > (1 << 24))
     return hipErrorInvalidValue;
   constexpr size_t smem = (size_t)NSTAGE * STAGE_WORDS * sizeof(uint32_t);

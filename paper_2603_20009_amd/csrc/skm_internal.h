@@ -112,8 +112,10 @@ constexpr int kSubListStride = 16;
 // Split-fp16 copy of a matrix in the byte order of the progressive kernel's LDS tiles (launch_split_rows): row stride
 // ds + 32 words; dims 16 g .. 16 g + 15 of a row are the 16 words at 16 (g + 1): 8 words of hi halves, 8 of lo halves
 // of the values scaled by split_scale(*absmax); the 16 words before and after the row's data are zero.
+// out_hi (optional): the hi halves once more as a plane of their own (row stride ds / 2 + 16 words: 8 zero words, the
+// row two dimensions a word, 8 zero words), which the low-precision first filter reads.
 hipError_t launch_split_rows(const float *A, int64_t lda, int64_t rows, int32_t ds, const unsigned int *absmax,
-                             uint32_t *out, hipStream_t st);
+                             uint32_t *out, hipStream_t st, uint32_t *out_hi = nullptr);
 
 struct ProgArgs {
   const uint32_t *A;       // split-fp16 copy of the rotated points of the chunk (launch_split_rows)
@@ -200,10 +202,12 @@ hipError_t launch_prune(const PruneArgs &a, hipStream_t st);
 // Regrouping (order, xr_out, label_out: all or none): output slot p of every array above takes point order[p] (a
 // permutation of 0 .. n - 1); the row of that point is copied to xr_out[p] (row stride ds) and its label to
 // label_out[p].  `assign` is still indexed by point.
+// xh (optional, with xs): also the plane of hi halves of launch_split_rows' out_hi.
 hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
                            const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st,
                            float *xnp = nullptr, uint32_t *xs = nullptr, const unsigned int *x_absmax = nullptr,
-                           const int32_t *order = nullptr, float *xr_out = nullptr, int32_t *label_out = nullptr);
+                           const int32_t *order = nullptr, float *xr_out = nullptr, int32_t *label_out = nullptr,
+                           uint32_t *xh = nullptr);
 // dst[idx[p]] = src[p] for 4-byte items
 hipError_t launch_scatter_by_index(const void *src, const int32_t *idx, int64_t n, void *dst, hipStream_t st);
 // order_out = order_in (points grouped by cluster, segment c = [off[c], off[c+1])) with every segment stably sorted by

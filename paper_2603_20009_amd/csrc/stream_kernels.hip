@@ -45,6 +45,7 @@ struct PrefixOut {
   int64_t n;
   int32_t ds;
   uint32_t *xs;      // [n][ds + 32] or NULL
+  uint32_t *xh;      // [n][ds / 2 + 16] or NULL (with xs): the hi halves as a plane of their own
   const unsigned int *absmax;   // bound of |X| (bit pattern) that fixes the scale of xs
   float scale;       // split_scale(*absmax), set by the kernel
   // Regrouping (all three or none): output slot p takes point order[p]; its row is copied to xr_out (row stride ds)
@@ -65,11 +66,18 @@ __device__ inline void emit_split(const PrefixOut &po, int64_t i, int c, const f
   uint32_t *dst = po.xs + i * (int64_t)(po.ds + 32) + 16 * (c / 16 + 1) + 2 * ((c / 4) & 3);
   *reinterpret_cast<uint2 *>(dst) = make_uint2(__builtin_bit_cast(unsigned int, h0), __builtin_bit_cast(unsigned int, h1));
   *reinterpret_cast<uint2 *>(dst + 8) = make_uint2(__builtin_bit_cast(unsigned int, l0), __builtin_bit_cast(unsigned int, l1));
+  if (po.xh)
+    *reinterpret_cast<uint2 *>(po.xh + i * (int64_t)(po.ds / 2 + 16) + 8 + c / 2) =
+        make_uint2(__builtin_bit_cast(unsigned int, h0), __builtin_bit_cast(unsigned int, h1));
 }
 // the zero granules before and after the data of row i (lanes 0..3 and 4..7, 16 bytes each)
 __device__ inline void emit_split_pads(const PrefixOut &po, int64_t i, int lane) {
   if (lane < 8) {
     uint32_t *dst = po.xs + i * (int64_t)(po.ds + 32) + (lane < 4 ? 4 * lane : po.ds + 16 + 4 * (lane - 4));
+    *reinterpret_cast<uint4 *>(dst) = make_uint4(0u, 0u, 0u, 0u);
+  } else if (lane < 12 && po.xh) {   // the 8 zero words at either end of the hi plane's row
+    const int e = lane - 8;
+    uint32_t *dst = po.xh + i * (int64_t)(po.ds / 2 + 16) + (e >> 1) * (8 + po.ds / 2) + 4 * (e & 1);
     *reinterpret_cast<uint4 *>(dst) = make_uint4(0u, 0u, 0u, 0u);
   }
 }
@@ -219,7 +227,7 @@ __global__ void __launch_bounds__(256) tau_init_kernel(const float *Xr, int64_t 
 hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, const float *Y, int64_t ldy,
                            const int32_t *assign, float *tau, unsigned long long *best, hipStream_t st, float *xnp,
                            uint32_t *xs, const unsigned int *x_absmax, const int32_t *order, float *xr_out,
-                           int32_t *label_out) {
+                           int32_t *label_out, uint32_t *xh) {
   if (n <= 0) return hipSuccess;
   const int nv = (ds + 255) / 256;
   const bool batch = xnp != nullptr && nv <= 8 && ds / 16 <= kPrefixStageRows;
@@ -229,7 +237,8 @@ hipError_t launch_tau_init(const float *Xr, int64_t ldx, int64_t n, int32_t ds, 
   if (xs && (ds % 16 != 0 || !x_absmax)) return hipErrorInvalidValue;
   if ((order != nullptr) != (xr_out != nullptr) || (order != nullptr) != (label_out != nullptr)) return hipErrorInvalidValue;
   if (xr_out && (reinterpret_cast<uintptr_t>(xr_out) & 15u)) return hipErrorInvalidValue;
-  const PrefixOut po{xnp, n, ds, xs, x_absmax, 0.f, order, xr_out, label_out};
+  if (xh && (!xs || (reinterpret_cast<uintptr_t>(xh) & 15u))) return hipErrorInvalidValue;
+  const PrefixOut po{xnp, n, ds, xs, xh, x_absmax, 0.f, order, xr_out, label_out};
 #define SKM_TAU_LAUNCH(NV)                                                                                      \
   do {                                                                                                          \
     if (batch && NV > 0)                                                                                        \
