@@ -150,9 +150,12 @@ typedef struct skm_params {
                             kernel, one fp16 product on the first d' dimensions and the first test theta(d', tau)
                             widened by the rounding bound find, per tile of 128 points, the centroids that can still
                             pass; the exact kernel (three products, exact tests and counters) then runs on those
-                            only.  0 = in steps that follow a step which cut at least 90 % of the pairs at the first
-                            test, 1 = in every pruned step, -1 = never.  Execution strategy only: a pair cut by the
-                            widened test is cut by the exact one as well */
+                            only.  In iteration 1, where nothing prunes, the same one-product multiply over all
+                            dimensions lists for every point the centroids that can be its nearest (those within the
+                            rounding bound of the row's smallest approximate distance), and only those get their exact
+                            distance.  0 = in pruned steps that follow a step which cut at least 90 % of the pairs at
+                            the first test, and in iteration 1 from 2048 centroids on; 1 = in every step; -1 = never.
+                            Execution strategy only: a pair the filter drops is dropped by the exact arithmetic too */
   int32_t tau_group;     /* 0    : centroids after which a point's threshold tau is refreshed inside a step.  0 (= k):
                             tau keeps its initial value for the whole step, the only form this library runs (the
                             result is then independent of the order in which tiles are processed); any other value

@@ -389,6 +389,8 @@ struct Ctx {
   uint32_t *colmask = nullptr;
   float *scr_arow = nullptr, *scr_ycol = nullptr;
   uint32_t *Xh = nullptr, *Yh = nullptr;   // [n][ds / 2 + 16], [k][ds / 2 + 16]: the hi halves of Xs, Ys as planes of their own
+  int32_t pruned_steps = 0;                // pruned steps this context has completed
+  bool exact_filter_off = false;           // iteration 1 takes the full GEMM (set after a candidate-list overflow)
   int32_t *scr_cnt = nullptr, *scr_first = nullptr, *scr_ntiles = nullptr, *scr_cols = nullptr, *scr_tile_rt = nullptr;
   unsigned int *amax = nullptr;      // [AM_COUNT] magnitude bounds of the GEMM operands
   enum { AM_XR = 0, AM_Y = 1, AM_X = 2, AM_Q = 3, AM_QR = 4, AM_COUNT = 8 };
@@ -474,6 +476,10 @@ struct Ctx {
     // each of the kSubLists parts must hold what the tiles of one XCD can hand over
     const int64_t tiles_chunk = progressive_tiles(std::min<int64_t>(chunk_rows, n), k);
     sub_cap = ((tiles_chunk + kSubLists - 1) / kSubLists) * per_tile;
+    // the filtered iteration 1 lists a few candidates per point in the same list (if it ever overflows, the step is
+    // redone with the full GEMM): room for 16 per point of a chunk in each of the eight parts
+    if (screen_mode > 0 || (screen_mode == 0 && k >= 2 * progressive_tile_cols()))
+      sub_cap = std::max<int64_t>(sub_cap, 16 * std::min<int64_t>(chunk_rows, n));
     pair_cap = sub_cap * kSubLists;
     if (pair_cap >= ((int64_t)1 << 32)) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
     HIPCHK(pool.get(&pairs, (size_t)pair_cap));
@@ -638,8 +644,91 @@ struct StepStats {
   bool pruned = false;  // false for the exact step of iteration 1
 };
 
+// Iteration 1 with the low-precision filter in front (screen.hip, exact mode): one fp16 product over all dimensions
+// lists, for every point, the centroids that can be its nearest; the gather kernel takes their exact distances and the
+// packed minimum is the exact nearest centroid (lowest index on ties).  A third of the matrix work of the full
+// three-product GEMM; pays once there are enough centroids.
+int step_exact_filtered(Ctx &c, StageTimer &tm, StepStats &ss) {
+  tm.mark(ST_NONE);
+  if (int rc = c.clear_step_block()) return rc;
+  const int32_t nb_all = (c.ds + kBlockDims - 1) / kBlockDims;
+  if (nb_all > kMaxBlocks) return fail(SKM_EINTERNAL, "too many blocks");
+  if (!c.xnp_valid) {
+    // the points' split copy, its hi plane and their norms do not exist before the first pruned step: the pass that
+    // writes them runs now (its thresholds, against centroid 0, are discarded)
+    HIPCHK(launch_fill_u32(reinterpret_cast<unsigned int *>(c.prev), c.n, 0u, c.st));
+    HIPCHK(launch_tau_init(c.Xr, c.ldx, c.n, c.ds, c.Y, c.ds, c.prev, c.tau, nullptr, c.st, c.xnp, c.Xs,
+                           c.amax + Ctx::AM_XR, nullptr, nullptr, nullptr, c.Xh));
+    c.xnp_valid = true;
+  }
+  // ||y||^2 and the block-major copy of ALL dimensions (the gather kernel starts every pair at dimension 0)
+  HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, c.ds, c.ynorm, 0, nb_all, c.Ypdx, c.st));
+  if (int rc = c.measure_y()) return rc;
+  HIPCHK(launch_split_rows(c.Y, c.ds, c.k, c.ds, c.amax + Ctx::AM_Y, c.Ys, c.st, c.Yh));
+  HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
+  unsigned int *rowmin = reinterpret_cast<unsigned int *>(c.tau);   // (no thresholds in this step)
+  HIPCHK(launch_fill_u32(rowmin, c.n, 0xffffffffu, c.st));
+  float *ratio = c.ratio_host;
+  for (int m = 0; m <= nb_all; ++m) ratio[m] = 1.f;   // nothing is dropped on the way
+  HIPCHK(hipMemcpyAsync(c.ratio_dev, ratio, sizeof(float) * ((size_t)nb_all + 1), hipMemcpyHostToDevice, c.st));
+  tm.mark(ST_TAU);
+  for (int32_t ch = 0; ch < c.nchunks; ++ch) {
+    const int64_t r0 = (int64_t)ch * c.chunk_rows;
+    const int64_t rows = std::min<int64_t>(c.chunk_rows, c.n - r0);
+    unsigned int *fill = c.counters + (size_t)ch * kSubLists * kSubListStride;
+    ScreenLaunch sl{};
+    sl.A = c.Xh + r0 * (c.ds / 2 + 16); sl.lda = c.ds / 2 + 16; sl.M = (int32_t)rows;
+    sl.B = c.Yh; sl.ldb = c.ds / 2 + 16; sl.N = c.k;
+    sl.a_absmax = c.amax + Ctx::AM_XR; sl.b_absmax = c.amax + Ctx::AM_Y;
+    sl.ds = c.ds; sl.dprime = c.ds; sl.ratio0 = 1.f;
+    sl.tau = c.tau; sl.row_base = r0;
+    sl.xn = c.xnp + (int64_t)(c.ds / 16 - 1) * c.n;   // the full norms: the last row of the prefix table
+    sl.yn = c.ynorm;
+    sl.arow = c.scr_arow; sl.ycol = c.scr_ycol;
+    sl.colmask = c.colmask; sl.cnt = c.scr_cnt; sl.first = c.scr_first; sl.ntiles = c.scr_ntiles;
+    sl.col_list = c.scr_cols; sl.tile_rt = c.scr_tile_rt;
+    sl.scal = c.scal;
+    sl.exact = 1; sl.rowmin = rowmin; sl.pairs = c.pairs; sl.pair_count = fill; sl.sub_capacity = (unsigned int)c.sub_cap;
+    sl.overflow = c.counters + c.ncounters;
+    HIPCHK(launch_screen(sl, c.st));
+    PruneArgs pa{c.pairs, fill, (unsigned int)c.sub_cap, c.Xr, c.ldx, c.n, c.Ypdx, c.k, 0, c.ds, nb_all, c.ratio_dev,
+                 c.best, c.scal, 0};
+    HIPCHK(launch_prune(pa, c.st));
+  }
+  tm.mark(ST_GEMM);
+  // the packed minima already hold the direct distances
+  HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.k, c.obj_partial, nullptr,
+                                c.counters + c.ncounters, c.st));
+  HIPCHK(launch_sum_partials(c.obj_partial, finalize_blocks(c.n), c.obj, c.st));
+  tm.mark(ST_TAU);
+  if (int rc = c.fetch_step_block()) return rc;
+  HIPCHK(hipStreamSynchronize(c.st));
+  c.rb_cnt_valid = true;
+  const size_t nscal = (size_t)SC_COUNT * kStatReplicas;
+  ss = StepStats();
+  for (int r = 0; r < kStatReplicas; ++r) {
+    ss.gather_pair_blocks += (int64_t)c.rb_scal[(size_t)r * SC_COUNT + SC_GATHER_PB];
+    ss.gather_pairs += (int64_t)c.rb_scal[(size_t)r * SC_COUNT + SC_GATHER_PAIRS];
+    ss.screen_dims += (int64_t)c.rb_scal[(size_t)r * SC_COUNT + SC_SCREEN_DIMS];
+  }
+  (void)nscal;
+  ss.objective = *c.rb_obj;
+  ss.dprime = c.d;
+  ss.changed = c.n;
+  return SKM_OK;
+}
+
 // Iteration 1 of Algorithm 1: exact assignment over all dims.  Leaves assign, dist, cluster sizes.
 int step_exact(Ctx &c, StageTimer &tm, StepStats &ss) {
+  // many centroids: the low-precision filter first, exact distances for the few candidates it leaves
+  if (c.colmask && !c.exact_filter_off && (c.screen_mode > 0 || c.k >= 2048)) {
+    if (int rc = step_exact_filtered(c, tm, ss)) return rc;
+    if ((*c.rb_flag & 1u) == 0) {
+      if (*c.rb_flag != 0) return fail(SKM_EINTERNAL, "a point was left without a centroid");
+      return SKM_OK;
+    }
+    c.exact_filter_off = true;   // the candidate list overflowed (never with the default capacities): the full GEMM instead
+  }
   tm.mark(ST_NONE);
   if (int rc = c.clear_step_block()) return rc;
   HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, c.ds, c.ynorm, 0, 0, nullptr, c.st));
@@ -690,7 +779,9 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, c.k, nullptr, nullptr, c.counters + c.ncounters, c.st));
     tm.mark(ST_GEMM);
   }
-  bool regroup = c.regroup_ok && !c.permuted && c.xnp_valid && c.order_fresh && c.Xr2 && have_prev;
+  // (not before one pruned step has run: the labels of iteration 1, assigned against the initial rows, group the points
+  // far less usefully than those of iteration 2)
+  bool regroup = c.regroup_ok && !c.permuted && c.xnp_valid && c.order_fresh && c.Xr2 && have_prev && c.pruned_steps >= 1;
   if (regroup) {
     // The update leaves the members of a cluster sorted by index only up to a size (larger clusters keep the order in
     // which the scatter placed them, which depends on scheduling): with such a cluster the new order, and with it the
@@ -767,7 +858,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     HIPCHK(launch_progressive(g, c.st));
     tm.mark(ST_GEMM);
     if (c.emit_max > 0) {
-      PruneArgs pa{c.pairs, fill, (unsigned int)c.sub_cap, c.Xr, c.ldx, c.Ypdx, c.k, dprime, c.ds, nb, c.ratio_dev,
+      PruneArgs pa{c.pairs, fill, (unsigned int)c.sub_cap, c.Xr, c.ldx, c.n, c.Ypdx, c.k, dprime, c.ds, nb, c.ratio_dev,
                    c.best, c.scal, c.block_stats ? 1 : 0};
       HIPCHK(launch_prune(pa, c.st));
       tm.mark(ST_PRUNE);
@@ -798,6 +889,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   ss.screen_dims = (int64_t)scal_h[SC_SCREEN_DIMS];
   ss.listed_tiles = (int64_t)scal_h[SC_LISTED_TILES];
   c.last_prune_frac = c.k > 1 ? 1.0 - (double)ss.survivors / ((double)c.n * (double)(c.k - 1)) : -1.0;
+  ++c.pruned_steps;
   for (int m = 0; m < std::min<int>(nb, SKM_MAX_BLOCKS); ++m) ss.enter[m] = (int64_t)scal_h[SC_ENTER + (size_t)m];
   ss.objective = obj;
   ss.dprime = dprime;

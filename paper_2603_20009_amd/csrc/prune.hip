@@ -50,7 +50,8 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
   // the part of its own XCD, so those rows and blocks are fetched into one L2 only and found there again.
   static_assert(kSubLists == 8, "one part per XCD");
   const unsigned int part = blockIdx.x & 7u;
-  const unsigned int total = a.count[part * kSubListStride];
+  // (a producer that ran out of room has still counted what it could not write: never read past the part's end)
+  const unsigned int total = min(a.count[part * kSubListStride], a.sub_capacity);
   const Pair *list = a.pairs + (size_t)part * a.sub_capacity;
   const unsigned int ngroups = (gridDim.x >> 3) * (PRUNE_THREADS / PAIR_LANES);
   const int q = tid & (PAIR_LANES - 1);
@@ -65,6 +66,16 @@ __global__ void __launch_bounds__(PRUNE_THREADS) prune_kernel(PruneArgs a) {
     m = (int)(jm >> 24);   // first block still to be added
     acc = pr.p;
     tau = pr.tau;
+    // An entry that names no point or centroid is skipped (finished at once, offering nothing).  Every producer
+    // writes valid entries only; but after a producer's overflow, which the host answers by redoing the step another
+    // way, slots inside the counted range may never have been written.
+    if ((unsigned int)i >= (unsigned int)a.n || j >= a.k || m > a.nb) {
+      i = 0;
+      j = 0;
+      m = a.nb;
+      acc = 1.f;
+      tau = 0.f;
+    }
   };
   if (active) {
     unpack(list[p]);

@@ -62,6 +62,13 @@ struct ScreenArgs {
   uint32_t *colmask;       // [row tiles of 128][maskw]: bit j = some point of the row tile may pass the first test against j
   int32_t maskw;           // words per row tile: 4 per 128 centroids
   unsigned long long *scal;     // step scalars: SC_SCREEN_DIMS
+  // exact mode (iteration 1): arow = the band of every row, ycol = ||y_j||^2 in accumulator units
+  unsigned int *rowmin;         // [n] running minimum of every point over the tiles done so far (ordered float bits), by row_base + row
+  int64_t row_base;
+  Pair *pairs;                  // kSubLists parts of sub_capacity slots: the candidates
+  unsigned int *pair_count;     // [kSubLists * kSubListStride]
+  unsigned int sub_capacity;
+  unsigned int *overflow;
 };
 
 // A workgroup of 8 wavefronts owns 256 points x 256 centroids; a wavefront owns 128 x 64 (4 x 2 accumulators of
@@ -74,10 +81,22 @@ struct ScreenArgs {
 // one contiguous plane (see launch_split_rows): a slab row is 64 contiguous bytes.  The kernel is persistent: every XCD walks a
 // contiguous range of tiles (column tile fastest inside panels of 8 column tiles), its workgroups take every n-th;
 // the first slab of a workgroup's next tile is requested before the finished tile is tested.
+//
+// EXACT (Algorithm 1, iteration 1, where nothing prunes): the same multiply over ALL dimensions finds, for every point,
+// the centroids that can be its nearest.  With v~(i, j) = ||y_j||^2 - 2 (x_i.y_j)~ from the one product and b_i a
+// bound of its error (twice the bound of the product: see the top of this file, with the full norms), the true
+// nearest j* has v~(i, j*) <= min_j v~(i, j) + 2 b_i.  Every tile takes the minimum of each of its rows over its 256
+// columns, lowers the point's running minimum by it (one atomic per row; the tiles of a row run in any order and a
+// stale value is only larger), and emits the pairs within 2 b_i of the smaller of the two: j* is among them whenever
+// its tile runs.  In random order a row emits in about ln(column tiles) tiles.  The gather kernel then takes the exact
+// distance of every emitted pair, and the packed minimum over those is the exact nearest centroid.
+template <bool EXACT>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) screen_kernel(ScreenArgs g) {
   extern __shared__ __align__(16) uint32_t smem[];   // [NSTAGE stages][A: BM rows | B: BN rows][ROW_WORDS]
   __shared__ __align__(16) float s_a[NSTAGE][BM];    // per row of a tile in flight: the widened threshold in accumulator units
   __shared__ __align__(16) float s_y[NSTAGE][BN];    // per column of a tile in flight: its prefix norm in the same units
+  __shared__ unsigned int s_rmin[EXACT ? BM : 1];    // EXACT: minimum of every row of the tile (ordered float bits)
+  __shared__ float s_thr[EXACT ? BM : 1];            // EXACT: emission threshold of every row
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -183,7 +202,16 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       // the matrix instructions before this point have consumed.)
       __builtin_amdgcn_s_barrier();
       request();         // slab cjob + DEPTH -> the stage slab cjob - 1 was in (NSTAGE = DEPTH + 1)
-      if (s == 0) {      // every accumulator element starts from its row's term
+      if (s == 0 && EXACT) {
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+        if (tid < BM) s_rmin[tid] = 0xffffffffu;   // (read after this tile's slab barriers)
+      }
+      if (s == 0 && !EXACT) {      // every accumulator element starts from its row's term
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -217,6 +245,80 @@ __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
     }
     dims_done += (unsigned long long)(BK * nslab);
+
+    if (EXACT) {
+      // ---- minimum of every row over the tile's columns
+      const float *yc = s_y[ctile & (NSTAGE - 1)] + wn * 64 + r32;
+      const float y0 = colok[0] ? yc[0] : 3.0e38f, y1 = colok[1] ? yc[32] : 3.0e38f;
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          if ((v & 3) == 0) asm volatile("" : : : "memory");   // (four rows at a time: see the registers note below)
+          float m = fminf(y0 - acc[a][0][v], y1 - acc[a][1][v]);
+          // over the 32 lanes that hold this row (same lane half): quads, half rows, rows, then the two rows of the half
+          m = fminf(m, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, m), 0xB1, 0xF, 0xF, false)));
+          m = fminf(m, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, m), 0x4E, 0xF, 0xF, false)));
+          m = fminf(m, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, m), 0x141, 0xF, 0xF, false)));
+          m = fminf(m, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, m), 0x140, 0xF, 0xF, false)));
+          m = fminf(m, __shfl_xor(m, 16, 64));
+          if (r32 == 0) atomicMin(&s_rmin[wm * 128 + a * 32 + 8 * (v >> 2) + 4 * kh + (v & 3)], f2ord(m));
+        }
+      __syncthreads();
+      // ---- the point's running minimum takes it; the threshold is the smaller of the two plus the band
+      if (tid < BM) {
+        const int row = rt * BM + tid;
+        float thr = -3.0e38f;
+        if (row < g.M) {
+          const unsigned int local = s_rmin[tid];
+          const unsigned int old = atomicMin(g.rowmin + g.row_base + row, local);
+          thr = ord2f(old < local ? old : local) + s_a[ctile & (NSTAGE - 1)][tid];
+        }
+        s_thr[tid] = thr;
+      }
+      __syncthreads();
+      // ---- emit the pairs at or below the threshold of their row
+      const int xsub = blockIdx.x & 7;
+      int zero = 0;
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          // (a value the compiler cannot see through, renewed every four rows: the thresholds are then fetched four
+          // at a time instead of all 64 ahead, which would not fit the registers next to the accumulators)
+          if ((v & 3) == 0) asm volatile("" : "+v"(zero) : : "memory");
+          const int rl = wm * 128 + a * 32 + 8 * (v >> 2) + 4 * kh + (v & 3) + zero;
+          const float thr = s_thr[rl];
+          // (v~ <= thr written from the accumulator's side: the differences of the first pass are not kept alive)
+          const bool e0 = acc[a][0][v] >= y0 - thr, e1 = acc[a][1][v] >= y1 - thr;
+          const unsigned long long b0 = __ballot(e0), b1 = __ballot(e1);
+          if (b0 | b1) {
+            const int n0 = __popcll(b0), tot = n0 + __popcll(b1);
+            unsigned int base = 0;
+            if (lane == 0) base = atomicAdd(g.pair_count + xsub * kSubListStride, (unsigned int)tot);
+            base = __builtin_amdgcn_readfirstlane(base);
+            if ((unsigned long long)base + tot > (unsigned long long)g.sub_capacity) {
+              if (lane == 0) atomicOr(g.overflow, 1u);
+            } else {
+              const unsigned long long below = (1ull << lane) - 1ull;
+              Pair pr;
+              pr.i = (int32_t)(g.row_base + rt * BM + rl);
+              pr.p = 0.f;
+              pr.tau = 3.0e38f;
+              Pair *dst = g.pairs + (size_t)xsub * g.sub_capacity + base;
+              if (e0) {
+                pr.j = col0 + wn * 64 + r32;
+                dst[__popcll(b0 & below)] = pr;
+              }
+              if (e1) {
+                pr.j = col0 + wn * 64 + 32 + r32;
+                dst[n0 + __popcll(b1 & below)] = pr;
+              }
+            }
+          }
+        }
+      continue;
+    }
 
     // ---- widened first test: a column stays if any row of this wavefront's row tile may pass theta(d', tau) against it
     bool alive[TN];
@@ -335,12 +437,24 @@ __global__ void __launch_bounds__(256) mask_fill_kernel(const uint32_t *mask, in
 __global__ void __launch_bounds__(256) screen_terms_kernel(const float *tau, const float *xn, int64_t row_base, int32_t M,
                                                            const float *yn, int32_t N, const float *ynmax, float ratio0,
                                                            int32_t dprime, const unsigned int *a_absmax,
-                                                           const unsigned int *b_absmax, float *arow, float *ycol) {
+                                                           const unsigned int *b_absmax, float *arow, float *ycol,
+                                                           int exact) {
   const float ax = __builtin_bit_cast(float, *a_absmax), ay = __builtin_bit_cast(float, *b_absmax);
   const float slack = (float)dprime * ax * ay * (1.f / 8589934592.f);   // d' * max|x| * max|y| * 2^-33
   const float inv_k = 0.5f * split_scale(*a_absmax) * split_scale(*b_absmax);
   const float symax = sqrtf(fmaxf(*ynmax, 0.f));
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (exact) {
+    // exact mode: the band 2 b_i around the smallest v~ of a row inside which the true nearest centroid must lie:
+    // b_i = 2 * (bound of the product's error) = widening ||x_i|| max_j ||y_j||, plus the slack and a guard for the
+    // rounding of the values compared (their size is at most ||y||^2 + 2 ||x|| ||y||); y_j = ||y_j||^2 / K
+    if (i < M) {
+      const float xs = sqrtf(fmaxf(xn[row_base + i], 0.f));
+      arow[i] = (2.f * kWiden * xs * symax + 2.f * slack + 4.f * kGuard * (symax * symax + 2.f * xs * symax)) * inv_k;
+    }
+    if (i < N) ycol[i] = yn[i] * inv_k;
+    return;
+  }
   if (i < M) {
     const float x2 = xn[row_base + i];
     const float th = ratio0 * tau[row_base + i];
@@ -369,13 +483,17 @@ hipError_t launch_screen(const ScreenLaunch &a, hipStream_t st) {
   if (a.dprime % 16 != 0 || a.dprime < 16 || a.dprime > a.ds || a.lda != a.ds / 2 + 16 || a.ldb != a.ds / 2 + 16 ||
       (reinterpret_cast<uintptr_t>(a.A) & 15u) || (reinterpret_cast<uintptr_t>(a.B) & 15u) || a.N > (1 << 24))
     return hipErrorInvalidValue;
+  if (a.exact && (!a.rowmin || !a.pairs || !a.pair_count || !a.overflow)) return hipErrorInvalidValue;
   constexpr size_t smem = (size_t)NSTAGE * STAGE_WORDS * sizeof(uint32_t);
   struct Setup {
     hipError_t rc;
     int wgs = 0;
     Setup() {
-      rc = hipFuncSetAttribute(reinterpret_cast<const void *>(screen_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)smem);
+      rc = hipFuncSetAttribute(reinterpret_cast<const void *>(screen_kernel<false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (rc == hipSuccess)
+        rc = hipFuncSetAttribute(reinterpret_cast<const void *>(screen_kernel<true>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       int dev = 0, cus = 256;
       (void)hipGetDevice(&dev);
       (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -395,11 +513,17 @@ hipError_t launch_screen(const ScreenLaunch &a, hipStream_t st) {
   hipLaunchKernelGGL(max_value_kernel, dim3(1), dim3(1024), 0, st, a.yn, a.N, ynmax);
   hipLaunchKernelGGL(screen_terms_kernel, dim3((unsigned)((std::max<int64_t>(a.M, a.N) + 255) / 256)), dim3(256), 0, st,
                      a.tau, a.xn, a.row_base, a.M, a.yn, a.N, (const float *)ynmax, a.ratio0, a.dprime, a.a_absmax,
-                     a.b_absmax, a.arow, a.ycol);
+                     a.b_absmax, a.arow, a.ycol, a.exact ? 1 : 0);
   g.arow = a.arow; g.ycol = a.ycol; g.colmask = a.colmask; g.maskw = 4 * nct;
   g.scal = a.scal;
+  g.rowmin = a.rowmin; g.row_base = a.row_base; g.pairs = a.pairs; g.pair_count = a.pair_count;
+  g.sub_capacity = a.sub_capacity; g.overflow = a.overflow;
   const int64_t grid = std::max<int64_t>(8, std::min<int64_t>(setup.wgs, (ntiles + 7) / 8 * 8));
-  hipLaunchKernelGGL(screen_kernel, dim3((unsigned)grid), dim3(NT), smem, st, g);
+  if (a.exact) {
+    hipLaunchKernelGGL(screen_kernel<true>, dim3((unsigned)grid), dim3(NT), smem, st, g);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(screen_kernel<false>, dim3((unsigned)grid), dim3(NT), smem, st, g);
   hipError_t rc = hipGetLastError();
   if (rc != hipSuccess) return rc;
   hipLaunchKernelGGL(mask_count_kernel, dim3((unsigned)((nrt + 3) / 4)), dim3(256), 0, st, a.colmask, nrt, 4 * nct, a.cnt);

@@ -166,8 +166,18 @@ struct ScreenLaunch {
   float *arow, *ycol;        // scratch: [M] and [N] (the test's per-point and per-centroid terms)
   uint32_t *colmask;         // scratch: [row tiles][4 * column tiles]
   int32_t *cnt, *first, *ntiles, *col_list, *tile_rt;   // (ntiles: two words, the second is scratch)
-  unsigned int *tile_counter;   // [8 * kSubListStride], zero before the launch
+  unsigned int *tile_counter;   // (unused)
   unsigned long long *scal;     // step scalars (SC_SCREEN_DIMS)
+  // Exact mode (iteration 1: dprime = ds, xn / yn the full norms, tau and ratio0 unused, no column lists): for every
+  // point the centroids that can be its nearest are appended to `pairs` (partial distance 0, first block 0, no
+  // threshold) for the gather kernel, which finishes their exact distances.  rowmin: [n] words of 0xffffffff before
+  // the first launch of the step, indexed by row_base + row.
+  int exact = 0;
+  unsigned int *rowmin = nullptr;
+  Pair *pairs = nullptr;
+  unsigned int *pair_count = nullptr;
+  unsigned int sub_capacity = 0;
+  unsigned int *overflow = nullptr;
 };
 hipError_t launch_screen(const ScreenLaunch &a, hipStream_t st);
 int64_t progressive_tiles(int64_t rows, int32_t k);
@@ -181,6 +191,7 @@ struct PruneArgs {
   unsigned int sub_capacity;
   const float *Xr;       // rotated points, row stride ldx, zero padded to ds columns
   int64_t ldx;
+  int64_t n;             // number of points (entries naming a point beyond it are skipped)
   const float *Ypdx;     // [nb][k][64] trailing centroid dimensions, block-major (PDX-style)
   int32_t k;
   int32_t dprime;

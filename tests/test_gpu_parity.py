@@ -275,7 +275,8 @@ def test_update(skm, orc, dg, n, d, k):
 def fit_pair(skm, orc, X, k, iters, seed, R, init_idx=None, **kw):
     kw.setdefault("eps0", EPS0)
     idx = orc.sample_rows(seed, len(X), k) if init_idx is None else np.asarray(init_idx, dtype=np.int64)
-    ref = orc.fit(X, k, iters, seed, orc.FitParams(**kw), R=R, init_idx=idx)
+    okw = {a: b for a, b in kw.items() if a != "screen"}     # an execution choice of the library, not of the method
+    ref = orc.fit(X, k, iters, seed, orc.FitParams(**okw), R=R, init_idx=idx)
     # without init_idx the library draws the same initial rows from the seed
     opts = skm.FitOptions(R=None if R is None else cuda(R), rotate=R is not None, block_stats=True,
                           init_idx=None if init_idx is None else list(idx), **kw)
@@ -327,16 +328,18 @@ def test_fit_without_rotation_or_final_pass(skm, orc, dg):
     assert np.abs(got.centroids.cpu().numpy() - S / np.bincount(a, minlength=24)[:, None]).max() < 1e-6
 
 
-def test_fit_splits_empty_clusters_like_the_oracle(skm, orc, dg):
+@pytest.mark.parametrize("screen", [0, 1])
+def test_fit_splits_empty_clusters_like_the_oracle(skm, orc, dg, screen):
     """Repeated initial rows leave clusters empty after iteration 1 (identical centroids tie and the
-    lowest index wins on both sides); the split must re-seed them from the same donors."""
+    lowest index wins on both sides, also when the low-precision filter picks the candidates of iteration 1);
+    the split must re-seed them from the same donors."""
     X = dg.mixture(6000, 64, 24, 10, "linear").numpy()
     R = orc.random_rotation(64, 10)
     idx = orc.sample_rows(1, 6000, 12)
     idx[1] = idx[0]
     idx[2] = idx[0]
     idx[7] = idx[6]
-    ref, got = fit_pair(skm, orc, X, 12, 5, 1, R, init_idx=idx, adjust_dprime=False)
+    ref, got = fit_pair(skm, orc, X, 12, 5, 1, R, init_idx=idx, adjust_dprime=False, screen=screen)
     assert [g["nempty"] for g in got.trace] == [r["nempty"] for r in ref.trace] and ref.trace[0]["nempty"] == 3
     check_assignment(got.assign.cpu().numpy(), ref.assign, orc.rotate(X, R), ref.centroids_rot,
                      own=(X, got.centroids.cpu().numpy()))
@@ -344,8 +347,9 @@ def test_fit_splits_empty_clusters_like_the_oracle(skm, orc, dg):
     assert (np.bincount(got.assign.cpu().numpy(), minlength=12) > 0).all()
 
 
+@pytest.mark.parametrize("screen", [0, 1])
 @pytest.mark.parametrize("case", range(8))
-def test_fit_over_seeded_shapes(skm, orc, dg, case):
+def test_fit_over_seeded_shapes(skm, orc, dg, case, screen):
     """Whole fits on shapes drawn from a seed: d not a multiple of 16 or 64, k below, at and above one tile, row
     counts that leave ragged tiles, with and without rotation and d' adjustment."""
     rng = np.random.default_rng(1000 + case)
@@ -358,7 +362,9 @@ def test_fit_over_seeded_shapes(skm, orc, dg, case):
     X = dg.mixture(n, d, max(k // 2, 3), 50 + case, kind).numpy()
     R = orc.random_rotation(d, case) if rotate else None
     say("fit shape", case, n, d, k, iters, kind, "rotate" if rotate else "plain")
-    ref, got = fit_pair(skm, orc, X, k, iters, 77 + case, R, adjust_dprime=case % 2 == 0)
+    # screen = 1: the low-precision filter in front of iteration 1 and of every pruned step
+    ref, got = fit_pair(skm, orc, X, k, iters, 77 + case, R, adjust_dprime=case % 2 == 0, screen=screen)
+    assert (got.trace[0]["screen_dims"] > 0) == (screen == 1)
     Xr = orc.rotate(X, R) if rotate else X
     check_assignment(got.assign.cpu().numpy(), ref.assign, Xr, ref.centroids_rot, own=(X, got.centroids.cpu().numpy()))
     check_centroids(got.centroids.cpu().numpy(), ref.centroids, got.assign.cpu().numpy(), ref.assign)
@@ -437,6 +443,31 @@ def test_update_after_a_split_that_moved_no_point(skm, orc, dg):
             mean = X[a == c].astype(np.float64).mean(0)
             errs = [np.abs(Y[c] - mean * f).max() for f in (1.0, 1.0 + eps * s, 1.0 - eps * s)]
             assert min(errs) < 1e-6, (c, errs)
+
+
+def test_filtered_first_iteration_is_the_exact_assignment(skm, orc, dg):
+    """Iteration 1 behind the low-precision filter: among the candidates the one-product multiply leaves for a point
+    the exact nearest centroid must always be present.  Several thousand centroids (the regime it is for), a ragged
+    last tile in both directions, and rows of very different length (the bound scales with the row's norm)."""
+    rng = np.random.default_rng(17)
+    n, d, k = 30_100, 96, 2300
+    X = dg.mixture(n, d, 300, 9, "embed").numpy() * rng.uniform(0.05, 20.0, (n, 1)).astype(np.float32)
+    R = orc.random_rotation(d, 5)
+    idx = orc.sample_rows(3, n, k)
+    got = skm.fit(cuda(X), k, 1, 3, skm.FitOptions(R=cuda(R), final_assign=False))          # screen = 0: on from 2048 centroids
+    off = skm.fit(cuda(X), k, 1, 3, skm.FitOptions(R=cuda(R), final_assign=False, screen=-1))
+    assert got.trace[0]["screen_dims"] > 0 and got.trace[0]["gather_pairs"] >= n and off.trace[0]["screen_dims"] == 0
+    say("candidates per point:", got.trace[0]["gather_pairs"] / n)
+    Xr = orc.rotate(X, R)
+    a_ref, d_ref = orc.assign_full(Xr, Xr[idx])
+    for fr in (got, off):
+        a = fr.assign.cpu().numpy()
+        check_assignment(a, a_ref, Xr, Xr[idx], min_agree=0.9995)
+        same = a == a_ref
+        assert np.abs(fr.dist.cpu().numpy()[same] - d_ref[same]).max() < 2e-5 * d_ref.max()
+        assert fr.trace[0]["objective"] == pytest.approx(d_ref.sum(), rel=1e-5)
+    assert (got.assign != off.assign).sum() <= 3
+    assert got.trace[0]["gather_pairs"] < 40 * n      # a handful of candidates per point, not the k of a full scan
 
 
 def test_fit_is_bitwise_reproducible(skm, orc, dg):
