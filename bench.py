@@ -121,21 +121,38 @@ def run_workload(name, steps, warmup, own_workspace, traffic_json, n_override=0)
     upd_bytes = float(np.mean([update_bytes(t, i == 0) for i, t in enumerate(last.trace[:last.iters_run])]))
     flops_rot = 2.0 * n * d * d
     flops_it1 = 2.0 * n * k * ds
+    # one-product (hi * hi') matrix work of the low-precision first filter, in units of one dimension of a 128 x 128 tile
+    it1_filtered = last.trace[0]["screen_dims"] > 0
+    screen_flop = float(np.mean([tile_flop * t["screen_dims"] for t in steps2])) if steps2 else 0.0
+    listed = float(np.mean([t["listed_tiles"] for t in steps2])) if steps2 else 0.0
+    n_screened = int(np.sum([t["screen_dims"] > 0 for t in steps2])) if steps2 else 0
     stages = {
         "rotation_gemm": dict(bound="mfma", ms=ms_rot, achieved=flops_rot / ms_rot / 1e9, unit="TFLOP/s"),
-        "iter1_gemm_argmin": dict(bound="mfma", ms=ms_it1_gemm, achieved=flops_it1 / ms_it1_gemm / 1e9, unit="TFLOP/s"),
+        "iter1_gemm_argmin": dict(bound="mfma", ms=ms_it1_gemm, achieved=flops_it1 / ms_it1_gemm / 1e9, unit="TFLOP/s",
+                                  filtered=bool(it1_filtered),
+                                  one_product_flop=tile_flop * last.trace[0]["screen_dims"],
+                                  exact_pairs_per_point=last.trace[0]["gather_pairs"] / n,
+                                  note="filtered: one fp16 product per dimension over all pairs keeps, per point, the "
+                                       "centroids inside a rigorous error band of the running row minimum; only those "
+                                       "pairs get the three-product exact distance (gather kernel), so the matrix work "
+                                       "per algorithmic flop is about one third of the unfiltered GEMM's"
+                                       if it1_filtered else "unfiltered three-product GEMM with argmin epilogue"),
         "progressive_gemm": dict(bound="mfma", ms=ms_prog, achieved=flop_alg / ms_prog / 1e9, unit="TFLOP/s",
-                                 executed=flop_exec / ms_prog / 1e9),
+                                 executed=flop_exec / ms_prog / 1e9,
+                                 steps_behind_first_filter=n_screened, one_product_flop_per_step=screen_flop,
+                                 listed_tiles_per_step=listed),
         "tau_init": dict(bound="hbm", ms=ms_tau, achieved=(n * ds * 4.0 + 12.0 * n) / ms_tau / 1e6, unit="GB/s"),
-        "gather_prune": dict(bound="hbm", ms=ms_prune, achieved=(prune_bytes / ms_prune / 1e6) if ms_prune > 0 else None,
+        "gather_prune": dict(bound="l2", ms=ms_prune, achieved=(prune_bytes / ms_prune / 1e6) if ms_prune > 0 else None,
                              unit="GB/s", bytes_per_step=prune_bytes,
-                             note="algorithmic bytes the gather kernel requests (512 B per gathered pair-block step + "
-                                  "16 B per pair); most are served by the XCD's L2, not by HBM"),
+                             note="requested bytes (512 B per gathered pair-block step + 16 B per pair) over the kernel's "
+                                  "time; the blocks of a point and of the centroids are re-read many times and are served "
+                                  "by the XCDs' L2 and the Infinity Cache, so this rate is not priced against HBM (no "
+                                  "frac); hbm_gbs_rocprof is the kernel's HBM-side rate from the committed counter runs"),
         "update": dict(bound="hbm", ms=ms_update, achieved=upd_bytes / ms_update / 1e6, unit="GB/s",
                        incremental_updates=int(last.timing.get("inc_updates", 0))),
     }
     for s in stages.values():
-        if s["achieved"] is not None:
+        if s["achieved"] is not None and s["bound"] in ("mfma", "hbm"):
             s["frac"] = s["achieved"] / (PEAK_SPLIT_TFLOPS if s["bound"] == "mfma" else PEAK_HBM_GBS)
     # dominant kernel of the fit by total time
     totals = {"rotation_gemm": ms_rot, "iter1_gemm_argmin": ms_it1_gemm, "progressive_gemm": total_prog}
@@ -144,7 +161,14 @@ def run_workload(name, steps, warmup, own_workspace, traffic_json, n_override=0)
     traffic_source = None
     if traffic_json and os.path.exists(traffic_json):
         try:
-            traffic = json.load(open(traffic_json)).get(name, {}).get(dom)
+            per_kernel = json.load(open(traffic_json)).get(name, {})
+            traffic = per_kernel.get(dom)
+            gp = per_kernel.get("gather_prune")
+            if gp and ms_prune > 0:
+                # HBM-side bytes per launch (committed rocprofv3 --pmc runs) over this run's time per launch
+                stages["gather_prune"]["hbm_bytes_per_launch_rocprof"] = gp["total_bytes"]
+                stages["gather_prune"]["hbm_gbs_rocprof"] = gp["total_bytes"] / ms_prune / 1e6
+                stages["gather_prune"]["hbm_frac_rocprof"] = gp["total_bytes"] / ms_prune / 1e6 / PEAK_HBM_GBS
             if traffic is not None:
                 traffic_source = (f"{os.path.relpath(traffic_json, ROOT)} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
                                   f"this command, committed; NOT measured in this run)")

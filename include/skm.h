@@ -153,8 +153,8 @@ typedef struct skm_params {
                             only.  In iteration 1, where nothing prunes, the same one-product multiply over all
                             dimensions lists for every point the centroids that can be its nearest (those within the
                             rounding bound of the row's smallest approximate distance), and only those get their exact
-                            distance.  0 = in pruned steps that follow a step which cut at least 90 % of the pairs at
-                            the first test, and in iteration 1 from 2048 centroids on; 1 = in every step; -1 = never.
+                            distance.  0 = in pruned steps that follow a step which cut at least half of the pairs at the
+                            first test, and in iteration 1 from 2048 centroids on; 1 = in every step; -1 = never.
                             Execution strategy only: a pair the filter drops is dropped by the exact arithmetic too */
   int32_t tau_group;     /* 0    : centroids after which a point's threshold tau is refreshed inside a step.  0 (= k):
                             tau keeps its initial value for the whole step, the only form this library runs (the

@@ -207,6 +207,40 @@ def test_pruned_step_with_low_precision_filter(skm, orc, dg, n, d, k, dp, budget
     assert (b.cpu().numpy() != a).sum() <= 1
 
 
+@pytest.mark.parametrize("screen", [-1, 1])
+def test_steps_on_rows_of_heavy_tailed_norm(skm, orc, dg, screen):
+    """The split-fp16 operands share one power-of-two scale per matrix: an entry keeps 22 significant bits while it
+    is at least 2^-18 of the matrix's largest entry, below that an absolute error of 2^-40 of the largest.  Rows whose
+    norms span five orders of magnitude (log-normal factors, clipped to 1e-3 .. 1e2) must still meet the near-tie
+    contract in the exact step and in a pruned step, with and without the low-precision first filter."""
+    say("heavy-tailed norms, screen", screen)
+    n, d, k = 6000, 256, 300
+    rng = np.random.default_rng(77)
+    scale = np.clip(np.exp(2.5 * rng.standard_normal(n)), 1e-3, 1e2).astype(np.float32)
+    X = (dg.mixture(n, d, 30, 5, "linear").numpy() * scale[:, None]).astype(np.float32)
+    pick = rng.choice(n, k, replace=False)
+    Y = (X[pick] * (1.0 + 0.01 * rng.standard_normal((k, d)))).astype(np.float32)
+    assert np.linalg.norm(X, axis=1).max() / np.linalg.norm(X, axis=1).min() > 3e4
+    R = orc.random_rotation(d, 78)
+    Xr, Yr = orc.rotate(X, R), orc.rotate(Y, R)
+    # exact step: iteration 1 of a fit (its centroids are the seeded sample of the rows), behind the filter or not
+    fr = skm.fit(cuda(X), k, 1, 3, skm.FitOptions(R=cuda(R), final_assign=False, screen=screen))
+    assert (fr.trace[0]["screen_dims"] > 0) == (screen > 0)
+    idx = orc.sample_rows(3, n, k)
+    ao, _ = orc.assign_full(Xr, Xr[idx])
+    check_assignment(fr.assign.cpu().numpy(), ao, Xr, Xr[idx])
+    # pruned step from a partly poor incumbent
+    prev = orc.assign_full(Xr, Yr)[0].astype(np.int32)
+    prev[::4] = rng.integers(0, k, len(prev[::4]))
+    dp = orc.dprime_init(d)
+    ref = orc.assign_pruned(Xr, Yr, prev, dp, EPS0, 0)
+    b, _, row = skm.assign(cuda(X), cuda(Y), cuda(prev), dp, skm.FitOptions(R=cuda(R), block_stats=True, screen=screen))
+    check_assignment(b.cpu().numpy(), ref.assign, Xr, Yr)
+    surv_ref = n * (k - 1) - ref.pruned_first
+    assert abs(row["survivors"] - surv_ref) <= max(2, 1e-3 * surv_ref)
+    assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])
+
+
 def test_pruned_step_without_previous_assignment(skm, orc, dg):
     X, R, Y, Xr, Yr, _ = pruned_case(orc, dg, 2500, 128, 90, 5, "linear")
     ref = orc.assign_pruned(Xr, Yr, None, 16, EPS0, 0)
