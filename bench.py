@@ -118,7 +118,17 @@ def run_workload(name, steps, warmup, own_workspace, traffic_json, n_override=0)
         if not first and 8 * t["changed"] <= n:
             return 2.0 * t["changed"] * ds * 4.0 + 8.0 * n + k * ds * 20.0
         return n * ds * 4.0 + 8.0 * n + 2.0 * k * ds * 4.0
-    upd_bytes = float(np.mean([update_bytes(t, i == 0) for i, t in enumerate(last.trace[:last.iters_run])]))
+    upd_rows = list(enumerate(last.trace[:last.iters_run]))
+    full_upd = [t for i, t in upd_rows if i == 0 or 8 * t["changed"] > n]
+    inc_upd = [t for i, t in upd_rows if not (i == 0 or 8 * t["changed"] > n)]
+    upd_bytes = float(np.mean([update_bytes(t, i == 0) for i, t in upd_rows]))
+    full_bytes = n * ds * 4.0 + 8.0 * n + 2.0 * k * ds * 4.0
+    ms_full_upd = float(np.mean([t["ms_update"] for t in full_upd]))
+    # threshold pass: every pruned step reads each point once; the first pruned step also writes the split-fp16 copy of the
+    # points, its plane of hi halves and the prefix-norm table, and the step that regroups the points writes them again in
+    # the new order.  The stage figure is the median step (the steady state); the two special steps are listed beside it.
+    tau_ms = sorted(t["ms_tau"] for t in steps2) if steps2 else [0.0]
+    ms_tau_med = float(np.median(tau_ms))
     flops_rot = 2.0 * n * d * d
     flops_it1 = 2.0 * n * k * ds
     # one-product (hi * hi') matrix work of the low-precision first filter, in units of one dimension of a 128 x 128 tile
@@ -141,15 +151,23 @@ def run_workload(name, steps, warmup, own_workspace, traffic_json, n_override=0)
                                  executed=flop_exec / ms_prog / 1e9,
                                  steps_behind_first_filter=n_screened, one_product_flop_per_step=screen_flop,
                                  listed_tiles_per_step=listed),
-        "tau_init": dict(bound="hbm", ms=ms_tau, achieved=(n * ds * 4.0 + 12.0 * n) / ms_tau / 1e6, unit="GB/s"),
+        "tau_init": dict(bound="hbm", ms=ms_tau_med, achieved=(n * ds * 4.0 + 12.0 * n) / ms_tau_med / 1e6, unit="GB/s",
+                         ms_mean=ms_tau, ms_two_largest=tau_ms[-2:],
+                         note="median pruned step (reads every point once, writes tau and the incumbent's key); the two "
+                              "largest are the first pruned step (also writes the split-fp16 copy of the points, its hi "
+                              "plane and the prefix norms) and the step that rewrites the points grouped by cluster"),
         "gather_prune": dict(bound="l2", ms=ms_prune, achieved=(prune_bytes / ms_prune / 1e6) if ms_prune > 0 else None,
                              unit="GB/s", bytes_per_step=prune_bytes,
                              note="requested bytes (512 B per gathered pair-block step + 16 B per pair) over the kernel's "
                                   "time; the blocks of a point and of the centroids are re-read many times and are served "
                                   "by the XCDs' L2 and the Infinity Cache, so this rate is not priced against HBM (no "
                                   "frac); hbm_gbs_rocprof is the kernel's HBM-side rate from the committed counter runs"),
-        "update": dict(bound="hbm", ms=ms_update, achieved=upd_bytes / ms_update / 1e6, unit="GB/s",
-                       incremental_updates=int(last.timing.get("inc_updates", 0))),
+        "update": dict(bound="hbm", ms=ms_full_upd, achieved=full_bytes / ms_full_upd / 1e6, unit="GB/s",
+                       full_updates=len(full_upd), incremental_updates=int(last.timing.get("inc_updates", 0)),
+                       ms_mean_all=ms_update, achieved_mean_all=upd_bytes / ms_update / 1e6,
+                       ms_incremental=[round(t["ms_update"], 4) for t in inc_upd],
+                       note="figure of a full update (every row read once: sort by cluster, segmented sums, means); "
+                            "incremental updates move only the rows that changed cluster and are latency-bound"),
     }
     for s in stages.values():
         if s["achieved"] is not None and s["bound"] in ("mfma", "hbm"):

@@ -356,6 +356,7 @@ struct Ctx {
   int32_t *pos_to_id = nullptr;  // [n] point of every position
   unsigned char *subkey = nullptr;   // [n] scratch: the key that orders the points inside a cluster
   bool regroup_ok = false;       // the caller has enough steps left for it to pay
+  int32_t max_cluster = -1;      // size of the largest cluster at the last update (-1: none yet)
   bool order_fresh = false;      // up.order groups the points by the labels now in `prev`
   bool permuted = false;
   unsigned long long *point_keys = nullptr;   // keys that name points (ETR ground truth): renumbered with the points
@@ -786,10 +787,8 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
     // The update leaves the members of a cluster sorted by index only up to a size (larger clusters keep the order in
     // which the scatter placed them, which depends on scheduling): with such a cluster the new order, and with it the
     // rounding of the results, would differ from run to run.  Those fits keep the input order.
-    std::vector<int32_t> off((size_t)c.k + 1);
-    HIPCHK(hipMemcpyAsync(off.data(), c.up.off, sizeof(int32_t) * off.size(), hipMemcpyDeviceToHost, c.st));
-    HIPCHK(hipStreamSynchronize(c.st));
-    for (int32_t j = 0; j < c.k && regroup; ++j) regroup = off[(size_t)j + 1] - off[(size_t)j] <= update_sort_cap();
+    // (the sizes came back with the previous step's scalars: no copy, no wait here)
+    regroup = c.max_cluster >= 0 && c.max_cluster <= update_sort_cap();
     if (!regroup) c.regroup_ok = false;
   }
   if (regroup) {
@@ -940,7 +939,12 @@ int split_empty(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t
   c.rb_cnt_valid = false;
   std::vector<int32_t> cnt(c.rb_cnt, c.rb_cnt + c.k);
   int64_t nempty = 0;
-  for (int32_t v : cnt) nempty += (v == 0);
+  int32_t largest = 0;
+  for (int32_t v : cnt) {
+    nempty += (v == 0);
+    largest = std::max(largest, v);
+  }
+  c.max_cluster = largest;   // of the labels the update just used (a split below moves a centroid, no label)
   *nempty_out = nempty;
   c.split_last = false;
   if (nempty > 0) {
