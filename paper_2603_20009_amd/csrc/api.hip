@@ -528,7 +528,7 @@ struct Ctx {
       HIPCHK(pool.get(&up.order, (size_t)n));
       up.max_segments = update_max_segments(n, k);
       HIPCHK(pool.get(&up.partial, (size_t)up.max_segments * ds));
-      HIPCHK(pool.get(&split_dev, (size_t)2 * k));
+      HIPCHK(pool.get(&split_dev, (size_t)3 * k + 2));   // (empty, donor) pairs | first split of every chain
       // the incremental update is used while at most one point in eight changes its label
       HIPCHK(pool.get(&S, (size_t)k * ds));
       inc.capacity = 2 * (n / 8) + 2;
@@ -949,36 +949,91 @@ int split_empty(Ctx &c, StageTimer &tm, Rng &split_rng, float split_eps, int64_t
   c.split_last = false;
   if (nempty > 0) {
     // empty clusters in increasing index; donor drawn with probability proportional to its size
-    // among clusters of at least two points; the donor's points are shared floor(n/2) / rest
+    // among clusters of at least two points; the donor's points are shared floor(n/2) / rest.
+    // The draw "first cluster whose cumulative weight exceeds r" runs on a Fenwick tree over the weights
+    // (size if >= 2, else 0): O(log k) per empty cluster instead of a pass over all sizes.
+    const int32_t k = c.k;
+    std::vector<uint64_t> fen((size_t)k + 1, 0);
+    auto weight = [](int32_t v) { return v >= 2 ? (uint64_t)v : 0ull; };
+    for (int32_t j = 0; j < k; ++j) fen[(size_t)j + 1] = weight(cnt[(size_t)j]);
+    for (int32_t j = 1; j <= k; ++j) {
+      const int32_t up = j + (j & -j);
+      if (up <= k) fen[(size_t)up] += fen[(size_t)j];
+    }
+    uint64_t total = 0;
+    for (int32_t v : cnt) total += weight(v);
+    auto fen_add = [&](int32_t j, int64_t delta) {
+      for (int32_t i = j + 1; i <= k; i += i & -i) fen[(size_t)i] = (uint64_t)((int64_t)fen[(size_t)i] + delta);
+    };
+    int32_t top = 1;
+    while ((top << 1) <= k) top <<= 1;
+    auto fen_find = [&](uint64_t r) {   // smallest j with weight(0) + ... + weight(j) > r   (r < total)
+      int32_t pos = 0;
+      for (int32_t step = top; step > 0; step >>= 1)
+        if (pos + step <= k && fen[(size_t)(pos + step)] <= r) {
+          pos += step;
+          r -= fen[(size_t)pos];
+        }
+      return pos;
+    };
     std::vector<int32_t> pairs;
-    for (int32_t e = 0; e < c.k; ++e) {
+    for (int32_t e = 0; e < k; ++e) {
       if (cnt[(size_t)e] != 0) continue;
-      uint64_t total = 0;
-      for (int32_t v : cnt)
-        if (v >= 2) total += (uint64_t)v;
       if (total == 0) continue;
       const uint64_t r = split_rng.next() % total;
-      uint64_t cum = 0;
-      int32_t donor = -1;
-      for (int32_t j = 0; j < c.k; ++j) {
-        if (cnt[(size_t)j] < 2) continue;
-        cum += (uint64_t)cnt[(size_t)j];
-        if (cum > r) {
-          donor = j;
-          break;
-        }
-      }
-      cnt[(size_t)e] = cnt[(size_t)donor] / 2;
-      cnt[(size_t)donor] -= cnt[(size_t)e];
+      const int32_t donor = fen_find(r);
+      const int32_t give = cnt[(size_t)donor] / 2, keep = cnt[(size_t)donor] - give;
+      const int64_t dd = (int64_t)weight(keep) - (int64_t)weight(cnt[(size_t)donor]);
+      const int64_t de = (int64_t)weight(give);
+      fen_add(donor, dd);
+      fen_add(e, de);
+      total = (uint64_t)((int64_t)total + dd + de);
+      cnt[(size_t)e] = give;
+      cnt[(size_t)donor] = keep;
       pairs.push_back(e);
       pairs.push_back(donor);
     }
     if (!pairs.empty()) {
-      HIPCHK(hipMemcpyAsync(c.split_dev, pairs.data(), sizeof(int32_t) * pairs.size(), hipMemcpyHostToDevice, c.st));
-      HIPCHK(launch_split(c.Y, c.ds, c.d, c.split_dev, (int32_t)(pairs.size() / 2), split_eps, c.st));
+      // Splits that share no cluster commute: they are grouped into chains (connected components of the clusters they
+      // touch, in order of first appearance, every chain keeping the order above) and the device applies the chains
+      // side by side.
+      const size_t ns = pairs.size() / 2;
+      std::vector<int32_t> parent((size_t)k);
+      for (int32_t j = 0; j < k; ++j) parent[(size_t)j] = j;
+      auto root = [&](int32_t v) {
+        while (parent[(size_t)v] != v) v = parent[(size_t)v] = parent[(size_t)parent[(size_t)v]];
+        return v;
+      };
+      for (size_t q = 0; q < ns; ++q) {
+        const int32_t a = root(pairs[2 * q]), b = root(pairs[2 * q + 1]);
+        if (a != b) parent[(size_t)a] = b;
+      }
+      std::vector<int32_t> chain_of((size_t)k, -1), chain(ns), len;
+      for (size_t q = 0; q < ns; ++q) {
+        const int32_t r0 = root(pairs[2 * q]);
+        if (chain_of[(size_t)r0] < 0) {
+          chain_of[(size_t)r0] = (int32_t)len.size();
+          len.push_back(0);
+        }
+        chain[q] = chain_of[(size_t)r0];
+        ++len[(size_t)chain[q]];
+      }
+      const size_t nchain = len.size();
+      // upload: [2 ns] pairs sorted by chain | at word 2 k: [nchain + 1] first split of every chain
+      std::vector<int32_t> up((size_t)2 * k + nchain + 1, 0);
+      std::vector<int32_t> cursor(nchain + 1, 0);
+      for (size_t q = 0; q < nchain; ++q) cursor[q + 1] = cursor[q] + len[q];
+      for (size_t q = 0; q <= nchain; ++q) up[(size_t)2 * k + q] = cursor[q];
+      for (size_t q = 0; q < ns; ++q) {
+        const int32_t at = cursor[(size_t)chain[q]]++;
+        up[(size_t)2 * at] = pairs[2 * q];
+        up[(size_t)2 * at + 1] = pairs[2 * q + 1];
+      }
+      HIPCHK(hipMemcpyAsync(c.split_dev, up.data(), sizeof(int32_t) * up.size(), hipMemcpyHostToDevice, c.st));
+      HIPCHK(launch_split(c.Y, c.ds, c.d, c.split_dev, c.split_dev + (size_t)2 * k, (int32_t)nchain, split_eps, c.st));
       c.y_amax_valid = false;
       c.split_last = true;
-      HIPCHK(hipStreamSynchronize(c.st));  // `pairs` must outlive the copy
+      HIPCHK(hipStreamSynchronize(c.st));  // `up` must outlive the copy
     }
   }
   tm.mark(ST_UPDATE);

@@ -290,8 +290,10 @@ hipError_t launch_update_incremental(const float *Xr, int64_t ldx, int64_t n, in
                                      const IncUpdateWs &inc, double *S, float *Y, int64_t ldy, hipStream_t st,
                                      unsigned int *y_absmax = nullptr);
 
-hipError_t launch_split(float *Y, int64_t ldy, int32_t d, const int32_t *pairs_dev, int32_t nsplit, float eps,
-                        hipStream_t st);
+// Empty-cluster splits: pairs_dev = (empty, donor) pairs grouped into chains (splits that share a cluster, in the
+// host's order); chain_first_dev[c] .. chain_first_dev[c + 1] are the splits of chain c.  One workgroup per chain.
+hipError_t launch_split(float *Y, int64_t ldy, int32_t d, const int32_t *pairs_dev, const int32_t *chain_first_dev,
+                        int32_t nchains, float eps, hipStream_t st);
 hipError_t launch_gather_rows(const float *src, int64_t lds, int32_t d, const int64_t *idx_dev, int32_t k, float *dst,
                               int64_t ldd, int32_t dpad, hipStream_t st);
 hipError_t launch_pad_copy(const float *src, int64_t lds, int64_t n, int32_t d, float *dst, int64_t ldd, int32_t dpad,

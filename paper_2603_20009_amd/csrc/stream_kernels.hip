@@ -920,11 +920,13 @@ hipError_t launch_update_incremental(const float *Xr, int64_t ldx, int64_t n, in
 }
 
 // ------------------------------------------------------------------ split of empty clusters
-// pairs = (empty, donor) in the order decided on the host; applied one after the other because a
-// donor may be used twice and a re-seeded cluster may itself donate later.
+// pairs = (empty, donor) in the order decided on the host.  A donor may be used twice and a re-seeded cluster may
+// itself donate later, so the splits of one chain (splits that share clusters, grouped by the host) are applied one
+// after the other by one workgroup; chains touch disjoint rows and run side by side.
 __global__ void __launch_bounds__(256) split_kernel(float *Y, int64_t ldy, int32_t d, const int32_t *pairs,
-                                                    int32_t nsplit, float eps) {
-  for (int s = 0; s < nsplit; ++s) {
+                                                    const int32_t *chain_first, float eps) {
+  const int s0 = chain_first[blockIdx.x], s1 = chain_first[blockIdx.x + 1];
+  for (int s = s0; s < s1; ++s) {
     const int e = pairs[2 * s], c = pairs[2 * s + 1];
     for (int j = threadIdx.x; j < d; j += 256) {
       const float sg = (j & 1) ? -1.f : 1.f;
@@ -935,10 +937,10 @@ __global__ void __launch_bounds__(256) split_kernel(float *Y, int64_t ldy, int32
     __syncthreads();
   }
 }
-hipError_t launch_split(float *Y, int64_t ldy, int32_t d, const int32_t *pairs_dev, int32_t nsplit, float eps,
-                        hipStream_t st) {
-  if (nsplit <= 0) return hipSuccess;
-  hipLaunchKernelGGL(split_kernel, dim3(1), dim3(256), 0, st, Y, ldy, d, pairs_dev, nsplit, eps);
+hipError_t launch_split(float *Y, int64_t ldy, int32_t d, const int32_t *pairs_dev, const int32_t *chain_first_dev,
+                        int32_t nchains, float eps, hipStream_t st) {
+  if (nchains <= 0) return hipSuccess;
+  hipLaunchKernelGGL(split_kernel, dim3((unsigned)nchains), dim3(256), 0, st, Y, ldy, d, pairs_dev, chain_first_dev, eps);
   return hipGetLastError();
 }
 
