@@ -507,6 +507,34 @@ def test_filtered_first_iteration_is_the_exact_assignment(skm, orc, dg):
     assert got.trace[0]["gather_pairs"] < 40 * n      # a handful of candidates per point, not the k of a full scan
 
 
+def test_filtered_first_iteration_falls_back_when_the_candidates_flood_the_list(skm, orc):
+    """A blob so tight that every centroid lies inside every point's rounding band: the one-product pass cannot rule out
+    anything, the candidate list (16 slots per point and list part) overflows, and the step must notice and run the
+    full three-product GEMM instead, with the exact result."""
+    rng = np.random.default_rng(23)
+    n, d, k = 4000, 64, 400
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    X = (u[None, :] + 0.045 * rng.standard_normal((n, d)) / np.sqrt(d)).astype(np.float32)   # pairwise ||x - y||^2 ~ 0.004
+    R = orc.random_rotation(d, 6)
+    idx = orc.sample_rows(3, n, k)
+    got = skm.fit(cuda(X), k, 1, 3, skm.FitOptions(R=cuda(R), final_assign=False, screen=1))
+    assert got.trace[0]["screen_dims"] == 0 and got.trace[0]["gather_pairs"] == 0      # the fallback's counters
+    Xr = orc.rotate(X, R)
+    a_ref, d_ref = orc.assign_full(Xr, Xr[idx])
+    a = got.assign.cpu().numpy()
+    check_assignment(a, a_ref, Xr, Xr[idx], min_agree=0.995)
+    same = a == a_ref
+    assert np.abs(got.dist.cpu().numpy()[same] - d_ref[same]).max() < 2e-5 * max(1.0, d_ref.max())
+    # half as many centroids fit the list: the filtered path then runs to the end and agrees as well
+    k2 = 100
+    got2 = skm.fit(cuda(X), k2, 1, 3, skm.FitOptions(R=cuda(R), final_assign=False, screen=1))
+    assert got2.trace[0]["screen_dims"] > 0 and got2.trace[0]["gather_pairs"] > 50 * n
+    idx2 = orc.sample_rows(3, n, k2)
+    a2_ref, _ = orc.assign_full(Xr, Xr[idx2])
+    check_assignment(got2.assign.cpu().numpy(), a2_ref, Xr, Xr[idx2], min_agree=0.995)
+
+
 def test_fit_is_bitwise_reproducible(skm, orc, dg):
     X = cuda(dg.mixture(30_000, 128, 64, 12, "linear").numpy())
     R = cuda(orc.random_rotation(128, 2))
