@@ -249,7 +249,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--own-workspace", action="store_true",
                     help="let the library allocate and free its workspace inside every call (default: the caller lends it)")
-    ap.add_argument("--cpu-sample", type=int, default=12288)
+    ap.add_argument("--cpu-sample", type=int, default=24576)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 1 GiB device copy first (a kernel of known traffic for scaling rocprofv3 --pmc counters)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
