@@ -479,13 +479,16 @@ struct Ctx {
     sub_cap = ((tiles_chunk + kSubLists - 1) / kSubLists) * per_tile;
     // the filtered iteration 1 lists a few candidates per point in the same list (if it ever overflows, the step is
     // redone with the full GEMM): room for 16 per point of a chunk in each of the eight parts
-    if (screen_mode > 0 || (screen_mode == 0 && k >= 2 * progressive_tile_cols()))
-      sub_cap = std::max<int64_t>(sub_cap, 16 * std::min<int64_t>(chunk_rows, n));
+    // (the kernels behind the filter address a listed centroid's row with 32-bit offsets: not for a centroid table of
+    // 2^31 words or more, where the steps simply run unfiltered)
+    const bool may_screen = (screen_mode > 0 || (screen_mode == 0 && k >= 2 * progressive_tile_cols())) &&
+                            (int64_t)k * (ds + 32) < ((int64_t)1 << 31);
+    if (may_screen) sub_cap = std::max<int64_t>(sub_cap, 16 * std::min<int64_t>(chunk_rows, n));
     pair_cap = sub_cap * kSubLists;
     if (pair_cap >= ((int64_t)1 << 32)) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
     HIPCHK(pool.get(&pairs, (size_t)pair_cap));
     ncounters = (size_t)nchunks * (kSubLists + 16) * kSubListStride;   // list fill counters, tile counters of the two tile kernels
-    if (screen_mode > 0 || (screen_mode == 0 && k >= 2 * progressive_tile_cols())) {   // (unless forced: of no use below two column tiles)
+    if (may_screen) {   // (unless forced: of no use below two column tiles)
       // one bit per (row tile, centroid); at most one tile of listed columns per (row tile, column tile) of the chunk
       const int64_t nrt_chunk = (std::min<int64_t>(chunk_rows, n) + 127) / 128;
       HIPCHK(pool.get(&colmask, (size_t)nrt_chunk * 4 * (size_t)col_tiles));
