@@ -172,6 +172,7 @@ class FitOptions:
     tau_group: int = 0
     screen: int = 0                          # low-precision first filter: 0 = by the previous step's prune fraction, 1 = always, -1 = never
     own_workspace: bool = False              # True: the library allocates and frees its workspace inside the call
+    workspace: "torch.Tensor | None" = None  # a uint8 device tensor to lend as is (default: one of workspace_bytes())
 
 
 @dataclass
@@ -240,6 +241,12 @@ def _lend_workspace(p: Params, o: FitOptions, n: int, d: int, k: int, device, ke
     """The workspace as a torch tensor (device memory is torch's business: its caching allocator hands the same block
     to the next call, so repeated fits allocate nothing).  Skipped for the variants that do not take one."""
     if o.own_workspace or (0.0 < o.sample_frac < 1.0):
+        return
+    if o.workspace is not None:
+        ws = _dev(o.workspace, torch.uint8, "workspace")
+        keep.append(o.workspace)
+        p.workspace = ws.value
+        p.workspace_bytes = o.workspace.numel()
         return
     nbytes = workspace_bytes(n, d, k, p)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=device)

@@ -535,6 +535,29 @@ def test_filtered_first_iteration_falls_back_when_the_candidates_flood_the_list(
     check_assignment(got2.assign.cpu().numpy(), a2_ref, Xr, Xr[idx2], min_agree=0.995)
 
 
+def test_lent_workspace_changes_nothing_and_a_small_one_is_refused(skm, dg):
+    """A fit in a workspace lent by the caller (whatever bytes it holds) gives the bits of a fit that allocates its
+    own; a workspace below skm_workspace_bytes is refused with the out-of-memory code before anything runs."""
+    X = cuda(dg.mixture(20_000, 128, 60, 3, "linear").numpy())
+    k, iters = 300, 6
+    own = skm.fit(X, k, iters, 5, skm.FitOptions(own_workspace=True))
+    need = skm.workspace_bytes(20_000, 128, k)
+    ws = torch.randint(0, 256, (need,), dtype=torch.uint8, device="cuda")     # garbage: nothing may be assumed zero
+    lent = skm.fit(X, k, iters, 5, skm.FitOptions(workspace=ws))
+    assert torch.equal(own.assign, lent.assign) and torch.equal(own.centroids, lent.centroids)
+    assert torch.equal(own.dist, lent.dist)
+    assert [t["survivors"] for t in own.trace] == [t["survivors"] for t in lent.trace]
+    again = skm.fit(X, k, iters, 5, skm.FitOptions(workspace=ws))             # and on what the last call left behind
+    assert torch.equal(own.assign, again.assign) and torch.equal(own.centroids, again.centroids)
+    with pytest.raises(skm.SkmError, match="memory"):
+        skm.fit(X, k, iters, 5, skm.FitOptions(workspace=ws[: need // 2]))
+    # the step call takes a workspace of its own size the same way
+    prev = own.assign
+    a0, d0, _ = skm.assign(X, own.centroids, prev, 0, skm.FitOptions(own_workspace=True))
+    a1, d1, _ = skm.assign(X, own.centroids, prev, 0, skm.FitOptions(workspace=ws))
+    assert torch.equal(a0, a1) and torch.equal(d0, d1)
+
+
 def test_fit_is_bitwise_reproducible(skm, orc, dg):
     X = cuda(dg.mixture(30_000, 128, 64, 12, "linear").numpy())
     R = cuda(orc.random_rotation(128, 2))
