@@ -357,6 +357,8 @@ struct Ctx {
   unsigned char *subkey = nullptr;   // [n] scratch: the key that orders the points inside a cluster
   bool regroup_ok = false;       // the caller has enough steps left for it to pay
   int32_t max_cluster = -1;      // size of the largest cluster at the last update (-1: none yet)
+  bool group_now = false;        // a single step that groups the points by their incumbents itself (assign_impl)
+  int32_t *grp_cnt = nullptr;    // [k] sizes of those groups
   bool order_fresh = false;      // up.order groups the points by the labels now in `prev`
   bool permuted = false;
   unsigned long long *point_keys = nullptr;   // keys that name points (ETR ground truth): renumbered with the points
@@ -786,6 +788,18 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   // (not before one pruned step has run: the labels of iteration 1, assigned against the initial rows, group the points
   // far less usefully than those of iteration 2)
   bool regroup = c.regroup_ok && !c.permuted && c.xnp_valid && c.order_fresh && c.Xr2 && have_prev && c.pruned_steps >= 1;
+  if (c.group_now && !c.permuted && c.Xr2) {
+    // A step on its own (no update before it left an order): the points are grouped by the incumbents they come with
+    // (or were just given above), so that a row tile holds the points of one or two clusters and the first filter has
+    // columns to drop.  One read-back of the group sizes decides whether the order is reproducible (see below).
+    HIPCHK(launch_group_order(c.prev, c.n, c.k, c.grp_cnt, c.up.off, c.up.cursor, c.up.segoff, c.up.order, c.st));
+    HIPCHK(hipMemcpyAsync(c.rb_cnt, c.grp_cnt, sizeof(int32_t) * (size_t)c.k, hipMemcpyDeviceToHost, c.st));
+    HIPCHK(hipStreamSynchronize(c.st));
+    c.max_cluster = *std::max_element(c.rb_cnt, c.rb_cnt + c.k);
+    c.rb_cnt_valid = false;
+    regroup = true;
+    c.group_now = false;
+  }
   if (regroup) {
     // The update leaves the members of a cluster sorted by index only up to a size (larger clusters keep the order in
     // which the scatter placed them, which depends on scheduling): with such a cluster the new order, and with it the
@@ -1140,6 +1154,11 @@ int ground_truth_keys(Pool &pool, const float *X, int64_t n, int32_t d, const fl
   return SKM_OK;
 }
 
+// A single assignment step regroups the points itself (see assign_impl) when there are thousands of centroids, several
+// points per centroid, rows that the regrouping pass covers, and the first filter is not switched off.
+inline bool assign_groups(int64_t n, int32_t ds, int32_t k, int32_t screen_mode) {
+  return screen_mode >= 0 && k >= 4096 && n >= 8 * (int64_t)k && ds <= 2048 && n < ((int64_t)1 << 31);
+}
 int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, int32_t k, const int32_t *prev_assign,
                 int32_t dprime_in, const skm_params *pp, int32_t *assign_out, float *dist_out);
 int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, uint64_t seed, const skm_params &p,
@@ -1692,7 +1711,8 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
   HostTimes host;
   const size_t ds0 = (size_t)round_up(d, 16);
   const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, false);
-  CallArena ws(plan ? plan + (size_t)n * ds0 * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + ((size_t)32 << 20) : 0,
+  const size_t grouping = assign_groups(n, (int32_t)ds0, k, p.screen) ? (size_t)n * ds0 * 4 + (size_t)n * 9 + (size_t)k * 20 + 4096 : 0;
+  CallArena ws(plan ? plan + grouping + (size_t)n * ds0 * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + ((size_t)32 << 20) : 0,
                p.workspace, p.workspace_bytes);
   if (ws.too_small) return fail(SKM_ENOMEM, "params->workspace is smaller than skm_workspace_bytes() for this call");
   host.workspace_ready();
@@ -1735,12 +1755,32 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
     if (rc) return rc;
     HIPCHK(hipMemcpyAsync(c.prev, prev_assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
   }
+  // Many centroids: a step on its own pays for what a fit does once in its third step.  The points are rewritten
+  // grouped by their incumbents and the first filter runs in front of the exact kernel (a million tiles of two slabs
+  // each otherwise: the fixed costs of a tile, not the arithmetic, are then the whole run time).
+  if (assign_groups(n, c.ds, k, p.screen) && c.colmask) {
+    HIPCHK(c.pool.get(&c.Xr2, (size_t)n * c.ds));
+    HIPCHK(c.pool.get(&c.pos_to_id, (size_t)n));
+    HIPCHK(c.pool.get(&c.subkey, (size_t)n));
+    HIPCHK(c.pool.get(&c.up.off, (size_t)k + 1));
+    HIPCHK(c.pool.get(&c.up.cursor, (size_t)k));
+    HIPCHK(c.pool.get(&c.up.segoff, (size_t)k + 1));
+    HIPCHK(c.pool.get(&c.up.order, (size_t)n));
+    HIPCHK(c.pool.get(&c.grp_cnt, (size_t)k));
+    c.group_now = true;
+    c.last_prune_frac = 1.0;   // the filter runs: with points grouped and thousands of centroids it has columns to drop
+  }
   const int32_t dprime = dprime_in > 0 ? snap16((double)dprime_in, d) : dprime_init(d, p.dprime_frac);
   StepStats ss;
   rc = step_pruned(c, tm, dprime, (double)p.eps0, prev_assign != nullptr, ss);
   if (rc) return rc;
-  HIPCHK(hipMemcpyAsync(assign_out, c.assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
-  if (dist_out) HIPCHK(hipMemcpyAsync(dist_out, c.dist, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+  if (c.permuted) {   // per-point results back in the caller's order
+    HIPCHK(launch_scatter_by_index(c.assign, c.pos_to_id, n, assign_out, c.st));
+    if (dist_out) HIPCHK(launch_scatter_by_index(c.dist, c.pos_to_id, n, dist_out, c.st));
+  } else {
+    HIPCHK(hipMemcpyAsync(assign_out, c.assign, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+    if (dist_out) HIPCHK(hipMemcpyAsync(dist_out, c.dist, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, c.st));
+  }
   HIPCHK(hipStreamSynchronize(c.st));
   float ms[ST_COUNT], total;
   tm.collect(ms, &total);

@@ -262,6 +262,10 @@ struct UpdateWs {
   int64_t max_segments;
 };
 int64_t update_max_segments(int64_t n, int32_t k);
+// The grouping half of launch_update alone: cnt[k] sizes, off[k+1] starts, order[n] point ids grouped by label (cursor[k]
+// and segoff[k+1] are scratch).
+hipError_t launch_group_order(const int32_t *labels, int64_t n, int32_t k, int32_t *cnt, int32_t *off, int32_t *cursor,
+                              int32_t *segoff, int32_t *order, hipStream_t st);
 // largest cluster whose members launch_update leaves sorted by index in w.order (larger ones: any order)
 int32_t update_sort_cap();
 // S (optional, [k][ds] fp64) receives the sum of every cluster; y_absmax (optional) the bit pattern of max |Y| of

@@ -877,6 +877,23 @@ hipError_t launch_update(const float *Xr, int64_t ldx, int64_t n, int32_t ds, co
   return hipGetLastError();
 }
 
+// order[] = the point ids grouped by label (members of a cluster of at most SORT_CAP points in ascending order), off[] the
+// start of every group, cnt[] the group sizes: the first half of launch_update, for callers that only want the grouping.
+hipError_t launch_group_order(const int32_t *labels, int64_t n, int32_t k, int32_t *cnt, int32_t *off, int32_t *cursor,
+                              int32_t *segoff, int32_t *order, hipStream_t st) {
+  hipError_t rc = launch_fill_u32(reinterpret_cast<unsigned int *>(cnt), k, 0u, st);
+  if (rc != hipSuccess) return rc;
+  rc = launch_histogram(labels, n, cnt, st);
+  if (rc != hipSuccess) return rc;
+  hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, st, cnt, k, off, cursor, segoff);
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(scatter_order_kernel, dim3((unsigned)blocks), dim3(256), 0, st, labels, n, off, cursor, order,
+                     (const int32_t *)nullptr);
+  hipLaunchKernelGGL(sort_segments_kernel, dim3(k), dim3(256), 0, st, off, order);
+  return hipGetLastError();
+}
+
 // The same update from the points that changed label only: S (the cluster sums of the previous update) takes the
 // rows of the points that joined minus those of the points that left, and every centroid is S / size again.
 // w.cnt holds the new cluster sizes; `changed` is the number of points with assign != prev (known to the host from
