@@ -654,11 +654,13 @@ struct StepStats {
 // lists, for every point, the centroids that can be its nearest; the gather kernel takes their exact distances and the
 // packed minimum is the exact nearest centroid (lowest index on ties).  A third of the matrix work of the full
 // three-product GEMM; pays once there are enough centroids.
-int step_exact_filtered(Ctx &c, StageTimer &tm, StepStats &ss) {
-  tm.mark(ST_NONE);
-  if (int rc = c.clear_step_block()) return rc;
-  const int32_t nb_all = (c.ds + kBlockDims - 1) / kBlockDims;
-  if (nb_all > kMaxBlocks) return fail(SKM_EINTERNAL, "too many blocks");
+// c.best[i] = packed (squared distance over dims [0, K), centroid) of the centroid nearest to point i on those dims,
+// exact (direct form, lowest index on ties): the one-product multiply over K dims lists the candidates, the gather
+// kernel takes their distances.  K = ds: the nearest centroid; K = d': the incumbent of a step that comes without one.
+// Clobbers ynorm, Ypdx, Ys / Yh, ratio_dev, tau; sets bit 0 of the step's flag word if the candidate list overflowed.
+int filtered_nearest(Ctx &c, int32_t K, StageTimer *tm = nullptr) {
+  const int32_t nbK = (K + kBlockDims - 1) / kBlockDims;
+  if (nbK > kMaxBlocks) return fail(SKM_EINTERNAL, "too many blocks");
   if (!c.xnp_valid) {
     // the points' split copy, its hi plane and their norms do not exist before the first pruned step: the pass that
     // writes them runs now (its thresholds, against centroid 0, are discarded)
@@ -667,17 +669,18 @@ int step_exact_filtered(Ctx &c, StageTimer &tm, StepStats &ss) {
                            c.amax + Ctx::AM_XR, nullptr, nullptr, nullptr, c.Xh));
     c.xnp_valid = true;
   }
-  // ||y||^2 and the block-major copy of ALL dimensions (the gather kernel starts every pair at dimension 0)
-  HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, c.ds, c.ynorm, 0, nb_all, c.Ypdx, c.st));
+  // ||y[0 : K)||^2 and the block-major copy of the first K dimensions, zero filled behind them (the gather kernel
+  // starts every pair at dimension 0 and is told that rows end at K)
+  HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, K, K, c.ynorm, 0, nbK, c.Ypdx, c.st));
   if (int rc = c.measure_y()) return rc;
   HIPCHK(launch_split_rows(c.Y, c.ds, c.k, c.ds, c.amax + Ctx::AM_Y, c.Ys, c.st, c.Yh));
   HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
-  unsigned int *rowmin = reinterpret_cast<unsigned int *>(c.tau);   // (no thresholds in this step)
+  unsigned int *rowmin = reinterpret_cast<unsigned int *>(c.tau);   // (no thresholds while this runs)
   HIPCHK(launch_fill_u32(rowmin, c.n, 0xffffffffu, c.st));
   float *ratio = c.ratio_host;
-  for (int m = 0; m <= nb_all; ++m) ratio[m] = 1.f;   // nothing is dropped on the way
-  HIPCHK(hipMemcpyAsync(c.ratio_dev, ratio, sizeof(float) * ((size_t)nb_all + 1), hipMemcpyHostToDevice, c.st));
-  tm.mark(ST_TAU);
+  for (int m = 0; m <= nbK; ++m) ratio[m] = 1.f;   // nothing is dropped on the way
+  HIPCHK(hipMemcpyAsync(c.ratio_dev, ratio, sizeof(float) * ((size_t)nbK + 1), hipMemcpyHostToDevice, c.st));
+  if (tm) tm->mark(ST_TAU);
   for (int32_t ch = 0; ch < c.nchunks; ++ch) {
     const int64_t r0 = (int64_t)ch * c.chunk_rows;
     const int64_t rows = std::min<int64_t>(c.chunk_rows, c.n - r0);
@@ -686,9 +689,9 @@ int step_exact_filtered(Ctx &c, StageTimer &tm, StepStats &ss) {
     sl.A = c.Xh + r0 * (c.ds / 2 + 16); sl.lda = c.ds / 2 + 16; sl.M = (int32_t)rows;
     sl.B = c.Yh; sl.ldb = c.ds / 2 + 16; sl.N = c.k;
     sl.a_absmax = c.amax + Ctx::AM_XR; sl.b_absmax = c.amax + Ctx::AM_Y;
-    sl.ds = c.ds; sl.dprime = c.ds; sl.ratio0 = 1.f;
+    sl.ds = c.ds; sl.dprime = K; sl.ratio0 = 1.f;
     sl.tau = c.tau; sl.row_base = r0;
-    sl.xn = c.xnp + (int64_t)(c.ds / 16 - 1) * c.n;   // the full norms: the last row of the prefix table
+    sl.xn = c.xnp + (int64_t)(K / 16 - 1) * c.n;   // ||x[0 : K)||^2: row K / 16 - 1 of the prefix table
     sl.yn = c.ynorm;
     sl.arow = c.scr_arow; sl.ycol = c.scr_ycol;
     sl.colmask = c.colmask; sl.cnt = c.scr_cnt; sl.first = c.scr_first; sl.ntiles = c.scr_ntiles;
@@ -697,10 +700,17 @@ int step_exact_filtered(Ctx &c, StageTimer &tm, StepStats &ss) {
     sl.exact = 1; sl.rowmin = rowmin; sl.pairs = c.pairs; sl.pair_count = fill; sl.sub_capacity = (unsigned int)c.sub_cap;
     sl.overflow = c.counters + c.ncounters;
     HIPCHK(launch_screen(sl, c.st));
-    PruneArgs pa{c.pairs, fill, (unsigned int)c.sub_cap, c.Xr, c.ldx, c.n, c.Ypdx, c.k, 0, c.ds, nb_all, c.ratio_dev,
+    PruneArgs pa{c.pairs, fill, (unsigned int)c.sub_cap, c.Xr, c.ldx, c.n, c.Ypdx, c.k, 0, K, nbK, c.ratio_dev,
                  c.best, c.scal, 0};
     HIPCHK(launch_prune(pa, c.st));
   }
+  return SKM_OK;
+}
+
+int step_exact_filtered(Ctx &c, StageTimer &tm, StepStats &ss) {
+  tm.mark(ST_NONE);
+  if (int rc = c.clear_step_block()) return rc;
+  if (int rc = filtered_nearest(c, c.ds, &tm)) return rc;
   tm.mark(ST_GEMM);
   // the packed minima already hold the direct distances
   HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.assign, c.dist, c.up.cnt, c.k, c.obj_partial, nullptr,
@@ -769,6 +779,20 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   const int32_t nb = (c.d - dprime + kBlockDims - 1) / kBlockDims;
   if (nb > kMaxBlocks) return fail(SKM_EINTERNAL, "too many trailing blocks");
   tm.mark(ST_NONE);
+  bool found = false;   // the incumbents of a step that came without them are in c.prev
+  if (!have_prev && c.colmask && !c.exact_filter_off && (c.screen_mode > 0 || c.k >= 2048)) {
+    // many centroids: the nearest centroid on the first d' dimensions through the low-precision filter (a third of
+    // the matrix work of the three-product GEMM below); if its candidate list overflows, that GEMM runs after all
+    if (int rc = c.clear_step_block()) return rc;
+    if (int rc = filtered_nearest(c, dprime, &tm)) return rc;
+    HIPCHK(launch_finalize_assign(c.best, nullptr, c.n, c.prev, nullptr, nullptr, c.k, nullptr, nullptr, c.counters + c.ncounters, c.st));
+    HIPCHK(hipMemcpyAsync(c.rb_flag, c.counters + c.ncounters, sizeof(unsigned int), hipMemcpyDeviceToHost, c.st));
+    HIPCHK(hipStreamSynchronize(c.st));
+    if (*c.rb_flag == 0) found = true;
+    else if (*c.rb_flag & 1u) c.exact_filter_off = true;
+    else return fail(SKM_EINTERNAL, "a point was left without a centroid");
+    tm.mark(ST_GEMM);
+  }
   HIPCHK(launch_prep_centroids(c.Y, c.ds, c.k, c.ds, dprime, c.ynorm, dprime, nb, c.Ypdx, c.st, c.ynp));
   if (int rc = c.measure_y()) return rc;
   // theta ratio at checkpoint m: t_m = min(d, d' + 64 m) dimensions seen
@@ -776,7 +800,7 @@ int step_pruned(Ctx &c, StageTimer &tm, int32_t dprime, double eps0, bool have_p
   for (int m = 0; m <= nb; ++m) ratio[m] = (float)theta_ratio(c.d, std::min(c.d, dprime + kBlockDims * m), eps0);
   HIPCHK(hipMemcpyAsync(c.ratio_dev, ratio, sizeof(float) * ((size_t)nb + 1), hipMemcpyHostToDevice, c.st));
   if (int rc = c.clear_step_block()) return rc;
-  if (!have_prev) {
+  if (!have_prev && !found) {
     HIPCHK(launch_fill_u64(c.best, c.n, ~0ull, c.st));
     GemmOperands g0{c.Xr, c.ldx, (int32_t)c.n, c.Y, c.ds, c.k, dprime};
     g0.a_absmax = c.amax + Ctx::AM_XR; g0.b_absmax = c.amax + Ctx::AM_Y;

@@ -248,6 +248,33 @@ def test_pruned_step_without_previous_assignment(skm, orc, dg):
     check_assignment(a.cpu().numpy(), ref.assign, Xr, Yr)
 
 
+@pytest.mark.parametrize("n,d,k,dp", [(6000, 208, 300, 48), (3000, 128, 257, 16), (5000, 1536, 300, 192),
+                                      (4000, 100, 130, 80)])
+def test_step_without_previous_assignment_finds_its_incumbents_through_the_filter(skm, orc, dg, n, d, k, dp):
+    """A step that comes without incumbents takes, for every point, the centroid nearest on the first d' dimensions.  With
+    the first filter on, that search is the one-product multiply over d' dimensions plus exact distances for the few
+    candidates (d' not a multiple of 64: the last gathered block is cut at d').  Same oracle, same contract, and the
+    same counters as the search by the three-product GEMM."""
+    say("no incumbents, filtered search", n, d, k, dp)
+    X, R, Y, Xr, Yr, _ = pruned_case(orc, dg, n, d, k, n + d, "linear" if d < 512 else "embed")
+    ref = orc.assign_pruned(Xr, Yr, None, dp, EPS0, 0)
+    a1, d1, row1 = skm.assign(cuda(X), cuda(Y), None, dp, skm.FitOptions(R=cuda(R), block_stats=True, screen=1))
+    a0, d0, row0 = skm.assign(cuda(X), cuda(Y), None, dp, skm.FitOptions(R=cuda(R), block_stats=True, screen=-1))
+    for a, dist, row in ((a1, d1, row1), (a0, d0, row0)):
+        a = a.cpu().numpy()
+        check_assignment(a, ref.assign, Xr, Yr)
+        same = a == ref.assign
+        assert np.abs(dist.cpu().numpy()[same] - ref.dist[same]).max() < 2e-5 * max(1.0, ref.dist.max())
+        surv_ref = n * (k - 1) - ref.pruned_first
+        assert abs(row["survivors"] - surv_ref) <= max(2, 1e-3 * surv_ref)
+        assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])
+        assert row["objective"] == pytest.approx(ref.dist.sum(), rel=1e-5)
+    assert row1["screen_dims"] > 0 and row0["screen_dims"] == 0
+    # the two searches may pick different incumbents only at ties of the partial distance: a handful of points
+    assert abs(row1["survivors"] - row0["survivors"]) <= max(2, 1e-4 * row0["survivors"])
+    assert (a1 != a0).sum().item() <= 2
+
+
 def test_pruned_step_without_statistical_test_is_exact(skm, orc, dg):
     X, R, Y, Xr, Yr, prev = pruned_case(orc, dg, 3000, 144, 77, 9, "linear")
     exact, _ = orc.assign_full(Xr, Yr)
