@@ -14,7 +14,7 @@ config, per-iteration seconds, host-clock figures (wall time of a call, wall min
 dominant kernel (algorithmic flop per launch over its HIP-event time, against the dense fp16 matrix peak divided by
 the three products of the split arithmetic), `stages` with the same figures for every kernel family,
 `other_workloads` (the rest of the metric's range, k = 4096 ... 32 768: C4, C3, C5, a few timed fits each, same
-figures) and `cpu_baseline` (the CPU oracle timed on a bounded sample of the headline workload).
+figures), `hierarchical` (the hierarchical fit of C4 beside the flat one) and `cpu_baseline` (the CPU oracle timed on a bounded sample of the headline workload).
 """
 from __future__ import annotations
 
@@ -245,6 +245,8 @@ def main():
     ap.add_argument("--config", default="C2", help="headline workload (a name in paper_2603_20009_amd.datagen.CONFIGS)")
     ap.add_argument("--others", default="C4,C3,C5",
                     help="further workloads timed in the same run (comma separated, '' for none): 1 untimed + 3 timed fits each")
+    ap.add_argument("--hierarchical", default="C4",
+                    help="workload on which the hierarchical fit is timed beside the flat one ('' for none)")
     ap.add_argument("--n", type=int, default=0, help="override the number of points of the headline workload (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--own-workspace", action="store_true",
@@ -298,6 +300,29 @@ def main():
         del Xo, ro
         torch.cuda.empty_cache()
     out["other_workloads"] = others
+    if args.hierarchical and args.hierarchical in datagen.CONFIGS:
+        # Hierarchical SuperKMeans (Section 6) on one of the workloads, beside the flat fit of the same k: wall time of
+        # whole calls (rotation, meso phase, fine phase, final assignment of all points), 1 untimed + 2 timed
+        hc = datagen.CONFIGS[args.hierarchical]
+        Xh = datagen.config_data(args.hierarchical, device="cuda")
+        torch.cuda.synchronize()
+        times = []
+        for rep in range(3):
+            t0 = time.time()
+            hr, sizes, counts = skm.fit_hierarchical(Xh, hc["k"], datagen.SEED_FIT)
+            torch.cuda.synchronize()
+            times.append((time.time() - t0) * 1e3)
+        flat = others.get(args.hierarchical, out if args.hierarchical == args.config else None)
+        out["hierarchical"] = {
+            "workload": args.hierarchical, "k": hc["k"], "meso_clusters": len(sizes), "meso_iters": 3, "fine_iters": 5,
+            "ms_per_fit": float(sum(times[1:]) / 2), "ms_meso_phase": hr.timing["ms_meso"], "ms_fine_phase": hr.timing["ms_fine"],
+            "ms_final_assignment": hr.trace[-1]["ms_step"], "final_prune_frac": hr.trace[-1]["prune_frac"],
+            "objective": hr.trace[-1]["objective"],
+            "objective_over_flat_fit": (hr.trace[-1]["objective"] / flat["objective_final"]) if flat else None,
+            "ms_flat_fit": flat["ms_per_step"] if flat else None,
+        }
+        del Xh, hr
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(Xs, cfg["k"], cfg["iters"], datagen.SEED_FIT, Rn, cores)
     print(json.dumps(out))

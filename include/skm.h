@@ -139,10 +139,13 @@ typedef struct skm_params {
                             one point in eight changes its cluster, the fp64 sums of the previous update are
                             corrected by the rows that joined and left (the same means up to fp64 rounding) */
   void *workspace;       /* NULL : device memory, 256-byte aligned, of at least skm_workspace_bytes(n, d, k, params)
-                            bytes that skm_fit_ex / skm_assign_ex use instead of allocating their own.  With it the
-                            call makes no device allocation at all; a workspace that is too small is refused with
-                            SKM_ENOMEM before any work is enqueued.  Contents are undefined afterwards.  The other
-                            entry points ignore it */
+                            bytes (skm_hier_workspace_bytes for the hierarchical fit) that skm_fit_ex (also with
+                            sample_frac), skm_assign_ex and skm_fit_hierarchical use instead of allocating their own.
+                            With it the call makes no device allocation at all; a workspace that is too small is
+                            refused with SKM_ENOMEM before any work is enqueued (the hierarchical fit runs its fine
+                            phase with as many concurrent fits, at most eight, as the workspace holds; one that cannot
+                            hold the largest fine fit is refused at that point).  Contents are undefined afterwards.
+                            skm_fit_host ignores it */
   int64_t workspace_bytes; /* 0  : size of `workspace` */
   float conv_tol;        /* 0    : > 0 = also stop (Section 3.3, the second termination condition) after an iteration
                             t >= 2 in which at most this share of the points changed its cluster */
@@ -168,6 +171,10 @@ void skm_params_default(skm_params *p);
  * call allocates itself when params->workspace is NULL, and what a caller-owned workspace must hold.  params may be
  * NULL (defaults).  Returns a negative SKM_E* code for an invalid shape. */
 int64_t skm_workspace_bytes(int64_t n, int32_t d, int32_t k, const skm_params *params);
+/* The same for skm_fit_hierarchical: the rotated rows, the centroids and membership arrays, and below them the largest
+ * of the meso fit, the final assignment and the worst case of the fine phase (one meso-cluster holding nearly every row
+ * and cluster: with balanced meso-clusters eight concurrent fine fits need a fraction of that). */
+int64_t skm_hier_workspace_bytes(int64_t n, int32_t d, int32_t k, const skm_params *params);
 
 /*
  * skm_fit -- Algorithm 1 with default parameters.

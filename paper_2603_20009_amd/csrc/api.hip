@@ -627,8 +627,32 @@ struct HostTimes {
 // Upper bound of the device bytes one plain fit (or one assignment call) of this shape carves from its arena: the
 // context's buffers, the rotated points and their regrouped copy, the rotation matrices and their generator, the ETR
 // buffers.  What skm_workspace_bytes reports.
+inline bool assign_groups(int64_t n, int32_t ds, int32_t k, int32_t screen_mode);
+// ... of one assignment call (assign_impl)
+size_t assign_workspace_need(int64_t n, int32_t d, int32_t k, const skm_params &p) {
+  const size_t ds0 = (size_t)((d + 15) / 16 * 16);
+  const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, false);
+  if (!plan) return 0;
+  const size_t grouping = assign_groups(n, (int32_t)ds0, k, p.screen) ? (size_t)n * ds0 * 4 + (size_t)n * 9 + (size_t)k * 20 + 4096 : 0;
+  return plan + grouping + (size_t)n * ds0 * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + ((size_t)32 << 20);
+}
+int64_t sample_size(int64_t n, int32_t k, float frac) {
+  const int64_t s = (int64_t)std::llround((double)frac * (double)n);
+  return std::min<int64_t>(std::max<int64_t>(s, k), n);
+}
 size_t fit_workspace_need(int64_t n, int32_t d, int32_t k, const skm_params &p) {
   const size_t ds0 = (size_t)((d + 15) / 16 * 16);
+  if (p.sample_frac > 0.f && p.sample_frac < 1.f) {
+    // the sampled fit: all rows rotated (and a dense copy of them when d is no multiple of 16), the sample, the
+    // centroids, and below them first the fit on the sample, then the assignment of all rows
+    skm_params q = p;
+    q.sample_frac = 0.f;
+    const int64_t s = sample_size(n, k, p.sample_frac);
+    const size_t a = fit_workspace_need(s, d, k, q), b = assign_workspace_need(n, d, k, q);
+    if (!a || !b) return 0;
+    return std::max(a, b) + (size_t)n * ds0 * 4 + (ds0 != (size_t)d ? (size_t)n * d * 4 : 0) + (size_t)s * (8 + (size_t)d * 4) +
+           (size_t)k * (d + ds0) * 4 + (size_t)n * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + ((size_t)32 << 20);
+  }
   const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, true);
   if (!plan) return 0;
   size_t need = plan + 2 * (size_t)n * ds0 * 4 + (size_t)n * 5 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 +
@@ -1733,11 +1757,7 @@ int assign_impl(const float *X, int64_t n, int32_t d, const float *centroids, in
     return fail(SKM_EINVAL, "tau_group: only 0 (= k, the threshold frozen for the whole step) is implemented");
   skm_trace *tr = p.trace;
   HostTimes host;
-  const size_t ds0 = (size_t)round_up(d, 16);
-  const size_t plan = plan_common_bytes(n, d, k, p.pair_budget, p.dense_frac, false);
-  const size_t grouping = assign_groups(n, (int32_t)ds0, k, p.screen) ? (size_t)n * ds0 * 4 + (size_t)n * 9 + (size_t)k * 20 + 4096 : 0;
-  CallArena ws(plan ? plan + grouping + (size_t)n * ds0 * 4 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + ((size_t)32 << 20) : 0,
-               p.workspace, p.workspace_bytes);
+  CallArena ws(assign_workspace_need(n, d, k, p), p.workspace, p.workspace_bytes);
   if (ws.too_small) return fail(SKM_ENOMEM, "params->workspace is smaller than skm_workspace_bytes() for this call");
   host.workspace_ready();
   Ctx c;
@@ -1824,10 +1844,15 @@ int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, 
                 float *centroids_out, int32_t *assign_out, float *dist_out) {
   if (p.etr) return fail(SKM_EINVAL, "sample_frac and ETR cannot be combined");
   if (!p.final_assign) return fail(SKM_EINVAL, "sample_frac needs the final assignment pass");
-  int64_t s = (int64_t)std::llround((double)p.sample_frac * (double)n);
-  s = std::min<int64_t>(std::max<int64_t>(s, k), n);
+  const int64_t s = sample_size(n, k, p.sample_frac);
   hipStream_t st = (hipStream_t)p.stream;
   const int32_t ds = round_up(d, 16);
+  HostTimes host;
+  // one workspace for the whole call (the caller's, if it lends one); the nested fit and the nested assignment carve
+  // theirs from it, one after the other
+  CallArena ws(fit_workspace_need(n, d, k, p), p.workspace, p.workspace_bytes);
+  if (ws.too_small) return fail(SKM_ENOMEM, "params->workspace is smaller than skm_workspace_bytes() for this call");
+  host.workspace_ready();
   Pool pool;
   Events evs;
   hipEvent_t e0 = evs.next(), e1 = evs.next();
@@ -1864,7 +1889,7 @@ int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, 
   pin.rotate = 0;
   pin.R = nullptr;
   pin.final_assign = 0;
-  pin.workspace = nullptr;   // the nested calls allocate their own
+  pin.workspace = nullptr;   // the nested calls carve from the arena of this call
   pin.workspace_bytes = 0;
   skm_trace inner{};
   skm_trace *tr = p.trace;
@@ -1920,8 +1945,24 @@ int fit_sampled(const float *X, int64_t n, int32_t d, int32_t k, int32_t iters, 
     tr->ms_etr_gt = 0.f;
     tr->ms_unrotate = 0.f;
     (void)hipEventElapsedTime(&tr->ms_total, e0, e1);
+    host.body_done(tr);
   }
   return SKM_OK;
+}
+
+// Upper bound of what a hierarchical fit carves from its workspace: the rotated rows (and a dense copy when d is no
+// multiple of 16), the meso and fine centroids, the membership arrays, and below them, one after the other, the meso
+// fit, the fine phase and the final assignment.  The fine phase is bounded by its worst case, a single meso-cluster
+// that holds nearly all rows and clusters; with balanced meso-clusters eight workers fit in that room many times over.
+size_t hier_workspace_need(int64_t n, int32_t d, int32_t k, const skm_params &p) {
+  const size_t ds0 = (size_t)((d + 15) / 16 * 16);
+  skm_params q = p;
+  q.sample_frac = 0.f;
+  q.etr = 0;
+  const size_t a = fit_workspace_need(n, d, k, q), b = assign_workspace_need(n, d, k, q);
+  if (!a || !b) return 0;
+  return std::max(a + (size_t)n * d * 4 + (size_t)n * 4 + 4096, b) + (size_t)n * ds0 * 4 + (ds0 != (size_t)d ? (size_t)n * d * 4 : 0) +
+         (size_t)k * (2 * (size_t)d + ds0) * 4 + (size_t)n * 16 + 10 * (size_t)d * ds0 * 4 + (size_t)d * 16384 + ((size_t)32 << 20);
 }
 
 // Hierarchical SuperKMeans (Section 6): Algorithm 1 with sqrt(k) clusters on all points (MESO), then Algorithm 1 inside
@@ -1945,6 +1986,10 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
   if (tr && (!tr->row || tr->capacity < 1)) return fail(SKM_EINVAL, "trace without rows");
   hipStream_t st = (hipStream_t)p.stream;
   const int32_t ds = round_up(d, 16);
+  HostTimes host;
+  CallArena ws(hier_workspace_need(n, d, k, p), p.workspace, p.workspace_bytes);
+  if (ws.too_small) return fail(SKM_ENOMEM, "params->workspace is smaller than skm_hier_workspace_bytes() for this call");
+  host.workspace_ready();
   Pool pool;
   Events evs;
   hipEvent_t e0 = evs.next(), e1 = evs.next(), e_meso = evs.next(), e_fine = evs.next();
@@ -1972,7 +2017,7 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
   pin.rotate = 0;
   pin.R = nullptr;
   pin.trace = nullptr;
-  pin.workspace = nullptr;   // the nested calls allocate their own
+  pin.workspace = nullptr;   // the nested calls carve from the arena of this call
   pin.workspace_bytes = 0;
 
   // ---- MESO
@@ -2031,11 +2076,22 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
     // The device exposes four hardware queues to a process; twice as many threads still gain a little (2 workers: 152 ms
     // for the fine phase of 1M x 1536 into 16 384 clusters, 4: 124, 8: 120, 12: 116), because the host side of one small
     // fit (some seventy launches and a dozen waits) then overlaps the device side of another.
-    const int nworkers = (int)std::min<int32_t>(8, km);
+    int nworkers = (int)std::min<int32_t>(8, km);
+    // workspace of the largest fine fit (a bound for every other: the need grows with the rows and with the clusters)
+    skm_params pneed = pin;
+    pneed.final_assign = 0;
+    const size_t want = fit_workspace_need(std::max<int64_t>(nmax, 1), d, std::max<int32_t>(kmax, 1), pneed);
+    if (!want) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
+    const size_t per_worker = want + (size_t)std::max<int64_t>(nmax, 1) * d * 4 + 1024;
+    Arena *top = tl_arena;
+    if (top && top->strict) {
+      // a caller's workspace: every worker's share comes out of it, so there are as many workers as shares fit
+      const size_t shares = (top->cap - std::min(top->cap, top->off + 512)) / per_worker;
+      if (shares < 1) return fail(SKM_ENOMEM, "params->workspace cannot hold the largest fine fit");
+      nworkers = (int)std::min<size_t>((size_t)nworkers, shares);
+    }
     std::vector<Worker> workers((size_t)nworkers);
-    // workspace of the largest fine fit, generously: per point the padded row copy, its split-fp16 copy, its table of prefix norms and
-    // the per-point arrays, per centroid three padded rows, plus the hand-over list of a small problem
-    const size_t want = (size_t)nmax * ((size_t)ds * 8 + (size_t)ds / 4 + 256) + (size_t)kmax * (size_t)ds * 24 + ((size_t)256 << 20);
+    Pool fine_pool;   // the workers' buffers and shares: given back to the arena when the fine phase ends
     int dev = 0;
     HIPCHK(hipGetDevice(&dev));
     struct StreamGuard {
@@ -2047,8 +2103,13 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
     } guard{workers};
     for (Worker &w : workers) {
       HIPCHK(hipStreamCreateWithFlags(&w.st, hipStreamNonBlocking));
-      HIPCHK(pool.get(&w.Xs, (size_t)std::max<int64_t>(nmax, 1) * d));
-      if (w.arena.init(want) != hipSuccess) {
+      HIPCHK(fine_pool.get(&w.Xs, (size_t)std::max<int64_t>(nmax, 1) * d));
+      if (top && top->cap - std::min(top->cap, top->off + 512) >= want) {
+        char *share = nullptr;
+        HIPCHK(fine_pool.get(&share, want));
+        w.arena.lend(share, want);
+        w.arena.strict = top->strict;   // the library's own arena: what does not fit may still come from hipMalloc
+      } else if (w.arena.init(want) != hipSuccess) {
         (void)hipGetLastError();
         w.arena.base = nullptr;
         w.arena.cap = 0;   // every buffer of this worker then comes from hipMalloc
@@ -2142,6 +2203,7 @@ int fit_hierarchical(const float *X, int64_t n, int32_t d, int32_t k, int32_t me
     (void)hipEventElapsedTime(&tr->ms_etr_gt, e_meso, e_fine);  // the whole fine phase
     tr->ms_unrotate = 0.f;
     (void)hipEventElapsedTime(&tr->ms_total, e0, e1);
+    host.body_done(tr);
   }
   return SKM_OK;
 }
@@ -2192,6 +2254,16 @@ int64_t skm_workspace_bytes(int64_t n, int32_t d, int32_t k, const skm_params *p
   skm_params p;
   if (params) p = *params; else skm_params_default(&p);
   const size_t need = fit_workspace_need(n, d, k, p);
+  if (!need) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
+  return (int64_t)need + 256;   // room to align the caller's pointer
+}
+
+int64_t skm_hier_workspace_bytes(int64_t n, int32_t d, int32_t k, const skm_params *params) {
+  if (n < 1 || n >= (int64_t)1 << 31 || d < 16 || d > 16384 || k < 1 || k > (1 << 24) || k > n)
+    return fail(SKM_EINVAL, "shape out of range");
+  skm_params p;
+  if (params) p = *params; else skm_params_default(&p);
+  const size_t need = hier_workspace_need(n, d, k, p);
   if (!need) return fail(SKM_EINVAL, "pair_budget too large (must stay below 2^32 pairs)");
   return (int64_t)need + 256;   // room to align the caller's pointer
 }

@@ -61,7 +61,7 @@ EXPORTS = [
     "skm_params_default", "skm_fit", "skm_fit_ex", "skm_assign", "skm_assign_ex", "skm_assign_exact", "skm_update",
     "skm_make_rotation", "skm_rotate", "skm_sample_rows", "skm_theta_ratio", "skm_dprime_init", "skm_dprime_adjust",
     "skm_strerror", "skm_last_error", "skm_version", "skm_fit_hierarchical", "skm_hier_meso_count", "skm_hier_alloc",
-    "skm_fit_host", "skm_workspace_bytes", "skm_debug_gemm_config",
+    "skm_fit_host", "skm_workspace_bytes", "skm_hier_workspace_bytes", "skm_debug_gemm_config",
     "skm_assign_exact_static", "skm_etr_ground_truth",
 ]
 
@@ -96,6 +96,8 @@ def lib():
         L.skm_hier_alloc.argtypes = [vp, i32, i32, vp]
         L.skm_workspace_bytes.argtypes = [i64, i32, i32, C.POINTER(Params)]
         L.skm_workspace_bytes.restype = i64
+        L.skm_hier_workspace_bytes.argtypes = [i64, i32, i32, C.POINTER(Params)]
+        L.skm_hier_workspace_bytes.restype = i64
         L.skm_etr_ground_truth.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp]
         L.skm_etr_ground_truth.restype = C.c_int
         L.skm_debug_gemm_config.argtypes = [i32, i32, i64]
@@ -237,10 +239,18 @@ def workspace_bytes(n: int, d: int, k: int, p: Params | None = None) -> int:
     return nbytes
 
 
-def _lend_workspace(p: Params, o: FitOptions, n: int, d: int, k: int, device, keep: list):
+def hier_workspace_bytes(n: int, d: int, k: int, p: Params | None = None) -> int:
+    """skm_hier_workspace_bytes: device bytes a hierarchical fit of this shape needs as workspace."""
+    nbytes = int(lib().skm_hier_workspace_bytes(n, d, k, None if p is None else C.byref(p)))
+    if nbytes < 0:
+        _check(nbytes)
+    return nbytes
+
+
+def _lend_workspace(p: Params, o: FitOptions, n: int, d: int, k: int, device, keep: list, hierarchical: bool = False):
     """The workspace as a torch tensor (device memory is torch's business: its caching allocator hands the same block
-    to the next call, so repeated fits allocate nothing).  Skipped for the variants that do not take one."""
-    if o.own_workspace or (0.0 < o.sample_frac < 1.0):
+    to the next call, so repeated fits allocate nothing)."""
+    if o.own_workspace:
         return
     if o.workspace is not None:
         ws = _dev(o.workspace, torch.uint8, "workspace")
@@ -248,7 +258,7 @@ def _lend_workspace(p: Params, o: FitOptions, n: int, d: int, k: int, device, ke
         p.workspace = ws.value
         p.workspace_bytes = o.workspace.numel()
         return
-    nbytes = workspace_bytes(n, d, k, p)
+    nbytes = hier_workspace_bytes(n, d, k, p) if hierarchical else workspace_bytes(n, d, k, p)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
     keep.append(ws)
     p.workspace = ws.data_ptr()
@@ -295,6 +305,7 @@ def fit_hierarchical(X: torch.Tensor, k: int, seed: int, meso_iters: int = 3, fi
     keep: list = []
     tr = _new_trace(meso_iters + 2, keep)
     p = _params(o, keep, tr)
+    _lend_workspace(p, o, n, d, k, X.device, keep, hierarchical=True)
     cent = torch.empty((k, d), device=X.device, dtype=torch.float32)
     assign = torch.empty(n, device=X.device, dtype=torch.int32)
     dist = torch.empty(n, device=X.device, dtype=torch.float32)

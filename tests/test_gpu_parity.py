@@ -583,6 +583,25 @@ def test_lent_workspace_changes_nothing_and_a_small_one_is_refused(skm, dg):
     a0, d0, _ = skm.assign(X, own.centroids, prev, 0, skm.FitOptions(own_workspace=True))
     a1, d1, _ = skm.assign(X, own.centroids, prev, 0, skm.FitOptions(workspace=ws))
     assert torch.equal(a0, a1) and torch.equal(d0, d1)
+    # the sampled fit: one workspace for the fit on the sample and the assignment of all rows
+    so = skm.fit(X, 64, 5, 5, skm.FitOptions(sample_frac=0.25, own_workspace=True))
+    p = skm._params(skm.FitOptions(sample_frac=0.25), [], None)
+    need_s = skm.workspace_bytes(20_000, 128, 64, p)
+    wss = torch.randint(0, 256, (need_s,), dtype=torch.uint8, device="cuda")
+    sl = skm.fit(X, 64, 5, 5, skm.FitOptions(sample_frac=0.25, workspace=wss))
+    assert torch.equal(so.assign, sl.assign) and torch.equal(so.centroids, sl.centroids)
+    with pytest.raises(skm.SkmError, match="memory"):
+        skm.fit(X, 64, 5, 5, skm.FitOptions(sample_frac=0.25, workspace=wss[: need_s // 3]))
+    # the hierarchical fit: every fine fit's share comes out of the workspace; with room for fewer than eight shares
+    # fewer fits run side by side, with the same result; without room for one the call is refused
+    ho, sizes_o, counts_o = skm.fit_hierarchical(X, 64, 13, 3, 5, skm.FitOptions(own_workspace=True))
+    need_h = skm.hier_workspace_bytes(20_000, 128, 64)
+    wsh = torch.randint(0, 256, (need_h,), dtype=torch.uint8, device="cuda")
+    hl, sizes_l, counts_l = skm.fit_hierarchical(X, 64, 13, 3, 5, skm.FitOptions(workspace=wsh))
+    assert sizes_o == sizes_l and counts_o == counts_l
+    assert torch.equal(ho.assign, hl.assign) and torch.equal(ho.centroids, hl.centroids)
+    with pytest.raises(skm.SkmError, match="memory"):
+        skm.fit_hierarchical(X, 64, 13, 3, 5, skm.FitOptions(workspace=wsh[: need_h // 4]))
 
 
 def test_fit_is_bitwise_reproducible(skm, orc, dg):
