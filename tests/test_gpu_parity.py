@@ -241,6 +241,36 @@ def test_steps_on_rows_of_heavy_tailed_norm(skm, orc, dg, screen):
     assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])
 
 
+@pytest.mark.parametrize("case", range(14))
+def test_filtered_steps_over_seeded_shapes(skm, orc, dg, case):
+    """Seeded odd shapes through the filtered step and the filtered incumbent search: point and centroid counts around the
+    edges of the 128- and 256-wide tiles, d not a multiple of 16, d' anywhere between 16 and d."""
+    rng = np.random.default_rng(1000 + case)
+    n = int(rng.choice([1, 2, 127, 129, 255, 257, 300, 1000, 2049, 3000]))
+    k = int(min(rng.choice([1, 2, 3, 127, 128, 129, 255, 256, 257, 513, 700]), max(n, 1)))
+    d = int(rng.choice([16, 20, 48, 100, 128, 200, 272, 400]))
+    ds = (d + 15) // 16 * 16
+    dp = int(rng.integers(1, max(d // 16, 1) + 1)) * 16
+    dp = min(dp, (d // 16) * 16) if d >= 16 else 16
+    say("filtered step, seeded shape", case, n, d, k, dp)
+    X = dg.mixture(n, d, 12, 50 + case, "linear").numpy()
+    R = orc.random_rotation(d, 60 + case)
+    Y = X[rng.choice(n, k, replace=False)] + (0.01 * rng.standard_normal((k, d))).astype(np.float32)
+    Xr, Yr = orc.rotate(X, R), orc.rotate(Y, R)
+    prev = orc.assign_full(Xr, Yr)[0].astype(np.int32)
+    prev[::3] = rng.integers(0, k, len(prev[::3]))
+    for pv in (prev, None):
+        ref = orc.assign_pruned(Xr, Yr, pv, dp, EPS0, 0)
+        a, dist, row = skm.assign(cuda(X), cuda(Y), None if pv is None else cuda(pv), dp,
+                                  skm.FitOptions(R=cuda(R), block_stats=True, screen=1))
+        a = a.cpu().numpy()
+        check_assignment(a, ref.assign, Xr, Yr, min_agree=0.995 if n < 2000 else 0.999)
+        surv_ref = n * (k - 1) - ref.pruned_first
+        assert abs(row["survivors"] - surv_ref) <= max(2, 1e-3 * surv_ref)
+        assert abs(row["completed"] - ref.enter[-1]) <= max(2, 1e-3 * ref.enter[-1])
+        assert row["objective"] == pytest.approx(ref.dist.sum(), rel=1e-5, abs=1e-9)
+
+
 def test_pruned_step_without_previous_assignment(skm, orc, dg):
     X, R, Y, Xr, Yr, _ = pruned_case(orc, dg, 2500, 128, 90, 5, "linear")
     ref = orc.assign_pruned(Xr, Yr, None, 16, EPS0, 0)
