@@ -344,6 +344,59 @@ def test_bad_labels_are_refused(skm, dg):
         skm.update(X, prev, Y)
 
 
+def test_argument_errors_return_codes_and_leave_outputs_untouched(skm, dg):
+    """Straight through the C ABI: every argument error comes back as SKM_EINVAL (a workspace that is too small as
+    SKM_ENOMEM) with a message, before anything is enqueued, and the output arrays keep what they held."""
+    import ctypes as C
+    L = skm.lib()
+    n, d, k = 2000, 64, 20
+    X = dg.mixture(n, d, 8, 2, "linear").cuda()
+    cent = torch.full((k, d), 7.0, device="cuda")
+    assign = torch.full((n,), -9, dtype=torch.int32, device="cuda")
+    dist = torch.full((n,), -3.0, device="cuda")
+    vp = lambda t: C.c_void_p(t.data_ptr())
+
+    def params(**kw):
+        p = skm.Params()
+        L.skm_params_default(C.byref(p))
+        for name, v in kw.items():
+            setattr(p, name, v)
+        return p
+
+    def fit(nn=n, dd=d, kk=k, iters=3, p=None, x=X, c=cent):
+        return L.skm_fit_ex(None if x is None else vp(x), nn, dd, kk, iters, C.c_uint64(1), None if p is None else C.byref(p),
+                            None if c is None else vp(c), vp(assign), vp(dist))
+
+    ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    cases = [
+        (fit(kk=n + 1), -1), (fit(kk=0), -1), (fit(nn=0), -1), (fit(dd=0), -1), (fit(dd=20000), -1), (fit(iters=0), -1),
+        (fit(x=None), -1), (fit(c=None), -1),
+        (fit(p=params(dprime_frac=0.0)), -1), (fit(p=params(dprime_frac=1.5)), -1), (fit(p=params(eps0=-1.0)), -1),
+        (fit(p=params(tau_group=5)), -1), (fit(p=params(conv_tol=2.0)), -1),
+        (fit(p=params(sample_frac=0.5, final_assign=0)), -1), (fit(p=params(angular=1, sample_frac=0.5)), -1),
+        (fit(p=params(workspace=ws.data_ptr(), workspace_bytes=1024)), -2),
+        (L.skm_assign_ex(vp(X), n, d, vp(cent), k, None, 0, C.byref(params(tau_group=3)), vp(assign), vp(dist)), -1),
+        (L.skm_assign_ex(vp(X), n, d, vp(cent), k, None, 0, C.byref(params(workspace=ws.data_ptr(), workspace_bytes=1024)),
+                         vp(assign), vp(dist)), -2),
+        (L.skm_assign_ex(vp(X), n, d, None, k, None, 0, None, vp(assign), vp(dist)), -1),
+        (L.skm_fit_hierarchical(vp(X), n, d, k, 0, 5, C.c_uint64(1), None, vp(cent), vp(assign), vp(dist), None, None), -1),
+        (L.skm_fit_hierarchical(vp(X), n, d, k, 3, 5, C.c_uint64(1), C.byref(params(etr=1)), vp(cent), vp(assign), vp(dist),
+                                None, None), -1),
+        (L.skm_assign_exact_static(vp(X), n, d + 1, vp(cent), k, None, vp(assign), vp(dist)), -1),
+        (L.skm_etr_ground_truth(vp(X), n, d, vp(X), 10, 0, None, vp(assign)), -1),
+    ]
+    for i, (rc, want) in enumerate(cases):
+        assert rc == want, f"case {i}: returned {rc}, expected {want}"
+    assert L.skm_last_error().decode() != ""
+    assert L.skm_strerror(-1).decode() != L.skm_strerror(-2).decode() != ""
+    torch.cuda.synchronize()
+    assert (assign == -9).all() and (dist == -3.0).all() and (cent == 7.0).all()
+    # and the same buffers take a good call afterwards
+    assert fit() == 0
+    torch.cuda.synchronize()
+    assert (assign >= 0).all() and (assign < k).all() and (dist >= 0).all() and not (cent == 7.0).all()
+
+
 # ------------------------------------------------------------------ update
 @pytest.mark.parametrize("n,d,k", [(5000, 128, 100), (3000, 100, 37), (40_000, 64, 5), (2000, 1536, 700)])
 def test_update(skm, orc, dg, n, d, k):
