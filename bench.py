@@ -35,6 +35,7 @@ PEAK_FP16_MFMA_TFLOPS = 2500.0
 SPLIT_PRODUCTS = 3
 PEAK_SPLIT_TFLOPS = PEAK_FP16_MFMA_TFLOPS / SPLIT_PRODUCTS
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
+PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (context: what an fp32 GEMM could reach at most)
 
 
 def cpu_baseline(X_sample, k, iters, seed, R, cores):
@@ -172,6 +173,9 @@ def run_workload(name, steps, warmup, own_workspace, traffic_json, n_override=0)
     for s in stages.values():
         if s["achieved"] is not None and s["bound"] in ("mfma", "hbm"):
             s["frac"] = s["achieved"] / (PEAK_SPLIT_TFLOPS if s["bound"] == "mfma" else PEAK_HBM_GBS)
+        if s["achieved"] is not None and s["bound"] == "mfma":
+            # the same rate against the chip's fp32 matrix peak (the path an fp32 GEMM would take: 157.3 TFLOP/s)
+            s["frac_of_fp32_mfma_peak"] = s["achieved"] / PEAK_FP32_MFMA_TFLOPS
     # dominant kernel of the fit by total time
     totals = {"rotation_gemm": ms_rot, "iter1_gemm_argmin": ms_it1_gemm, "progressive_gemm": total_prog}
     dom = max(totals, key=totals.get)
@@ -197,6 +201,7 @@ def run_workload(name, steps, warmup, own_workspace, traffic_json, n_override=0)
     # traffic: HBM bytes per launch of that kernel (scaled FETCH_SIZE + WRITE_SIZE of the committed counter runs)
     roofline = dict(bound="mfma", kernel=kname, achieved=stages[dom]["achieved"], peak=PEAK_SPLIT_TFLOPS,
                     unit="TFLOP/s", frac=stages[dom]["frac"],
+                    frac_of_fp32_mfma_peak=stages[dom]["achieved"] / PEAK_FP32_MFMA_TFLOPS,
                     traffic=None if traffic is None else traffic.get("total_bytes"), traffic_source=traffic_source,
                     traffic_detail=traffic,
                     ms_per_step=stages[dom]["ms"], total_ms_per_fit=totals[dom],
