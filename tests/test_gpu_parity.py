@@ -687,6 +687,33 @@ def test_lent_workspace_changes_nothing_and_a_small_one_is_refused(skm, dg):
         skm.fit_hierarchical(X, 64, 13, 3, 5, skm.FitOptions(workspace=wsh[: need_h // 4]))
 
 
+def test_fit_with_the_library_rotation_matches_the_oracle_run_with_that_matrix(skm, orc, dg):
+    """A fit that makes its rotation matrix itself (from the seed, on the device) must match the oracle run with the
+    very matrix skm_make_rotation returns for that seed, and a fit that is handed that matrix, at every step."""
+    n, d, k, iters, seed = 70_000, 256, 50, 5, 11
+    X = dg.mixture(n, d, 40, 8, "linear").numpy()
+    R = skm.make_rotation(d, seed)
+    ref = orc.fit(X, k, iters, seed, orc.FitParams(eps0=EPS0), R=R.cpu().numpy())
+    got = skm.fit(cuda(X), k, iters, seed, skm.FitOptions(eps0=EPS0))                 # R from the seed, inside the fit
+    given = skm.fit(cuda(X), k, iters, seed, skm.FitOptions(eps0=EPS0, R=R))
+    assert got.timing["ms_rotate"] > 0
+    Xr = orc.rotate(X, R.cpu().numpy())
+    for fr in (got, given):
+        a = fr.assign.cpu().numpy()
+        Yg = fr.centroids.cpu().numpy()
+        check_assignment(a, ref.assign, Xr, ref.centroids_rot, own=(X, Yg), max_far=20)
+        check_centroids(Yg, ref.centroids, a, ref.assign)
+        for g, r in zip(fr.trace, ref.trace):
+            assert g["objective"] == pytest.approx(r["objective"], rel=1e-4) and g["dprime"] == r["dprime"]
+    assert (got.assign != given.assign).sum().item() <= 20
+    assert got.trace[0]["objective"] == pytest.approx(given.trace[0]["objective"], rel=1e-6)
+    # and the labels of iteration 1 alone (a fit of one iteration without the final pass returns them)
+    one = skm.fit(cuda(X), k, 1, seed, skm.FitOptions(eps0=EPS0, final_assign=False))
+    ref1 = orc.fit(X, k, 1, seed, orc.FitParams(eps0=EPS0, final_assign=False), R=R.cpu().numpy())
+    check_assignment(one.assign.cpu().numpy(), ref1.assign, Xr, Xr[orc.sample_rows(seed, n, k)])
+    assert rel_l2(one.centroids.cpu().numpy(), ref1.centroids) < 1e-5
+
+
 def test_fit_is_bitwise_reproducible(skm, orc, dg):
     X = cuda(dg.mixture(30_000, 128, 64, 12, "linear").numpy())
     R = cuda(orc.random_rotation(128, 2))
